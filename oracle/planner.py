@@ -1,0 +1,561 @@
+"""Planner oracle for the out-of-core training step (TEST INFRASTRUCTURE ONLY).
+
+This file is the slow, plain reference for the planner half of the hot path.  Only
+tests, the smoke check and the benchmark's cpu_baseline leg may import it; the product
+library never does, and the two share no code.
+
+What it follows (KARMA, SC20):
+  * Sec. III-E "capacity-based strategy": keep the tail of the model resident, swap a
+    block out right after its forward, prefetch in FIFO order of need for as long as
+    memory allows.
+  * Sec. III-F and the second optimisation problem (Eq. 10, constraint 10.1): a block
+    is recomputed instead of swapped when recomputing up to the next checkpoint is
+    cheaper than the swap-in it replaces; the goal of recompute is makespan, not memory.
+  * Constraint 9.4: device memory in use never exceeds the capacity, at any instant.
+  * Eq. 1: occupancy = busy / (busy + idle) of the compute queue.
+  * Algorithm 1 and the worked six-block schedule of Sec. III-F.3: the plan is printed
+    as stages `F`, `B`, `S^in`, `S^out` joined by "->" with "||" for overlap.
+
+The paper hands its two integer programs to a proprietary stochastic solver; a result
+of that solver cannot be reproduced.  The deterministic procedure below stands in for
+it.  All arithmetic is on Python integers (nanoseconds and bytes).
+
+Model of one step (a "block" of the paper is one layer record here):
+  three in-order queues (compute, device-to-host, host-to-device) and one arena of
+  `budget - fixed` bytes managed by a two-ended first-fit allocator.  Long-lived
+  buffers (layer inputs x_i, saved internals s_i) are carved from the lowest fitting
+  free range, short-lived ones (workspace, activation gradients dx_i) from the highest.
+"""
+from collections import deque, namedtuple
+
+KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN = 0, 1, 2, 3, 4
+N_ACTIONS = 5
+ALIGN = 256
+
+# per-layer costs.  tf/tb/trc: forward, backward, recompute time (ns).  sav: bytes of
+# internals backward needs besides the layer input.  out: bytes of the layer output
+# (= the next layer's input).  ws: transient workspace bytes of any op of this layer.
+Layer = namedtuple("Layer", "tf tb trc sav out ws")
+# host link: bytes/s per direction and a fixed per-copy latency (ns)
+Link = namedtuple("Link", "bw_h2d bw_d2h lat_ns")
+# loss op that sits between forward and backward: time and workspace
+Loss = namedtuple("Loss", "t ws")
+Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN
+
+
+class Infeasible(Exception):
+    pass
+
+
+def al(b):
+    return (b + ALIGN - 1) // ALIGN * ALIGN
+
+
+def copy_ns(b, bw, lat):
+    """Time of one copy: latency plus bytes over bandwidth, rounded up (Eq. 4 reading:
+    one measured throughput per direction)."""
+    if b == 0:
+        return 0
+    return lat + (b * 10**9 + bw - 1) // bw
+
+
+class Arena:
+    """Two-ended first-fit allocator over [0, cap) with coalescing free list."""
+
+    def __init__(self, cap):
+        self.cap = cap
+        self.free = [[0, cap]] if cap > 0 else []   # sorted [offset, size]
+        self.used = 0
+        self.peak_used = 0
+        self.peak_extent_lo = 0     # highest end of a low-end allocation
+        self.low_water_hi = cap     # lowest start of a high-end allocation
+
+    def total_free(self):
+        return self.cap - self.used
+
+    def alloc(self, size, low):
+        """Returns offset, or None when no free range fits.  size is already aligned
+        and > 0."""
+        fl = self.free
+        rng = range(len(fl)) if low else range(len(fl) - 1, -1, -1)
+        for k in rng:
+            off, sz = fl[k]
+            if sz >= size:
+                if low:
+                    res = off
+                    if sz == size:
+                        del fl[k]
+                    else:
+                        fl[k][0] = off + size
+                        fl[k][1] = sz - size
+                    self.peak_extent_lo = max(self.peak_extent_lo, res + size)
+                else:
+                    res = off + sz - size
+                    if sz == size:
+                        del fl[k]
+                    else:
+                        fl[k][1] = sz - size
+                    self.low_water_hi = min(self.low_water_hi, res)
+                self.used += size
+                if self.used > self.peak_used:
+                    self.peak_used = self.used
+                return res
+        return None
+
+    def release(self, off, size):
+        fl = self.free
+        k = 0
+        while k < len(fl) and fl[k][0] < off:
+            k += 1
+        fl.insert(k, [off, size])
+        if k + 1 < len(fl) and fl[k][0] + fl[k][1] == fl[k + 1][0]:
+            fl[k][1] += fl[k + 1][1]
+            del fl[k + 1]
+        if k > 0 and fl[k - 1][0] + fl[k - 1][1] == fl[k][0]:
+            fl[k - 1][1] += fl[k][1]
+            del fl[k]
+        self.used -= size
+
+
+def valid_actions(actions):
+    prev = KEEP
+    for i, a in enumerate(actions):
+        if not 0 <= a < N_ACTIONS:
+            return False
+        if a == RC_CHAIN and (i == 0 or prev not in (RC_KEEP, RC_SWAP, RC_CHAIN)):
+            return False
+        prev = a
+    return True
+
+
+def backward_units(actions):
+    """Backward proceeds over units in descending layer order.  A unit is either one
+    KEEP/SWAP layer, or a recompute segment: a head (RC_KEEP / RC_SWAP, the checkpoint)
+    plus the RC_CHAIN layers that follow it (the set of blocks up to the next
+    checkpoint, Eq. 10)."""
+    units = []
+    i = len(actions) - 1
+    while i >= 0:
+        h = i
+        while actions[h] == RC_CHAIN:
+            h -= 1
+        units.append((h, i))
+        i = h - 1
+    return units
+
+
+def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
+    """Timeline of one training step under a given per-layer action vector.
+
+    Returns a dict with makespan_ns, stall_ns, busy_ns, peak_bytes, bytes_d2h,
+    bytes_h2d, recompute_ns (and `ops` when asked).  Raises Infeasible when the arena
+    cannot grant an allocation (constraint 9.4)."""
+    L = len(layers)
+    if not valid_actions(actions) or len(actions) != L:
+        raise ValueError("invalid action vector")
+    cap = budget - fixed
+    if cap <= 0:
+        raise Infeasible()
+    ar = Arena(cap)
+    # xb[i] = aligned bytes of x_i, the input of layer i; x_0 is the step input and
+    # lives in the fixed region, x_L feeds the loss.
+    xraw = [0] + [layers[i].out for i in range(L)]
+    xb = [al(b) for b in xraw]
+    sb = [al(l.sav) for l in layers]
+    wsb = [al(l.ws) for l in layers]
+    X = [None] * (L + 1)      # offsets
+    S = [None] * L
+    DX = [None] * (L + 1)
+    pending = deque()         # (time, [(off, size), ...]) frees at D2H completion
+    ops = []
+    tc = td = th = 0
+    busy = 0
+    d2h = h2d = rc_ns = 0
+
+    def apply_pending(t):
+        while pending and pending[0][0] <= t:
+            for off, size in pending.popleft()[1]:
+                ar.release(off, size)
+
+    def grant(size, low, t):
+        """Allocate, waiting on outstanding swap-outs if need be (a memory stall)."""
+        if size == 0:
+            return None, t
+        while True:
+            off = ar.alloc(size, low)
+            if off is not None:
+                return off, t
+            if not pending:
+                raise Infeasible()
+            tm, bufs = pending.popleft()
+            for o, s in bufs:
+                ar.release(o, s)
+            if tm > t:
+                t = tm
+
+    def rel(off, size):
+        if off is not None:
+            ar.release(off, size)
+
+    # ---------------- forward ----------------
+    for i in range(L):
+        t = tc
+        apply_pending(t)
+        X[i + 1], t = grant(xb[i + 1], True, t)
+        S[i], t = grant(sb[i], True, t)
+        w, t = grant(wsb[i], False, t)
+        end = t + layers[i].tf
+        busy += layers[i].tf
+        if want_ops:
+            ops.append(Op("F", i, t, end, (X[i + 1], S[i], w)))
+        tc = end
+        rel(w, wsb[i])
+        a = actions[i]
+        if a == SWAP or a == RC_SWAP:
+            nbytes = xraw[i] + (layers[i].sav if a == SWAP else 0)
+            bufs = []
+            if X[i] is not None:
+                bufs.append((X[i], xb[i]))
+            if a == SWAP and S[i] is not None:
+                bufs.append((S[i], sb[i]))
+            if nbytes:
+                st = max(td, end)
+                td = st + copy_ns(nbytes, link.bw_d2h, link.lat_ns)
+                d2h += nbytes
+                pending.append((td, bufs))
+                if want_ops:
+                    ops.append(Op("OUT", i, st, td, ()))
+            if a == RC_SWAP:
+                rel(S[i], sb[i])
+        elif a == RC_KEEP:
+            rel(S[i], sb[i])
+        elif a == RC_CHAIN:
+            rel(S[i], sb[i])
+            rel(X[i], xb[i])
+
+    # ---------------- prefetch queue and reserves ----------------
+    units = backward_units(actions)
+    items = deque(i for i in range(L - 1, -1, -1)
+                  if (actions[i] == SWAP and xraw[i] + layers[i].sav) or
+                     (actions[i] == RC_SWAP and xraw[i]))
+    arrive = {}
+
+    def unit_need(h, e):
+        if actions[h] in (KEEP, SWAP):
+            return xb[h] + wsb[h]
+        s = sum(sb[j] for j in range(h, e + 1)) + sum(xb[j + 1] for j in range(h, e))
+        return s + max(xb[j] + wsb[j] for j in range(h, e + 1))
+
+    needs = [unit_need(h, e) for h, e in units]
+    res_after = [0] * len(units)
+    for k in range(len(units) - 2, -1, -1):
+        res_after[k] = max(res_after[k + 1], needs[k + 1])
+    res_all = max(needs) if needs else 0
+    loss_need = xb[L] + al(loss.ws)
+
+    def place(i):
+        """Try to allocate the swap-in buffers of layer i (low end); roll back on
+        failure."""
+        xo = so = None
+        if xb[i]:
+            xo = ar.alloc(xb[i], True)
+            if xo is None:
+                return False
+        if actions[i] == SWAP and sb[i]:
+            so = ar.alloc(sb[i], True)
+            if so is None:
+                if xo is not None:
+                    ar.release(xo, xb[i])
+                return False
+        X[i] = xo
+        if actions[i] == SWAP:
+            S[i] = so
+        return True
+
+    def issue_in(i, t):
+        nonlocal th, h2d
+        nbytes = xraw[i] + (layers[i].sav if actions[i] == SWAP else 0)
+        st = max(th, t)
+        th = st + copy_ns(nbytes, link.bw_h2d, link.lat_ns)
+        h2d += nbytes
+        arrive[i] = th
+        if want_ops:
+            ops.append(Op("IN", i, st, th, (X[i], S[i] if actions[i] == SWAP else None)))
+
+    def admit(t, reserve):
+        """Swap in ahead of need, in order of need, while the arena keeps `reserve`
+        bytes for the compute ops still to come (Sec. III-E: keep swapping in as long
+        as there is space)."""
+        apply_pending(t)
+        while items:
+            i = items[0]
+            need = xb[i] + (sb[i] if actions[i] == SWAP else 0)
+            if ar.total_free() < need + reserve or not place(i):
+                break
+            items.popleft()
+            issue_in(i, t)
+
+    def force(i, t):
+        """Layer i's data is needed now: admit everything up to and including it."""
+        while i not in arrive:
+            j = items.popleft()
+            X[j], t = grant(xb[j], True, t)
+            if actions[j] == SWAP:
+                S[j], t = grant(sb[j], True, t)
+            issue_in(j, t)
+        return t
+
+    # ---------------- loss ----------------
+    admit(tc, max(res_all, loss_need))
+    t = tc
+    apply_pending(t)
+    DX[L], t = grant(xb[L], False, t)
+    w, t = grant(al(loss.ws), False, t)
+    end = t + loss.t
+    busy += loss.t
+    if want_ops:
+        ops.append(Op("L", L, t, end, (DX[L], w)))
+    tc = end
+    rel(w, al(loss.ws))
+    rel(X[L], xb[L])
+    admit(tc, res_all)
+
+    # ---------------- backward ----------------
+    def backward_op(j, t, reserve):
+        nonlocal tc, busy
+        apply_pending(t)
+        DX[j], t = grant(xb[j], False, t)
+        w, t = grant(wsb[j], False, t)
+        end = t + layers[j].tb
+        busy += layers[j].tb
+        if want_ops:
+            ops.append(Op("B", j, t, end, (DX[j], w)))
+        tc = end
+        rel(w, wsb[j])
+        rel(DX[j + 1], xb[j + 1])
+        rel(S[j], sb[j])
+        rel(X[j], xb[j])
+        admit(tc, reserve)
+
+    for k, (h, e) in enumerate(units):
+        a = actions[h]
+        t = tc
+        if a in (SWAP, RC_SWAP) and (h in arrive or h in items):
+            t = force(h, t)
+            t = max(t, arrive[h])
+        if a in (KEEP, SWAP):
+            backward_op(h, t, res_after[k])
+            continue
+        inner = max(xb[j] + wsb[j] for j in range(h, e + 1))
+        for j in range(h, e + 1):
+            apply_pending(t)
+            S[j], t = grant(sb[j], True, t)
+            if j < e:
+                X[j + 1], t = grant(xb[j + 1], True, t)
+            w, t = grant(wsb[j], False, t)
+            end = t + layers[j].trc
+            busy += layers[j].trc
+            rc_ns += layers[j].trc
+            if want_ops:
+                ops.append(Op("R", j, t, end, (S[j], X[j + 1] if j < e else None, w)))
+            tc = end
+            rel(w, wsb[j])
+            t = end
+        for j in range(e, h - 1, -1):
+            backward_op(j, tc, res_after[k] if j == h else max(res_after[k], inner))
+
+    apply_pending(max(tc, td, th))
+    assert ar.used == 0, "ledger leak"
+    makespan = max(tc, td, th)
+    res = dict(makespan_ns=makespan, stall_ns=tc - busy, busy_ns=busy,
+               peak_bytes=fixed + ar.peak_used, bytes_d2h=d2h, bytes_h2d=h2d,
+               recompute_ns=rc_ns)
+    if want_ops:
+        res["ops"] = ops
+    return res
+
+
+def occupancy(summary):
+    """Eq. 1 on the compute queue of the whole step."""
+    return summary["busy_ns"] / (summary["busy_ns"] + summary["stall_ns"])
+
+
+def cost_tuple(summary):
+    return (summary["makespan_ns"], summary["bytes_d2h"] + summary["bytes_h2d"],
+            summary["recompute_ns"])
+
+
+def try_cost(layers, link, budget, fixed, loss, actions):
+    try:
+        return cost_tuple(simulate(layers, link, budget, fixed, loss, actions))
+    except Infeasible:
+        return None
+
+
+def plan(layers, link, budget, fixed, loss):
+    """Deterministic stand-in for the paper's two-tier optimisation.
+
+    1. Capacity rule (Sec. III-E): everything fits -> all KEEP.  Otherwise the resident
+       tail is as long as memory allows, the prefix before it is swapped.
+    2. Recompute marking (Eq. 10.1, read with the prose above it): going down the
+       prefix, a swapped layer becomes a recompute layer when its recompute time is
+       strictly less than the swap-in it replaces.
+    3. Makespan refinement (`refine`): local search on (makespan, bytes moved,
+       recompute time), from two starts (swapped prefix after step 2; recomputed
+       prefix); the better local optimum wins.
+    Returns (actions, summary); raises Infeasible when no assignment tried fits."""
+    L = len(layers)
+    cur = [KEEP] * L
+    c = try_cost(layers, link, budget, fixed, loss, cur)
+    if c is not None:
+        return cur, simulate(layers, link, budget, fixed, loss, cur)
+
+    # step 1: longest resident tail; the prefix before it swapped, or (second start)
+    # recomputed from kept checkpoints; patterns that hold less memory as fall-backs.
+    def longest_tail(fill):
+        for k in range(1, L + 1):
+            cand = [fill] * k + [KEEP] * (L - k)
+            if fill == RC_CHAIN:
+                cand[0] = RC_KEEP
+            if try_cost(layers, link, budget, fixed, loss, cand) is not None:
+                return cand
+        return None
+
+    starts = [s for s in (longest_tail(SWAP), longest_tail(RC_KEEP)) if s is not None]
+    if not starts:
+        s = longest_tail(RC_CHAIN)
+        if s is None:
+            raise Infeasible()
+        starts = [s]
+
+    # step 2: Eq. 10.1 scan over the swapped prefix of the first start, descending
+    xraw = [0] + [l.out for l in layers]
+    cur = starts[0]
+    for i in range(L - 1, -1, -1):
+        if cur[i] != SWAP:
+            continue
+        t_in = copy_ns(xraw[i] + layers[i].sav, link.bw_h2d, link.lat_ns)
+        if layers[i].trc < t_in:
+            for a in (RC_KEEP, RC_SWAP):
+                cand = list(cur)
+                cand[i] = a
+                if valid_actions(cand) and try_cost(layers, link, budget, fixed, loss, cand) is not None:
+                    cur = cand
+                    break
+    starts[0] = cur
+
+    # step 3: refinement of each start; the best local optimum wins
+    best = None
+    for start in starts:
+        key = refine(layers, link, budget, fixed, loss, start)
+        if best is None or key < best:
+            best = key
+    cur = best[1]
+    return cur, simulate(layers, link, budget, fixed, loss, cur)
+
+
+def refine(layers, link, budget, fixed, loss, start):
+    """Local search.  A candidate replaces the incumbent when its (cost tuple, action
+    vector) is lexicographically smaller.  Neighbourhoods, in this order, repeated
+    until a full round changes nothing: (a) one layer takes another action; (b) two
+    layers exchange their actions; (c) two neighbouring layers take any pair of
+    actions.  Returns (cost tuple, actions)."""
+    L = len(layers)
+    key = (try_cost(layers, link, budget, fixed, loss, start), list(start))
+
+    def consider(cand):
+        nonlocal key
+        if not valid_actions(cand):
+            return False
+        cc = try_cost(layers, link, budget, fixed, loss, cand)
+        if cc is not None and (cc, cand) < key:
+            key = (cc, cand)
+            return True
+        return False
+
+    changed = True
+    while changed:
+        changed = False
+        for i in range(L):
+            for a in range(N_ACTIONS):
+                if a != key[1][i]:
+                    cand = list(key[1])
+                    cand[i] = a
+                    changed |= consider(cand)
+        for i in range(L):
+            for j in range(i + 1, L):
+                if key[1][i] != key[1][j]:
+                    cand = list(key[1])
+                    cand[i], cand[j] = cand[j], cand[i]
+                    changed |= consider(cand)
+        for i in range(L - 1):
+            for a in range(N_ACTIONS):
+                for b in range(N_ACTIONS):
+                    if (a, b) != (key[1][i], key[1][i + 1]):
+                        cand = list(key[1])
+                        cand[i], cand[i + 1] = a, b
+                        changed |= consider(cand)
+    return key
+
+
+def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN)):
+    """Exhaustive search over every valid assignment: smallest cost tuple, ties to the
+    lexicographically smallest action vector.  Exponential; for small stacks only."""
+    L = len(layers)
+    best = None
+    cur = [alphabet[0]] * L
+
+    def rec(i):
+        nonlocal best
+        if i == L:
+            c = try_cost(layers, link, budget, fixed, loss, cur)
+            if c is not None and (best is None or (c, cur) < best):
+                best = (c, list(cur))
+            return
+        for a in alphabet:
+            if a == RC_CHAIN and (i == 0 or cur[i - 1] not in (RC_KEEP, RC_SWAP, RC_CHAIN)):
+                continue
+            cur[i] = a
+            rec(i + 1)
+
+    rec(0)
+    return best
+
+
+def stage_string(ops):
+    """Algorithm 1's output in the paper's notation.  One stage per forward, backward
+    or recompute op (a recompute is printed as F, as in the worked example); a copy is
+    listed on the stage that is running when the copy starts.  Recompute stages are
+    inserted as fresh stages by Algorithm 1 and carry no copies: a copy that starts
+    during one is listed on the next forward/backward stage.  Layers print 1-based."""
+    stages = [o for o in ops if o.kind in "FBR"]
+    copies = [o for o in ops if o.kind in ("IN", "OUT")]
+    att = [[] for _ in stages]
+    for c in copies:
+        idx = None
+        for k, s in enumerate(stages):
+            if s.kind != "R" and s.end > c.start:
+                idx = k
+                break
+        if idx is None:
+            idx = len(stages) - 1
+        att[idx].append(c)
+    parts = []
+    for s, cs in zip(stages, att):
+        txt = ("B" if s.kind == "B" else "F") + str(s.layer + 1)
+        for c in cs:
+            txt += "||S%d^%s" % (c.layer + 1, "in" if c.kind == "IN" else "out")
+        parts.append(txt)
+    return " -> ".join(parts)
+
+
+# ---- comparison policies run through the same simulator (Fig. 2 a/b) ----
+def policy_eager_swap(L):
+    """vDNN-style: every layer is swapped out after its forward, the last one too."""
+    return [SWAP] * L
+
+
+def policy_checkpoint_every(L, stride):
+    """Plain gradient checkpointing: a kept checkpoint every `stride` layers, the rest
+    dropped and recomputed."""
+    return [RC_KEEP if i % stride == 0 else RC_CHAIN for i in range(L)]

@@ -1,0 +1,116 @@
+"""Seeded synthetic inputs shared by the oracle-side tests and the GPU-side harness.
+
+Holds no arithmetic of the method itself: only a counter-based random generator
+(splitmix64 -> uniform / Box-Muller normal), the initialisers the workload list
+prescribes (Xavier-uniform for the MLP, N(0, 0.02) for GPT weights) and random cost
+records for planner tests.  Everything is produced on the host as numpy arrays and
+handed to whichever side asks, so initialisation is never a parity variable.
+"""
+import numpy as np
+
+_M64 = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+
+def splitmix64(seed, n):
+    """n 64-bit words of the splitmix64 stream that starts at `seed`."""
+    with np.errstate(over="ignore"):
+        idx = np.arange(1, n + 1, dtype=np.uint64)
+        z = np.uint64(seed) + idx * np.uint64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+def uniform01(seed, n):
+    """Doubles in [0, 1) from the top 53 bits."""
+    return (splitmix64(seed, n) >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
+
+
+def normal(seed, shape, std=1.0):
+    n = int(np.prod(shape))
+    m = (n + 1) // 2
+    u1 = 1.0 - uniform01(seed, m)                      # (0, 1]
+    u2 = uniform01(seed ^ 0x5DEECE66D, m)
+    r = np.sqrt(-2.0 * np.log(u1))
+    z = np.concatenate([r * np.cos(2 * np.pi * u2), r * np.sin(2 * np.pi * u2)])[:n]
+    return (z * std).reshape(shape)
+
+
+def uniform(seed, shape, lo, hi):
+    n = int(np.prod(shape))
+    return (lo + (hi - lo) * uniform01(seed, n)).reshape(shape)
+
+
+def randint(seed, shape, hi):
+    n = int(np.prod(shape))
+    return (splitmix64(seed, n) % np.uint64(hi)).astype(np.int64).reshape(shape)
+
+
+# ------------------------------------------------------------------ workloads
+def mlp_problem(seed=2008114201, n_layers=8, width=256, batch=32):
+    """Config 1: Xavier-uniform weights [out, in], zero biases, N(0,1) inputs/targets."""
+    bound = float(np.sqrt(6.0 / (width + width)))
+    Ws = [uniform(seed + 11 * i + 1, (width, width), -bound, bound) for i in range(n_layers)]
+    bs = [np.zeros(width) for _ in range(n_layers)]
+    x = normal(seed + 1001, (batch, width))
+    t = normal(seed + 1002, (batch, width))
+    return Ws, bs, x, t
+
+
+def gpt_problem(seed=2008114202, n_layers=24, hidden=1024, ffn=4096, vocab=32000,
+                seq=1024, batch=32, std=0.02, bias_std=0.0):
+    """Configs 2/4/5: N(0, std) weights, LayerNorm gain 1 / shift 0, biases N(0,
+    bias_std) (0 by default; tests use a non-zero value so that bias paths matter),
+    token ids and labels uniform over the vocabulary."""
+    def w(k, shape, s=std):
+        return normal(seed + 7919 * k, shape, s)
+    params = dict(wte=w(1, (vocab, hidden)), wpe=w(2, (seq, hidden)),
+                  lnf_g=np.ones(hidden), lnf_b=np.zeros(hidden), blocks=[])
+    for i in range(n_layers):
+        k = 10 + 10 * i
+        def bias(j, n):
+            return w(k + j, (n,), bias_std) if bias_std else np.zeros(n)
+        params["blocks"].append(dict(
+            ln1_g=np.ones(hidden) + (w(k + 8, (hidden,), bias_std) if bias_std else 0),
+            ln1_b=bias(9, hidden),
+            wqkv=w(k, (3 * hidden, hidden)), bqkv=bias(4, 3 * hidden),
+            wo=w(k + 1, (hidden, hidden)), bo=bias(5, hidden),
+            ln2_g=np.ones(hidden) + (w(k + 8, (hidden,), bias_std)[::-1] if bias_std else 0),
+            ln2_b=bias(9, hidden)[::-1].copy(),
+            w1=w(k + 2, (ffn, hidden)), b1=bias(6, ffn),
+            w2=w(k + 3, (hidden, ffn)), b2=bias(7, hidden)))
+    ids = randint(seed + 3, (batch, seq), vocab)
+    labels = randint(seed + 5, (batch, seq), vocab)
+    return params, ids, labels
+
+
+# ------------------------------------------------------------------ planner stacks
+def random_stack(seed, n_layers, kind="homogeneous"):
+    """Random integer cost records (tf, tb, trc, sav, out, ws) for planner tests.
+    kinds: homogeneous | front_heavy (memory shrinks with depth, as in CNNs) |
+    back_heavy | imbalanced (compute and memory uncorrelated)."""
+    r = splitmix64(seed, 8 * n_layers + 8)
+    rows = []
+    for i in range(n_layers):
+        a = [int(v) for v in r[8 * i:8 * i + 8]]
+        if kind == "homogeneous":
+            tf = 1000 + a[0] % 50
+            sav = 4096 * (8 + a[1] % 2)
+            out = 4096
+        elif kind == "front_heavy":
+            tf = 800 + a[0] % 400
+            sav = 4096 * (2 + 30 * (n_layers - i) // n_layers + a[1] % 3)
+            out = 1024 * (1 + 8 * (n_layers - i) // n_layers)
+        elif kind == "back_heavy":
+            tf = 800 + a[0] % 400
+            sav = 4096 * (2 + 30 * (i + 1) // n_layers + a[1] % 3)
+            out = 1024 * (1 + 8 * (i + 1) // n_layers)
+        else:
+            tf = 200 + a[0] % 3000
+            sav = 1024 * (1 + a[1] % 64)
+            out = 256 * (1 + a[2] % 32)
+        tb = 2 * tf + a[3] % 100
+        trc = tf - a[4] % (tf // 10 + 1)
+        ws = 256 * (a[5] % 8)
+        rows.append((tf, tb, trc, sav, out, ws))
+    return rows
