@@ -1,0 +1,223 @@
+/*
+ * karma.h -- C ABI of the MI355X out-of-core training-step library.
+ *
+ * The library runs one training step of a layer stack whose activations do not fit a
+ * configured HBM budget, following KARMA (SC20): a CPU planner chooses per layer between
+ * keeping, swapping to host and dropping-and-recomputing (Sec. III-E capacity-based
+ * strategy, Sec. III-F interleaved recompute, Fig. 4 optimisation problems), a schedule
+ * generator turns the choice into stages (Algorithm 1), and a three-stream executor
+ * overlaps layer compute with swap-out and prefetch (Fig. 2(c)), updating fp32 master
+ * weights on the host (Sec. III-G, pipeline stage 5).
+ *
+ * Conventions for every entry point
+ *   - returns a karma_status (0 = ok, negative = error); never throws, never aborts;
+ *     karma_last_error() gives a text for the last failure of a context.
+ *   - pointers named *_host are host memory, *_dev are device (HBM) memory; output
+ *     buffers are allocated and owned by the caller; inputs are only read during the call.
+ *   - a layer record stands for one "block" of the paper (footnote in Sec. III-B).
+ *   - all times are integer nanoseconds, all sizes integer bytes.
+ *   - a context is not thread-safe; calls on one context must not overlap.
+ */
+#ifndef KARMA_H
+#define KARMA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct karma_ctx karma_ctx;
+
+typedef enum {
+  KARMA_OK = 0,
+  KARMA_E_INVAL = -1,   /* bad argument (null pointer, bad shape, invalid action vector) */
+  KARMA_E_BUDGET = -2,  /* no assignment fits the budget (constraint 9.4 cannot be met) */
+  KARMA_E_OOM = -3,     /* caller's buffer or arena too small */
+  KARMA_E_HIP = -4,     /* a HIP runtime call failed */
+  KARMA_E_STATE = -5,   /* call out of order (step before plan, ...) */
+  KARMA_E_HOSTMEM = -6  /* pinned host allocation failed */
+} karma_status;
+
+/* Per-layer action.  x_i is the layer's input tensor, "internals" what backward needs
+ * besides x_i.
+ *   KEEP      both stay in HBM (the resident tail of Sec. III-E)
+ *   SWAP      both copied to host right after F_i, copied back before B_i
+ *   RC_KEEP   internals dropped after F_i and recomputed before B_i; x_i stays (checkpoint)
+ *   RC_SWAP   as RC_KEEP, but the checkpoint x_i itself is swapped
+ *   RC_CHAIN  x_i and internals dropped; recomputed by the chain that starts at the
+ *             nearest preceding RC_KEEP / RC_SWAP (the set "Delta" of Eq. 10)
+ * RC_CHAIN is valid only directly after RC_KEEP, RC_SWAP or RC_CHAIN, never at layer 0. */
+typedef enum { KARMA_KEEP = 0, KARMA_SWAP = 1, KARMA_RC_KEEP = 2, KARMA_RC_SWAP = 3, KARMA_RC_CHAIN = 4 } karma_action;
+
+/* Cost-model inputs (Sec. III-C compute cost, Sec. III-D memory per variable type). */
+typedef struct {
+  int64_t tf_ns, tb_ns, trc_ns; /* forward, backward, recompute time */
+  uint64_t sav_bytes;           /* internals needed by backward, excluding x_i */
+  uint64_t out_bytes;           /* output = input of the next layer (x_0 is the step input
+                                   and lives in the fixed region) */
+  uint64_t ws_bytes;            /* transient workspace of any one op of the layer */
+} karma_layer_cost;
+
+typedef struct {
+  uint64_t bw_h2d, bw_d2h; /* bytes per second, one measured figure per direction (Eq. 4) */
+  int64_t lat_ns;          /* fixed cost per copy */
+} karma_link;
+
+typedef struct {
+  int64_t t_ns;      /* loss op (forward and gradient w.r.t. its input) */
+  uint64_t ws_bytes; /* its workspace */
+} karma_loss_cost;
+
+typedef struct {
+  int64_t makespan_ns;  /* end of the last op on any queue */
+  int64_t stall_ns;     /* idle time of the compute queue (Eq. 1 denominator minus busy) */
+  int64_t busy_ns;      /* compute-queue busy time, recompute included */
+  int64_t recompute_ns; /* part of busy_ns spent recomputing */
+  uint64_t peak_bytes;  /* fixed + high-water mark of the arena */
+  uint64_t bytes_d2h, bytes_h2d;
+} karma_plan_summary;
+
+/* One op of the simulated/executed timeline, in issue order.
+ * kind: 'F' forward, 'B' backward, 'R' recompute, 'L' loss, 'O' swap-out, 'I' swap-in.
+ * off[]: arena offsets (relative to the end of the fixed region, -1 = none) of what the
+ *   op allocates: F {x_{i+1}, internals, workspace}; R {internals, x_{i+1}, workspace};
+ *   B and L {dx, workspace, -1}; I {x_i, internals, -1}; O {-1,-1,-1}. */
+typedef struct {
+  uint8_t kind;
+  uint32_t layer;
+  int64_t start_ns, end_ns;
+  int64_t off[3];
+} karma_op;
+
+/* ---- planner: pure CPU functions, no GPU needed -------------------------------- */
+
+/* Timeline of one step under a given action vector (three in-order queues and a
+ * two-ended first-fit arena of budget - fixed bytes; constraint 9.4 is checked at every
+ * allocation).  ops_out may be NULL; otherwise *n_ops_inout holds its capacity on entry
+ * and the number of ops on return (KARMA_E_OOM if too small: at most 6*n+2 are written).
+ * Errors: KARMA_E_INVAL (invalid vector), KARMA_E_BUDGET (does not fit). */
+int karma_simulate(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                   const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
+                   const uint8_t* actions, karma_plan_summary* summary_out, karma_op* ops_out,
+                   uint32_t* n_ops_inout);
+
+/* The planner (Sec. III-E capacity rule, Eq. 10.1 recompute marking, makespan
+ * refinement by local search over the simulator).  Writes n_layers actions.
+ * Errors: KARMA_E_BUDGET when nothing fits. */
+int karma_plan_pure(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                    const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
+                    uint8_t* actions_out, karma_plan_summary* summary_out);
+
+/* Algorithm 1's output in the paper's notation ("F1 -> F2||S1^out -> ...", layers
+ * 1-based, recompute printed as F).  Writes a NUL-terminated string; KARMA_E_OOM if
+ * buf_len is too small. */
+int karma_stage_string(const karma_op* ops, uint32_t n_ops, char* buf, size_t buf_len);
+
+/* ---- model and context ---------------------------------------------------------- */
+
+typedef enum { KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2 } karma_model_kind;
+typedef enum { KARMA_OPT_SGD = 1, KARMA_OPT_ADAM = 2 } karma_opt_kind;
+
+typedef struct {
+  uint32_t kind;      /* karma_model_kind */
+  uint32_t n_layers;  /* MLP: Linear+ReLU layers; GPT: transformer blocks */
+  uint32_t width;     /* MLP width / GPT hidden size */
+  uint32_t batch;
+  uint32_t seq;       /* GPT only */
+  uint32_t n_heads;   /* GPT only; width / n_heads must be 64 or 128 */
+  uint32_t ffn;       /* GPT only */
+  uint32_t vocab;     /* GPT only */
+} karma_model_desc;
+
+typedef struct {
+  uint32_t optimizer; /* karma_opt_kind */
+  float lr, beta1, beta2, eps;
+  uint32_t host_threads; /* worker threads of the host optimiser (0 = 1) */
+} karma_config;
+
+/* Number of plannable layer records of a model (MLP: n_layers; GPT: n_layers + 1, record
+ * 0 being the embedding) and of parameter tensors of record `layer`. */
+int karma_model_layers(const karma_model_desc* desc, uint32_t* n_out);
+
+/* Creates a context.  arena_dev: device slab of arena_bytes owned by the caller (e.g. a
+ * torch uint8 tensor), 256-byte aligned, must outlive the context.  The three streams are
+ * hipStream_t values owned by the caller, all of default priority.  The library owns its
+ * pinned host pool, events, host master weights and everything it places in the slab. */
+int karma_create(const karma_model_desc* desc, const karma_config* cfg, void* arena_dev,
+                 uint64_t arena_bytes, void* stream_compute, void* stream_h2d, void* stream_d2h,
+                 karma_ctx** out);
+void karma_destroy(karma_ctx* ctx);
+const char* karma_last_error(const karma_ctx* ctx);
+
+/* Parameter tensors.  Record/tensor numbering: see karma_param_count/karma_param_size.
+ * set: copies n fp32 values into the host master copy and uploads the device copy
+ * (rounded to bf16 by round-to-nearest-even for bf16 models).  get_param reads the
+ * master copy; get_grad copies the gradient of the last step (converted to fp32). */
+int karma_param_count(const karma_ctx* ctx, uint32_t layer, uint32_t* n_tensors_out);
+int karma_param_size(const karma_ctx* ctx, uint32_t layer, uint32_t tensor, uint64_t* n_elems_out);
+int karma_set_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, const float* host_fp32, uint64_t n);
+int karma_get_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_fp32_out, uint64_t n);
+int karma_get_grad(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_fp32_out, uint64_t n);
+
+/* Cost records of the model: bytes from shapes (exact, the library owns the allocator),
+ * times from the last karma_measure (0 before).  layers_out has karma_model_layers
+ * entries.  fixed_out: bytes resident for the whole step (weights, gradients, inputs). */
+int karma_get_costs(karma_ctx* ctx, karma_layer_cost* layers_out, karma_loss_cost* loss_out,
+                    uint64_t* fixed_out);
+/* Measures per-layer forward/backward/recompute times (in-core, median of `reps`) and the
+ * pinned-copy bandwidth of both directions (Sec. III-D: profiled once per model).  Needs
+ * arena_bytes large enough for one layer in-core. */
+int karma_measure(karma_ctx* ctx, uint32_t reps, karma_link* link_out);
+/* Overrides measured figures (tests, reproducible plans). */
+int karma_set_costs(karma_ctx* ctx, const karma_layer_cost* layers, const karma_loss_cost* loss,
+                    const karma_link* link);
+
+/* Plans for a budget (<= arena_bytes) with the current cost records and builds the
+ * executable schedule.  actions_out (may be NULL) receives the chosen actions. */
+int karma_plan(karma_ctx* ctx, uint64_t budget_bytes, uint8_t* actions_out, karma_plan_summary* summary_out);
+/* Forces an action vector (validated against the budget by simulation). */
+int karma_set_plan(karma_ctx* ctx, uint64_t budget_bytes, const uint8_t* actions, karma_plan_summary* summary_out);
+/* Stage string of the current plan. */
+int karma_plan_string(karma_ctx* ctx, char* buf, size_t buf_len);
+
+#define KARMA_STEP_APPLY_OPTIMIZER 1u /* D2H gradients, host update of the master weights, H2D new weights */
+/* One training step.  MLP: inputs_host fp32 [batch, width], labels_host fp32 targets of
+ * the same shape.  GPT: inputs_host int32 token ids [batch, seq], labels_host int32
+ * [batch, seq].  Synchronous: on return the loss is valid, all streams are drained and
+ * gradients can be read. */
+int karma_step(karma_ctx* ctx, const void* inputs_host, const void* labels_host, uint32_t flags, float* loss_out);
+
+/* Debug read-back of the hidden state that entered record `layer` in the last step
+ * (only for records whose input is still resident or swapped: not RC_CHAIN), fp32. */
+typedef struct {
+  double step_ms;          /* wall time of the last step */
+  double compute_busy_ms;  /* sum of compute-op durations from events */
+  double d2h_ms, h2d_ms;   /* busy time of the copy streams */
+  uint64_t bytes_d2h, bytes_h2d;
+  uint64_t arena_peak_bytes;
+  double host_opt_ms;      /* host optimiser wall time */
+} karma_step_stats;
+int karma_get_stats(karma_ctx* ctx, karma_step_stats* out);
+
+/* ---- single kernels (device pointers, launched on `stream`, asynchronous) --------
+ * Exposed so that each can be checked against the CPU oracle on its own.  Shapes are
+ * row-major.  bf16 tensors are uint16_t bit patterns. */
+
+/* fp32 fully connected layer with ReLU (Sec. III-C): z = x W^T + b, y = max(z, 0).
+ * x [m,k], w [n,k], b [n], z and y [m,n]. */
+int karma_k_linear_relu_fwd_f32(const float* x_dev, const float* w_dev, const float* b_dev, float* z_dev,
+                                float* y_dev, uint32_t m, uint32_t n, uint32_t k, void* stream);
+/* dz = dy * (z > 0); dx = dz W (skipped when dx_dev is NULL); dW = dz^T x; db = colsum dz. */
+int karma_k_linear_relu_bwd_f32(const float* x_dev, const float* w_dev, const float* z_dev, const float* dy_dev,
+                                float* dz_ws_dev, float* dx_dev, float* dw_dev, float* db_dev, uint32_t m,
+                                uint32_t n, uint32_t k, void* stream);
+/* loss = mean((y - t)^2) over n elements, dy = 2 (y - t) / n; partial_ws_dev: >= 1024 floats. */
+int karma_k_mse_f32(const float* y_dev, const float* t_dev, float* dy_dev, float* loss_dev, float* partial_ws_dev,
+                    uint64_t n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KARMA_H */

@@ -1,0 +1,481 @@
+// Planner of the out-of-core training step: timeline simulator, assignment search and
+// stage printing.  Pure host code (no HIP calls), integer arithmetic only.
+//
+// KARMA, Sec. III-E (capacity-based swapping: resident tail, swap-out right after the
+// forward of a block, prefetch in order of need while memory allows), Sec. III-F and
+// Eq. 10 / 10.1 (recompute instead of swap where that shortens the makespan),
+// constraint 9.4 (memory in use never above capacity), Eq. 1 (occupancy), Algorithm 1
+// (stage list).  The paper solves its two integer programs with a stochastic solver; a
+// deterministic local search over the simulator takes its place here.
+#include "planner.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <string>
+
+namespace karma {
+
+static inline int64_t align_up(int64_t b) { return (b + 255) / 256 * 256; }
+
+int64_t copy_ns(uint64_t bytes, uint64_t bw, int64_t lat) {
+  if (bytes == 0) return 0;
+  unsigned __int128 num = (unsigned __int128)bytes * 1000000000ull + (bw - 1);
+  return lat + (int64_t)(num / bw);
+}
+
+// ---- two-ended first-fit allocator ------------------------------------------------
+void Arena::reset(int64_t capacity) {
+  cap = capacity;
+  holes.clear();
+  if (cap > 0) holes.push_back({0, cap});
+  used = 0;
+  peak = 0;
+}
+
+int64_t Arena::take(int64_t size, bool low) {
+  if (low) {
+    for (size_t k = 0; k < holes.size(); ++k) {
+      if (holes[k].size >= size) {
+        int64_t at = holes[k].off;
+        if (holes[k].size == size) holes.erase(holes.begin() + k);
+        else { holes[k].off += size; holes[k].size -= size; }
+        used += size;
+        peak = std::max(peak, used);
+        return at;
+      }
+    }
+  } else {
+    for (size_t k = holes.size(); k-- > 0;) {
+      if (holes[k].size >= size) {
+        int64_t at = holes[k].off + holes[k].size - size;
+        if (holes[k].size == size) holes.erase(holes.begin() + k);
+        else holes[k].size -= size;
+        used += size;
+        peak = std::max(peak, used);
+        return at;
+      }
+    }
+  }
+  return -1;
+}
+
+void Arena::give(int64_t off, int64_t size) {
+  size_t k = 0;
+  while (k < holes.size() && holes[k].off < off) ++k;
+  holes.insert(holes.begin() + k, Hole{off, size});
+  if (k + 1 < holes.size() && holes[k].off + holes[k].size == holes[k + 1].off) {
+    holes[k].size += holes[k + 1].size;
+    holes.erase(holes.begin() + k + 1);
+  }
+  if (k > 0 && holes[k - 1].off + holes[k - 1].size == holes[k].off) {
+    holes[k - 1].size += holes[k].size;
+    holes.erase(holes.begin() + k);
+  }
+  used -= size;
+}
+
+bool actions_valid(const uint8_t* a, uint32_t n) {
+  uint8_t prev = KARMA_KEEP;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (a[i] > KARMA_RC_CHAIN) return false;
+    if (a[i] == KARMA_RC_CHAIN && (i == 0 || prev < KARMA_RC_KEEP)) return false;
+    prev = a[i];
+  }
+  return true;
+}
+
+// ---- timeline simulator -----------------------------------------------------------
+namespace {
+
+struct Timeline {
+  const Problem& P;
+  const uint8_t* act;
+  std::vector<karma_op>* ops;
+  uint32_t L;
+  Arena arena;
+  std::vector<int64_t> x_raw, x_sz, s_sz, w_sz;   // bytes of x_i (raw / aligned), internals, workspace
+  std::vector<int64_t> x_at, s_at, dx_at;        // current offsets, -1 = not allocated
+  struct Pending { int64_t when; int64_t off[2], size[2]; int n; };
+  std::deque<Pending> outgoing;                   // frees that happen when a swap-out ends
+  std::deque<uint32_t> wanted;                    // layers still to prefetch, in order of need
+  std::vector<int64_t> arrival;                   // end of the swap-in of layer i, -1 = not issued
+  int64_t t_comp = 0, t_out = 0, t_in = 0, busy = 0, redo = 0;
+  uint64_t moved_out = 0, moved_in = 0;
+  bool failed = false;
+
+  Timeline(const Problem& p, const uint8_t* a, std::vector<karma_op>* o) : P(p), act(a), ops(o), L(p.n) {}
+
+  void emit(uint8_t kind, uint32_t layer, int64_t s, int64_t e, int64_t a0, int64_t a1, int64_t a2) {
+    if (ops) ops->push_back(karma_op{kind, layer, s, e, {a0, a1, a2}});
+  }
+  void settle(int64_t now) {
+    while (!outgoing.empty() && outgoing.front().when <= now) {
+      const Pending& p = outgoing.front();
+      for (int k = 0; k < p.n; ++k) arena.give(p.off[k], p.size[k]);
+      outgoing.pop_front();
+    }
+  }
+  // allocate; when the arena is full wait for the next swap-out to finish
+  int64_t obtain(int64_t size, bool low, int64_t& now) {
+    if (size == 0 || failed) return -1;
+    for (;;) {
+      int64_t at = arena.take(size, low);
+      if (at >= 0) return at;
+      if (outgoing.empty()) { failed = true; return -1; }
+      const Pending& p = outgoing.front();
+      for (int k = 0; k < p.n; ++k) arena.give(p.off[k], p.size[k]);
+      now = std::max(now, p.when);
+      outgoing.pop_front();
+    }
+  }
+  void drop(int64_t& at, int64_t size) {
+    if (at >= 0) { arena.give(at, size); at = -1; }
+  }
+  bool swapped_whole(uint32_t i) const { return act[i] == KARMA_SWAP; }
+  int64_t move_bytes(uint32_t i) const { return x_raw[i] + (swapped_whole(i) ? (int64_t)P.layers[i].sav_bytes : 0); }
+
+  void start_prefetch(uint32_t i, int64_t now) {
+    int64_t nbytes = move_bytes(i);
+    int64_t s = std::max(t_in, now);
+    t_in = s + copy_ns((uint64_t)nbytes, P.link.bw_h2d, P.link.lat_ns);
+    moved_in += (uint64_t)nbytes;
+    arrival[i] = t_in;
+    emit('I', i, s, t_in, x_at[i], swapped_whole(i) ? s_at[i] : -1, -1);
+  }
+  void prefetch_ahead(int64_t now, int64_t reserve) {
+    settle(now);
+    while (!wanted.empty()) {
+      uint32_t i = wanted.front();
+      int64_t need = x_sz[i] + (swapped_whole(i) ? s_sz[i] : 0);
+      if (arena.cap - arena.used < need + reserve) break;
+      int64_t xa = -1, sa = -1;
+      if (x_sz[i]) { xa = arena.take(x_sz[i], true); if (xa < 0) break; }
+      if (swapped_whole(i) && s_sz[i]) {
+        sa = arena.take(s_sz[i], true);
+        if (sa < 0) { if (xa >= 0) arena.give(xa, x_sz[i]); break; }
+      }
+      x_at[i] = xa;
+      if (swapped_whole(i)) s_at[i] = sa;
+      wanted.pop_front();
+      start_prefetch(i, now);
+    }
+  }
+  int64_t prefetch_now(uint32_t i, int64_t now) {
+    while (arrival[i] < 0 && !failed) {
+      uint32_t j = wanted.front();
+      wanted.pop_front();
+      x_at[j] = obtain(x_sz[j], true, now);
+      if (swapped_whole(j)) s_at[j] = obtain(s_sz[j], true, now);
+      if (!failed) start_prefetch(j, now);
+    }
+    return now;
+  }
+  void backward(uint32_t j, int64_t now, int64_t reserve) {
+    settle(now);
+    dx_at[j] = obtain(x_sz[j], false, now);
+    int64_t w = obtain(w_sz[j], false, now);
+    if (failed) return;
+    int64_t end = now + P.layers[j].tb_ns;
+    busy += P.layers[j].tb_ns;
+    emit('B', j, now, end, dx_at[j], w, -1);
+    t_comp = end;
+    drop(w, w_sz[j]);
+    drop(dx_at[j + 1], x_sz[j + 1]);
+    drop(s_at[j], s_sz[j]);
+    drop(x_at[j], x_sz[j]);
+    prefetch_ahead(t_comp, reserve);
+  }
+
+  bool run(karma_plan_summary* out) {
+    int64_t cap = (int64_t)P.budget - (int64_t)P.fixed;
+    if (cap <= 0) return false;
+    arena.reset(cap);
+    x_raw.assign(L + 1, 0); x_sz.assign(L + 1, 0); s_sz.assign(L, 0); w_sz.assign(L, 0);
+    for (uint32_t i = 0; i < L; ++i) {
+      x_raw[i + 1] = (int64_t)P.layers[i].out_bytes;
+      x_sz[i + 1] = align_up(x_raw[i + 1]);
+      s_sz[i] = align_up((int64_t)P.layers[i].sav_bytes);
+      w_sz[i] = align_up((int64_t)P.layers[i].ws_bytes);
+    }
+    x_at.assign(L + 1, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
+    x_sz.push_back(0);  // x_sz[L+1] so that backward(L-1...) can index j+1 == L safely
+    arrival.assign(L, -1);
+
+    // forward
+    for (uint32_t i = 0; i < L && !failed; ++i) {
+      int64_t now = t_comp;
+      settle(now);
+      x_at[i + 1] = obtain(x_sz[i + 1], true, now);
+      s_at[i] = obtain(s_sz[i], true, now);
+      int64_t w = obtain(w_sz[i], false, now);
+      if (failed) break;
+      int64_t end = now + P.layers[i].tf_ns;
+      busy += P.layers[i].tf_ns;
+      emit('F', i, now, end, x_at[i + 1], s_at[i], w);
+      t_comp = end;
+      drop(w, w_sz[i]);
+      switch (act[i]) {
+        case KARMA_SWAP:
+        case KARMA_RC_SWAP: {
+          int64_t nbytes = move_bytes(i);
+          Pending p{0, {0, 0}, {0, 0}, 0};
+          if (x_at[i] >= 0) { p.off[p.n] = x_at[i]; p.size[p.n] = x_sz[i]; ++p.n; }
+          if (act[i] == KARMA_SWAP && s_at[i] >= 0) { p.off[p.n] = s_at[i]; p.size[p.n] = s_sz[i]; ++p.n; }
+          if (nbytes) {
+            int64_t s = std::max(t_out, end);
+            t_out = s + copy_ns((uint64_t)nbytes, P.link.bw_d2h, P.link.lat_ns);
+            moved_out += (uint64_t)nbytes;
+            p.when = t_out;
+            outgoing.push_back(p);
+            emit('O', i, s, t_out, -1, -1, -1);
+            x_at[i] = -1;
+            if (act[i] == KARMA_SWAP) s_at[i] = -1;
+          }
+          if (act[i] == KARMA_RC_SWAP) drop(s_at[i], s_sz[i]);
+          break;
+        }
+        case KARMA_RC_KEEP: drop(s_at[i], s_sz[i]); break;
+        case KARMA_RC_CHAIN: drop(s_at[i], s_sz[i]); drop(x_at[i], x_sz[i]); break;
+        default: break;
+      }
+    }
+    if (failed) return false;
+
+    // backward units: single KEEP/SWAP layers, or recompute segments head..tail
+    struct Unit { uint32_t head, tail; int64_t need, inner; };
+    std::vector<Unit> units;
+    for (int64_t i = (int64_t)L - 1; i >= 0;) {
+      int64_t h = i;
+      while (act[h] == KARMA_RC_CHAIN) --h;
+      Unit u{(uint32_t)h, (uint32_t)i, 0, 0};
+      if (act[h] <= KARMA_SWAP) {
+        u.need = x_sz[h] + w_sz[h];
+      } else {
+        int64_t held = 0, top = 0;
+        for (int64_t j = h; j <= i; ++j) {
+          held += s_sz[j];
+          if (j < i) held += x_sz[j + 1];
+          top = std::max(top, x_sz[j] + w_sz[j]);
+        }
+        u.need = held + top;
+        u.inner = top;
+      }
+      units.push_back(u);
+      i = h - 1;
+    }
+    std::vector<int64_t> after(units.size(), 0);
+    for (size_t k = units.size(); k-- > 1;) after[k - 1] = std::max(after[k], units[k].need);
+    int64_t any = 0;
+    for (const Unit& u : units) any = std::max(any, u.need);
+    for (int64_t i = (int64_t)L - 1; i >= 0; --i)
+      if ((act[i] == KARMA_SWAP && move_bytes(i) > 0) || (act[i] == KARMA_RC_SWAP && x_raw[i] > 0))
+        wanted.push_back((uint32_t)i);
+
+    // loss
+    int64_t lw_sz = align_up((int64_t)P.loss.ws_bytes);
+    prefetch_ahead(t_comp, std::max(any, x_sz[L] + lw_sz));
+    {
+      int64_t now = t_comp;
+      settle(now);
+      dx_at[L] = obtain(x_sz[L], false, now);
+      int64_t w = obtain(lw_sz, false, now);
+      if (failed) return false;
+      int64_t end = now + P.loss.t_ns;
+      busy += P.loss.t_ns;
+      emit('L', L, now, end, dx_at[L], w, -1);
+      t_comp = end;
+      drop(w, lw_sz);
+      drop(x_at[L], x_sz[L]);
+      prefetch_ahead(t_comp, any);
+    }
+
+    for (size_t k = 0; k < units.size() && !failed; ++k) {
+      const Unit& u = units[k];
+      uint8_t a = act[u.head];
+      int64_t now = t_comp;
+      bool moved = (a == KARMA_SWAP && move_bytes(u.head) > 0) || (a == KARMA_RC_SWAP && x_raw[u.head] > 0);
+      if (moved) {
+        now = prefetch_now(u.head, now);
+        if (failed) break;
+        now = std::max(now, arrival[u.head]);
+      }
+      if (a <= KARMA_SWAP) {
+        backward(u.head, now, after[k]);
+        continue;
+      }
+      for (uint32_t j = u.head; j <= u.tail && !failed; ++j) {
+        settle(now);
+        s_at[j] = obtain(s_sz[j], true, now);
+        if (j < u.tail) x_at[j + 1] = obtain(x_sz[j + 1], true, now);
+        int64_t w = obtain(w_sz[j], false, now);
+        if (failed) break;
+        int64_t end = now + P.layers[j].trc_ns;
+        busy += P.layers[j].trc_ns;
+        redo += P.layers[j].trc_ns;
+        emit('R', j, now, end, s_at[j], j < u.tail ? x_at[j + 1] : -1, w);
+        t_comp = end;
+        drop(w, w_sz[j]);
+        now = end;
+      }
+      for (int64_t j = u.tail; j >= (int64_t)u.head && !failed; --j)
+        backward((uint32_t)j, t_comp, j == (int64_t)u.head ? after[k] : std::max(after[k], u.inner));
+    }
+    if (failed) return false;
+    int64_t endall = std::max(t_comp, std::max(t_out, t_in));
+    if (out) {
+      out->makespan_ns = endall;
+      out->stall_ns = t_comp - busy;
+      out->busy_ns = busy;
+      out->recompute_ns = redo;
+      out->peak_bytes = P.fixed + (uint64_t)arena.peak;
+      out->bytes_d2h = moved_out;
+      out->bytes_h2d = moved_in;
+    }
+    return true;
+  }
+};
+
+struct Cost {
+  int64_t makespan; uint64_t moved; int64_t redo;
+  bool operator<(const Cost& o) const {
+    if (makespan != o.makespan) return makespan < o.makespan;
+    if (moved != o.moved) return moved < o.moved;
+    return redo < o.redo;
+  }
+  bool operator==(const Cost& o) const { return makespan == o.makespan && moved == o.moved && redo == o.redo; }
+};
+
+bool evaluate(const Problem& P, const std::vector<uint8_t>& a, Cost& c) {
+  karma_plan_summary s;
+  if (!actions_valid(a.data(), P.n)) return false;
+  Timeline tl(P, a.data(), nullptr);
+  if (!tl.run(&s)) return false;
+  c = Cost{s.makespan_ns, s.bytes_d2h + s.bytes_h2d, s.recompute_ns};
+  return true;
+}
+
+struct Incumbent {
+  Cost cost; std::vector<uint8_t> act;
+  bool beaten_by(const Cost& c, const std::vector<uint8_t>& a) const {
+    if (c < cost) return true;
+    if (!(c == cost)) return false;
+    return a < act;   // lexicographic
+  }
+};
+
+// Local search: single-layer changes, exchanges of two layers' actions, pairs of
+// neighbouring layers; repeated until a whole round changes nothing.
+void improve(const Problem& P, Incumbent& inc) {
+  const uint32_t L = P.n;
+  auto attempt = [&](const std::vector<uint8_t>& cand) {
+    Cost c;
+    if (evaluate(P, cand, c) && inc.beaten_by(c, cand)) { inc.cost = c; inc.act = cand; return true; }
+    return false;
+  };
+  bool moved = true;
+  std::vector<uint8_t> cand;
+  while (moved) {
+    moved = false;
+    for (uint32_t i = 0; i < L; ++i)
+      for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
+        if (a != inc.act[i]) { cand = inc.act; cand[i] = a; moved |= attempt(cand); }
+    for (uint32_t i = 0; i < L; ++i)
+      for (uint32_t j = i + 1; j < L; ++j)
+        if (inc.act[i] != inc.act[j]) { cand = inc.act; std::swap(cand[i], cand[j]); moved |= attempt(cand); }
+    for (uint32_t i = 0; i + 1 < L; ++i)
+      for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
+        for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b)
+          if (a != inc.act[i] || b != inc.act[i + 1]) { cand = inc.act; cand[i] = a; cand[i + 1] = b; moved |= attempt(cand); }
+  }
+}
+
+}  // namespace
+
+bool simulate(const Problem& P, const uint8_t* actions, karma_plan_summary* out, std::vector<karma_op>* ops) {
+  Timeline tl(P, actions, ops);
+  return tl.run(out);
+}
+
+bool plan(const Problem& P, std::vector<uint8_t>& actions, karma_plan_summary* out) {
+  const uint32_t L = P.n;
+  Cost c;
+  actions.assign(L, KARMA_KEEP);
+  if (evaluate(P, actions, c)) return simulate(P, actions.data(), out, nullptr);   // everything fits
+
+  // capacity rule: the longest resident tail for a given treatment of the prefix
+  auto longest_tail = [&](uint8_t fill, std::vector<uint8_t>& res) {
+    for (uint32_t k = 1; k <= L; ++k) {
+      res.assign(L, KARMA_KEEP);
+      for (uint32_t i = 0; i < k; ++i) res[i] = fill;
+      if (fill == KARMA_RC_CHAIN) res[0] = KARMA_RC_KEEP;
+      if (evaluate(P, res, c)) return true;
+    }
+    return false;
+  };
+  std::vector<std::vector<uint8_t>> starts;
+  std::vector<uint8_t> s;
+  if (longest_tail(KARMA_SWAP, s)) starts.push_back(s);
+  if (longest_tail(KARMA_RC_KEEP, s)) starts.push_back(s);
+  if (starts.empty()) {
+    if (!longest_tail(KARMA_RC_CHAIN, s)) return false;
+    starts.push_back(s);
+  }
+  // Eq. 10.1: recompute where it is cheaper than the swap-in it replaces
+  {
+    std::vector<uint8_t>& cur = starts[0];
+    for (int64_t i = (int64_t)L - 1; i >= 0; --i) {
+      if (cur[i] != KARMA_SWAP) continue;
+      uint64_t xin = i ? P.layers[i - 1].out_bytes : 0;
+      int64_t t_in = copy_ns(xin + P.layers[i].sav_bytes, P.link.bw_h2d, P.link.lat_ns);
+      if (P.layers[i].trc_ns < t_in) {
+        for (uint8_t a : {(uint8_t)KARMA_RC_KEEP, (uint8_t)KARMA_RC_SWAP}) {
+          std::vector<uint8_t> cand = cur;
+          cand[i] = a;
+          if (evaluate(P, cand, c)) { cur = cand; break; }
+        }
+      }
+    }
+  }
+  bool have = false;
+  Incumbent best;
+  for (auto& st : starts) {
+    Incumbent inc;
+    inc.act = st;
+    if (!evaluate(P, st, inc.cost)) continue;
+    improve(P, inc);
+    if (!have || best.beaten_by(inc.cost, inc.act)) { best = inc; have = true; }
+  }
+  if (!have) return false;
+  actions = best.act;
+  return simulate(P, actions.data(), out, nullptr);
+}
+
+// Algorithm 1's notation.  A copy is printed on the stage that is running when the copy
+// starts; recompute stages are inserted as fresh stages and carry no copies.
+std::string stage_string(const karma_op* ops, uint32_t n) {
+  std::vector<uint32_t> stages;
+  for (uint32_t k = 0; k < n; ++k)
+    if (ops[k].kind == 'F' || ops[k].kind == 'B' || ops[k].kind == 'R') stages.push_back(k);
+  std::vector<std::string> text(stages.size());
+  for (size_t s = 0; s < stages.size(); ++s) {
+    const karma_op& o = ops[stages[s]];
+    text[s] = std::string(o.kind == 'B' ? "B" : "F") + std::to_string(o.layer + 1);
+  }
+  for (uint32_t k = 0; k < n; ++k) {
+    if (ops[k].kind != 'I' && ops[k].kind != 'O') continue;
+    if (stages.empty()) break;
+    size_t at = stages.size() - 1;
+    for (size_t s = 0; s < stages.size(); ++s) {
+      const karma_op& o = ops[stages[s]];
+      if (o.kind != 'R' && o.end_ns > ops[k].start_ns) { at = s; break; }
+    }
+    text[at] += "||S" + std::to_string(ops[k].layer + 1) + (ops[k].kind == 'I' ? "^in" : "^out");
+  }
+  std::string res;
+  for (size_t s = 0; s < text.size(); ++s) { if (s) res += " -> "; res += text[s]; }
+  return res;
+}
+
+}  // namespace karma

@@ -1,0 +1,91 @@
+"""Acceptance (a): the library planner and simulator agree with the oracle bit for bit.
+CPU only: the planner entry points need no GPU."""
+import pytest
+
+import paper_2008_11421_amd as K
+from oracle import planner as P
+import synth_inputs as si
+from test_oracle_planner import cases, golden_schedule, mk, six_block_model
+
+KIND = {"F": "F", "B": "B", "R": "R", "L": "L", "OUT": "O", "IN": "I"}
+
+
+def ops_equal(lib_ops, ora_ops):
+    assert len(lib_ops) == len(ora_ops)
+    for a, b in zip(lib_ops, ora_ops):
+        assert chr(a.kind) == KIND[b.kind] and a.layer == b.layer
+        assert (a.start_ns, a.end_ns) == (b.start, b.end)
+        offs = [(-1 if o is None else o) for o in b.offs] + [-1] * (3 - len(b.offs))
+        assert list(a.off) == offs
+
+
+def summaries_equal(s_lib, s_ora):
+    for k in ("makespan_ns", "stall_ns", "busy_ns", "recompute_ns", "peak_bytes", "bytes_d2h", "bytes_h2d"):
+        assert s_lib[k] == s_ora[k], k
+
+
+def all_vectors(L, stride, seed):
+    """A deterministic sample of valid action vectors."""
+    r = [int(v) for v in si.splitmix64(seed, 400 * L)]
+    for k in range(0, len(r) - L, L * stride):
+        v = [r[k + i] % 5 for i in range(L)]
+        if P.valid_actions(v):
+            yield v
+
+
+def test_simulator_bit_exact_on_random_vectors():
+    n = 0
+    for layers, link, budget, loss in cases(7, seeds=(3,), fracs=(0.4, 0.9), bwmuls=(0.5, 3.0)):
+        for v in all_vectors(7, 1, 17):
+            try:
+                so = P.simulate(layers, link, budget, 0, loss, v, want_ops=True)
+            except P.Infeasible:
+                with pytest.raises(K.KarmaError) as e:
+                    K.karma_simulate(layers, link, loss, budget, 0, v)
+                assert e.value.status == K.E_BUDGET
+                continue
+            sl, ops = K.karma_simulate(layers, link, loss, budget, 0, v, want_ops=True)
+            summaries_equal(sl, so)
+            ops_equal(ops, so["ops"])
+            assert K.karma_stage_string(ops) == P.stage_string(so["ops"])
+            n += 1
+    assert n > 200
+
+
+def test_plan_bit_exact_on_random_stacks():
+    for L, seeds in ((6, (0, 1, 2)), (11, (4,))):
+        for layers, link, budget, loss in cases(L, seeds=seeds, fracs=(0.35, 0.7)):
+            try:
+                ao, so = P.plan(layers, link, budget, 0, loss)
+            except P.Infeasible:
+                with pytest.raises(K.KarmaError):
+                    K.karma_plan_pure(layers, link, loss, budget, 0)
+                continue
+            al, sl = K.karma_plan_pure(layers, link, loss, budget, 0)
+            assert al == ao
+            summaries_equal(sl, so)
+
+
+def test_worked_example_through_library():
+    layers, link, loss = six_block_model()
+    acts = [K.SWAP, K.RC_KEEP, K.SWAP, K.RC_KEEP, K.KEEP, K.KEEP]
+    s, ops = K.karma_simulate(layers, link, loss, 10**6, 0, acts, want_ops=True)
+    assert K.karma_stage_string(ops) == golden_schedule()
+    assert s["stall_ns"] == 0 and s["makespan_ns"] == 14000
+
+
+def test_fixed_region_and_errors():
+    layers = mk(1, 4, "homogeneous")
+    link, loss = (10**9, 10**9, 0), (0, 0)
+    with pytest.raises(K.KarmaError) as e:
+        K.karma_plan_pure(layers, link, loss, 4096, 0)
+    assert e.value.status == K.E_BUDGET
+    with pytest.raises(K.KarmaError) as e:
+        K.karma_simulate(layers, link, loss, 10**6, 0, [4, 0, 0, 0])
+    assert e.value.status == K.E_INVAL
+    with pytest.raises(K.KarmaError) as e:
+        K.karma_simulate(layers, (0, 1, 0), loss, 10**6, 0, [0, 0, 0, 0])
+    assert e.value.status == K.E_INVAL
+    s1 = K.karma_simulate(layers, link, loss, 10**6 + 5000, 5000, [0] * 4)
+    s0 = P.simulate([P.Layer(*l) for l in layers], P.Link(*link), 10**6 + 5000, 5000, P.Loss(*loss), [0] * 4)
+    summaries_equal(s1, s0)
