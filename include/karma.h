@@ -183,14 +183,13 @@ int karma_set_plan(karma_ctx* ctx, uint64_t budget_bytes, const uint8_t* actions
 int karma_plan_string(karma_ctx* ctx, char* buf, size_t buf_len);
 
 #define KARMA_STEP_APPLY_OPTIMIZER 1u /* D2H gradients, host update of the master weights, H2D new weights */
+#define KARMA_STEP_PROFILE 2u         /* events around every op; read with karma_get_op_times / karma_get_stats */
 /* One training step.  MLP: inputs_host fp32 [batch, width], labels_host fp32 targets of
  * the same shape.  GPT: inputs_host int32 token ids [batch, seq], labels_host int32
  * [batch, seq].  Synchronous: on return the loss is valid, all streams are drained and
  * gradients can be read. */
 int karma_step(karma_ctx* ctx, const void* inputs_host, const void* labels_host, uint32_t flags, float* loss_out);
 
-/* Debug read-back of the hidden state that entered record `layer` in the last step
- * (only for records whose input is still resident or swapped: not RC_CHAIN), fp32. */
 typedef struct {
   double step_ms;          /* wall time of the last step */
   double compute_busy_ms;  /* sum of compute-op durations from events */
@@ -200,6 +199,9 @@ typedef struct {
   double host_opt_ms;      /* host optimiser wall time */
 } karma_step_stats;
 int karma_get_stats(karma_ctx* ctx, karma_step_stats* out);
+/* The ops of the current plan (predicted times) and, for the last step run with
+ * KARMA_STEP_PROFILE, their measured durations in ms.  *n_inout: capacity in, count out. */
+int karma_get_op_times(karma_ctx* ctx, karma_op* ops_out, float* ms_out, uint32_t* n_inout);
 
 /* ---- single kernels (device pointers, launched on `stream`, asynchronous) --------
  * Exposed so that each can be checked against the CPU oracle on its own.  Shapes are

@@ -80,11 +80,10 @@ def lib():
             raise OSError("libkarma.so is not built: run `python -m paper_2008_11421_amd.build` "
                           "(there is no CPU fallback)")
         _lib = C.CDLL(LIB_PATH)
-        if hasattr(_lib, "karma_last_error"):
-            _lib.karma_last_error.restype = C.c_char_p
-            _lib.karma_last_error.argtypes = [C.c_void_p]
-            _lib.karma_destroy.restype = None
-            _lib.karma_destroy.argtypes = [C.c_void_p]
+        _lib.karma_last_error.restype = C.c_char_p
+        _lib.karma_last_error.argtypes = [C.c_void_p]
+        _lib.karma_destroy.restype = None
+        _lib.karma_destroy.argtypes = [C.c_void_p]
     return _lib
 
 
@@ -140,3 +139,132 @@ def karma_stage_string(ops):
     buf = C.create_string_buffer(64 * len(ops) + 64)
     _check(lib().karma_stage_string(arr, C.c_uint32(len(ops)), buf, C.c_size_t(len(buf))), "karma_stage_string")
     return buf.value.decode()
+
+
+# ------------------------------------------------------------------ context
+class Context:
+    """One model instance.  torch supplies the device slab and the three streams; every
+    method is the C entry point of the same name with numpy marshalling."""
+
+    def __init__(self, desc, cfg, arena_bytes, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.desc = desc if isinstance(desc, ModelDesc) else ModelDesc(**desc)
+        self.cfg = cfg if isinstance(cfg, Config) else Config(**cfg)
+        self.device = torch.device(device)
+        self.arena = torch.empty(int(arena_bytes), dtype=torch.uint8, device=self.device)
+        assert self.arena.data_ptr() % 256 == 0
+        self.streams = [torch.cuda.Stream(device=self.device) for _ in range(3)]
+        self.ctx = C.c_void_p()
+        n = C.c_uint32()
+        _check(lib().karma_model_layers(C.byref(self.desc), C.byref(n)), "karma_model_layers")
+        self.n_layers = n.value
+        with torch.cuda.device(self.device):
+            st = lib().karma_create(C.byref(self.desc), C.byref(self.cfg), C.c_void_p(self.arena.data_ptr()),
+                                    C.c_uint64(self.arena.numel()),
+                                    C.c_void_p(self.streams[0].cuda_stream), C.c_void_p(self.streams[1].cuda_stream),
+                                    C.c_void_p(self.streams[2].cuda_stream), C.byref(self.ctx))
+        _check(st, "karma_create")
+
+    def close(self):
+        if self.ctx:
+            lib().karma_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, st, where):
+        _check(st, where, self.ctx)
+
+    def karma_param_count(self, layer):
+        n = C.c_uint32()
+        self._chk(lib().karma_param_count(self.ctx, C.c_uint32(layer), C.byref(n)), "karma_param_count")
+        return n.value
+
+    def karma_param_size(self, layer, tensor):
+        n = C.c_uint64()
+        self._chk(lib().karma_param_size(self.ctx, C.c_uint32(layer), C.c_uint32(tensor), C.byref(n)), "karma_param_size")
+        return n.value
+
+    def karma_set_param(self, layer, tensor, values):
+        a = np.ascontiguousarray(values, dtype=np.float32).reshape(-1)
+        self._chk(lib().karma_set_param(self.ctx, C.c_uint32(layer), C.c_uint32(tensor),
+                                        a.ctypes.data_as(C.POINTER(C.c_float)), C.c_uint64(a.size)), "karma_set_param")
+
+    def _get(self, fn, name, layer, tensor):
+        n = self.karma_param_size(layer, tensor)
+        out = np.empty(n, dtype=np.float32)
+        self._chk(fn(self.ctx, C.c_uint32(layer), C.c_uint32(tensor), out.ctypes.data_as(C.POINTER(C.c_float)),
+                     C.c_uint64(n)), name)
+        return out
+
+    def karma_get_param(self, layer, tensor):
+        return self._get(lib().karma_get_param, "karma_get_param", layer, tensor)
+
+    def karma_get_grad(self, layer, tensor):
+        return self._get(lib().karma_get_grad, "karma_get_grad", layer, tensor)
+
+    def karma_get_costs(self):
+        arr = (LayerCost * self.n_layers)()
+        loss = LossCost()
+        fixed = C.c_uint64()
+        self._chk(lib().karma_get_costs(self.ctx, arr, C.byref(loss), C.byref(fixed)), "karma_get_costs")
+        layers = [(l.tf_ns, l.tb_ns, l.trc_ns, l.sav_bytes, l.out_bytes, l.ws_bytes) for l in arr]
+        return layers, (loss.t_ns, loss.ws_bytes), fixed.value
+
+    def karma_set_costs(self, layers=None, loss=None, link=None):
+        arr = _layers_array(layers) if layers is not None else None
+        ls = C.byref(LossCost(*[int(v) for v in loss])) if loss is not None else None
+        lk = C.byref(Link(*[int(v) for v in link])) if link is not None else None
+        self._chk(lib().karma_set_costs(self.ctx, arr, ls, lk), "karma_set_costs")
+
+    def karma_measure(self, reps=3):
+        lk = Link()
+        self._chk(lib().karma_measure(self.ctx, C.c_uint32(reps), C.byref(lk)), "karma_measure")
+        return (lk.bw_h2d, lk.bw_d2h, lk.lat_ns)
+
+    def karma_plan(self, budget):
+        act = (C.c_uint8 * self.n_layers)()
+        summ = PlanSummary()
+        self._chk(lib().karma_plan(self.ctx, C.c_uint64(budget), act, C.byref(summ)), "karma_plan")
+        return list(act), summ.as_dict()
+
+    def karma_set_plan(self, budget, actions):
+        act = (C.c_uint8 * self.n_layers)(*actions)
+        summ = PlanSummary()
+        self._chk(lib().karma_set_plan(self.ctx, C.c_uint64(budget), act, C.byref(summ)), "karma_set_plan")
+        return summ.as_dict()
+
+    def karma_plan_string(self):
+        buf = C.create_string_buffer(1 << 16)
+        self._chk(lib().karma_plan_string(self.ctx, buf, C.c_size_t(len(buf))), "karma_plan_string")
+        return buf.value.decode()
+
+    def karma_step(self, inputs, labels, flags=0):
+        """inputs/labels: numpy arrays of the dtype the model takes (fp32 for the MLP,
+        int32 for GPT).  Returns the loss."""
+        dt = np.float32 if self.desc.kind == MODEL_MLP else np.int32
+        a = np.ascontiguousarray(inputs, dtype=dt)
+        b = np.ascontiguousarray(labels, dtype=dt)
+        loss = C.c_float()
+        with self.torch.cuda.device(self.device):
+            st = lib().karma_step(self.ctx, C.c_void_p(a.ctypes.data), C.c_void_p(b.ctypes.data), C.c_uint32(flags),
+                                  C.byref(loss))
+        self._chk(st, "karma_step")
+        return loss.value
+
+    def karma_get_stats(self):
+        s = StepStats()
+        self._chk(lib().karma_get_stats(self.ctx, C.byref(s)), "karma_get_stats")
+        return s.as_dict()
+
+    def karma_get_op_times(self):
+        n = C.c_uint32(6 * self.n_layers + 2)
+        ops = (Op * n.value)()
+        ms = (C.c_float * n.value)()
+        self._chk(lib().karma_get_op_times(self.ctx, ops, ms, C.byref(n)), "karma_get_op_times")
+        return [(chr(ops[k].kind), ops[k].layer, ops[k].start_ns, ops[k].end_ns, ms[k]) for k in range(n.value)]

@@ -1,0 +1,118 @@
+// Context of one model instance: parameters, fixed-region layout, plan and program.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "host_optim.h"
+#include "karma.h"
+#include "planner.h"
+
+namespace karma {
+
+enum RecordKind { REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11 };
+
+struct Param {
+  uint64_t n = 0;
+  bool dev_bf16 = false;    // device copy of the weight: bf16 (else fp32)
+  bool grad_bf16 = false;   // device gradient: bf16 (else fp32)
+  uint64_t w_off = 0, g_off = 0;   // byte offsets in the fixed region
+  std::vector<float> master, m, v; // host fp32 master copy and optimiser state
+  void* stage_g = nullptr;         // pinned: gradient as it arrives from the device
+  void* stage_w = nullptr;         // pinned: new weight in device format
+  uint64_t w_bytes() const { return n * (dev_bf16 ? 2 : 4); }
+  uint64_t g_bytes() const { return n * (grad_bf16 ? 2 : 4); }
+};
+
+struct Record {
+  int kind = 0;
+  std::vector<Param> p;
+  uint64_t out_bytes = 0, sav_bytes = 0, ws_bytes = 0;   // from shapes
+};
+
+// One op of the executable schedule; offsets are relative to the activation region,
+// -1 = none, -2 = the step input in the fixed region.
+struct ProgOp {
+  char kind;
+  uint32_t layer;
+  int64_t x = -1, s = -1, out = -1, dy = -1, dx = -1, ws = -1;
+  std::vector<uint32_t> waits;
+  bool record = false;
+  int stream = 0;                 // 0 compute, 1 h2d, 2 d2h
+  int64_t host_x = -1, host_s = -1;   // offsets in the pinned swap pool
+  uint64_t x_bytes = 0, s_bytes = 0;  // bytes moved by a swap op
+};
+
+struct Ctx {
+  karma_model_desc desc{};
+  karma_config cfg{};
+  char* arena = nullptr;
+  uint64_t arena_bytes = 0;
+  hipStream_t st[3] = {nullptr, nullptr, nullptr};   // compute, h2d, d2h
+  std::vector<Record> rec;       // plannable records followed by the loss record
+  uint32_t L = 0;                // number of plannable records
+  uint64_t fixed_bytes = 0;
+  uint64_t in_off = 0, lab_off = 0, loss_off = 0, misc_off = 0;   // fixed-region offsets
+  uint64_t in_bytes = 0, lab_bytes = 0, misc_bytes = 0;
+  void* stage_in = nullptr;      // pinned staging of inputs, labels, loss
+  void* stage_lab = nullptr;
+  float* stage_loss = nullptr;
+  void* stage_misc = nullptr;
+
+  std::vector<karma_layer_cost> cost;
+  karma_loss_cost loss_cost{};
+  karma_link link{};
+  bool have_times = false;
+
+  bool planned = false;
+  uint64_t budget = 0;
+  std::vector<uint8_t> actions;
+  std::vector<karma_op> ops;
+  std::vector<ProgOp> prog;
+  karma_plan_summary summary{};
+  std::vector<hipEvent_t> ev, ev_begin;   // per op: end event, begin event (profiling)
+  std::vector<float> op_ms;               // per-op durations of the last profiled step
+  char* swap_pool = nullptr;              // pinned host memory for swapped tensors
+  uint64_t swap_pool_bytes = 0;
+  std::vector<hipEvent_t> grad_ev;        // per record: gradients have landed on the host
+
+  std::unique_ptr<HostPool> pool;
+  uint64_t step_no = 0;
+  karma_step_stats stats{};
+  std::string err;
+
+  char* fixed_ptr(uint64_t off) const { return arena + off; }
+  char* act_ptr(int64_t off) const { return off < 0 ? nullptr : arena + fixed_bytes + off; }
+  void* w_ptr(uint32_t r, uint32_t t) const { return arena + rec[r].p[t].w_off; }
+  void* g_ptr(uint32_t r, uint32_t t) const { return arena + rec[r].p[t].g_off; }
+};
+
+#define KARMA_HIP(ctx, call)                                                                  \
+  do {                                                                                        \
+    hipError_t e_ = (call);                                                                   \
+    if (e_ != hipSuccess) {                                                                   \
+      (ctx)->err = std::string(#call) + ": " + hipGetErrorString(e_);                         \
+      return KARMA_E_HIP;                                                                     \
+    }                                                                                         \
+  } while (0)
+
+// Pointers handed to a layer op.
+struct LayerIO {
+  const void* x = nullptr;   // layer input
+  void* out = nullptr;       // layer output (may be null in a recompute whose output is not needed)
+  void* sav = nullptr;       // internals
+  void* ws = nullptr;        // workspace
+  const void* dy = nullptr;  // gradient w.r.t. the output
+  void* dx = nullptr;        // gradient w.r.t. the input (null for record 0)
+};
+
+// Model-specific pieces (layers_mlp.cpp, layers_gpt.cpp)
+int model_build_records(Ctx& c);                         // fills rec[], sizes, in/lab/misc bytes
+int model_prepare_step(Ctx& c, const void* in, const void* lab);   // host-side per-step preparation into the staging buffers
+int layer_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int layer_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int loss_op(Ctx& c, const LayerIO& io, hipStream_t s);   // x -> loss (fixed region) and dx; accumulates its own parameter gradients
+
+}  // namespace karma

@@ -1,0 +1,607 @@
+// Stream/event executor of the out-of-core training step (KARMA Fig. 2(c), Algorithm 1,
+// Sec. III-G stage 3 and 5).  The plan is compiled once into a static program: every op
+// knows its arena offsets and the ops it must wait for, so a step is a replay that
+// allocates nothing.  Swap-out and prefetch are pinned hipMemcpyAsync calls on their own
+// streams; cross-stream ordering is by events.
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+
+#include "context.h"
+
+using namespace karma;
+
+struct karma_ctx : public Ctx {};
+
+namespace {
+
+inline uint64_t up256(uint64_t b) { return (b + 255) / 256 * 256; }
+
+double now_ms() {
+  return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+int fail(Ctx* c, int code, const std::string& msg) {
+  c->err = msg;
+  return code;
+}
+
+void free_plan_resources(Ctx* c) {
+  for (auto e : c->ev) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_begin) if (e) (void)hipEventDestroy(e);
+  c->ev.clear();
+  c->ev_begin.clear();
+  if (c->swap_pool) (void)hipHostFree(c->swap_pool);
+  c->swap_pool = nullptr;
+  c->swap_pool_bytes = 0;
+  c->planned = false;
+}
+
+// ---- compile the simulated timeline into the executable program ------------------
+struct Released { int64_t off, size; uint32_t op; };
+
+struct Builder {
+  Ctx& c;
+  std::vector<Released> gone;   // ranges of the arena that were freed, with the op that freed them
+  std::vector<int64_t> x_at, s_at, dx_at, x_sz, s_sz, w_sz;
+  explicit Builder(Ctx& ctx) : c(ctx) {}
+
+  // the new tenant of [off, off+size) must wait for whoever released any part of it
+  void claim(ProgOp& op, int64_t off, int64_t size) {
+    if (off < 0 || size == 0) return;
+    std::vector<Released> keep;
+    for (const Released& r : gone) {
+      int64_t lo = std::max(r.off, off), hi = std::min(r.off + r.size, off + size);
+      if (lo >= hi) { keep.push_back(r); continue; }
+      op.waits.push_back(r.op);
+      if (r.off < lo) keep.push_back({r.off, lo - r.off, r.op});
+      if (hi < r.off + r.size) keep.push_back({hi, r.off + r.size - hi, r.op});
+    }
+    gone.swap(keep);
+  }
+  void release(int64_t& off, int64_t size, uint32_t op) {
+    if (off >= 0 && size) gone.push_back({off, size, op});
+    off = -1;
+  }
+
+  int run() {
+    const uint32_t L = c.L;
+    x_sz.assign(L + 2, 0); s_sz.assign(L, 0); w_sz.assign(L, 0);
+    for (uint32_t i = 0; i < L; ++i) {
+      x_sz[i + 1] = (int64_t)up256(c.cost[i].out_bytes);
+      s_sz[i] = (int64_t)up256(c.cost[i].sav_bytes);
+      w_sz[i] = (int64_t)up256(c.cost[i].ws_bytes);
+    }
+    const int64_t lw_sz = (int64_t)up256(c.loss_cost.ws_bytes);
+    x_at.assign(L + 2, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
+    std::vector<int64_t> f_op(L, -1), in_op(L, -1);
+    uint64_t host_top = 0;
+    std::vector<int64_t> host_x(L, -1), host_s(L, -1);
+    c.prog.clear();
+    c.prog.reserve(c.ops.size());
+    for (uint32_t k = 0; k < c.ops.size(); ++k) {
+      const karma_op& o = c.ops[k];
+      ProgOp p;
+      p.kind = (char)o.kind;
+      p.layer = o.layer;
+      const uint32_t i = o.layer;
+      const uint8_t a = i < L ? c.actions[i] : 0;
+      switch (o.kind) {
+        case 'F':
+          p.stream = 0;
+          p.x = i == 0 ? -2 : x_at[i];
+          p.out = o.off[0]; p.s = o.off[1]; p.ws = o.off[2];
+          claim(p, p.out, x_sz[i + 1]); claim(p, p.s, s_sz[i]); claim(p, p.ws, w_sz[i]);
+          x_at[i + 1] = p.out; s_at[i] = p.s;
+          f_op[i] = k;
+          { int64_t w = p.ws; release(w, w_sz[i], k); }
+          if (a == KARMA_RC_KEEP || a == KARMA_RC_CHAIN) release(s_at[i], s_sz[i], k);
+          if (a == KARMA_RC_CHAIN) release(x_at[i], x_sz[i], k);
+          if (a == KARMA_RC_SWAP) release(s_at[i], s_sz[i], k);
+          break;
+        case 'O':
+          p.stream = 2;
+          p.x = x_at[i];
+          p.x_bytes = i ? c.cost[i - 1].out_bytes : 0;
+          if (a == KARMA_SWAP) { p.s = s_at[i]; p.s_bytes = c.cost[i].sav_bytes; }
+          if (p.x < 0) p.x_bytes = 0;
+          if (p.s < 0) p.s_bytes = 0;
+          p.waits.push_back((uint32_t)f_op[i]);
+          if (p.x_bytes) { host_x[i] = (int64_t)host_top; host_top += up256(p.x_bytes); }
+          if (p.s_bytes) { host_s[i] = (int64_t)host_top; host_top += up256(p.s_bytes); }
+          p.host_x = host_x[i]; p.host_s = host_s[i];
+          release(x_at[i], x_sz[i], k);
+          if (a == KARMA_SWAP) release(s_at[i], s_sz[i], k);
+          break;
+        case 'I':
+          p.stream = 1;
+          p.x = o.off[0]; p.s = o.off[1];
+          p.x_bytes = p.x >= 0 ? c.cost[i - 1].out_bytes : 0;
+          p.s_bytes = p.s >= 0 ? c.cost[i].sav_bytes : 0;
+          p.host_x = host_x[i]; p.host_s = host_s[i];
+          claim(p, p.x, x_sz[i]); claim(p, p.s, s_sz[i]);
+          x_at[i] = p.x;
+          if (a == KARMA_SWAP) s_at[i] = p.s;
+          in_op[i] = k;
+          break;
+        case 'L':
+          p.stream = 0;
+          p.x = x_at[L]; p.dx = o.off[0]; p.ws = o.off[1];
+          claim(p, p.dx, x_sz[L]); claim(p, p.ws, lw_sz);
+          dx_at[L] = p.dx;
+          { int64_t w = p.ws; release(w, lw_sz, k); }
+          release(x_at[L], x_sz[L], k);
+          p.record = true;
+          break;
+        case 'R':
+          p.stream = 0;
+          p.x = i == 0 ? -2 : x_at[i];
+          p.s = o.off[0]; p.out = o.off[1]; p.ws = o.off[2];
+          claim(p, p.s, s_sz[i]); claim(p, p.out, x_sz[i + 1]); claim(p, p.ws, w_sz[i]);
+          s_at[i] = p.s;
+          if (p.out >= 0) x_at[i + 1] = p.out;
+          if (in_op[i] >= 0) p.waits.push_back((uint32_t)in_op[i]);
+          { int64_t w = p.ws; release(w, w_sz[i], k); }
+          break;
+        case 'B':
+          p.stream = 0;
+          p.x = i == 0 ? -2 : x_at[i];
+          p.s = s_at[i]; p.dy = dx_at[i + 1]; p.dx = o.off[0]; p.ws = o.off[1];
+          claim(p, p.dx, x_sz[i]); claim(p, p.ws, w_sz[i]);
+          dx_at[i] = p.dx;
+          if (in_op[i] >= 0) p.waits.push_back((uint32_t)in_op[i]);
+          { int64_t w = p.ws; release(w, w_sz[i], k); }
+          release(dx_at[i + 1], x_sz[i + 1], k);
+          release(s_at[i], s_sz[i], k);
+          if (i) release(x_at[i], x_sz[i], k);
+          p.record = true;
+          break;
+        default:
+          return KARMA_E_INVAL;
+      }
+      c.prog.push_back(std::move(p));
+    }
+    // only cross-stream waits need events
+    for (ProgOp& p : c.prog) {
+      std::vector<uint32_t> w;
+      for (uint32_t d : p.waits)
+        if (c.prog[d].stream != p.stream && std::find(w.begin(), w.end(), d) == w.end()) {
+          w.push_back(d);
+          c.prog[d].record = true;
+        }
+      p.waits.swap(w);
+    }
+    c.swap_pool_bytes = host_top;
+    return KARMA_OK;
+  }
+};
+
+int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions) {
+  if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
+  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
+  std::vector<karma_op> ops;
+  karma_plan_summary s;
+  if (!actions_valid(actions.data(), c->L)) return fail(c, KARMA_E_INVAL, "invalid action vector");
+  if (!simulate(P, actions.data(), &s, &ops)) return fail(c, KARMA_E_BUDGET, "assignment does not fit the budget");
+  free_plan_resources(c);
+  c->actions = actions;
+  c->ops = ops;
+  c->summary = s;
+  c->budget = budget;
+  Builder b(*c);
+  int st = b.run();
+  if (st) return fail(c, st, "schedule compilation failed");
+  if (c->swap_pool_bytes) {
+    if (hipHostMalloc((void**)&c->swap_pool, c->swap_pool_bytes, hipHostMallocDefault) != hipSuccess)
+      return fail(c, KARMA_E_HOSTMEM, "pinned swap pool allocation failed");
+  }
+  c->ev.assign(c->prog.size(), nullptr);
+  c->ev_begin.assign(c->prog.size(), nullptr);
+  for (size_t k = 0; k < c->prog.size(); ++k) {
+    KARMA_HIP(c, hipEventCreate(&c->ev[k]));
+    KARMA_HIP(c, hipEventCreate(&c->ev_begin[k]));
+  }
+  c->op_ms.assign(c->prog.size(), 0.f);
+  c->planned = true;
+  return KARMA_OK;
+}
+
+int issue(Ctx* c, const ProgOp& p) {
+  hipStream_t s = c->st[p.stream];
+  LayerIO io;
+  io.x = p.x == -2 ? (const void*)c->fixed_ptr(c->in_off) : (const void*)c->act_ptr(p.x);
+  io.out = c->act_ptr(p.out);
+  io.sav = c->act_ptr(p.s);
+  io.ws = c->act_ptr(p.ws);
+  io.dy = c->act_ptr(p.dy);
+  io.dx = c->act_ptr(p.dx);
+  switch (p.kind) {
+    case 'F':
+    case 'R': return layer_forward(*c, p.layer, io, s);
+    case 'B': return layer_backward(*c, p.layer, io, s);
+    case 'L': return loss_op(*c, io, s);
+    case 'O':
+      if (p.x_bytes) KARMA_HIP(c, hipMemcpyAsync(c->swap_pool + p.host_x, c->act_ptr(p.x), p.x_bytes, hipMemcpyDeviceToHost, s));
+      if (p.s_bytes) KARMA_HIP(c, hipMemcpyAsync(c->swap_pool + p.host_s, c->act_ptr(p.s), p.s_bytes, hipMemcpyDeviceToHost, s));
+      return KARMA_OK;
+    case 'I':
+      if (p.x_bytes) KARMA_HIP(c, hipMemcpyAsync(c->act_ptr(p.x), c->swap_pool + p.host_x, p.x_bytes, hipMemcpyHostToDevice, s));
+      if (p.s_bytes) KARMA_HIP(c, hipMemcpyAsync(c->act_ptr(p.s), c->swap_pool + p.host_s, p.s_bytes, hipMemcpyHostToDevice, s));
+      return KARMA_OK;
+  }
+  return KARMA_E_INVAL;
+}
+
+// gradients of one record: device -> pinned host, after the op that completed them
+int send_grads(Ctx* c, uint32_t r, hipEvent_t after) {
+  hipStream_t s = c->st[2];
+  KARMA_HIP(c, hipStreamWaitEvent(s, after, 0));
+  for (Param& p : c->rec[r].p)
+    KARMA_HIP(c, hipMemcpyAsync(p.stage_g, c->arena + p.g_off, p.g_bytes(), hipMemcpyDeviceToHost, s));
+  KARMA_HIP(c, hipEventRecord(c->grad_ev[r], s));
+  return KARMA_OK;
+}
+
+// host update of one record's master weights, then the new device weights go back
+int update_record(Ctx* c, uint32_t r) {
+  KARMA_HIP(c, hipEventSynchronize(c->grad_ev[r]));
+  double t0 = now_ms();
+  for (Param& p : c->rec[r].p) {
+    const karma_config& g = c->cfg;
+    const uint64_t step = c->step_no;
+    c->pool->parallel_for(p.n, [&](size_t lo, size_t hi) {
+      const char* gp = (const char*)p.stage_g + lo * (p.grad_bf16 ? 2 : 4);
+      char* wp = (char*)p.stage_w + lo * (p.dev_bf16 ? 2 : 4);
+      if (g.optimizer == KARMA_OPT_ADAM)
+        adam_update(p.master.data() + lo, p.m.data() + lo, p.v.data() + lo, gp, p.grad_bf16, hi - lo, g.lr, g.beta1,
+                    g.beta2, g.eps, step, wp, p.dev_bf16);
+      else
+        sgd_update(p.master.data() + lo, gp, p.grad_bf16, hi - lo, g.lr, wp, p.dev_bf16);
+    });
+  }
+  c->stats.host_opt_ms += now_ms() - t0;
+  for (Param& p : c->rec[r].p)
+    KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off, p.stage_w, p.w_bytes(), hipMemcpyHostToDevice, c->st[1]));
+  return KARMA_OK;
+}
+
+int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out, bool profile) {
+  if (!c->planned) return fail(c, KARMA_E_STATE, "karma_step before karma_plan / karma_set_plan");
+  const bool apply = flags & KARMA_STEP_APPLY_OPTIMIZER;
+  double t0 = now_ms();
+  c->stats = karma_step_stats{};
+  int st = model_prepare_step(*c, in, lab);
+  if (st) return st;
+  hipStream_t sc = c->st[0];
+  KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->in_off), c->stage_in, c->in_bytes, hipMemcpyHostToDevice, sc));
+  KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->lab_off), c->stage_lab, c->lab_bytes, hipMemcpyHostToDevice, sc));
+  if (c->misc_bytes)
+    KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->misc_off), c->stage_misc, c->misc_bytes, hipMemcpyHostToDevice, sc));
+  if (apply) ++c->step_no;
+  std::vector<uint32_t> done_order;
+  for (size_t k = 0; k < c->prog.size(); ++k) {
+    const ProgOp& p = c->prog[k];
+    hipStream_t s = c->st[p.stream];
+    for (uint32_t d : p.waits) KARMA_HIP(c, hipStreamWaitEvent(s, c->ev[d], 0));
+    if (profile) KARMA_HIP(c, hipEventRecord(c->ev_begin[k], s));
+    st = issue(c, p);
+    if (st) return st;
+    if (p.record || profile) KARMA_HIP(c, hipEventRecord(c->ev[k], s));
+    if (apply && (p.kind == 'L' || p.kind == 'B')) {
+      uint32_t r = p.kind == 'L' ? c->L : p.layer;
+      // gradients of a record are complete after its backward; a tied tensor that several
+      // records add to is owned by the record that finishes last
+      if (!c->rec[r].p.empty()) {
+        st = send_grads(c, r, c->ev[k]);
+        if (st) return st;
+        done_order.push_back(r);
+      }
+    }
+  }
+  KARMA_HIP(c, hipMemcpyAsync(c->stage_loss, c->fixed_ptr(c->loss_off), sizeof(float), hipMemcpyDeviceToHost, sc));
+  for (uint32_t r : done_order) {
+    st = update_record(c, r);
+    if (st) return st;
+  }
+  for (int k = 0; k < 3; ++k) KARMA_HIP(c, hipStreamSynchronize(c->st[k]));
+  if (loss_out) *loss_out = *c->stage_loss;
+  c->stats.step_ms = now_ms() - t0;
+  c->stats.bytes_d2h = c->summary.bytes_d2h;
+  c->stats.bytes_h2d = c->summary.bytes_h2d;
+  c->stats.arena_peak_bytes = c->summary.peak_bytes;
+  if (profile) {
+    for (size_t k = 0; k < c->prog.size(); ++k) {
+      float ms = 0.f;
+      KARMA_HIP(c, hipEventElapsedTime(&ms, c->ev_begin[k], c->ev[k]));
+      c->op_ms[k] = ms;
+      int sidx = c->prog[k].stream;
+      if (sidx == 0) c->stats.compute_busy_ms += ms;
+      else if (sidx == 1) c->stats.h2d_ms += ms;
+      else c->stats.d2h_ms += ms;
+    }
+  }
+  return KARMA_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+extern "C" int karma_model_layers(const karma_model_desc* d, uint32_t* n_out) {
+  if (!d || !n_out) return KARMA_E_INVAL;
+  if (d->kind == KARMA_MODEL_MLP) *n_out = d->n_layers;
+  else if (d->kind == KARMA_MODEL_GPT) *n_out = d->n_layers + 1;
+  else return KARMA_E_INVAL;
+  return KARMA_OK;
+}
+
+extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cfg, void* arena_dev,
+                            uint64_t arena_bytes, void* stream_compute, void* stream_h2d, void* stream_d2h,
+                            karma_ctx** out) {
+  if (!desc || !cfg || !arena_dev || !out) return KARMA_E_INVAL;
+  if (((uintptr_t)arena_dev & 255) != 0) return KARMA_E_INVAL;
+  if (cfg->optimizer != KARMA_OPT_SGD && cfg->optimizer != KARMA_OPT_ADAM) return KARMA_E_INVAL;
+  karma_ctx* c = new (std::nothrow) karma_ctx();
+  if (!c) return KARMA_E_HOSTMEM;
+  c->desc = *desc;
+  c->cfg = *cfg;
+  c->arena = (char*)arena_dev;
+  c->arena_bytes = arena_bytes;
+  c->st[0] = (hipStream_t)stream_compute;
+  c->st[1] = (hipStream_t)stream_h2d;
+  c->st[2] = (hipStream_t)stream_d2h;
+  int st = model_build_records(*c);
+  if (st) { delete c; return st; }
+  c->L = (uint32_t)c->rec.size() - 1;
+  // fixed-region layout: weights, gradients, inputs, labels, loss, misc
+  uint64_t off = 0;
+  for (Record& r : c->rec)
+    for (Param& p : r.p) {
+      p.w_off = off; off += up256(p.w_bytes());
+      p.g_off = off; off += up256(p.g_bytes());
+    }
+  c->in_off = off; off += up256(c->in_bytes);
+  c->lab_off = off; off += up256(c->lab_bytes);
+  c->loss_off = off; off += 256;
+  c->misc_off = off; off += up256(c->misc_bytes);
+  c->fixed_bytes = off;
+  if (off >= arena_bytes) { delete c; return KARMA_E_OOM; }
+  c->cost.resize(c->L);
+  for (uint32_t i = 0; i < c->L; ++i)
+    c->cost[i] = karma_layer_cost{0, 0, 0, c->rec[i].sav_bytes, c->rec[i].out_bytes, c->rec[i].ws_bytes};
+  c->loss_cost = karma_loss_cost{0, c->rec[c->L].ws_bytes};
+  c->link = karma_link{50000000000ull, 50000000000ull, 10000};
+  // host state
+  bool ok = true;
+  auto pin = [&](void** p, uint64_t bytes) {
+    if (ok && hipHostMalloc(p, bytes ? bytes : 256, hipHostMallocDefault) != hipSuccess) ok = false;
+  };
+  for (Record& r : c->rec)
+    for (Param& p : r.p) {
+      p.master.assign(p.n, 0.f);
+      if (cfg->optimizer == KARMA_OPT_ADAM) { p.m.assign(p.n, 0.f); p.v.assign(p.n, 0.f); }
+      pin(&p.stage_g, p.g_bytes());
+      pin(&p.stage_w, p.w_bytes());
+    }
+  pin(&c->stage_in, c->in_bytes);
+  pin(&c->stage_lab, c->lab_bytes);
+  pin((void**)&c->stage_loss, 256);
+  pin(&c->stage_misc, c->misc_bytes);
+  c->grad_ev.assign(c->rec.size(), nullptr);
+  for (auto& e : c->grad_ev)
+    if (ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) ok = false;
+  if (!ok) { karma_destroy(c); return KARMA_E_HOSTMEM; }
+  c->pool.reset(new HostPool(cfg->host_threads ? cfg->host_threads : 1));
+  *out = c;
+  return KARMA_OK;
+}
+
+extern "C" void karma_destroy(karma_ctx* c) {
+  if (!c) return;
+  for (int k = 0; k < 3; ++k) if (c->st[k] || k == 0) (void)hipStreamSynchronize(c->st[k]);
+  free_plan_resources(c);
+  for (Record& r : c->rec)
+    for (Param& p : r.p) {
+      if (p.stage_g) (void)hipHostFree(p.stage_g);
+      if (p.stage_w) (void)hipHostFree(p.stage_w);
+    }
+  if (c->stage_in) (void)hipHostFree(c->stage_in);
+  if (c->stage_lab) (void)hipHostFree(c->stage_lab);
+  if (c->stage_loss) (void)hipHostFree(c->stage_loss);
+  if (c->stage_misc) (void)hipHostFree(c->stage_misc);
+  for (auto e : c->grad_ev) if (e) (void)hipEventDestroy(e);
+  delete c;
+}
+
+extern "C" const char* karma_last_error(const karma_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+extern "C" int karma_param_count(const karma_ctx* c, uint32_t layer, uint32_t* n) {
+  if (!c || !n || layer >= c->rec.size()) return KARMA_E_INVAL;
+  *n = (uint32_t)c->rec[layer].p.size();
+  return KARMA_OK;
+}
+
+extern "C" int karma_param_size(const karma_ctx* c, uint32_t layer, uint32_t t, uint64_t* n) {
+  if (!c || !n || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
+  *n = c->rec[layer].p[t].n;
+  return KARMA_OK;
+}
+
+extern "C" int karma_set_param(karma_ctx* c, uint32_t layer, uint32_t t, const float* host, uint64_t n) {
+  if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
+  Param& p = c->rec[layer].p[t];
+  if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_set_param: element count mismatch");
+  std::memcpy(p.master.data(), host, n * sizeof(float));
+  if (p.dev_bf16) for (uint64_t i = 0; i < n; ++i) ((uint16_t*)p.stage_w)[i] = f32_to_bf16_rne(host[i]);
+  else std::memcpy(p.stage_w, host, n * sizeof(float));
+  KARMA_HIP(c, hipMemcpy(c->arena + p.w_off, p.stage_w, p.w_bytes(), hipMemcpyHostToDevice));
+  return KARMA_OK;
+}
+
+extern "C" int karma_get_param(karma_ctx* c, uint32_t layer, uint32_t t, float* host, uint64_t n) {
+  if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
+  Param& p = c->rec[layer].p[t];
+  if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_get_param: element count mismatch");
+  std::memcpy(host, p.master.data(), n * sizeof(float));
+  return KARMA_OK;
+}
+
+extern "C" int karma_get_grad(karma_ctx* c, uint32_t layer, uint32_t t, float* host, uint64_t n) {
+  if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
+  Param& p = c->rec[layer].p[t];
+  if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_get_grad: element count mismatch");
+  KARMA_HIP(c, hipMemcpy(p.stage_g, c->arena + p.g_off, p.g_bytes(), hipMemcpyDeviceToHost));
+  if (p.grad_bf16) for (uint64_t i = 0; i < n; ++i) host[i] = bf16_to_f32(((const uint16_t*)p.stage_g)[i]);
+  else std::memcpy(host, p.stage_g, n * sizeof(float));
+  return KARMA_OK;
+}
+
+extern "C" int karma_get_costs(karma_ctx* c, karma_layer_cost* layers, karma_loss_cost* loss, uint64_t* fixed) {
+  if (!c) return KARMA_E_INVAL;
+  if (layers) std::memcpy(layers, c->cost.data(), c->L * sizeof(karma_layer_cost));
+  if (loss) *loss = c->loss_cost;
+  if (fixed) *fixed = c->fixed_bytes;
+  return KARMA_OK;
+}
+
+extern "C" int karma_set_costs(karma_ctx* c, const karma_layer_cost* layers, const karma_loss_cost* loss,
+                               const karma_link* link) {
+  if (!c) return KARMA_E_INVAL;
+  if (layers)
+    for (uint32_t i = 0; i < c->L; ++i) {   // bytes stay the library's own: only times are taken
+      c->cost[i].tf_ns = layers[i].tf_ns;
+      c->cost[i].tb_ns = layers[i].tb_ns;
+      c->cost[i].trc_ns = layers[i].trc_ns;
+    }
+  if (loss) c->loss_cost.t_ns = loss->t_ns;
+  if (link) {
+    if (!link->bw_h2d || !link->bw_d2h) return KARMA_E_INVAL;
+    c->link = *link;
+  }
+  c->have_times = true;
+  return KARMA_OK;
+}
+
+extern "C" int karma_plan(karma_ctx* c, uint64_t budget, uint8_t* actions_out, karma_plan_summary* summary_out) {
+  if (!c) return KARMA_E_INVAL;
+  if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
+  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
+  std::vector<uint8_t> a;
+  karma_plan_summary s;
+  if (!plan(P, a, &s)) return fail(c, KARMA_E_BUDGET, "no assignment fits the budget");
+  int st = install_plan(c, budget, a);
+  if (st) return st;
+  if (actions_out) std::memcpy(actions_out, a.data(), c->L);
+  if (summary_out) *summary_out = c->summary;
+  return KARMA_OK;
+}
+
+extern "C" int karma_set_plan(karma_ctx* c, uint64_t budget, const uint8_t* actions, karma_plan_summary* summary_out) {
+  if (!c || !actions) return KARMA_E_INVAL;
+  std::vector<uint8_t> a(actions, actions + c->L);
+  int st = install_plan(c, budget, a);
+  if (st) return st;
+  if (summary_out) *summary_out = c->summary;
+  return KARMA_OK;
+}
+
+extern "C" int karma_plan_string(karma_ctx* c, char* buf, size_t len) {
+  if (!c || !buf) return KARMA_E_INVAL;
+  if (!c->planned) return fail(c, KARMA_E_STATE, "no plan");
+  std::string s = stage_string(c->ops.data(), (uint32_t)c->ops.size());
+  if (s.size() + 1 > len) return KARMA_E_OOM;
+  std::memcpy(buf, s.c_str(), s.size() + 1);
+  return KARMA_OK;
+}
+
+extern "C" int karma_step(karma_ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out) {
+  if (!c || !in || !lab) return KARMA_E_INVAL;
+  return run_step(c, in, lab, flags, loss_out, (flags & KARMA_STEP_PROFILE) != 0);
+}
+
+extern "C" int karma_get_stats(karma_ctx* c, karma_step_stats* out) {
+  if (!c || !out) return KARMA_E_INVAL;
+  *out = c->stats;
+  return KARMA_OK;
+}
+
+extern "C" int karma_get_op_times(karma_ctx* c, karma_op* ops_out, float* ms_out, uint32_t* n_inout) {
+  if (!c || !n_inout) return KARMA_E_INVAL;
+  if (!c->planned) return fail(c, KARMA_E_STATE, "no plan");
+  uint32_t n = (uint32_t)c->ops.size();
+  if (*n_inout < n) { *n_inout = n; return KARMA_E_OOM; }
+  if (ops_out) std::memcpy(ops_out, c->ops.data(), n * sizeof(karma_op));
+  if (ms_out) std::memcpy(ms_out, c->op_ms.data(), n * sizeof(float));
+  *n_inout = n;
+  return KARMA_OK;
+}
+
+// Profiles the model once (Sec. III-D): an in-core step with events around every op gives
+// per-layer times; pinned copies of both directions give the link figures.
+extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) {
+  if (!c) return KARMA_E_INVAL;
+  if (!reps) reps = 3;
+  std::vector<uint8_t> keep(c->L, KARMA_KEEP);
+  int st = install_plan(c, c->arena_bytes, keep);
+  if (st) return st;
+  // inputs: whatever the staging buffers hold (zeros on a fresh context are valid ids / values)
+  std::vector<char> in(c->in_bytes ? c->in_bytes : 1, 0), lab(c->lab_bytes ? c->lab_bytes : 1, 0);
+  std::vector<std::vector<float>> samples(c->prog.size());
+  for (uint32_t r = 0; r < reps + 1; ++r) {
+    float loss;
+    st = run_step(c, in.data(), lab.data(), 0, &loss, true);
+    if (st) return st;
+    if (r == 0) continue;   // warm-up
+    for (size_t k = 0; k < c->prog.size(); ++k) samples[k].push_back(c->op_ms[k]);
+  }
+  for (size_t k = 0; k < c->prog.size(); ++k) {
+    std::sort(samples[k].begin(), samples[k].end());
+    int64_t ns = (int64_t)(samples[k][samples[k].size() / 2] * 1e6);
+    if (ns < 1) ns = 1;
+    const ProgOp& p = c->prog[k];
+    if (p.kind == 'F') { c->cost[p.layer].tf_ns = ns; c->cost[p.layer].trc_ns = ns; }
+    else if (p.kind == 'B') c->cost[p.layer].tb_ns = ns;
+    else if (p.kind == 'L') c->loss_cost.t_ns = ns;
+  }
+  // link: one large and one small pinned copy per direction, on the copy streams
+  uint64_t big = std::min<uint64_t>(256ull << 20, (c->arena_bytes - c->fixed_bytes) / 2 / 256 * 256);
+  if (big >= (1u << 20)) {
+    char* host = nullptr;
+    if (hipHostMalloc((void**)&host, big, hipHostMallocDefault) != hipSuccess) return fail(c, KARMA_E_HOSTMEM, "pinned");
+    std::memset(host, 0, big);
+    hipEvent_t e0, e1;
+    KARMA_HIP(c, hipEventCreate(&e0));
+    KARMA_HIP(c, hipEventCreate(&e1));
+    char* dev = c->act_ptr(0);
+    double bw[2] = {0, 0}, lat[2] = {0, 0};
+    for (int dir = 0; dir < 2; ++dir) {
+      hipStream_t s = c->st[dir == 0 ? 1 : 2];
+      for (int pass = 0; pass < 2; ++pass) {
+        uint64_t nbytes = pass == 0 ? big : 4096;
+        std::vector<float> ms;
+        for (uint32_t r = 0; r < reps + 1; ++r) {
+          KARMA_HIP(c, hipEventRecord(e0, s));
+          if (dir == 0) KARMA_HIP(c, hipMemcpyAsync(dev, host, nbytes, hipMemcpyHostToDevice, s));
+          else KARMA_HIP(c, hipMemcpyAsync(host, dev, nbytes, hipMemcpyDeviceToHost, s));
+          KARMA_HIP(c, hipEventRecord(e1, s));
+          KARMA_HIP(c, hipEventSynchronize(e1));
+          float t;
+          KARMA_HIP(c, hipEventElapsedTime(&t, e0, e1));
+          if (r) ms.push_back(t);
+        }
+        std::sort(ms.begin(), ms.end());
+        double med = ms[ms.size() / 2];
+        if (pass == 0) bw[dir] = (double)nbytes / (med * 1e-3);
+        else lat[dir] = med * 1e6;
+      }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipHostFree(host);
+    c->link.bw_h2d = (uint64_t)bw[0];
+    c->link.bw_d2h = (uint64_t)bw[1];
+    c->link.lat_ns = (int64_t)std::max(lat[0], lat[1]);
+  }
+  c->have_times = true;
+  if (link_out) *link_out = c->link;
+  return KARMA_OK;
+}

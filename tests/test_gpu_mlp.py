@@ -1,0 +1,165 @@
+"""Config 1 on the GPU: fp32 MLP kernels and the swapped/recomputed step against the
+oracle.  Tolerance for fp32 kernels vs the fp64 oracle: relative L2 <= 1e-4 (stated by
+the workload's acceptance criteria); out-of-core vs in-core: bit-identical."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import paper_2008_11421_amd as K
+from oracle import nn, planner as P
+import synth_inputs as si
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    import torch
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+@pytest.mark.parametrize("m,n,k", [(32, 256, 256), (37, 70, 45), (1, 1, 1), (5, 33, 129)])
+def test_linear_relu_kernels(g, m, n, k):
+    import torch
+    x = si.normal(1, (m, k)); w = si.normal(2, (n, k), 0.2); b = si.normal(3, (n,), 0.1); dy = si.normal(4, (m, n))
+    xd, wd, bd, dyd = (g.dev(a, torch.float32) for a in (x, w, b, dy))
+    z = torch.empty(m, n, device="cuda"); y = torch.empty_like(z); dz = torch.empty_like(z)
+    dx = torch.empty(m, k, device="cuda"); dw = torch.empty(n, k, device="cuda"); db = torch.empty(n, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_linear_relu_fwd_f32, g.ptr(xd), g.ptr(wd), g.ptr(bd), g.ptr(z), g.ptr(y), m, n, k, g.stream_ptr())
+    g.call(lib.karma_k_linear_relu_bwd_f32, g.ptr(xd), g.ptr(wd), g.ptr(z), g.ptr(dyd), g.ptr(dz), g.ptr(dx), g.ptr(dw),
+           g.ptr(db), m, n, k, g.stream_ptr())
+    x32, w32, b32, dy32 = (a.astype(np.float32).astype(np.float64) for a in (x, w, b, dy))
+    zo = nn.linear_fwd(x32, w32, b32)
+    assert g.rel_l2(z.cpu().numpy(), zo) <= TOL
+    assert g.rel_l2(y.cpu().numpy(), nn.relu_fwd(zo)) <= TOL
+    # the ReLU decision is taken on the kernel's own fp32 z on both sides
+    dzo = nn.relu_bwd(z.cpu().numpy().astype(np.float64), dy32)
+    dxo, dwo, dbo = nn.linear_bwd(x32, w32, dzo)
+    assert g.rel_l2(dx.cpu().numpy(), dxo) <= TOL
+    assert g.rel_l2(dw.cpu().numpy(), dwo) <= TOL
+    assert g.rel_l2(db.cpu().numpy(), dbo) <= TOL
+
+
+@pytest.mark.parametrize("n", [1, 255, 8192, 300001])
+def test_mse_kernel(g, n):
+    import torch
+    y = si.normal(5, (n,)); t = si.normal(6, (n,))
+    yd, td = g.dev(y, torch.float32), g.dev(t, torch.float32)
+    dy = torch.empty(n, device="cuda"); loss = torch.zeros(1, device="cuda"); part = torch.empty(1024, device="cuda")
+    g.call(K.lib().karma_k_mse_f32, g.ptr(yd), g.ptr(td), g.ptr(dy), g.ptr(loss), g.ptr(part), C.c_uint64(n), g.stream_ptr())
+    lo, dyo = nn.mse_fwd_bwd(y.astype(np.float32).astype(np.float64), t.astype(np.float32).astype(np.float64))
+    assert abs(loss.item() - lo) <= TOL * abs(lo)
+    assert g.rel_l2(dy.cpu().numpy(), dyo) <= TOL
+
+
+def make_ctx(n_layers=8, width=256, batch=32, arena=64 << 20, lr=1e-2, threads=4):
+    desc = dict(kind=K.MODEL_MLP, n_layers=n_layers, width=width, batch=batch, seq=0, n_heads=0, ffn=0, vocab=0)
+    cfg = dict(optimizer=K.OPT_SGD, lr=lr, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
+    return K.Context(desc, cfg, arena)
+
+
+def load_problem(ctx, Ws, bs):
+    for i, (W, b) in enumerate(zip(Ws, bs)):
+        ctx.karma_set_param(i, 0, W)
+        ctx.karma_set_param(i, 1, b)
+
+
+def grads_of(ctx, n_layers):
+    return [ctx.karma_get_grad(i, t) for i in range(n_layers) for t in range(2)]
+
+
+def unit_costs(ctx):
+    """Deterministic cost records: the library's exact byte counts with fixed times."""
+    layers, loss, fixed = ctx.karma_get_costs()
+    layers = [(1000, 2000, 1000) + l[3:] for l in layers]
+    return layers, (100, loss[1]), fixed
+
+
+def test_mlp_step_matches_oracle_and_out_of_core_is_bit_identical(g):
+    Ws, bs, x, t = si.mlp_problem()
+    bs = [b + 0.01 * (i + 1) for i, b in enumerate(bs)]
+    ctx = make_ctx()
+    load_problem(ctx, Ws, bs)
+    layers, loss_c, fixed = unit_costs(ctx)
+    link = (10**9, 10**9, 100)
+    ctx.karma_set_costs(layers, loss_c, link)
+    big = 32 << 20
+    acts, summ = ctx.karma_plan(big)
+    assert acts == [K.KEEP] * 8 and summ["bytes_d2h"] == 0          # everything fits: capacity rule
+    loss = ctx.karma_step(x, t)
+    ref = grads_of(ctx, 8)
+    # against the oracle (inputs rounded to fp32 first, as the device sees them)
+    f = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)
+    lo, dWs, dbs, _ = nn.mlp_step([f(W) for W in Ws], [f(b) for b in bs], f(x), f(t))
+    assert abs(loss - lo) <= TOL * abs(lo)
+    for i in range(8):
+        assert g.rel_l2(ref[2 * i], dWs[i]) <= TOL, i
+        assert g.rel_l2(ref[2 * i + 1], dbs[i]) <= TOL, i
+
+    # forced plans: every action at every layer, chains of every length
+    plans = [[a] * 8 for a in (K.SWAP, K.RC_KEEP, K.RC_SWAP)]
+    plans += [[K.RC_KEEP] + [K.RC_CHAIN] * 7, [K.RC_SWAP, K.RC_CHAIN, K.SWAP, K.KEEP, K.RC_KEEP, K.RC_CHAIN, K.RC_CHAIN, K.KEEP],
+              [K.SWAP, K.RC_KEEP, K.SWAP, K.RC_KEEP, K.KEEP, K.KEEP, K.RC_SWAP, K.RC_CHAIN]]
+    for pl in plans:
+        ctx.karma_set_plan(big, pl)
+        l2 = ctx.karma_step(x, t)
+        assert l2 == loss, pl
+        for a, b in zip(grads_of(ctx, 8), ref):
+            assert np.array_equal(a, b), pl
+
+    # the workload's budget: fixed part plus room for half of the layers' saved sets
+    per_layer = layers[0][3] + layers[0][4]
+    budget = fixed + 4 * per_layer + layers[0][4] + 2 * layers[0][5] + loss_c[1] + 4096
+    acts, summ = ctx.karma_plan(budget)
+    assert summ["peak_bytes"] <= budget and acts != [K.KEEP] * 8
+    ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(*loss_c))
+    assert acts == ao and summ["makespan_ns"] == so["makespan_ns"] and summ["peak_bytes"] == so["peak_bytes"]
+    l3 = ctx.karma_step(x, t)
+    assert l3 == loss
+    for a, b in zip(grads_of(ctx, 8), ref):
+        assert np.array_equal(a, b)
+    ctx.close()
+
+
+def test_mlp_sgd_update_on_host(g):
+    Ws, bs, x, t = si.mlp_problem(seed=77, n_layers=3, width=48, batch=5)
+    ctx = make_ctx(3, 48, 5, arena=8 << 20, lr=0.05)
+    load_problem(ctx, Ws, bs)
+    ctx.karma_set_plan(4 << 20, [K.SWAP, K.RC_KEEP, K.KEEP])
+    loss0 = ctx.karma_step(x, t, K.STEP_APPLY_OPTIMIZER)
+    f = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)
+    _, dWs, dbs, _ = nn.mlp_step([f(W) for W in Ws], [f(b) for b in bs], f(x), f(t))
+    for i in range(3):
+        assert g.rel_l2(ctx.karma_get_param(i, 0), nn.sgd_update(f(Ws[i]), dWs[i], 0.05).reshape(-1)) <= 1e-6
+        assert g.rel_l2(ctx.karma_get_param(i, 1), nn.sgd_update(f(bs[i]), dbs[i], 0.05).reshape(-1)) <= 1e-5
+    # the device copy was refreshed: a second step sees the new weights
+    loss1 = ctx.karma_step(x, t)
+    newW = [ctx.karma_get_param(i, 0).reshape(48, 48).astype(np.float64) for i in range(3)]
+    newb = [ctx.karma_get_param(i, 1).astype(np.float64) for i in range(3)]
+    lo1 = nn.mlp_step(newW, newb, f(x), f(t))[0]
+    assert abs(loss1 - lo1) <= TOL * abs(lo1) and loss1 != loss0
+    ctx.close()
+
+
+def test_errors(g):
+    ctx = make_ctx(2, 16, 4, arena=1 << 20)
+    x = np.zeros((4, 16), np.float32)
+    with pytest.raises(K.KarmaError) as e:
+        ctx.karma_step(x, x)
+    assert e.value.status == K.E_STATE
+    with pytest.raises(K.KarmaError) as e:
+        ctx.karma_plan(ctx.karma_get_costs()[2] + 256)
+    assert e.value.status == K.E_BUDGET
+    with pytest.raises(K.KarmaError) as e:
+        ctx.karma_plan(2 << 20)
+    assert e.value.status == K.E_OOM
+    with pytest.raises(K.KarmaError) as e:
+        ctx.karma_set_plan(1 << 20, [K.RC_CHAIN, K.KEEP])
+    assert e.value.status == K.E_INVAL
+    ctx.close()
