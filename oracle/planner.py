@@ -167,6 +167,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
     S = [None] * L
     DX = [None] * (L + 1)
     pending = deque()         # (time, [(off, size), ...]) frees at D2H completion
+    out_end = [0] * L         # end of layer i's swap-out: its swap-in cannot start earlier
     ops = []
     tc = td = th = 0
     busy = 0
@@ -223,6 +224,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
                 td = st + copy_ns(nbytes, link.bw_d2h, link.lat_ns)
                 d2h += nbytes
                 pending.append((td, bufs))
+                out_end[i] = td
                 if want_ops:
                     ops.append(Op("OUT", i, st, td, ()))
             if a == RC_SWAP:
@@ -275,7 +277,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
     def issue_in(i, t):
         nonlocal th, h2d
         nbytes = xraw[i] + (layers[i].sav if actions[i] == SWAP else 0)
-        st = max(th, t)
+        st = max(th, t, out_end[i])
         th = st + copy_ns(nbytes, link.bw_h2d, link.lat_ns)
         h2d += nbytes
         arrive[i] = th

@@ -74,7 +74,7 @@ struct Builder {
     }
     const int64_t lw_sz = (int64_t)up256(c.loss_cost.ws_bytes);
     x_at.assign(L + 2, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
-    std::vector<int64_t> f_op(L, -1), in_op(L, -1);
+    std::vector<int64_t> f_op(L, -1), in_op(L, -1), out_op(L, -1);
     uint64_t host_top = 0;
     std::vector<int64_t> host_x(L, -1), host_s(L, -1);
     c.prog.clear();
@@ -110,6 +110,7 @@ struct Builder {
           if (p.x_bytes) { host_x[i] = (int64_t)host_top; host_top += up256(p.x_bytes); }
           if (p.s_bytes) { host_s[i] = (int64_t)host_top; host_top += up256(p.s_bytes); }
           p.host_x = host_x[i]; p.host_s = host_s[i];
+          out_op[i] = k;
           release(x_at[i], x_sz[i], k);
           if (a == KARMA_SWAP) release(s_at[i], s_sz[i], k);
           break;
@@ -120,6 +121,7 @@ struct Builder {
           p.s_bytes = p.s >= 0 ? c.cost[i].sav_bytes : 0;
           p.host_x = host_x[i]; p.host_s = host_s[i];
           claim(p, p.x, x_sz[i]); claim(p, p.s, s_sz[i]);
+          if (out_op[i] >= 0) p.waits.push_back((uint32_t)out_op[i]);   // host copy must be complete
           x_at[i] = p.x;
           if (a == KARMA_SWAP) s_at[i] = p.s;
           in_op[i] = k;

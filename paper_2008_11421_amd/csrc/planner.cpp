@@ -101,6 +101,7 @@ struct Timeline {
   std::deque<Pending> outgoing;                   // frees that happen when a swap-out ends
   std::deque<uint32_t> wanted;                    // layers still to prefetch, in order of need
   std::vector<int64_t> arrival;                   // end of the swap-in of layer i, -1 = not issued
+  std::vector<int64_t> left;                      // end of the swap-out of layer i
   int64_t t_comp = 0, t_out = 0, t_in = 0, busy = 0, redo = 0;
   uint64_t moved_out = 0, moved_in = 0;
   bool failed = false;
@@ -138,7 +139,7 @@ struct Timeline {
 
   void start_prefetch(uint32_t i, int64_t now) {
     int64_t nbytes = move_bytes(i);
-    int64_t s = std::max(t_in, now);
+    int64_t s = std::max(std::max(t_in, now), left[i]);   // data must have reached the host first
     t_in = s + copy_ns((uint64_t)nbytes, P.link.bw_h2d, P.link.lat_ns);
     moved_in += (uint64_t)nbytes;
     arrival[i] = t_in;
@@ -202,6 +203,7 @@ struct Timeline {
     x_at.assign(L + 1, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
     x_sz.push_back(0);  // x_sz[L+1] so that backward(L-1...) can index j+1 == L safely
     arrival.assign(L, -1);
+    left.assign(L, 0);
 
     // forward
     for (uint32_t i = 0; i < L && !failed; ++i) {
@@ -228,6 +230,7 @@ struct Timeline {
             t_out = s + copy_ns((uint64_t)nbytes, P.link.bw_d2h, P.link.lat_ns);
             moved_out += (uint64_t)nbytes;
             p.when = t_out;
+            left[i] = t_out;
             outgoing.push_back(p);
             emit('O', i, s, t_out, -1, -1, -1);
             x_at[i] = -1;

@@ -54,8 +54,10 @@ def test_single_swap_timeline_by_hand():
     out = [o for o in r["ops"] if o.kind == "OUT"][0]
     inn = [o for o in r["ops"] if o.kind == "IN"][0]
     assert (out.start, out.end) == (200, 200 + 5 + nbytes // 2)
-    # prefetch is admitted when backward begins (t = 300): runs 300 .. 300+5+2000
-    assert (inn.start, inn.end) == (300, 305 + nbytes // 2)
+    # prefetch is admitted when backward begins (t = 300) but the data is still on its way
+    # out: the swap-in starts when the swap-out has ended (Sec. III-E, eager strategy:
+    # "wait until the last block is swapped out and then swap it in again")
+    assert (inn.start, inn.end) == (out.end, out.end + 5 + nbytes // 2)
     b1 = [o for o in r["ops"] if o.kind == "B" and o.layer == 1][0]
     assert b1.start == inn.end                      # compute waits for the swap-in
     assert r["stall_ns"] == inn.end - 400
