@@ -219,6 +219,20 @@ int karma_k_linear_relu_bwd_f32(const float* x_dev, const float* w_dev, const fl
 int karma_k_mse_f32(const float* y_dev, const float* t_dev, float* dy_dev, float* loss_dev, float* partial_ws_dev,
                     uint64_t n, void* stream);
 
+/* bf16 GEMM with fp32 accumulation on the matrix cores (the fully connected layer of
+ * Sec. III-C and its two gradients): c[m,n] = sum_k A(m,k) B(n,k) + bias[n] + residual[m,n].
+ * a_dev is [m][k] (k contiguous) or, with KARMA_GEMM_A_STRIDED, [k][m]; b_dev is [n][k] or,
+ * with KARMA_GEMM_B_STRIDED, [k][n].  bias_dev (bf16 [n]) and residual_dev (bf16 [m][n]) may
+ * be NULL.  Output bf16 [m][n], or fp32 with KARMA_GEMM_OUT_F32 (then KARMA_GEMM_ACCUMULATE
+ * adds to what c_dev holds; no residual).  k must be a multiple of 8; a strided operand
+ * needs its row count to be a multiple of 4.  Errors: KARMA_E_INVAL. */
+#define KARMA_GEMM_A_STRIDED 1u
+#define KARMA_GEMM_B_STRIDED 2u
+#define KARMA_GEMM_OUT_F32 4u
+#define KARMA_GEMM_ACCUMULATE 8u
+int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev,
+                      const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,6 +15,8 @@ OK, E_INVAL, E_BUDGET, E_OOM, E_HIP, E_STATE, E_HOSTMEM = 0, -1, -2, -3, -4, -5,
 MODEL_MLP, MODEL_GPT = 1, 2
 OPT_SGD, OPT_ADAM = 1, 2
 STEP_APPLY_OPTIMIZER = 1
+STEP_PROFILE = 2
+GEMM_A_STRIDED, GEMM_B_STRIDED, GEMM_OUT_F32, GEMM_ACCUMULATE = 1, 2, 4, 8
 
 
 class LayerCost(C.Structure):

@@ -18,4 +18,15 @@ int linear_relu_bwd_f32(const float* x, const float* w, const float* z, const fl
                         float* dw, float* db, int m, int n, int k, hipStream_t s);
 int mse_f32(const float* y, const float* t, float* dy, float* loss, float* partial, size_t n, hipStream_t s);
 
+// ---- bf16 GEMM on the matrix cores (gemm_bf16.hip)
+// C[M,N] = sum_k A(m,k) B(n,k) (+ bias[n]) (+ residual[m,n]).  a_kc: A is [M][lda] with k
+// contiguous, else [K][lda] with m contiguous; same for B with n.
+struct GemmArgs {
+  const bf16_t* A; const bf16_t* B; void* C;
+  const bf16_t* bias; const bf16_t* residual;
+  int M, N, K, lda, ldb, ldc;
+  bool a_kc, b_kc, out_f32, accumulate;
+};
+int gemm_bf16(const GemmArgs& g, hipStream_t s);
+
 }  // namespace karma
