@@ -233,6 +233,51 @@ int karma_k_mse_f32(const float* y_dev, const float* t_dev, float* dy_dev, float
 int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev,
                       const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* stream);
 
+/* LayerNorm over the last dimension (eps 1e-5, biased variance), bf16 in/out, fp32
+ * statistics: stats_dev[2*row] = mean, [2*row+1] = 1/std.  h multiple of 8, <= 6144. */
+int karma_k_layernorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const void* beta_dev, void* y_dev,
+                               float* stats_dev, uint32_t rows, uint32_t h, void* stream);
+/* Its backward: dx (+ add_dev if not NULL, e.g. a residual gradient), dgamma/dbeta fp32 [h]
+ * reduced in a fixed order.  ws_dev: ceil(rows/64)*2*h floats (KARMA_E_OOM if smaller). */
+int karma_k_layernorm_bwd_bf16(const void* dy_dev, const void* x_dev, const float* stats_dev, const void* gamma_dev,
+                               const void* add_dev, void* dx_dev, float* dgamma_dev, float* dbeta_dev, float* ws_dev,
+                               uint64_t ws_bytes, uint32_t rows, uint32_t h, void* stream);
+/* out[c] = sum over rows of x[r][c] (bias gradients), fixed order.  ws: ceil(rows/128)*cols floats. */
+int karma_k_colsum_bf16(const void* x_dev, float* out_dev, float* ws_dev, uint64_t ws_bytes, uint32_t rows,
+                        uint32_t cols, void* stream);
+/* tanh-form GELU and its gradient dx = dy * gelu'(x); n multiple of 8. */
+int karma_k_gelu_fwd_bf16(const void* x_dev, void* y_dev, uint64_t n, void* stream);
+int karma_k_gelu_bwd_bf16(const void* x_dev, const void* dy_dev, void* dx_dev, uint64_t n, void* stream);
+/* out[t] = wte[ids[t]] + wpe[t % seq]. */
+int karma_k_embed_fwd_bf16(const int32_t* ids_dev, const void* wte_dev, const void* wpe_dev, void* out_dev,
+                           uint32_t tokens, uint32_t seq, uint32_t h, void* stream);
+/* Embedding gradients without atomics.  order_dev: token positions sorted by id (stable);
+ * seg_start_dev[u..u+1] delimits the run of the u-th distinct id seg_id_dev[u] (n_seg runs,
+ * n_seg+1 starts).  dwte_f32_dev [vocab][h] is added to; dwpe_dev bf16 [seq][h] is written. */
+int karma_k_embed_bwd_bf16(const void* dx_dev, const int32_t* order_dev, const int32_t* seg_start_dev,
+                           const int32_t* seg_id_dev, uint32_t n_seg, float* dwte_f32_dev, void* dwpe_dev,
+                           uint32_t batch, uint32_t seq, uint32_t h, void* stream);
+/* Softmax cross-entropy, forward and gradient in one pass (Sec. III-C softmax layer):
+ * rowloss_dev[r] = logsumexp(z_r) - z_r[label_r]; logits_dev is overwritten with
+ * (softmax(z_r) - onehot) * scale.  cols multiple of 8, cols*2 bytes <= 150 KiB. */
+int karma_k_softmax_ce_bf16(void* logits_dev, const int32_t* labels_dev, float* rowloss_dev, uint32_t rows,
+                            uint32_t cols, float scale, void* stream);
+/* out = scale * sum(x[0..n)) in a fixed order; ws_dev >= 1024 floats. */
+int karma_k_sum_f32(const float* x_dev, float* out_dev, float* ws_dev, uint64_t n, float scale, void* stream);
+
+/* Fused causal self-attention, Attention(Q,K,V) = Softmax(QK^T/sqrt(d)) V per head
+ * (Sec. III-C self-attention layer).  qkv_dev bf16 [batch][seq][3*heads*d] with q|k|v in
+ * thirds and head j in columns j*d..; ctx_dev bf16 [batch][seq][heads*d]; lse_dev fp32
+ * [batch][heads][seq] receives log2 of the row sums of 2^(score*log2(e)/sqrt(d)).
+ * seq must be a multiple of 128, d 64 or 128 (else KARMA_E_INVAL). */
+int karma_k_attention_fwd_bf16(const void* qkv_dev, void* ctx_dev, float* lse_dev, uint32_t batch, uint32_t seq,
+                               uint32_t heads, uint32_t d, void* stream);
+/* Its backward: dqkv_dev (same layout as qkv) from dctx_dev, the forward's ctx and lse.
+ * delta_ws_dev: batch*heads*seq floats of workspace.  No atomics: results are reproducible. */
+int karma_k_attention_bwd_bf16(const void* qkv_dev, const void* ctx_dev, const void* dctx_dev, const float* lse_dev,
+                               float* delta_ws_dev, void* dqkv_dev, uint32_t batch, uint32_t seq, uint32_t heads,
+                               uint32_t d, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,22 +11,10 @@
 #include <hip/hip_runtime.h>
 
 #include "karma.h"
+#include "device_utils.h"
 #include "kernels.h"
 
 namespace karma {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-
-__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((unsigned)b << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  unsigned u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
 
 struct GemmEpilogue {
   void* C;                 // bf16 or fp32 [M][ldc]
@@ -44,76 +32,6 @@ struct GemmEpilogue {
     } else {
       if (residual) v += bf2f(residual[at]);
       ((bf16_t*)C)[at] = f2bf(v);
-    }
-  }
-};
-
-constexpr int LDS_PAD = 8;   // elements: a 16-byte skew per row keeps ds_read_b128 conflict-free
-
-// One operand tile (ROWS x BK) on its way global -> registers -> LDS.
-// KC: global is [rows][k] (k contiguous): each thread moves 16-byte k-runs unchanged.
-// !KC: global is [k][rows]: each thread loads an 8(k) x 4(rows) patch as eight 8-byte
-//      pieces and writes four transposed 16-byte k-runs.
-template <int ROWS, int BK, int T, bool KC>
-struct TileMover {
-  static constexpr int PITCH = BK + LDS_PAD;
-  static constexpr int VECS = ROWS * BK / 8 / T;
-  static_assert(ROWS * BK % (8 * T) == 0 && VECS >= 1, "tile does not divide over the workgroup");
-  static_assert(KC || VECS % 4 == 0, "transposing mover needs whole 8x4 patches per thread");
-  u32x4 reg[VECS];
-
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ G, int ld, int row0, int k0, int rows_total,
-                                       int k_total, int tid) {
-    if (KC) {
-#pragma unroll
-      for (int i = 0; i < VECS; ++i) {
-        int v = tid + i * T, row = v / (BK / 8), kc = v % (BK / 8);
-        int gr = row0 + row, gk = k0 + kc * 8;
-        u32x4 z = {0, 0, 0, 0};
-        reg[i] = (gr < rows_total && gk < k_total) ? *(const u32x4*)(G + (size_t)gr * ld + gk) : z;
-      }
-    } else {
-#pragma unroll
-      for (int b = 0; b < VECS / 4; ++b) {
-        int v = tid + b * T, rg = v % (ROWS / 4), kg = v / (ROWS / 4);
-        int gr = row0 + rg * 4;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          int gk = k0 + kg * 8 + q;
-          u32x2 z = {0, 0};
-          u32x2 r = (gr < rows_total && gk < k_total) ? *(const u32x2*)(G + (size_t)gk * ld + gr) : z;
-          reg[b * 4 + q / 2][(q & 1) * 2] = r.x;
-          reg[b * 4 + q / 2][(q & 1) * 2 + 1] = r.y;
-        }
-      }
-    }
-  }
-
-  __device__ __forceinline__ void store(bf16_t* __restrict__ S, int tid) const {
-    if (KC) {
-#pragma unroll
-      for (int i = 0; i < VECS; ++i) {
-        int v = tid + i * T, row = v / (BK / 8), kc = v % (BK / 8);
-        *(u32x4*)(S + row * PITCH + kc * 8) = reg[i];
-      }
-    } else {
-#pragma unroll
-      for (int b = 0; b < VECS / 4; ++b) {
-        int v = tid + b * T, rg = v % (ROWS / 4), kg = v / (ROWS / 4);
-        // reg[b*4 + p] = { k=2p: (r0 r1 | r2 r3), k=2p+1: (r0 r1 | r2 r3) } as dwords x y z w
-        u32x4 t[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          unsigned e0 = reg[b * 4 + p].x, e1 = reg[b * 4 + p].y;   // row k = 2p
-          unsigned o0 = reg[b * 4 + p].z, o1 = reg[b * 4 + p].w;   // row k = 2p + 1
-          t[0][p] = (e0 & 0xffffu) | (o0 << 16);
-          t[1][p] = (e0 >> 16) | (o0 & 0xffff0000u);
-          t[2][p] = (e1 & 0xffffu) | (o1 << 16);
-          t[3][p] = (e1 >> 16) | (o1 & 0xffff0000u);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *(u32x4*)(S + (rg * 4 + j) * PITCH + kg * 8) = t[j];
-      }
     }
   }
 };

@@ -29,4 +29,28 @@ struct GemmArgs {
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
 
+
+// ---- HBM-bound bf16 kernels (norm_act.hip)
+int layernorm_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, bf16_t* y, float* stats, int rows, int h, hipStream_t s);
+size_t layernorm_bwd_ws_bytes(int rows, int h);
+// dx = LayerNorm backward (+ add, may be null); dgamma/dbeta fp32 [h]
+int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* add, bf16_t* dx,
+                  float* dgamma, float* dbeta, float* partial_ws, int rows, int h, hipStream_t s);
+size_t colsum_ws_bytes(int rows, int cols);
+int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int cols, hipStream_t s);
+int gelu_fwd(const bf16_t* x, bf16_t* y, size_t n, hipStream_t s);
+int gelu_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, size_t n, hipStream_t s);
+int embed_fwd(const int* ids, const bf16_t* wte, const bf16_t* wpe, bf16_t* out, int tokens, int seq, int h, hipStream_t s);
+int embed_bwd(const bf16_t* dx, const int* order, const int* seg_start, const int* seg_id, int n_seg, float* dwte_f32,
+              bf16_t* dwpe, int batch, int seq, int h, hipStream_t s);
+int softmax_ce(bf16_t* logits, const int* labels, float* rowloss, int rows, int cols, float scale, hipStream_t s);
+int sum_f32(const float* x, float* out, float* partial_ws, size_t n, float scale, hipStream_t s);
+int fill_zero(void* p, size_t bytes, hipStream_t s);
+int cast_f32_to_bf16(const float* x, bf16_t* y, size_t n, hipStream_t s);
+
+// ---- fused causal attention (attention.hip); seq multiple of 128, d in {64, 128}
+int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq, int heads, int d, hipStream_t s);
+int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,
+                  bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s);
+
 }  // namespace karma

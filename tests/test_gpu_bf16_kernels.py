@@ -85,3 +85,161 @@ def test_gemm_rejects_bad_shapes(g):
     assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 6, 8, 8, K.GEMM_A_STRIDED, g.stream_ptr()) == K.E_INVAL
     assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 8, 8, 8, K.GEMM_ACCUMULATE, g.stream_ptr()) == K.E_INVAL
     assert lib.karma_k_gemm_bf16(None, g.ptr(t), g.ptr(t), None, None, 8, 8, 8, 0, g.stream_ptr()) == K.E_INVAL
+
+
+TOL_ATTN = 1e-2   # three chained bf16 roundings (probabilities, dS, result), each <= 2^-9
+
+
+@pytest.mark.parametrize("rows,h", [(64, 1024), (37, 256), (5, 3072), (130, 4256), (3, 8)])
+def test_layernorm(g, rows, h):
+    import torch
+    x, xd = bf(si.normal(11, (rows, h), 2.0) + 0.5)
+    gam, gd = bf(1.0 + si.normal(12, (h,), 0.2))
+    bet, bd = bf(si.normal(13, (h,), 0.2))
+    dy, dyd = bf(si.normal(14, (rows, h)))
+    add, addd = bf(si.normal(15, (rows, h)))
+    y = torch.empty(rows, h, dtype=torch.bfloat16, device="cuda")
+    stats = torch.empty(rows, 2, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_layernorm_fwd_bf16, g.ptr(xd), g.ptr(gd), g.ptr(bd), g.ptr(y), g.ptr(stats), rows, h, g.stream_ptr())
+    yo, cache = nn.layernorm_fwd(x, gam, bet)
+    assert g.rel_l2(back(y), yo) <= TOL_BF16
+    assert g.rel_l2(stats[:, 0].cpu().numpy(), x.mean(-1)) <= TOL_F32 + 1e-6
+    assert g.rel_l2(stats[:, 1].cpu().numpy(), cache[1].reshape(-1)) <= TOL_F32
+    dx = torch.empty_like(y)
+    dg = torch.empty(h, device="cuda"); db = torch.empty(h, device="cuda")
+    nws = ((rows + 63) // 64) * 2 * h
+    ws = torch.empty(nws, device="cuda")
+    for use_add in (False, True):
+        g.call(lib.karma_k_layernorm_bwd_bf16, g.ptr(dyd), g.ptr(xd), g.ptr(stats), g.ptr(gd), g.ptr(addd) if use_add else None,
+               g.ptr(dx), g.ptr(dg), g.ptr(db), g.ptr(ws), C.c_uint64(nws * 4), rows, h, g.stream_ptr())
+        dxo, dgo, dbo = nn.layernorm_bwd(dy, gam, cache)
+        if use_add:
+            dxo = dxo + add
+        assert g.rel_l2(back(dx), dxo) <= TOL_BF16
+        assert g.rel_l2(dg.cpu().numpy(), dgo) <= TOL_F32 * 10
+        assert g.rel_l2(db.cpu().numpy(), dbo) <= TOL_F32
+    assert lib.karma_k_layernorm_bwd_bf16(g.ptr(dyd), g.ptr(xd), g.ptr(stats), g.ptr(gd), None, g.ptr(dx), g.ptr(dg),
+                                          g.ptr(db), g.ptr(ws), C.c_uint64(8), rows, h, g.stream_ptr()) == K.E_OOM
+
+
+@pytest.mark.parametrize("rows,cols", [(1000, 4096), (129, 24), (1, 8), (300, 2056)])
+def test_colsum(g, rows, cols):
+    import torch
+    x, xd = bf(si.normal(21, (rows, cols)))
+    out = torch.empty(cols, device="cuda")
+    nws = ((rows + 127) // 128) * cols
+    ws = torch.empty(nws, device="cuda")
+    g.call(K.lib().karma_k_colsum_bf16, g.ptr(xd), g.ptr(out), g.ptr(ws), C.c_uint64(nws * 4), rows, cols, g.stream_ptr())
+    assert g.rel_l2(out.cpu().numpy(), x.sum(0)) <= TOL_F32
+
+
+@pytest.mark.parametrize("n", [8, 4096 * 33, 1000 * 8])
+def test_gelu(g, n):
+    import torch
+    x, xd = bf(si.normal(31, (n,), 2.0))
+    dy, dyd = bf(si.normal(32, (n,)))
+    y = torch.empty(n, dtype=torch.bfloat16, device="cuda"); dx = torch.empty_like(y)
+    g.call(K.lib().karma_k_gelu_fwd_bf16, g.ptr(xd), g.ptr(y), C.c_uint64(n), g.stream_ptr())
+    g.call(K.lib().karma_k_gelu_bwd_bf16, g.ptr(xd), g.ptr(dyd), g.ptr(dx), C.c_uint64(n), g.stream_ptr())
+    assert g.rel_l2(back(y), nn.gelu_fwd(x)) <= TOL_BF16
+    assert g.rel_l2(back(dx), nn.gelu_bwd(x, dy)) <= TOL_BF16
+
+
+def sort_tokens(ids):
+    """Host-side preparation the step does for the embedding gradient: stable sort of
+    token positions by id and the run boundaries."""
+    flat = ids.reshape(-1)
+    order = np.argsort(flat, kind="stable").astype(np.int32)
+    sid = flat[order]
+    starts = np.flatnonzero(np.r_[True, sid[1:] != sid[:-1]]).astype(np.int32)
+    return order, np.r_[starts, len(flat)].astype(np.int32), sid[starts].astype(np.int32)
+
+
+def test_embedding(g):
+    import torch
+    B, S, h, V = 3, 16, 64, 50
+    wte, wted = bf(si.normal(41, (V, h)))
+    wpe, wped = bf(si.normal(42, (S, h)))
+    ids = si.randint(43, (B, S), V).astype(np.int32)
+    ids[0, :5] = 7
+    out = torch.empty(B * S, h, dtype=torch.bfloat16, device="cuda")
+    idd = g.dev(ids.reshape(-1))
+    g.call(K.lib().karma_k_embed_fwd_bf16, g.ptr(idd), g.ptr(wted), g.ptr(wped), g.ptr(out), B * S, S, h, g.stream_ptr())
+    ref = wte[ids] + wpe[np.arange(S)][None]
+    assert g.rel_l2(back(out), ref.reshape(B * S, h)) <= TOL_BF16
+    dx, dxd = bf(si.normal(44, (B * S, h)))
+    order, starts, segid = sort_tokens(ids)
+    base = si.normal(45, (V, h)).astype(np.float32)
+    dwte = torch.from_numpy(base.copy()).cuda()
+    dwpe = torch.empty(S, h, dtype=torch.bfloat16, device="cuda")
+    od, sd, gd = g.dev(order), g.dev(starts), g.dev(segid)     # keep the device copies alive
+    g.call(K.lib().karma_k_embed_bwd_bf16, g.ptr(dxd), g.ptr(od), g.ptr(sd), g.ptr(gd),
+           len(segid), g.ptr(dwte), g.ptr(dwpe), B, S, h, g.stream_ptr())
+    refw = base.astype(np.float64)
+    np.add.at(refw, ids.reshape(-1), dx)
+    assert g.rel_l2(dwte.cpu().numpy(), refw) <= TOL_F32
+    assert g.rel_l2(back(dwpe), dx.reshape(B, S, h).sum(0)) <= TOL_BF16
+
+
+@pytest.mark.parametrize("rows,cols", [(7, 32000), (300, 51200), (5, 8), (64, 1000)])
+def test_softmax_cross_entropy(g, rows, cols):
+    import torch
+    z, zd = bf(si.normal(51, (rows, cols), 3.0))
+    labels = si.randint(52, (rows,), cols).astype(np.int32)
+    rowloss = torch.empty(rows, device="cuda")
+    scale = 1.0 / rows
+    labd = g.dev(labels)
+    g.call(K.lib().karma_k_softmax_ce_bf16, g.ptr(zd), g.ptr(labd), g.ptr(rowloss), rows, cols, C.c_float(scale),
+           g.stream_ptr())
+    loss, d = nn.cross_entropy_fwd_bwd(z, labels)
+    out = torch.zeros(1, device="cuda"); ws = torch.empty(1024, device="cuda")
+    g.call(K.lib().karma_k_sum_f32, g.ptr(rowloss), g.ptr(out), g.ptr(ws), C.c_uint64(rows), C.c_float(scale), g.stream_ptr())
+    assert abs(out.item() - loss) <= TOL_F32 * abs(loss)
+    assert g.rel_l2(back(zd), d) <= TOL_BF16
+    # uniform logits: loss ln(cols), gradient rows sum to ~0
+    zd.zero_()
+    g.call(K.lib().karma_k_softmax_ce_bf16, g.ptr(zd), g.ptr(labd), g.ptr(rowloss), rows, cols, C.c_float(1.0),
+           g.stream_ptr())
+    assert np.allclose(rowloss.cpu().numpy(), np.log(cols), rtol=1e-5)
+
+
+@pytest.mark.parametrize("B,S,H,D", [(2, 256, 3, 64), (1, 128, 1, 64), (1, 384, 2, 128), (2, 1024, 2, 64)])
+def test_attention(g, B, S, H, D):
+    import torch
+    h = H * D
+    qkv, qkvd = bf(si.normal(61, (B, S, 3 * h), 1.5))
+    dctx, dctxd = bf(si.normal(62, (B, S, h)))
+    ctx = torch.empty(B, S, h, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(B, H, S, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_attention_fwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(lse), B, S, H, D, g.stream_ptr())
+    ctxo, probs = nn.mha_fwd(qkv, H)
+    assert g.rel_l2(back(ctx), ctxo) <= TOL_ATTN
+    # lse in the base-2 domain of the scaled scores
+    q = qkv[0, :, :D]; k = qkv[0, :, h:h + D]
+    s = (q @ k.T) / np.sqrt(D)
+    s[np.triu(np.ones((S, S), bool), 1)] = -np.inf
+    lse_ref = (np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)) / np.log(2)
+    assert np.allclose(lse[0, 0].cpu().numpy(), lse_ref, rtol=1e-4, atol=1e-4)
+    dqkv = torch.zeros(B, S, 3 * h, dtype=torch.bfloat16, device="cuda")
+    delta = torch.empty(B, H, S, device="cuda")
+    g.call(lib.karma_k_attention_bwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(dctxd), g.ptr(lse), g.ptr(delta), g.ptr(dqkv),
+           B, S, H, D, g.stream_ptr())
+    dqkvo = nn.mha_bwd(qkv, H, probs, dctx)
+    got = back(dqkv)
+    for name, sl in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+        assert g.rel_l2(got[:, :, sl], dqkvo[:, :, sl]) <= TOL_ATTN, name
+    # a second run gives the same bits (no atomics)
+    dqkv2 = torch.zeros_like(dqkv)
+    g.call(lib.karma_k_attention_bwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(dctxd), g.ptr(lse), g.ptr(delta), g.ptr(dqkv2),
+           B, S, H, D, g.stream_ptr())
+    assert torch.equal(dqkv, dqkv2)
+
+
+def test_attention_rejects_unsupported(g):
+    import torch
+    t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda"); f = torch.zeros(1 << 12, device="cuda")
+    lib = K.lib()
+    assert lib.karma_k_attention_fwd_bf16(g.ptr(t), g.ptr(t), g.ptr(f), 1, 100, 1, 64, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_attention_fwd_bf16(g.ptr(t), g.ptr(t), g.ptr(f), 1, 128, 1, 152, g.stream_ptr()) == K.E_INVAL
