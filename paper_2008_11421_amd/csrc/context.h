@@ -78,6 +78,7 @@ struct Ctx {
   uint64_t swap_pool_bytes = 0;
   std::vector<hipEvent_t> grad_ev;        // per record: gradients have landed on the host
 
+  uint32_t n_segments = 0;                // GPT: distinct token ids of the current step
   std::unique_ptr<HostPool> pool;
   uint64_t step_no = 0;
   karma_step_stats stats{};

@@ -1,10 +1,309 @@
-// GPT workload (placeholder until the bf16 kernels land).
+// GPT-style transformer workload: token + position embedding, pre-LN blocks
+//   x += Proj(Attn(LN1(x)));  x += FC2(GELU(FC1(LN2(x))))
+// and a loss op made of the final LayerNorm, the LM head tied to the token embedding and
+// the mean next-token cross-entropy.  bf16 tensors in HBM, fp32 accumulation everywhere.
+// The layer types are those of KARMA Sec. III-C (fully connected, self-attention, softmax);
+// the block is the unit the planner keeps, swaps or recomputes.
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+#include "kernels.h"
 #include "layers.h"
 
 namespace karma {
-int gpt_build_records(Ctx&) { return KARMA_E_INVAL; }
-int gpt_prepare_step(Ctx&, const void*, const void*) { return KARMA_E_INVAL; }
-int gpt_forward(Ctx&, uint32_t, const LayerIO&, hipStream_t) { return KARMA_E_INVAL; }
-int gpt_backward(Ctx&, uint32_t, const LayerIO&, hipStream_t) { return KARMA_E_INVAL; }
-int gpt_loss(Ctx&, const LayerIO&, hipStream_t) { return KARMA_E_INVAL; }
+
+namespace {
+
+inline uint64_t up256(uint64_t b) { return (b + 255) / 256 * 256; }
+
+struct Dims {
+  int B, S, H, D, h, ffn, V, T;
+  explicit Dims(const karma_model_desc& d)
+      : B((int)d.batch), S((int)d.seq), H((int)d.n_heads), D((int)(d.width / d.n_heads)), h((int)d.width),
+        ffn((int)d.ffn), V((int)d.vocab), T((int)(d.batch * d.seq)) {}
+};
+
+// internals of one block, in the order they are produced
+struct BlockSaved {
+  uint64_t a, stats1, qkv, ctx, lse, r1, stats2, m, f1, g, total;
+  explicit BlockSaved(const Dims& d) {
+    uint64_t o = 0;
+    auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
+    a = take((uint64_t)d.T * d.h * 2);
+    stats1 = take((uint64_t)d.T * 2 * 4);
+    qkv = take((uint64_t)d.T * 3 * d.h * 2);
+    ctx = take((uint64_t)d.T * d.h * 2);
+    lse = take((uint64_t)d.B * d.H * d.S * 4);
+    r1 = take((uint64_t)d.T * d.h * 2);
+    stats2 = take((uint64_t)d.T * 2 * 4);
+    m = take((uint64_t)d.T * d.h * 2);
+    f1 = take((uint64_t)d.T * d.ffn * 2);
+    g = take((uint64_t)d.T * d.ffn * 2);
+    total = o;
+  }
+};
+
+// backward workspace of one block
+struct BlockWs {
+  uint64_t wide, t1, t2, t3, delta, part, total;
+  explicit BlockWs(const Dims& d) {
+    uint64_t o = 0;
+    auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
+    wide = take((uint64_t)d.T * std::max(d.ffn, 3 * d.h) * 2);   // dg -> df1, later dqkv
+    t1 = take((uint64_t)d.T * d.h * 2);                           // dm, later dctx
+    t2 = take((uint64_t)d.T * d.h * 2);                           // dr1
+    t3 = take((uint64_t)d.T * d.h * 2);                           // da
+    delta = take((uint64_t)d.B * d.H * d.S * 4);
+    part = take(std::max(layernorm_bwd_ws_bytes(d.T, d.h), colsum_ws_bytes(d.T, std::max(d.ffn, 3 * d.h))));
+    total = o;
+  }
+};
+
+constexpr int HEAD_CHUNK = 4096;   // tokens per LM-head chunk: the full logits never exist
+
+struct LossWs {
+  uint64_t xf, stats, logits, dxf, rowloss, part, total;
+  int chunk;
+  explicit LossWs(const Dims& d) {
+    chunk = std::min(d.T, HEAD_CHUNK);
+    uint64_t o = 0;
+    auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
+    xf = take((uint64_t)d.T * d.h * 2);
+    stats = take((uint64_t)d.T * 2 * 4);
+    logits = take((uint64_t)chunk * d.V * 2);
+    dxf = take((uint64_t)d.T * d.h * 2);
+    rowloss = take((uint64_t)d.T * 4);
+    part = take(std::max<uint64_t>(layernorm_bwd_ws_bytes(d.T, d.h), 1024 * 4));
+    total = o;
+  }
+};
+
+enum BlockParam { LN1_G, LN1_B, WQKV, BQKV, WO, BO, LN2_G, LN2_B, W1, B1, W2, B2 };
+
+Param make_param(uint64_t n, bool matrix) {
+  Param p;
+  p.n = n;
+  p.dev_bf16 = true;
+  p.grad_bf16 = matrix;   // vectors (biases, LayerNorm parameters) keep fp32 gradients
+  return p;
+}
+
+int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
+         bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s) {
+  GemmArgs g{};
+  g.A = A; g.B = B; g.C = C; g.bias = bias; g.residual = res;
+  g.M = M; g.N = N; g.K = K;
+  g.a_kc = a_kc; g.b_kc = b_kc;
+  g.lda = a_kc ? K : M;
+  g.ldb = b_kc ? K : N;
+  g.ldc = N;
+  g.out_f32 = out_f32; g.accumulate = acc;
+  return gemm_bf16(g, s);
+}
+
+#define TRY(call)          \
+  do {                     \
+    int st_ = (call);      \
+    if (st_) return st_;   \
+  } while (0)
+
+}  // namespace
+
+int gpt_build_records(Ctx& c) {
+  const karma_model_desc& md = c.desc;
+  if (!md.n_layers || !md.width || !md.batch || !md.seq || !md.n_heads || !md.ffn || !md.vocab) return KARMA_E_INVAL;
+  if (md.width % md.n_heads) return KARMA_E_INVAL;
+  Dims d(md);
+  if ((d.D != 64 && d.D != 128) || d.S % 128 || d.h % 8 || d.ffn % 8 || d.V % 8) return KARMA_E_INVAL;
+  if ((uint64_t)d.V * 2 > 150 * 1024) return KARMA_E_INVAL;
+  const uint64_t act = (uint64_t)d.T * d.h * 2;
+  c.rec.clear();
+  Record emb;
+  emb.kind = REC_EMBED;
+  emb.p.push_back(make_param((uint64_t)d.V * d.h, true));
+  emb.p.back().grad_bf16 = false;   // fp32 accumulator: LM head chunks + scatter-add land here
+  emb.p.push_back(make_param((uint64_t)d.S * d.h, true));
+  emb.out_bytes = act;
+  c.rec.push_back(std::move(emb));
+  BlockSaved sv(d);
+  BlockWs ws(d);
+  for (uint32_t i = 0; i < md.n_layers; ++i) {
+    Record r;
+    r.kind = REC_BLOCK;
+    r.p.resize(12);
+    r.p[LN1_G] = make_param(d.h, false); r.p[LN1_B] = make_param(d.h, false);
+    r.p[WQKV] = make_param((uint64_t)3 * d.h * d.h, true); r.p[BQKV] = make_param(3 * d.h, false);
+    r.p[WO] = make_param((uint64_t)d.h * d.h, true); r.p[BO] = make_param(d.h, false);
+    r.p[LN2_G] = make_param(d.h, false); r.p[LN2_B] = make_param(d.h, false);
+    r.p[W1] = make_param((uint64_t)d.ffn * d.h, true); r.p[B1] = make_param(d.ffn, false);
+    r.p[W2] = make_param((uint64_t)d.h * d.ffn, true); r.p[B2] = make_param(d.h, false);
+    r.out_bytes = act;
+    r.sav_bytes = sv.total;
+    r.ws_bytes = ws.total;
+    c.rec.push_back(std::move(r));
+  }
+  Record loss;
+  loss.kind = REC_LOSS_LMHEAD;
+  loss.p.push_back(make_param(d.h, false));
+  loss.p.push_back(make_param(d.h, false));
+  loss.ws_bytes = LossWs(d).total;
+  c.rec.push_back(std::move(loss));
+  c.in_bytes = (uint64_t)d.T * 4;
+  c.lab_bytes = (uint64_t)d.T * 4;
+  c.misc_bytes = ((uint64_t)3 * d.T + 1) * 4;   // order[T], seg_start[T+1], seg_id[T]
+  return KARMA_OK;
+}
+
+// Host-side preparation: ids/labels into the staging buffers; stable sort of the token
+// positions by id for the atomic-free embedding gradient.
+int gpt_prepare_step(Ctx& c, const void* in, const void* lab) {
+  Dims d(c.desc);
+  const int32_t* ids = (const int32_t*)in;
+  const int32_t* labels = (const int32_t*)lab;
+  for (int t = 0; t < d.T; ++t)
+    if (ids[t] < 0 || ids[t] >= d.V || labels[t] < 0 || labels[t] >= d.V) {
+      c.err = "token id or label outside the vocabulary";
+      return KARMA_E_INVAL;
+    }
+  std::memcpy(c.stage_in, in, c.in_bytes);
+  std::memcpy(c.stage_lab, lab, c.lab_bytes);
+  int32_t* order = (int32_t*)c.stage_misc;
+  int32_t* seg_start = order + d.T;
+  int32_t* seg_id = seg_start + d.T + 1;
+  std::iota(order, order + d.T, 0);
+  std::stable_sort(order, order + d.T, [&](int32_t a, int32_t b) { return ids[a] < ids[b]; });
+  int n = 0;
+  for (int p = 0; p < d.T; ++p)
+    if (p == 0 || ids[order[p]] != ids[order[p - 1]]) {
+      seg_start[n] = p;
+      seg_id[n] = ids[order[p]];
+      ++n;
+    }
+  seg_start[n] = d.T;
+  c.n_segments = (uint32_t)n;
+  return KARMA_OK;
+}
+
+int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
+  Dims d(c.desc);
+  if (i == 0) {
+    if (!io.out) return KARMA_OK;
+    return embed_fwd((const int*)io.x, (const bf16_t*)c.w_ptr(0, 0), (const bf16_t*)c.w_ptr(0, 1), (bf16_t*)io.out, d.T,
+                     d.S, d.h, s);
+  }
+  BlockSaved sv(d);
+  char* S = (char*)io.sav;
+  const bf16_t* x = (const bf16_t*)io.x;
+  bf16_t* a = (bf16_t*)(S + sv.a);
+  bf16_t* qkv = (bf16_t*)(S + sv.qkv);
+  bf16_t* ctx = (bf16_t*)(S + sv.ctx);
+  bf16_t* r1 = (bf16_t*)(S + sv.r1);
+  bf16_t* m = (bf16_t*)(S + sv.m);
+  bf16_t* f1 = (bf16_t*)(S + sv.f1);
+  bf16_t* g = (bf16_t*)(S + sv.g);
+  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t); };
+  TRY(layernorm_fwd(x, W(LN1_G), W(LN1_B), a, (float*)(S + sv.stats1), d.T, d.h, s));
+  TRY(gemm(a, W(WQKV), qkv, W(BQKV), nullptr, d.T, 3 * d.h, d.h, true, true, false, false, s));
+  TRY(attention_fwd(qkv, ctx, (float*)(S + sv.lse), d.B, d.S, d.H, d.D, s));
+  TRY(gemm(ctx, W(WO), r1, W(BO), x, d.T, d.h, d.h, true, true, false, false, s));
+  TRY(layernorm_fwd(r1, W(LN2_G), W(LN2_B), m, (float*)(S + sv.stats2), d.T, d.h, s));
+  TRY(gemm(m, W(W1), f1, W(B1), nullptr, d.T, d.ffn, d.h, true, true, false, false, s));
+  TRY(gelu_fwd(f1, g, (size_t)d.T * d.ffn, s));
+  // a recompute whose output nobody needs stops here: backward only reads the internals
+  if (io.out) TRY(gemm(g, W(W2), io.out, W(B2), r1, d.T, d.h, d.ffn, true, true, false, false, s));
+  return KARMA_OK;
+}
+
+int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
+  Dims d(c.desc);
+  const bf16_t* dy = (const bf16_t*)io.dy;
+  if (i == 0) {
+    const int32_t* order = (const int32_t*)c.fixed_ptr(c.misc_off);
+    const int32_t* seg_start = order + d.T;
+    const int32_t* seg_id = seg_start + d.T + 1;
+    return embed_bwd(dy, order, seg_start, seg_id, (int)c.n_segments, (float*)c.g_ptr(0, 0), (bf16_t*)c.g_ptr(0, 1),
+                     d.B, d.S, d.h, s);
+  }
+  BlockSaved sv(d);
+  BlockWs wl(d);
+  char* S = (char*)io.sav;
+  char* Wk = (char*)io.ws;
+  const bf16_t* x = (const bf16_t*)io.x;
+  const bf16_t* a = (const bf16_t*)(S + sv.a);
+  const bf16_t* qkv = (const bf16_t*)(S + sv.qkv);
+  const bf16_t* ctx = (const bf16_t*)(S + sv.ctx);
+  const bf16_t* r1 = (const bf16_t*)(S + sv.r1);
+  const bf16_t* m = (const bf16_t*)(S + sv.m);
+  const bf16_t* f1 = (const bf16_t*)(S + sv.f1);
+  const bf16_t* g = (const bf16_t*)(S + sv.g);
+  bf16_t* wide = (bf16_t*)(Wk + wl.wide);
+  bf16_t* t1 = (bf16_t*)(Wk + wl.t1);
+  bf16_t* dr1 = (bf16_t*)(Wk + wl.t2);
+  bf16_t* da = (bf16_t*)(Wk + wl.t3);
+  float* part = (float*)(Wk + wl.part);
+  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t); };
+  auto G = [&](int t) { return c.g_ptr(i, t); };
+
+  // FC2: y = r1 + g W2^T + b2
+  TRY(gemm(dy, W(W2), wide, nullptr, nullptr, d.T, d.ffn, d.h, true, false, false, false, s));     // dg = dy W2
+  TRY(gemm(dy, g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s));        // dW2 = dy^T g
+  TRY(colsum_bf16(dy, (float*)G(B2), part, d.T, d.h, s));
+  TRY(gelu_bwd(f1, wide, wide, (size_t)d.T * d.ffn, s));                                            // df1
+  // FC1
+  TRY(gemm(wide, W(W1), t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
+  TRY(gemm(wide, m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s));      // dW1 = df1^T m
+  TRY(colsum_bf16(wide, (float*)G(B1), part, d.T, d.ffn, s));
+  // LN2 and the residual branch: dr1 = LN2'(dm) + dy
+  TRY(layernorm_bwd(t1, r1, (const float*)(S + sv.stats2), W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), part,
+                    d.T, d.h, s));
+  // attention output projection
+  TRY(gemm(dr1, W(WO), t1, nullptr, nullptr, d.T, d.h, d.h, true, false, false, false, s));         // dctx = dr1 Wo
+  TRY(gemm(dr1, ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s));       // dWo = dr1^T ctx
+  TRY(colsum_bf16(dr1, (float*)G(BO), part, d.T, d.h, s));
+  // attention
+  TRY(attention_bwd(qkv, ctx, t1, (const float*)(S + sv.lse), (float*)(Wk + wl.delta), wide, d.B, d.S, d.H, d.D, s));
+  // QKV projection
+  TRY(gemm(wide, W(WQKV), da, nullptr, nullptr, d.T, d.h, 3 * d.h, true, false, false, false, s));  // da = dqkv Wqkv
+  TRY(gemm(wide, a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s));  // dWqkv = dqkv^T a
+  TRY(colsum_bf16(wide, (float*)G(BQKV), part, d.T, 3 * d.h, s));
+  // LN1 and the residual: dx = LN1'(da) + dr1
+  TRY(layernorm_bwd(da, x, (const float*)(S + sv.stats1), W(LN1_G), dr1, (bf16_t*)io.dx, (float*)G(LN1_G),
+                    (float*)G(LN1_B), part, d.T, d.h, s));
+  return KARMA_OK;
+}
+
+// Final LayerNorm, tied LM head and mean cross-entropy with their gradients, chunked over
+// tokens so that only HEAD_CHUNK rows of logits exist at a time.
+int gpt_loss(Ctx& c, const LayerIO& io, hipStream_t s) {
+  Dims d(c.desc);
+  LossWs wl(d);
+  const uint32_t R = c.L;   // the loss record
+  char* Wk = (char*)io.ws;
+  const bf16_t* x = (const bf16_t*)io.x;
+  bf16_t* xf = (bf16_t*)(Wk + wl.xf);
+  float* stats = (float*)(Wk + wl.stats);
+  bf16_t* logits = (bf16_t*)(Wk + wl.logits);
+  bf16_t* dxf = (bf16_t*)(Wk + wl.dxf);
+  float* rowloss = (float*)(Wk + wl.rowloss);
+  float* part = (float*)(Wk + wl.part);
+  const bf16_t* wte = (const bf16_t*)c.w_ptr(0, 0);
+  float* dwte = (float*)c.g_ptr(0, 0);
+  const int* labels = (const int*)c.fixed_ptr(c.lab_off);
+  TRY(fill_zero(dwte, (size_t)d.V * d.h * 4, s));
+  TRY(layernorm_fwd(x, (const bf16_t*)c.w_ptr(R, 0), (const bf16_t*)c.w_ptr(R, 1), xf, stats, d.T, d.h, s));
+  for (int t0 = 0; t0 < d.T; t0 += wl.chunk) {
+    const int n = std::min(wl.chunk, d.T - t0);
+    const bf16_t* xc = xf + (size_t)t0 * d.h;
+    TRY(gemm(xc, wte, logits, nullptr, nullptr, n, d.V, d.h, true, true, false, false, s));          // logits = xf wte^T
+    TRY(softmax_ce(logits, labels + t0, rowloss + t0, n, d.V, 1.0f / (float)d.T, s));                 // -> dlogits
+    TRY(gemm(logits, wte, dxf + (size_t)t0 * d.h, nullptr, nullptr, n, d.h, d.V, true, false, false, false, s));
+    TRY(gemm(logits, xc, dwte, nullptr, nullptr, d.V, d.h, n, false, false, true, true, s));          // dwte += dlogits^T xf
+  }
+  TRY(sum_f32(rowloss, (float*)c.fixed_ptr(c.loss_off), part, (size_t)d.T, 1.0f / (float)d.T, s));
+  TRY(layernorm_bwd(dxf, x, stats, (const bf16_t*)c.w_ptr(R, 0), nullptr, (bf16_t*)io.dx, (float*)c.g_ptr(R, 0),
+                    (float*)c.g_ptr(R, 1), part, d.T, d.h, s));
+  return KARMA_OK;
+}
+
 }  // namespace karma
