@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the out-of-core training step on one MI355X.
+
+Workload (configs[1] of the baseline): 24-layer GPT-style pre-LN transformer, hidden 1024,
+16 heads, FFN 4096, sequence 1024, batch 32, vocabulary 32000, bf16 compute with fp32 host
+master weights and host Adam, HBM budget 16 GiB, seeded synthetic token ids.
+
+One "step" = one whole training step (forward, loss, backward with swap-out / prefetch /
+recompute as planned, gradient D2H, host Adam, weight H2D).  The in-core rate (same
+library, same kernels, budget lifted) is measured alongside.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+GIB = 1 << 30
+CFG = dict(n_layers=24, hidden=1024, heads=16, ffn=4096, vocab=32000, seq=1024, batch=32)
+BUDGET = 16 * GIB
+ARENA = 32 * GIB
+SEED = 2008114202
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline():
+    """The oracle as it stands, timed on the host: one sequence at true widths with the
+    depth truncated to 1 and to 2 blocks; block and head costs extrapolated to 24 blocks."""
+    import numpy as np
+    from oracle import nn
+    import synth_inputs as si
+    ts = []
+    for depth in (1, 2):
+        params, ids, labels = si.gpt_problem(seed=SEED, n_layers=depth, hidden=CFG["hidden"], ffn=CFG["ffn"],
+                                             vocab=CFG["vocab"], seq=CFG["seq"], batch=1)
+        t0 = time.perf_counter()
+        nn.gpt_step(params, ids, labels, CFG["heads"])
+        ts.append(time.perf_counter() - t0)
+    t_block = max(ts[1] - ts[0], 1e-9)
+    t_rest = max(ts[0] - t_block, 0.0)
+    per_sample = CFG["n_layers"] * t_block + t_rest
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return dict(value=1.0 / per_sample, unit="samples/s", cores=cores, kind="oracle",
+                sample="fp64 numpy oracle, full step on 1 sequence of 1024 tokens at true widths, depth 1 and 2 "
+                       "(%.1f s + %.1f s); per-block %.2f s and embedding+head %.2f s extrapolated to 24 blocks"
+                       % (ts[0], ts[1], t_block, t_rest))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2008_11421_amd as K
+    import synth_inputs as si
+    from oracle import nn as oracle_nn
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    K.lib()   # fails loudly when the HIP library is missing
+
+    threads = int(os.environ.get("OMP_NUM_THREADS", "16"))
+    desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=CFG["batch"], seq=CFG["seq"],
+                n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"])
+    cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
+    t0 = time.perf_counter()
+    ctx = K.Context(desc, cfg, ARENA)
+    params, ids, labels = si.gpt_problem(seed=SEED, n_layers=CFG["n_layers"], hidden=CFG["hidden"], ffn=CFG["ffn"],
+                                         vocab=CFG["vocab"], seq=CFG["seq"], batch=CFG["batch"])
+    ctx.karma_set_param(0, 0, params["wte"])
+    ctx.karma_set_param(0, 1, params["wpe"])
+    for i, b in enumerate(params["blocks"]):
+        for t, name in enumerate(oracle_nn.BLOCK_TENSORS):
+            ctx.karma_set_param(i + 1, t, b[name])
+    ctx.karma_set_param(CFG["n_layers"] + 1, 0, params["lnf_g"])
+    ctx.karma_set_param(CFG["n_layers"] + 1, 1, params["lnf_b"])
+    del params
+    ids = ids.astype(np.int32)
+    labels = labels.astype(np.int32)
+    log("setup %.1f s" % (time.perf_counter() - t0))
+
+    link = ctx.karma_measure(3)
+    layers, loss_c, fixed = ctx.karma_get_costs()
+    log("link h2d %.1f GB/s d2h %.1f GB/s lat %d ns; block fwd %.2f ms bwd %.2f ms; loss %.2f ms; fixed %.2f GiB"
+        % (link[0] / 1e9, link[1] / 1e9, link[2], layers[1][0] / 1e6, layers[1][1] / 1e6, loss_c[0] / 1e6, fixed / GIB))
+
+    def timed(budget, flags):
+        acts, summ = ctx.karma_plan(budget)
+        for _ in range(args.warmup):
+            ctx.karma_step(ids, labels, flags)
+        torch.cuda.synchronize()
+        n_l, ms_l, fl_l = 0, 0.0, 0.0
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            loss = ctx.karma_step(ids, labels, flags)
+            if flags & K.STEP_KERNEL_TIMES:
+                n, ms, fl = ctx.karma_get_gemm_stats()
+                n_l += n; ms_l += ms; fl_l += fl
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        return acts, summ, dt, loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
+
+    acts_in, summ_in, dt_in, loss_in, _, st_in = timed(ARENA, K.STEP_APPLY_OPTIMIZER)
+    log("in-core: %.1f ms/step (host optimiser %.1f ms), plan all-keep=%s" % (dt_in * 1e3, st_in["host_opt_ms"], acts_in == [0] * len(acts_in)))
+    acts, summ, dt, loss, gem, st = timed(BUDGET, K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
+    log("16 GiB: %.1f ms/step, plan %s" % (dt * 1e3, acts))
+    log("predicted makespan %.1f ms, peak %.2f GiB, swap %.2f GiB each way" %
+        (summ["makespan_ns"] / 1e6, summ["peak_bytes"] / GIB, summ["bytes_d2h"] / GIB))
+
+    n_l, ms_l, fl_l = gem
+    achieved = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
+    out = {
+        "metric": "samples/s at fixed HBM budget",
+        "value": CFG["batch"] / dt,
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: 24-layer pre-LN GPT, hidden 1024, 16 heads, FFN 4096, seq 1024, batch 32, "
+                               "vocab 32000, bf16 + fp32 host master/Adam, HBM budget 16 GiB",
+                   "hbm_budget_gib": 16, "global_batch": CFG["batch"], "seq_len": CFG["seq"],
+                   "plan": "".join("KSRrc"[a] for a in acts), "plan_legend": "K keep, S swap, R recompute from kept input, "
+                   "r recompute from swapped input, c recompute in chain"},
+        "in_core_samples_per_s": CFG["batch"] / dt_in,
+        "in_core_ms_per_step": dt_in * 1e3,
+        "pct_of_in_core": 100.0 * dt_in / dt,
+        "loss": loss,
+        "predicted_makespan_ms": summ["makespan_ns"] / 1e6,
+        "arena_peak_gib": summ["peak_bytes"] / GIB,
+        "swap_gib_each_way": summ["bytes_d2h"] / GIB,
+        "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9},
+        "host_opt_ms": st["host_opt_ms"],
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all launches of the timed steps)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "launches_per_step": n_l / max(args.steps, 1), "avg_launch_ms": ms_l / max(n_l, 1),
+                     "flops_per_launch": fl_l / max(n_l, 1), "traffic": None},
+    }
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

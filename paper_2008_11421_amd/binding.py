@@ -16,6 +16,7 @@ MODEL_MLP, MODEL_GPT = 1, 2
 OPT_SGD, OPT_ADAM = 1, 2
 STEP_APPLY_OPTIMIZER = 1
 STEP_PROFILE = 2
+STEP_KERNEL_TIMES = 4
 GEMM_A_STRIDED, GEMM_B_STRIDED, GEMM_OUT_F32, GEMM_ACCUMULATE = 1, 2, 4, 8
 
 
@@ -263,6 +264,11 @@ class Context:
         s = StepStats()
         self._chk(lib().karma_get_stats(self.ctx, C.byref(s)), "karma_get_stats")
         return s.as_dict()
+
+    def karma_get_gemm_stats(self):
+        n, ms, fl = C.c_uint64(), C.c_double(), C.c_double()
+        self._chk(lib().karma_get_gemm_stats(self.ctx, C.byref(n), C.byref(ms), C.byref(fl)), "karma_get_gemm_stats")
+        return n.value, ms.value, fl.value
 
     def karma_get_op_times(self):
         n = C.c_uint32(6 * self.n_layers + 2)

@@ -78,6 +78,14 @@ struct Ctx {
   uint64_t swap_pool_bytes = 0;
   std::vector<hipEvent_t> grad_ev;        // per record: gradients have landed on the host
 
+  // per-launch timing of the GEMM kernel (KARMA_STEP_KERNEL_TIMES)
+  bool ktime = false;
+  std::vector<hipEvent_t> kev;            // event pool, two per launch
+  size_t kev_used = 0;
+  std::vector<double> kflops;             // flops of launch j (events 2j, 2j+1)
+  uint64_t gemm_launches = 0;
+  double gemm_ms = 0, gemm_flops = 0;     // totals of the last step run with the flag
+
   uint32_t n_segments = 0;                // GPT: distinct token ids of the current step
   std::unique_ptr<HostPool> pool;
   uint64_t step_no = 0;

@@ -270,6 +270,9 @@ int update_record(Ctx* c, uint32_t r) {
 int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out, bool profile) {
   if (!c->planned) return fail(c, KARMA_E_STATE, "karma_step before karma_plan / karma_set_plan");
   const bool apply = flags & KARMA_STEP_APPLY_OPTIMIZER;
+  c->ktime = (flags & KARMA_STEP_KERNEL_TIMES) != 0;
+  c->kev_used = 0;
+  c->kflops.clear();
   double t0 = now_ms();
   c->stats = karma_step_stats{};
   int st = model_prepare_step(*c, in, lab);
@@ -311,6 +314,17 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
   c->stats.bytes_d2h = c->summary.bytes_d2h;
   c->stats.bytes_h2d = c->summary.bytes_h2d;
   c->stats.arena_peak_bytes = c->summary.peak_bytes;
+  if (c->ktime) {
+    c->gemm_launches = c->kflops.size();
+    c->gemm_ms = 0;
+    c->gemm_flops = 0;
+    for (size_t j = 0; j < c->kflops.size(); ++j) {
+      float ms = 0.f;
+      KARMA_HIP(c, hipEventElapsedTime(&ms, c->kev[2 * j], c->kev[2 * j + 1]));
+      c->gemm_ms += ms;
+      c->gemm_flops += c->kflops[j];
+    }
+  }
   if (profile) {
     for (size_t k = 0; k < c->prog.size(); ++k) {
       float ms = 0.f;
@@ -411,6 +425,7 @@ extern "C" void karma_destroy(karma_ctx* c) {
   if (c->stage_loss) (void)hipHostFree(c->stage_loss);
   if (c->stage_misc) (void)hipHostFree(c->stage_misc);
   for (auto e : c->grad_ev) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->kev) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -523,6 +538,14 @@ extern "C" int karma_step(karma_ctx* c, const void* in, const void* lab, uint32_
 extern "C" int karma_get_stats(karma_ctx* c, karma_step_stats* out) {
   if (!c || !out) return KARMA_E_INVAL;
   *out = c->stats;
+  return KARMA_OK;
+}
+
+extern "C" int karma_get_gemm_stats(karma_ctx* c, uint64_t* launches, double* ms, double* flops) {
+  if (!c || !launches || !ms || !flops) return KARMA_E_INVAL;
+  *launches = c->gemm_launches;
+  *ms = c->gemm_ms;
+  *flops = c->gemm_flops;
   return KARMA_OK;
 }
 

@@ -89,8 +89,8 @@ Param make_param(uint64_t n, bool matrix) {
   return p;
 }
 
-int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
-         bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s) {
+int gemm_raw(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
+             bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s) {
   GemmArgs g{};
   g.A = A; g.B = B; g.C = C; g.bias = bias; g.residual = res;
   g.M = M; g.N = N; g.K = K;
@@ -100,6 +100,25 @@ int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf
   g.ldc = N;
   g.out_f32 = out_f32; g.accumulate = acc;
   return gemm_bf16(g, s);
+}
+
+// every GEMM of the model goes through here so that a profiled step can time each launch
+thread_local Ctx* g_ctx = nullptr;
+int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
+         bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s) {
+  Ctx* c = g_ctx;
+  if (!c || !c->ktime) return gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s);
+  while (c->kev.size() < c->kev_used + 2) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return KARMA_E_HIP;
+    c->kev.push_back(e);
+  }
+  if (hipEventRecord(c->kev[c->kev_used], s) != hipSuccess) return KARMA_E_HIP;
+  int st = gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s);
+  if (hipEventRecord(c->kev[c->kev_used + 1], s) != hipSuccess) return KARMA_E_HIP;
+  c->kev_used += 2;
+  c->kflops.push_back(2.0 * M * N * K);
+  return st;
 }
 
 #define TRY(call)          \
@@ -187,6 +206,7 @@ int gpt_prepare_step(Ctx& c, const void* in, const void* lab) {
 
 int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
+  g_ctx = &c;
   if (i == 0) {
     if (!io.out) return KARMA_OK;
     return embed_fwd((const int*)io.x, (const bf16_t*)c.w_ptr(0, 0), (const bf16_t*)c.w_ptr(0, 1), (bf16_t*)io.out, d.T,
@@ -217,6 +237,7 @@ int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
 
 int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
+  g_ctx = &c;
   const bf16_t* dy = (const bf16_t*)io.dy;
   if (i == 0) {
     const int32_t* order = (const int32_t*)c.fixed_ptr(c.misc_off);
@@ -277,6 +298,7 @@ int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
 // tokens so that only HEAD_CHUNK rows of logits exist at a time.
 int gpt_loss(Ctx& c, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
+  g_ctx = &c;
   LossWs wl(d);
   const uint32_t R = c.L;   // the loss record
   char* Wk = (char*)io.ws;
