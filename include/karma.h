@@ -229,13 +229,17 @@ int karma_k_mse_f32(const float* y_dev, const float* t_dev, float* dy_dev, float
  * with KARMA_GEMM_B_STRIDED, [k][n].  bias_dev (bf16 [n]) and residual_dev (bf16 [m][n]) may
  * be NULL.  Output bf16 [m][n], or fp32 with KARMA_GEMM_OUT_F32 (then KARMA_GEMM_ACCUMULATE
  * adds to what c_dev holds; no residual).  k must be a multiple of 8; a strided operand
- * needs its row count to be a multiple of 4.  Errors: KARMA_E_INVAL. */
+ * needs its row count to be a multiple of 4.  ws_dev (may be NULL): workspace that lets the
+ * kernel split a long reduction over more workgroups when m*n alone cannot fill the chip
+ * (up to 16*m*n floats are used; partial sums are added in a fixed order).
+ * Errors: KARMA_E_INVAL. */
 #define KARMA_GEMM_A_STRIDED 1u
 #define KARMA_GEMM_B_STRIDED 2u
 #define KARMA_GEMM_OUT_F32 4u
 #define KARMA_GEMM_ACCUMULATE 8u
 int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev,
-                      const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* stream);
+                      const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* ws_dev,
+                      uint64_t ws_bytes, void* stream);
 
 /* LayerNorm over the last dimension (eps 1e-5, biased variance), bf16 in/out, fp32
  * statistics: stats_dev[2*row] = mean, [2*row+1] = 1/std.  h multiple of 8, <= 6144. */

@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
 // query tiles at or after them.  Scores are computed with queries on the rows so that the
 // probabilities sit in registers as the (key x query) operand of dV = P^T dO and dK = dS^T Q.
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ lse, const float* __restrict__ delta,
                                                             bf16_t* __restrict__ dqkv, int S, int H) {
   constexpr int PK = D + LDS_PAD, PT = 64 + LDS_PAD, TT = (D * 64 / 32 < 256) ? D * 64 / 32 : 256;
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
   __shared__ __attribute__((aligned(16))) bf16_t Os[64 * PK];
   __shared__ __attribute__((aligned(16))) bf16_t Qt[D * PT];
   __shared__ __attribute__((aligned(16))) bf16_t Ot[D * PT];
-  __shared__ float lse_s[64], delta_s[64];
+  __shared__ __attribute__((aligned(16))) float lse_s[64], delta_s[64];
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
   const int k0 = blockIdx.x * 128, head = blockIdx.y, b = blockIdx.z;
@@ -360,19 +360,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[ks], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ofr, vf[ks], dp, 0, 0, 0);
         }
-        f32x16 ds;
+        // p in s, dS in dp (in place); the per-query statistics come four at a time
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qi = mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-          float p = exp2f(s[r] * c - lse_s[qi]);
-          if (diag && key > qq0 + qi) p = 0.f;
-          s[r] = p;
-          ds[r] = p * (dp[r] - delta_s[qi]);
+        for (int rg = 0; rg < 4; ++rg) {
+          const int qb = mt * 32 + rg * 8 + g * 4;
+          const float4 l4 = *(const float4*)(lse_s + qb);
+          const float4 d4 = *(const float4*)(delta_s + qb);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = rg * 4 + e;
+            float p = exp2f(s[r] * c - lv[e]);
+            if (diag && key > qq0 + qb + e) p = 0.f;
+            s[r] = p;
+            dp[r] = p * (dp[r] - dl[e]);
+          }
         }
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
           bf16x8 pf = frag_regs(s, st, 1.f);
-          bf16x8 dsf = frag_regs(ds, st, scale);
+          bf16x8 dsf = frag_regs(dp, st, scale);
 #pragma unroll
           for (int i = 0; i < D / 32; ++i) {
             bf16x8 otf = frag2(Ot + (i * 32 + lrow) * PT + mt * 32 + st * 16 + g * 4);

@@ -19,7 +19,14 @@ __device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest even, Na
   u += 0x7fffu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
-__device__ __forceinline__ unsigned pack2(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
+// two floats -> packed bf16 pair with the hardware converter (v_cvt_pk_bf16_f32, RNE)
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ unsigned pack2(float lo, float hi) {
+  f32x2_t f = {lo, hi};
+  bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+  return __builtin_bit_cast(unsigned, b);
+}
 
 constexpr int LDS_PAD = 8;   // elements: a 16-byte skew per row keeps ds_read_b128 conflict-free
 
@@ -36,8 +43,30 @@ struct TileMover {
   static_assert(KC || VECS % 4 == 0, "transposing mover needs whole 8x4 patches per thread");
   u32x4 reg[VECS];
 
+  // full: the whole tile lies inside the matrix, no bounds checks needed
   __device__ __forceinline__ void load(const bf16_t* __restrict__ G, size_t ld, int row0, int k0, int rows_total,
-                                       int k_total, int tid) {
+                                       int k_total, int tid, bool full = false) {
+    if (full) {
+      if (KC) {
+#pragma unroll
+        for (int i = 0; i < VECS; ++i) {
+          int v = tid + i * T, row = v / (BK / 8), kc = v % (BK / 8);
+          reg[i] = *(const u32x4*)(G + (size_t)(row0 + row) * ld + k0 + kc * 8);
+        }
+      } else {
+#pragma unroll
+        for (int b = 0; b < VECS / 4; ++b) {
+          int v = tid + b * T, rg = v % (ROWS / 4), kg = v / (ROWS / 4);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            u32x2 r = *(const u32x2*)(G + (size_t)(k0 + kg * 8 + q) * ld + row0 + rg * 4);
+            reg[b * 4 + q / 2][(q & 1) * 2] = r.x;
+            reg[b * 4 + q / 2][(q & 1) * 2 + 1] = r.y;
+          }
+        }
+      }
+      return;
+    }
     if (KC) {
 #pragma unroll
       for (int i = 0; i < VECS; ++i) {

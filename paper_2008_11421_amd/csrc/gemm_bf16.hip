@@ -9,6 +9,7 @@
 // one register-resident tile in flight (double buffer); v_mfma_f32_32x32x16_bf16 does the
 // arithmetic; the workgroup -> tile map keeps each XCD's L2 on a compact patch of C.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 
 #include "karma.h"
 #include "device_utils.h"
@@ -23,126 +24,285 @@ struct GemmEpilogue {
   int ldc;
   int out_f32;             // store fp32 instead of bf16
   int accumulate;          // fp32 output only: C += result
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
-    if (bias) v += bf2f(bias[n]);
-    size_t at = (size_t)m * ldc + n;
-    if (out_f32) {
-      float* c = (float*)C;
-      c[at] = accumulate ? c[at] + v : v;
+  // eight consecutive columns n..n+7 of row m (n multiple of 8); cols = how many are inside the matrix
+  __device__ __forceinline__ void octet(int m, int n, int cols, const float4& lo, const float4& hi) const {
+    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    const size_t at = (size_t)m * ldc + n;
+    if (cols == 8 && (ldc & 7) == 0) {
+      if (bias) {
+        u32x4 b = *(const u32x4*)(bias + n);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(b[e] << 16); v[2 * e + 1] += __uint_as_float(b[e] & 0xffff0000u); }
+      }
+      if (out_f32) {
+        float4* c = (float4*)((float*)C + at);
+        float4 o0 = make_float4(v[0], v[1], v[2], v[3]), o1 = make_float4(v[4], v[5], v[6], v[7]);
+        if (accumulate) {
+          float4 p0 = c[0], p1 = c[1];
+          o0.x += p0.x; o0.y += p0.y; o0.z += p0.z; o0.w += p0.w;
+          o1.x += p1.x; o1.y += p1.y; o1.z += p1.z; o1.w += p1.w;
+        }
+        c[0] = o0;
+        c[1] = o1;
+      } else {
+        if (residual) {
+          u32x4 r = *(const u32x4*)(residual + at);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(r[e] << 16); v[2 * e + 1] += __uint_as_float(r[e] & 0xffff0000u); }
+        }
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = pack2(v[2 * e], v[2 * e + 1]);
+        __builtin_nontemporal_store(o, (u32x4*)((bf16_t*)C + at));
+      }
     } else {
-      if (residual) v += bf2f(residual[at]);
-      ((bf16_t*)C)[at] = f2bf(v);
+      for (int e = 0; e < cols; ++e) {
+        float x = v[e];
+        if (bias) x += bf2f(bias[n + e]);
+        if (out_f32) {
+          float* c = (float*)C;
+          c[at + e] = accumulate ? c[at + e] + x : x;
+        } else {
+          if (residual) x += bf2f(residual[at + e]);
+          ((bf16_t*)C)[at + e] = f2bf(x);
+        }
+      }
     }
   }
 };
 
+// Persistent kernel: each workgroup walks work items (output tile x k-split) with stride
+// gridDim.x.  Per item: the first k-tile is already in registers (loaded while the previous
+// item's results were being written out), the main loop is software-pipelined by hand
+// (fragments of step kk+1 are read from LDS while the MFMAs of step kk run; the next
+// k-tile's global loads are issued at the top and parked in LDS half way through), and the
+// results leave through an LDS strip so that stores are row-contiguous.  The stores are
+// not waited for: they drain while the next item computes.
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                    const bf16_t* __restrict__ B, int M, int N, int K,
                                                                    int lda, int ldb, int tiles_m, int tiles_n,
-                                                                   GemmEpilogue ep) {
+                                                                   int splits, int k_per_split, GemmEpilogue ep,
+                                                                   float* __restrict__ partial) {
   constexpr int T = WGM * WGN * 64;
   constexpr int PITCH = BK + LDS_PAD;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int KSTEPS = BK / 16;
+  static_assert(KSTEPS % 2 == 0, "fragment double buffer alternates per step");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* As = (bf16_t*)smem;          // [2][BM][PITCH]
   bf16_t* Bs = As + 2 * BM * PITCH;    // [2][BN][PITCH]
 
-  // workgroup -> tile: consecutive ids go round-robin over the 8 XCDs, so give each XCD a
-  // contiguous range of tiles, and walk tiles in bands of 8 tile-rows so that a band's B
-  // panel stays in that XCD's L2.
-  const int total = tiles_m * tiles_n;
-  int id = blockIdx.x;
-  if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
-  constexpr int BAND = 8;
-  const int band_sz = BAND * tiles_n;
-  const int first_m = (id / band_sz) * BAND;
-  const int rows_in_band = min(tiles_m - first_m, BAND);
-  const int tile_m = first_m + (id % band_sz) % rows_in_band;
-  const int tile_n = (id % band_sz) / rows_in_band;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int lrow = lane & 31, lk = (lane >> 5) * 8;
+  const int total_tiles = tiles_m * tiles_n;
+  const int total_items = total_tiles * splits;
+
+  // item -> (tile, split).  Consecutive workgroup ids go round-robin over the 8 XCDs, so
+  // each XCD gets a contiguous range of tiles, walked in bands of 8 tile rows: a band's B
+  // panel stays in that XCD's L2.
+  auto decode = [&](int item, int& m0, int& n0, int& kb, int& ke, int& split) {
+    split = item / total_tiles;
+    int id = item % total_tiles;
+    if (total_tiles % 8 == 0) id = (id % 8) * (total_tiles / 8) + id / 8;
+    constexpr int BAND = 8;
+    const int band_sz = BAND * tiles_n;
+    const int first_m = (id / band_sz) * BAND;
+    const int rows_in_band = min(tiles_m - first_m, BAND);
+    m0 = (first_m + (id % band_sz) % rows_in_band) * BM;
+    n0 = ((id % band_sz) / rows_in_band) * BN;
+    kb = split * k_per_split;
+    ke = min(K, kb + k_per_split);
+  };
 
   TileMover<BM, BK, T, A_KC> ma;
   TileMover<BN, BK, T, B_KC> mb;
-  f32x16 acc[TM][TN];
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto read_frags = [&](int buf, int cur, int kk) {
+    const bf16_t* as = As + cur * BM * PITCH + (wm * WTM + lrow) * PITCH + lk + kk * 16;
+    const bf16_t* bs = Bs + cur * BN * PITCH + (wn * WTN + lrow) * PITCH + lk + kk * 16;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) af[buf][i] = *(const bf16x8*)(as + i * 32 * PITCH);
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int j = 0; j < TN; ++j) bfr[buf][j] = *(const bf16x8*)(bs + j * 32 * PITCH);
+  };
 
-  const int KT = (K + BK - 1) / BK;
-  ma.load(A, lda, m0, 0, M, K, tid);
-  mb.load(B, ldb, n0, 0, N, K, tid);
-  ma.store(As, tid);
-  mb.store(Bs, tid);
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) {
-      ma.load(A, lda, m0, (kt + 1) * BK, M, K, tid);
-      mb.load(B, ldb, n0, (kt + 1) * BK, N, K, tid);
-    }
-    const bf16_t* as = As + cur * BM * PITCH + (wm * WTM + lrow) * PITCH + lk;
-    const bf16_t* bs = Bs + cur * BN * PITCH + (wn * WTN + lrow) * PITCH + lk;
+  int item = blockIdx.x;
+  if (item >= total_items) return;
+  int m0, n0, kb, ke, split;
+  decode(item, m0, n0, kb, ke, split);
+  bool full = m0 + BM <= M && n0 + BN <= N && (ke - kb) % BK == 0;
+  ma.load(A, lda, m0, kb, M, ke, tid, full);
+  mb.load(B, ldb, n0, kb, N, ke, tid, full);
+
+  for (;;) {
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[TM], bfr[TN];
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(as + i * 32 * PITCH + kk * 16);
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(bs + j * 32 * PITCH + kk * 16);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) {
-      ma.store(As + (cur ^ 1) * BM * PITCH, tid);
-      mb.store(Bs + (cur ^ 1) * BN * PITCH, tid);
-    }
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    __syncthreads();   // the previous item's strip reads are done
+    ma.store(As, tid);
+    mb.store(Bs, tid);
     __syncthreads();
-  }
+    read_frags(0, 0, 0);
+    const int KT = (ke - kb + BK - 1) / BK;
+    for (int kt = 0; kt < KT; ++kt) {
+      const int cur = kt & 1;
+      const bool more = kt + 1 < KT;
+      if (more) {
+        ma.load(A, lda, m0, kb + (kt + 1) * BK, M, ke, tid, full);
+        mb.load(B, ldb, n0, kb + (kt + 1) * BK, N, ke, tid, full);
+      }
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, cur, kk + 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk == KSTEPS / 2 - 1 && more) {
+          ma.store(As + (cur ^ 1) * BM * PITCH, tid);
+          mb.store(Bs + (cur ^ 1) * BN * PITCH, tid);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __syncthreads();
+      if (more) read_frags(0, cur ^ 1, 0);
+    }
 
-  // accumulator layout of the 32x32 MFMA: register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
-  // column l%32
+    // where the results of this item go
+    const int out_m0 = m0, out_n0 = n0, out_split = split;
+    // start fetching the next item's first k-tile before writing this one out
+    item += gridDim.x;
+    const bool have_next = item < total_items;
+    if (have_next) {
+      decode(item, m0, n0, kb, ke, split);
+      full = m0 + BM <= M && n0 + BN <= N && (ke - kb) % BK == 0;
+      ma.load(A, lda, m0, kb, M, ke, tid, full);
+      mb.load(B, ldb, n0, kb, N, ke, tid, full);
+    }
+
+    // Epilogue through LDS (the operand tiles are dead now): each wavefront parks one 32-row
+    // strip of its tile as fp32 [32][WTN], then reads it back row-wise so that a run of lanes
+    // stores one contiguous piece of a row.  Accumulator layout of the 32x32 MFMA: register r
+    // of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32.
+    constexpr int SP = WTN + 4;   // fp32 pitch of the strip
+    static_assert((size_t)WGM * WGN * 32 * SP * 4 <= (size_t)2 * (BM + BN) * PITCH * 2, "strip does not fit the tile LDS");
+    float* strip = (float*)smem + wave * 32 * SP;
+    constexpr int QPR = WTN / 8;              // octets per strip row
+    constexpr int RPI = 64 / QPR;             // rows covered per pass of the wavefront
+    static_assert(64 % QPR == 0 && 32 % RPI == 0, "strip read-out does not tile");
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      if (i) __syncthreads();
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * WTN + j * 32 + lrow;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WTM + i * 32 + (r / 4) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (m < M && n < N) ep(m, n, acc[i][j][r]);
+        for (int r = 0; r < 16; ++r)
+          strip[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * SP + j * 32 + lrow] = acc[i][j][r];
+      __syncthreads();
+      const int q = lane % QPR, rr = lane / QPR;
+      const int n = out_n0 + wn * WTN + q * 8;
+#pragma unroll
+      for (int pass = 0; pass < 32 / RPI; ++pass) {
+        const int row = pass * RPI + rr;
+        const int m = out_m0 + wm * WTM + i * 32 + row;
+        const float4 v = *(const float4*)(strip + row * SP + q * 8);
+        const float4 u = *(const float4*)(strip + row * SP + q * 8 + 4);
+        if (m < M && n < N) {
+          if (splits > 1) {
+            float* dst = partial + ((size_t)out_split * M + m) * N + n;
+            const float vv[8] = {v.x, v.y, v.z, v.w, u.x, u.y, u.z, u.w};
+            if (n + 8 <= N && (N & 3) == 0) { *(float4*)dst = v; *(float4*)(dst + 4) = u; }
+            else for (int e = 0; e < N - n && e < 8; ++e) dst[e] = vv[e];
+          } else {
+            ep.octet(m, n, min(8, N - n), v, u);
+          }
+        }
       }
     }
+    if (!have_next) break;
+  }
+}
+
+// out = sum over splits (ascending) of partial[s], then the epilogue's conversions
+__global__ void splitk_reduce_kernel(const float* __restrict__ partial, int splits, size_t mn, GemmEpilogue ep, int N) {
+  size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= mn) return;
+  const int cnt = (int)min((size_t)4, mn - i);
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s)
+    for (int e = 0; e < cnt; ++e) v[e] += partial[(size_t)s * mn + i + e];
+  // rows are dense (ldc == N) in the split-k path, so element i is (i / N, i % N)
+  for (int e = 0; e < cnt; ++e) {
+    const size_t at = i + e;
+    float x = v[e];
+    if (ep.bias) x += bf2f(ep.bias[at % N]);
+    if (ep.out_f32) {
+      float* c = (float*)ep.C;
+      c[at] = ep.accumulate ? c[at] + x : x;
+    } else {
+      if (ep.residual) x += bf2f(ep.residual[at]);
+      ((bf16_t*)ep.C)[at] = f2bf(x);
+    }
+  }
+}
+
+static int g_cus = 0;
+static int compute_units() {
+  if (!g_cus) {
+    int dev = 0;
+    hipDeviceProp_t p;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess) g_cus = p.multiProcessorCount;
+    if (g_cus <= 0) g_cus = 256;
+  }
+  return g_cus;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN>
 static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const int tiles = tiles_m * tiles_n;
+  const int cus = compute_units();
+  // split the reduction when the tiles alone cannot fill the chip (weight gradients:
+  // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
+  int splits = 1;
+  if (g.ws && g.ldc == g.N && tiles < 2 * cus) {
+    splits = std::min(16, (2 * cus + tiles - 1) / tiles);
+    splits = std::min(splits, std::max(1, g.K / (4 * BK)));
+    while (splits > 1 && (size_t)splits * g.M * g.N * sizeof(float) > g.ws_bytes) --splits;
+  }
+  int k_per_split = (g.K + splits - 1) / splits;
+  k_per_split = (k_per_split + BK - 1) / BK * BK;
+  splits = (g.K + k_per_split - 1) / k_per_split;
   const size_t lds = (size_t)2 * (BM + BN) * (BK + LDS_PAD) * sizeof(bf16_t);
   GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate};
-  dim3 grid(tiles_m * tiles_n), block(WGM * WGN * 64);
+  dim3 grid(std::min(tiles * splits, cus)), block(WGM * WGN * 64);
 #define KARMA_GEMM_LAUNCH(AK, BKC)                                                                      \
   do {                                                                                                  \
     auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, AK, BKC>;                                        \
     if (lds > 64 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-    hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, ep);  \
+    hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,  \
+                       k_per_split, ep, (float*)g.ws);                                                  \
   } while (0)
   if (g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(true, true);
   else if (g.a_kc && !g.b_kc) KARMA_GEMM_LAUNCH(true, false);
   else if (!g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(false, true);
   else KARMA_GEMM_LAUNCH(false, false);
 #undef KARMA_GEMM_LAUNCH
+  if (splits > 1) {
+    const size_t mn = (size_t)g.M * g.N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((mn / 4 + 255) / 256 + 1)), dim3(256), 0, s,
+                       (const float*)g.ws, splits, mn, ep, g.N);
+  }
   return hipGetLastError() == hipSuccess ? KARMA_OK : KARMA_E_HIP;
 }
 
@@ -154,6 +314,7 @@ int gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.b_kc ? (g.ldb % 8) : (g.ldb % 4 || g.N % 4)) return KARMA_E_INVAL;
   if (g.accumulate && !g.out_f32) return KARMA_E_INVAL;
   if (g.residual && g.out_f32) return KARMA_E_INVAL;
+  if (g.M > 128 && g.N > 128) return launch_cfg<256, 256, 64, 2, 4>(g, s);
   return launch_cfg<128, 128, 64, 2, 2>(g, s);
 }
 
@@ -162,7 +323,8 @@ int gemm_bf16(const GemmArgs& g, hipStream_t s) {
 using namespace karma;
 
 extern "C" int karma_k_gemm_bf16(const void* a, const void* b, void* c, const void* bias, const void* residual,
-                                 uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* stream) {
+                                 uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* ws, uint64_t ws_bytes,
+                                 void* stream) {
   GemmArgs g{};
   g.A = (const bf16_t*)a;
   g.B = (const bf16_t*)b;
@@ -177,5 +339,7 @@ extern "C" int karma_k_gemm_bf16(const void* a, const void* b, void* c, const vo
   g.ldc = (int)n;
   g.out_f32 = (flags & KARMA_GEMM_OUT_F32) != 0;
   g.accumulate = (flags & KARMA_GEMM_ACCUMULATE) != 0;
+  g.ws = ws;
+  g.ws_bytes = ws ? (size_t)ws_bytes : 0;
   return gemm_bf16(g, (hipStream_t)stream);
 }

@@ -26,6 +26,8 @@ struct GemmArgs {
   const bf16_t* bias; const bf16_t* residual;
   int M, N, K, lda, ldb, ldc;
   bool a_kc, b_kc, out_f32, accumulate;
+  void* ws;          // optional fp32 workspace for split-k partial sums (dense C only)
+  size_t ws_bytes;
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
 

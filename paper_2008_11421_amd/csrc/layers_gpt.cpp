@@ -46,7 +46,7 @@ struct BlockSaved {
 
 // backward workspace of one block
 struct BlockWs {
-  uint64_t wide, t1, t2, t3, delta, part, total;
+  uint64_t wide, t1, t2, t3, delta, part, splitk, splitk_bytes, total;
   explicit BlockWs(const Dims& d) {
     uint64_t o = 0;
     auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
@@ -56,6 +56,8 @@ struct BlockWs {
     t3 = take((uint64_t)d.T * d.h * 2);                           // da
     delta = take((uint64_t)d.B * d.H * d.S * 4);
     part = take(std::max(layernorm_bwd_ws_bytes(d.T, d.h), colsum_ws_bytes(d.T, std::max(d.ffn, 3 * d.h))));
+    splitk_bytes = (uint64_t)8 * std::max(d.ffn, 3 * d.h) * d.h * 4;   // partial sums of the weight-gradient GEMMs
+    splitk = take(splitk_bytes);
     total = o;
   }
 };
@@ -90,7 +92,7 @@ Param make_param(uint64_t n, bool matrix) {
 }
 
 int gemm_raw(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
-             bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s) {
+             bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s, void* ws, size_t ws_bytes) {
   GemmArgs g{};
   g.A = A; g.B = B; g.C = C; g.bias = bias; g.residual = res;
   g.M = M; g.N = N; g.K = K;
@@ -99,22 +101,23 @@ int gemm_raw(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, cons
   g.ldb = b_kc ? K : N;
   g.ldc = N;
   g.out_f32 = out_f32; g.accumulate = acc;
+  g.ws = ws; g.ws_bytes = ws_bytes;
   return gemm_bf16(g, s);
 }
 
 // every GEMM of the model goes through here so that a profiled step can time each launch
 thread_local Ctx* g_ctx = nullptr;
 int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
-         bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s) {
+         bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s, void* ws = nullptr, size_t ws_bytes = 0) {
   Ctx* c = g_ctx;
-  if (!c || !c->ktime) return gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s);
+  if (!c || !c->ktime) return gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s, ws, ws_bytes);
   while (c->kev.size() < c->kev_used + 2) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return KARMA_E_HIP;
     c->kev.push_back(e);
   }
   if (hipEventRecord(c->kev[c->kev_used], s) != hipSuccess) return KARMA_E_HIP;
-  int st = gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s);
+  int st = gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s, ws, ws_bytes);
   if (hipEventRecord(c->kev[c->kev_used + 1], s) != hipSuccess) return KARMA_E_HIP;
   c->kev_used += 2;
   c->kflops.push_back(2.0 * M * N * K);
@@ -268,25 +271,25 @@ int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
 
   // FC2: y = r1 + g W2^T + b2
   TRY(gemm(dy, W(W2), wide, nullptr, nullptr, d.T, d.ffn, d.h, true, false, false, false, s));     // dg = dy W2
-  TRY(gemm(dy, g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s));        // dW2 = dy^T g
+  TRY(gemm(dy, g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));        // dW2 = dy^T g
   TRY(colsum_bf16(dy, (float*)G(B2), part, d.T, d.h, s));
   TRY(gelu_bwd(f1, wide, wide, (size_t)d.T * d.ffn, s));                                            // df1
   // FC1
   TRY(gemm(wide, W(W1), t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
-  TRY(gemm(wide, m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s));      // dW1 = df1^T m
+  TRY(gemm(wide, m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));      // dW1 = df1^T m
   TRY(colsum_bf16(wide, (float*)G(B1), part, d.T, d.ffn, s));
   // LN2 and the residual branch: dr1 = LN2'(dm) + dy
   TRY(layernorm_bwd(t1, r1, (const float*)(S + sv.stats2), W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), part,
                     d.T, d.h, s));
   // attention output projection
   TRY(gemm(dr1, W(WO), t1, nullptr, nullptr, d.T, d.h, d.h, true, false, false, false, s));         // dctx = dr1 Wo
-  TRY(gemm(dr1, ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s));       // dWo = dr1^T ctx
+  TRY(gemm(dr1, ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));       // dWo = dr1^T ctx
   TRY(colsum_bf16(dr1, (float*)G(BO), part, d.T, d.h, s));
   // attention
   TRY(attention_bwd(qkv, ctx, t1, (const float*)(S + sv.lse), (float*)(Wk + wl.delta), wide, d.B, d.S, d.H, d.D, s));
   // QKV projection
   TRY(gemm(wide, W(WQKV), da, nullptr, nullptr, d.T, d.h, 3 * d.h, true, false, false, false, s));  // da = dqkv Wqkv
-  TRY(gemm(wide, a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s));  // dWqkv = dqkv^T a
+  TRY(gemm(wide, a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));  // dWqkv = dqkv^T a
   TRY(colsum_bf16(wide, (float*)G(BQKV), part, d.T, 3 * d.h, s));
   // LN1 and the residual: dx = LN1'(da) + dr1
   TRY(layernorm_bwd(da, x, (const float*)(S + sv.stats1), W(LN1_G), dr1, (bf16_t*)io.dx, (float*)G(LN1_G),

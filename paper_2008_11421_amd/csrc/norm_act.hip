@@ -169,15 +169,26 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
   }
 }
 
-// out[c] = sum_p partial[p][c] in ascending p, converted to bf16 or kept fp32
-__global__ void colsum_finish_kernel(const float* __restrict__ partial, int parts, int stride, int cols,
-                                     bf16_t* __restrict__ out_bf16, float* __restrict__ out_f32) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= cols) return;
+// out[c] = sum_p partial[p][c]: eight slices of threads sum every eighth partial, then the
+// slices are added in ascending order (a fixed association, so results are reproducible)
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial, int parts, int stride,
+                                                             int cols, bf16_t* __restrict__ out_bf16,
+                                                             float* __restrict__ out_f32) {
+  __shared__ float red[8][32];
+  const int cl = threadIdx.x & 31, slice = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
   float s = 0.f;
-  for (int p = 0; p < parts; ++p) s += partial[(size_t)p * stride + c];
-  if (out_bf16) out_bf16[c] = f2bf_(s);
-  if (out_f32) out_f32[c] = s;
+  if (c < cols)
+    for (int p = slice; p < parts; p += 8) s += partial[(size_t)p * stride + c];
+  red[slice][cl] = s;
+  __syncthreads();
+  if (slice == 0 && c < cols) {
+    float t = red[0][cl];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) t += red[k][cl];
+    if (out_bf16) out_bf16[c] = f2bf_(t);
+    if (out_f32) out_f32[c] = t;
+  }
 }
 
 // column sums of a bf16 matrix [rows][cols]: each workgroup sums a band of rows
@@ -414,9 +425,9 @@ int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const b
   else if (per_lane <= 9) KARMA_LN_BWD(9);
   else KARMA_LN_BWD(12);
 #undef KARMA_LN_BWD
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((h + 255) / 256), dim3(256), 0, s, partial_ws, parts, 2 * h, h,
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((h + 31) / 32), dim3(256), 0, s, partial_ws, parts, 2 * h, h,
                      (bf16_t*)nullptr, dgamma);
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((h + 255) / 256), dim3(256), 0, s, partial_ws + h, parts, 2 * h, h,
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((h + 31) / 32), dim3(256), 0, s, partial_ws + h, parts, 2 * h, h,
                      (bf16_t*)nullptr, dbeta);
   return ok();
 }
@@ -427,7 +438,7 @@ int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int co
   if (cols % 8 || rows <= 0) return KARMA_E_INVAL;
   const int parts = (rows + CS_ROWS - 1) / CS_ROWS;
   hipLaunchKernelGGL(colsum_partial_kernel, dim3(parts, (cols / 8 + 255) / 256), dim3(256), 0, s, x, partial_ws, rows, cols);
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, partial_ws, parts, cols, cols,
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, partial_ws, parts, cols, cols,
                      (bf16_t*)nullptr, out);
   return ok();
 }

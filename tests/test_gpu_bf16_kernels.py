@@ -49,11 +49,11 @@ def test_gemm_layouts(g, m, n, k, flags):
     if flags & K.GEMM_B_STRIDED:
         bd = bd.t().contiguous()
     c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
-    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), None, None, m, n, k, flags, g.stream_ptr())
+    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), None, None, m, n, k, flags, None, 0, g.stream_ptr())
     assert g.rel_l2(back(c), ref) <= TOL_BF16
     c32 = torch.empty(m, n, dtype=torch.float32, device="cuda")
     g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c32), None, None, m, n, k, flags | K.GEMM_OUT_F32,
-           g.stream_ptr())
+           None, 0, g.stream_ptr())
     assert g.rel_l2(back(c32), ref) <= TOL_F32
     # element-wise bound as well: no single entry may be off by more than a few ulps of bf16
     scale = np.abs(a) @ np.abs(b.T)
@@ -68,23 +68,56 @@ def test_gemm_epilogues(g):
     bias, biasd = bf(si.normal(5, (n,)))
     res, resd = bf(si.normal(6, (m, n)))
     c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
-    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), g.ptr(biasd), g.ptr(resd), m, n, k, 0, g.stream_ptr())
+    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), g.ptr(biasd), g.ptr(resd), m, n, k, 0, None, 0, g.stream_ptr())
     assert g.rel_l2(back(c), a @ b.T + bias + res) <= TOL_BF16
     acc0 = si.normal(7, (m, n)).astype(np.float32)
     c32 = torch.from_numpy(acc0).cuda()
     g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c32), None, None, m, n, k,
-           K.GEMM_OUT_F32 | K.GEMM_ACCUMULATE, g.stream_ptr())
+           K.GEMM_OUT_F32 | K.GEMM_ACCUMULATE, None, 0, g.stream_ptr())
     assert g.rel_l2(back(c32), acc0.astype(np.float64) + a @ b.T) <= TOL_F32
+
+
+@pytest.mark.parametrize("m,n,k,flags", [(512, 256, 8192, 3), (200, 136, 4096 + 72, 0), (1024, 1024, 32768, 3), (384, 264, 2048, 2)])
+def test_gemm_split_k(g, m, n, k, flags):
+    """With a workspace the reduction is split over workgroups and summed in a fixed order:
+    same tolerance, bit-identical from run to run, epilogues still applied."""
+    import torch
+    a, ad = bf(si.normal(8, (m, k)))
+    b, bd = bf(si.normal(9, (n, k)))
+    ref = a @ b.T
+    if flags & K.GEMM_A_STRIDED:
+        ad = ad.t().contiguous()
+    if flags & K.GEMM_B_STRIDED:
+        bd = bd.t().contiguous()
+    ws = torch.empty(16 * m * n, dtype=torch.float32, device="cuda")
+    outs = []
+    for _ in range(2):
+        c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+        g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), None, None, m, n, k, flags, g.ptr(ws),
+               C.c_uint64(ws.numel() * 4), g.stream_ptr())
+        outs.append(c)
+    assert g.rel_l2(back(outs[0]), ref) <= TOL_BF16
+    assert torch.equal(outs[0], outs[1])
+    acc0 = si.normal(7, (m, n)).astype(np.float32)
+    c32 = torch.from_numpy(acc0).cuda()
+    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c32), None, None, m, n, k,
+           flags | K.GEMM_OUT_F32 | K.GEMM_ACCUMULATE, g.ptr(ws), C.c_uint64(ws.numel() * 4), g.stream_ptr())
+    assert g.rel_l2(back(c32), acc0.astype(np.float64) + ref) <= TOL_F32
+    # a workspace that is too small for any split still gives the right answer
+    c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), None, None, m, n, k, flags, g.ptr(ws),
+           C.c_uint64(1024), g.stream_ptr())
+    assert g.rel_l2(back(c), ref) <= TOL_BF16
 
 
 def test_gemm_rejects_bad_shapes(g):
     import torch
     t = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
     lib = K.lib()
-    assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 8, 8, 12, 0, g.stream_ptr()) == K.E_INVAL
-    assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 6, 8, 8, K.GEMM_A_STRIDED, g.stream_ptr()) == K.E_INVAL
-    assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 8, 8, 8, K.GEMM_ACCUMULATE, g.stream_ptr()) == K.E_INVAL
-    assert lib.karma_k_gemm_bf16(None, g.ptr(t), g.ptr(t), None, None, 8, 8, 8, 0, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 8, 8, 12, 0, None, 0, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 6, 8, 8, K.GEMM_A_STRIDED, None, 0, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_gemm_bf16(g.ptr(t), g.ptr(t), g.ptr(t), None, None, 8, 8, 8, K.GEMM_ACCUMULATE, None, 0, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_gemm_bf16(None, g.ptr(t), g.ptr(t), None, None, 8, 8, 8, 0, None, 0, g.stream_ptr()) == K.E_INVAL
 
 
 TOL_ATTN = 1e-2   # three chained bf16 roundings (probabilities, dS, result), each <= 2^-9
