@@ -250,7 +250,7 @@ int karma_k_layernorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const v
 int karma_k_layernorm_bwd_bf16(const void* dy_dev, const void* x_dev, const float* stats_dev, const void* gamma_dev,
                                const void* add_dev, void* dx_dev, float* dgamma_dev, float* dbeta_dev, float* ws_dev,
                                uint64_t ws_bytes, uint32_t rows, uint32_t h, void* stream);
-/* out[c] = sum over rows of x[r][c] (bias gradients), fixed order.  ws: ceil(rows/128)*cols floats. */
+/* out[c] = sum over rows of x[r][c] (bias gradients), fixed order.  ws: ceil(rows/64)*cols floats. */
 int karma_k_colsum_bf16(const void* x_dev, float* out_dev, float* ws_dev, uint64_t ws_bytes, uint32_t rows,
                         uint32_t cols, void* stream);
 /* tanh-form GELU and its gradient dx = dy * gelu'(x); n multiple of 8. */

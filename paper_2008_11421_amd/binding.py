@@ -82,6 +82,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise OSError("libkarma.so is not built: run `python -m paper_2008_11421_amd.build` "
                           "(there is no CPU fallback)")
+        # torch ships its own HIP runtime: load it first so that the library binds to the same
+        # one (two runtimes in a process do not share allocations)
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         _lib.karma_last_error.restype = C.c_char_p
         _lib.karma_last_error.argtypes = [C.c_void_p]

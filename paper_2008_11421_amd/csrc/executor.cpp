@@ -5,6 +5,7 @@
 // streams; cross-stream ordering is by events.
 #include <algorithm>
 #include <chrono>
+#include <cstdio>
 #include <cstring>
 
 #include "context.h"
@@ -389,7 +390,12 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   // host state
   bool ok = true;
   auto pin = [&](void** p, uint64_t bytes) {
-    if (ok && hipHostMalloc(p, bytes ? bytes : 256, hipHostMallocDefault) != hipSuccess) ok = false;
+    if (!ok) return;
+    hipError_t e = hipHostMalloc(p, bytes ? bytes : 256, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      std::fprintf(stderr, "karma_create: hipHostMalloc(%llu) failed: %s\n", (unsigned long long)bytes, hipGetErrorString(e));
+      ok = false;
+    }
   };
   for (Record& r : c->rec)
     for (Param& p : r.p) {
@@ -404,7 +410,10 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   pin(&c->stage_misc, c->misc_bytes);
   c->grad_ev.assign(c->rec.size(), nullptr);
   for (auto& e : c->grad_ev)
-    if (ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) ok = false;
+    if (ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+      std::fprintf(stderr, "karma_create: hipEventCreate failed\n");
+      ok = false;
+    }
   if (!ok) { karma_destroy(c); return KARMA_E_HOSTMEM; }
   c->pool.reset(new HostPool(cfg->host_threads ? cfg->host_threads : 1));
   *out = c;
@@ -570,6 +579,14 @@ extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) 
   if (st) return st;
   // inputs: whatever the staging buffers hold (zeros on a fresh context are valid ids / values)
   std::vector<char> in(c->in_bytes ? c->in_bytes : 1, 0), lab(c->lab_bytes ? c->lab_bytes : 1, 0);
+  if (c->desc.kind == KARMA_MODEL_GPT) {   // spread token ids over the vocabulary, as real batches do
+    int32_t* ids = (int32_t*)in.data();
+    int32_t* lb = (int32_t*)lab.data();
+    for (uint64_t t = 0; t < c->in_bytes / 4; ++t) {
+      ids[t] = (int32_t)((t * 7919u) % c->desc.vocab);
+      lb[t] = (int32_t)((t * 104729u + 1) % c->desc.vocab);
+    }
+  }
   std::vector<std::vector<float>> samples(c->prog.size());
   for (uint32_t r = 0; r < reps + 1; ++r) {
     float loss;

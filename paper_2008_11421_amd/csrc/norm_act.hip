@@ -192,7 +192,7 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restr
 }
 
 // column sums of a bf16 matrix [rows][cols]: each workgroup sums a band of rows
-constexpr int CS_ROWS = 128;
+constexpr int CS_ROWS = 64;
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ x, float* __restrict__ partial,
                                                               int rows, int cols) {
   // thread owns 8 consecutive columns; 256 threads cover 2048 columns per blockIdx.y
@@ -200,7 +200,20 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __res
   if (c8 >= cols) return;
   float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   const int r0 = blockIdx.x * CS_ROWS, r1 = min(rows, r0 + CS_ROWS);
-  for (int r = r0; r < r1; ++r) {
+  int r = r0;
+  for (; r + 8 <= r1; r += 8) {   // eight independent loads in flight, added in row order
+    u32x4 q[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) q[k] = *(const u32x4*)(x + (size_t)(r + k) * cols + c8);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      float v[8];
+      unpack8(q[k], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] += v[e];
+    }
+  }
+  for (; r < r1; ++r) {
     float v[8];
     unpack8(*(const u32x4*)(x + (size_t)r * cols + c8), v);
 #pragma unroll

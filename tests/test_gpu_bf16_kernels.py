@@ -161,7 +161,7 @@ def test_colsum(g, rows, cols):
     import torch
     x, xd = bf(si.normal(21, (rows, cols)))
     out = torch.empty(cols, device="cuda")
-    nws = ((rows + 127) // 128) * cols
+    nws = ((rows + 63) // 64) * cols
     ws = torch.empty(nws, device="cuda")
     g.call(K.lib().karma_k_colsum_bf16, g.ptr(xd), g.ptr(out), g.ptr(ws), C.c_uint64(nws * 4), rows, cols, g.stream_ptr())
     assert g.rel_l2(out.cpu().numpy(), x.sum(0)) <= TOL_F32

@@ -1,0 +1,131 @@
+"""Parity at the benchmark's full sizes (configs[1]: 32768 tokens, hidden 1024, FFN 4096,
+vocabulary 32000, 16 heads), in the launch configurations bench.py times.  The oracle
+cannot compute whole results at these sizes in seconds, so it computes sampled outputs
+one by one (rows, heads, entries) from the same seeded inputs."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import paper_2008_11421_amd as K
+from oracle import nn
+import synth_inputs as si
+from test_gpu_bf16_kernels import TOL_ATTN, TOL_BF16, TOL_F32, back
+
+T, H, FFN, V, HEADS, S, B = 32768, 1024, 4096, 32000, 16, 1024, 32
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    import torch
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def dev_normal(seed, shape, std=1.0):
+    """Large seeded bf16 tensor: generated on the host in fp32, rounded to bf16."""
+    import torch
+    a = si.normal(seed, shape, std).astype(np.float32)
+    t = torch.from_numpy(a).to(torch.bfloat16).cuda()
+    return t
+
+
+def rows_of(t, idx):
+    return t[idx].float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("m,n,k,flags,use_ws", [(T, FFN, H, 0, False), (T, H, FFN, K.GEMM_B_STRIDED, False),
+                                                (FFN, H, T, K.GEMM_A_STRIDED | K.GEMM_B_STRIDED, True),
+                                                (4096, V, H, 0, False)])
+def test_gemm_full_size_sampled_entries(g, m, n, k, flags, use_ws):
+    import torch
+    a = dev_normal(101, (k, m) if flags & K.GEMM_A_STRIDED else (m, k))
+    b = dev_normal(102, (k, n) if flags & K.GEMM_B_STRIDED else (n, k))
+    c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(8 * m * n, dtype=torch.float32, device="cuda") if use_ws else None
+    g.call(K.lib().karma_k_gemm_bf16, g.ptr(a), g.ptr(b), g.ptr(c), None, None, m, n, k, flags,
+           g.ptr(ws) if use_ws else None, C.c_uint64(ws.numel() * 4 if use_ws else 0), g.stream_ptr())
+    rng = np.random.default_rng(5)
+    ms = np.r_[0, m - 1, rng.integers(0, m, 30)]
+    ns = np.r_[0, n - 1, rng.integers(0, n, 30)]
+    A = (a[:, ms].t() if flags & K.GEMM_A_STRIDED else a[ms]).float().cpu().numpy().astype(np.float64)   # [32, k]
+    Bm = (b[:, ns].t() if flags & K.GEMM_B_STRIDED else b[ns]).float().cpu().numpy().astype(np.float64)
+    ref = A @ Bm.T
+    got = c[ms][:, ns].float().cpu().numpy()
+    assert g.rel_l2(got, ref) <= TOL_BF16
+    assert np.all(np.abs(got - ref) <= 2.0 ** -7 * (np.abs(A) @ np.abs(Bm.T)) / np.sqrt(k) * 8 + 1e-6)
+
+
+def test_attention_full_size_sampled_heads(g):
+    import torch
+    qkv = dev_normal(111, (B, S, 3 * H), 1.2)
+    dctx = dev_normal(112, (B, S, H))
+    ctx = torch.empty(B, S, H, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(B, HEADS, S, device="cuda")
+    dqkv = torch.empty_like(qkv)
+    delta = torch.empty(B, HEADS, S, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_attention_fwd_bf16, g.ptr(qkv), g.ptr(ctx), g.ptr(lse), B, S, HEADS, 64, g.stream_ptr())
+    g.call(lib.karma_k_attention_bwd_bf16, g.ptr(qkv), g.ptr(ctx), g.ptr(dctx), g.ptr(lse), g.ptr(delta), g.ptr(dqkv),
+           B, S, HEADS, 64, g.stream_ptr())
+    for (b, hd) in [(0, 0), (31, 15), (7, 9)]:
+        sl = [slice(c * H + hd * 64, c * H + (hd + 1) * 64) for c in range(3)]
+        q, k, v = (qkv[b, :, s_].float().cpu().numpy().astype(np.float64) for s_ in sl)
+        do = dctx[b, :, sl[0]].float().cpu().numpy().astype(np.float64)
+        o, p = nn.attention_fwd(q, k, v)
+        assert g.rel_l2(back(ctx[b, :, sl[0]]), o) <= TOL_ATTN
+        dq, dk, dv = nn.attention_bwd(q, k, v, p, do)
+        for name, ref, s_ in (("dq", dq, sl[0]), ("dk", dk, sl[1]), ("dv", dv, sl[2])):
+            assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
+
+
+def test_rowwise_kernels_full_size_sampled_rows(g):
+    import torch
+    lib = K.lib()
+    rng = np.random.default_rng(9)
+    rows = np.r_[0, T - 1, rng.integers(0, T, 14)]
+    # LayerNorm forward / backward
+    x = dev_normal(121, (T, H), 2.0)
+    gam = dev_normal(122, (H,), 0.2) + 1
+    bet = dev_normal(123, (H,), 0.2)
+    dy = dev_normal(124, (T, H))
+    y = torch.empty_like(x); dx = torch.empty_like(x)
+    stats = torch.empty(T, 2, device="cuda")
+    dg = torch.empty(H, device="cuda"); db = torch.empty(H, device="cuda")
+    nws = (T // 64) * 2 * H
+    ws = torch.empty(nws, device="cuda")
+    g.call(lib.karma_k_layernorm_fwd_bf16, g.ptr(x), g.ptr(gam), g.ptr(bet), g.ptr(y), g.ptr(stats), T, H, g.stream_ptr())
+    g.call(lib.karma_k_layernorm_bwd_bf16, g.ptr(dy), g.ptr(x), g.ptr(stats), g.ptr(gam), None, g.ptr(dx), g.ptr(dg),
+           g.ptr(db), g.ptr(ws), C.c_uint64(nws * 4), T, H, g.stream_ptr())
+    xo, go, bo, dyo = rows_of(x, rows), back(gam), back(bet), rows_of(dy, rows)
+    yo, cache = nn.layernorm_fwd(xo, go, bo)
+    assert g.rel_l2(rows_of(y, rows), yo) <= TOL_BF16
+    dxo, _, _ = nn.layernorm_bwd(dyo, go, cache)
+    assert g.rel_l2(rows_of(dx, rows), dxo) <= TOL_BF16
+    # the column reductions over all 32768 rows: a few columns in full
+    cols = [0, 17, H - 1]
+    xc = x[:, cols].float().cpu().numpy().astype(np.float64); dyc = dy[:, cols].float().cpu().numpy().astype(np.float64)
+    st = stats.cpu().numpy().astype(np.float64)
+    xhat = (xc - st[:, :1]) * st[:, 1:]
+    assert g.rel_l2(dg[cols].cpu().numpy(), (dyc * xhat).sum(0)) <= 1e-3
+    assert g.rel_l2(db[cols].cpu().numpy(), dyc.sum(0)) <= TOL_F32
+    # GELU on the FFN activation
+    f = dev_normal(131, (T, FFN), 1.5)
+    gy = torch.empty_like(f)
+    g.call(lib.karma_k_gelu_fwd_bf16, g.ptr(f), g.ptr(gy), C.c_uint64(T * FFN), g.stream_ptr())
+    assert g.rel_l2(rows_of(gy, rows), nn.gelu_fwd(rows_of(f, rows))) <= TOL_BF16
+    # softmax cross-entropy on one head chunk (4096 x 32000)
+    z = dev_normal(141, (4096, V), 2.0)
+    zr = rows_of(z, rows % 4096)
+    labels = si.randint(142, (4096,), V).astype(np.int32)
+    labd = g.dev(labels)
+    rowloss = torch.empty(4096, device="cuda")
+    g.call(lib.karma_k_softmax_ce_bf16, g.ptr(z), g.ptr(labd), g.ptr(rowloss), 4096, V, C.c_float(1.0 / T), g.stream_ptr())
+    rr = rows % 4096
+    for j, r in enumerate(rr):
+        loss, d = nn.cross_entropy_fwd_bwd(zr[j:j + 1], labels[r:r + 1])
+        assert abs(rowloss[r].item() - loss) <= 1e-4 * abs(loss) + 1e-5
+        assert g.rel_l2(rows_of(z, [r]), d / T) <= TOL_BF16
