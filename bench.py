@@ -124,6 +124,20 @@ def main():
     log("predicted makespan %.1f ms, peak %.2f GiB, swap %.2f GiB each way" %
         (summ["makespan_ns"] / 1e6, summ["peak_bytes"] / GIB, summ["bytes_d2h"] / GIB))
 
+    # one more step with events around every op: achieved host-link rate during the swaps and
+    # the measured occupancy of the compute stream (Eq. 1)
+    ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER | K.STEP_PROFILE)
+    st_prof = ctx.karma_get_stats()
+    swap = {"O": [0.0, 0.0], "I": [0.0, 0.0]}
+    for kind, layer, t0_, t1_, ms in ctx.karma_get_op_times():
+        if kind in swap:
+            nbytes = (layers[layer - 1][4] if layer else 0) + (layers[layer][3] if acts[layer] == K.SWAP else 0)
+            swap[kind][0] += nbytes
+            swap[kind][1] += ms
+    link_achieved = {("d2h" if k == "O" else "h2d"): (v[0] / (v[1] * 1e-3) / 1e9 if v[1] > 0 else None) for k, v in swap.items()}
+    occupancy = st_prof["compute_busy_ms"] / st_prof["step_ms"] if st_prof["step_ms"] > 0 else None
+    log("swap link achieved: %s GB/s; compute busy %.1f of %.1f ms" % (link_achieved, st_prof["compute_busy_ms"], st_prof["step_ms"]))
+
     n_l, ms_l, fl_l = gem
     achieved = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
     out = {
@@ -152,6 +166,9 @@ def main():
         "arena_peak_gib": summ["peak_bytes"] / GIB,
         "swap_gib_each_way": summ["bytes_d2h"] / GIB,
         "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9},
+        "swap_link_achieved_gbps": link_achieved,
+        "compute_occupancy_measured": occupancy,
+        "compute_occupancy_predicted": summ["busy_ns"] / max(summ["busy_ns"] + summ["stall_ns"], 1),
         "host_opt_ms": st["host_opt_ms"],
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all launches of the timed steps)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,

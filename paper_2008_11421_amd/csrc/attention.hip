@@ -24,6 +24,9 @@ namespace karma {
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+// v_exp_f32: 2^x without the range fix-ups of exp2f (arguments here are <= 0 or -inf)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 union Frag {
   bf16x8 v;
   u32x4 u;
@@ -46,12 +49,15 @@ __device__ __forceinline__ bf16x8 frag_regs(const f32x16& a, int s, float mul) {
 }
 
 // ------------------------------------------------------------------------------- forward
-// grid (seq/128, heads, batch), 256 threads; wavefront w owns queries q0+32w .. q0+32w+31.
+// grid (seq/128, heads, batch), 256 threads; wavefront w owns queries q0+32w .. q0+32w+31
+// and walks the keys in tiles of 128 (four 32-key sub-tiles; sub-tiles entirely after the
+// wavefront's queries are skipped).
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                         float* __restrict__ lse, int S, int H) {
-  constexpr int PK = D + LDS_PAD, PV = 64 + LDS_PAD, TV = (D * 64 / 32 < 256) ? D * 64 / 32 : 256;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * PK];
+  constexpr int KT = 128;   // keys per tile
+  constexpr int PK = D + LDS_PAD, PV = KT + LDS_PAD;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[KT * PK];
   __shared__ __attribute__((aligned(16))) bf16_t Vt[D * PV];
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
@@ -76,23 +82,30 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
   for (int i = 0; i < D / 32; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY, l = 0.f;   // m: running maximum of the raw scores (before the 1/sqrt(d) scale)
 
-  TileMover<64, D, 256, true> mk;
-  TileMover<D, 64, TV, false> mv;
-  const int n_kt = (q0 + 128) / 64;
+  TileMover<KT, D, 256, true> mk;
+  TileMover<D, KT, 256, false> mv;
+  const int n_kt = (q0 + 128) / KT;
+  mk.load(Kg, ld, 0, 0, S, D, tid, true);
+  mv.load(Vg, ld, 0, 0, D, S, tid, true);
   for (int kt = 0; kt < n_kt; ++kt) {
-    const int key0 = kt * 64;
-    mk.load(Kg, ld, key0, 0, S, D, tid);
-    if (tid < TV) mv.load(Vg, ld, 0, key0, D, S, tid);
+    const int key0 = kt * KT;
     __syncthreads();   // previous tile fully consumed
     mk.store(Ks, tid);
-    if (tid < TV) mv.store(Vt, tid);
+    mv.store(Vt, tid);
     __syncthreads();
-    if (key0 <= qbase + 31) {
-      f32x16 s[2];
+    if (kt + 1 < n_kt) {   // next tile's loads stay in flight while this one is computed
+      mk.load(Kg, ld, key0 + KT, 0, S, D, tid, true);
+      mv.load(Vg, ld, 0, key0 + KT, D, S, tid, true);
+    }
+    // sub-tiles this wavefront needs: keys key0 + 32*mt <= last query
+    const int n_mt = min(4, (qbase + 31 - key0) / 32 + 1);
+    f32x16 s[4];
+    float tmax = -INFINITY;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 4; ++mt) {
+      if (mt < n_mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
 #pragma unroll
@@ -100,43 +113,40 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
           bf16x8 kf = *(const bf16x8*)(Ks + (mt * 32 + lrow) * PK + ks * 16 + g * 8);
           s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[mt], 0, 0, 0);
         }
-      }
-      // scale into the base-2 domain, mask keys after the query, tile maximum
-      float tmax = -INFINITY;
-      const bool diag = key0 + 63 > qbase;
+        if (key0 + mt * 32 + 31 > qbase) {   // sub-tile touches the diagonal: mask keys after the query
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[mt][r] * c;
-          if (diag) {
-            int key = key0 + mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-            if (key > query) v = -INFINITY;
+          for (int r = 0; r < 16; ++r) {
+            const int key = key0 + mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+            if (key > query) s[mt][r] = -INFINITY;
           }
-          s[mt][r] = v;
-          tmax = fmaxf(tmax, v);
         }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(m, tmax);
-      const float alpha = exp2f(m - m_new);
-      m = m_new;
-      float psum = 0.f;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = exp2f(s[mt][r] - m_new);
-          s[mt][r] = p;
-          psum += p;
-        }
-      l = l * alpha + psum;
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[mt][r]);
+      }
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m, tmax);
+    const float mc = m_new * c;
+    if (__any(m_new != m)) {   // rescale only when some query's maximum moved
+      const float alpha = fast_exp2(m * c - mc);
+      l *= alpha;
 #pragma unroll
       for (int i = 0; i < D / 32; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
-      // O^T += V^T P^T
+      m = m_new;
+    }
+    float psum = 0.f;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 4; ++mt) {
+      if (mt < n_mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = fast_exp2(fmaf(s[mt][r], c, -mc));
+          s[mt][r] = p;
+          psum += p;
+        }
+        // O^T += V^T P^T
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
           bf16x8 pf = frag_regs(s[mt], st, 1.f);
@@ -146,7 +156,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
             o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[i], 0, 0, 0);
           }
         }
+      }
     }
+    l += psum;
   }
   l += __shfl_xor(l, 32, 64);
   const float inv = 1.f / l;
@@ -160,7 +172,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
       v.y = pack2(o[i][rg * 4 + 2] * inv, o[i][rg * 4 + 3] * inv);
       *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
     }
-  if (g == 0) lse[((size_t)b * H + head) * S + query] = m + log2f(l);
+  if (g == 0) lse[((size_t)b * H + head) * S + query] = m * c + log2f(l);
 }
 
 // ------------------------------------------------------------------ backward: delta
@@ -190,15 +202,17 @@ __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __
 }
 
 // ------------------------------------------------------------------ backward: dQ
-// Same tiling as forward: wavefront owns 32 queries, loops over key tiles.
+// Same tiling as forward: wavefront owns 32 queries, walks the keys in tiles of 128.
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16_t* __restrict__ dqkv, int S, int H) {
-  constexpr int PK = D + LDS_PAD, PT = 64 + LDS_PAD, TT = (D * 64 / 32 < 256) ? D * 64 / 32 : 256;
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[64 * PK];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * PK];
-  __shared__ __attribute__((aligned(16))) bf16_t Kt[D * PT];
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout, const float* __restrict__ lse,
+    const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H) {
+  constexpr int KT = 128;
+  constexpr int PK = D + LDS_PAD, PT = KT + LDS_PAD;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
+  bf16_t* Ks = (bf16_t*)smem_attn;   // [KT][PK]
+  bf16_t* Vs = Ks + KT * PK;         // [KT][PK]
+  bf16_t* Kt = Vs + KT * PK;         // [D][PT]   K transposed
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
   const int q0 = blockIdx.x * 128, head = blockIdx.y, b = blockIdx.z;
@@ -226,23 +240,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
-  TileMover<64, D, 256, true> mk, mv;
-  TileMover<D, 64, TT, false> mkt;
-  const int n_kt = (q0 + 128) / 64;
+  TileMover<KT, D, 256, true> mk, mv;
+  TileMover<D, KT, 256, false> mkt;
+  const int n_kt = (q0 + 128) / KT;
+  mk.load(Kg, ld, 0, 0, S, D, tid, true);
+  mv.load(Vg, ld, 0, 0, S, D, tid, true);
+  mkt.load(Kg, ld, 0, 0, D, S, tid, true);
   for (int kt = 0; kt < n_kt; ++kt) {
-    const int key0 = kt * 64;
-    mk.load(Kg, ld, key0, 0, S, D, tid);
-    mv.load(Vg, ld, key0, 0, S, D, tid);
-    if (tid < TT) mkt.load(Kg, ld, 0, key0, D, S, tid);
+    const int key0 = kt * KT;
     __syncthreads();
     mk.store(Ks, tid);
     mv.store(Vs, tid);
-    if (tid < TT) mkt.store(Kt, tid);
+    mkt.store(Kt, tid);
     __syncthreads();
-    if (key0 <= qbase + 31) {
-      const bool diag = key0 + 63 > qbase;
+    if (kt + 1 < n_kt) {
+      mk.load(Kg, ld, key0 + KT, 0, S, D, tid, true);
+      mv.load(Vg, ld, key0 + KT, 0, S, D, tid, true);
+      mkt.load(Kg, ld, 0, key0 + KT, D, S, tid, true);
+    }
+    const int n_mt = min(4, (qbase + 31 - key0) / 32 + 1);
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 4; ++mt) {
+      if (mt < n_mt) {
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
@@ -253,11 +272,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[ks], dp, 0, 0, 0);
         }
+        const bool diag = key0 + mt * 32 + 31 > qbase;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = exp2f(s[r] * c - my_lse);
+          float p = fast_exp2(fmaf(s[r], c, -my_lse));
           if (diag) {
-            int key = key0 + mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+            const int key = key0 + mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
             if (key > query) p = 0.f;
           }
           s[r] = p * (dp[r] - my_delta);   // dS^T (before the 1/sqrt(d) factor)
@@ -288,18 +308,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
 
 // ------------------------------------------------------------------ backward: dK, dV
 // grid (seq/128, heads, batch); wavefront w owns keys k0+32w .. +31 and loops over the
-// query tiles at or after them.  Scores are computed with queries on the rows so that the
-// probabilities sit in registers as the (key x query) operand of dV = P^T dO and dK = dS^T Q.
+// query tiles (64 queries, two 32-query sub-tiles) at or after them.  Scores are computed
+// with queries on the rows so that the probabilities sit in registers as the (key x query)
+// operand of dV = P^T dO and dK = dS^T Q.
 template <int D>
-__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                            bf16_t* __restrict__ dqkv, int S, int H) {
-  constexpr int PK = D + LDS_PAD, PT = 64 + LDS_PAD, TT = (D * 64 / 32 < 256) ? D * 64 / 32 : 256;
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[64 * PK];
-  __shared__ __attribute__((aligned(16))) bf16_t Os[64 * PK];
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[D * PT];
-  __shared__ __attribute__((aligned(16))) bf16_t Ot[D * PT];
-  __shared__ __attribute__((aligned(16))) float lse_s[64], delta_s[64];
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
+    const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout, const float* __restrict__ lse,
+    const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H) {
+  constexpr int QT = 64;
+  constexpr int TT = (D * QT / 32 < 256) ? D * QT / 32 : 256;   // threads of the transposing movers
+  constexpr int PK = D + LDS_PAD, PT = QT + LDS_PAD;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
+  bf16_t* Qs = (bf16_t*)smem_attn;   // [QT][PK]
+  bf16_t* Os = Qs + QT * PK;         // [QT][PK]   dO
+  bf16_t* Qt = Os + QT * PK;         // [D][PT]    Q transposed
+  bf16_t* Ot = Qt + D * PT;          // [D][PT]    dO transposed
+  float* lse_s = (float*)(Ot + D * PT);
+  float* delta_s = lse_s + QT;
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
   const int k0 = blockIdx.x * 128, head = blockIdx.y, b = blockIdx.z;
@@ -324,16 +349,23 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(co
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-  TileMover<64, D, 256, true> mq, mo;
-  TileMover<D, 64, TT, false> mqt, mot;
-  for (int qt = k0 / 64; qt < S / 64; ++qt) {
-    const int qq0 = qt * 64;
-    mq.load(base, ld, qq0, 0, S, D, tid);
-    mo.load(dOg, (size_t)h, qq0, 0, S, D, tid);
+  TileMover<QT, D, 256, true> mq, mo;
+  TileMover<D, QT, TT, false> mqt, mot;
+  auto fetch = [&](int qq) {
+    mq.load(base, ld, qq, 0, S, D, tid, true);
+    mo.load(dOg, (size_t)h, qq, 0, S, D, tid, true);
     if (tid < TT) {
-      mqt.load(base, ld, 0, qq0, D, S, tid);
-      mot.load(dOg, (size_t)h, 0, qq0, D, S, tid);
+      mqt.load(base, ld, 0, qq, D, S, tid, true);
+      mot.load(dOg, (size_t)h, 0, qq, D, S, tid, true);
     }
+  };
+  fetch(k0);
+  float lse_r = 0.f, delta_r = 0.f;
+  if (tid < QT) {
+    lse_r = lse[((size_t)b * H + head) * S + k0 + tid];
+    delta_r = delta[((size_t)b * H + head) * S + k0 + tid];
+  }
+  for (int qq0 = k0; qq0 < S; qq0 += QT) {
     __syncthreads();
     mq.store(Qs, tid);
     mo.store(Os, tid);
@@ -341,15 +373,23 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(co
       mqt.store(Qt, tid);
       mot.store(Ot, tid);
     }
-    if (tid < 64) {
-      lse_s[tid] = lse[((size_t)b * H + head) * S + qq0 + tid];
-      delta_s[tid] = delta[((size_t)b * H + head) * S + qq0 + tid];
+    if (tid < QT) {
+      lse_s[tid] = lse_r;
+      delta_s[tid] = delta_r;
     }
     __syncthreads();
-    if (qq0 + 63 >= kbase) {
-      const bool diag = qq0 < kbase + 31;
+    if (qq0 + QT < S) {
+      fetch(qq0 + QT);
+      if (tid < QT) {
+        lse_r = lse[((size_t)b * H + head) * S + qq0 + QT + tid];
+        delta_r = delta[((size_t)b * H + head) * S + qq0 + QT + tid];
+      }
+    }
+    // sub-tiles of 32 queries; those entirely before this wavefront's keys contribute nothing
+    const int first_mt = max(0, (kbase - qq0) / 32);
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {   // 32 queries each
+    for (int mt = 0; mt < QT / 32; ++mt) {
+      if (mt >= first_mt) {
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
@@ -360,6 +400,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(co
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[ks], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ofr, vf[ks], dp, 0, 0, 0);
         }
+        const bool diag = qq0 + mt * 32 < kbase + 31;
         // p in s, dS in dp (in place); the per-query statistics come four at a time
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
@@ -370,7 +411,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(co
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = rg * 4 + e;
-            float p = exp2f(s[r] * c - lv[e]);
+            float p = fast_exp2(fmaf(s[r], c, -lv[e]));
             if (diag && key > qq0 + qb + e) p = 0.f;
             s[r] = p;
             dp[r] = p * (dp[r] - dl[e]);
@@ -403,6 +444,13 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(co
     }
 }
 
+template <int D>
+constexpr size_t attn_dq_lds() { return (size_t)(2 * 128 * (D + LDS_PAD) + D * (128 + LDS_PAD)) * sizeof(bf16_t); }
+template <int D>
+constexpr size_t attn_dkv_lds() {
+  return (size_t)(2 * 64 * (D + LDS_PAD) + 2 * D * (64 + LDS_PAD)) * sizeof(bf16_t) + 2 * 64 * sizeof(float);
+}
+
 // ------------------------------------------------------------------------------ launchers
 static inline int ok() { return hipGetLastError() == hipSuccess ? KARMA_OK : KARMA_E_HIP; }
 
@@ -414,6 +462,18 @@ int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq
   return ok();
 }
 
+template <int D>
+static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* dctx, const float* lse,
+                       const float* delta, bf16_t* dqkv, int seq, int heads) {
+  constexpr size_t l1 = attn_dq_lds<D>(), l2 = attn_dkv_lds<D>();
+  if (l1 > 64 * 1024)
+    (void)hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l1);
+  if (l2 > 64 * 1024)
+    (void)hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<D>, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+}
+
 int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,
                   bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s) {
   if (seq % 128 || (d != 64 && d != 128) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
@@ -422,12 +482,10 @@ int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, cons
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (d == 64) {
     hipLaunchKernelGGL(attn_delta_kernel<64>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), 0, s, qkv, dctx, lse, delta, dqkv, seq, heads);
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, grid, dim3(256), 0, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    launch_bwd<64>(grid, s, qkv, dctx, lse, delta, dqkv, seq, heads);
   } else {
     hipLaunchKernelGGL(attn_delta_kernel<128>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(256), 0, s, qkv, dctx, lse, delta, dqkv, seq, heads);
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, grid, dim3(256), 0, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    launch_bwd<128>(grid, s, qkv, dctx, lse, delta, dqkv, seq, heads);
   }
   return ok();
 }
