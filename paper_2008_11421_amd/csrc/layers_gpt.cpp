@@ -65,7 +65,7 @@ struct BlockWs {
 constexpr int HEAD_CHUNK = 4096;   // tokens per LM-head chunk: the full logits never exist
 
 struct LossWs {
-  uint64_t xf, stats, logits, dxf, rowloss, part, total;
+  uint64_t xf, stats, logits, dxf, rowloss, part, splitk, splitk_bytes, total;
   int chunk;
   explicit LossWs(const Dims& d) {
     chunk = std::min(d.T, HEAD_CHUNK);
@@ -77,6 +77,8 @@ struct LossWs {
     dxf = take((uint64_t)d.T * d.h * 2);
     rowloss = take((uint64_t)d.T * 4);
     part = take(std::max<uint64_t>(layernorm_bwd_ws_bytes(d.T, d.h), 1024 * 4));
+    splitk_bytes = (uint64_t)8 * chunk * d.h * 4;   // the dx GEMM of a chunk has few tiles and a long reduction
+    splitk = take(splitk_bytes);
     total = o;
   }
 };
@@ -322,7 +324,8 @@ int gpt_loss(Ctx& c, const LayerIO& io, hipStream_t s) {
     const bf16_t* xc = xf + (size_t)t0 * d.h;
     TRY(gemm(xc, wte, logits, nullptr, nullptr, n, d.V, d.h, true, true, false, false, s));          // logits = xf wte^T
     TRY(softmax_ce(logits, labels + t0, rowloss + t0, n, d.V, 1.0f / (float)d.T, s));                 // -> dlogits
-    TRY(gemm(logits, wte, dxf + (size_t)t0 * d.h, nullptr, nullptr, n, d.h, d.V, true, false, false, false, s));
+    TRY(gemm(logits, wte, dxf + (size_t)t0 * d.h, nullptr, nullptr, n, d.h, d.V, true, false, false, false, s,
+             Wk + wl.splitk, wl.splitk_bytes));
     TRY(gemm(logits, xc, dwte, nullptr, nullptr, d.V, d.h, n, false, false, true, true, s));          // dwte += dlogits^T xf
   }
   TRY(sum_f32(rowloss, (float*)c.fixed_ptr(c.loss_off), part, (size_t)d.T, 1.0f / (float)d.T, s));

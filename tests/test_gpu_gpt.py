@@ -107,7 +107,7 @@ def test_gpt_step_matches_oracle_and_plans_are_bit_identical(g):
 
     # a budget that holds about half of the blocks' saved sets: plan equals the oracle's plan
     per_block = layers[1][3] + layers[1][4]
-    budget = fixed + int(1.6 * per_block) + layers[1][5] + loss_c[1]
+    budget = fixed + int(1.6 * per_block) + max(layers[1][5], loss_c[1]) + 2 * layers[1][4]
     acts, summ = ctx.karma_plan(budget)
     ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(*loss_c))
     assert acts == ao and summ["makespan_ns"] == so["makespan_ns"] and summ["peak_bytes"] == so["peak_bytes"]
