@@ -22,9 +22,14 @@ struct Param {
   std::vector<float> master, m, v; // host fp32 master copy and optimiser state
   void* stage_g = nullptr;         // pinned: gradient as it arrives from the device
   void* stage_w = nullptr;         // pinned: new weight in device format
+  std::vector<hipEvent_t> chunk_ev; // gradient chunk k has landed on the host
   uint64_t w_bytes() const { return n * (dev_bf16 ? 2 : 4); }
   uint64_t g_bytes() const { return n * (grad_bf16 ? 2 : 4); }
 };
+
+// Large tensors cross the link and the optimiser in chunks so that gradient D2H, host update
+// and weight H2D of one tensor overlap (this matters for the record that finishes last).
+constexpr uint64_t PARAM_CHUNK = 4ull << 20;   // elements
 
 struct Record {
   int kind = 0;
@@ -76,7 +81,6 @@ struct Ctx {
   std::vector<float> op_ms;               // per-op durations of the last profiled step
   char* swap_pool = nullptr;              // pinned host memory for swapped tensors
   uint64_t swap_pool_bytes = 0;
-  std::vector<hipEvent_t> grad_ev;        // per record: gradients have landed on the host
 
   // per-launch timing of the GEMM kernel (KARMA_STEP_KERNEL_TIMES)
   bool ktime = false;
@@ -119,7 +123,8 @@ struct LayerIO {
 
 // Model-specific pieces (layers_mlp.cpp, layers_gpt.cpp)
 int model_build_records(Ctx& c);                         // fills rec[], sizes, in/lab/misc bytes
-int model_prepare_step(Ctx& c, const void* in, const void* lab);   // host-side per-step preparation into the staging buffers
+int model_prepare_step(Ctx& c, const void* in, const void* lab);   // inputs and labels into the staging buffers
+int model_prepare_late(Ctx& c);   // host work only backward needs (runs while the GPU is busy with forward); fills stage_misc
 int layer_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int layer_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int loss_op(Ctx& c, const LayerIO& io, hipStream_t s);   // x -> loss (fixed region) and dx; accumulates its own parameter gradients

@@ -235,36 +235,46 @@ int issue(Ctx* c, const ProgOp& p) {
   return KARMA_E_INVAL;
 }
 
-// gradients of one record: device -> pinned host, after the op that completed them
+// gradients of one record: device -> pinned host in chunks, after the op that completed them
 int send_grads(Ctx* c, uint32_t r, hipEvent_t after) {
   hipStream_t s = c->st[2];
   KARMA_HIP(c, hipStreamWaitEvent(s, after, 0));
-  for (Param& p : c->rec[r].p)
-    KARMA_HIP(c, hipMemcpyAsync(p.stage_g, c->arena + p.g_off, p.g_bytes(), hipMemcpyDeviceToHost, s));
-  KARMA_HIP(c, hipEventRecord(c->grad_ev[r], s));
+  for (Param& p : c->rec[r].p) {
+    const uint64_t gs = p.grad_bf16 ? 2 : 4;
+    for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
+      const uint64_t lo = k * PARAM_CHUNK, n = std::min(PARAM_CHUNK, p.n - lo);
+      KARMA_HIP(c, hipMemcpyAsync((char*)p.stage_g + lo * gs, c->arena + p.g_off + lo * gs, n * gs, hipMemcpyDeviceToHost, s));
+      KARMA_HIP(c, hipEventRecord(p.chunk_ev[k], s));
+    }
+  }
   return KARMA_OK;
 }
 
-// host update of one record's master weights, then the new device weights go back
+// host update of one record's master weights, chunk by chunk as the gradients land; each
+// chunk's new device weights go back at once
 int update_record(Ctx* c, uint32_t r) {
-  KARMA_HIP(c, hipEventSynchronize(c->grad_ev[r]));
-  double t0 = now_ms();
+  const karma_config& g = c->cfg;
+  const uint64_t step = c->step_no;
   for (Param& p : c->rec[r].p) {
-    const karma_config& g = c->cfg;
-    const uint64_t step = c->step_no;
-    c->pool->parallel_for(p.n, [&](size_t lo, size_t hi) {
-      const char* gp = (const char*)p.stage_g + lo * (p.grad_bf16 ? 2 : 4);
-      char* wp = (char*)p.stage_w + lo * (p.dev_bf16 ? 2 : 4);
-      if (g.optimizer == KARMA_OPT_ADAM)
-        adam_update(p.master.data() + lo, p.m.data() + lo, p.v.data() + lo, gp, p.grad_bf16, hi - lo, g.lr, g.beta1,
-                    g.beta2, g.eps, step, wp, p.dev_bf16);
-      else
-        sgd_update(p.master.data() + lo, gp, p.grad_bf16, hi - lo, g.lr, wp, p.dev_bf16);
-    });
+    const uint64_t gs = p.grad_bf16 ? 2 : 4, ws = p.dev_bf16 ? 2 : 4;
+    for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
+      const uint64_t base = k * PARAM_CHUNK, n = std::min(PARAM_CHUNK, p.n - base);
+      KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
+      double t0 = now_ms();
+      c->pool->parallel_for(n, [&](size_t lo, size_t hi) {
+        const char* gp = (const char*)p.stage_g + (base + lo) * gs;
+        char* wp = (char*)p.stage_w + (base + lo) * ws;
+        if (g.optimizer == KARMA_OPT_ADAM)
+          adam_update(p.master.data() + base + lo, p.m.data() + base + lo, p.v.data() + base + lo, gp, p.grad_bf16,
+                      hi - lo, g.lr, g.beta1, g.beta2, g.eps, step, wp, p.dev_bf16);
+        else
+          sgd_update(p.master.data() + base + lo, gp, p.grad_bf16, hi - lo, g.lr, wp, p.dev_bf16);
+      });
+      c->stats.host_opt_ms += now_ms() - t0;
+      KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off + base * ws, (char*)p.stage_w + base * ws, n * ws,
+                                  hipMemcpyHostToDevice, c->st[1]));
+    }
   }
-  c->stats.host_opt_ms += now_ms() - t0;
-  for (Param& p : c->rec[r].p)
-    KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off, p.stage_w, p.w_bytes(), hipMemcpyHostToDevice, c->st[1]));
   return KARMA_OK;
 }
 
@@ -281,14 +291,18 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
   hipStream_t sc = c->st[0];
   KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->in_off), c->stage_in, c->in_bytes, hipMemcpyHostToDevice, sc));
   KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->lab_off), c->stage_lab, c->lab_bytes, hipMemcpyHostToDevice, sc));
-  if (c->misc_bytes)
-    KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->misc_off), c->stage_misc, c->misc_bytes, hipMemcpyHostToDevice, sc));
   if (apply) ++c->step_no;
   std::vector<uint32_t> done_order;
   for (size_t k = 0; k < c->prog.size(); ++k) {
     const ProgOp& p = c->prog[k];
     hipStream_t s = c->st[p.stream];
     for (uint32_t d : p.waits) KARMA_HIP(c, hipStreamWaitEvent(s, c->ev[d], 0));
+    if (p.kind == 'B' && p.layer == 0 && c->misc_bytes) {
+      // host-side preparation that only this op needs; the GPU has been busy all along
+      st = model_prepare_late(*c);
+      if (st) return st;
+      KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->misc_off), c->stage_misc, c->misc_bytes, hipMemcpyHostToDevice, s));
+    }
     if (profile) KARMA_HIP(c, hipEventRecord(c->ev_begin[k], s));
     st = issue(c, p);
     if (st) return st;
@@ -408,11 +422,14 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   pin(&c->stage_lab, c->lab_bytes);
   pin((void**)&c->stage_loss, 256);
   pin(&c->stage_misc, c->misc_bytes);
-  c->grad_ev.assign(c->rec.size(), nullptr);
-  for (auto& e : c->grad_ev)
-    if (ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
-      std::fprintf(stderr, "karma_create: hipEventCreate failed\n");
-      ok = false;
+  for (Record& r : c->rec)
+    for (Param& p : r.p) {
+      p.chunk_ev.assign((size_t)((p.n + PARAM_CHUNK - 1) / PARAM_CHUNK), nullptr);
+      for (auto& e : p.chunk_ev)
+        if (ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+          std::fprintf(stderr, "karma_create: hipEventCreate failed\n");
+          ok = false;
+        }
     }
   if (!ok) { karma_destroy(c); return KARMA_E_HOSTMEM; }
   c->pool.reset(new HostPool(cfg->host_threads ? cfg->host_threads : 1));
@@ -428,12 +445,12 @@ extern "C" void karma_destroy(karma_ctx* c) {
     for (Param& p : r.p) {
       if (p.stage_g) (void)hipHostFree(p.stage_g);
       if (p.stage_w) (void)hipHostFree(p.stage_w);
+      for (auto e : p.chunk_ev) if (e) (void)hipEventDestroy(e);
     }
   if (c->stage_in) (void)hipHostFree(c->stage_in);
   if (c->stage_lab) (void)hipHostFree(c->stage_lab);
   if (c->stage_loss) (void)hipHostFree(c->stage_loss);
   if (c->stage_misc) (void)hipHostFree(c->stage_misc);
-  for (auto e : c->grad_ev) if (e) (void)hipEventDestroy(e);
   for (auto e : c->kev) (void)hipEventDestroy(e);
   delete c;
 }

@@ -275,8 +275,8 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   // split the reduction when the tiles alone cannot fill the chip (weight gradients:
   // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
   int splits = 1;
-  if (g.ws && g.ldc == g.N && tiles < 2 * cus) {
-    splits = std::min(16, (2 * cus + tiles - 1) / tiles);
+  if (g.ws && g.ldc == g.N && tiles < cus) {
+    splits = std::min(16, (cus + tiles - 1) / tiles);   // about one work item per compute unit
     splits = std::min(splits, std::max(1, g.K / (4 * BK)));
     while (splits > 1 && (size_t)splits * g.M * g.N * sizeof(float) > g.ws_bytes) --splits;
   }

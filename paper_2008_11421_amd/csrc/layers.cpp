@@ -14,6 +14,7 @@ int model_build_records(Ctx& c) {
 int model_prepare_step(Ctx& c, const void* in, const void* lab) {
   return c.desc.kind == KARMA_MODEL_MLP ? mlp_prepare_step(c, in, lab) : gpt_prepare_step(c, in, lab);
 }
+int model_prepare_late(Ctx& c) { return c.desc.kind == KARMA_MODEL_MLP ? mlp_prepare_late(c) : gpt_prepare_late(c); }
 int layer_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   return c.desc.kind == KARMA_MODEL_MLP ? mlp_forward(c, i, io, s) : gpt_forward(c, i, io, s);
 }

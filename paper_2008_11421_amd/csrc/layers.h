@@ -4,12 +4,14 @@
 namespace karma {
 int mlp_build_records(Ctx& c);
 int mlp_prepare_step(Ctx& c, const void* in, const void* lab);
+int mlp_prepare_late(Ctx& c);
 int mlp_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int mlp_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int mlp_loss(Ctx& c, const LayerIO& io, hipStream_t s);
 
 int gpt_build_records(Ctx& c);
 int gpt_prepare_step(Ctx& c, const void* in, const void* lab);
+int gpt_prepare_late(Ctx& c);
 int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int gpt_loss(Ctx& c, const LayerIO& io, hipStream_t s);

@@ -179,8 +179,7 @@ int gpt_build_records(Ctx& c) {
   return KARMA_OK;
 }
 
-// Host-side preparation: ids/labels into the staging buffers; stable sort of the token
-// positions by id for the atomic-free embedding gradient.
+// Host-side preparation: ids/labels into the staging buffers.
 int gpt_prepare_step(Ctx& c, const void* in, const void* lab) {
   Dims d(c.desc);
   const int32_t* ids = (const int32_t*)in;
@@ -192,6 +191,14 @@ int gpt_prepare_step(Ctx& c, const void* in, const void* lab) {
     }
   std::memcpy(c.stage_in, in, c.in_bytes);
   std::memcpy(c.stage_lab, lab, c.lab_bytes);
+  return KARMA_OK;
+}
+
+// Stable sort of the token positions by id for the atomic-free embedding gradient: only the
+// very last backward op needs it, so it runs on the host while the GPU computes.
+int gpt_prepare_late(Ctx& c) {
+  Dims d(c.desc);
+  const int32_t* ids = (const int32_t*)c.stage_in;
   int32_t* order = (int32_t*)c.stage_misc;
   int32_t* seg_start = order + d.T;
   int32_t* seg_id = seg_start + d.T + 1;

@@ -178,8 +178,17 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restr
   const int cl = threadIdx.x & 31, slice = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cl;
   float s = 0.f;
-  if (c < cols)
-    for (int p = slice; p < parts; p += 8) s += partial[(size_t)p * stride + c];
+  if (c < cols) {
+    int p = slice;
+    for (; p + 56 < parts; p += 64) {   // eight loads in flight, added in ascending order
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = partial[(size_t)(p + 8 * k) * stride + c];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += v[k];
+    }
+    for (; p < parts; p += 8) s += partial[(size_t)p * stride + c];
+  }
   red[slice][cl] = s;
   __syncthreads();
   if (slice == 0 && c < cols) {
