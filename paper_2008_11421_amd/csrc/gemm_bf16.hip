@@ -151,13 +151,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
     __syncthreads();
     read_frags(0, 0, 0);
     const int KT = (ke - kb + BK - 1) / BK;
+    // the second k-tile starts its trip right away: a tile's loads are issued one whole
+    // tile time before they are parked in LDS (half way through the tile before it is used)
+    if (KT > 1) {
+      ma.load(A, lda, m0, kb + BK, M, ke, tid, full);
+      mb.load(B, ldb, n0, kb + BK, N, ke, tid, full);
+    }
     for (int kt = 0; kt < KT; ++kt) {
       const int cur = kt & 1;
       const bool more = kt + 1 < KT;
-      if (more) {
-        ma.load(A, lda, m0, kb + (kt + 1) * BK, M, ke, tid, full);
-        mb.load(B, ldb, n0, kb + (kt + 1) * BK, N, ke, tid, full);
-      }
 #pragma unroll
       for (int kk = 0; kk < KSTEPS; ++kk) {
         if (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, cur, kk + 1);
@@ -171,6 +173,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
         if (kk == KSTEPS / 2 - 1 && more) {
           ma.store(As + (cur ^ 1) * BM * PITCH, tid);
           mb.store(Bs + (cur ^ 1) * BN * PITCH, tid);
+          if (kt + 2 < KT) {
+            ma.load(A, lda, m0, kb + (kt + 2) * BK, M, ke, tid, full);
+            mb.load(B, ldb, n0, kb + (kt + 2) * BK, N, ke, tid, full);
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
