@@ -22,6 +22,11 @@ __device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest even, Na
 // two floats -> packed bf16 pair with the hardware converter (v_cvt_pk_bf16_f32, RNE)
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+// Workgroup barrier that orders LDS traffic only: waits for this wavefront's LDS operations,
+// not for its global loads still in flight (a plain __syncthreads() waits for those too,
+// which would put the latency of prefetched tiles back on the critical path).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ unsigned pack2(float lo, float hi) {
   f32x2_t f = {lo, hi};
   bf16x2_t b = __builtin_convertvector(f, bf16x2_t);

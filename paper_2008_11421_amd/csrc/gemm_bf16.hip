@@ -53,7 +53,7 @@ struct GemmEpilogue {
         u32x4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = pack2(v[2 * e], v[2 * e + 1]);
-        __builtin_nontemporal_store(o, (u32x4*)((bf16_t*)C + at));
+        *(u32x4*)((bf16_t*)C + at) = o;
       }
     } else {
       for (int e = 0; e < cols; ++e) {
@@ -71,13 +71,13 @@ struct GemmEpilogue {
   }
 };
 
-// Persistent kernel: each workgroup walks work items (output tile x k-split) with stride
-// gridDim.x.  Per item: the first k-tile is already in registers (loaded while the previous
+// Persistent kernel: each workgroup walks the work items (output tile x k-split) of its
+// XCD's range.  Per item: the first k-tile is already in registers (loaded while the previous
 // item's results were being written out), the main loop is software-pipelined by hand
 // (fragments of step kk+1 are read from LDS while the MFMAs of step kk run; the next
 // k-tile's global loads are issued at the top and parked in LDS half way through), and the
-// results leave through an LDS strip so that stores are row-contiguous.  The stores are
-// not waited for: they drain while the next item computes.
+// results leave through a per-wavefront LDS strip so that stores are row-contiguous.  The
+// stores are not waited for: they drain while the next item computes.
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                    const bf16_t* __restrict__ B, int M, int N, int K,
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int KSTEPS = BK / 16;
-  static_assert(KSTEPS % 2 == 0, "fragment double buffer alternates per step");
+  static_assert(KSTEPS % 2 == 0 && KSTEPS >= 4, "fragment double buffer alternates per step; tiles are parked before the barrier of step KSTEPS-2");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* As = (bf16_t*)smem;          // [2][BM][PITCH]
   bf16_t* Bs = As + 2 * BM * PITCH;    // [2][BN][PITCH]
@@ -100,13 +100,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
   const int total_tiles = tiles_m * tiles_n;
   const int total_items = total_tiles * splits;
 
-  // item -> (tile, split).  Consecutive workgroup ids go round-robin over the 8 XCDs, so
-  // each XCD gets a contiguous range of tiles, walked in bands of 8 tile rows: a band's B
-  // panel stays in that XCD's L2.
-  auto decode = [&](int item, int& m0, int& n0, int& kb, int& ke, int& split) {
+  // Work items are numbered split-major (item = split * tiles + tile) and cut into 8 equal
+  // contiguous ranges, one per XCD: workgroup ids go round-robin over the XCDs, so workgroup
+  // b serves range b % 8, starting at position b / 8 and advancing by gridDim.x / 8.  What
+  // runs together on one XCD is then a compact patch of tiles inside one k-split (tiles are
+  // walked in bands of 8 tile rows), so its L2 fetches every operand panel about once.
+  const int per_xcd = (total_items + 7) / 8;
+  const int xcd_first = (int)(blockIdx.x % 8) * per_xcd;
+  const int xcd_step = (int)gridDim.x / 8;
+  auto decode = [&](int pos, int& m0, int& n0, int& kb, int& ke, int& split) {
+    const int item = xcd_first + pos;
     split = item / total_tiles;
-    int id = item % total_tiles;
-    if (total_tiles % 8 == 0) id = (id % 8) * (total_tiles / 8) + id / 8;
+    const int id = item % total_tiles;
     constexpr int BAND = 8;
     const int band_sz = BAND * tiles_n;
     const int first_m = (id / band_sz) * BAND;
@@ -116,6 +121,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
     kb = split * k_per_split;
     ke = min(K, kb + k_per_split);
   };
+  auto valid = [&](int pos) { return pos < per_xcd && xcd_first + pos < total_items; };
 
   TileMover<BM, BK, T, A_KC> ma;
   TileMover<BN, BK, T, B_KC> mb;
@@ -129,10 +135,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
     for (int j = 0; j < TN; ++j) bfr[buf][j] = *(const bf16x8*)(bs + j * 32 * PITCH);
   };
 
-  int item = blockIdx.x;
-  if (item >= total_items) return;
+  int pos = blockIdx.x / 8;
+  if (!valid(pos)) return;
   int m0, n0, kb, ke, split;
-  decode(item, m0, n0, kb, ke, split);
+  decode(pos, m0, n0, kb, ke, split);
   bool full = m0 + BM <= M && n0 + BN <= N && (ke - kb) % BK == 0;
   ma.load(A, lda, m0, kb, M, ke, tid, full);
   mb.load(B, ldb, n0, kb, N, ke, tid, full);
@@ -145,10 +151,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    __syncthreads();   // the previous item's strip reads are done
+    lds_barrier();   // every wavefront is done with the previous item's tiles
     ma.store(As, tid);
     mb.store(Bs, tid);
-    __syncthreads();
+    lds_barrier();
     read_frags(0, 0, 0);
     const int KT = (ke - kb + BK - 1) / BK;
     // the second k-tile starts its trip right away: a tile's loads are issued one whole
@@ -162,60 +168,78 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
       const bool more = kt + 1 < KT;
 #pragma unroll
       for (int kk = 0; kk < KSTEPS; ++kk) {
+        // fragments of the next step; the last step already reads the next tile (the barrier
+        // after the step before it has made that tile visible and retired this one)
         if (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, cur, kk + 1);
+        else if (more) read_frags(0, cur ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (kk == KSTEPS / 2 - 1 && more) {
+        // The next tile is parked in LDS half way through the current one and its registers
+        // are refilled at once with the tile after next.  Transposed tiles, whose LDS writes
+        // are slower, go in two halves (A after step 0, B after step 1) so that the eight
+        // wavefronts' writes do not all land in the same step.
+        constexpr int A_AT = 0;
+        constexpr int B_AT = A_KC ? 0 : 1;
+        if (kk == A_AT && more) {
           ma.store(As + (cur ^ 1) * BM * PITCH, tid);
+          if (A_AT != B_AT && kt + 2 < KT) ma.load(A, lda, m0, kb + (kt + 2) * BK, M, ke, tid, full);
+        }
+        if (kk == B_AT && more) {
           mb.store(Bs + (cur ^ 1) * BN * PITCH, tid);
           if (kt + 2 < KT) {
-            ma.load(A, lda, m0, kb + (kt + 2) * BK, M, ke, tid, full);
+            if (A_AT == B_AT) ma.load(A, lda, m0, kb + (kt + 2) * BK, M, ke, tid, full);
             mb.load(B, ldb, n0, kb + (kt + 2) * BK, N, ke, tid, full);
           }
-          __builtin_amdgcn_sched_barrier(0);
         }
+        if ((kk == A_AT || kk == B_AT) && more) __builtin_amdgcn_sched_barrier(0);
+        if (kk == KSTEPS - 2) lds_barrier();
       }
-      __syncthreads();
-      if (more) read_frags(0, cur ^ 1, 0);
     }
+    lds_barrier();   // the last tile's reads are done: LDS is free for the epilogue
 
     // where the results of this item go
     const int out_m0 = m0, out_n0 = n0, out_split = split;
     // start fetching the next item's first k-tile before writing this one out
-    item += gridDim.x;
-    const bool have_next = item < total_items;
+    pos += xcd_step;
+    const bool have_next = valid(pos);
     if (have_next) {
-      decode(item, m0, n0, kb, ke, split);
+      decode(pos, m0, n0, kb, ke, split);
       full = m0 + BM <= M && n0 + BN <= N && (ke - kb) % BK == 0;
       ma.load(A, lda, m0, kb, M, ke, tid, full);
       mb.load(B, ldb, n0, kb, N, ke, tid, full);
     }
 
-    // Epilogue through LDS (the operand tiles are dead now): each wavefront parks one 32-row
-    // strip of its tile as fp32 [32][WTN], then reads it back row-wise so that a run of lanes
-    // stores one contiguous piece of a row.  Accumulator layout of the 32x32 MFMA: register r
-    // of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32.
+    // Epilogue through LDS (the operand tiles are dead now: the k-loop ended on a barrier).
+    // The MFMAs ran with the operands exchanged, so each accumulator holds the transposed
+    // tile: register r of lane l is column (r/4)*8 + (l/32)*4 + r%4 of row l%32, i.e. four
+    // consecutive columns per register quad.  Each wavefront parks one 32-row strip of its
+    // tile in its own fp32 [32][WTN] patch of LDS with 16-byte writes, then reads it back so
+    // that a run of lanes stores one contiguous piece of a row (stores that scatter 16-byte
+    // pieces over 32 rows are several times slower).  The patch is private to the wavefront,
+    // whose LDS operations execute in order: no barrier in here.
     constexpr int SP = WTN + 4;   // fp32 pitch of the strip
     static_assert((size_t)WGM * WGN * 32 * SP * 4 <= (size_t)2 * (BM + BN) * PITCH * 2, "strip does not fit the tile LDS");
     float* strip = (float*)smem + wave * 32 * SP;
     constexpr int QPR = WTN / 8;              // octets per strip row
     constexpr int RPI = 64 / QPR;             // rows covered per pass of the wavefront
-    static_assert(64 % QPR == 0 && 32 % RPI == 0, "strip read-out does not tile");
+    static_assert(QPR >= 4 && 64 % QPR == 0 && RPI % 2 == 0 && 32 % RPI == 0, "strip read-out does not tile");
+    // lane -> (octet q, row rr) such that eight consecutive lanes read two rows' worth of
+    // alternate 16-byte units (conflict-free with the odd pitch in 16-byte units)
+    const int q = (lane & 3) | (((lane >> 3) % (QPR / 4)) << 2);
+    const int rr = ((lane >> 2) & 1) | ((lane / (2 * QPR)) << 1);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      if (i) __syncthreads();
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          strip[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * SP + j * 32 + lrow] = acc[i][j][r];
-      __syncthreads();
-      const int q = lane % QPR, rr = lane / QPR;
+        for (int g = 0; g < 4; ++g)
+          *(float4*)(strip + lrow * SP + j * 32 + g * 8 + (lane >> 5) * 4) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
       const int n = out_n0 + wn * WTN + q * 8;
 #pragma unroll
       for (int pass = 0; pass < 32 / RPI; ++pass) {
@@ -282,16 +306,24 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
   int splits = 1;
   if (g.ws && g.ldc == g.N && tiles < cus) {
-    splits = std::min(16, (cus + tiles - 1) / tiles);   // about one work item per compute unit
-    splits = std::min(splits, std::max(1, g.K / (4 * BK)));
-    while (splits > 1 && (size_t)splits * g.M * g.N * sizeof(float) > g.ws_bytes) --splits;
+    // the split count that best fills whole rounds of the chip, fewer splits preferred
+    // (every split writes and re-reads an M x N fp32 partial)
+    const int max_splits = std::min(16, std::max(1, g.K / (4 * BK)));
+    double best = -1.0;
+    for (int sp = 1; sp <= max_splits; ++sp) {
+      if (sp > 1 && (size_t)sp * g.M * g.N * sizeof(float) > g.ws_bytes) break;
+      const int items = tiles * sp, rounds = (items + cus - 1) / cus;
+      const double score = (double)items / ((double)rounds * cus) - 0.01 * sp;
+      if (score > best) { best = score; splits = sp; }
+    }
   }
   int k_per_split = (g.K + splits - 1) / splits;
   k_per_split = (k_per_split + BK - 1) / BK * BK;
   splits = (g.K + k_per_split - 1) / k_per_split;
   const size_t lds = (size_t)2 * (BM + BN) * (BK + LDS_PAD) * sizeof(bf16_t);
   GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate};
-  dim3 grid(std::min(tiles * splits, cus)), block(WGM * WGN * 64);
+  // a multiple of 8 workgroups: the kernel deals work items out per XCD
+  dim3 grid(std::min((tiles * splits + 7) / 8 * 8, std::max(8, cus / 8 * 8))), block(WGM * WGN * 64);
 #define KARMA_GEMM_LAUNCH(AK, BKC)                                                                      \
   do {                                                                                                  \
     auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, AK, BKC>;                                        \
