@@ -52,6 +52,27 @@ __device__ __forceinline__ bf16x8 frag_regs(const f32x16& a, int s, float mul) {
 // grid (seq/128, heads, batch), 256 threads; wavefront w owns queries q0+32w .. q0+32w+31
 // and walks the keys in tiles of 128 (four 32-key sub-tiles; sub-tiles entirely after the
 // wavefront's queries are skipped).
+// Workgroup -> (tile, head, batch).  Workgroup ids go round-robin over the 8 XCDs; all tiles
+// of one (batch, head) are given to the same XCD, so that head's K and V are fetched into one
+// L2 only, and the heaviest tile of the causal triangle goes first (heavy_high: the last
+// tile is the heaviest).
+__device__ __forceinline__ void attn_block(int& tile, int& head, int& b, bool heavy_high) {
+  const int nt = gridDim.x, H = gridDim.y, hb_total = gridDim.y * gridDim.z;
+  const int L = blockIdx.x + nt * (blockIdx.y + H * blockIdx.z);
+  int t, hb;
+  if (hb_total % 8 == 0) {
+    const int slot = L / 8;
+    hb = (slot / nt) * 8 + L % 8;
+    t = slot % nt;
+  } else {
+    t = L % nt;
+    hb = L / nt;
+  }
+  tile = heavy_high ? nt - 1 - t : t;
+  head = hb % H;
+  b = hb / H;
+}
+
 template <int D>
 __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                         float* __restrict__ lse, int S, int H) {
@@ -61,7 +82,9 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
   __shared__ __attribute__((aligned(16))) bf16_t Vt[D * PV];
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
-  const int q0 = blockIdx.x * 128, head = blockIdx.y, b = blockIdx.z;
+  int tile, head, b;
+  attn_block(tile, head, b, true);
+  const int q0 = tile * 128;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lrow = lane & 31, g = lane >> 5;
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * D;
   const bf16_t* Qg = base;
@@ -215,7 +238,9 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
   bf16_t* Kt = Vs + KT * PK;         // [D][PT]   K transposed
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
-  const int q0 = blockIdx.x * 128, head = blockIdx.y, b = blockIdx.z;
+  int tile, head, b;
+  attn_block(tile, head, b, true);
+  const int q0 = tile * 128;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lrow = lane & 31, g = lane >> 5;
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * D;
   const bf16_t* Kg = base + h;
@@ -327,7 +352,9 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
   float* delta_s = lse_s + QT;
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
-  const int k0 = blockIdx.x * 128, head = blockIdx.y, b = blockIdx.z;
+  int tile, head, b;
+  attn_block(tile, head, b, false);
+  const int k0 = tile * 128;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lrow = lane & 31, g = lane >> 5;
   const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * D;
   const bf16_t* dOg = dout + (size_t)b * S * h + (size_t)head * D;
