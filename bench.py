@@ -24,6 +24,10 @@ BUDGET = 16 * GIB
 ARENA = 32 * GIB
 SEED = 2008114202
 PEAK_BF16_TFLOPS = 2500.0
+# Average HBM-side bytes per GEMM launch of this workload: FETCH_SIZE + WRITE_SIZE of all
+# gemm_bf16_kernel launches, each scaled by the same counter's reading for the 1 GiB copy
+# below (profiles/gpt24_step_kernel_stats_and_hbm_traffic.txt: 325.9 MiB + 111.4 MiB).
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (325.9 + 111.4) * 1048576
 CPU_SAMPLE_BATCH = 8   # sequences in the oracle's timed sample (about 20 s of host work)
 
 
@@ -183,7 +187,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all launches of the timed steps)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "launches_per_step": n_l / max(args.steps, 1), "avg_launch_ms": ms_l / max(n_l, 1),
-                     "flops_per_launch": fl_l / max(n_l, 1), "traffic": None},
+                     "flops_per_launch": fl_l / max(n_l, 1), "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)"},
     }
     ctx.close()
     del ctx
