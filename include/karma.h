@@ -58,6 +58,10 @@ typedef struct {
   uint64_t out_bytes;           /* output = input of the next layer (x_0 is the step input
                                    and lives in the fixed region) */
   uint64_t ws_bytes;            /* transient workspace of any one op of the layer */
+  uint64_t w_bytes;             /* weights streamed over the host link for this layer (Sec. III-G:
+                                   a swapped block carries its weights); 0 = weights resident,
+                                   their bytes are part of the fixed region */
+  uint64_t g_bytes;             /* gradients of those weights (ignored when w_bytes is 0) */
 } karma_layer_cost;
 
 typedef struct {
@@ -80,10 +84,12 @@ typedef struct {
 } karma_plan_summary;
 
 /* One op of the simulated/executed timeline, in issue order.
- * kind: 'F' forward, 'B' backward, 'R' recompute, 'L' loss, 'O' swap-out, 'I' swap-in.
+ * kind: 'F' forward, 'B' backward, 'R' recompute, 'L' loss, 'O' swap-out, 'I' swap-in,
+ *   'W' copy-in of a layer's streamed weights, 'G' copy-out of their gradients.
  * off[]: arena offsets (relative to the end of the fixed region, -1 = none) of what the
  *   op allocates: F {x_{i+1}, internals, workspace}; R {internals, x_{i+1}, workspace};
- *   B and L {dx, workspace, -1}; I {x_i, internals, -1}; O {-1,-1,-1}. */
+ *   B {dx, workspace, gradients of streamed weights}; L {dx, workspace, -1};
+ *   I {x_i, internals, -1}; W {weights, -1, -1}; O and G {-1,-1,-1}. */
 typedef struct {
   uint8_t kind;
   uint32_t layer;
@@ -95,23 +101,32 @@ typedef struct {
 
 /* Timeline of one step under a given action vector (three in-order queues and a
  * two-ended first-fit arena of budget - fixed bytes; constraint 9.4 is checked at every
- * allocation).  ops_out may be NULL; otherwise *n_ops_inout holds its capacity on entry
- * and the number of ops on return (KARMA_E_OOM if too small: at most 6*n+2 are written).
+ * allocation).  weights_kept (host, n_layers bytes, may be NULL = all 0) says per layer
+ * with streamed weights whether they stay in HBM from F_i to B_i (1) or are freed after
+ * F_i and copied in again before R_i / B_i (0); weights are copied in one layer ahead of
+ * the forward pass and queued with the swap-ins, in order of need, during backward;
+ * gradients leave right after B_i (Sec. III-G, pipeline stage 3).  ops_out may be NULL;
+ * otherwise *n_ops_inout holds its capacity on entry and the number of ops on return
+ * (KARMA_E_OOM if too small: at most 8*n+2 are written).
  * Errors: KARMA_E_INVAL (invalid vector), KARMA_E_BUDGET (does not fit). */
 int karma_simulate(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
                    const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
-                   const uint8_t* actions, karma_plan_summary* summary_out, karma_op* ops_out,
-                   uint32_t* n_ops_inout);
+                   const uint8_t* actions, const uint8_t* weights_kept, karma_plan_summary* summary_out,
+                   karma_op* ops_out, uint32_t* n_ops_inout);
 
 /* The planner (Sec. III-E capacity rule, Eq. 10.1 recompute marking, makespan
- * refinement by local search over the simulator).  Writes n_layers actions.
+ * refinement by local search over the simulator; then, for layers with streamed weights,
+ * the capacity rule applied to weights: going down from the last layer, a layer keeps
+ * its weights between F_i and B_i while that fits and does not lengthen the step).
+ * Writes n_layers actions and, when weights_kept_out is not NULL, n_layers bytes.
  * Errors: KARMA_E_BUDGET when nothing fits. */
 int karma_plan_pure(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
                     const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
-                    uint8_t* actions_out, karma_plan_summary* summary_out);
+                    uint8_t* actions_out, uint8_t* weights_kept_out, karma_plan_summary* summary_out);
 
 /* Algorithm 1's output in the paper's notation ("F1 -> F2||S1^out -> ...", layers
- * 1-based, recompute printed as F).  Writes a NUL-terminated string; KARMA_E_OOM if
+ * 1-based, recompute printed as F; copies of streamed weights and of their gradients
+ * print as W<i>^in and G<i>^out).  Writes a NUL-terminated string; KARMA_E_OOM if
  * buf_len is too small. */
 int karma_stage_string(const karma_op* ops, uint32_t n_ops, char* buf, size_t buf_len);
 
@@ -129,6 +144,10 @@ typedef struct {
   uint32_t n_heads;   /* GPT only; width / n_heads must be 64 or 128 */
   uint32_t ffn;       /* GPT only */
   uint32_t vocab;     /* GPT only */
+  uint32_t stream_weights; /* 1: the weights of every MLP layer / transformer block live in
+                              pinned host memory and are streamed through the arena around the
+                              layer's ops, their gradients streamed out after its backward
+                              (Sec. III-G); embeddings and the final LayerNorm stay resident */
 } karma_model_desc;
 
 typedef struct {
@@ -153,8 +172,9 @@ const char* karma_last_error(const karma_ctx* ctx);
 
 /* Parameter tensors.  Record/tensor numbering: see karma_param_count/karma_param_size.
  * set: copies n fp32 values into the host master copy and uploads the device copy
- * (rounded to bf16 by round-to-nearest-even for bf16 models).  get_param reads the
- * master copy; get_grad copies the gradient of the last step (converted to fp32). */
+ * (rounded to bf16 by round-to-nearest-even for bf16 models; for streamed weights the
+ * "device copy" is the pinned host buffer the next step streams from).  get_param reads
+ * the master copy; get_grad copies the gradient of the last step (converted to fp32). */
 int karma_param_count(const karma_ctx* ctx, uint32_t layer, uint32_t* n_tensors_out);
 int karma_param_size(const karma_ctx* ctx, uint32_t layer, uint32_t tensor, uint64_t* n_elems_out);
 int karma_set_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, const float* host_fp32, uint64_t n);
@@ -175,10 +195,15 @@ int karma_set_costs(karma_ctx* ctx, const karma_layer_cost* layers, const karma_
                     const karma_link* link);
 
 /* Plans for a budget (<= arena_bytes) with the current cost records and builds the
- * executable schedule.  actions_out (may be NULL) receives the chosen actions. */
-int karma_plan(karma_ctx* ctx, uint64_t budget_bytes, uint8_t* actions_out, karma_plan_summary* summary_out);
-/* Forces an action vector (validated against the budget by simulation). */
-int karma_set_plan(karma_ctx* ctx, uint64_t budget_bytes, const uint8_t* actions, karma_plan_summary* summary_out);
+ * executable schedule.  actions_out and weights_kept_out (each may be NULL, n_layers
+ * bytes) receive the chosen actions and, for streamed weights, which layers keep them
+ * between forward and backward. */
+int karma_plan(karma_ctx* ctx, uint64_t budget_bytes, uint8_t* actions_out, uint8_t* weights_kept_out,
+               karma_plan_summary* summary_out);
+/* Forces an action vector and weight choice (weights_kept may be NULL = no layer keeps
+ * its streamed weights); validated against the budget by simulation. */
+int karma_set_plan(karma_ctx* ctx, uint64_t budget_bytes, const uint8_t* actions, const uint8_t* weights_kept,
+                   karma_plan_summary* summary_out);
 /* Stage string of the current plan. */
 int karma_plan_string(karma_ctx* ctx, char* buf, size_t buf_len);
 

@@ -25,6 +25,15 @@ Model of one step (a "block" of the paper is one layer record here):
   `budget - fixed` bytes managed by a two-ended first-fit allocator.  Long-lived
   buffers (layer inputs x_i, saved internals s_i) are carved from the lowest fitting
   free range, short-lived ones (workspace, activation gradients dx_i) from the highest.
+
+Weight streaming (Sec. III-G: a swapped block carries its weights; stage 3 of the
+pipeline swaps a block's gradients out after its backward while earlier blocks are
+swapped in): a layer with wb > 0 keeps its weights on the host.  They are copied in
+before F_i, one layer ahead of the compute queue.  With wres[i] = 1 they then stay until
+B_i ends (the capacity-based choice for the tail of the model); with wres[i] = 0 they are
+freed after F_i and copied in again before R_i / B_i, queued with the activation swap-ins
+in order of need.  The gradients get a buffer when B_i starts and leave on the
+device-to-host queue when it ends.
 """
 from collections import deque, namedtuple
 
@@ -35,12 +44,14 @@ ALIGN = 256
 # per-layer costs.  tf/tb/trc: forward, backward, recompute time (ns).  sav: bytes of
 # internals backward needs besides the layer input.  out: bytes of the layer output
 # (= the next layer's input).  ws: transient workspace bytes of any op of this layer.
-Layer = namedtuple("Layer", "tf tb trc sav out ws")
+# wb/gb: bytes of the layer's weights / weight gradients when they are streamed over the
+# host link instead of living in the fixed region (0 = resident).
+Layer = namedtuple("Layer", "tf tb trc sav out ws wb gb", defaults=(0, 0))
 # host link: bytes/s per direction and a fixed per-copy latency (ns)
 Link = namedtuple("Link", "bw_h2d bw_d2h lat_ns")
 # loss op that sits between forward and backward: time and workspace
 Loss = namedtuple("Loss", "t ws")
-Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN
+Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN WIN GOUT
 
 
 class Infeasible(Exception):
@@ -144,8 +155,9 @@ def backward_units(actions):
     return units
 
 
-def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
-    """Timeline of one training step under a given per-layer action vector.
+def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=None):
+    """Timeline of one training step under a given per-layer action vector (and, for
+    layers with streamed weights, the per-layer choice `wres`).
 
     Returns a dict with makespan_ns, stall_ns, busy_ns, peak_bytes, bytes_d2h,
     bytes_h2d, recompute_ns (and `ops` when asked).  Raises Infeasible when the arena
@@ -163,9 +175,18 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
     xb = [al(b) for b in xraw]
     sb = [al(l.sav) for l in layers]
     wsb = [al(l.ws) for l in layers]
+    wB = [al(l.wb) for l in layers]       # streamed weights (0 = resident in `fixed`)
+    gB = [al(l.gb) if l.wb else 0 for l in layers]
+    if wres is None:
+        wres = [0] * L
+    if len(wres) != L:
+        raise ValueError("invalid wres vector")
     X = [None] * (L + 1)      # offsets
     S = [None] * L
     DX = [None] * (L + 1)
+    W = [None] * L
+    G = [None] * L
+    warr = [0] * L            # arrival time of the weights for the current phase
     pending = deque()         # (time, [(off, size), ...]) frees at D2H completion
     out_end = [0] * L         # end of layer i's swap-out: its swap-in cannot start earlier
     ops = []
@@ -198,19 +219,42 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
         if off is not None:
             ar.release(off, size)
 
+    def weight_in(i, t):
+        """Copy of layer i's weights into W[i] (already allocated), on the H2D queue."""
+        nonlocal th, h2d
+        st = max(th, t)
+        th = st + copy_ns(layers[i].wb, link.bw_h2d, link.lat_ns)
+        h2d += layers[i].wb
+        warr[i] = th
+        if want_ops:
+            ops.append(Op("WIN", i, st, th, (W[i],)))
+
     # ---------------- forward ----------------
     for i in range(L):
         t = tc
         apply_pending(t)
+        if wB[i] and W[i] is None:      # not prefetched: fetched now, the layer waits
+            W[i], t = grant(wB[i], bool(wres[i]), t)
+            weight_in(i, t)
         X[i + 1], t = grant(xb[i + 1], True, t)
         S[i], t = grant(sb[i], True, t)
         w, t = grant(wsb[i], False, t)
+        if wB[i]:
+            t = max(t, warr[i])
+        # the next layer's weights start their trip when this layer starts computing
+        if i + 1 < L and wB[i + 1]:
+            W[i + 1] = ar.alloc(wB[i + 1], bool(wres[i + 1]))
+            if W[i + 1] is not None:
+                weight_in(i + 1, t)
         end = t + layers[i].tf
         busy += layers[i].tf
         if want_ops:
             ops.append(Op("F", i, t, end, (X[i + 1], S[i], w)))
         tc = end
         rel(w, wsb[i])
+        if wB[i] and not wres[i]:
+            rel(W[i], wB[i])
+            W[i] = None
         a = actions[i]
         if a == SWAP or a == RC_SWAP:
             nbytes = xraw[i] + (layers[i].sav if a == SWAP else 0)
@@ -236,17 +280,23 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
             rel(X[i], xb[i])
 
     # ---------------- prefetch queue and reserves ----------------
+    # Items of the H2D queue during backward, in order of need: ("A", i) = the swapped
+    # tensors of layer i, ("W", i) = the weights of a layer that did not keep them.
     units = backward_units(actions)
-    items = deque(i for i in range(L - 1, -1, -1)
-                  if (actions[i] == SWAP and xraw[i] + layers[i].sav) or
-                     (actions[i] == RC_SWAP and xraw[i]))
+    items = deque()
+    for h, e in units:
+        if (actions[h] == SWAP and xraw[h] + layers[h].sav) or (actions[h] == RC_SWAP and xraw[h]):
+            items.append(("A", h))
+        for j in range(h, e + 1):
+            if wB[j] and not wres[j]:
+                items.append(("W", j))
     arrive = {}
 
     def unit_need(h, e):
         if actions[h] in (KEEP, SWAP):
-            return xb[h] + wsb[h]
+            return xb[h] + wsb[h] + gB[h]
         s = sum(sb[j] for j in range(h, e + 1)) + sum(xb[j + 1] for j in range(h, e))
-        return s + max(xb[j] + wsb[j] for j in range(h, e + 1))
+        return s + max(xb[j] + wsb[j] + gB[j] for j in range(h, e + 1))
 
     needs = [unit_need(h, e) for h, e in units]
     res_after = [0] * len(units)
@@ -255,9 +305,22 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
     res_all = max(needs) if needs else 0
     loss_need = xb[L] + al(loss.ws)
 
-    def place(i):
-        """Try to allocate the swap-in buffers of layer i (low end); roll back on
+    def item_need(it):
+        kind, i = it
+        if kind == "W":
+            return wB[i]
+        return xb[i] + (sb[i] if actions[i] == SWAP else 0)
+
+    def place(it):
+        """Try to allocate the buffers of a queued copy (low end); roll back on
         failure."""
+        kind, i = it
+        if kind == "W":
+            off = ar.alloc(wB[i], True)
+            if off is None:
+                return False
+            W[i] = off
+            return True
         xo = so = None
         if xb[i]:
             xo = ar.alloc(xb[i], True)
@@ -274,37 +337,51 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
             S[i] = so
         return True
 
-    def issue_in(i, t):
+    def issue_in(it, t):
         nonlocal th, h2d
+        kind, i = it
+        if kind == "W":
+            weight_in(i, t)
+            arrive[it] = th
+            return
         nbytes = xraw[i] + (layers[i].sav if actions[i] == SWAP else 0)
         st = max(th, t, out_end[i])
         th = st + copy_ns(nbytes, link.bw_h2d, link.lat_ns)
         h2d += nbytes
-        arrive[i] = th
+        arrive[it] = th
         if want_ops:
             ops.append(Op("IN", i, st, th, (X[i], S[i] if actions[i] == SWAP else None)))
 
     def admit(t, reserve):
-        """Swap in ahead of need, in order of need, while the arena keeps `reserve`
+        """Copy in ahead of need, in order of need, while the arena keeps `reserve`
         bytes for the compute ops still to come (Sec. III-E: keep swapping in as long
         as there is space)."""
         apply_pending(t)
         while items:
-            i = items[0]
-            need = xb[i] + (sb[i] if actions[i] == SWAP else 0)
-            if ar.total_free() < need + reserve or not place(i):
+            it = items[0]
+            if ar.total_free() < item_need(it) + reserve or not place(it):
                 break
             items.popleft()
-            issue_in(i, t)
+            issue_in(it, t)
 
-    def force(i, t):
-        """Layer i's data is needed now: admit everything up to and including it."""
-        while i not in arrive:
-            j = items.popleft()
-            X[j], t = grant(xb[j], True, t)
-            if actions[j] == SWAP:
-                S[j], t = grant(sb[j], True, t)
-            issue_in(j, t)
+    def force(it, t):
+        """This item is needed now: admit everything up to and including it."""
+        while it not in arrive:
+            jt = items.popleft()
+            kind, j = jt
+            if kind == "W":
+                W[j], t = grant(wB[j], True, t)
+            else:
+                X[j], t = grant(xb[j], True, t)
+                if actions[j] == SWAP:
+                    S[j], t = grant(sb[j], True, t)
+            issue_in(jt, t)
+        return t
+
+    def wait_for(it, t):
+        if it in arrive or it in items:
+            t = force(it, t)
+            t = max(t, arrive[it])
         return t
 
     # ---------------- loss ----------------
@@ -324,32 +401,45 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False):
 
     # ---------------- backward ----------------
     def backward_op(j, t, reserve):
-        nonlocal tc, busy
+        nonlocal tc, td, busy, d2h
         apply_pending(t)
         DX[j], t = grant(xb[j], False, t)
         w, t = grant(wsb[j], False, t)
+        G[j], t = grant(gB[j], False, t)
         end = t + layers[j].tb
         busy += layers[j].tb
         if want_ops:
-            ops.append(Op("B", j, t, end, (DX[j], w)))
+            ops.append(Op("B", j, t, end, (DX[j], w, G[j])))
         tc = end
         rel(w, wsb[j])
         rel(DX[j + 1], xb[j + 1])
         rel(S[j], sb[j])
         rel(X[j], xb[j])
+        if wB[j]:
+            rel(W[j], wB[j])
+            W[j] = None
+        if gB[j]:
+            # the gradients leave right after the layer's backward (pipeline stage 3)
+            st = max(td, end)
+            td = st + copy_ns(layers[j].gb, link.bw_d2h, link.lat_ns)
+            d2h += layers[j].gb
+            pending.append((td, [(G[j], gB[j])]))
+            if want_ops:
+                ops.append(Op("GOUT", j, st, td, ()))
         admit(tc, reserve)
 
     for k, (h, e) in enumerate(units):
         a = actions[h]
         t = tc
-        if a in (SWAP, RC_SWAP) and (h in arrive or h in items):
-            t = force(h, t)
-            t = max(t, arrive[h])
+        if a in (SWAP, RC_SWAP):
+            t = wait_for(("A", h), t)
         if a in (KEEP, SWAP):
+            t = wait_for(("W", h), t)
             backward_op(h, t, res_after[k])
             continue
-        inner = max(xb[j] + wsb[j] for j in range(h, e + 1))
+        inner = max(xb[j] + wsb[j] + gB[j] for j in range(h, e + 1))
         for j in range(h, e + 1):
+            t = wait_for(("W", j), t)
             apply_pending(t)
             S[j], t = grant(sb[j], True, t)
             if j < e:
@@ -387,9 +477,9 @@ def cost_tuple(summary):
             summary["recompute_ns"])
 
 
-def try_cost(layers, link, budget, fixed, loss, actions):
+def try_cost(layers, link, budget, fixed, loss, actions, wres=None):
     try:
-        return cost_tuple(simulate(layers, link, budget, fixed, loss, actions))
+        return cost_tuple(simulate(layers, link, budget, fixed, loss, actions, wres=wres))
     except Infeasible:
         return None
 
@@ -397,20 +487,30 @@ def try_cost(layers, link, budget, fixed, loss, actions):
 def plan(layers, link, budget, fixed, loss):
     """Deterministic stand-in for the paper's two-tier optimisation.
 
-    1. Capacity rule (Sec. III-E): everything fits -> all KEEP.  Otherwise the resident
-       tail is as long as memory allows, the prefix before it is swapped.
+    1. Capacity rule (Sec. III-E): everything fits -> all KEEP (streamed weights stay
+       from F_i to B_i).  Otherwise the resident tail is as long as memory allows, the
+       prefix before it is swapped.
     2. Recompute marking (Eq. 10.1, read with the prose above it): going down the
        prefix, a swapped layer becomes a recompute layer when its recompute time is
        strictly less than the swap-in it replaces.
     3. Makespan refinement (`refine`): local search on (makespan, bytes moved,
        recompute time), from two starts (swapped prefix after step 2; recomputed
        prefix); the better local optimum wins.
-    Returns (actions, summary); raises Infeasible when no assignment tried fits."""
+    4. Streamed weights (steps 1-3 run with every streamed layer fetching its weights
+       twice): going down from the last layer, a layer keeps its weights between F_i and
+       B_i as long as that fits and does not lengthen the step (the capacity-based rule
+       applied to weights: the tail of the model stays); the first layer that cannot
+       ends the scan.
+    Returns (actions, summary) with summary["wres"] the per-layer weight choice; raises
+    Infeasible when no assignment tried fits."""
     L = len(layers)
+    streamed = [1 if l.wb else 0 for l in layers]
     cur = [KEEP] * L
-    c = try_cost(layers, link, budget, fixed, loss, cur)
+    c = try_cost(layers, link, budget, fixed, loss, cur, streamed)
     if c is not None:
-        return cur, simulate(layers, link, budget, fixed, loss, cur)
+        res = simulate(layers, link, budget, fixed, loss, cur, wres=streamed)
+        res["wres"] = streamed
+        return cur, res
 
     # step 1: longest resident tail; the prefix before it swapped, or (second start)
     # recomputed from kept checkpoints; patterns that hold less memory as fall-backs.
@@ -452,8 +552,22 @@ def plan(layers, link, budget, fixed, loss):
         key = refine(layers, link, budget, fixed, loss, start)
         if best is None or key < best:
             best = key
-    cur = best[1]
-    return cur, simulate(layers, link, budget, fixed, loss, cur)
+    cost, cur = best
+
+    # step 4: the tail keeps its streamed weights
+    wres = [0] * L
+    for i in range(L - 1, -1, -1):
+        if not streamed[i]:
+            continue
+        cand = list(wres)
+        cand[i] = 1
+        cc = try_cost(layers, link, budget, fixed, loss, cur, cand)
+        if cc is None or not cc < cost:
+            break
+        wres, cost = cand, cc
+    res = simulate(layers, link, budget, fixed, loss, cur, wres=wres)
+    res["wres"] = wres
+    return cur, res
 
 
 def refine(layers, link, budget, fixed, loss, start):
@@ -500,7 +614,7 @@ def refine(layers, link, budget, fixed, loss, start):
     return key
 
 
-def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN)):
+def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN), wres=None):
     """Exhaustive search over every valid assignment: smallest cost tuple, ties to the
     lexicographically smallest action vector.  Exponential; for small stacks only."""
     L = len(layers)
@@ -510,7 +624,7 @@ def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP
     def rec(i):
         nonlocal best
         if i == L:
-            c = try_cost(layers, link, budget, fixed, loss, cur)
+            c = try_cost(layers, link, budget, fixed, loss, cur, wres)
             if c is not None and (best is None or (c, cur) < best):
                 best = (c, list(cur))
             return
@@ -531,7 +645,7 @@ def stage_string(ops):
     inserted as fresh stages by Algorithm 1 and carry no copies: a copy that starts
     during one is listed on the next forward/backward stage.  Layers print 1-based."""
     stages = [o for o in ops if o.kind in "FBR"]
-    copies = [o for o in ops if o.kind in ("IN", "OUT")]
+    copies = [o for o in ops if o.kind in ("IN", "OUT", "WIN", "GOUT")]
     att = [[] for _ in stages]
     for c in copies:
         idx = None
@@ -546,7 +660,8 @@ def stage_string(ops):
     for s, cs in zip(stages, att):
         txt = ("B" if s.kind == "B" else "F") + str(s.layer + 1)
         for c in cs:
-            txt += "||S%d^%s" % (c.layer + 1, "in" if c.kind == "IN" else "out")
+            txt += "||%s%d^%s" % ({"WIN": "W", "GOUT": "G"}.get(c.kind, "S"), c.layer + 1,
+                                  "in" if c.kind in ("IN", "WIN") else "out")
         parts.append(txt)
     return " -> ".join(parts)
 

@@ -22,7 +22,8 @@ GEMM_A_STRIDED, GEMM_B_STRIDED, GEMM_OUT_F32, GEMM_ACCUMULATE = 1, 2, 4, 8
 
 class LayerCost(C.Structure):
     _fields_ = [("tf_ns", C.c_int64), ("tb_ns", C.c_int64), ("trc_ns", C.c_int64),
-                ("sav_bytes", C.c_uint64), ("out_bytes", C.c_uint64), ("ws_bytes", C.c_uint64)]
+                ("sav_bytes", C.c_uint64), ("out_bytes", C.c_uint64), ("ws_bytes", C.c_uint64),
+                ("w_bytes", C.c_uint64), ("g_bytes", C.c_uint64)]
 
 
 class Link(C.Structure):
@@ -49,7 +50,8 @@ class Op(C.Structure):
 
 class ModelDesc(C.Structure):
     _fields_ = [("kind", C.c_uint32), ("n_layers", C.c_uint32), ("width", C.c_uint32), ("batch", C.c_uint32),
-                ("seq", C.c_uint32), ("n_heads", C.c_uint32), ("ffn", C.c_uint32), ("vocab", C.c_uint32)]
+                ("seq", C.c_uint32), ("n_heads", C.c_uint32), ("ffn", C.c_uint32), ("vocab", C.c_uint32),
+                ("stream_weights", C.c_uint32)]
 
 
 class Config(C.Structure):
@@ -110,18 +112,19 @@ def _check(st, where, ctx=None):
 
 
 # ------------------------------------------------------------------ pure planner
-def karma_simulate(layers, link, loss, budget, fixed, actions, want_ops=False):
-    """layers: sequence of (tf, tb, trc, sav, out, ws); link: (bw_h2d, bw_d2h, lat);
+def karma_simulate(layers, link, loss, budget, fixed, actions, want_ops=False, weights_kept=None):
+    """layers: sequence of (tf, tb, trc, sav, out, ws[, wb, gb]); link: (bw_h2d, bw_d2h, lat);
     loss: (t, ws).  Returns summary dict (and ops list when asked)."""
     n = len(layers)
     arr = _layers_array(layers)
     lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
     act = (C.c_uint8 * n)(*actions)
+    kept = (C.c_uint8 * n)(*weights_kept) if weights_kept is not None else None
     summ = PlanSummary()
-    ops = (Op * (6 * n + 2))() if want_ops else None
-    nops = C.c_uint32(6 * n + 2)
+    ops = (Op * (8 * n + 2))() if want_ops else None
+    nops = C.c_uint32(8 * n + 2)
     st = lib().karma_simulate(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget), C.c_uint64(fixed),
-                              act, C.byref(summ), ops, C.byref(nops))
+                              act, kept, C.byref(summ), ops, C.byref(nops))
     _check(st, "karma_simulate")
     if want_ops:
         return summ.as_dict(), [ops[k] for k in range(nops.value)]
@@ -133,11 +136,14 @@ def karma_plan_pure(layers, link, loss, budget, fixed):
     arr = _layers_array(layers)
     lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
     act = (C.c_uint8 * n)()
+    kept = (C.c_uint8 * n)()
     summ = PlanSummary()
     st = lib().karma_plan_pure(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget), C.c_uint64(fixed),
-                               act, C.byref(summ))
+                               act, kept, C.byref(summ))
     _check(st, "karma_plan_pure")
-    return list(act), summ.as_dict()
+    res = summ.as_dict()
+    res["wres"] = list(kept)
+    return list(act), res
 
 
 def karma_stage_string(ops):
@@ -219,7 +225,7 @@ class Context:
         loss = LossCost()
         fixed = C.c_uint64()
         self._chk(lib().karma_get_costs(self.ctx, arr, C.byref(loss), C.byref(fixed)), "karma_get_costs")
-        layers = [(l.tf_ns, l.tb_ns, l.trc_ns, l.sav_bytes, l.out_bytes, l.ws_bytes) for l in arr]
+        layers = [(l.tf_ns, l.tb_ns, l.trc_ns, l.sav_bytes, l.out_bytes, l.ws_bytes, l.w_bytes, l.g_bytes) for l in arr]
         return layers, (loss.t_ns, loss.ws_bytes), fixed.value
 
     def karma_set_costs(self, layers=None, loss=None, link=None):
@@ -235,14 +241,18 @@ class Context:
 
     def karma_plan(self, budget):
         act = (C.c_uint8 * self.n_layers)()
+        kept = (C.c_uint8 * self.n_layers)()
         summ = PlanSummary()
-        self._chk(lib().karma_plan(self.ctx, C.c_uint64(budget), act, C.byref(summ)), "karma_plan")
-        return list(act), summ.as_dict()
+        self._chk(lib().karma_plan(self.ctx, C.c_uint64(budget), act, kept, C.byref(summ)), "karma_plan")
+        res = summ.as_dict()
+        res["wres"] = list(kept)
+        return list(act), res
 
-    def karma_set_plan(self, budget, actions):
+    def karma_set_plan(self, budget, actions, weights_kept=None):
         act = (C.c_uint8 * self.n_layers)(*actions)
+        kept = (C.c_uint8 * self.n_layers)(*weights_kept) if weights_kept is not None else None
         summ = PlanSummary()
-        self._chk(lib().karma_set_plan(self.ctx, C.c_uint64(budget), act, C.byref(summ)), "karma_set_plan")
+        self._chk(lib().karma_set_plan(self.ctx, C.c_uint64(budget), act, kept, C.byref(summ)), "karma_set_plan")
         return summ.as_dict()
 
     def karma_plan_string(self):

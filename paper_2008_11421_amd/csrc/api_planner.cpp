@@ -7,15 +7,15 @@ using namespace karma;
 
 extern "C" int karma_simulate(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
                               const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
-                              const uint8_t* actions, karma_plan_summary* summary_out, karma_op* ops_out,
-                              uint32_t* n_ops_inout) {
+                              const uint8_t* actions, const uint8_t* weights_kept, karma_plan_summary* summary_out,
+                              karma_op* ops_out, uint32_t* n_ops_inout) {
   if (!layers || !n_layers || !link || !loss || !actions || !link->bw_h2d || !link->bw_d2h) return KARMA_E_INVAL;
   if (ops_out && !n_ops_inout) return KARMA_E_INVAL;
   if (!actions_valid(actions, n_layers)) return KARMA_E_INVAL;
   Problem P{layers, n_layers, *link, *loss, budget_bytes, fixed_bytes};
   std::vector<karma_op> ops;
   karma_plan_summary s;
-  if (!simulate(P, actions, &s, ops_out ? &ops : nullptr)) return KARMA_E_BUDGET;
+  if (!simulate(P, actions, weights_kept, &s, ops_out ? &ops : nullptr)) return KARMA_E_BUDGET;
   if (summary_out) *summary_out = s;
   if (ops_out) {
     if (ops.size() > *n_ops_inout) { *n_ops_inout = (uint32_t)ops.size(); return KARMA_E_OOM; }
@@ -27,13 +27,14 @@ extern "C" int karma_simulate(const karma_layer_cost* layers, uint32_t n_layers,
 
 extern "C" int karma_plan_pure(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
                                const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
-                               uint8_t* actions_out, karma_plan_summary* summary_out) {
+                               uint8_t* actions_out, uint8_t* weights_kept_out, karma_plan_summary* summary_out) {
   if (!layers || !n_layers || !link || !loss || !actions_out || !link->bw_h2d || !link->bw_d2h) return KARMA_E_INVAL;
   Problem P{layers, n_layers, *link, *loss, budget_bytes, fixed_bytes};
-  std::vector<uint8_t> a;
+  std::vector<uint8_t> a, kw;
   karma_plan_summary s;
-  if (!plan(P, a, &s)) return KARMA_E_BUDGET;
+  if (!plan(P, a, kw, &s)) return KARMA_E_BUDGET;
   std::memcpy(actions_out, a.data(), n_layers);
+  if (weights_kept_out) std::memcpy(weights_kept_out, kw.data(), n_layers);
   if (summary_out) *summary_out = s;
   return KARMA_OK;
 }

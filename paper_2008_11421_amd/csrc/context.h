@@ -18,7 +18,8 @@ struct Param {
   uint64_t n = 0;
   bool dev_bf16 = false;    // device copy of the weight: bf16 (else fp32)
   bool grad_bf16 = false;   // device gradient: bf16 (else fp32)
-  uint64_t w_off = 0, g_off = 0;   // byte offsets in the fixed region
+  uint64_t w_off = 0, g_off = 0;   // byte offsets in the fixed region (resident weights)
+  uint64_t w_rel = 0, g_rel = 0;   // byte offsets in the record's streamed weight / gradient buffer
   std::vector<float> master, m, v; // host fp32 master copy and optimiser state
   void* stage_g = nullptr;         // pinned: gradient as it arrives from the device
   void* stage_w = nullptr;         // pinned: new weight in device format
@@ -35,6 +36,13 @@ struct Record {
   int kind = 0;
   std::vector<Param> p;
   uint64_t out_bytes = 0, sav_bytes = 0, ws_bytes = 0;   // from shapes
+  // Streamed weights (Sec. III-G: a swapped block carries its weights): the device copy
+  // lives in pinned host memory, one contiguous buffer per record, and visits the arena
+  // only around the record's ops; the gradients take the opposite way after its backward.
+  bool streamed = false;
+  uint64_t w_total = 0, g_total = 0;     // bytes of the two buffers (parameters 256-B aligned)
+  char* stage_w_all = nullptr;           // pinned; Param::stage_w point into it
+  char* stage_g_all = nullptr;           // pinned; Param::stage_g point into it
 };
 
 // One op of the executable schedule; offsets are relative to the activation region,
@@ -43,6 +51,7 @@ struct ProgOp {
   char kind;
   uint32_t layer;
   int64_t x = -1, s = -1, out = -1, dy = -1, dx = -1, ws = -1;
+  int64_t w = -1, g = -1;         // streamed weights / their gradients (F, R, B, W, G ops)
   std::vector<uint32_t> waits;
   bool record = false;
   int stream = 0;                 // 0 compute, 1 h2d, 2 d2h
@@ -74,6 +83,7 @@ struct Ctx {
   bool planned = false;
   uint64_t budget = 0;
   std::vector<uint8_t> actions;
+  std::vector<uint8_t> keepw;             // per record: streamed weights stay from F_i to B_i
   std::vector<karma_op> ops;
   std::vector<ProgOp> prog;
   karma_plan_summary summary{};
@@ -100,6 +110,14 @@ struct Ctx {
   char* act_ptr(int64_t off) const { return off < 0 ? nullptr : arena + fixed_bytes + off; }
   void* w_ptr(uint32_t r, uint32_t t) const { return arena + rec[r].p[t].w_off; }
   void* g_ptr(uint32_t r, uint32_t t) const { return arena + rec[r].p[t].g_off; }
+  // weights / gradients of a record's tensor as an op sees them: inside the op's streamed
+  // buffers when the record is streamed, in the fixed region otherwise
+  void* w_ptr(uint32_t r, uint32_t t, const void* w_base) const {
+    return rec[r].streamed ? (char*)w_base + rec[r].p[t].w_rel : arena + rec[r].p[t].w_off;
+  }
+  void* g_ptr(uint32_t r, uint32_t t, void* g_base) const {
+    return rec[r].streamed ? (char*)g_base + rec[r].p[t].g_rel : arena + rec[r].p[t].g_off;
+  }
 };
 
 #define KARMA_HIP(ctx, call)                                                                  \
@@ -119,6 +137,8 @@ struct LayerIO {
   void* ws = nullptr;        // workspace
   const void* dy = nullptr;  // gradient w.r.t. the output
   void* dx = nullptr;        // gradient w.r.t. the input (null for record 0)
+  const void* w = nullptr;   // streamed weights of the record (null when resident)
+  void* g = nullptr;         // buffer for the gradients of streamed weights (backward only)
 };
 
 // Model-specific pieces (layers_mlp.cpp, layers_gpt.cpp)

@@ -45,6 +45,7 @@ struct Builder {
   Ctx& c;
   std::vector<Released> gone;   // ranges of the arena that were freed, with the op that freed them
   std::vector<int64_t> x_at, s_at, dx_at, x_sz, s_sz, w_sz;
+  std::vector<int64_t> p_at, g_at, p_sz, g_sz;   // streamed weights and their gradients
   explicit Builder(Ctx& ctx) : c(ctx) {}
 
   // the new tenant of [off, off+size) must wait for whoever released any part of it
@@ -68,11 +69,16 @@ struct Builder {
   int run() {
     const uint32_t L = c.L;
     x_sz.assign(L + 2, 0); s_sz.assign(L, 0); w_sz.assign(L, 0);
+    p_sz.assign(L, 0); g_sz.assign(L, 0);
     for (uint32_t i = 0; i < L; ++i) {
       x_sz[i + 1] = (int64_t)up256(c.cost[i].out_bytes);
       s_sz[i] = (int64_t)up256(c.cost[i].sav_bytes);
       w_sz[i] = (int64_t)up256(c.cost[i].ws_bytes);
+      p_sz[i] = (int64_t)up256(c.cost[i].w_bytes);
+      g_sz[i] = c.cost[i].w_bytes ? (int64_t)up256(c.cost[i].g_bytes) : 0;
     }
+    p_at.assign(L, -1); g_at.assign(L, -1);
+    std::vector<int64_t> win_op(L, -1), b_op(L, -1);
     const int64_t lw_sz = (int64_t)up256(c.loss_cost.ws_bytes);
     x_at.assign(L + 2, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
     std::vector<int64_t> f_op(L, -1), in_op(L, -1), out_op(L, -1);
@@ -96,6 +102,11 @@ struct Builder {
           x_at[i + 1] = p.out; s_at[i] = p.s;
           f_op[i] = k;
           { int64_t w = p.ws; release(w, w_sz[i], k); }
+          if (p_sz[i]) {
+            p.w = p_at[i];
+            p.waits.push_back((uint32_t)win_op[i]);
+            if (!c.keepw[i]) release(p_at[i], p_sz[i], k);
+          }
           if (a == KARMA_RC_KEEP || a == KARMA_RC_CHAIN) release(s_at[i], s_sz[i], k);
           if (a == KARMA_RC_CHAIN) release(x_at[i], x_sz[i], k);
           if (a == KARMA_RC_SWAP) release(s_at[i], s_sz[i], k);
@@ -127,6 +138,20 @@ struct Builder {
           if (a == KARMA_SWAP) s_at[i] = p.s;
           in_op[i] = k;
           break;
+        case 'W':
+          p.stream = 1;
+          p.w = o.off[0];
+          claim(p, p.w, p_sz[i]);
+          p_at[i] = p.w;
+          win_op[i] = k;
+          break;
+        case 'G':
+          p.stream = 2;
+          p.g = g_at[i];
+          p.waits.push_back((uint32_t)b_op[i]);
+          release(g_at[i], g_sz[i], k);
+          p.record = true;   // the host update waits for it
+          break;
         case 'L':
           p.stream = 0;
           p.x = x_at[L]; p.dx = o.off[0]; p.ws = o.off[1];
@@ -145,6 +170,10 @@ struct Builder {
           if (p.out >= 0) x_at[i + 1] = p.out;
           if (in_op[i] >= 0) p.waits.push_back((uint32_t)in_op[i]);
           { int64_t w = p.ws; release(w, w_sz[i], k); }
+          if (p_sz[i]) {
+            p.w = p_at[i];
+            p.waits.push_back((uint32_t)win_op[i]);
+          }
           break;
         case 'B':
           p.stream = 0;
@@ -157,6 +186,15 @@ struct Builder {
           release(dx_at[i + 1], x_sz[i + 1], k);
           release(s_at[i], s_sz[i], k);
           if (i) release(x_at[i], x_sz[i], k);
+          if (p_sz[i]) {
+            p.w = p_at[i];
+            p.waits.push_back((uint32_t)win_op[i]);
+            release(p_at[i], p_sz[i], k);
+            p.g = o.off[2];
+            claim(p, p.g, g_sz[i]);
+            g_at[i] = p.g;
+            b_op[i] = k;
+          }
           p.record = true;
           break;
         default:
@@ -179,15 +217,16 @@ struct Builder {
   }
 };
 
-int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions) {
+int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions, const std::vector<uint8_t>& keepw) {
   if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
   Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
   std::vector<karma_op> ops;
   karma_plan_summary s;
   if (!actions_valid(actions.data(), c->L)) return fail(c, KARMA_E_INVAL, "invalid action vector");
-  if (!simulate(P, actions.data(), &s, &ops)) return fail(c, KARMA_E_BUDGET, "assignment does not fit the budget");
+  if (!simulate(P, actions.data(), keepw.data(), &s, &ops)) return fail(c, KARMA_E_BUDGET, "assignment does not fit the budget");
   free_plan_resources(c);
   c->actions = actions;
+  c->keepw = keepw;
   c->ops = ops;
   c->summary = s;
   c->budget = budget;
@@ -218,6 +257,8 @@ int issue(Ctx* c, const ProgOp& p) {
   io.ws = c->act_ptr(p.ws);
   io.dy = c->act_ptr(p.dy);
   io.dx = c->act_ptr(p.dx);
+  io.w = c->act_ptr(p.w);
+  io.g = c->act_ptr(p.g);
   switch (p.kind) {
     case 'F':
     case 'R': return layer_forward(*c, p.layer, io, s);
@@ -230,6 +271,12 @@ int issue(Ctx* c, const ProgOp& p) {
     case 'I':
       if (p.x_bytes) KARMA_HIP(c, hipMemcpyAsync(c->act_ptr(p.x), c->swap_pool + p.host_x, p.x_bytes, hipMemcpyHostToDevice, s));
       if (p.s_bytes) KARMA_HIP(c, hipMemcpyAsync(c->act_ptr(p.s), c->swap_pool + p.host_s, p.s_bytes, hipMemcpyHostToDevice, s));
+      return KARMA_OK;
+    case 'W':
+      KARMA_HIP(c, hipMemcpyAsync(c->act_ptr(p.w), c->rec[p.layer].stage_w_all, c->rec[p.layer].w_total, hipMemcpyHostToDevice, s));
+      return KARMA_OK;
+    case 'G':
+      KARMA_HIP(c, hipMemcpyAsync(c->rec[p.layer].stage_g_all, c->act_ptr(p.g), c->rec[p.layer].g_total, hipMemcpyDeviceToHost, s));
       return KARMA_OK;
   }
   return KARMA_E_INVAL;
@@ -252,14 +299,18 @@ int send_grads(Ctx* c, uint32_t r, hipEvent_t after) {
 
 // host update of one record's master weights, chunk by chunk as the gradients land; each
 // chunk's new device weights go back at once
-int update_record(Ctx* c, uint32_t r) {
+int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed) {
   const karma_config& g = c->cfg;
   const uint64_t step = c->step_no;
+  const bool streamed = c->rec[r].streamed;
+  // streamed records: the whole gradient buffer arrives with one copy of the program, and
+  // the new weights stay in pinned memory for the next step's copy-in
+  if (streamed) KARMA_HIP(c, hipEventSynchronize(grads_landed));
   for (Param& p : c->rec[r].p) {
     const uint64_t gs = p.grad_bf16 ? 2 : 4, ws = p.dev_bf16 ? 2 : 4;
     for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
       const uint64_t base = k * PARAM_CHUNK, n = std::min(PARAM_CHUNK, p.n - base);
-      KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
+      if (!streamed) KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
       double t0 = now_ms();
       c->pool->parallel_for(n, [&](size_t lo, size_t hi) {
         const char* gp = (const char*)p.stage_g + (base + lo) * gs;
@@ -271,8 +322,9 @@ int update_record(Ctx* c, uint32_t r) {
           sgd_update(p.master.data() + base + lo, gp, p.grad_bf16, hi - lo, g.lr, wp, p.dev_bf16);
       });
       c->stats.host_opt_ms += now_ms() - t0;
-      KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off + base * ws, (char*)p.stage_w + base * ws, n * ws,
-                                  hipMemcpyHostToDevice, c->st[1]));
+      if (!streamed)
+        KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off + base * ws, (char*)p.stage_w + base * ws, n * ws,
+                                    hipMemcpyHostToDevice, c->st[1]));
     }
   }
   return KARMA_OK;
@@ -292,7 +344,7 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
   KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->in_off), c->stage_in, c->in_bytes, hipMemcpyHostToDevice, sc));
   KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->lab_off), c->stage_lab, c->lab_bytes, hipMemcpyHostToDevice, sc));
   if (apply) ++c->step_no;
-  std::vector<uint32_t> done_order;
+  std::vector<std::pair<uint32_t, hipEvent_t>> done_order;   // record, event after which its gradients are on the host
   for (size_t k = 0; k < c->prog.size(); ++k) {
     const ProgOp& p = c->prog[k];
     hipStream_t s = c->st[p.stream];
@@ -311,16 +363,17 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
       uint32_t r = p.kind == 'L' ? c->L : p.layer;
       // gradients of a record are complete after its backward; a tied tensor that several
       // records add to is owned by the record that finishes last
-      if (!c->rec[r].p.empty()) {
+      if (!c->rec[r].p.empty() && !c->rec[r].streamed) {
         st = send_grads(c, r, c->ev[k]);
         if (st) return st;
-        done_order.push_back(r);
+        done_order.push_back({r, nullptr});
       }
     }
+    if (apply && p.kind == 'G') done_order.push_back({p.layer, c->ev[k]});
   }
   KARMA_HIP(c, hipMemcpyAsync(c->stage_loss, c->fixed_ptr(c->loss_off), sizeof(float), hipMemcpyDeviceToHost, sc));
-  for (uint32_t r : done_order) {
-    st = update_record(c, r);
+  for (const auto& d : done_order) {
+    st = update_record(c, d.first, d.second);
     if (st) return st;
   }
   for (int k = 0; k < 3; ++k) KARMA_HIP(c, hipStreamSynchronize(c->st[k]));
@@ -385,11 +438,19 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   c->L = (uint32_t)c->rec.size() - 1;
   // fixed-region layout: weights, gradients, inputs, labels, loss, misc
   uint64_t off = 0;
-  for (Record& r : c->rec)
+  for (Record& r : c->rec) {
+    if (r.streamed) {
+      for (Param& p : r.p) {
+        p.w_rel = r.w_total; r.w_total += up256(p.w_bytes());
+        p.g_rel = r.g_total; r.g_total += up256(p.g_bytes());
+      }
+      continue;
+    }
     for (Param& p : r.p) {
       p.w_off = off; off += up256(p.w_bytes());
       p.g_off = off; off += up256(p.g_bytes());
     }
+  }
   c->in_off = off; off += up256(c->in_bytes);
   c->lab_off = off; off += up256(c->lab_bytes);
   c->loss_off = off; off += 256;
@@ -398,7 +459,8 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   if (off >= arena_bytes) { delete c; return KARMA_E_OOM; }
   c->cost.resize(c->L);
   for (uint32_t i = 0; i < c->L; ++i)
-    c->cost[i] = karma_layer_cost{0, 0, 0, c->rec[i].sav_bytes, c->rec[i].out_bytes, c->rec[i].ws_bytes};
+    c->cost[i] = karma_layer_cost{0, 0, 0, c->rec[i].sav_bytes, c->rec[i].out_bytes, c->rec[i].ws_bytes,
+                                  c->rec[i].streamed ? c->rec[i].w_total : 0, c->rec[i].streamed ? c->rec[i].g_total : 0};
   c->loss_cost = karma_loss_cost{0, c->rec[c->L].ws_bytes};
   c->link = karma_link{50000000000ull, 50000000000ull, 10000};
   // host state
@@ -411,13 +473,23 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
       ok = false;
     }
   };
-  for (Record& r : c->rec)
+  for (Record& r : c->rec) {
+    if (r.streamed) {
+      pin((void**)&r.stage_w_all, r.w_total);
+      pin((void**)&r.stage_g_all, r.g_total);
+      if (ok) { std::memset(r.stage_w_all, 0, r.w_total); std::memset(r.stage_g_all, 0, r.g_total); }
+    }
     for (Param& p : r.p) {
       p.master.assign(p.n, 0.f);
       if (cfg->optimizer == KARMA_OPT_ADAM) { p.m.assign(p.n, 0.f); p.v.assign(p.n, 0.f); }
-      pin(&p.stage_g, p.g_bytes());
-      pin(&p.stage_w, p.w_bytes());
+      if (r.streamed) {
+        if (ok) { p.stage_w = r.stage_w_all + p.w_rel; p.stage_g = r.stage_g_all + p.g_rel; }
+      } else {
+        pin(&p.stage_g, p.g_bytes());
+        pin(&p.stage_w, p.w_bytes());
+      }
     }
+  }
   pin(&c->stage_in, c->in_bytes);
   pin(&c->stage_lab, c->lab_bytes);
   pin((void**)&c->stage_loss, 256);
@@ -441,12 +513,15 @@ extern "C" void karma_destroy(karma_ctx* c) {
   if (!c) return;
   for (int k = 0; k < 3; ++k) if (c->st[k] || k == 0) (void)hipStreamSynchronize(c->st[k]);
   free_plan_resources(c);
-  for (Record& r : c->rec)
+  for (Record& r : c->rec) {
     for (Param& p : r.p) {
-      if (p.stage_g) (void)hipHostFree(p.stage_g);
-      if (p.stage_w) (void)hipHostFree(p.stage_w);
+      if (!r.streamed && p.stage_g) (void)hipHostFree(p.stage_g);
+      if (!r.streamed && p.stage_w) (void)hipHostFree(p.stage_w);
       for (auto e : p.chunk_ev) if (e) (void)hipEventDestroy(e);
     }
+    if (r.stage_w_all) (void)hipHostFree(r.stage_w_all);
+    if (r.stage_g_all) (void)hipHostFree(r.stage_g_all);
+  }
   if (c->stage_in) (void)hipHostFree(c->stage_in);
   if (c->stage_lab) (void)hipHostFree(c->stage_lab);
   if (c->stage_loss) (void)hipHostFree(c->stage_loss);
@@ -476,7 +551,7 @@ extern "C" int karma_set_param(karma_ctx* c, uint32_t layer, uint32_t t, const f
   std::memcpy(p.master.data(), host, n * sizeof(float));
   if (p.dev_bf16) for (uint64_t i = 0; i < n; ++i) ((uint16_t*)p.stage_w)[i] = f32_to_bf16_rne(host[i]);
   else std::memcpy(p.stage_w, host, n * sizeof(float));
-  KARMA_HIP(c, hipMemcpy(c->arena + p.w_off, p.stage_w, p.w_bytes(), hipMemcpyHostToDevice));
+  if (!c->rec[layer].streamed) KARMA_HIP(c, hipMemcpy(c->arena + p.w_off, p.stage_w, p.w_bytes(), hipMemcpyHostToDevice));
   return KARMA_OK;
 }
 
@@ -492,7 +567,8 @@ extern "C" int karma_get_grad(karma_ctx* c, uint32_t layer, uint32_t t, float* h
   if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
   Param& p = c->rec[layer].p[t];
   if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_get_grad: element count mismatch");
-  KARMA_HIP(c, hipMemcpy(p.stage_g, c->arena + p.g_off, p.g_bytes(), hipMemcpyDeviceToHost));
+  // gradients of streamed weights were copied out by the step itself
+  if (!c->rec[layer].streamed) KARMA_HIP(c, hipMemcpy(p.stage_g, c->arena + p.g_off, p.g_bytes(), hipMemcpyDeviceToHost));
   if (p.grad_bf16) for (uint64_t i = 0; i < n; ++i) host[i] = bf16_to_f32(((const uint16_t*)p.stage_g)[i]);
   else std::memcpy(host, p.stage_g, n * sizeof(float));
   return KARMA_OK;
@@ -524,24 +600,29 @@ extern "C" int karma_set_costs(karma_ctx* c, const karma_layer_cost* layers, con
   return KARMA_OK;
 }
 
-extern "C" int karma_plan(karma_ctx* c, uint64_t budget, uint8_t* actions_out, karma_plan_summary* summary_out) {
+extern "C" int karma_plan(karma_ctx* c, uint64_t budget, uint8_t* actions_out, uint8_t* weights_kept_out,
+                          karma_plan_summary* summary_out) {
   if (!c) return KARMA_E_INVAL;
   if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
   Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
-  std::vector<uint8_t> a;
+  std::vector<uint8_t> a, kw;
   karma_plan_summary s;
-  if (!plan(P, a, &s)) return fail(c, KARMA_E_BUDGET, "no assignment fits the budget");
-  int st = install_plan(c, budget, a);
+  if (!plan(P, a, kw, &s)) return fail(c, KARMA_E_BUDGET, "no assignment fits the budget");
+  int st = install_plan(c, budget, a, kw);
   if (st) return st;
   if (actions_out) std::memcpy(actions_out, a.data(), c->L);
+  if (weights_kept_out) std::memcpy(weights_kept_out, kw.data(), c->L);
   if (summary_out) *summary_out = c->summary;
   return KARMA_OK;
 }
 
-extern "C" int karma_set_plan(karma_ctx* c, uint64_t budget, const uint8_t* actions, karma_plan_summary* summary_out) {
+extern "C" int karma_set_plan(karma_ctx* c, uint64_t budget, const uint8_t* actions, const uint8_t* weights_kept,
+                              karma_plan_summary* summary_out) {
   if (!c || !actions) return KARMA_E_INVAL;
   std::vector<uint8_t> a(actions, actions + c->L);
-  int st = install_plan(c, budget, a);
+  std::vector<uint8_t> kw(c->L, 0);
+  if (weights_kept) kw.assign(weights_kept, weights_kept + c->L);
+  int st = install_plan(c, budget, a, kw);
   if (st) return st;
   if (summary_out) *summary_out = c->summary;
   return KARMA_OK;
@@ -591,8 +672,9 @@ extern "C" int karma_get_op_times(karma_ctx* c, karma_op* ops_out, float* ms_out
 extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) {
   if (!c) return KARMA_E_INVAL;
   if (!reps) reps = 3;
-  std::vector<uint8_t> keep(c->L, KARMA_KEEP);
-  int st = install_plan(c, c->arena_bytes, keep);
+  std::vector<uint8_t> keep(c->L, KARMA_KEEP), kw(c->L, 0);
+  for (uint32_t i = 0; i < c->L; ++i) kw[i] = c->rec[i].streamed ? 1 : 0;
+  int st = install_plan(c, c->arena_bytes, keep, kw);
   if (st) return st;
   // inputs: whatever the staging buffers hold (zeros on a fresh context are valid ids / values)
   std::vector<char> in(c->in_bytes ? c->in_bytes : 1, 0), lab(c->lab_bytes ? c->lab_bytes : 1, 0);

@@ -165,6 +165,7 @@ int gpt_build_records(Ctx& c) {
     r.out_bytes = act;
     r.sav_bytes = sv.total;
     r.ws_bytes = ws.total;
+    r.streamed = md.stream_weights != 0;
     c.rec.push_back(std::move(r));
   }
   Record loss;
@@ -234,7 +235,7 @@ int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   bf16_t* m = (bf16_t*)(S + sv.m);
   bf16_t* f1 = (bf16_t*)(S + sv.f1);
   bf16_t* g = (bf16_t*)(S + sv.g);
-  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t); };
+  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t, io.w); };
   TRY(layernorm_fwd(x, W(LN1_G), W(LN1_B), a, (float*)(S + sv.stats1), d.T, d.h, s));
   TRY(gemm(a, W(WQKV), qkv, W(BQKV), nullptr, d.T, 3 * d.h, d.h, true, true, false, false, s));
   TRY(attention_fwd(qkv, ctx, (float*)(S + sv.lse), d.B, d.S, d.H, d.D, s));
@@ -275,8 +276,8 @@ int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   bf16_t* dr1 = (bf16_t*)(Wk + wl.t2);
   bf16_t* da = (bf16_t*)(Wk + wl.t3);
   float* part = (float*)(Wk + wl.part);
-  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t); };
-  auto G = [&](int t) { return c.g_ptr(i, t); };
+  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t, io.w); };
+  auto G = [&](int t) { return c.g_ptr(i, t, io.g); };
 
   // FC2: y = r1 + g W2^T + b2
   TRY(gemm(dy, W(W2), wide, nullptr, nullptr, d.T, d.ffn, d.h, true, false, false, false, s));     // dg = dy W2

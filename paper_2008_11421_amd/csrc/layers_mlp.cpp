@@ -21,6 +21,7 @@ int mlp_build_records(Ctx& c) {
     r.out_bytes = act;
     r.sav_bytes = act;   // z
     r.ws_bytes = act;    // dz in backward
+    r.streamed = d.stream_weights != 0;
     c.rec.push_back(std::move(r));
   }
   Record loss;
@@ -45,15 +46,15 @@ int mlp_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   const int m = (int)c.desc.batch, n = (int)c.desc.width;
   // a recompute whose output is not needed still writes y somewhere: the workspace
   float* y = io.out ? (float*)io.out : (float*)io.ws;
-  return linear_relu_fwd_f32((const float*)io.x, (const float*)c.w_ptr(i, 0), (const float*)c.w_ptr(i, 1),
+  return linear_relu_fwd_f32((const float*)io.x, (const float*)c.w_ptr(i, 0, io.w), (const float*)c.w_ptr(i, 1, io.w),
                              (float*)io.sav, y, m, n, n, s);
 }
 
 int mlp_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   const int m = (int)c.desc.batch, n = (int)c.desc.width;
-  return linear_relu_bwd_f32((const float*)io.x, (const float*)c.w_ptr(i, 0), (const float*)io.sav,
-                             (const float*)io.dy, (float*)io.ws, (float*)io.dx, (float*)c.g_ptr(i, 0),
-                             (float*)c.g_ptr(i, 1), m, n, n, s);
+  return linear_relu_bwd_f32((const float*)io.x, (const float*)c.w_ptr(i, 0, io.w), (const float*)io.sav,
+                             (const float*)io.dy, (float*)io.ws, (float*)io.dx, (float*)c.g_ptr(i, 0, io.g),
+                             (float*)c.g_ptr(i, 1, io.g), m, n, n, s);
 }
 
 int mlp_loss(Ctx& c, const LayerIO& io, hipStream_t s) {

@@ -92,21 +92,29 @@ namespace {
 struct Timeline {
   const Problem& P;
   const uint8_t* act;
+  const uint8_t* keepw;                           // per layer: streamed weights stay from F_i to B_i (null = none do)
   std::vector<karma_op>* ops;
   uint32_t L;
   Arena arena;
   std::vector<int64_t> x_raw, x_sz, s_sz, w_sz;   // bytes of x_i (raw / aligned), internals, workspace
+  std::vector<int64_t> p_sz, g_sz;               // streamed weights and their gradients (0 = resident)
   std::vector<int64_t> x_at, s_at, dx_at;        // current offsets, -1 = not allocated
+  std::vector<int64_t> p_at, g_at, p_here;       // weight / gradient buffers; arrival of the weights
   struct Pending { int64_t when; int64_t off[2], size[2]; int n; };
-  std::deque<Pending> outgoing;                   // frees that happen when a swap-out ends
-  std::deque<uint32_t> wanted;                    // layers still to prefetch, in order of need
-  std::vector<int64_t> arrival;                   // end of the swap-in of layer i, -1 = not issued
+  std::deque<Pending> outgoing;                   // frees that happen when a device-to-host copy ends
+  // copies still to prefetch during backward, in order of need: the swapped tensors of a
+  // layer, or the weights of a layer that did not keep them
+  struct Want { bool weights; uint32_t layer; };
+  std::deque<Want> wanted;
+  std::vector<int64_t> arrival, w_arrival;        // end of that copy, -1 = not issued
   std::vector<int64_t> left;                      // end of the swap-out of layer i
   int64_t t_comp = 0, t_out = 0, t_in = 0, busy = 0, redo = 0;
   uint64_t moved_out = 0, moved_in = 0;
   bool failed = false;
 
-  Timeline(const Problem& p, const uint8_t* a, std::vector<karma_op>* o) : P(p), act(a), ops(o), L(p.n) {}
+  Timeline(const Problem& p, const uint8_t* a, const uint8_t* kw, std::vector<karma_op>* o)
+      : P(p), act(a), keepw(kw), ops(o), L(p.n) {}
+  bool keeps(uint32_t i) const { return keepw && keepw[i]; }
 
   void emit(uint8_t kind, uint32_t layer, int64_t s, int64_t e, int64_t a0, int64_t a1, int64_t a2) {
     if (ops) ops->push_back(karma_op{kind, layer, s, e, {a0, a1, a2}});
@@ -137,7 +145,21 @@ struct Timeline {
   bool swapped_whole(uint32_t i) const { return act[i] == KARMA_SWAP; }
   int64_t move_bytes(uint32_t i) const { return x_raw[i] + (swapped_whole(i) ? (int64_t)P.layers[i].sav_bytes : 0); }
 
-  void start_prefetch(uint32_t i, int64_t now) {
+  // copy of layer i's weights into p_at[i] (already allocated)
+  void fetch_weights(uint32_t i, int64_t now) {
+    int64_t s = std::max(t_in, now);
+    t_in = s + copy_ns(P.layers[i].w_bytes, P.link.bw_h2d, P.link.lat_ns);
+    moved_in += P.layers[i].w_bytes;
+    p_here[i] = t_in;
+    emit('W', i, s, t_in, p_at[i], -1, -1);
+  }
+  void start_prefetch(const Want& it, int64_t now) {
+    const uint32_t i = it.layer;
+    if (it.weights) {
+      fetch_weights(i, now);
+      w_arrival[i] = t_in;
+      return;
+    }
     int64_t nbytes = move_bytes(i);
     int64_t s = std::max(std::max(t_in, now), left[i]);   // data must have reached the host first
     t_in = s + copy_ns((uint64_t)nbytes, P.link.bw_h2d, P.link.lat_ns);
@@ -148,44 +170,72 @@ struct Timeline {
   void prefetch_ahead(int64_t now, int64_t reserve) {
     settle(now);
     while (!wanted.empty()) {
-      uint32_t i = wanted.front();
-      int64_t need = x_sz[i] + (swapped_whole(i) ? s_sz[i] : 0);
+      const Want it = wanted.front();
+      const uint32_t i = it.layer;
+      int64_t need = it.weights ? p_sz[i] : x_sz[i] + (swapped_whole(i) ? s_sz[i] : 0);
       if (arena.cap - arena.used < need + reserve) break;
-      int64_t xa = -1, sa = -1;
-      if (x_sz[i]) { xa = arena.take(x_sz[i], true); if (xa < 0) break; }
-      if (swapped_whole(i) && s_sz[i]) {
-        sa = arena.take(s_sz[i], true);
-        if (sa < 0) { if (xa >= 0) arena.give(xa, x_sz[i]); break; }
+      if (it.weights) {
+        int64_t pa = arena.take(p_sz[i], true);
+        if (pa < 0) break;
+        p_at[i] = pa;
+      } else {
+        int64_t xa = -1, sa = -1;
+        if (x_sz[i]) { xa = arena.take(x_sz[i], true); if (xa < 0) break; }
+        if (swapped_whole(i) && s_sz[i]) {
+          sa = arena.take(s_sz[i], true);
+          if (sa < 0) { if (xa >= 0) arena.give(xa, x_sz[i]); break; }
+        }
+        x_at[i] = xa;
+        if (swapped_whole(i)) s_at[i] = sa;
       }
-      x_at[i] = xa;
-      if (swapped_whole(i)) s_at[i] = sa;
       wanted.pop_front();
-      start_prefetch(i, now);
+      start_prefetch(it, now);
     }
   }
-  int64_t prefetch_now(uint32_t i, int64_t now) {
-    while (arrival[i] < 0 && !failed) {
-      uint32_t j = wanted.front();
+  // the copy `it` is needed now: admit everything up to and including it, then wait for it
+  int64_t need_now(const Want& it, int64_t now) {
+    std::vector<int64_t>& arr = it.weights ? w_arrival : arrival;
+    bool queued = false;
+    for (const Want& q : wanted) queued |= (q.weights == it.weights && q.layer == it.layer);
+    if (arr[it.layer] < 0 && !queued) return now;
+    while (arr[it.layer] < 0 && !failed) {
+      const Want j = wanted.front();
       wanted.pop_front();
-      x_at[j] = obtain(x_sz[j], true, now);
-      if (swapped_whole(j)) s_at[j] = obtain(s_sz[j], true, now);
+      if (j.weights) {
+        p_at[j.layer] = obtain(p_sz[j.layer], true, now);
+      } else {
+        x_at[j.layer] = obtain(x_sz[j.layer], true, now);
+        if (swapped_whole(j.layer)) s_at[j.layer] = obtain(s_sz[j.layer], true, now);
+      }
       if (!failed) start_prefetch(j, now);
     }
-    return now;
+    if (failed) return now;
+    return std::max(now, arr[it.layer]);
   }
   void backward(uint32_t j, int64_t now, int64_t reserve) {
     settle(now);
     dx_at[j] = obtain(x_sz[j], false, now);
     int64_t w = obtain(w_sz[j], false, now);
+    g_at[j] = obtain(g_sz[j], false, now);
     if (failed) return;
     int64_t end = now + P.layers[j].tb_ns;
     busy += P.layers[j].tb_ns;
-    emit('B', j, now, end, dx_at[j], w, -1);
+    emit('B', j, now, end, dx_at[j], w, g_at[j]);
     t_comp = end;
     drop(w, w_sz[j]);
     drop(dx_at[j + 1], x_sz[j + 1]);
     drop(s_at[j], s_sz[j]);
     drop(x_at[j], x_sz[j]);
+    if (p_sz[j]) drop(p_at[j], p_sz[j]);
+    if (g_sz[j]) {
+      // the gradients leave right after the layer's backward (pipeline stage 3)
+      int64_t s = std::max(t_out, end);
+      t_out = s + copy_ns(P.layers[j].g_bytes, P.link.bw_d2h, P.link.lat_ns);
+      moved_out += P.layers[j].g_bytes;
+      outgoing.push_back(Pending{t_out, {g_at[j], 0}, {g_sz[j], 0}, 1});
+      g_at[j] = -1;
+      emit('G', j, s, t_out, -1, -1, -1);
+    }
     prefetch_ahead(t_comp, reserve);
   }
 
@@ -194,30 +244,47 @@ struct Timeline {
     if (cap <= 0) return false;
     arena.reset(cap);
     x_raw.assign(L + 1, 0); x_sz.assign(L + 1, 0); s_sz.assign(L, 0); w_sz.assign(L, 0);
+    p_sz.assign(L, 0); g_sz.assign(L, 0);
     for (uint32_t i = 0; i < L; ++i) {
       x_raw[i + 1] = (int64_t)P.layers[i].out_bytes;
       x_sz[i + 1] = align_up(x_raw[i + 1]);
       s_sz[i] = align_up((int64_t)P.layers[i].sav_bytes);
       w_sz[i] = align_up((int64_t)P.layers[i].ws_bytes);
+      p_sz[i] = align_up((int64_t)P.layers[i].w_bytes);
+      g_sz[i] = P.layers[i].w_bytes ? align_up((int64_t)P.layers[i].g_bytes) : 0;
     }
     x_at.assign(L + 1, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
+    p_at.assign(L, -1); g_at.assign(L, -1); p_here.assign(L, 0);
     x_sz.push_back(0);  // x_sz[L+1] so that backward(L-1...) can index j+1 == L safely
     arrival.assign(L, -1);
+    w_arrival.assign(L, -1);
     left.assign(L, 0);
 
     // forward
     for (uint32_t i = 0; i < L && !failed; ++i) {
       int64_t now = t_comp;
       settle(now);
+      if (p_sz[i] && p_at[i] < 0) {   // not prefetched: fetched now, the layer waits
+        p_at[i] = obtain(p_sz[i], keeps(i), now);
+        if (failed) break;
+        fetch_weights(i, now);
+      }
       x_at[i + 1] = obtain(x_sz[i + 1], true, now);
       s_at[i] = obtain(s_sz[i], true, now);
       int64_t w = obtain(w_sz[i], false, now);
       if (failed) break;
+      if (p_sz[i]) now = std::max(now, p_here[i]);
+      // the next layer's weights start their trip when this layer starts computing
+      if (i + 1 < L && p_sz[i + 1]) {
+        p_at[i + 1] = arena.take(p_sz[i + 1], keeps(i + 1));
+        if (p_at[i + 1] >= 0) fetch_weights(i + 1, now);
+      }
       int64_t end = now + P.layers[i].tf_ns;
       busy += P.layers[i].tf_ns;
       emit('F', i, now, end, x_at[i + 1], s_at[i], w);
       t_comp = end;
       drop(w, w_sz[i]);
+      if (p_sz[i] && !keeps(i)) drop(p_at[i], p_sz[i]);
       switch (act[i]) {
         case KARMA_SWAP:
         case KARMA_RC_SWAP: {
@@ -254,13 +321,13 @@ struct Timeline {
       while (act[h] == KARMA_RC_CHAIN) --h;
       Unit u{(uint32_t)h, (uint32_t)i, 0, 0};
       if (act[h] <= KARMA_SWAP) {
-        u.need = x_sz[h] + w_sz[h];
+        u.need = x_sz[h] + w_sz[h] + g_sz[h];
       } else {
         int64_t held = 0, top = 0;
         for (int64_t j = h; j <= i; ++j) {
           held += s_sz[j];
           if (j < i) held += x_sz[j + 1];
-          top = std::max(top, x_sz[j] + w_sz[j]);
+          top = std::max(top, x_sz[j] + w_sz[j] + g_sz[j]);
         }
         u.need = held + top;
         u.inner = top;
@@ -272,9 +339,13 @@ struct Timeline {
     for (size_t k = units.size(); k-- > 1;) after[k - 1] = std::max(after[k], units[k].need);
     int64_t any = 0;
     for (const Unit& u : units) any = std::max(any, u.need);
-    for (int64_t i = (int64_t)L - 1; i >= 0; --i)
-      if ((act[i] == KARMA_SWAP && move_bytes(i) > 0) || (act[i] == KARMA_RC_SWAP && x_raw[i] > 0))
-        wanted.push_back((uint32_t)i);
+    for (const Unit& u : units) {
+      const uint32_t h = u.head;
+      if ((act[h] == KARMA_SWAP && move_bytes(h) > 0) || (act[h] == KARMA_RC_SWAP && x_raw[h] > 0))
+        wanted.push_back(Want{false, h});
+      for (uint32_t j = h; j <= u.tail; ++j)
+        if (p_sz[j] && !keeps(j)) wanted.push_back(Want{true, j});
+    }
 
     // loss
     int64_t lw_sz = align_up((int64_t)P.loss.ws_bytes);
@@ -298,17 +369,19 @@ struct Timeline {
       const Unit& u = units[k];
       uint8_t a = act[u.head];
       int64_t now = t_comp;
-      bool moved = (a == KARMA_SWAP && move_bytes(u.head) > 0) || (a == KARMA_RC_SWAP && x_raw[u.head] > 0);
-      if (moved) {
-        now = prefetch_now(u.head, now);
+      if (a == KARMA_SWAP || a == KARMA_RC_SWAP) {
+        now = need_now(Want{false, u.head}, now);
         if (failed) break;
-        now = std::max(now, arrival[u.head]);
       }
       if (a <= KARMA_SWAP) {
+        now = need_now(Want{true, u.head}, now);
+        if (failed) break;
         backward(u.head, now, after[k]);
         continue;
       }
       for (uint32_t j = u.head; j <= u.tail && !failed; ++j) {
+        now = need_now(Want{true, j}, now);
+        if (failed) break;
         settle(now);
         s_at[j] = obtain(s_sz[j], true, now);
         if (j < u.tail) x_at[j + 1] = obtain(x_sz[j + 1], true, now);
@@ -350,10 +423,10 @@ struct Cost {
   bool operator==(const Cost& o) const { return makespan == o.makespan && moved == o.moved && redo == o.redo; }
 };
 
-bool evaluate(const Problem& P, const std::vector<uint8_t>& a, Cost& c) {
+bool evaluate(const Problem& P, const std::vector<uint8_t>& a, Cost& c, const uint8_t* keepw = nullptr) {
   karma_plan_summary s;
   if (!actions_valid(a.data(), P.n)) return false;
-  Timeline tl(P, a.data(), nullptr);
+  Timeline tl(P, a.data(), keepw, nullptr);
   if (!tl.run(&s)) return false;
   c = Cost{s.makespan_ns, s.bytes_d2h + s.bytes_h2d, s.recompute_ns};
   return true;
@@ -396,16 +469,21 @@ void improve(const Problem& P, Incumbent& inc) {
 
 }  // namespace
 
-bool simulate(const Problem& P, const uint8_t* actions, karma_plan_summary* out, std::vector<karma_op>* ops) {
-  Timeline tl(P, actions, ops);
+bool simulate(const Problem& P, const uint8_t* actions, const uint8_t* keepw, karma_plan_summary* out,
+              std::vector<karma_op>* ops) {
+  Timeline tl(P, actions, keepw, ops);
   return tl.run(out);
 }
 
-bool plan(const Problem& P, std::vector<uint8_t>& actions, karma_plan_summary* out) {
+bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>& keepw, karma_plan_summary* out) {
   const uint32_t L = P.n;
   Cost c;
   actions.assign(L, KARMA_KEEP);
-  if (evaluate(P, actions, c)) return simulate(P, actions.data(), out, nullptr);   // everything fits
+  keepw.assign(L, 0);
+  for (uint32_t i = 0; i < L; ++i) keepw[i] = P.layers[i].w_bytes ? 1 : 0;
+  if (evaluate(P, actions, c, keepw.data())) return simulate(P, actions.data(), keepw.data(), out, nullptr);   // everything fits
+  const std::vector<uint8_t> streamed = keepw;
+  keepw.assign(L, 0);
 
   // capacity rule: the longest resident tail for a given treatment of the prefix
   auto longest_tail = [&](uint8_t fill, std::vector<uint8_t>& res) {
@@ -452,7 +530,20 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, karma_plan_summary* o
   }
   if (!have) return false;
   actions = best.act;
-  return simulate(P, actions.data(), out, nullptr);
+  // the tail of the model keeps its streamed weights between forward and backward for as
+  // long as that fits and does not lengthen the step; the first layer that cannot ends the scan
+  Cost cost = best.cost;
+  for (int64_t i = (int64_t)L - 1; i >= 0; --i) {
+    if (!streamed[i]) continue;
+    keepw[i] = 1;
+    if (evaluate(P, actions, c, keepw.data()) && c < cost) {
+      cost = c;
+    } else {
+      keepw[i] = 0;
+      break;
+    }
+  }
+  return simulate(P, actions.data(), keepw.data(), out, nullptr);
 }
 
 // Algorithm 1's notation.  A copy is printed on the stage that is running when the copy
@@ -467,14 +558,16 @@ std::string stage_string(const karma_op* ops, uint32_t n) {
     text[s] = std::string(o.kind == 'B' ? "B" : "F") + std::to_string(o.layer + 1);
   }
   for (uint32_t k = 0; k < n; ++k) {
-    if (ops[k].kind != 'I' && ops[k].kind != 'O') continue;
+    const uint8_t kd = ops[k].kind;
+    if (kd != 'I' && kd != 'O' && kd != 'W' && kd != 'G') continue;
     if (stages.empty()) break;
     size_t at = stages.size() - 1;
     for (size_t s = 0; s < stages.size(); ++s) {
       const karma_op& o = ops[stages[s]];
       if (o.kind != 'R' && o.end_ns > ops[k].start_ns) { at = s; break; }
     }
-    text[at] += "||S" + std::to_string(ops[k].layer + 1) + (ops[k].kind == 'I' ? "^in" : "^out");
+    text[at] += std::string("||") + (kd == 'W' ? "W" : kd == 'G' ? "G" : "S") + std::to_string(ops[k].layer + 1) +
+                ((kd == 'I' || kd == 'W') ? "^in" : "^out");
   }
   std::string res;
   for (size_t s = 0; s < text.size(); ++s) { if (s) res += " -> "; res += text[s]; }

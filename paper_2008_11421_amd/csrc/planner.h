@@ -29,8 +29,10 @@ struct Arena {
 
 int64_t copy_ns(uint64_t bytes, uint64_t bw, int64_t lat);
 bool actions_valid(const uint8_t* a, uint32_t n);
-bool simulate(const Problem& P, const uint8_t* actions, karma_plan_summary* out, std::vector<karma_op>* ops);
-bool plan(const Problem& P, std::vector<uint8_t>& actions, karma_plan_summary* out);
+// keepw: per layer, streamed weights stay in HBM from F_i to B_i (null = no layer keeps them)
+bool simulate(const Problem& P, const uint8_t* actions, const uint8_t* keepw, karma_plan_summary* out,
+              std::vector<karma_op>* ops);
+bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>& keepw, karma_plan_summary* out);
 std::string stage_string(const karma_op* ops, uint32_t n);
 
 }  // namespace karma

@@ -7,7 +7,7 @@ from oracle import planner as P
 import synth_inputs as si
 from test_oracle_planner import cases, golden_schedule, mk, six_block_model
 
-KIND = {"F": "F", "B": "B", "R": "R", "L": "L", "OUT": "O", "IN": "I"}
+KIND = {"F": "F", "B": "B", "R": "R", "L": "L", "OUT": "O", "IN": "I", "WIN": "W", "GOUT": "G"}
 
 
 def ops_equal(lib_ops, ora_ops):
@@ -89,3 +89,38 @@ def test_fixed_region_and_errors():
     s1 = K.karma_simulate(layers, link, loss, 10**6 + 5000, 5000, [0] * 4)
     s0 = P.simulate([P.Layer(*l) for l in layers], P.Link(*link), 10**6 + 5000, 5000, P.Loss(*loss), [0] * 4)
     summaries_equal(s1, s0)
+
+
+def test_streamed_weights_bit_exact():
+    """Simulator and planner with streamed weights (Sec. III-G) against the oracle: random
+    action vectors times random weight choices, then whole plans."""
+    from test_oracle_weight_stream import with_weights
+    n = 0
+    for base, link, budget, loss in cases(7, seeds=(8,), fracs=(0.45, 0.9), bwmuls=(0.5, 3.0)):
+        layers = with_weights(base, 21, scale=2.0)
+        budget += 2 * max(P.al(l.wb) + P.al(l.gb) for l in layers)
+        bits = [int(v) for v in si.splitmix64(5, 64)]
+        for vi, v in enumerate(all_vectors(7, 3, 29)):
+            wres = [(bits[(vi + k) % 64] >> k) & 1 if layers[k].wb else 0 for k in range(7)]
+            try:
+                so = P.simulate(layers, link, budget, 0, loss, v, want_ops=True, wres=wres)
+            except P.Infeasible:
+                with pytest.raises(K.KarmaError) as e:
+                    K.karma_simulate(layers, link, loss, budget, 0, v, weights_kept=wres)
+                assert e.value.status == K.E_BUDGET
+                continue
+            sl, ops = K.karma_simulate(layers, link, loss, budget, 0, v, want_ops=True, weights_kept=wres)
+            summaries_equal(sl, so)
+            ops_equal(ops, so["ops"])
+            assert K.karma_stage_string(ops) == P.stage_string(so["ops"])
+            n += 1
+        try:
+            ao, so = P.plan(layers, link, budget, 0, loss)
+        except P.Infeasible:
+            with pytest.raises(K.KarmaError):
+                K.karma_plan_pure(layers, link, loss, budget, 0)
+            continue
+        al, sl = K.karma_plan_pure(layers, link, loss, budget, 0)
+        assert al == ao and sl["wres"] == so["wres"]
+        summaries_equal(sl, so)
+    assert n > 100
