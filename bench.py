@@ -74,8 +74,8 @@ def cpu_baseline(n_seq):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", type=int, default=1, choices=sorted(WORKLOADS))
     args = ap.parse_args()
@@ -176,6 +176,40 @@ def main():
     occupancy = st_prof["compute_busy_ms"] / st_prof["step_ms"] if st_prof["step_ms"] > 0 else None
     log("swap link achieved: %s GB/s; compute busy %.1f of %.1f ms" % (link_achieved, st_prof["compute_busy_ms"], st_prof["step_ms"]))
 
+    # The comparison policies of Fig. 2 through the same executor, kernels and budget:
+    # (a) eager swapping of every block, the last one included; (b) capacity-based swapping
+    # without recompute (longest resident tail, the prefix swapped); plain checkpointing
+    # every 5 blocks.  A few steps each: context for the planner's choice, not the metric.
+    L = len(acts)
+    candidates = {"eager_swap_all": [K.SWAP] * L,
+                  "checkpoint_every_5": [K.RC_KEEP if i % 5 == 0 else K.RC_CHAIN for i in range(L)]}
+    for k in range(1, L + 1):
+        cand = [K.SWAP] * k + [K.KEEP] * (L - k)
+        try:
+            ctx.karma_set_plan(BUDGET, cand)
+        except K.KarmaError:
+            continue
+        candidates["capacity_swap_no_recompute"] = cand
+        break
+    policies = {}
+    n_pol = max(2, min(5, args.steps))
+    for name, cand in candidates.items():
+        try:
+            sp = ctx.karma_set_plan(BUDGET, cand)
+        except K.KarmaError:
+            policies[name] = {"feasible": False}
+            continue
+        ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(n_pol):
+            ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+        torch.cuda.synchronize()
+        dtp = (time.perf_counter() - t1) / n_pol
+        policies[name] = {"feasible": True, "ms_per_step": dtp * 1e3, "samples_per_s": CFG["batch"] / dtp,
+                          "predicted_makespan_ms": sp["makespan_ns"] / 1e6, "planned_over_this": dtp / dt}
+        log("policy %s: %.1f ms/step (planned schedule is %.2fx faster)" % (name, dtp * 1e3, dtp / dt))
+
     n_l, ms_l, fl_l = gem
     achieved = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
     out = {
@@ -208,6 +242,7 @@ def main():
         "compute_occupancy_measured": occupancy,
         "compute_occupancy_predicted": summ["busy_ns"] / max(summ["busy_ns"] + summ["stall_ns"], 1),
         "host_opt_ms": st["host_opt_ms"],
+        "comparison_policies": policies,
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (all launches of the timed steps)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "launches_per_step": n_l / max(args.steps, 1), "avg_launch_ms": ms_l / max(n_l, 1),
