@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-policies", action="store_true", help="skip the comparison policies (profiling runs)")
     ap.add_argument("--config", type=int, default=1, choices=sorted(WORKLOADS))
     args = ap.parse_args()
     global CFG, BUDGET, ARENA, SEED
@@ -193,7 +194,7 @@ def main():
         break
     policies = {}
     n_pol = max(2, min(5, args.steps))
-    for name, cand in candidates.items():
+    for name, cand in ({} if args.no_policies else candidates).items():
         try:
             sp = ctx.karma_set_plan(BUDGET, cand)
         except K.KarmaError:
