@@ -311,6 +311,52 @@ int karma_k_attention_bwd_bf16(const void* qkv_dev, const void* ctx_dev, const v
                                float* delta_ws_dev, void* dqkv_dev, uint32_t batch, uint32_t seq, uint32_t heads,
                                uint32_t d, void* stream);
 
+/* ---- convolutional workload (Sec. III-C: convolution, batch normalisation, ReLU and
+ * pooling layers).  Tensors are NHWC bf16, convolution weights [c_out][r][s][c_in]; c_in and
+ * c_out must be multiples of 8 (an image with 3 channels is stored with 8, the rest zero).
+ * Output size per dimension: (in + 2*pad - kernel)/stride + 1.  KARMA_E_INVAL on bad shapes. */
+typedef struct {
+  uint32_t n, h, w, c_in, c_out, r, s, stride, pad;
+} karma_conv_shape;
+
+/* y[n][ho][wo][c_out] = sum over the r x s taps and c_in channels, padding counting as
+ * zero: the direct convolution of Sec. III-C computed as an implicit GEMM (no im2col). */
+int karma_k_conv2d_fwd_bf16(const void* x_dev, const void* w_dev, void* y_dev, const karma_conv_shape* shape, void* stream);
+/* dx_dev [n][h][w][c_in] (+ add_dev, same shape, may be NULL) from dy_dev [n][ho][wo][c_out].
+ * wt_ws_dev: r*s*c_in*c_out bf16 elements of workspace (transposed weights); may be NULL
+ * for a 1x1 stride-1 convolution. */
+int karma_k_conv2d_dgrad_bf16(const void* dy_dev, const void* w_dev, void* wt_ws_dev, const void* add_dev, void* dx_dev,
+                              const karma_conv_shape* shape, void* stream);
+/* dw_dev [c_out][r][s][c_in] bf16.  ws_dev/ws_bytes: optional fp32 workspace that lets the
+ * reduction over the pixels be split (up to 16 * c_out*r*s*c_in floats are used); results
+ * are reproducible either way. */
+int karma_k_conv2d_wgrad_bf16(const void* dy_dev, const void* x_dev, void* dw_dev, void* ws_dev, uint64_t ws_bytes,
+                              const karma_conv_shape* shape, void* stream);
+
+/* Training-mode batch normalisation of x_dev bf16 [rows][c] over its rows (rows = n*h*w):
+ * mean and biased variance per channel, eps 1e-5; y = xhat*gamma + beta (+ add_dev, may be
+ * NULL), then ReLU when relu != 0.  stats_dev fp32 [2][c] receives mean and 1/sqrt(var+eps);
+ * ws_dev: ceil(rows/256) * 2 * c floats.  c must be a multiple of 8. */
+int karma_k_batchnorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const void* beta_dev, const void* add_dev,
+                               void* y_dev, void* stats_dev, void* ws_dev, uint32_t rows, uint32_t c, uint32_t relu,
+                               void* stream);
+/* Its backward from the forward's x and stats.  relu != 0: dy first passes the ReLU that
+ * followed the normalisation (the mask is recomputed from xhat*gamma + beta > 0).
+ * dgamma_dev, dbeta_dev fp32 [c]; ws_dev as above. */
+int karma_k_batchnorm_bwd_bf16(const void* dy_dev, const void* x_dev, const void* stats_dev, const void* gamma_dev,
+                               const void* beta_dev, uint32_t relu, void* dx_dev, void* dgamma_dev, void* dbeta_dev,
+                               void* ws_dev, uint32_t rows, uint32_t c, void* stream);
+/* dz = dy where y > 0, else 0; n elements, multiple of 8. */
+int karma_k_relu_mask_bwd_bf16(const void* dy_dev, const void* y_dev, void* dz_dev, uint64_t n, void* stream);
+/* 3x3 max pooling, stride 2, padding 1 (Sec. III-C pooling layer); the backward gives the
+ * gradient of a window to its first maximum in row-major window order, without atomics. */
+int karma_k_maxpool_fwd_bf16(const void* x_dev, void* y_dev, uint32_t n, uint32_t h, uint32_t w, uint32_t c, void* stream);
+int karma_k_maxpool_bwd_bf16(const void* x_dev, const void* dy_dev, void* dx_dev, uint32_t n, uint32_t h, uint32_t w,
+                             uint32_t c, void* stream);
+/* Global average pooling over hw positions: x [n][hw][c] -> y [n][c], and its backward. */
+int karma_k_avgpool_fwd_bf16(const void* x_dev, void* y_dev, uint32_t n, uint32_t hw, uint32_t c, void* stream);
+int karma_k_avgpool_bwd_bf16(const void* dy_dev, void* dx_dev, uint32_t n, uint32_t hw, uint32_t c, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

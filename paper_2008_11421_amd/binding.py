@@ -54,6 +54,11 @@ class ModelDesc(C.Structure):
                 ("stream_weights", C.c_uint32)]
 
 
+class ConvShape(C.Structure):
+    _fields_ = [("n", C.c_uint32), ("h", C.c_uint32), ("w", C.c_uint32), ("c_in", C.c_uint32), ("c_out", C.c_uint32),
+                ("r", C.c_uint32), ("s", C.c_uint32), ("stride", C.c_uint32), ("pad", C.c_uint32)]
+
+
 class Config(C.Structure):
     _fields_ = [("optimizer", C.c_uint32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float), ("host_threads", C.c_uint32)]

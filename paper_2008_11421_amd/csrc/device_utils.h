@@ -97,6 +97,66 @@ struct TileMover {
     }
   }
 
+  // Element offset of (pixel p of the Ho x Wo grid, tap) in the gathered NHWC tensor, or -1
+  // where the convolution reads padding.
+  static __device__ __forceinline__ long conv_offset(const ConvGather& cg, int p, int tap) {
+    const int hw = cg.Ho * cg.Wo;
+    const int img = p / hw, rem = p - img * hw;
+    const int ho = rem / cg.Wo, wo = rem - ho * cg.Wo;
+    const int r = tap / cg.S, s = tap - r * cg.S;
+    int hi, wi;
+    if (!cg.transposed) {
+      hi = ho * cg.stride - cg.pad + r;
+      wi = wo * cg.stride - cg.pad + s;
+    } else {
+      const int th = ho + cg.pad - r, tw = wo + cg.pad - s;
+      if (th < 0 || tw < 0 || th % cg.stride || tw % cg.stride) return -1;
+      hi = th / cg.stride;
+      wi = tw / cg.stride;
+    }
+    if ((unsigned)hi >= (unsigned)cg.H || (unsigned)wi >= (unsigned)cg.W) return -1;
+    return ((long)(img * cg.H + hi) * cg.W + wi) * cg.C;
+  }
+
+  // k-contiguous operand gathered through a convolution: row = output pixel, k = (tap, channel)
+  __device__ __forceinline__ void load_conv(const bf16_t* __restrict__ G, const ConvGather& cg, int row0, int k0,
+                                            int rows_total, int k_total, int tid) {
+    static_assert(KC || VECS % 4 == 0, "");
+    if (KC) {
+#pragma unroll
+      for (int i = 0; i < VECS; ++i) {
+        int v = tid + i * T, row = v / (BK / 8), kc = v % (BK / 8);
+        int gr = row0 + row, gk = k0 + kc * 8;
+        u32x4 z = {0, 0, 0, 0};
+        reg[i] = z;
+        if (gr < rows_total && gk < k_total) {
+          const int tap = gk / cg.C, c = gk - tap * cg.C;
+          const long at = conv_offset(cg, gr, tap);
+          if (at >= 0) reg[i] = *(const u32x4*)(G + at + c);
+        }
+      }
+    } else {
+      // strided operand: row index n = (tap, channel), k = output pixel
+#pragma unroll
+      for (int b = 0; b < VECS / 4; ++b) {
+        int v = tid + b * T, rg = v % (ROWS / 4), kg = v / (ROWS / 4);
+        int gr = row0 + rg * 4;
+        const int tap = gr / cg.C, c = gr - tap * cg.C;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          int gk = k0 + kg * 8 + q;
+          u32x2 r = {0, 0};
+          if (gr < rows_total && gk < k_total) {
+            const long at = conv_offset(cg, gk, tap);
+            if (at >= 0) r = *(const u32x2*)(G + at + c);
+          }
+          reg[b * 4 + q / 2][(q & 1) * 2] = r.x;
+          reg[b * 4 + q / 2][(q & 1) * 2 + 1] = r.y;
+        }
+      }
+    }
+  }
+
   __device__ __forceinline__ void store(bf16_t* __restrict__ S, int tid) const {
     if (KC) {
 #pragma unroll

@@ -78,12 +78,15 @@ struct GemmEpilogue {
 // k-tile's global loads are issued at the top and parked in LDS half way through), and the
 // results leave through a per-wavefront LDS strip so that stores are row-contiguous.  The
 // stores are not waited for: they drain while the next item computes.
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
+// CONV 1: A is an NHWC tensor gathered through a convolution (rows = output pixels, forward
+// and input-gradient passes); CONV 2: B is (reduction index = output pixels, weight gradient).
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                    const bf16_t* __restrict__ B, int M, int N, int K,
                                                                    int lda, int ldb, int tiles_m, int tiles_n,
                                                                    int splits, int k_per_split, GemmEpilogue ep,
-                                                                   float* __restrict__ partial) {
+                                                                   float* __restrict__ partial, ConvGather cg) {
+  static_assert(CONV == 0 || (CONV == 1 && A_KC) || (CONV == 2 && !B_KC), "which operand a convolution gathers");
   constexpr int T = WGM * WGN * 64;
   constexpr int PITCH = BK + LDS_PAD;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -125,6 +128,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
 
   TileMover<BM, BK, T, A_KC> ma;
   TileMover<BN, BK, T, B_KC> mb;
+  auto load_a = [&](int row0, int k0, int k_end, bool whole) {
+    if (CONV == 1) ma.load_conv(A, cg, row0, k0, M, k_end, tid);
+    else ma.load(A, lda, row0, k0, M, k_end, tid, whole);
+  };
+  auto load_b = [&](int row0, int k0, int k_end, bool whole) {
+    if (CONV == 2) mb.load_conv(B, cg, row0, k0, N, k_end, tid);
+    else mb.load(B, ldb, row0, k0, N, k_end, tid, whole);
+  };
   bf16x8 af[2][TM], bfr[2][TN];
   auto read_frags = [&](int buf, int cur, int kk) {
     const bf16_t* as = As + cur * BM * PITCH + (wm * WTM + lrow) * PITCH + lk + kk * 16;
@@ -140,8 +151,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
   int m0, n0, kb, ke, split;
   decode(pos, m0, n0, kb, ke, split);
   bool full = m0 + BM <= M && n0 + BN <= N && (ke - kb) % BK == 0;
-  ma.load(A, lda, m0, kb, M, ke, tid, full);
-  mb.load(B, ldb, n0, kb, N, ke, tid, full);
+  load_a(m0, kb, ke, full);
+  load_b(n0, kb, ke, full);
 
   for (;;) {
     f32x16 acc[TM][TN];
@@ -160,8 +171,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
     // the second k-tile starts its trip right away: a tile's loads are issued one whole
     // tile time before they are parked in LDS (half way through the tile before it is used)
     if (KT > 1) {
-      ma.load(A, lda, m0, kb + BK, M, ke, tid, full);
-      mb.load(B, ldb, n0, kb + BK, N, ke, tid, full);
+      load_a(m0, kb + BK, ke, full);
+      load_b(n0, kb + BK, ke, full);
     }
     for (int kt = 0; kt < KT; ++kt) {
       const int cur = kt & 1;
@@ -187,13 +198,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
         constexpr int B_AT = A_KC ? 0 : 1;
         if (kk == A_AT && more) {
           ma.store(As + (cur ^ 1) * BM * PITCH, tid);
-          if (A_AT != B_AT && kt + 2 < KT) ma.load(A, lda, m0, kb + (kt + 2) * BK, M, ke, tid, full);
+          if (A_AT != B_AT && kt + 2 < KT) load_a(m0, kb + (kt + 2) * BK, ke, full);
         }
         if (kk == B_AT && more) {
           mb.store(Bs + (cur ^ 1) * BN * PITCH, tid);
           if (kt + 2 < KT) {
-            if (A_AT == B_AT) ma.load(A, lda, m0, kb + (kt + 2) * BK, M, ke, tid, full);
-            mb.load(B, ldb, n0, kb + (kt + 2) * BK, N, ke, tid, full);
+            if (A_AT == B_AT) load_a(m0, kb + (kt + 2) * BK, ke, full);
+            load_b(n0, kb + (kt + 2) * BK, ke, full);
           }
         }
         if ((kk == A_AT || kk == B_AT) && more) __builtin_amdgcn_sched_barrier(0);
@@ -210,8 +221,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* 
     if (have_next) {
       decode(pos, m0, n0, kb, ke, split);
       full = m0 + BM <= M && n0 + BN <= N && (ke - kb) % BK == 0;
-      ma.load(A, lda, m0, kb, M, ke, tid, full);
-      mb.load(B, ldb, n0, kb, N, ke, tid, full);
+      load_a(m0, kb, ke, full);
+      load_b(n0, kb, ke, full);
     }
 
     // Epilogue through LDS (the operand tiles are dead now: the k-loop ended on a barrier).
@@ -297,7 +308,7 @@ static int compute_units() {
   return g_cus;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, bool CONVS = false>
 static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const int tiles = tiles_m * tiles_n;
@@ -324,17 +335,20 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate};
   // a multiple of 8 workgroups: the kernel deals work items out per XCD
   dim3 grid(std::min((tiles * splits + 7) / 8 * 8, std::max(8, cus / 8 * 8))), block(WGM * WGN * 64);
-#define KARMA_GEMM_LAUNCH(AK, BKC)                                                                      \
+#define KARMA_GEMM_LAUNCH(AK, BKC, CV)                                                                      \
   do {                                                                                                  \
-    auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, AK, BKC>;                                        \
+    auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, AK, BKC, CV>;                                    \
     if (lds > 64 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,  \
-                       k_per_split, ep, (float*)g.ws);                                                  \
+                       k_per_split, ep, (float*)g.ws, g.conv);                                          \
   } while (0)
-  if (g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(true, true);
-  else if (g.a_kc && !g.b_kc) KARMA_GEMM_LAUNCH(true, false);
-  else if (!g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(false, true);
-  else KARMA_GEMM_LAUNCH(false, false);
+  if (CONVS) {   // the convolution variants exist for one tile shape only
+    if (g.conv_mode == 1) KARMA_GEMM_LAUNCH(true, true, (CONVS ? 1 : 0));
+    else KARMA_GEMM_LAUNCH(false, false, (CONVS ? 2 : 0));
+  } else if (g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(true, true, 0);
+  else if (g.a_kc && !g.b_kc) KARMA_GEMM_LAUNCH(true, false, 0);
+  else if (!g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(false, true, 0);
+  else KARMA_GEMM_LAUNCH(false, false, 0);
 #undef KARMA_GEMM_LAUNCH
   if (splits > 1) {
     const size_t mn = (size_t)g.M * g.N;
@@ -347,11 +361,22 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
 int gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (!g.A || !g.B || !g.C || g.M <= 0 || g.N <= 0 || g.K <= 0) return KARMA_E_INVAL;
   // 16-byte k-runs (k-contiguous) or 8-byte row runs (strided) must stay aligned and whole
-  if (g.K % 8) return KARMA_E_INVAL;
-  if (g.a_kc ? (g.lda % 8) : (g.lda % 4 || g.M % 4)) return KARMA_E_INVAL;
-  if (g.b_kc ? (g.ldb % 8) : (g.ldb % 4 || g.N % 4)) return KARMA_E_INVAL;
+  if ((g.a_kc || g.b_kc) && g.K % 8) return KARMA_E_INVAL;   // strided operands take any K: every k-row is bounds-checked
+  if (g.conv_mode != 1 && (g.a_kc ? (g.lda % 8) : (g.lda % 4 || g.M % 4))) return KARMA_E_INVAL;
+  if (g.conv_mode != 2 && (g.b_kc ? (g.ldb % 8) : (g.ldb % 4 || g.N % 4))) return KARMA_E_INVAL;
+  if (g.conv_mode < 0 || g.conv_mode > 2) return KARMA_E_INVAL;
   if (g.accumulate && !g.out_f32) return KARMA_E_INVAL;
   if (g.residual && g.out_f32) return KARMA_E_INVAL;
+  if (g.conv_mode) {
+    const ConvGather& cg = g.conv;
+    if (g.conv_mode == 1 ? !(g.a_kc && g.b_kc) : (g.a_kc || g.b_kc)) return KARMA_E_INVAL;
+    if (cg.C % 8 || cg.H <= 0 || cg.W <= 0 || cg.Ho <= 0 || cg.Wo <= 0 || cg.R <= 0 || cg.S <= 0 || cg.stride <= 0 || cg.pad < 0)
+      return KARMA_E_INVAL;
+    // the gathered operand's index ranges must be what the convolution spans
+    const long pixels = (long)cg.Ho * cg.Wo, taps_c = (long)cg.R * cg.S * cg.C;
+    if (g.conv_mode == 1 ? (g.M % pixels || g.K != taps_c) : (g.K % pixels || g.N != taps_c)) return KARMA_E_INVAL;
+    return launch_cfg<128, 128, 64, 2, 2, true>(g, s);
+  }
   if (g.M > 128 && g.N > 128) return launch_cfg<256, 256, 64, 2, 4>(g, s);
   return launch_cfg<128, 128, 64, 2, 2>(g, s);
 }

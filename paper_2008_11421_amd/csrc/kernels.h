@@ -19,6 +19,16 @@ int linear_relu_bwd_f32(const float* x, const float* w, const float* z, const fl
 int mse_f32(const float* y, const float* t, float* dy, float* loss, float* partial, size_t n, hipStream_t s);
 
 // ---- bf16 GEMM on the matrix cores (gemm_bf16.hip)
+// An operand that is an NHWC tensor seen through a convolution (implicit GEMM): GEMM row (or,
+// for the weight gradient, reduction index) p = (image, ho, wo) on the Ho x Wo grid and
+// index j = (r*S + s)*C + c address element (image, hi, wi, c) of the H x W x C tensor with
+//   hi = ho*stride - pad + r, wi = wo*stride - pad + s              (transposed = 0), or
+//   hi = (ho + pad - r)/stride, wi = (wo + pad - s)/stride where both divide (transposed = 1:
+//   the gradient of a strided convolution w.r.t. its input); positions outside count as zero.
+struct ConvGather {
+  int H, W, C, Ho, Wo, R, S, stride, pad, transposed;
+};
+
 // C[M,N] = sum_k A(m,k) B(n,k) (+ bias[n]) (+ residual[m,n]).  a_kc: A is [M][lda] with k
 // contiguous, else [K][lda] with m contiguous; same for B with n.
 struct GemmArgs {
@@ -28,6 +38,10 @@ struct GemmArgs {
   bool a_kc, b_kc, out_f32, accumulate;
   void* ws;          // optional fp32 workspace for split-k partial sums (dense C only)
   size_t ws_bytes;
+  // conv_mode 1: A (k-contiguous) is gathered, rows = output pixels, k = (tap, channel);
+  // conv_mode 2: B (strided) is gathered, k = output pixels, n = (tap, channel)
+  int conv_mode;
+  ConvGather conv;
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
 
@@ -49,6 +63,30 @@ int softmax_ce(bf16_t* logits, const int* labels, float* rowloss, int rows, int 
 int sum_f32(const float* x, float* out, float* partial_ws, size_t n, float scale, hipStream_t s);
 int fill_zero(void* p, size_t bytes, hipStream_t s);
 int cast_f32_to_bf16(const float* x, bf16_t* y, size_t n, hipStream_t s);
+
+// ---- convolutional workload (conv_bn.hip): NHWC bf16, weights [c_out][r][s][c_in]
+struct ConvShape { int N, H, W, Cin, Cout, R, S, stride, pad; };
+int conv_out_dim(int n, int k, int stride, int pad);
+int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s);
+size_t conv2d_dgrad_ws_elems(const ConvShape& c);   // elements of the transposed-weight buffer (0 for 1x1 stride 1)
+// dx = gradient w.r.t. the input (+ add, may be null)
+int conv2d_dgrad(const bf16_t* dy, const bf16_t* w, bf16_t* wt_ws, const bf16_t* add, bf16_t* dx, const ConvShape& c,
+                 hipStream_t s);
+// dw [c_out][r][s][c_in]; ws: optional fp32 split-k workspace
+int conv2d_wgrad(const bf16_t* dy, const bf16_t* x, bf16_t* dw, void* ws, size_t ws_bytes, const ConvShape& c, hipStream_t s);
+size_t bn_ws_bytes(int rows, int c);
+// training-mode batch normalisation over the rows of [rows][c]; stats = mean[c], rstd[c];
+// y = xhat*g + b (+ add) (ReLU when relu != 0)
+int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, float* stats, float* ws,
+           int rows, int c, int relu, hipStream_t s);
+// relu != 0: dy first passes the ReLU that followed the normalisation (mask recomputed)
+int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
+           float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s);
+int relu_mask_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dz, size_t n, hipStream_t s);
+int maxpool_fwd(const bf16_t* x, bf16_t* y, int n, int h, int w, int c, hipStream_t s);   // 3x3, stride 2, pad 1
+int maxpool_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int w, int c, hipStream_t s);
+int avgpool_fwd(const bf16_t* x, bf16_t* y, int n, int hw, int c, hipStream_t s);         // global
+int avgpool_bwd(const bf16_t* dy, bf16_t* dx, int n, int hw, int c, hipStream_t s);
 
 // ---- fused causal attention (attention.hip); seq multiple of 128, d in {64, 128}
 int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq, int heads, int d, hipStream_t s);
