@@ -132,22 +132,30 @@ int karma_stage_string(const karma_op* ops, uint32_t n_ops, char* buf, size_t bu
 
 /* ---- model and context ---------------------------------------------------------- */
 
-typedef enum { KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2 } karma_model_kind;
-typedef enum { KARMA_OPT_SGD = 1, KARMA_OPT_ADAM = 2 } karma_opt_kind;
+typedef enum { KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2, KARMA_MODEL_CNN = 3 } karma_model_kind;
+/* SGD with momentum: buf = beta1 * buf + g; w -= lr * buf (no dampening, no Nesterov) */
+typedef enum { KARMA_OPT_SGD = 1, KARMA_OPT_ADAM = 2, KARMA_OPT_SGD_MOMENTUM = 3 } karma_opt_kind;
 
 typedef struct {
   uint32_t kind;      /* karma_model_kind */
-  uint32_t n_layers;  /* MLP: Linear+ReLU layers; GPT: transformer blocks */
-  uint32_t width;     /* MLP width / GPT hidden size */
+  uint32_t n_layers;  /* MLP: Linear+ReLU layers; GPT: transformer blocks; CNN: ignored */
+  uint32_t width;     /* MLP width / GPT hidden size / CNN: bottleneck width of the first stage (64) */
   uint32_t batch;
-  uint32_t seq;       /* GPT only */
+  uint32_t seq;       /* GPT: sequence length; CNN: image height = width (multiple of 32) */
   uint32_t n_heads;   /* GPT only; width / n_heads must be 64 or 128 */
   uint32_t ffn;       /* GPT only */
-  uint32_t vocab;     /* GPT only */
+  uint32_t vocab;     /* GPT: vocabulary; CNN: number of classes (multiple of 8) */
   uint32_t stream_weights; /* 1: the weights of every MLP layer / transformer block live in
                               pinned host memory and are streamed through the arena around the
                               layer's ops, their gradients streamed out after its backward
                               (Sec. III-G); embeddings and the final LayerNorm stay resident */
+  uint32_t stage_blocks[4]; /* CNN only: bottleneck blocks per stage (ResNet-200: 3, 24, 36, 3).
+                               Stage k has bottleneck width `width << k` and 4x that many output
+                               channels; its first block carries stride 2 (stage 0: 1) on the 3x3
+                               convolution and a projection shortcut.  Stem: 7x7 stride-2
+                               convolution to `width` channels, batch norm, ReLU, 3x3 stride-2 max
+                               pooling; head: global average pooling, fully connected layer, mean
+                               cross entropy.  Inputs: fp32 images [batch][seq][seq][3]; labels int32. */
 } karma_model_desc;
 
 typedef struct {
@@ -157,7 +165,8 @@ typedef struct {
 } karma_config;
 
 /* Number of plannable layer records of a model (MLP: n_layers; GPT: n_layers + 1, record
- * 0 being the embedding) and of parameter tensors of record `layer`. */
+ * 0 being the embedding; CNN: 1 + sum of stage_blocks, record 0 being the stem) and of
+ * parameter tensors of record `layer`. */
 int karma_model_layers(const karma_model_desc* desc, uint32_t* n_out);
 
 /* Creates a context.  arena_dev: device slab of arena_bytes owned by the caller (e.g. a

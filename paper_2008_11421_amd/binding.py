@@ -12,8 +12,8 @@ LIB_PATH = os.path.join(_HERE, "libkarma.so")
 
 KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN = range(5)
 OK, E_INVAL, E_BUDGET, E_OOM, E_HIP, E_STATE, E_HOSTMEM = 0, -1, -2, -3, -4, -5, -6
-MODEL_MLP, MODEL_GPT = 1, 2
-OPT_SGD, OPT_ADAM = 1, 2
+MODEL_MLP, MODEL_GPT, MODEL_CNN = 1, 2, 3
+OPT_SGD, OPT_ADAM, OPT_SGD_MOMENTUM = 1, 2, 3
 STEP_APPLY_OPTIMIZER = 1
 STEP_PROFILE = 2
 STEP_KERNEL_TIMES = 4
@@ -51,7 +51,7 @@ class Op(C.Structure):
 class ModelDesc(C.Structure):
     _fields_ = [("kind", C.c_uint32), ("n_layers", C.c_uint32), ("width", C.c_uint32), ("batch", C.c_uint32),
                 ("seq", C.c_uint32), ("n_heads", C.c_uint32), ("ffn", C.c_uint32), ("vocab", C.c_uint32),
-                ("stream_weights", C.c_uint32)]
+                ("stream_weights", C.c_uint32), ("stage_blocks", C.c_uint32 * 4)]
 
 
 class ConvShape(C.Structure):
@@ -166,7 +166,12 @@ class Context:
     def __init__(self, desc, cfg, arena_bytes, device="cuda:0"):
         import torch
         self.torch = torch
-        self.desc = desc if isinstance(desc, ModelDesc) else ModelDesc(**desc)
+        if not isinstance(desc, ModelDesc):
+            desc = dict(desc)
+            if "stage_blocks" in desc:
+                desc["stage_blocks"] = (C.c_uint32 * 4)(*desc["stage_blocks"])
+            desc = ModelDesc(**desc)
+        self.desc = desc
         self.cfg = cfg if isinstance(cfg, Config) else Config(**cfg)
         self.device = torch.device(device)
         self.arena = torch.empty(int(arena_bytes), dtype=torch.uint8, device=self.device)
@@ -266,11 +271,10 @@ class Context:
         return buf.value.decode()
 
     def karma_step(self, inputs, labels, flags=0):
-        """inputs/labels: numpy arrays of the dtype the model takes (fp32 for the MLP,
-        int32 for GPT).  Returns the loss."""
-        dt = np.float32 if self.desc.kind == MODEL_MLP else np.int32
-        a = np.ascontiguousarray(inputs, dtype=dt)
-        b = np.ascontiguousarray(labels, dtype=dt)
+        """inputs/labels: numpy arrays of the dtype the model takes (MLP: fp32 / fp32, GPT:
+        int32 ids / int32, CNN: fp32 images [n][h][w][3] / int32 classes).  Returns the loss."""
+        a = np.ascontiguousarray(inputs, dtype=np.int32 if self.desc.kind == MODEL_GPT else np.float32)
+        b = np.ascontiguousarray(labels, dtype=np.float32 if self.desc.kind == MODEL_MLP else np.int32)
         loss = C.c_float()
         with self.torch.cuda.device(self.device):
             st = lib().karma_step(self.ctx, C.c_void_p(a.ctypes.data), C.c_void_p(b.ctypes.data), C.c_uint32(flags),

@@ -12,7 +12,10 @@
 
 namespace karma {
 
-enum RecordKind { REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11 };
+enum RecordKind {
+  REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_CNN_STEM = 4, REC_CNN_BLOCK = 5,
+  REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11, REC_LOSS_CNN_HEAD = 12
+};
 
 struct Param {
   uint64_t n = 0;

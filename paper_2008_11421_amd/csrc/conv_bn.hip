@@ -405,6 +405,14 @@ int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add,
   return ok();
 }
 
+int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, int rows,
+             int c, int relu, hipStream_t s) {
+  if (!x || !stats || !g || !b || !y || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
+  const size_t nvec = (size_t)rows * (c / 8);
+  hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, x, stats, g, b, add, y, nvec, c, relu);
+  return ok();
+}
+
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
            float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s) {
   if (!dy || !x || !stats || !g || !b || !dx || !dgamma || !dbeta || !ws || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;

@@ -318,6 +318,9 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed) {
         if (g.optimizer == KARMA_OPT_ADAM)
           adam_update(p.master.data() + base + lo, p.m.data() + base + lo, p.v.data() + base + lo, gp, p.grad_bf16,
                       hi - lo, g.lr, g.beta1, g.beta2, g.eps, step, wp, p.dev_bf16);
+        else if (g.optimizer == KARMA_OPT_SGD_MOMENTUM)
+          sgd_momentum_update(p.master.data() + base + lo, p.m.data() + base + lo, gp, p.grad_bf16, hi - lo, g.lr, g.beta1, wp,
+                              p.dev_bf16);
         else
           sgd_update(p.master.data() + base + lo, gp, p.grad_bf16, hi - lo, g.lr, wp, p.dev_bf16);
       });
@@ -414,6 +417,7 @@ extern "C" int karma_model_layers(const karma_model_desc* d, uint32_t* n_out) {
   if (!d || !n_out) return KARMA_E_INVAL;
   if (d->kind == KARMA_MODEL_MLP) *n_out = d->n_layers;
   else if (d->kind == KARMA_MODEL_GPT) *n_out = d->n_layers + 1;
+  else if (d->kind == KARMA_MODEL_CNN) *n_out = 1 + d->stage_blocks[0] + d->stage_blocks[1] + d->stage_blocks[2] + d->stage_blocks[3];
   else return KARMA_E_INVAL;
   return KARMA_OK;
 }
@@ -423,7 +427,8 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
                             karma_ctx** out) {
   if (!desc || !cfg || !arena_dev || !out) return KARMA_E_INVAL;
   if (((uintptr_t)arena_dev & 255) != 0) return KARMA_E_INVAL;
-  if (cfg->optimizer != KARMA_OPT_SGD && cfg->optimizer != KARMA_OPT_ADAM) return KARMA_E_INVAL;
+  if (cfg->optimizer != KARMA_OPT_SGD && cfg->optimizer != KARMA_OPT_ADAM && cfg->optimizer != KARMA_OPT_SGD_MOMENTUM)
+    return KARMA_E_INVAL;
   karma_ctx* c = new (std::nothrow) karma_ctx();
   if (!c) return KARMA_E_HOSTMEM;
   c->desc = *desc;
@@ -482,6 +487,7 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
     for (Param& p : r.p) {
       p.master.assign(p.n, 0.f);
       if (cfg->optimizer == KARMA_OPT_ADAM) { p.m.assign(p.n, 0.f); p.v.assign(p.n, 0.f); }
+      if (cfg->optimizer == KARMA_OPT_SGD_MOMENTUM) p.m.assign(p.n, 0.f);
       if (r.streamed) {
         if (ok) { p.stage_w = r.stage_w_all + p.w_rel; p.stage_g = r.stage_g_all + p.g_rel; }
       } else {

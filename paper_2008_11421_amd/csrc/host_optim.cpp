@@ -134,6 +134,29 @@ static void adam_loop(float* __restrict__ w, float* __restrict__ m, float* __res
   }
 }
 
+template <bool G_BF16, bool O_BF16>
+static void sgd_momentum_loop(float* __restrict__ w, float* __restrict__ buf, const void* __restrict__ g, size_t n, float lr,
+                              float mu, void* __restrict__ out) {
+  for (size_t i = 0; i < n; ++i) {
+    float bi = mu * buf[i] + load_g<G_BF16>(g, i);
+    buf[i] = bi;
+    float nw = w[i] - lr * bi;
+    w[i] = nw;
+    store_w<O_BF16>(out, i, nw);
+  }
+}
+
+void sgd_momentum_update(float* w, float* buf, const void* g, bool g_is_bf16, size_t n, float lr, float mu, void* out,
+                         bool out_is_bf16) {
+  if (g_is_bf16) {
+    if (out_is_bf16) sgd_momentum_loop<true, true>(w, buf, g, n, lr, mu, out);
+    else sgd_momentum_loop<true, false>(w, buf, g, n, lr, mu, out);
+  } else {
+    if (out_is_bf16) sgd_momentum_loop<false, true>(w, buf, g, n, lr, mu, out);
+    else sgd_momentum_loop<false, false>(w, buf, g, n, lr, mu, out);
+  }
+}
+
 void sgd_update(float* w, const void* g, bool g_is_bf16, size_t n, float lr, void* out, bool out_is_bf16) {
   if (g_is_bf16) {
     if (out_is_bf16) sgd_loop<true, true>(w, g, n, lr, out); else sgd_loop<true, false>(w, g, n, lr, out);

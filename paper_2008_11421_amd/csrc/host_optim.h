@@ -36,6 +36,9 @@ uint16_t f32_to_bf16_rne(float f);
 
 // w -= lr * g ; new weights also written in device format to `out`.
 void sgd_update(float* w, const void* g, bool g_is_bf16, size_t n, float lr, void* out, bool out_is_bf16);
+// buf = mu * buf + g; w -= lr * buf (no dampening, no Nesterov)
+void sgd_momentum_update(float* w, float* buf, const void* g, bool g_is_bf16, size_t n, float lr, float mu, void* out,
+                         bool out_is_bf16);
 // Bias-corrected Adam without weight decay; `step` counts from 1.
 void adam_update(float* w, float* m, float* v, const void* g, bool g_is_bf16, size_t n, float lr, float beta1,
                  float beta2, float eps, uint64_t step, void* out, bool out_is_bf16);

@@ -79,6 +79,9 @@ size_t bn_ws_bytes(int rows, int c);
 // y = xhat*g + b (+ add) (ReLU when relu != 0)
 int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, float* stats, float* ws,
            int rows, int c, int relu, hipStream_t s);
+// the normalisation alone, from statistics already computed (recomputing an output)
+int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, int rows,
+             int c, int relu, hipStream_t s);
 // relu != 0: dy first passes the ReLU that followed the normalisation (mask recomputed)
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
            float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s);

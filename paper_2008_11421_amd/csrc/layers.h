@@ -15,4 +15,11 @@ int gpt_prepare_late(Ctx& c);
 int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int gpt_loss(Ctx& c, const LayerIO& io, hipStream_t s);
+
+int cnn_build_records(Ctx& c);
+int cnn_prepare_step(Ctx& c, const void* in, const void* lab);
+int cnn_prepare_late(Ctx& c);
+int cnn_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int cnn_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int cnn_loss(Ctx& c, const LayerIO& io, hipStream_t s);
 }  // namespace karma

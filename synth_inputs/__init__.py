@@ -114,3 +114,47 @@ def random_stack(seed, n_layers, kind="homogeneous"):
         ws = 256 * (a[5] % 8)
         rows.append((tf, tb, trc, sav, out, ws))
     return rows
+
+
+# ------------------------------------------------------------------ bottleneck CNN
+def cnn_problem(seed=2008114203, width=64, stage_blocks=(3, 24, 36, 3), image=224, batch=64, classes=1000,
+                bn_jitter=0.0):
+    """Config 3: bottleneck residual network.  Convolution weights N(0, sqrt(2 / (k*k*c_out)))
+    (Kaiming-normal, fan-out), batch-norm gain 1 / shift 0 (plus N(0, bn_jitter) in tests so
+    that both matter), fully connected layer N(0, 0.01) with zero bias, images N(0, 1),
+    labels uniform over the classes.  Layout: weights [c_out][k][k][c_in], images NHWC."""
+    k = [0]
+
+    def nxt():
+        k[0] += 1
+        return seed + 7919 * k[0]
+
+    def conv(co, r, ci):
+        return normal(nxt(), (co, r, r, ci), (2.0 / (r * r * co)) ** 0.5)
+
+    def bn(c):
+        g, b = np.ones(c), np.zeros(c)
+        if bn_jitter:
+            g = g + normal(nxt(), (c,), bn_jitter)
+            b = b + normal(nxt(), (c,), bn_jitter)
+        return g, b
+
+    g, b = bn(width)
+    params = dict(stem=dict(w=conv(width, 7, 3), g=g, b=b), blocks=[], head=None)
+    cin = width
+    for st, nb in enumerate(stage_blocks):
+        mid, cout = width << st, 4 * (width << st)
+        for j in range(nb):
+            p = dict(w1=conv(mid, 1, cin), w2=conv(mid, 3, mid), w3=conv(cout, 1, mid))
+            p["g1"], p["b1"] = bn(mid)
+            p["g2"], p["b2"] = bn(mid)
+            p["g3"], p["b3"] = bn(cout)
+            if j == 0:
+                p["wp"] = conv(cout, 1, cin)
+                p["gp"], p["bp"] = bn(cout)
+            params["blocks"].append((p, 2 if (j == 0 and st > 0) else 1))
+            cin = cout
+    params["head"] = dict(w=normal(nxt(), (classes, cin), 0.01), b=np.zeros(classes))
+    images = normal(nxt(), (batch, image, image, 3))
+    labels = randint(nxt(), (batch,), classes)
+    return params, images, labels
