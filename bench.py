@@ -26,6 +26,10 @@ WORKLOADS = {
             budget=16 * GIB, arena=32 * GIB, seed=2008114202, stream=0,
             name="configs[1]: 24-layer pre-LN GPT, hidden 1024, 16 heads, FFN 4096, seq 1024, batch 32, "
                  "vocab 32000, bf16 + fp32 host master/Adam, HBM budget 16 GiB"),
+    2: dict(cfg=dict(width=64, stage_blocks=(3, 24, 36, 3), image=224, batch=64, classes=1000),
+            budget=32 * GIB, arena=40 * GIB, seed=2008114203, stream=0, kind="cnn", low_budget=4 * GIB,
+            name="configs[2]: ResNet-200-shaped bottleneck CNN (stages 3/24/36/3, widths 256..2048), 224x224x3 images, "
+                 "batch 64, 1000 classes, BatchNorm + ReLU, bf16, host SGD with momentum, HBM budget 32 GiB"),
     3: dict(cfg=dict(n_layers=72, hidden=3072, heads=24, ffn=12288, vocab=51200, seq=1024, batch=8),
             budget=32 * GIB, arena=96 * GIB, seed=2008114204, stream=1,
             name="configs[3]: 72-layer pre-LN GPT (8.3B parameters), hidden 3072, 24 heads, FFN 12288, seq 1024, "
@@ -71,6 +75,84 @@ def cpu_baseline(n_seq):
                        % (n_seq, ts[0], ts[1], t_block, t_rest, CFG["n_layers"]))
 
 
+def bench_cnn(args, wl, K, si, torch, np, threads):
+    """configs[2]: the bottleneck CNN.  It fits its 32 GiB budget in-core (the planner returns
+    all-KEEP); a supplementary run under `low_budget` shows the out-of-core schedule."""
+    from oracle import cnn as oracle_cnn
+    cfg_m = wl["cfg"]
+    desc = dict(kind=K.MODEL_CNN, n_layers=0, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0, ffn=0,
+                vocab=cfg_m["classes"], stream_weights=0, stage_blocks=cfg_m["stage_blocks"])
+    cfg = dict(optimizer=K.OPT_SGD_MOMENTUM, lr=1e-3, beta1=0.9, beta2=0.0, eps=0.0, host_threads=threads)
+    t0 = time.perf_counter()
+    ctx = K.Context(desc, cfg, wl["arena"])
+    params, images, labels = si.cnn_problem(seed=wl["seed"], **cfg_m)
+    w = params["stem"]["w"]
+    wp = np.zeros(w.shape[:3] + (8,), dtype=np.float32)
+    wp[..., :3] = w
+    ctx.karma_set_param(0, 0, wp)
+    ctx.karma_set_param(0, 1, params["stem"]["g"])
+    ctx.karma_set_param(0, 2, params["stem"]["b"])
+    for i, (p, _) in enumerate(params["blocks"]):
+        for t, name in enumerate(oracle_cnn.BOTTLENECK_TENSORS):
+            if name in p:
+                ctx.karma_set_param(i + 1, t, p[name])
+    L = len(params["blocks"]) + 1
+    ctx.karma_set_param(L, 0, params["head"]["w"])
+    ctx.karma_set_param(L, 1, params["head"]["b"])
+    del params
+    images = images.astype(np.float32)
+    labels = labels.astype(np.int32)
+    log("setup %.1f s" % (time.perf_counter() - t0))
+    link = ctx.karma_measure(3)
+    layers, loss_c, fixed = ctx.karma_get_costs()
+    log("link h2d %.1f GB/s d2h %.1f GB/s; fixed %.2f GiB; saved sets %.2f GiB; forward %.1f ms backward %.1f ms"
+        % (link[0] / 1e9, link[1] / 1e9, fixed / GIB, sum(l[3] + l[4] for l in layers) / GIB,
+           sum(l[0] for l in layers) / 1e6, sum(l[1] for l in layers) / 1e6))
+
+    def timed(budget, flags):
+        acts, summ = ctx.karma_plan(budget)
+        for _ in range(args.warmup):
+            ctx.karma_step(images, labels, flags)
+        torch.cuda.synchronize()
+        n_l, ms_l, fl_l = 0, 0.0, 0.0
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            loss = ctx.karma_step(images, labels, flags)
+            if flags & K.STEP_KERNEL_TIMES:
+                n, ms, fl = ctx.karma_get_gemm_stats()
+                n_l += n; ms_l += ms; fl_l += fl
+        torch.cuda.synchronize()
+        return acts, summ, (time.perf_counter() - t1) / args.steps, loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
+
+    acts, summ, dt, loss, gem, st = timed(wl["budget"], K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
+    log("%d GiB: %.1f ms/step, all-keep=%s, peak %.2f GiB" % (wl["budget"] // GIB, dt * 1e3, acts == [0] * len(acts), summ["peak_bytes"] / GIB))
+    acts_lo, summ_lo, dt_lo, loss_lo, _, _ = timed(wl["low_budget"], K.STEP_APPLY_OPTIMIZER)
+    log("%d GiB: %.1f ms/step, plan %s" % (wl["low_budget"] // GIB, dt_lo * 1e3, "".join("KSRrc"[a] for a in acts_lo)))
+    n_l, ms_l, fl_l = gem
+    achieved = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
+    batch = cfg_m["batch"]
+    out = {
+        "metric": "samples/s at fixed HBM budget", "value": batch / dt, "unit": "samples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl["name"], "hbm_budget_gib": wl["budget"] // GIB, "global_batch": batch,
+                   "plan": "".join("KSRrc"[a] for a in acts)},
+        "in_core_samples_per_s": batch / dt, "pct_of_in_core": 100.0, "loss": loss,
+        "predicted_makespan_ms": summ["makespan_ns"] / 1e6, "arena_peak_gib": summ["peak_bytes"] / GIB,
+        "supplementary_low_budget": {"hbm_budget_gib": wl["low_budget"] // GIB, "ms_per_step": dt_lo * 1e3,
+                                     "samples_per_s": batch / dt_lo, "pct_of_in_core": 100.0 * dt / dt_lo,
+                                     "plan": "".join("KSRrc"[a] for a in acts_lo), "arena_peak_gib": summ_lo["peak_bytes"] / GIB,
+                                     "swap_gib_each_way": summ_lo["bytes_d2h"] / GIB},
+        "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9}, "host_opt_ms": st["host_opt_ms"],
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (convolutions as implicit GEMMs and the FC layer, all launches)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "launches_per_step": n_l / max(args.steps, 1), "avg_launch_ms": ms_l / max(n_l, 1),
+                     "flops_per_launch": fl_l / max(n_l, 1), "traffic": None},
+    }
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +191,8 @@ def main():
     torch.cuda.empty_cache()
 
     threads = int(os.environ.get("OMP_NUM_THREADS", "16"))
+    if wl.get("kind") == "cnn":
+        return bench_cnn(args, wl, K, si, torch, np, threads)
     desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=CFG["batch"], seq=CFG["seq"],
                 n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=wl["stream"])
     cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)

@@ -9,6 +9,7 @@
 #include <cstring>
 
 #include "context.h"
+#include "kernels.h"
 
 using namespace karma;
 
@@ -339,6 +340,11 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
   c->ktime = (flags & KARMA_STEP_KERNEL_TIMES) != 0;
   c->kev_used = 0;
   c->kflops.clear();
+  GemmTimer timer{&c->kev, &c->kev_used, &c->kflops};
+  struct TimerScope {   // per-launch GEMM timing for the duration of this step only
+    explicit TimerScope(GemmTimer* t) { g_gemm_timer = t; }
+    ~TimerScope() { g_gemm_timer = nullptr; }
+  } timer_scope(c->ktime ? &timer : nullptr);
   double t0 = now_ms();
   c->stats = karma_step_stats{};
   int st = model_prepare_step(*c, in, lab);

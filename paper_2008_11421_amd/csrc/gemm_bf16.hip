@@ -358,7 +358,27 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? KARMA_OK : KARMA_E_HIP;
 }
 
+thread_local GemmTimer* g_gemm_timer = nullptr;
+
+static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s);
+
 int gemm_bf16(const GemmArgs& g, hipStream_t s) {
+  GemmTimer* t = g_gemm_timer;
+  if (!t) return gemm_bf16_launch(g, s);
+  while (t->events->size() < *t->used + 2) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return KARMA_E_HIP;
+    t->events->push_back(e);
+  }
+  if (hipEventRecord((*t->events)[*t->used], s) != hipSuccess) return KARMA_E_HIP;
+  const int st = gemm_bf16_launch(g, s);
+  if (hipEventRecord((*t->events)[*t->used + 1], s) != hipSuccess) return KARMA_E_HIP;
+  *t->used += 2;
+  t->flops->push_back(2.0 * g.M * g.N * g.K);
+  return st;
+}
+
+static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
   if (!g.A || !g.B || !g.C || g.M <= 0 || g.N <= 0 || g.K <= 0) return KARMA_E_INVAL;
   // 16-byte k-runs (k-contiguous) or 8-byte row runs (strided) must stay aligned and whole
   if ((g.a_kc || g.b_kc) && g.K % 8) return KARMA_E_INVAL;   // strided operands take any K: every k-row is bounds-checked

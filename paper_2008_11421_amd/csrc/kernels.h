@@ -6,6 +6,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <vector>
 
 namespace karma {
 
@@ -44,6 +45,15 @@ struct GemmArgs {
   ConvGather conv;
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
+// While non-null on the calling thread, every gemm_bf16 call records an event before and
+// after its launch (pairs appended from *used on, created on demand) and its flop count:
+// the benchmark's per-launch timing of the dominant kernel.
+struct GemmTimer {
+  std::vector<hipEvent_t>* events;
+  size_t* used;
+  std::vector<double>* flops;
+};
+extern thread_local GemmTimer* g_gemm_timer;
 
 
 // ---- HBM-bound bf16 kernels (norm_act.hip)

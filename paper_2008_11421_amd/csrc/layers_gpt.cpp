@@ -107,23 +107,9 @@ int gemm_raw(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, cons
   return gemm_bf16(g, s);
 }
 
-// every GEMM of the model goes through here so that a profiled step can time each launch
-thread_local Ctx* g_ctx = nullptr;
 int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf16_t* res, int M, int N, int K,
          bool a_kc, bool b_kc, bool out_f32, bool acc, hipStream_t s, void* ws = nullptr, size_t ws_bytes = 0) {
-  Ctx* c = g_ctx;
-  if (!c || !c->ktime) return gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s, ws, ws_bytes);
-  while (c->kev.size() < c->kev_used + 2) {
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return KARMA_E_HIP;
-    c->kev.push_back(e);
-  }
-  if (hipEventRecord(c->kev[c->kev_used], s) != hipSuccess) return KARMA_E_HIP;
-  int st = gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s, ws, ws_bytes);
-  if (hipEventRecord(c->kev[c->kev_used + 1], s) != hipSuccess) return KARMA_E_HIP;
-  c->kev_used += 2;
-  c->kflops.push_back(2.0 * M * N * K);
-  return st;
+  return gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s, ws, ws_bytes);
 }
 
 #define TRY(call)          \
@@ -219,7 +205,6 @@ int gpt_prepare_late(Ctx& c) {
 
 int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
-  g_ctx = &c;
   if (i == 0) {
     if (!io.out) return KARMA_OK;
     return embed_fwd((const int*)io.x, (const bf16_t*)c.w_ptr(0, 0), (const bf16_t*)c.w_ptr(0, 1), (bf16_t*)io.out, d.T,
@@ -250,7 +235,6 @@ int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
 
 int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
-  g_ctx = &c;
   const bf16_t* dy = (const bf16_t*)io.dy;
   if (i == 0) {
     const int32_t* order = (const int32_t*)c.fixed_ptr(c.misc_off);
@@ -311,7 +295,6 @@ int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
 // tokens so that only HEAD_CHUNK rows of logits exist at a time.
 int gpt_loss(Ctx& c, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
-  g_ctx = &c;
   LossWs wl(d);
   const uint32_t R = c.L;   // the loss record
   char* Wk = (char*)io.ws;
