@@ -317,14 +317,17 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
   int splits = 1;
   if (g.ws && g.ldc == g.N && tiles < cus) {
-    // the split count that best fills whole rounds of the chip, fewer splits preferred
-    // (every split writes and re-reads an M x N fp32 partial)
-    const int max_splits = std::min(16, std::max(1, g.K / (4 * BK)));
+    // the split count that best fills whole rounds of the chip, fewer splits preferred: every
+    // split writes and re-reads an M x N fp32 partial, which is weighed against the operand
+    // bytes of the whole product (a skinny weight gradient with a very long reduction takes
+    // hundreds of splits, a square one a handful)
+    const int max_splits = std::min(256, std::max(1, g.K / (4 * BK)));
+    const double per_split = std::min(0.01, 0.5 * (8.0 * g.M * g.N) / (2.0 * ((double)g.M + g.N) * g.K));
     double best = -1.0;
     for (int sp = 1; sp <= max_splits; ++sp) {
       if (sp > 1 && (size_t)sp * g.M * g.N * sizeof(float) > g.ws_bytes) break;
       const int items = tiles * sp, rounds = (items + cus - 1) / cus;
-      const double score = (double)items / ((double)rounds * cus) - 0.01 * sp;
+      const double score = (double)items / ((double)rounds * cus) - per_split * sp;
       if (score > best) { best = score; splits = sp; }
     }
   }

@@ -25,6 +25,14 @@ struct BlockGeom {
   int P2() const { return N * Ho * Wo; }   // pixels of the output
 };
 
+// fp32 workspace that lets a weight-gradient GEMM (M x N result, reduction over the pixels)
+// split its reduction far enough to fill the chip: few output tiles need many splits
+uint64_t splitk_want(uint64_t m, uint64_t n) {
+  const uint64_t tiles = ((m + 127) / 128) * ((n + 127) / 128);
+  const uint64_t splits = std::min<uint64_t>(256, (512 + tiles - 1) / tiles);
+  return splits * m * n * 4;
+}
+
 struct Net {
   int N, S, classes, width, stem_c;
   std::vector<BlockGeom> blocks;   // index = record - 1
@@ -97,7 +105,8 @@ struct BlockWs {
     dxa = take(g.proj ? (uint64_t)g.P() * g.cin * 2 : 0);   // input gradient through the projection
     wt = take((uint64_t)std::max(9 * g.mid * g.mid, g.proj && g.stride > 1 ? g.cin * g.cout : 0) * 2);
     bn = take(std::max(bn_ws_bytes(g.P(), g.mid), bn_ws_bytes(g.P2(), g.cout)));
-    splitk_bytes = (uint64_t)16 * std::max({9 * g.mid * g.mid, g.cout * g.mid, g.proj ? g.cin * g.cout : 0, g.cin * g.mid}) * 4;
+    splitk_bytes = std::max({splitk_want(g.mid, 9 * g.mid), splitk_want(g.cout, g.mid), splitk_want(g.mid, g.cin),
+                             g.proj ? splitk_want(g.cout, g.cin) : 0});
     splitk = take(splitk_bytes);
     total = o;
   }
@@ -128,7 +137,7 @@ struct StemWs {
     auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
     da0 = take((uint64_t)g.N * g.H1 * g.H1 * g.C * 2);
     bn = take(bn_ws_bytes(g.N * g.H1 * g.H1, g.C));
-    splitk_bytes = (uint64_t)16 * g.C * 49 * IMG_C * 4;
+    splitk_bytes = splitk_want(g.C, 49 * IMG_C);
     splitk = take(splitk_bytes);
     total = o;
   }
