@@ -109,18 +109,19 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* __restric
   }
 }
 
-// Adds the band partials in ascending order (eight interleaved slices, then the slices).
+// Adds the band partials in a fixed order: 32 interleaved slices of the bands per channel,
+// then the slices in ascending order.
 //   forward:  stats[0][c] = mean, stats[1][c] = 1/sqrt(var + eps) (biased variance)
 //   backward: out0[c] = dbeta, out1[c] = dgamma
 __global__ __launch_bounds__(256) void bn_finish_kernel(const float* __restrict__ partial, int bands, int C, int rows,
                                                          const bf16_t* __restrict__ x_row0, float* __restrict__ out0,
                                                          float* __restrict__ out1, int bwd) {
-  __shared__ float red[2][8][32];
-  const int cl = threadIdx.x & 31, slice = threadIdx.x >> 5;
-  const int c = blockIdx.x * 32 + cl;
+  __shared__ float red[2][32][8];
+  const int cl = threadIdx.x & 7, slice = threadIdx.x >> 3;
+  const int c = blockIdx.x * 8 + cl;
   float s0 = 0.f, s1 = 0.f;
   if (c < C)
-    for (int p = slice; p < bands; p += 8) {
+    for (int p = slice; p < bands; p += 32) {
       s0 += partial[(size_t)p * 2 * C + c];
       s1 += partial[(size_t)p * 2 * C + C + c];
     }
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(256) void bn_finish_kernel(const float* __restrict_
   if (slice == 0 && c < C) {
     float t0 = red[0][0][cl], t1 = red[1][0][cl];
 #pragma unroll
-    for (int k = 1; k < 8; ++k) { t0 += red[0][k][cl]; t1 += red[1][k][cl]; }
+    for (int k = 1; k < 32; ++k) { t0 += red[0][k][cl]; t1 += red[1][k][cl]; }
     if (bwd) {
       out0[c] = t0;
       out1[c] = t1;
@@ -327,7 +328,7 @@ bool shape_ok(const ConvShape& c) {
 
 int conv_out_dim(int n, int k, int stride, int pad) { return (n + 2 * pad - k) / stride + 1; }
 
-int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s) {
+int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s, void* ws, size_t ws_bytes) {
   if (!x || !w || !y || !shape_ok(c)) return KARMA_E_INVAL;
   const int Ho = conv_out_dim(c.H, c.R, c.stride, c.pad), Wo = conv_out_dim(c.W, c.S, c.stride, c.pad);
   GemmArgs g{};
@@ -335,6 +336,7 @@ int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, 
   g.M = c.N * Ho * Wo; g.N = c.Cout; g.K = c.R * c.S * c.Cin;
   g.a_kc = g.b_kc = true;
   g.lda = g.K; g.ldb = g.K; g.ldc = g.N;
+  g.ws = ws; g.ws_bytes = ws_bytes;   // late stages: few output tiles, long reductions
   if (!plain_gemm(c)) {
     g.conv_mode = 1;
     g.conv = ConvGather{c.H, c.W, c.Cin, Ho, Wo, c.R, c.S, c.stride, c.pad, 0};
@@ -345,12 +347,13 @@ int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, 
 size_t conv2d_dgrad_ws_elems(const ConvShape& c) { return plain_gemm(c) ? 0 : (size_t)c.R * c.S * c.Cin * c.Cout; }
 
 int conv2d_dgrad(const bf16_t* dy, const bf16_t* w, bf16_t* wt_ws, const bf16_t* add, bf16_t* dx, const ConvShape& c,
-                 hipStream_t s) {
+                 hipStream_t s, void* ws, size_t ws_bytes) {
   if (!dy || !w || !dx || !shape_ok(c)) return KARMA_E_INVAL;
   const int Ho = conv_out_dim(c.H, c.R, c.stride, c.pad), Wo = conv_out_dim(c.W, c.S, c.stride, c.pad);
   GemmArgs g{};
   g.A = dy; g.C = dx; g.residual = add;
   g.M = c.N * c.H * c.W; g.N = c.Cin; g.ldc = g.N;
+  g.ws = ws; g.ws_bytes = ws_bytes;
   if (plain_gemm(c)) {
     g.B = w;            // B(n = ci, k = co) = w[co][ci]: strided
     g.K = c.Cout;
@@ -399,7 +402,7 @@ int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add,
   const int bands = (rows + BN_BAND - 1) / BN_BAND;
   hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, (const bf16_t*)nullptr,
                      (const float*)nullptr, g, b, ws, rows, c, 0);
-  hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 31) / 32), dim3(256), 0, s, ws, bands, c, rows, x, stats, stats + c, 0);
+  hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, x, stats, stats + c, 0);
   const size_t nvec = (size_t)rows * (c / 8);
   hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, x, stats, g, b, add, y, nvec, c, relu);
   return ok();
@@ -419,7 +422,7 @@ int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* 
   const int bands = (rows + BN_BAND - 1) / BN_BAND;
   hipLaunchKernelGGL(bn_partial_kernel<true>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, dy, stats, g, b, ws, rows,
                      c, relu);
-  hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 31) / 32), dim3(256), 0, s, ws, bands, c, rows, (const bf16_t*)nullptr, dbeta,
+  hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, (const bf16_t*)nullptr, dbeta,
                      dgamma, 1);
   const size_t nvec = (size_t)rows * (c / 8);
   hipLaunchKernelGGL(bn_apply_bwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, dy, x, stats, g, b, dgamma, dbeta, dx,
@@ -472,14 +475,14 @@ static ConvShape shape_of(const karma_conv_shape* c) {
 
 extern "C" int karma_k_conv2d_fwd_bf16(const void* x, const void* w, void* y, const karma_conv_shape* c, void* stream) {
   if (!c) return KARMA_E_INVAL;
-  return conv2d_fwd((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, shape_of(c), (hipStream_t)stream);
+  return conv2d_fwd((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, shape_of(c), (hipStream_t)stream, nullptr, 0);
 }
 
 extern "C" int karma_k_conv2d_dgrad_bf16(const void* dy, const void* w, void* wt_ws, const void* add, void* dx,
                                          const karma_conv_shape* c, void* stream) {
   if (!c) return KARMA_E_INVAL;
   return conv2d_dgrad((const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)wt_ws, (const bf16_t*)add, (bf16_t*)dx, shape_of(c),
-                      (hipStream_t)stream);
+                      (hipStream_t)stream, nullptr, 0);
 }
 
 extern "C" int karma_k_conv2d_wgrad_bf16(const void* dy, const void* x, void* dw, void* ws, uint64_t ws_bytes,

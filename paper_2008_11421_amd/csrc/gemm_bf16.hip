@@ -81,7 +81,7 @@ struct GemmEpilogue {
 // CONV 1: A is an NHWC tensor gathered through a convolution (rows = output pixels, forward
 // and input-gradient passes); CONV 2: B is (reduction index = output pixels, weight gradient).
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int CONV = 0>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
+__global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                    const bf16_t* __restrict__ B, int M, int N, int K,
                                                                    int lda, int ldb, int tiles_m, int tiles_n,
                                                                    int splits, int k_per_split, GemmEpilogue ep,
@@ -312,7 +312,8 @@ template <int BM, int BN, int BK, int WGM, int WGN, bool CONVS = false>
 static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const int tiles = tiles_m * tiles_n;
-  const int cus = compute_units();
+  // workgroups that run at once: the small tile leaves LDS and registers for two per compute unit
+  const int cus = compute_units() * (BM <= 128 && BN <= 128 ? 2 : 1);
   // split the reduction when the tiles alone cannot fill the chip (weight gradients:
   // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
   int splits = 1;

@@ -77,11 +77,13 @@ int cast_f32_to_bf16(const float* x, bf16_t* y, size_t n, hipStream_t s);
 // ---- convolutional workload (conv_bn.hip): NHWC bf16, weights [c_out][r][s][c_in]
 struct ConvShape { int N, H, W, Cin, Cout, R, S, stride, pad; };
 int conv_out_dim(int n, int k, int stride, int pad);
-int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s);
+// ws / ws_bytes: optional fp32 workspace that lets a product with few output tiles split its reduction
+int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s, void* ws = nullptr,
+               size_t ws_bytes = 0);
 size_t conv2d_dgrad_ws_elems(const ConvShape& c);   // elements of the transposed-weight buffer (0 for 1x1 stride 1)
 // dx = gradient w.r.t. the input (+ add, may be null)
 int conv2d_dgrad(const bf16_t* dy, const bf16_t* w, bf16_t* wt_ws, const bf16_t* add, bf16_t* dx, const ConvShape& c,
-                 hipStream_t s);
+                 hipStream_t s, void* ws = nullptr, size_t ws_bytes = 0);
 // dw [c_out][r][s][c_in]; ws: optional fp32 split-k workspace
 int conv2d_wgrad(const bf16_t* dy, const bf16_t* x, bf16_t* dw, void* ws, size_t ws_bytes, const ConvShape& c, hipStream_t s);
 size_t bn_ws_bytes(int rows, int c);

@@ -266,7 +266,7 @@ int cnn_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
     bf16_t* c0 = (bf16_t*)(S + sv.c0);
     bf16_t* a0 = (bf16_t*)(S + sv.a0);
     const int rows = g.N * g.H1 * g.H1;
-    TRY(conv2d_fwd((const bf16_t*)io.x, W(SW), c0, ConvShape{g.N, g.S, g.S, IMG_C, g.C, 7, 7, 2, 3}, s));
+    TRY(conv2d_fwd((const bf16_t*)io.x, W(SW), c0, ConvShape{g.N, g.S, g.S, IMG_C, g.C, 7, 7, 2, 3}, s, Wk + wl.splitk, wl.splitk_bytes));
     TRY(bn_fwd(c0, W(SG), W(SB), nullptr, a0, (float*)(S + sv.st), (float*)(Wk + wl.bn), rows, g.C, 1, s));
     if (io.out) TRY(maxpool_fwd(a0, (bf16_t*)io.out, g.N, g.H1, g.H1, g.C, s));
     return KARMA_OK;
@@ -282,17 +282,17 @@ int cnn_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   bf16_t* c3 = (bf16_t*)(S + sv.c3);
   bf16_t* cp = (bf16_t*)(S + sv.cp);
   float* bnws = (float*)(Wk + wl.bn);
-  TRY(conv2d_fwd(x, W(W1), c1, ConvShape{g.N, g.H, g.W, g.cin, g.mid, 1, 1, 1, 0}, s));
+  TRY(conv2d_fwd(x, W(W1), c1, ConvShape{g.N, g.H, g.W, g.cin, g.mid, 1, 1, 1, 0}, s, Wk + wl.splitk, wl.splitk_bytes));
   TRY(bn_fwd(c1, W(G1), W(B1), nullptr, a1, (float*)(S + sv.st1), bnws, g.P(), g.mid, 1, s));
-  TRY(conv2d_fwd(a1, W(W2), c2, ConvShape{g.N, g.H, g.W, g.mid, g.mid, 3, 3, g.stride, 1}, s));
+  TRY(conv2d_fwd(a1, W(W2), c2, ConvShape{g.N, g.H, g.W, g.mid, g.mid, 3, 3, g.stride, 1}, s, Wk + wl.splitk, wl.splitk_bytes));
   TRY(bn_fwd(c2, W(G2), W(B2), nullptr, a2, (float*)(S + sv.st2), bnws, g.P2(), g.mid, 1, s));
-  TRY(conv2d_fwd(a2, W(W3), c3, ConvShape{g.N, g.Ho, g.Wo, g.mid, g.cout, 1, 1, 1, 0}, s));
+  TRY(conv2d_fwd(a2, W(W3), c3, ConvShape{g.N, g.Ho, g.Wo, g.mid, g.cout, 1, 1, 1, 0}, s, Wk + wl.splitk, wl.splitk_bytes));
   // a recompute whose output nobody needs still has to produce every saved tensor, statistics
   // included; only the last elementwise pass can be dropped
   bf16_t* y = io.out ? (bf16_t*)io.out : (bf16_t*)(Wk + wl.big) + (size_t)g.P2() * g.cout;
   if (g.proj) {
     bf16_t* sc = (bf16_t*)(Wk + wl.big);
-    TRY(conv2d_fwd(x, W(WP), cp, ConvShape{g.N, g.H, g.W, g.cin, g.cout, 1, 1, g.stride, 0}, s));
+    TRY(conv2d_fwd(x, W(WP), cp, ConvShape{g.N, g.H, g.W, g.cin, g.cout, 1, 1, g.stride, 0}, s, Wk + wl.splitk, wl.splitk_bytes));
     TRY(bn_fwd(cp, W(GP), W(BP), nullptr, sc, (float*)(S + sv.stp), bnws, g.P2(), g.cout, 0, s));
     TRY(bn_fwd(c3, W(G3), W(B3), sc, y, (float*)(S + sv.st3), bnws, g.P2(), g.cout, 1, s));
   } else {
@@ -359,20 +359,20 @@ int cnn_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   // main branch
   TRY(bn_bwd(dz, c3, st3, W(G3), W(B3), 0, big2, (float*)G(G3), (float*)G(B3), bnws, g.P2(), g.cout, s));   // dc3
   TRY(conv2d_wgrad(big2, a2, (bf16_t*)G(W3), sk, wl.splitk_bytes, s3, s));
-  TRY(conv2d_dgrad(big2, W(W3), nullptr, nullptr, m2, s3, s));                                               // da2
+  TRY(conv2d_dgrad(big2, W(W3), nullptr, nullptr, m2, s3, s, sk, wl.splitk_bytes));                                               // da2
   TRY(bn_bwd(m2, c2, st2, W(G2), W(B2), 1, m2, (float*)G(G2), (float*)G(B2), bnws, g.P2(), g.mid, s));       // dc2
   TRY(conv2d_wgrad(m2, a1, (bf16_t*)G(W2), sk, wl.splitk_bytes, s2, s));
-  TRY(conv2d_dgrad(m2, W(W2), wt, nullptr, m1, s2, s));                                                      // da1
+  TRY(conv2d_dgrad(m2, W(W2), wt, nullptr, m1, s2, s, sk, wl.splitk_bytes));                                                      // da1
   TRY(bn_bwd(m1, c1, st1, W(G1), W(B1), 1, m1, (float*)G(G1), (float*)G(B1), bnws, g.P(), g.mid, s));        // dc1
   TRY(conv2d_wgrad(m1, x, (bf16_t*)G(W1), sk, wl.splitk_bytes, s1, s));
   // shortcut, then dx = gradient through the first convolution + gradient through the shortcut
   if (g.proj) {
     TRY(bn_bwd(dz, cp, stp, W(GP), W(BP), 0, big2, (float*)G(GP), (float*)G(BP), bnws, g.P2(), g.cout, s));  // dcp
     TRY(conv2d_wgrad(big2, x, (bf16_t*)G(WP), sk, wl.splitk_bytes, sp, s));
-    TRY(conv2d_dgrad(big2, W(WP), wt, nullptr, dxa, sp, s));
-    TRY(conv2d_dgrad(m1, W(W1), nullptr, dxa, (bf16_t*)io.dx, s1, s));
+    TRY(conv2d_dgrad(big2, W(WP), wt, nullptr, dxa, sp, s, sk, wl.splitk_bytes));
+    TRY(conv2d_dgrad(m1, W(W1), nullptr, dxa, (bf16_t*)io.dx, s1, s, sk, wl.splitk_bytes));
   } else {
-    TRY(conv2d_dgrad(m1, W(W1), nullptr, dz, (bf16_t*)io.dx, s1, s));
+    TRY(conv2d_dgrad(m1, W(W1), nullptr, dz, (bf16_t*)io.dx, s1, s, sk, wl.splitk_bytes));
   }
   return KARMA_OK;
 }
