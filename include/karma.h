@@ -345,7 +345,9 @@ int karma_k_conv2d_wgrad_bf16(const void* dy_dev, const void* x_dev, void* dw_de
 /* Training-mode batch normalisation of x_dev bf16 [rows][c] over its rows (rows = n*h*w):
  * mean and biased variance per channel, eps 1e-5; y = xhat*gamma + beta (+ add_dev, may be
  * NULL), then ReLU when relu != 0.  stats_dev fp32 [2][c] receives mean and 1/sqrt(var+eps);
- * ws_dev: ceil(rows/256) * 2 * c floats.  c must be a multiple of 8. */
+ * ws_dev: karma_k_batchnorm_ws_bytes(rows, c) bytes (per-band channel sums).  c must be a
+ * multiple of 8. */
+uint64_t karma_k_batchnorm_ws_bytes(uint32_t rows, uint32_t c);
 int karma_k_batchnorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const void* beta_dev, const void* add_dev,
                                void* y_dev, void* stats_dev, void* ws_dev, uint32_t rows, uint32_t c, uint32_t relu,
                                void* stream);

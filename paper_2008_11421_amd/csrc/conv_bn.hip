@@ -41,7 +41,14 @@ static inline int ok() { return hipGetLastError() == hipSuccess ? KARMA_OK : KAR
 static inline unsigned blocks_for(size_t n, unsigned per) { return (unsigned)((n + per - 1) / per); }
 
 constexpr float BN_EPS = 1e-5f;
-constexpr int BN_BAND = 256;   // rows of pixels per workgroup
+// Rows of pixels per workgroup: eight per thread.  A workgroup is vc vector columns (8
+// channels each, at most 256) times 256 / vc row lanes, so wide layers take short bands
+// (enough workgroups even when only a few thousand pixels are left) and narrow ones long bands.
+__host__ __device__ inline int bn_band(int C) {
+  const int vc = C / 8 < 256 ? C / 8 : 256;
+  const int band = 8 * (256 / vc);
+  return band < 16 ? 16 : band;
+}
 
 // Per-channel partial sums over a band of rows.  The 256 threads form vc vector columns (8
 // channels each) times rl row lanes; a thread walks rows rl, rl + RL, ... of the band, the
@@ -72,7 +79,9 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* __restric
     } else {
       unpack8(*(const u32x4*)(x + c8), p0);
     }
-    const int r0 = blockIdx.x * BN_BAND, r1 = min(rows, r0 + BN_BAND);
+    const int band = bn_band(C);
+    const int r0 = blockIdx.x * band, r1 = min(rows, r0 + band);
+#pragma unroll 2
     for (int r = r0 + rl; r < r1; r += RL) {
       float v[8];
       unpack8(*(const u32x4*)(x + (size_t)r * C + c8), v);
@@ -145,49 +154,76 @@ __global__ __launch_bounds__(256) void bn_finish_kernel(const float* __restrict_
   }
 }
 
-// y = (x - mean) * rstd * g + b (+ add) (ReLU)
-__global__ void bn_apply_fwd_kernel(const bf16_t* __restrict__ x, const float* __restrict__ stats,
-                                    const bf16_t* __restrict__ g, const bf16_t* __restrict__ b,
-                                    const bf16_t* __restrict__ add, bf16_t* __restrict__ y, size_t nvec, int C, int relu) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= nvec) return;
-  const int c8 = (int)(i % (size_t)(C / 8)) * 8;
-  float v[8], gg[8], bb[8], a[8];
-  unpack8(((const u32x4*)x)[i], v);
+// y = (x - mean) * rstd * g + b (+ add) (ReLU).  Same thread layout as the partial sums: a
+// thread keeps its eight channels' scale and shift in registers and walks the rows of a band.
+__global__ __launch_bounds__(256) void bn_apply_fwd_kernel(const bf16_t* __restrict__ x, const float* __restrict__ stats,
+                                                            const bf16_t* __restrict__ g, const bf16_t* __restrict__ b,
+                                                            const bf16_t* __restrict__ add, bf16_t* __restrict__ y, int rows,
+                                                            int C, int relu) {
+  const int nv = C / 8;
+  const int VC = min(nv - (int)blockIdx.y * 256, 256), RL = 256 / VC;
+  const int vc = threadIdx.x % VC, rl = threadIdx.x / VC;
+  if (rl >= RL) return;
+  const int c8 = (blockIdx.y * 256 + vc) * 8;
+  float gg[8], bb[8], mean[8], rstd[8];
   unpack8(*(const u32x4*)(g + c8), gg);
   unpack8(*(const u32x4*)(b + c8), bb);
-  if (add) unpack8(((const u32x4*)add)[i], a);
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float t = (v[e] - stats[c8 + e]) * stats[C + c8 + e] * gg[e] + bb[e];
-    if (add) t += a[e];
-    v[e] = relu ? fmaxf(t, 0.f) : t;
+  for (int e = 0; e < 8; ++e) { mean[e] = stats[c8 + e]; rstd[e] = stats[C + c8 + e]; }
+  const int band = bn_band(C);
+  const int r0 = blockIdx.x * band, r1 = min(rows, r0 + band);
+  for (int r = r0 + rl; r < r1; r += RL) {
+    const size_t at = (size_t)r * C + c8;
+    float v[8], a[8];
+    unpack8(*(const u32x4*)(x + at), v);
+    if (add) unpack8(*(const u32x4*)(add + at), a);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      // kept as (x - mean) * rstd * g + b: the backward pass recomputes exactly this expression
+      float t = (v[e] - mean[e]) * rstd[e] * gg[e] + bb[e];
+      if (add) t += a[e];
+      v[e] = relu ? fmaxf(t, 0.f) : t;
+    }
+    *(u32x4*)(y + at) = pack8(v);
   }
-  ((u32x4*)y)[i] = pack8(v);
 }
 
 // dx = g * rstd * (dy' - dbeta/M - xhat * dgamma/M)
-__global__ void bn_apply_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
-                                    const float* __restrict__ stats, const bf16_t* __restrict__ g,
-                                    const bf16_t* __restrict__ b, const float* __restrict__ dgamma,
-                                    const float* __restrict__ dbeta, bf16_t* __restrict__ dx, size_t nvec, int C,
-                                    float inv_rows, int relu) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= nvec) return;
-  const int c8 = (int)(i % (size_t)(C / 8)) * 8;
-  float v[8], d[8], gg[8], bb[8];
-  unpack8(((const u32x4*)x)[i], v);
-  unpack8(((const u32x4*)dy)[i], d);
+__global__ __launch_bounds__(256) void bn_apply_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
+                                                            const float* __restrict__ stats, const bf16_t* __restrict__ g,
+                                                            const bf16_t* __restrict__ b, const float* __restrict__ dgamma,
+                                                            const float* __restrict__ dbeta, bf16_t* __restrict__ dx, int rows,
+                                                            int C, float inv_rows, int relu) {
+  const int nv = C / 8;
+  const int VC = min(nv - (int)blockIdx.y * 256, 256), RL = 256 / VC;
+  const int vc = threadIdx.x % VC, rl = threadIdx.x / VC;
+  if (rl >= RL) return;
+  const int c8 = (blockIdx.y * 256 + vc) * 8;
+  float gg[8], bb[8], mean[8], rstd[8], k0[8], k1[8];
   unpack8(*(const u32x4*)(g + c8), gg);
   unpack8(*(const u32x4*)(b + c8), bb);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const float rstd = stats[C + c8 + e];
-    const float xh = (v[e] - stats[c8 + e]) * rstd;
-    const float dd = (relu && !(xh * gg[e] + bb[e] > 0.f)) ? 0.f : d[e];
-    v[e] = gg[e] * rstd * (dd - dbeta[c8 + e] * inv_rows - xh * dgamma[c8 + e] * inv_rows);
+    mean[e] = stats[c8 + e];
+    rstd[e] = stats[C + c8 + e];
+    k0[e] = dbeta[c8 + e] * inv_rows;
+    k1[e] = dgamma[c8 + e] * inv_rows;
   }
-  ((u32x4*)dx)[i] = pack8(v);
+  const int band = bn_band(C);
+  const int r0 = blockIdx.x * band, r1 = min(rows, r0 + band);
+  for (int r = r0 + rl; r < r1; r += RL) {
+    const size_t at = (size_t)r * C + c8;
+    float v[8], d[8];
+    unpack8(*(const u32x4*)(x + at), v);
+    unpack8(*(const u32x4*)(dy + at), d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float xh = (v[e] - mean[e]) * rstd[e];
+      const float dd = (relu && !(xh * gg[e] + bb[e] > 0.f)) ? 0.f : d[e];
+      v[e] = gg[e] * rstd[e] * (dd - k0[e] - xh * k1[e]);
+    }
+    *(u32x4*)(dx + at) = pack8(v);
+  }
 }
 
 // dz = dy where y > 0, else 0 (gradient through the ReLU that produced y)
@@ -394,39 +430,41 @@ int conv2d_wgrad(const bf16_t* dy, const bf16_t* x, bf16_t* dw, void* ws, size_t
   return gemm_bf16(g, s);
 }
 
-size_t bn_ws_bytes(int rows, int c) { return (size_t)((rows + BN_BAND - 1) / BN_BAND) * 2 * c * sizeof(float); }
+size_t bn_ws_bytes(int rows, int c) {
+  const int band = bn_band(c > 8 ? c : 8);
+  return (size_t)((rows + band - 1) / band) * 2 * c * sizeof(float);
+}
 
 int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, float* stats, float* ws,
            int rows, int c, int relu, hipStream_t s) {
   if (!x || !g || !b || !y || !stats || !ws || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
-  const int bands = (rows + BN_BAND - 1) / BN_BAND;
+  const int bands = (rows + bn_band(c) - 1) / bn_band(c);
   hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, (const bf16_t*)nullptr,
                      (const float*)nullptr, g, b, ws, rows, c, 0);
   hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, x, stats, stats + c, 0);
-  const size_t nvec = (size_t)rows * (c / 8);
-  hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, x, stats, g, b, add, y, nvec, c, relu);
+  hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3((rows + bn_band(c) - 1) / bn_band(c), (c / 8 + 255) / 256), dim3(256), 0, s, x, stats,
+                     g, b, add, y, rows, c, relu);
   return ok();
 }
 
 int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, int rows,
              int c, int relu, hipStream_t s) {
   if (!x || !stats || !g || !b || !y || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
-  const size_t nvec = (size_t)rows * (c / 8);
-  hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, x, stats, g, b, add, y, nvec, c, relu);
+  hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3((rows + bn_band(c) - 1) / bn_band(c), (c / 8 + 255) / 256), dim3(256), 0, s, x, stats,
+                     g, b, add, y, rows, c, relu);
   return ok();
 }
 
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
            float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s) {
   if (!dy || !x || !stats || !g || !b || !dx || !dgamma || !dbeta || !ws || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
-  const int bands = (rows + BN_BAND - 1) / BN_BAND;
+  const int bands = (rows + bn_band(c) - 1) / bn_band(c);
   hipLaunchKernelGGL(bn_partial_kernel<true>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, dy, stats, g, b, ws, rows,
                      c, relu);
   hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, (const bf16_t*)nullptr, dbeta,
                      dgamma, 1);
-  const size_t nvec = (size_t)rows * (c / 8);
-  hipLaunchKernelGGL(bn_apply_bwd_kernel, dim3(blocks_for(nvec, 256)), dim3(256), 0, s, dy, x, stats, g, b, dgamma, dbeta, dx,
-                     nvec, c, 1.f / (float)rows, relu);
+  hipLaunchKernelGGL(bn_apply_bwd_kernel, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, dy, x, stats, g, b, dgamma, dbeta,
+                     dx, rows, c, 1.f / (float)rows, relu);
   return ok();
 }
 
@@ -490,6 +528,8 @@ extern "C" int karma_k_conv2d_wgrad_bf16(const void* dy, const void* x, void* dw
   if (!c) return KARMA_E_INVAL;
   return conv2d_wgrad((const bf16_t*)dy, (const bf16_t*)x, (bf16_t*)dw, ws, (size_t)ws_bytes, shape_of(c), (hipStream_t)stream);
 }
+
+extern "C" uint64_t karma_k_batchnorm_ws_bytes(uint32_t rows, uint32_t c) { return (uint64_t)bn_ws_bytes((int)rows, (int)c); }
 
 extern "C" int karma_k_batchnorm_fwd_bf16(const void* x, const void* gamma, const void* beta, const void* add, void* y,
                                           void* stats, void* ws, uint32_t rows, uint32_t c, uint32_t relu, void* stream) {

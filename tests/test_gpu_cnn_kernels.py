@@ -101,7 +101,8 @@ def test_batchnorm(g, rows, c, relu, with_add):
     bet, bd = bf(si.normal(7, (c,), 0.2))
     add, addd = bf(si.normal(8, (rows, c)))
     lib = K.lib()
-    ws = torch.empty((rows + 255) // 256 * 2 * c, dtype=torch.float32, device="cuda")
+    lib.karma_k_batchnorm_ws_bytes.restype = C.c_uint64
+    ws = torch.empty(lib.karma_k_batchnorm_ws_bytes(rows, c) // 4, dtype=torch.float32, device="cuda")
     stats = torch.empty(2, c, dtype=torch.float32, device="cuda")
     y = torch.empty(rows, c, dtype=torch.bfloat16, device="cuda")
     g.call(lib.karma_k_batchnorm_fwd_bf16, g.ptr(xd), g.ptr(gd), g.ptr(bd), g.ptr(addd) if with_add else None, g.ptr(y),
