@@ -129,11 +129,23 @@ __global__ __launch_bounds__(256) void bn_finish_kernel(const float* __restrict_
   const int cl = threadIdx.x & 7, slice = threadIdx.x >> 3;
   const int c = blockIdx.x * 8 + cl;
   float s0 = 0.f, s1 = 0.f;
-  if (c < C)
-    for (int p = slice; p < bands; p += 32) {
+  if (c < C) {
+    int p = slice;
+    for (; p + 96 < bands; p += 128) {   // four bands in flight, added in ascending order
+      float a[4], b[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        a[k] = partial[(size_t)(p + 32 * k) * 2 * C + c];
+        b[k] = partial[(size_t)(p + 32 * k) * 2 * C + C + c];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { s0 += a[k]; s1 += b[k]; }
+    }
+    for (; p < bands; p += 32) {
       s0 += partial[(size_t)p * 2 * C + c];
       s1 += partial[(size_t)p * 2 * C + C + c];
     }
+  }
   red[0][slice][cl] = s0;
   red[1][slice][cl] = s1;
   __syncthreads();

@@ -297,6 +297,41 @@ __global__ void splitk_reduce_kernel(const float* __restrict__ partial, int spli
   }
 }
 
+// The same reduction for many splits of a small result (weight gradients of convolutions:
+// a few thousand elements, up to 256 splits): eight slices of threads each add every eighth
+// partial in ascending order, then the slices are added in ascending order.  The association
+// is fixed, so results are reproducible (it differs from the kernel above, which is used for
+// few splits: the choice depends on the split count only).
+__global__ __launch_bounds__(256) void splitk_reduce_sliced_kernel(const float* __restrict__ partial, int splits, size_t mn,
+                                                                    GemmEpilogue ep, int N) {
+  __shared__ float red[8][32][4];
+  const int q = threadIdx.x & 31, slice = threadIdx.x >> 5;
+  const size_t i = ((size_t)blockIdx.x * 32 + q) * 4;
+  const int cnt = i < mn ? (int)min((size_t)4, mn - i) : 0;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s = slice; s < splits; s += 8)
+    for (int e = 0; e < cnt; ++e) v[e] += partial[(size_t)s * mn + i + e];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[slice][q][e] = v[e];
+  __syncthreads();
+  if (slice != 0 || cnt == 0) return;
+  for (int k = 1; k < 8; ++k)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += red[k][q][e];
+  for (int e = 0; e < cnt; ++e) {
+    const size_t at = i + e;
+    float x = v[e];
+    if (ep.bias) x += bf2f(ep.bias[at % N]);
+    if (ep.out_f32) {
+      float* c = (float*)ep.C;
+      c[at] = ep.accumulate ? c[at] + x : x;
+    } else {
+      if (ep.residual) x += bf2f(ep.residual[at]);
+      ((bf16_t*)ep.C)[at] = f2bf(x);
+    }
+  }
+}
+
 static int g_cus = 0;
 static int compute_units() {
   if (!g_cus) {
@@ -356,8 +391,12 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
 #undef KARMA_GEMM_LAUNCH
   if (splits > 1) {
     const size_t mn = (size_t)g.M * g.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((mn / 4 + 255) / 256 + 1)), dim3(256), 0, s,
-                       (const float*)g.ws, splits, mn, ep, g.N);
+    if (splits >= 16)
+      hipLaunchKernelGGL(splitk_reduce_sliced_kernel, dim3((unsigned)((mn / 4 + 31) / 32 + 1)), dim3(256), 0, s,
+                         (const float*)g.ws, splits, mn, ep, g.N);
+    else
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((mn / 4 + 255) / 256 + 1)), dim3(256), 0, s,
+                         (const float*)g.ws, splits, mn, ep, g.N);
   }
   return hipGetLastError() == hipSuccess ? KARMA_OK : KARMA_E_HIP;
 }
