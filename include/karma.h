@@ -218,7 +218,7 @@ int karma_plan_string(karma_ctx* ctx, char* buf, size_t buf_len);
 
 #define KARMA_STEP_APPLY_OPTIMIZER 1u /* D2H gradients, host update of the master weights, H2D new weights */
 #define KARMA_STEP_PROFILE 2u         /* events around every op; read with karma_get_op_times / karma_get_stats */
-#define KARMA_STEP_KERNEL_TIMES 4u    /* events around every GEMM launch; read with karma_get_gemm_stats */
+#define KARMA_STEP_KERNEL_TIMES 4u    /* events around one GEMM launch in eight (which ones rotates from step to step); read with karma_get_gemm_stats */
 /* One training step.  MLP: inputs_host fp32 [batch, width], labels_host fp32 targets of
  * the same shape.  GPT: inputs_host int32 token ids [batch, seq], labels_host int32
  * [batch, seq].  Synchronous: on return the loss is valid, all streams are drained and
@@ -234,8 +234,9 @@ typedef struct {
   double host_opt_ms;      /* host optimiser wall time */
 } karma_step_stats;
 int karma_get_stats(karma_ctx* ctx, karma_step_stats* out);
-/* GEMM launches of the last step run with KARMA_STEP_KERNEL_TIMES: how many, the sum of
- * their durations (HIP events on the compute stream) and of their 2*m*n*k flop counts. */
+/* The sampled GEMM launches of the last step run with KARMA_STEP_KERNEL_TIMES: how many were
+ * timed, the sum of their durations (HIP events on the compute stream) and of their 2*m*n*k
+ * flop counts.  Eight consecutive steps sample every launch of a step once. */
 int karma_get_gemm_stats(karma_ctx* ctx, uint64_t* launches_out, double* ms_out, double* flops_out);
 /* The ops of the current plan (predicted times) and, for the last step run with
  * KARMA_STEP_PROFILE, their measured durations in ms.  *n_inout: capacity in, count out. */

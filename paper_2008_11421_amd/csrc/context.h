@@ -97,6 +97,7 @@ struct Ctx {
 
   // per-launch timing of the GEMM kernel (KARMA_STEP_KERNEL_TIMES)
   bool ktime = false;
+  uint64_t ktime_steps = 0;               // steps run with kernel timing so far (rotates which launches are sampled)
   std::vector<hipEvent_t> kev;            // event pool, two per launch
   size_t kev_used = 0;
   std::vector<double> kflops;             // flops of launch j (events 2j, 2j+1)

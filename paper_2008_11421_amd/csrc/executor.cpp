@@ -334,13 +334,16 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed) {
   return KARMA_OK;
 }
 
+// one GEMM launch in this many carries timing events under KARMA_STEP_KERNEL_TIMES
+static const unsigned GEMM_TIMER_STRIDE = 8;
+
 int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out, bool profile) {
   if (!c->planned) return fail(c, KARMA_E_STATE, "karma_step before karma_plan / karma_set_plan");
   const bool apply = flags & KARMA_STEP_APPLY_OPTIMIZER;
   c->ktime = (flags & KARMA_STEP_KERNEL_TIMES) != 0;
   c->kev_used = 0;
   c->kflops.clear();
-  GemmTimer timer{&c->kev, &c->kev_used, &c->kflops};
+  GemmTimer timer{&c->kev, &c->kev_used, &c->kflops, GEMM_TIMER_STRIDE, (unsigned)(c->ktime_steps++ % GEMM_TIMER_STRIDE), 0};
   struct TimerScope {   // per-launch GEMM timing for the duration of this step only
     explicit TimerScope(GemmTimer* t) { g_gemm_timer = t; }
     ~TimerScope() { g_gemm_timer = nullptr; }

@@ -10,6 +10,7 @@
 // arithmetic; the workgroup -> tile map keeps each XCD's L2 on a compact patch of C.
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <cstdint>
 
 #include "karma.h"
 #include "device_utils.h"
@@ -274,6 +275,274 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same product for shapes made of whole tiles, with the two gfx950 additions that take
+// the operand tiles off the vector-register path:
+//  * global_load_lds_dwordx4 copies 16 bytes per lane from global memory straight into LDS
+//    (lane l's piece lands at M0 + 16*l): no staging registers, no ds_write burst in which
+//    all eight wavefronts stall at once, and the loads are waited for only at the single
+//    barrier per k-tile;
+//  * ds_read_b64_tr_b16 reads a strided operand (k-rows of m-contiguous elements) out of LDS
+//    already transposed into the MFMA's 8-consecutive-k-per-lane layout, so strided tiles
+//    need no register transposes either.
+// LDS holds two stages of (A tile, B tile) without padding; bank conflicts are avoided by
+// choosing which 16-byte piece of global memory each lane fetches (an XOR swizzle of the
+// piece index with low bits of the row), undone in the fragment addresses.
+// The tile stream is continuous across work items: while the last k-tile of an item is being
+// multiplied, the first k-tile of the next item is already landing in the other stage; the
+// epilogue's fp32 strip aliases the stage of the last tile (plus a small margin).
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+#define KARMA_LDS(T) __attribute__((address_space(3))) T
+
+// 16 bytes per lane from g (per-lane address) to LDS byte address lds (wavefront-uniform) + 16*lane.
+// The s_nop covers the SALU-writes-M0 -> LDS-DMA hazard, which the assembler does not see in inline code.
+__device__ __forceinline__ void load_to_lds16(const bf16_t* g, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds)), "v"(g)
+               : "memory");
+}
+// LDS-only workgroup barrier written with builtins, so that the compiler's own wait-count
+// bookkeeping knows that every LDS read issued before it has returned.
+__device__ __forceinline__ void lds_barrier_visible() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), other counters untouched
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                                         int M, int N, int K, int lda, int ldb, int tiles_m,
+                                                                         int tiles_n, int splits, int k_per_split,
+                                                                         GemmEpilogue ep, float* __restrict__ partial) {
+  constexpr int WAVES = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int KSTEPS = BK / 16;
+  static_assert(BK == 64 && KSTEPS == 4, "swizzles below are written for 128-byte k-rows");
+  static_assert(BM == 256 && BN == 256, "strided swizzle assumes 512-byte k-rows");
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int CH_A = A_BYTES / 1024 / WAVES, CH_B = B_BYTES / 1024 / WAVES;   // 1 KiB pieces per wavefront
+  constexpr int LPT = CH_A + CH_B;                                               // direct loads per lane per k-tile
+  constexpr int SP = WTN + 4;
+  constexpr int STRIP = WAVES * 32 * SP * 4;
+  constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [EXTRA][stage 0][stage 1][EXTRA]
+  const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int lrow = lane & 31;
+  const int total_tiles = tiles_m * tiles_n;
+  const int total_items = total_tiles * splits;
+  const int per_xcd = (total_items + 7) / 8;
+  const int xcd_first = (int)(blockIdx.x % 8) * per_xcd;
+  const int xcd_step = (int)gridDim.x / 8;
+  auto decode = [&](int pos, int& m0, int& n0, int& kb, int& ke, int& split) {
+    const int item = xcd_first + pos;
+    split = item / total_tiles;
+    const int id = item % total_tiles;
+    constexpr int BAND = 8;
+    const int band_sz = BAND * tiles_n;
+    const int first_m = (id / band_sz) * BAND;
+    const int rows_in_band = min(tiles_m - first_m, BAND);
+    m0 = (first_m + (id % band_sz) % rows_in_band) * BM;
+    n0 = ((id % band_sz) / rows_in_band) * BN;
+    kb = split * k_per_split;
+    ke = min(K, kb + k_per_split);
+  };
+  auto valid = [&](int pos) { return pos < per_xcd && xcd_first + pos < total_items; };
+
+  // ---- global side of the direct loads.  A wavefront moves CH 1-KiB pieces per operand and
+  // k-tile; piece i of wavefront w is rows 32w + 8i .. +7 of a k-contiguous tile (eight
+  // 16-byte pieces per 128-byte row) or k-rows 8w + 2i, +1 of a strided one (32 pieces per
+  // 512-byte k-row).  The lane at LDS piece p of a row fetches global piece p ^ swizzle(row):
+  //   k-contiguous: swizzle = (row / 2) % 8     strided: swizzle = (k % 4) * 4
+  // Both depend on i only through its parity, so two column offsets per lane suffice.
+  static_assert((BM / WAVES) % 16 == 0 && (BN / WAVES) % 16 == 0 && (BK / WAVES) % 4 == 0, "swizzle parity per piece");
+  const int a_row = A_KC ? wave * (BM / WAVES) + (lane >> 3) : wave * (BK / WAVES) + (lane >> 5);
+  const int b_row = B_KC ? wave * (BN / WAVES) + (lane >> 3) : wave * (BK / WAVES) + (lane >> 5);
+  int a_col[2], b_col[2];
+#pragma unroll
+  for (int odd = 0; odd < 2; ++odd) {
+    const int kc_col = ((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) * 8;
+    const int st_col = ((lane & 31) ^ ((2 * odd + (lane >> 5)) << 2)) * 8;
+    a_col[odd] = A_KC ? kc_col : st_col;
+    b_col[odd] = B_KC ? kc_col : st_col;
+  }
+  // element offset of this lane's piece 0 of k-tile 0 of an item (without the column swizzle)
+  auto a_origin = [&](int m0, int kb) { return A_KC ? (size_t)(m0 + a_row) * lda + kb : (size_t)(kb + a_row) * lda + m0; };
+  auto b_origin = [&](int n0, int kb) { return B_KC ? (size_t)(n0 + b_row) * ldb + kb : (size_t)(kb + b_row) * ldb + n0; };
+  auto issue_a = [&](int stage, size_t ao, int t) {
+    const unsigned sa = lds0 + EXTRA + stage * STAGE + wave * (CH_A * 1024);
+    const bf16_t* pa = A + ao + (A_KC ? (size_t)t * BK : (size_t)t * BK * lda);
+#pragma unroll
+    for (int i = 0; i < CH_A; ++i) load_to_lds16(pa + (size_t)i * (A_KC ? 8 : 2) * lda + a_col[i & 1], sa + i * 1024);
+  };
+  auto issue_b = [&](int stage, size_t bo, int t) {
+    const unsigned sb = lds0 + EXTRA + stage * STAGE + A_BYTES + wave * (CH_B * 1024);
+    const bf16_t* pb = B + bo + (B_KC ? (size_t)t * BK : (size_t)t * BK * ldb);
+#pragma unroll
+    for (int i = 0; i < CH_B; ++i) load_to_lds16(pb + (size_t)i * (B_KC ? 8 : 2) * ldb + b_col[i & 1], sb + i * 1024);
+  };
+  auto issue = [&](int stage, size_t ao, size_t bo, int t) {
+    issue_a(stage, ao, t);
+    issue_b(stage, bo, t);
+  };
+
+  // ---- LDS side: fragment addresses (bytes from the start of the operand's tile).
+  // k-contiguous: lane reads 16 bytes: row = block row + lane%32, piece (lane/32 + 2*kk) ^ swizzle.
+  // strided: two transposing 8-byte reads (k + 0..3 and k + 4..7); in each group of 16 lanes,
+  // lane 4e+q supplies k-row e, columns 4q..4q+3, and receives column (its index in the group),
+  // k-rows 0..3: lane group g covers block rows 16*(g%2).. and k offset 8*(g/2).
+  const int grp = lane >> 4, e4 = (lane >> 2) & 3, q4 = lane & 3;
+  auto frag_base = [&](bool kc, int wrow0, int blk) -> unsigned {
+    if (kc) return (unsigned)((wrow0 + blk * 32 + lrow) * (BK * 2));
+    const int m = wrow0 + blk * 32 + 16 * (grp & 1) + 4 * q4;
+    const int piece = (m >> 3) ^ (e4 << 2);
+    return (unsigned)((8 * (grp >> 1) + e4) * (BM * 2) + piece * 16 + (m & 7) * 2);
+  };
+  const unsigned kc_k0 = (unsigned)(((lane >> 5) ^ ((lrow >> 1) & 7)) * 16);   // piece for kk = 0; kk flips bits 5-6
+  unsigned a_fb[TM], b_fb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a_fb[i] = frag_base(A_KC, wm * WTM, i) + (A_KC ? kc_k0 : 0u);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) b_fb[j] = frag_base(B_KC, wn * WTN, j) + (B_KC ? kc_k0 : 0u);
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto read_one = [&](bool kc, unsigned tile_lds, unsigned fb, int kk) -> bf16x8 {
+    if (kc) return *(const KARMA_LDS(bf16x8)*)(uintptr_t)(tile_lds + (fb ^ (unsigned)(kk << 5)));
+    const unsigned at = tile_lds + fb + (unsigned)(kk * 16 * (BM * 2));
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((KARMA_LDS(s16x4_t)*)(uintptr_t)at);
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((KARMA_LDS(s16x4_t)*)(uintptr_t)(at + 4 * (BM * 2)));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto read_frags = [&](int buf, int stage, int kk) {
+    const unsigned ta = lds0 + EXTRA + stage * STAGE, tb = ta + A_BYTES;
+    // in the order the MFMAs below want them: (a0, b0), (a0, b1), (a1, ...), ...
+#pragma unroll
+    for (int x = 0; x < (TM > TN ? TM : TN); ++x) {
+      if (x < TN) bfr[buf][x] = read_one(B_KC, tb, b_fb[x], kk);
+      if (x < TM) af[buf][x] = read_one(A_KC, ta, a_fb[x], kk);
+    }
+  };
+
+  int pos = blockIdx.x / 8;
+  if (!valid(pos)) return;
+  int m0, n0, kb, ke, split;
+  decode(pos, m0, n0, kb, ke, split);
+  size_t ao = a_origin(m0, kb), bo = b_origin(n0, kb);
+  int s0 = 0;   // stage of the current item's first k-tile
+  issue(s0, ao, bo, 0);
+
+  for (;;) {
+    const int KT = (ke - kb) / BK;
+    // the next item, whose first k-tile is fetched while this one is still computing
+    int m0n = 0, n0n = 0, kbn = 0, ken = 0, splitn = 0;
+    const bool have_next = valid(pos + xcd_step);
+    size_t aon = 0, bon = 0;
+    if (have_next) {
+      decode(pos + xcd_step, m0n, n0n, kbn, ken, splitn);
+      aon = a_origin(m0n, kbn);
+      bon = b_origin(n0n, kbn);
+    }
+    lds_barrier_visible();   // the previous item's strip (which overlays stage s0 ^ 1) has been read out by every wavefront
+    if (KT > 1) issue(s0 ^ 1, ao, bo, 1);
+    else if (have_next) issue(s0 ^ 1, aon, bon, 0);
+    if (KT > 1 || have_next) wait_vm<LPT>();   // everything older than the loads just issued: tile 0 has landed
+    else wait_vm<0>();
+    lds_barrier_visible();
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    read_frags(0, s0, 0);
+    int st = s0;
+    for (int kt = 0; kt < KT; ++kt) {
+      const bool more = kt + 1 < KT;
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, st, kk + 1);
+        else read_frags(0, st ^ 1, 0);   // the next tile's first step (not used after the item's last tile)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+        // one LDS read in the shadow of each MFMA
+#pragma unroll
+        for (int r = 0; r < TM + TN; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk == KSTEPS - 2 && more) {
+          // The next k-tile (issued one tile ago) must have landed, for every wavefront; past
+          // the barrier nobody reads this stage any more (the last step's fragments were
+          // fetched before this step's MFMAs), so the tile after next goes into it at once.
+          wait_vm<0>();
+          lds_barrier_visible();
+          if (kt + 2 < KT) issue_a(st, ao, kt + 2);
+          else if (have_next) issue_a(st, aon, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kk == KSTEPS - 1 && more) {
+          if (kt + 2 < KT) issue_b(st, bo, kt + 2);
+          else if (have_next) issue_b(st, bon, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      st ^= 1;
+    }
+    lds_barrier_visible();   // the last tile's reads are done: its stage is free for the strip
+
+    // Epilogue as in the kernel above: accumulators hold the transposed tile; each wavefront
+    // parks a 32-row strip in its own fp32 patch of LDS and reads it back row-contiguously.
+    float* strip = (float*)(smem + ((st ^ 1) == 0 ? 0 : EXTRA + STAGE)) + wave * 32 * SP;
+    constexpr int QPR = WTN / 8;
+    constexpr int RPI = 64 / QPR;
+    static_assert(QPR >= 4 && 64 % QPR == 0 && RPI % 2 == 0 && 32 % RPI == 0, "strip read-out does not tile");
+    const int q = (lane & 3) | (((lane >> 3) % (QPR / 4)) << 2);
+    const int rr = ((lane >> 2) & 1) | ((lane / (2 * QPR)) << 1);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *(float4*)(strip + lrow * SP + j * 32 + g * 8 + (lane >> 5) * 4) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      const int n = n0 + wn * WTN + q * 8;
+#pragma unroll
+      for (int pass = 0; pass < 32 / RPI; ++pass) {
+        const int row = pass * RPI + rr;
+        const int m = m0 + wm * WTM + i * 32 + row;
+        const float4 v = *(const float4*)(strip + row * SP + q * 8);
+        const float4 u = *(const float4*)(strip + row * SP + q * 8 + 4);
+        if (splits > 1) {
+          float* dst = partial + ((size_t)split * M + m) * N + n;
+          *(float4*)dst = v;
+          *(float4*)(dst + 4) = u;
+        } else {
+          ep.octet(m, n, 8, v, u);
+        }
+      }
+    }
+    if (!have_next) break;
+    pos += xcd_step;
+    m0 = m0n; n0 = n0n; kb = kbn; ke = ken; split = splitn;
+    ao = aon; bo = bon;
+    s0 = st;
+  }
+}
+
 // out = sum over splits (ascending) of partial[s], then the epilogue's conversions
 __global__ void splitk_reduce_kernel(const float* __restrict__ partial, int splits, size_t mn, GemmEpilogue ep, int N) {
   size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -343,6 +612,28 @@ static int compute_units() {
   return g_cus;
 }
 
+template <int BM, int BN, int BK, int WGM, int WGN>
+static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 block, int tiles_m, int tiles_n, int splits,
+                          int k_per_split, const GemmEpilogue& ep) {
+  if constexpr (BM == 256 && BN == 256 && BK == 64) {
+    constexpr int STAGE = (BM + BN) * BK * 2, STRIP = WGM * WGN * 32 * (BN / WGN + 4) * 4;
+    constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
+    const int lds = 2 * STAGE + 2 * EXTRA;
+#define KARMA_DL_LAUNCH(AK, BKC)                                                                                  \
+  do {                                                                                                            \
+    auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC>;                                               \
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);                \
+    hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits, \
+                       k_per_split, ep, (float*)g.ws);                                                            \
+  } while (0)
+    if (g.a_kc && g.b_kc) KARMA_DL_LAUNCH(true, true);
+    else if (g.a_kc && !g.b_kc) KARMA_DL_LAUNCH(true, false);
+    else if (!g.a_kc && g.b_kc) KARMA_DL_LAUNCH(false, true);
+    else KARMA_DL_LAUNCH(false, false);
+#undef KARMA_DL_LAUNCH
+  }
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, bool CONVS = false>
 static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
@@ -381,7 +672,15 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,  \
                        k_per_split, ep, (float*)g.ws, g.conv);                                          \
   } while (0)
-  if (CONVS) {   // the convolution variants exist for one tile shape only
+  // whole tiles, 16-byte aligned rows: the direct-to-LDS kernel
+  bool direct = false;
+  if (!CONVS && BM == 256 && BN == 256 && BK == 64 && WGM == 2 && WGN == 4) {
+    direct = g.M % BM == 0 && g.N % BN == 0 && g.K % BK == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
+             ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (splits == 1 || g.N % 4 == 0);
+  }
+  if (direct) {
+    launch_direct<BM, BN, BK, WGM, WGN>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
+  } else if (CONVS) {   // the convolution variants exist for one tile shape only
     if (g.conv_mode == 1) KARMA_GEMM_LAUNCH(true, true, (CONVS ? 1 : 0));
     else KARMA_GEMM_LAUNCH(false, false, (CONVS ? 2 : 0));
   } else if (g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(true, true, 0);
@@ -408,6 +707,7 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s);
 int gemm_bf16(const GemmArgs& g, hipStream_t s) {
   GemmTimer* t = g_gemm_timer;
   if (!t) return gemm_bf16_launch(g, s);
+  if (t->stride > 1 && (t->seq++ % t->stride) != t->phase % t->stride) return gemm_bf16_launch(g, s);
   while (t->events->size() < *t->used + 2) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return KARMA_E_HIP;

@@ -45,13 +45,17 @@ struct GemmArgs {
   ConvGather conv;
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
-// While non-null on the calling thread, every gemm_bf16 call records an event before and
-// after its launch (pairs appended from *used on, created on demand) and its flop count:
-// the benchmark's per-launch timing of the dominant kernel.
+// While non-null on the calling thread, gemm_bf16 calls record an event before and after
+// their launch (pairs appended from *used on, created on demand) and their flop count: the
+// benchmark's per-launch timing of the dominant kernel.  One call in `stride` is timed (the
+// one whose running index `seq` is congruent to `phase`), so that the events, each of which
+// also keeps consecutive kernels from overlapping, stay a small part of the step; the caller
+// rotates the phase from step to step so that every launch site is sampled.
 struct GemmTimer {
   std::vector<hipEvent_t>* events;
   size_t* used;
   std::vector<double>* flops;
+  unsigned stride, phase, seq;
 };
 extern thread_local GemmTimer* g_gemm_timer;
 
