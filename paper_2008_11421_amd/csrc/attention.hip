@@ -16,6 +16,8 @@
 // Reductions over tiles run in a fixed order; there are no atomics (dQ has its own pass).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "karma.h"
 #include "device_utils.h"
 #include "kernels.h"
@@ -198,6 +200,201 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
   if (g == 0) lse[((size_t)b * H + head) * S + query] = m * c + log2f(l);
 }
 
+// ---------------------------------------------------------- head dimension 64: direct loads
+// The kernels below (D = 64) keep every operand tile as it lies in memory, [rows][64] with
+// 128-byte rows, fetched straight into LDS by global_load_lds_dwordx4 (two stages, one
+// barrier per tile) and read either by rows (ds_read_b128: the operand whose reduction index
+// is the head dimension) or transposed (ds_read_b64_tr_b16: the operand whose reduction index
+// is the tile's row index), so no tile is loaded twice or transposed in registers.
+// 16-byte piece p of row r is stored at piece p ^ swz64(r): row reads (16 consecutive rows,
+// one piece) and transposing reads (4 rows x 4 pieces) are both free of bank conflicts.
+__device__ __forceinline__ int swz64(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+
+// direct loads of a [ROWS][64] tile (row pitch ld elements in memory) by WAVES wavefronts
+template <int ROWS, int WAVES>
+__device__ __forceinline__ void issue_tile64(const bf16_t* g, size_t ld, unsigned lds, int wave, int lane) {
+  constexpr int CH = ROWS / 8 / WAVES;   // 1 KiB pieces (8 rows) per wavefront
+  static_assert(CH >= 1 && ROWS % (8 * WAVES) == 0, "tile does not divide over the wavefronts");
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = wave * CH + i;
+    const int row = 8 * c + (lane >> 3);
+    load_to_lds16(g + (size_t)row * ld + (((lane & 7) ^ swz64(row)) * 8), lds + c * 1024);
+  }
+}
+
+// per-lane address parts of the two fragment kinds
+struct Frag64 {
+  unsigned row_off;      // row read: lane%32 * 128
+  unsigned ko[4];        // row read: byte offset of the lane's piece for k-step ks (d = 16 ks + 8 g ..)
+  unsigned tro[2][2];    // transposing read: [32-wide block of the transposed rows][first / second four k]
+  __device__ __forceinline__ void init(int lane) {
+    const int lrow = lane & 31, g = lane >> 5, grp = lane >> 4, e4 = (lane >> 2) & 3, q4 = lane & 3;
+    row_off = (unsigned)(lrow * 128);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ko[ks] = (unsigned)(((2 * ks + g) ^ swz64(lrow)) * 16);
+    // the lane supplies (tile row = base + 4 g + 8 h + e4, columns 32 i + 16 (grp % 2) + 4 q4 ..): base is a
+    // multiple of 16, so the swizzle of that row is known here
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int f = ((e4 >> 1) << 2) | ((g + 2 * h) & 3);
+        const int piece = (4 * i + 2 * (grp & 1) + (q4 >> 1)) ^ f;
+        tro[i][h] = (unsigned)((4 * g + 8 * h + e4) * 128 + piece * 16 + (q4 & 1) * 8);
+      }
+  }
+  // rows r0 + lane%32 of the tile, k = d in [16 ks + 8 g, +8)
+  __device__ __forceinline__ bf16x8 rows(unsigned tile, int r0, int ks) const {
+    return *(const KARMA_LDS(bf16x8)*)(uintptr_t)(tile + (unsigned)(r0 * 128) + row_off + ko[ks]);
+  }
+  // transposed: MFMA row = column 32 i + lane%32 of the tile, k-slots = tile rows base + 4g + {0..3, 8..11}
+  __device__ __forceinline__ bf16x8 cols(unsigned tile, int base, int i) const {
+    const unsigned at = tile + (unsigned)(base * 128);
+    return read_tr_pair(at + tro[i][0], at + tro[i][1]);
+  }
+};
+
+__global__ __launch_bounds__(256, 2) void attn_fwd_dl_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+                                                              float* __restrict__ lse, int S, int H) {
+  constexpr int D = 64, KT = 128, TILE = KT * D * 2, STAGE = 2 * TILE;   // stage = K tile | V tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
+  const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
+  const int h = H * D;
+  const size_t ld = 3 * (size_t)h;
+  int tile, head, b;
+  attn_block(tile, head, b, true);
+  const int q0 = tile * 128;
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lrow = lane & 31, g = lane >> 5;
+  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * D;
+  const bf16_t* Kg = base + h;
+  const bf16_t* Vg = base + 2 * h;
+  const int qbase = q0 + 32 * w, query = qbase + lrow;
+  const float c = LOG2E * rsqrtf((float)D);
+  Frag64 fr;
+  fr.init(lane);
+
+  auto issue = [&](int kt) {
+    const unsigned st = lds0 + (kt & 1) * STAGE;
+    issue_tile64<KT, 4>(Kg + (size_t)kt * KT * ld, ld, st, w, lane);
+    issue_tile64<KT, 4>(Vg + (size_t)kt * KT * ld, ld, st + TILE, w, lane);
+  };
+  const int n_kt = (q0 + 128) / KT;
+  issue(0);
+
+  bf16x8 qf[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    Frag f;
+    f.u = *(const u32x4*)(base + (size_t)query * ld + ks * 16 + g * 8);
+    qf[ks] = f.v;
+  }
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;   // m: running maximum of the raw scores (before the 1/sqrt(d) scale)
+
+  // One 128-key tile.  FULL: every key precedes every query of the workgroup (all tiles but the
+  // last): no masking, no skipped sub-tiles, and the four sub-tiles' MFMA chains are independent
+  // instruction streams the scheduler can interleave with each other and with the exponentials.
+  auto tile_step = [&](int kt, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const int key0 = kt * KT;
+    wait_vm<0>();            // this wavefront's share of tile kt has landed
+    lds_barrier_visible();   // ... and everybody's; tile kt - 1 is no longer read
+    if (kt + 1 < n_kt) issue(kt + 1);
+    const unsigned Ks = lds0 + (kt & 1) * STAGE, Vs = Ks + TILE;
+    // sub-tiles this wavefront needs: keys key0 + 32*mt <= last query
+    const int n_mt = FULL ? 4 : min(4, (qbase + 31 - key0) / 32 + 1);
+    f32x16 s[4];
+    float tmax = -INFINITY;
+    if (FULL) {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+          s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Ks, mt * 32, ks), qf[ks], s[mt], 0, 0, 0);
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[mt][r]);
+    } else {
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        if (mt < n_mt) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < D / 16; ++ks) s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Ks, mt * 32, ks), qf[ks], s[mt], 0, 0, 0);
+          if (key0 + mt * 32 + 31 > qbase) {   // sub-tile touches the diagonal: mask keys after the query
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = key0 + mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+              if (key > query) s[mt][r] = -INFINITY;
+            }
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[mt][r]);
+        }
+      }
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m, tmax);
+    const float mc = m_new * c;
+    if (__any(m_new != m)) {   // rescale only when some query's maximum moved
+      const float alpha = fast_exp2(m * c - mc);
+      l *= alpha;
+#pragma unroll
+      for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+      m = m_new;
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      if (FULL || mt < n_mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = fast_exp2(fmaf(s[mt][r], c, -mc));
+          s[mt][r] = p;
+          psum += p;
+        }
+        // O^T += V^T P^T: the probabilities' k-slots are keys 16 st + 4 g + {0..3, 8..11}, which is
+        // exactly what the transposing read delivers
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 pf = frag_regs(s[mt], st, 1.f);
+#pragma unroll
+          for (int i = 0; i < D / 32; ++i) o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.cols(Vs, mt * 32 + st * 16, i), pf, o[i], 0, 0, 0);
+        }
+      }
+    }
+    l += psum;
+  };
+  for (int kt = 0; kt + 1 < n_kt; ++kt) tile_step(kt, std::true_type{});
+  tile_step(n_kt - 1, std::false_type{});
+  l += __shfl_xor(l, 32, 64);
+  const float inv = 1.f / l;
+  bf16_t* out = ctx + ((size_t)b * S + query) * h + (size_t)head * D;
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      u32x2 v;
+      v.x = pack2(o[i][rg * 4 + 0] * inv, o[i][rg * 4 + 1] * inv);
+      v.y = pack2(o[i][rg * 4 + 2] * inv, o[i][rg * 4 + 3] * inv);
+      *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
+    }
+  if (g == 0) lse[((size_t)b * H + head) * S + query] = m * c + log2f(l);
+}
+
 // ------------------------------------------------------------------ backward: delta
 // delta[b][head][q] = sum_d dO[b][q][head*D + d] * O[b][q][head*D + d]
 template <int D>
@@ -319,6 +516,105 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
       }
     }
   }
+  bf16_t* out = dqkv + ((size_t)b * S + query) * ld + (size_t)head * D;
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      u32x2 v;
+      v.x = pack2(dq[i][rg * 4 + 0], dq[i][rg * 4 + 1]);
+      v.y = pack2(dq[i][rg * 4 + 2], dq[i][rg * 4 + 3]);
+      *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
+    }
+}
+
+// dQ for head dimension 64 with direct loads: K and V tiles as they lie in memory; K is read by
+// rows for the scores and transposed for dQ^T += K^T dS^T.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                 bf16_t* __restrict__ dqkv, int S, int H) {
+  constexpr int D = 64, KT = 128, TILE = KT * D * 2, STAGE = 2 * TILE;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
+  const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
+  const int h = H * D;
+  const size_t ld = 3 * (size_t)h;
+  int tile, head, b;
+  attn_block(tile, head, b, true);
+  const int q0 = tile * 128;
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lrow = lane & 31, g = lane >> 5;
+  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * D;
+  const bf16_t* Kg = base + h;
+  const bf16_t* Vg = base + 2 * h;
+  const int qbase = q0 + 32 * w, query = qbase + lrow;
+  const float scale = rsqrtf((float)D), c = LOG2E * scale;
+  Frag64 fr;
+  fr.init(lane);
+  auto issue = [&](int kt) {
+    const unsigned st = lds0 + (kt & 1) * STAGE;
+    issue_tile64<KT, 4>(Kg + (size_t)kt * KT * ld, ld, st, w, lane);
+    issue_tile64<KT, 4>(Vg + (size_t)kt * KT * ld, ld, st + TILE, w, lane);
+  };
+  const int n_kt = (q0 + 128) / KT;
+  issue(0);
+
+  bf16x8 qf[D / 16], dof[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    Frag f;
+    f.u = *(const u32x4*)(base + (size_t)query * ld + ks * 16 + g * 8);
+    qf[ks] = f.v;
+    f.u = *(const u32x4*)(dout + ((size_t)b * S + query) * h + (size_t)head * D + ks * 16 + g * 8);
+    dof[ks] = f.v;
+  }
+  const float my_lse = lse[((size_t)b * H + head) * S + query];
+  const float my_delta = delta[((size_t)b * H + head) * S + query];
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
+
+  auto tile_step = [&](int kt, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const int key0 = kt * KT;
+    wait_vm<0>();
+    lds_barrier_visible();
+    if (kt + 1 < n_kt) issue(kt + 1);
+    const unsigned Ks = lds0 + (kt & 1) * STAGE, Vs = Ks + TILE;
+    const int n_mt = FULL ? 4 : min(4, (qbase + 31 - key0) / 32 + 1);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      if (FULL || mt < n_mt) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Ks, mt * 32, ks), qf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Vs, mt * 32, ks), dof[ks], dp, 0, 0, 0);
+        }
+        const bool diag = !FULL && key0 + mt * 32 + 31 > qbase;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = fast_exp2(fmaf(s[r], c, -my_lse));
+          if (diag) {
+            const int key = key0 + mt * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+            if (key > query) p = 0.f;
+          }
+          s[r] = p * (dp[r] - my_delta);   // dS^T (before the 1/sqrt(d) factor)
+        }
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 dsf = frag_regs(s, st, scale);
+#pragma unroll
+          for (int i = 0; i < D / 32; ++i) dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.cols(Ks, mt * 32 + st * 16, i), dsf, dq[i], 0, 0, 0);
+        }
+      }
+    }
+  };
+  for (int kt = 0; kt + 1 < n_kt; ++kt) tile_step(kt, std::true_type{});
+  tile_step(n_kt - 1, std::false_type{});
+
   bf16_t* out = dqkv + ((size_t)b * S + query) * ld + (size_t)head * D;
 #pragma unroll
   for (int i = 0; i < D / 32; ++i)
@@ -471,6 +767,137 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
     }
 }
 
+// dK, dV for head dimension 64 with direct loads: Q and dO tiles of 64 queries as they lie in
+// memory, read by rows for S = Q K^T and dP = dO V^T and transposed for dV += P^T dO, dK += dS^T Q.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                                  const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                  bf16_t* __restrict__ dqkv, int S, int H) {
+  constexpr int D = 64, QT = 64, TILE = QT * D * 2, STAGE = 2 * TILE;   // stage = Q tile | dO tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
+  const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
+  float* stat = (float*)(smem_attn + 2 * STAGE);   // [2 stages][lse | delta][QT]
+  const int h = H * D;
+  const size_t ld = 3 * (size_t)h;
+  int tile, head, b;
+  attn_block(tile, head, b, false);
+  const int k0 = tile * 128;
+  const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lrow = lane & 31, g = lane >> 5;
+  const bf16_t* base = qkv + (size_t)b * S * ld + (size_t)head * D;
+  const bf16_t* dOg = dout + (size_t)b * S * h + (size_t)head * D;
+  const float* lse_g = lse + ((size_t)b * H + head) * S;
+  const float* delta_g = delta + ((size_t)b * H + head) * S;
+  const int kbase = k0 + 32 * w, key = kbase + lrow;
+  const float scale = rsqrtf((float)D), c = LOG2E * scale;
+  Frag64 fr;
+  fr.init(lane);
+  auto issue = [&](int t) {   // query tile t of this workgroup: queries k0 + 64 t ..
+    const unsigned st = lds0 + (t & 1) * STAGE;
+    const int qq = k0 + t * QT;
+    issue_tile64<QT, 4>(base + (size_t)qq * ld, ld, st, w, lane);
+    issue_tile64<QT, 4>(dOg + (size_t)qq * h, (size_t)h, st + TILE, w, lane);
+  };
+  const int n_t = (S - k0) / QT;
+  issue(0);
+
+  bf16x8 kf[D / 16], vf[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    Frag f;
+    f.u = *(const u32x4*)(base + h + (size_t)key * ld + ks * 16 + g * 8);
+    kf[ks] = f.v;
+    f.u = *(const u32x4*)(base + 2 * h + (size_t)key * ld + ks * 16 + g * 8);
+    vf[ks] = f.v;
+  }
+  f32x16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+  float lse_r = 0.f, delta_r = 0.f;
+  if (tid < QT) {
+    lse_r = lse_g[k0 + tid];
+    delta_r = delta_g[k0 + tid];
+  }
+
+  auto tile_step = [&](int t, auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const int qq0 = k0 + t * QT;
+    float* lse_s = stat + (t & 1) * 2 * QT;
+    float* delta_s = lse_s + QT;
+    if (tid < QT) {   // this tile's per-query statistics (fetched one tile ago); the buffer was last read two tiles ago
+      lse_s[tid] = lse_r;
+      delta_s[tid] = delta_r;
+    }
+    wait_vm<0>();
+    lds_barrier_visible();
+    if (t + 1 < n_t) {
+      issue(t + 1);
+      if (tid < QT) {
+        lse_r = lse_g[qq0 + QT + tid];
+        delta_r = delta_g[qq0 + QT + tid];
+      }
+    }
+    const unsigned Qs = lds0 + (t & 1) * STAGE, Os = Qs + TILE;
+    // sub-tiles of 32 queries; those entirely before this wavefront's keys contribute nothing
+    const int first_mt = FULL ? 0 : max(0, (kbase - qq0) / 32);
+#pragma unroll
+    for (int mt = 0; mt < QT / 32; ++mt) {
+      if (FULL || mt >= first_mt) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Qs, mt * 32, ks), kf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Os, mt * 32, ks), vf[ks], dp, 0, 0, 0);
+        }
+        const bool diag = !FULL && qq0 + mt * 32 < kbase + 31;
+        // p in s, dS in dp (in place); the per-query statistics come four at a time
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int qb = mt * 32 + rg * 8 + g * 4;
+          const float4 l4 = *(const float4*)(lse_s + qb);
+          const float4 d4 = *(const float4*)(delta_s + qb);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = rg * 4 + e;
+            float p = fast_exp2(fmaf(s[r], c, -lv[e]));
+            if (diag && key > qq0 + qb + e) p = 0.f;
+            s[r] = p;
+            dp[r] = p * (dp[r] - dl[e]);
+          }
+        }
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          bf16x8 pf = frag_regs(s, st, 1.f);
+          bf16x8 dsf = frag_regs(dp, st, scale);
+#pragma unroll
+          for (int i = 0; i < D / 32; ++i) {
+            dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, fr.cols(Os, mt * 32 + st * 16, i), dv[i], 0, 0, 0);
+            dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, fr.cols(Qs, mt * 32 + st * 16, i), dk[i], 0, 0, 0);
+          }
+        }
+      }
+    }
+  };
+  // the first two query tiles overlap this workgroup's 128 keys; all later ones lie after them
+  int t = 0;
+  for (; t < n_t && t < 2; ++t) tile_step(t, std::false_type{});
+  for (; t < n_t; ++t) tile_step(t, std::true_type{});
+
+  // dk[i][r]: key = kbase + (r/4)*8 + 4g + r%4, d = i*32 + lane%32
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kk = kbase + (r >> 2) * 8 + g * 4 + (r & 3);
+      bf16_t* row = dqkv + ((size_t)b * S + kk) * ld + (size_t)head * D + i * 32 + lrow;
+      row[h] = f2bf(dk[i][r]);
+      row[2 * h] = f2bf(dv[i][r]);
+    }
+}
+
 template <int D>
 constexpr size_t attn_dq_lds() { return (size_t)(2 * 128 * (D + LDS_PAD) + D * (128 + LDS_PAD)) * sizeof(bf16_t); }
 template <int D>
@@ -484,7 +911,11 @@ static inline int ok() { return hipGetLastError() == hipSuccess ? KARMA_OK : KAR
 int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq, int heads, int d, hipStream_t s) {
   if (seq % 128 || (d != 64 && d != 128) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
   dim3 grid(seq / 128, heads, batch);
-  if (d == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), 0, s, qkv, ctx, lse, seq, heads);
+  if (d == 64) {
+    constexpr int lds = 2 * 2 * 128 * 64 * 2;   // two stages of (K tile, V tile)
+    (void)hipFuncSetAttribute((const void*)attn_fwd_dl_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipLaunchKernelGGL(attn_fwd_dl_kernel, grid, dim3(256), lds, s, qkv, ctx, lse, seq, heads);
+  }
   else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, s, qkv, ctx, lse, seq, heads);
   return ok();
 }
@@ -492,13 +923,21 @@ int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq
 template <int D>
 static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* dctx, const float* lse,
                        const float* delta, bf16_t* dqkv, int seq, int heads) {
-  constexpr size_t l1 = attn_dq_lds<D>(), l2 = attn_dkv_lds<D>();
-  if (l1 > 64 * 1024)
-    (void)hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l1);
-  if (l2 > 64 * 1024)
-    (void)hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<D>, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+  if constexpr (D == 64) {
+    constexpr int l1 = 2 * 2 * 128 * 64 * 2;                       // two stages of (K tile, V tile)
+    constexpr int l2 = 2 * 2 * 64 * 64 * 2 + 2 * 2 * 64 * 4;       // two stages of (Q tile, dO tile) + their lse, delta
+    (void)hipFuncSetAttribute((const void*)attn_bwd_dq_dl_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, l1);
+    hipLaunchKernelGGL(attn_bwd_dq_dl_kernel, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    hipLaunchKernelGGL(attn_bwd_dkv_dl_kernel, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+  } else {
+    constexpr size_t l1 = attn_dq_lds<D>(), l2 = attn_dkv_lds<D>();
+    if (l1 > 64 * 1024)
+      (void)hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l1);
+    if (l2 > 64 * 1024)
+      (void)hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<D>, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+  }
 }
 
 int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,

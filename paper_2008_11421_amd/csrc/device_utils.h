@@ -3,6 +3,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
+
 #include "kernels.h"
 
 namespace karma {
@@ -31,6 +33,39 @@ __device__ __forceinline__ unsigned pack2(float lo, float hi) {
   f32x2_t f = {lo, hi};
   bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
   return __builtin_bit_cast(unsigned, b);
+}
+
+// ---- gfx950: direct global -> LDS loads and transposing LDS reads
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+#define KARMA_LDS(T) __attribute__((address_space(3))) T
+
+// 16 bytes per lane from g (per-lane address) to LDS byte address lds (wavefront-uniform) + 16*lane.
+// The s_nop covers the SALU-writes-M0 -> LDS-DMA hazard, which the assembler does not see in inline code.
+__device__ __forceinline__ void load_to_lds16(const bf16_t* g, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds)), "v"(g)
+               : "memory");
+}
+// LDS-only workgroup barrier written with builtins, so that the compiler's own wait-count
+// bookkeeping knows that every LDS read issued before it has returned.
+__device__ __forceinline__ void lds_barrier_visible() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), other counters untouched
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Two transposing 8-byte reads make one MFMA k-operand (k-slots 0..3 from `at`, 4..7 from `at2`).
+// In each group of 16 lanes, lane 4e+q supplies the address of (k-row e, columns 4q..4q+3) and
+// receives, for the column that is its own index in the group, k-rows 0..3.
+__device__ __forceinline__ bf16x8 read_tr_pair(unsigned at, unsigned at2) {
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((KARMA_LDS(s16x4_t)*)(uintptr_t)at);
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((KARMA_LDS(s16x4_t)*)(uintptr_t)at2);
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 constexpr int LDS_PAD = 8;   // elements: a 16-byte skew per row keeps ds_read_b128 conflict-free

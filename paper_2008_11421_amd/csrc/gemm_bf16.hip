@@ -291,29 +291,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
 // The tile stream is continuous across work items: while the last k-tile of an item is being
 // multiplied, the first k-tile of the next item is already landing in the other stage; the
 // epilogue's fp32 strip aliases the stage of the last tile (plus a small margin).
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x8_t __attribute__((ext_vector_type(8)));
-#define KARMA_LDS(T) __attribute__((address_space(3))) T
-
-// 16 bytes per lane from g (per-lane address) to LDS byte address lds (wavefront-uniform) + 16*lane.
-// The s_nop covers the SALU-writes-M0 -> LDS-DMA hazard, which the assembler does not see in inline code.
-__device__ __forceinline__ void load_to_lds16(const bf16_t* g, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds)), "v"(g)
-               : "memory");
-}
-// LDS-only workgroup barrier written with builtins, so that the compiler's own wait-count
-// bookkeeping knows that every LDS read issued before it has returned.
-__device__ __forceinline__ void lds_barrier_visible() {
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), other counters untouched
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                          int M, int N, int K, int lda, int ldb, int tiles_m,
