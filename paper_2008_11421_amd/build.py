@@ -15,7 +15,8 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-
           "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wno-unused-command-line-argument", "-Wno-option-ignored"]
-HOST_SIMD = ["-mavx2", "-mfma", "-mf16c"]
+HOST_SIMD = ["-mavx2", "-mfma", "-mf16c", "-fno-math-errno"]
+HOST_SIMD_512 = HOST_SIMD + ["-mavx512f", "-mavx512bw", "-mavx512vl", "-mavx512dq", "-mprefer-vector-width=512"]
 
 
 def sources():
@@ -28,7 +29,8 @@ def compile_one(src):
     if src.endswith(".hip"):
         cmd += DEVICE + ["-x", "hip"]
     else:
-        cmd += HOST_SIMD if src.startswith("host_") else []
+        if src.startswith("host_"):
+            cmd += HOST_SIMD_512 if "avx512" in src else HOST_SIMD
     cmd += ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -81,101 +81,46 @@ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
-// The update loops are instantiated per gradient / output format so that the inner loop is
-// branch-free and the compiler can vectorise it (AVX2 + FMA).
-template <bool G_BF16>
-static inline float load_g(const void* g, size_t i) {
-  if (G_BF16) {
-    uint32_t u = (uint32_t)((const uint16_t*)g)[i] << 16;
-    float f;
-    std::memcpy(&f, &u, 4);
-    return f;
-  }
-  return ((const float*)g)[i];
-}
-template <bool O_BF16>
-static inline void store_w(void* out, size_t i, float w) {
-  if (O_BF16) {
-    uint32_t u;
-    std::memcpy(&u, &w, 4);
-    uint32_t r = u + 0x7fffu + ((u >> 16) & 1u);
-    // NaN stays NaN (quiet bit set); weights are finite in practice, the select keeps the loop branch-free
-    uint32_t is_nan = (u & 0x7fffffffu) > 0x7f800000u ? 0xffffffffu : 0u;
-    r = (r & ~is_nan) | ((u | 0x400000u) & is_nan);
-    ((uint16_t*)out)[i] = (uint16_t)(r >> 16);
-  } else {
-    ((float*)out)[i] = w;
-  }
-}
+}  // namespace karma
 
-template <bool G_BF16, bool O_BF16>
-static void sgd_loop(float* __restrict__ w, const void* __restrict__ g, size_t n, float lr, void* __restrict__ out) {
-  for (size_t i = 0; i < n; ++i) {
-    float nw = w[i] - lr * load_g<G_BF16>(g, i);
-    w[i] = nw;
-    store_w<O_BF16>(out, i, nw);
-  }
-}
+#define HOST_OPTIM_NS avx2
+#include "host_optim_loops.h"
+#undef HOST_OPTIM_NS
 
-template <bool G_BF16, bool O_BF16>
-static void adam_loop(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v, const void* __restrict__ g,
-                      size_t n, float lr, float beta1, float beta2, float eps, float c1, float c2,
-                      void* __restrict__ out) {
-  const float ob1 = 1.0f - beta1, ob2 = 1.0f - beta2;
-  for (size_t i = 0; i < n; ++i) {
-    float gi = load_g<G_BF16>(g, i);
-    float mi = beta1 * m[i] + ob1 * gi;
-    float vi = beta2 * v[i] + ob2 * gi * gi;
-    m[i] = mi;
-    v[i] = vi;
-    float nw = w[i] - lr * (mi * c1) / (std::sqrt(vi * c2) + eps);
-    w[i] = nw;
-    store_w<O_BF16>(out, i, nw);
-  }
-}
+namespace karma {
 
-template <bool G_BF16, bool O_BF16>
-static void sgd_momentum_loop(float* __restrict__ w, float* __restrict__ buf, const void* __restrict__ g, size_t n, float lr,
-                              float mu, void* __restrict__ out) {
-  for (size_t i = 0; i < n; ++i) {
-    float bi = mu * buf[i] + load_g<G_BF16>(g, i);
-    buf[i] = bi;
-    float nw = w[i] - lr * bi;
-    w[i] = nw;
-    store_w<O_BF16>(out, i, nw);
-  }
+// the same loops built for AVX-512 (host_optim_avx512.cpp)
+namespace avx512 {
+void sgd_update(float* w, const void* g, bool g_is_bf16, size_t n, float lr, void* out, bool out_is_bf16);
+void sgd_momentum_update(float* w, float* buf, const void* g, bool g_is_bf16, size_t n, float lr, float mu, void* out,
+                         bool out_is_bf16);
+void adam_update(float* w, float* m, float* v, const void* g, bool g_is_bf16, size_t n, float lr, float beta1, float beta2,
+                 float eps, float c1, float c2, void* out, bool out_is_bf16);
+}  // namespace avx512
+
+static bool wide_vectors() {
+  static const bool yes = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") &&
+                          __builtin_cpu_supports("avx512vl") && __builtin_cpu_supports("avx512dq");
+  return yes;
 }
 
 void sgd_momentum_update(float* w, float* buf, const void* g, bool g_is_bf16, size_t n, float lr, float mu, void* out,
                          bool out_is_bf16) {
-  if (g_is_bf16) {
-    if (out_is_bf16) sgd_momentum_loop<true, true>(w, buf, g, n, lr, mu, out);
-    else sgd_momentum_loop<true, false>(w, buf, g, n, lr, mu, out);
-  } else {
-    if (out_is_bf16) sgd_momentum_loop<false, true>(w, buf, g, n, lr, mu, out);
-    else sgd_momentum_loop<false, false>(w, buf, g, n, lr, mu, out);
-  }
+  if (wide_vectors()) avx512::sgd_momentum_update(w, buf, g, g_is_bf16, n, lr, mu, out, out_is_bf16);
+  else avx2::sgd_momentum_entry(w, buf, g, g_is_bf16, n, lr, mu, out, out_is_bf16);
 }
 
 void sgd_update(float* w, const void* g, bool g_is_bf16, size_t n, float lr, void* out, bool out_is_bf16) {
-  if (g_is_bf16) {
-    if (out_is_bf16) sgd_loop<true, true>(w, g, n, lr, out); else sgd_loop<true, false>(w, g, n, lr, out);
-  } else {
-    if (out_is_bf16) sgd_loop<false, true>(w, g, n, lr, out); else sgd_loop<false, false>(w, g, n, lr, out);
-  }
+  if (wide_vectors()) avx512::sgd_update(w, g, g_is_bf16, n, lr, out, out_is_bf16);
+  else avx2::sgd_entry(w, g, g_is_bf16, n, lr, out, out_is_bf16);
 }
 
 void adam_update(float* w, float* m, float* v, const void* g, bool g_is_bf16, size_t n, float lr, float beta1,
                  float beta2, float eps, uint64_t step, void* out, bool out_is_bf16) {
   const float c1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)step)));
   const float c2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)step)));
-  if (g_is_bf16) {
-    if (out_is_bf16) adam_loop<true, true>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-    else adam_loop<true, false>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-  } else {
-    if (out_is_bf16) adam_loop<false, true>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-    else adam_loop<false, false>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-  }
+  if (wide_vectors()) avx512::adam_update(w, m, v, g, g_is_bf16, n, lr, beta1, beta2, eps, c1, c2, out, out_is_bf16);
+  else avx2::adam_entry(w, m, v, g, g_is_bf16, n, lr, beta1, beta2, eps, c1, c2, out, out_is_bf16);
 }
 
 }  // namespace karma
