@@ -276,6 +276,17 @@ int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const v
                       const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* ws_dev,
                       uint64_t ws_bytes, void* stream);
 
+/* The same product with the GELU of the feed-forward layer (Sec. III-C, fully connected layer followed by its
+ * activation) folded into the kernel's output stage, bf16 output only.
+ * KARMA_GEMM_GELU_FWD: c_dev = a b^T + bias (the pre-activation, which backward needs) and aux_dev (bf16 [m][n],
+ * written) = GELU(c_dev as stored).  KARMA_GEMM_GELU_BWD: c_dev = (a b^T) * GELU'(aux_dev), aux_dev (read)
+ * holding the pre-activation; bias_dev must be NULL.  Layouts as the feed-forward layer has them: FWD takes both
+ * operands k-contiguous (flags 0), BWD takes b_dev strided (flags KARMA_GEMM_B_STRIDED).  Errors: KARMA_E_INVAL. */
+#define KARMA_GEMM_GELU_FWD 1u
+#define KARMA_GEMM_GELU_BWD 2u
+int karma_k_gemm_gelu_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev, void* aux_dev,
+                           uint32_t m, uint32_t n, uint32_t k, uint32_t flags, uint32_t mode, void* stream);
+
 /* LayerNorm over the last dimension (eps 1e-5, biased variance), bf16 in/out, fp32
  * statistics: stats_dev[2*row] = mean, [2*row+1] = 1/std.  h multiple of 8, <= 6144. */
 int karma_k_layernorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const void* beta_dev, void* y_dev,

@@ -18,6 +18,7 @@ STEP_APPLY_OPTIMIZER = 1
 STEP_PROFILE = 2
 STEP_KERNEL_TIMES = 4
 GEMM_A_STRIDED, GEMM_B_STRIDED, GEMM_OUT_F32, GEMM_ACCUMULATE = 1, 2, 4, 8
+GEMM_GELU_FWD, GEMM_GELU_BWD = 1, 2
 
 
 class LayerCost(C.Structure):

@@ -35,6 +35,20 @@ __device__ __forceinline__ unsigned pack2(float lo, float hi) {
   return __builtin_bit_cast(unsigned, b);
 }
 
+// GELU, tanh form: 0.5 x (1 + tanh(u)), u = sqrt(2/pi) (x + 0.044715 x^3).  With
+// sig = 1 / (1 + e^(-2u)) = (1 + tanh u) / 2 this is x * sig, and the derivative is
+// sig + 2 x sig (1 - sig) u'(x): one hardware exponential and one reciprocal per element.
+__device__ __forceinline__ float gelu_sig(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-2.885390081777927f * u));   // 2 log2(e)
+}
+__device__ __forceinline__ float gelu_f(float x) { return x * gelu_sig(x); }
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  const float sg = gelu_sig(x);
+  const float du = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
+  return sg + 2.f * x * sg * (1.f - sg) * du;
+}
+
 // ---- gfx950: direct global -> LDS loads and transposing LDS reads
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));

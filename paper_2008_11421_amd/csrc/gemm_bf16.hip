@@ -25,7 +25,9 @@ struct GemmEpilogue {
   int ldc;
   int out_f32;             // store fp32 instead of bf16
   int accumulate;          // fp32 output only: C += result
+  bf16_t* aux;             // [M][ldc]: octet<1> writes GELU(C) there, octet<2> multiplies the result by GELU'(aux) (bf16 C only)
   // eight consecutive columns n..n+7 of row m (n multiple of 8); cols = how many are inside the matrix
+  template <int ACT = 0>
   __device__ __forceinline__ void octet(int m, int n, int cols, const float4& lo, const float4& hi) const {
     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     const size_t at = (size_t)m * ldc + n;
@@ -51,10 +53,25 @@ struct GemmEpilogue {
 #pragma unroll
           for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(r[e] << 16); v[2 * e + 1] += __uint_as_float(r[e] & 0xffff0000u); }
         }
+        if (ACT == 2) {
+          u32x4 r = *(const u32x4*)(aux + at);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[2 * e] *= gelu_grad_f(__uint_as_float(r[e] << 16));
+            v[2 * e + 1] *= gelu_grad_f(__uint_as_float(r[e] & 0xffff0000u));
+          }
+        }
         u32x4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = pack2(v[2 * e], v[2 * e + 1]);
         *(u32x4*)((bf16_t*)C + at) = o;
+        if (ACT == 1) {   // the activation of the value as stored (what a separate pass over C would compute)
+          u32x4 a2;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            a2[e] = pack2(gelu_f(__uint_as_float(o[e] << 16)), gelu_f(__uint_as_float(o[e] & 0xffff0000u)));
+          *(u32x4*)(aux + at) = a2;
+        }
       }
     } else {
       for (int e = 0; e < cols; ++e) {
@@ -65,7 +82,10 @@ struct GemmEpilogue {
           c[at + e] = accumulate ? c[at + e] + x : x;
         } else {
           if (residual) x += bf2f(residual[at + e]);
-          ((bf16_t*)C)[at + e] = f2bf(x);
+          if (ACT == 2) x *= gelu_grad_f(bf2f(aux[at + e]));
+          const bf16_t stored = f2bf(x);
+          ((bf16_t*)C)[at + e] = stored;
+          if (ACT == 1) aux[at + e] = f2bf(gelu_f(bf2f(stored)));
         }
       }
     }
@@ -81,7 +101,7 @@ struct GemmEpilogue {
 // stores are not waited for: they drain while the next item computes.
 // CONV 1: A is an NHWC tensor gathered through a convolution (rows = output pixels, forward
 // and input-gradient passes); CONV 2: B is (reduction index = output pixels, weight gradient).
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int CONV = 0>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int CONV = 0, int ACT = 0>
 __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) void gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                    const bf16_t* __restrict__ B, int M, int N, int K,
                                                                    int lda, int ldb, int tiles_m, int tiles_n,
@@ -266,7 +286,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
             if (n + 8 <= N && (N & 3) == 0) { *(float4*)dst = v; *(float4*)(dst + 4) = u; }
             else for (int e = 0; e < N - n && e < 8; ++e) dst[e] = vv[e];
           } else {
-            ep.octet(m, n, min(8, N - n), v, u);
+            ep.template octet<ACT>(m, n, min(8, N - n), v, u);
           }
         }
       }
@@ -291,7 +311,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
 // The tile stream is continuous across work items: while the last k-tile of an item is being
 // multiplied, the first k-tile of the next item is already landing in the other stage; the
 // epilogue's fp32 strip aliases the stage of the last tile (plus a small margin).
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                          int M, int N, int K, int lda, int ldb, int tiles_m,
                                                                          int tiles_n, int splits, int k_per_split,
@@ -508,7 +528,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
           *(float4*)dst = v;
           *(float4*)(dst + 4) = u;
         } else {
-          ep.octet(m, n, 8, v, u);
+          ep.template octet<ACT>(m, n, 8, v, u);
         }
       }
     }
@@ -596,17 +616,19 @@ static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 bloc
     constexpr int STAGE = (BM + BN) * BK * 2, STRIP = WGM * WGN * 32 * (BN / WGN + 4) * 4;
     constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
     const int lds = 2 * STAGE + 2 * EXTRA;
-#define KARMA_DL_LAUNCH(AK, BKC)                                                                                  \
+#define KARMA_DL_LAUNCH(AK, BKC, ACT)                                                                             \
   do {                                                                                                            \
-    auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC>;                                               \
+    auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC, ACT>;                                          \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);                \
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits, \
                        k_per_split, ep, (float*)g.ws);                                                            \
   } while (0)
-    if (g.a_kc && g.b_kc) KARMA_DL_LAUNCH(true, true);
-    else if (g.a_kc && !g.b_kc) KARMA_DL_LAUNCH(true, false);
-    else if (!g.a_kc && g.b_kc) KARMA_DL_LAUNCH(false, true);
-    else KARMA_DL_LAUNCH(false, false);
+    if (g.act == 1) KARMA_DL_LAUNCH(true, true, 1);          // the layouts were checked by the caller
+    else if (g.act == 2) KARMA_DL_LAUNCH(true, false, 2);
+    else if (g.a_kc && g.b_kc) KARMA_DL_LAUNCH(true, true, 0);
+    else if (g.a_kc && !g.b_kc) KARMA_DL_LAUNCH(true, false, 0);
+    else if (!g.a_kc && g.b_kc) KARMA_DL_LAUNCH(false, true, 0);
+    else KARMA_DL_LAUNCH(false, false, 0);
 #undef KARMA_DL_LAUNCH
   }
 }
@@ -620,7 +642,7 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   // split the reduction when the tiles alone cannot fill the chip (weight gradients:
   // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
   int splits = 1;
-  if (g.ws && g.ldc == g.N && tiles < cus) {
+  if (g.ws && g.ldc == g.N && tiles < cus && !g.act) {
     // the split count that best fills whole rounds of the chip, fewer splits preferred: every
     // split writes and re-reads an M x N fp32 partial, which is weighed against the operand
     // bytes of the whole product (a skinny weight gradient with a very long reduction takes
@@ -639,12 +661,12 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   k_per_split = (k_per_split + BK - 1) / BK * BK;
   splits = (g.K + k_per_split - 1) / k_per_split;
   const size_t lds = (size_t)2 * (BM + BN) * (BK + LDS_PAD) * sizeof(bf16_t);
-  GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate};
+  GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate, (bf16_t*)g.aux};
   // a multiple of 8 workgroups: the kernel deals work items out per XCD
   dim3 grid(std::min((tiles * splits + 7) / 8 * 8, std::max(8, cus / 8 * 8))), block(WGM * WGN * 64);
-#define KARMA_GEMM_LAUNCH(AK, BKC, CV)                                                                      \
+#define KARMA_GEMM_LAUNCH(AK, BKC, CV, ACT)                                                                 \
   do {                                                                                                  \
-    auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, AK, BKC, CV>;                                    \
+    auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, AK, BKC, CV, ACT>;                               \
     if (lds > 64 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,  \
                        k_per_split, ep, (float*)g.ws, g.conv);                                          \
@@ -658,12 +680,14 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   if (direct) {
     launch_direct<BM, BN, BK, WGM, WGN>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
   } else if (CONVS) {   // the convolution variants exist for one tile shape only
-    if (g.conv_mode == 1) KARMA_GEMM_LAUNCH(true, true, (CONVS ? 1 : 0));
-    else KARMA_GEMM_LAUNCH(false, false, (CONVS ? 2 : 0));
-  } else if (g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(true, true, 0);
-  else if (g.a_kc && !g.b_kc) KARMA_GEMM_LAUNCH(true, false, 0);
-  else if (!g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(false, true, 0);
-  else KARMA_GEMM_LAUNCH(false, false, 0);
+    if (g.conv_mode == 1) KARMA_GEMM_LAUNCH(true, true, (CONVS ? 1 : 0), 0);
+    else KARMA_GEMM_LAUNCH(false, false, (CONVS ? 2 : 0), 0);
+  } else if (g.act == 1) KARMA_GEMM_LAUNCH(true, true, 0, 1);
+  else if (g.act == 2) KARMA_GEMM_LAUNCH(true, false, 0, 2);
+  else if (g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(true, true, 0, 0);
+  else if (g.a_kc && !g.b_kc) KARMA_GEMM_LAUNCH(true, false, 0, 0);
+  else if (!g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(false, true, 0, 0);
+  else KARMA_GEMM_LAUNCH(false, false, 0, 0);
 #undef KARMA_GEMM_LAUNCH
   if (splits > 1) {
     const size_t mn = (size_t)g.M * g.N;
@@ -706,6 +730,10 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
   if (g.conv_mode != 2 && (g.b_kc ? (g.ldb % 8) : (g.ldb % 4 || g.N % 4))) return KARMA_E_INVAL;
   if (g.conv_mode < 0 || g.conv_mode > 2) return KARMA_E_INVAL;
   if (g.accumulate && !g.out_f32) return KARMA_E_INVAL;
+  if (g.act < 0 || g.act > 2 || (g.act && (!g.aux || g.out_f32 || g.residual || g.conv_mode))) return KARMA_E_INVAL;
+  // the fused forms exist for the layouts of the feed-forward layer: forward x W1^T (both operands
+  // k-contiguous), backward dy W2 (second operand strided)
+  if ((g.act == 1 && !(g.a_kc && g.b_kc)) || (g.act == 2 && !(g.a_kc && !g.b_kc))) return KARMA_E_INVAL;
   if (g.residual && g.out_f32) return KARMA_E_INVAL;
   if (g.conv_mode) {
     const ConvGather& cg = g.conv;
@@ -724,6 +752,26 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
 }  // namespace karma
 
 using namespace karma;
+
+extern "C" int karma_k_gemm_gelu_bf16(const void* a, const void* b, void* c, const void* bias, void* aux, uint32_t m,
+                                      uint32_t n, uint32_t k, uint32_t flags, uint32_t mode, void* stream) {
+  if (mode != KARMA_GEMM_GELU_FWD && mode != KARMA_GEMM_GELU_BWD) return KARMA_E_INVAL;
+  if (flags & (KARMA_GEMM_OUT_F32 | KARMA_GEMM_ACCUMULATE)) return KARMA_E_INVAL;
+  GemmArgs g{};
+  g.A = (const bf16_t*)a;
+  g.B = (const bf16_t*)b;
+  g.C = c;
+  g.bias = (const bf16_t*)bias;
+  g.M = (int)m; g.N = (int)n; g.K = (int)k;
+  g.a_kc = !(flags & KARMA_GEMM_A_STRIDED);
+  g.b_kc = !(flags & KARMA_GEMM_B_STRIDED);
+  g.lda = g.a_kc ? (int)k : (int)m;
+  g.ldb = g.b_kc ? (int)k : (int)n;
+  g.ldc = (int)n;
+  g.act = (int)mode;
+  g.aux = aux;
+  return gemm_bf16(g, (hipStream_t)stream);
+}
 
 extern "C" int karma_k_gemm_bf16(const void* a, const void* b, void* c, const void* bias, const void* residual,
                                  uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* ws, uint64_t ws_bytes,

@@ -43,6 +43,10 @@ struct GemmArgs {
   // conv_mode 2: B (strided) is gathered, k = output pixels, n = (tap, channel)
   int conv_mode;
   ConvGather conv;
+  // act 1: C = A B^T + bias as usual and aux (bf16 [M][ldc], written) = GELU(C as stored);
+  // act 2: C = (A B^T) * GELU'(aux), aux (read) holding the pre-activation.  bf16 C, no residual, no split.
+  int act;
+  void* aux;
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
 // While non-null on the calling thread, gemm_bf16 calls record an event before and after

@@ -112,6 +112,22 @@ int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf
   return gemm_raw(A, B, C, bias, res, M, N, K, a_kc, b_kc, out_f32, acc, s, ws, ws_bytes);
 }
 
+// the product with the feed-forward GELU folded into its output stage (mode 1: aux = GELU(C) written;
+// mode 2: C = (A B^T) * GELU'(aux))
+int gemm_gelu(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, bf16_t* aux, int M, int N, int K, bool a_kc,
+              bool b_kc, int mode, hipStream_t s) {
+  GemmArgs g{};
+  g.A = A; g.B = B; g.C = C; g.bias = bias;
+  g.M = M; g.N = N; g.K = K;
+  g.a_kc = a_kc; g.b_kc = b_kc;
+  g.lda = a_kc ? K : M;
+  g.ldb = b_kc ? K : N;
+  g.ldc = N;
+  g.act = mode;
+  g.aux = aux;
+  return gemm_bf16(g, s);
+}
+
 #define TRY(call)          \
   do {                     \
     int st_ = (call);      \
@@ -226,8 +242,7 @@ int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   TRY(attention_fwd(qkv, ctx, (float*)(S + sv.lse), d.B, d.S, d.H, d.D, s));
   TRY(gemm(ctx, W(WO), r1, W(BO), x, d.T, d.h, d.h, true, true, false, false, s));
   TRY(layernorm_fwd(r1, W(LN2_G), W(LN2_B), m, (float*)(S + sv.stats2), d.T, d.h, s));
-  TRY(gemm(m, W(W1), f1, W(B1), nullptr, d.T, d.ffn, d.h, true, true, false, false, s));
-  TRY(gelu_fwd(f1, g, (size_t)d.T * d.ffn, s));
+  TRY(gemm_gelu(m, W(W1), f1, W(B1), g, d.T, d.ffn, d.h, true, true, 1, s));   // f1 = m W1^T + b1, g = GELU(f1)
   // a recompute whose output nobody needs stops here: backward only reads the internals
   if (io.out) TRY(gemm(g, W(W2), io.out, W(B2), r1, d.T, d.h, d.ffn, true, true, false, false, s));
   return KARMA_OK;
@@ -264,10 +279,9 @@ int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   auto G = [&](int t) { return c.g_ptr(i, t, io.g); };
 
   // FC2: y = r1 + g W2^T + b2
-  TRY(gemm(dy, W(W2), wide, nullptr, nullptr, d.T, d.ffn, d.h, true, false, false, false, s));     // dg = dy W2
+  TRY(gemm_gelu(dy, W(W2), wide, nullptr, (bf16_t*)f1, d.T, d.ffn, d.h, true, false, 2, s));         // df1 = (dy W2) * GELU'(f1)
   TRY(gemm(dy, g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));        // dW2 = dy^T g
   TRY(colsum_bf16(dy, (float*)G(B2), part, d.T, d.h, s));
-  TRY(gelu_bwd(f1, wide, wide, (size_t)d.T * d.ffn, s));                                            // df1
   // FC1
   TRY(gemm(wide, W(W1), t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
   TRY(gemm(wide, m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));      // dW1 = df1^T m

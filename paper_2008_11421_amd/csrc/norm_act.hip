@@ -7,11 +7,10 @@
 #include <hip/hip_runtime.h>
 
 #include "karma.h"
+#include "device_utils.h"
 #include "kernels.h"
 
 namespace karma {
-
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 __device__ __forceinline__ float bf2f_(bf16_t b) { return __uint_as_float((unsigned)b << 16); }
 __device__ __forceinline__ bf16_t f2bf_(float f) {
@@ -233,16 +232,6 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __res
 }
 
 // ---- GELU (tanh form) ------------------------------------------------------------
-__device__ __forceinline__ float gelu_f(float x) {
-  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  return 0.5f * x * (1.f + tanhf(u));
-}
-__device__ __forceinline__ float gelu_grad_f(float x) {
-  const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  const float t = tanhf(u);
-  const float du = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
-  return 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * du;
-}
 __global__ void gelu_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y, size_t nvec) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= nvec) return;

@@ -110,6 +110,37 @@ def test_gemm_split_k(g, m, n, k, flags):
     assert g.rel_l2(back(c), ref) <= TOL_BF16
 
 
+@pytest.mark.parametrize("m,n,k", [(512, 512, 256), (200, 136, 72), (1024, 768, 1024)])
+def test_gemm_with_gelu_output_stage(g, m, n, k):
+    """The feed-forward products with GELU folded into the kernel's output stage: forward writes the
+    pre-activation and its GELU; backward multiplies the product by GELU' of a stored pre-activation."""
+    import torch
+    a, ad = bf(si.normal(41, (m, k), 0.5))
+    b, bd = bf(si.normal(42, (n, k), 0.1))
+    bias, biasd = bf(si.normal(43, (n,)))
+    pre = a @ b.T + bias
+    c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    act = torch.empty_like(c)
+    g.call(K.lib().karma_k_gemm_gelu_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c), g.ptr(biasd), g.ptr(act), m, n, k, 0,
+           K.GEMM_GELU_FWD, g.stream_ptr())
+    assert g.rel_l2(back(c), pre) <= TOL_BF16
+    # the activation is taken of the value as stored (one rounding away from the exact pre-activation)
+    assert g.rel_l2(back(act), nn.gelu_fwd(back(c))) <= TOL_BF16
+    assert g.rel_l2(back(act), nn.gelu_fwd(pre)) <= 2 * TOL_BF16
+    # backward: dy [m][k2] times w [k2][n] (strided operand, as in dX = dY W), times GELU'(pre)
+    x, xd = bf(si.normal(44, (m, n), 2.0))
+    w, wd = bf(si.normal(45, (n, k), 0.1))      # [n][k] -> product over k of a[m][k] w[n][k]
+    wt = wd.t().contiguous()                     # stored [k][n]: strided B operand
+    dx = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    g.call(K.lib().karma_k_gemm_gelu_bf16, g.ptr(ad), g.ptr(wt), g.ptr(dx), None, g.ptr(xd), m, n, k, K.GEMM_B_STRIDED,
+           K.GEMM_GELU_BWD, g.stream_ptr())
+    assert g.rel_l2(back(dx), nn.gelu_bwd(x, a @ w.T)) <= TOL_BF16
+    lib = K.lib()
+    assert lib.karma_k_gemm_gelu_bf16(g.ptr(ad), g.ptr(bd), g.ptr(c), None, None, m, n, k, 0, K.GEMM_GELU_FWD, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_gemm_gelu_bf16(g.ptr(ad), g.ptr(bd), g.ptr(c), None, g.ptr(act), m, n, k, 0, 3, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_gemm_gelu_bf16(g.ptr(ad), g.ptr(bd), g.ptr(c), None, g.ptr(act), m, n, k, K.GEMM_OUT_F32, 1, g.stream_ptr()) == K.E_INVAL
+
+
 def test_gemm_rejects_bad_shapes(g):
     import torch
     t = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
