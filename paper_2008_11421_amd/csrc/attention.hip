@@ -26,6 +26,13 @@ namespace karma {
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+// Tile sizes of the head-dimension-64 kernels, from a sweep on 32 x 16 heads x 1024 x 64 (times of
+// forward / dQ+dK/dV passes): forward 128, 64, 32 keys per tile: 143, 121, 139 us; dQ 128 -> 64 keys:
+// -40 us; dK/dV 128, 64, 32 queries: 0, 0, -25 us.  Smaller tiles need fewer registers per
+// wavefront and let the two workgroups of a compute unit drift apart, so that one's MFMAs overlap
+// the other's exponentials; below these sizes the barrier per tile costs more than that gains.
+constexpr int ATTN_FWD_KT = 64, ATTN_DQ_KT = 64, ATTN_DKV_QT = 32;
+
 // v_exp_f32: 2^x without the range fix-ups of exp2f (arguments here are <= 0 or -inf)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -255,9 +262,10 @@ struct Frag64 {
   }
 };
 
-__global__ __launch_bounds__(256, 2) void attn_fwd_dl_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+template <int KT, int WGS>
+__global__ __launch_bounds__(256, WGS) void attn_fwd_dl_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                               float* __restrict__ lse, int S, int H) {
-  constexpr int D = 64, KT = 128, TILE = KT * D * 2, STAGE = 2 * TILE;   // stage = K tile | V tile
+  constexpr int D = 64, NMT = KT / 32, TILE = KT * D * 2, STAGE = 2 * TILE;   // stage = K tile | V tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
   const int h = H * D;
@@ -307,26 +315,26 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_dl_kernel(const bf16_t* __res
     if (kt + 1 < n_kt) issue(kt + 1);
     const unsigned Ks = lds0 + (kt & 1) * STAGE, Vs = Ks + TILE;
     // sub-tiles this wavefront needs: keys key0 + 32*mt <= last query
-    const int n_mt = FULL ? 4 : min(4, (qbase + 31 - key0) / 32 + 1);
-    f32x16 s[4];
+    const int n_mt = FULL ? NMT : min(NMT, (qbase + 31 - key0) / 32 + 1);
+    f32x16 s[NMT];
     float tmax = -INFINITY;
     if (FULL) {
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < NMT; ++mt)
           s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.rows(Ks, mt * 32, ks), qf[ks], s[mt], 0, 0, 0);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int mt = 0; mt < NMT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[mt][r]);
     } else {
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
+      for (int mt = 0; mt < NMT; ++mt) {
         if (mt < n_mt) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
@@ -358,7 +366,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_dl_kernel(const bf16_t* __res
     }
     float psum = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {
       if (FULL || mt < n_mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -378,8 +386,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_dl_kernel(const bf16_t* __res
     }
     l += psum;
   };
-  for (int kt = 0; kt + 1 < n_kt; ++kt) tile_step(kt, std::true_type{});
-  tile_step(n_kt - 1, std::false_type{});
+  const int n_full = q0 / KT;   // tiles whose keys all precede the workgroup's first query
+  for (int kt = 0; kt < n_full; ++kt) tile_step(kt, std::true_type{});
+  for (int kt = n_full; kt < n_kt; ++kt) tile_step(kt, std::false_type{});
   l += __shfl_xor(l, 32, 64);
   const float inv = 1.f / l;
   bf16_t* out = ctx + ((size_t)b * S + query) * h + (size_t)head * D;
@@ -530,10 +539,13 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
 
 // dQ for head dimension 64 with direct loads: K and V tiles as they lie in memory; K is read by
 // rows for the scores and transposed for dQ^T += K^T dS^T.
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-                                                                 const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                 bf16_t* __restrict__ dqkv, int S, int H) {
-  constexpr int D = 64, KT = 128, TILE = KT * D * 2, STAGE = 2 * TILE;
+// It also computes delta[q] = sum_d dO[q][d] O[q][d] for its queries (each lane holds half a row of dO
+// as MFMA fragments anyway) and stores it for the dK/dV pass.
+template <int KT>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+                                                                 const bf16_t* __restrict__ dout, const float* __restrict__ lse,
+                                                                 float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H) {
+  constexpr int D = 64, NMT = KT / 32, TILE = KT * D * 2, STAGE = 2 * TILE;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
   const int h = H * D;
@@ -567,7 +579,20 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
     dof[ks] = f.v;
   }
   const float my_lse = lse[((size_t)b * H + head) * S + query];
-  const float my_delta = delta[((size_t)b * H + head) * S + query];
+  float my_delta = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    Frag fo, fd;
+    fo.u = *(const u32x4*)(o + ((size_t)b * S + query) * h + (size_t)head * D + ks * 16 + g * 8);
+    fd.v = dof[ks];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      my_delta = fmaf(__uint_as_float(fo.u[e] << 16), __uint_as_float(fd.u[e] << 16), my_delta);
+      my_delta = fmaf(__uint_as_float(fo.u[e] & 0xffff0000u), __uint_as_float(fd.u[e] & 0xffff0000u), my_delta);
+    }
+  }
+  my_delta += __shfl_xor(my_delta, 32, 64);   // the other half of the row
+  if (g == 0) delta[((size_t)b * H + head) * S + query] = my_delta;
   f32x16 dq[D / 32];
 #pragma unroll
   for (int i = 0; i < D / 32; ++i)
@@ -581,9 +606,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
     lds_barrier_visible();
     if (kt + 1 < n_kt) issue(kt + 1);
     const unsigned Ks = lds0 + (kt & 1) * STAGE, Vs = Ks + TILE;
-    const int n_mt = FULL ? 4 : min(4, (qbase + 31 - key0) / 32 + 1);
+    const int n_mt = FULL ? NMT : min(NMT, (qbase + 31 - key0) / 32 + 1);
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {
       if (FULL || mt < n_mt) {
         f32x16 s, dp;
 #pragma unroll
@@ -612,8 +637,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
       }
     }
   };
-  for (int kt = 0; kt + 1 < n_kt; ++kt) tile_step(kt, std::true_type{});
-  tile_step(n_kt - 1, std::false_type{});
+  const int n_full = q0 / KT;   // tiles whose keys all precede the workgroup's first query
+  for (int kt = 0; kt < n_full; ++kt) tile_step(kt, std::true_type{});
+  for (int kt = n_full; kt < n_kt; ++kt) tile_step(kt, std::false_type{});
 
   bf16_t* out = dqkv + ((size_t)b * S + query) * ld + (size_t)head * D;
 #pragma unroll
@@ -767,12 +793,13 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
     }
 }
 
-// dK, dV for head dimension 64 with direct loads: Q and dO tiles of 64 queries as they lie in
+// dK, dV for head dimension 64 with direct loads: Q and dO tiles of 128 queries as they lie in
 // memory, read by rows for S = Q K^T and dP = dO V^T and transposed for dV += P^T dO, dK += dS^T Q.
+template <int QT>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
                                                                   bf16_t* __restrict__ dqkv, int S, int H) {
-  constexpr int D = 64, QT = 64, TILE = QT * D * 2, STAGE = 2 * TILE;   // stage = Q tile | dO tile
+  constexpr int D = 64, TILE = QT * D * 2, STAGE = 2 * TILE;   // stage = Q tile | dO tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
   float* stat = (float*)(smem_attn + 2 * STAGE);   // [2 stages][lse | delta][QT]
@@ -790,7 +817,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* _
   const float scale = rsqrtf((float)D), c = LOG2E * scale;
   Frag64 fr;
   fr.init(lane);
-  auto issue = [&](int t) {   // query tile t of this workgroup: queries k0 + 64 t ..
+  auto issue = [&](int t) {   // query tile t of this workgroup: queries k0 + 128 t ..
     const unsigned st = lds0 + (t & 1) * STAGE;
     const int qq = k0 + t * QT;
     issue_tile64<QT, 4>(base + (size_t)qq * ld, ld, st, w, lane);
@@ -881,10 +908,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* _
       }
     }
   };
-  // the first two query tiles overlap this workgroup's 128 keys; all later ones lie after them
-  int t = 0;
-  for (; t < n_t && t < 2; ++t) tile_step(t, std::false_type{});
-  for (; t < n_t; ++t) tile_step(t, std::true_type{});
+  // the first 128 queries are the workgroup's own keys (the diagonal); all later tiles lie after them
+  for (int t = 0; t < 128 / QT; ++t) tile_step(t, std::false_type{});
+  for (int t = 128 / QT; t < n_t; ++t) tile_step(t, std::true_type{});
 
   // dk[i][r]: key = kbase + (r/4)*8 + 4g + r%4, d = i*32 + lane%32
 #pragma unroll
@@ -912,23 +938,28 @@ int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq
   if (seq % 128 || (d != 64 && d != 128) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
   dim3 grid(seq / 128, heads, batch);
   if (d == 64) {
-    constexpr int lds = 2 * 2 * 128 * 64 * 2;   // two stages of (K tile, V tile)
-    (void)hipFuncSetAttribute((const void*)attn_fwd_dl_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    hipLaunchKernelGGL(attn_fwd_dl_kernel, grid, dim3(256), lds, s, qkv, ctx, lse, seq, heads);
+    constexpr int KT = ATTN_FWD_KT, lds = 2 * 2 * KT * 64 * 2;   // two stages of (K tile, V tile)
+    auto kern = attn_fwd_dl_kernel<KT, 2>;
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, qkv, ctx, lse, seq, heads);
   }
   else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, s, qkv, ctx, lse, seq, heads);
   return ok();
 }
 
 template <int D>
-static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* dctx, const float* lse,
-                       const float* delta, bf16_t* dqkv, int seq, int heads) {
+static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse,
+                       float* delta, bf16_t* dqkv, int seq, int heads) {
   if constexpr (D == 64) {
-    constexpr int l1 = 2 * 2 * 128 * 64 * 2;                       // two stages of (K tile, V tile)
-    constexpr int l2 = 2 * 2 * 64 * 64 * 2 + 2 * 2 * 64 * 4;       // two stages of (Q tile, dO tile) + their lse, delta
-    (void)hipFuncSetAttribute((const void*)attn_bwd_dq_dl_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, l1);
-    hipLaunchKernelGGL(attn_bwd_dq_dl_kernel, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
-    hipLaunchKernelGGL(attn_bwd_dkv_dl_kernel, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    constexpr int KT = ATTN_DQ_KT, QT = ATTN_DKV_QT;
+    constexpr int l1 = 2 * 2 * KT * 64 * 2;                      // two stages of (K tile, V tile)
+    constexpr int l2 = 2 * 2 * QT * 64 * 2 + 2 * 2 * QT * 4;     // two stages of (Q tile, dO tile) + their lse, delta
+    auto kq = attn_bwd_dq_dl_kernel<KT>;
+    auto kkv = attn_bwd_dkv_dl_kernel<QT>;
+    (void)hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, l1);
+    (void)hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, l2);
+    hipLaunchKernelGGL(kq, grid, dim3(256), l1, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
+    hipLaunchKernelGGL(kkv, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
   } else {
     constexpr size_t l1 = attn_dq_lds<D>(), l2 = attn_dkv_lds<D>();
     if (l1 > 64 * 1024)
@@ -946,12 +977,11 @@ int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, cons
   dim3 grid(seq / 128, heads, batch);
   const size_t total = (size_t)batch * seq * heads;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  if (d == 64) {
-    hipLaunchKernelGGL(attn_delta_kernel<64>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
-    launch_bwd<64>(grid, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+  if (d == 64) {   // the dQ pass computes delta itself
+    launch_bwd<64>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
   } else {
     hipLaunchKernelGGL(attn_delta_kernel<128>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
-    launch_bwd<128>(grid, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    launch_bwd<128>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
   }
   return ok();
 }
