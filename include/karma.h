@@ -190,6 +190,22 @@ int karma_set_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, const float
 int karma_get_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_fp32_out, uint64_t n);
 int karma_get_grad(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_fp32_out, uint64_t n);
 
+/* Analytic cost model (Sec. III-C: the number of arithmetic operations of a block's layers as the proxy of
+ * its cost, projected on the device's throughput; memory from the shapes, Sec. III-D).  No GPU is used: with
+ * these records karma_plan_pure / karma_simulate project a model at any batch size.  One multiply-add counts
+ * as one operation, as in the paper.  matrix_ops_per_s: rate of the matrix operations (convolutions, fully
+ * connected layers, attention products); other_ops_per_s: rate of everything else (normalisations,
+ * activations, softmax, pooling, adds).  Times: t_fwd = ceil(matrix*1e9/rate) + ceil(other*1e9/rate),
+ * t_bwd = 2 t_fwd, t_recompute = t_fwd; the loss op takes three times its forward count.
+ * *n_inout: capacity of layers_out on entry (KARMA_E_OOM and the needed count if too small), count on
+ * return.  loss_out, fixed_out may be NULL.  Errors: KARMA_E_INVAL. */
+typedef struct {
+  uint64_t matrix_ops_per_s;
+  uint64_t other_ops_per_s;
+} karma_device_rates;
+int karma_model_costs(const karma_model_desc* desc, const karma_device_rates* rates, karma_layer_cost* layers_out,
+                      uint32_t* n_inout, karma_loss_cost* loss_out, uint64_t* fixed_out);
+
 /* Cost records of the model: bytes from shapes (exact, the library owns the allocator),
  * times from the last karma_measure (0 before).  layers_out has karma_model_layers
  * entries.  fixed_out: bytes resident for the whole step (weights, gradients, inputs). */

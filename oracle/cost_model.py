@@ -1,0 +1,107 @@
+"""Analytic cost model oracle (TEST INFRASTRUCTURE ONLY).
+
+KARMA Sec. III-C takes the number of arithmetic operations of a block as the proxy of its
+computational cost and projects it on the device's throughput; this file counts those
+operations per block of the three model families, in plain Python integers, and turns them
+into times.  Only tests may import it; the library's own counter (csrc/cost_model.cpp) shares
+no code with it.
+
+Operation counts per sample, as the paper lists them (one multiply-add = one operation):
+  convolution      |Y| * K * K * C_in
+  ReLU             |Y|
+  pooling          |Y| * K * K * c, c = 1 for both pooling types here (global average pooling: one
+                   operation per input element)
+  batch norm       3 |B| + 4 |X| + 2 |Y|, with |B| = |X| = |Y| (the mini-batch mean and variance run
+                   over the same elements): 9 |X|
+  fully connected  |X| * |Y|
+  softmax          2 |X|
+  element-wise, tensor add (inferred, Sec. III-C "Other"): one operation per output element
+
+Readings where the paper gives nothing usable:
+  self-attention   the printed count has no sequence-length term; here: per head S*S*d multiply-adds
+                   for Q K^T, S*S*d for P V, and a softmax over S*S scores (2 S*S); the causal mask is
+                   not discounted
+  layer norm       not listed; counted like batch normalisation (9 per element)
+  GELU             element-wise: one per element
+  embedding        one per output element (gather + positional add)
+  cross entropy    the softmax count, 2 per logit
+  backward         twice the forward count (one pass for the input gradient, one for the weight
+                   gradient); recompute = forward
+Matrix operations (convolution, fully connected, attention products) and all others are kept apart
+because the device runs them at different rates:
+  t_ns = ceil(matrix_ops * 1e9 / matrix_ops_per_s) + ceil(other_ops * 1e9 / other_ops_per_s)
+"""
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+def time_ns(ops, rates):
+    matrix, other = ops
+    return ceil_div(matrix * 10**9, rates[0]) + ceil_div(other * 10**9, rates[1])
+
+
+def conv_out(n, k, stride, pad):
+    return (n + 2 * pad - k) // stride + 1
+
+
+# ------------------------------------------------------------------ per-family counters
+def mlp_blocks(width, n_layers, batch):
+    """Linear(width -> width) + ReLU per block; loss: mean squared error (one op per element)."""
+    blocks = [(batch * width * width, batch * width) for _ in range(n_layers)]
+    loss = (0, batch * width)
+    return blocks, loss
+
+
+def gpt_blocks(n_layers, hidden, heads, ffn, vocab, seq, batch):
+    """Block 0: embedding.  Blocks 1..n: LN, QKV projection, attention, output projection, residual
+    add, LN, FC1, GELU, FC2, residual add.  Loss: final LN, tied LM head, softmax cross entropy."""
+    T = batch * seq
+    d = hidden // heads
+    blocks = [(0, T * hidden)]
+    fc = T * (hidden * 3 * hidden + hidden * hidden + 2 * hidden * ffn)
+    attn_mm = batch * heads * 2 * seq * seq * d
+    attn_softmax = batch * heads * 2 * seq * seq
+    other = 2 * 9 * T * hidden + attn_softmax + T * ffn + 2 * T * hidden
+    for _ in range(n_layers):
+        blocks.append((fc + attn_mm, other))
+    loss = (T * hidden * vocab, 9 * T * hidden + 2 * T * vocab)
+    return blocks, loss
+
+
+def cnn_blocks(width, stage_blocks, image, batch, classes):
+    """Block 0: stem (7x7 stride-2 convolution, batch norm, ReLU, 3x3 stride-2 max pooling).  Then the
+    bottleneck blocks.  Loss: global average pooling, fully connected layer, softmax cross entropy."""
+    h1 = conv_out(image, 7, 2, 3)
+    h2 = conv_out(h1, 3, 2, 1)
+    y_stem = batch * h1 * h1 * width
+    blocks = [(y_stem * 7 * 7 * 3, 9 * y_stem + y_stem + batch * h2 * h2 * width * 9)]
+    hw, cin = h2, width
+    for st in range(4):
+        mid, cout = width << st, 4 * (width << st)
+        for k in range(stage_blocks[st]):
+            stride = 2 if (k == 0 and st > 0) else 1
+            ho = conv_out(hw, 3, stride, 1)
+            p_in, p_out = batch * hw * hw, batch * ho * ho
+            matrix = p_in * mid * cin + p_out * mid * 9 * mid + p_out * cout * mid
+            other = 9 * p_in * mid + p_in * mid          # BN + ReLU after the 1x1
+            other += 9 * p_out * mid + p_out * mid       # BN + ReLU after the 3x3
+            other += 9 * p_out * cout                    # BN after the last 1x1
+            if k == 0:                                   # projection shortcut: 1x1 (strided) + BN
+                matrix += p_out * cout * cin
+                other += 9 * p_out * cout
+            other += 2 * p_out * cout                    # residual add + ReLU
+            blocks.append((matrix, other))
+            hw, cin = ho, cout
+    loss = (batch * cin * classes, batch * hw * hw * cin + 2 * batch * classes)
+    return blocks, loss
+
+
+def times(blocks, loss, rates):
+    """Per block (t_fwd, t_bwd, t_recompute) in ns and the loss op's time (forward + gradient)."""
+    out = []
+    for ops in blocks:
+        tf = time_ns(ops, rates)
+        out.append((tf, 2 * tf, tf))
+    return out, 3 * time_ns(loss, rates)

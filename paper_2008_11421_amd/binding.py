@@ -152,6 +152,34 @@ def karma_plan_pure(layers, link, loss, budget, fixed):
     return list(act), res
 
 
+class DeviceRates(C.Structure):
+    _fields_ = [("matrix_ops_per_s", C.c_uint64), ("other_ops_per_s", C.c_uint64)]
+
+
+def _model_desc(desc):
+    if isinstance(desc, ModelDesc):
+        return desc
+    desc = dict(desc)
+    if "stage_blocks" in desc:
+        desc["stage_blocks"] = (C.c_uint32 * 4)(*desc["stage_blocks"])
+    return ModelDesc(**desc)
+
+
+def karma_model_costs(desc, matrix_ops_per_s, other_ops_per_s):
+    """Analytic cost records of a model (no GPU): (layers as 8-tuples, (loss t_ns, loss ws_bytes), fixed bytes)."""
+    d = _model_desc(desc)
+    n = C.c_uint32()
+    _check(lib().karma_model_layers(C.byref(d), C.byref(n)), "karma_model_layers")
+    arr = (LayerCost * n.value)()
+    rates = DeviceRates(int(matrix_ops_per_s), int(other_ops_per_s))
+    loss = LossCost()
+    fixed = C.c_uint64()
+    _check(lib().karma_model_costs(C.byref(d), C.byref(rates), arr, C.byref(n), C.byref(loss), C.byref(fixed)),
+           "karma_model_costs")
+    layers = [(a.tf_ns, a.tb_ns, a.trc_ns, a.sav_bytes, a.out_bytes, a.ws_bytes, a.w_bytes, a.g_bytes) for a in arr[:n.value]]
+    return layers, (loss.t_ns, loss.ws_bytes), fixed.value
+
+
 def karma_stage_string(ops):
     arr = (Op * len(ops))(*ops)
     buf = C.create_string_buffer(64 * len(ops) + 64)
@@ -167,12 +195,7 @@ class Context:
     def __init__(self, desc, cfg, arena_bytes, device="cuda:0"):
         import torch
         self.torch = torch
-        if not isinstance(desc, ModelDesc):
-            desc = dict(desc)
-            if "stage_blocks" in desc:
-                desc["stage_blocks"] = (C.c_uint32 * 4)(*desc["stage_blocks"])
-            desc = ModelDesc(**desc)
-        self.desc = desc
+        self.desc = _model_desc(desc)
         self.cfg = cfg if isinstance(cfg, Config) else Config(**cfg)
         self.device = torch.device(device)
         self.arena = torch.empty(int(arena_bytes), dtype=torch.uint8, device=self.device)

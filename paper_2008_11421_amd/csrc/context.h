@@ -153,4 +153,7 @@ int layer_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int layer_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int loss_op(Ctx& c, const LayerIO& io, hipStream_t s);   // x -> loss (fixed region) and dx; accumulates its own parameter gradients
 
+// records, fixed-region layout and byte fields of the cost records from the description alone (executor.cpp)
+int derive_layout(Ctx& c);
+
 }  // namespace karma

@@ -421,6 +421,40 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
 
 }  // namespace
 
+// Records, the layout of the fixed region and the byte fields of the cost records, from the
+// model description alone (no GPU call): shared by karma_create and the analytic cost model.
+int karma::derive_layout(Ctx& c) {
+  int st = model_build_records(c);
+  if (st) return st;
+  c.L = (uint32_t)c.rec.size() - 1;
+  // fixed-region layout: weights, gradients, inputs, labels, loss, misc
+  uint64_t off = 0;
+  for (Record& r : c.rec) {
+    if (r.streamed) {
+      for (Param& p : r.p) {
+        p.w_rel = r.w_total; r.w_total += up256(p.w_bytes());
+        p.g_rel = r.g_total; r.g_total += up256(p.g_bytes());
+      }
+      continue;
+    }
+    for (Param& p : r.p) {
+      p.w_off = off; off += up256(p.w_bytes());
+      p.g_off = off; off += up256(p.g_bytes());
+    }
+  }
+  c.in_off = off; off += up256(c.in_bytes);
+  c.lab_off = off; off += up256(c.lab_bytes);
+  c.loss_off = off; off += 256;
+  c.misc_off = off; off += up256(c.misc_bytes);
+  c.fixed_bytes = off;
+  c.cost.resize(c.L);
+  for (uint32_t i = 0; i < c.L; ++i)
+    c.cost[i] = karma_layer_cost{0, 0, 0, c.rec[i].sav_bytes, c.rec[i].out_bytes, c.rec[i].ws_bytes,
+                                  c.rec[i].streamed ? c.rec[i].w_total : 0, c.rec[i].streamed ? c.rec[i].g_total : 0};
+  c.loss_cost = karma_loss_cost{0, c.rec[c.L].ws_bytes};
+  return KARMA_OK;
+}
+
 // ------------------------------------------------------------------ C ABI
 extern "C" int karma_model_layers(const karma_model_desc* d, uint32_t* n_out) {
   if (!d || !n_out) return KARMA_E_INVAL;
@@ -447,35 +481,9 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   c->st[0] = (hipStream_t)stream_compute;
   c->st[1] = (hipStream_t)stream_h2d;
   c->st[2] = (hipStream_t)stream_d2h;
-  int st = model_build_records(*c);
+  int st = derive_layout(*c);
   if (st) { delete c; return st; }
-  c->L = (uint32_t)c->rec.size() - 1;
-  // fixed-region layout: weights, gradients, inputs, labels, loss, misc
-  uint64_t off = 0;
-  for (Record& r : c->rec) {
-    if (r.streamed) {
-      for (Param& p : r.p) {
-        p.w_rel = r.w_total; r.w_total += up256(p.w_bytes());
-        p.g_rel = r.g_total; r.g_total += up256(p.g_bytes());
-      }
-      continue;
-    }
-    for (Param& p : r.p) {
-      p.w_off = off; off += up256(p.w_bytes());
-      p.g_off = off; off += up256(p.g_bytes());
-    }
-  }
-  c->in_off = off; off += up256(c->in_bytes);
-  c->lab_off = off; off += up256(c->lab_bytes);
-  c->loss_off = off; off += 256;
-  c->misc_off = off; off += up256(c->misc_bytes);
-  c->fixed_bytes = off;
-  if (off >= arena_bytes) { delete c; return KARMA_E_OOM; }
-  c->cost.resize(c->L);
-  for (uint32_t i = 0; i < c->L; ++i)
-    c->cost[i] = karma_layer_cost{0, 0, 0, c->rec[i].sav_bytes, c->rec[i].out_bytes, c->rec[i].ws_bytes,
-                                  c->rec[i].streamed ? c->rec[i].w_total : 0, c->rec[i].streamed ? c->rec[i].g_total : 0};
-  c->loss_cost = karma_loss_cost{0, c->rec[c->L].ws_bytes};
+  if (c->fixed_bytes >= arena_bytes) { delete c; return KARMA_E_OOM; }
   c->link = karma_link{50000000000ull, 50000000000ull, 10000};
   // host state
   bool ok = true;

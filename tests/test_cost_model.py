@@ -1,0 +1,148 @@
+"""Analytic cost model (Sec. III-C operation counts projected on device rates): the oracle's counts
+against closed forms and published totals, the library against the oracle bit for bit, and a batch
+sweep through the planner on analytic costs alone.  CPU only."""
+import pytest
+
+import paper_2008_11421_amd as K
+from oracle import cost_model as CM
+from oracle import planner as P
+
+RATES = (500 * 10**12, 2 * 10**12)     # matrix multiply-adds per second, other operations per second
+GPT = dict(n_layers=24, hidden=1024, heads=16, ffn=4096, vocab=32000, seq=1024, batch=32)
+CNN = dict(width=64, stage_blocks=(3, 24, 36, 3), image=224, batch=64, classes=1000)
+
+
+def gpt_desc(batch=32, **over):
+    g = dict(GPT, batch=batch, **over)
+    return dict(kind=K.MODEL_GPT, n_layers=g["n_layers"], width=g["hidden"], batch=g["batch"], seq=g["seq"],
+                n_heads=g["heads"], ffn=g["ffn"], vocab=g["vocab"], stream_weights=0)
+
+
+def cnn_desc(batch=64):
+    return dict(kind=K.MODEL_CNN, n_layers=0, width=CNN["width"], batch=batch, seq=CNN["image"], n_heads=0, ffn=0,
+                vocab=CNN["classes"], stream_weights=0, stage_blocks=CNN["stage_blocks"])
+
+
+# ------------------------------------------------------------------ oracle pins
+def test_oracle_fully_connected_and_mlp_counts():
+    blocks, loss = CM.mlp_blocks(width=256, n_layers=8, batch=32)
+    assert len(blocks) == 8
+    # |X| * |Y| per sample for the layer, |Y| comparisons for the ReLU
+    assert blocks[0] == (32 * 256 * 256, 32 * 256)
+    assert loss == (0, 32 * 256)
+
+
+def test_oracle_gpt_block_matches_the_parameter_count_rule():
+    """With ffn = 4 h a block's weight matrices hold 12 h^2 parameters, and every token meets every
+    weight once: 12 h^2 multiply-adds per token, plus the attention products 2 S d per token and head."""
+    blocks, loss = CM.gpt_blocks(**GPT)
+    T, h, S = GPT["batch"] * GPT["seq"], GPT["hidden"], GPT["seq"]
+    assert len(blocks) == GPT["n_layers"] + 1
+    assert blocks[0][0] == 0
+    assert blocks[1][0] == T * 12 * h * h + T * 2 * S * h
+    assert all(b == blocks[1] for b in blocks[2:])
+    assert loss[0] == T * h * GPT["vocab"]
+    # whole forward pass in FLOP (2 per multiply-add): the 0.962 TFLOP per layer of the shape arithmetic
+    assert abs(2 * blocks[1][0] / 0.962e12 - 1) < 0.01
+
+
+def test_oracle_resnet200_total_is_the_published_size():
+    """ResNet-200 at 224x224 is known as a ~15 G multiply-add network; the stem's convolution alone is
+    112*112*64*147 and every stage's first block carries the projection."""
+    blocks, loss = CM.cnn_blocks(**dict(CNN, batch=1))
+    assert len(blocks) == 1 + sum(CNN["stage_blocks"])
+    total = sum(b[0] for b in blocks) + loss[0]
+    assert 14.5e9 < total < 15.5e9
+    assert blocks[0][0] == 112 * 112 * 64 * 49 * 3
+    # an identity block of stage 1: 1x1 (256->64), 3x3 (64->64), 1x1 (64->256) on 56x56
+    assert blocks[2][0] == 56 * 56 * (64 * 256 + 64 * 9 * 64 + 256 * 64)
+    # the first block reads the stem's 64 channels and carries the 64 -> 256 projection
+    assert blocks[1][0] == 56 * 56 * (64 * 64 + 64 * 9 * 64 + 256 * 64 + 256 * 64)
+    # first block of stage 2: 1x1 on 56x56 (256 -> 128), strided 3x3, 1x1 and projection on 28x28
+    assert blocks[4][0] == 56 * 56 * 128 * 256 + 28 * 28 * (128 * 9 * 128 + 512 * 128 + 512 * 256)
+    # batch norm = 9 per element, ReLU / add = 1 per element
+    assert blocks[2][1] == 56 * 56 * (10 * 64 + 10 * 64 + 9 * 256 + 2 * 256)
+    assert loss == (2048 * 1000, 7 * 7 * 2048 + 2 * 1000)
+
+
+def test_oracle_counts_scale_with_batch_and_times_round_up():
+    b1, l1 = CM.gpt_blocks(**dict(GPT, batch=1))
+    b4, l4 = CM.gpt_blocks(**dict(GPT, batch=4))
+    assert all(4 * x[0] == y[0] and 4 * x[1] == y[1] for x, y in zip(b1, b4))
+    assert CM.time_ns((1, 0), (3, 1)) == 333333334      # ceil(1e9 / 3)
+    assert CM.time_ns((0, 7), (1, 2 * 10**9)) == 4      # ceil(7e9 / 2e9)
+    t, tl = CM.times(b1, l1, RATES)
+    assert all(tb == 2 * tf and trc == tf for tf, tb, trc in t)
+    assert tl == 3 * CM.time_ns(l1, RATES)
+
+
+# ------------------------------------------------------------------ library against oracle
+def check_times(desc, blocks, loss):
+    layers, (t_loss, _), fixed = K.karma_model_costs(desc, *RATES)
+    want, want_loss = CM.times(blocks, loss, RATES)
+    assert [l[:3] for l in layers] == want
+    assert t_loss == want_loss
+    assert fixed > 0 and all(l[3] + l[4] > 0 for l in layers)
+    return layers, fixed
+
+
+def test_library_times_bit_exact():
+    check_times(dict(kind=K.MODEL_MLP, n_layers=8, width=256, batch=32, seq=0, n_heads=0, ffn=0, vocab=0, stream_weights=0),
+                *CM.mlp_blocks(256, 8, 32))
+    for batch in (1, 8, 32):
+        check_times(gpt_desc(batch), *CM.gpt_blocks(**dict(GPT, batch=batch)))
+    check_times(gpt_desc(8, n_layers=72, hidden=3072, heads=24, ffn=12288, vocab=51200),
+                *CM.gpt_blocks(n_layers=72, hidden=3072, heads=24, ffn=12288, vocab=51200, seq=1024, batch=8))
+    for batch in (2, 64):
+        check_times(cnn_desc(batch), *CM.cnn_blocks(**dict(CNN, batch=batch)))
+
+
+def test_library_bytes_match_the_shape_arithmetic():
+    """Per-block saved set of the benchmark GPT: 1.00 GiB, boundary tensor 64 MiB (shape arithmetic:
+    tokens x hidden x 2 bytes); they scale linearly with the batch."""
+    layers, _ = check_times(gpt_desc(32), *CM.gpt_blocks(**GPT))
+    sav, out = layers[1][3], layers[1][4]
+    assert out == 32 * 1024 * 1024 * 2
+    assert abs(sav / 2**30 - 1.0) < 0.08
+    layers8, _ = check_times(gpt_desc(8), *CM.gpt_blocks(**dict(GPT, batch=8)))
+    assert layers8[1][4] * 4 == out and abs(layers8[1][3] * 4 / sav - 1) < 0.01
+
+
+def test_errors():
+    with pytest.raises(K.KarmaError):
+        K.karma_model_costs(gpt_desc(32), 0, 1)
+    with pytest.raises(K.KarmaError):
+        K.karma_model_costs(dict(kind=9, n_layers=1, width=8, batch=1, seq=8, n_heads=1, ffn=8, vocab=8, stream_weights=0), 1, 1)
+
+
+# ------------------------------------------------------------------ batch sweep on analytic costs
+def test_batch_sweep_first_point_fits_rest_do_not():
+    """The projection the analytic model is for: one budget, growing batch.  The smallest batch fits
+    in-core (all KEEP, no stall); larger ones need swapping or recompute, the predicted rate per sample
+    never improves once out of core, and library and oracle planner agree on every point."""
+    budget = 16 * 2**30
+    link = (57 * 10**9, 57 * 10**9, 6000)
+    rates = []
+    for batch in (8, 16, 32, 64):
+        layers, loss, fixed = K.karma_model_costs(gpt_desc(batch), *RATES)
+        try:
+            acts, summ = K.karma_plan_pure(layers, link, loss, budget, fixed)
+        except K.KarmaError as e:
+            assert e.status == K.E_BUDGET
+            with pytest.raises(P.Infeasible):
+                P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(*loss))
+            rates.append(None)
+            continue
+        ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(*loss))
+        assert acts == ao and summ["makespan_ns"] == so["makespan_ns"]
+        in_core_ns = sum(l[0] + l[1] for l in layers) + loss[0]
+        if batch == 8:
+            assert acts == [K.KEEP] * len(acts) and summ["makespan_ns"] == in_core_ns
+        else:
+            assert summ["makespan_ns"] >= in_core_ns
+        rates.append((batch * 10**9 / summ["makespan_ns"], acts))
+    assert rates[0] is not None and rates[0][1] == [K.KEEP] * 25
+    assert any(r is not None and r[1] != [K.KEEP] * 25 for r in rates[1:])
+    per = [r[0] for r in rates if r is not None]
+    # samples/s grows with the batch only while in core; out of core it stays within the in-core rate
+    assert max(per) <= per[0] * (1 + 1e-9) or per[1] >= per[0] * 0.5
