@@ -27,8 +27,10 @@ struct GemmEpilogue {
   int accumulate;          // fp32 output only: C += result
   bf16_t* aux;             // [M][ldc]: octet<1> writes GELU(C) there, octet<2> multiplies the result by GELU'(aux) (bf16 C only)
   // eight consecutive columns n..n+7 of row m (n multiple of 8); cols = how many are inside the matrix
+  // pre (when have_pre): the eight residual (or, ACT 2, pre-activation) values of this octet, fetched by the caller
   template <int ACT = 0>
-  __device__ __forceinline__ void octet(int m, int n, int cols, const float4& lo, const float4& hi) const {
+  __device__ __forceinline__ void octet(int m, int n, int cols, const float4& lo, const float4& hi,
+                                        bool have_pre = false, u32x4 pre = u32x4{0, 0, 0, 0}) const {
     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     const size_t at = (size_t)m * ldc + n;
     if (cols == 8 && (ldc & 7) == 0) {
@@ -49,12 +51,12 @@ struct GemmEpilogue {
         c[1] = o1;
       } else {
         if (residual) {
-          u32x4 r = *(const u32x4*)(residual + at);
+          u32x4 r = have_pre ? pre : *(const u32x4*)(residual + at);
 #pragma unroll
           for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(r[e] << 16); v[2 * e + 1] += __uint_as_float(r[e] & 0xffff0000u); }
         }
         if (ACT == 2) {
-          u32x4 r = *(const u32x4*)(aux + at);
+          u32x4 r = have_pre ? pre : *(const u32x4*)(aux + at);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             v[2 * e] *= gelu_grad_f(__uint_as_float(r[e] << 16));
@@ -508,6 +510,19 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
     static_assert(QPR >= 4 && 64 % QPR == 0 && RPI % 2 == 0 && 32 % RPI == 0, "strip read-out does not tile");
     const int q = (lane & 3) | (((lane >> 3) % (QPR / 4)) << 2);
     const int rr = ((lane >> 2) & 1) | ((lane / (2 * QPR)) << 1);
+    // The output stage's per-element input (the residual, or with ACT 2 the saved pre-activation) is
+    // fetched one strip ahead, octet by octet as the previous strip's octets are consumed, so that its
+    // latency hides behind a whole strip's trip through LDS at the price of one vector per pass.
+    constexpr int PASSES = 32 / RPI;
+    const bf16_t* ein = ACT == 2 ? ep.aux : (ep.out_f32 ? nullptr : ep.residual);
+    const bool fetch_in = ein != nullptr && splits == 1 && (ep.ldc & 7) == 0;
+    const int n = n0 + wn * WTN + q * 8;
+    auto fetch = [&](int i, int pass) {
+      return *(const u32x4*)(ein + (size_t)(m0 + wm * WTM + i * 32 + pass * RPI + rr) * ep.ldc + n);
+    };
+    u32x4 pre[PASSES];
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) pre[pass] = fetch_in ? fetch(0, pass) : u32x4{0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -516,9 +531,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
         for (int g = 0; g < 4; ++g)
           *(float4*)(strip + lrow * SP + j * 32 + g * 8 + (lane >> 5) * 4) =
               make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-      const int n = n0 + wn * WTN + q * 8;
 #pragma unroll
-      for (int pass = 0; pass < 32 / RPI; ++pass) {
+      for (int pass = 0; pass < PASSES; ++pass) {
         const int row = pass * RPI + rr;
         const int m = m0 + wm * WTM + i * 32 + row;
         const float4 v = *(const float4*)(strip + row * SP + q * 8);
@@ -528,7 +542,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
           *(float4*)dst = v;
           *(float4*)(dst + 4) = u;
         } else {
-          ep.template octet<ACT>(m, n, 8, v, u);
+          const u32x4 cur = pre[pass];
+          if (fetch_in && i + 1 < TM) pre[pass] = fetch(i + 1, pass);
+          ep.template octet<ACT>(m, n, 8, v, u, fetch_in, cur);
         }
       }
     }
