@@ -190,6 +190,17 @@ int karma_set_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, const float
 int karma_get_param(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_fp32_out, uint64_t n);
 int karma_get_grad(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_fp32_out, uint64_t n);
 
+/* One host-optimiser update of n parameters (Sec. III-G stage 5: the weights are updated on the CPU), through
+ * the loops karma_step runs per record as its gradients land.  All pointers are host pointers.  master (fp32,
+ * updated in place), m and v (fp32 moments, in place; m alone for SGD with momentum, none for SGD), grad (fp32 or,
+ * with grad_is_bf16, bf16 bit patterns), out (the new weights in device format: bf16 when out_is_bf16, else fp32).
+ * optimizer: karma_opt_kind; Adam is bias-corrected, step counts from 1.  narrow_vectors != 0 forces the AVX2
+ * build of the loops (the AVX-512 build is used where the CPU has it; both give identical results).  Not
+ * thread-safe.  Errors: KARMA_E_INVAL. */
+int karma_host_update(uint32_t optimizer, float* master, float* m, float* v, const void* grad, uint32_t grad_is_bf16,
+                      uint64_t n, float lr, float beta1, float beta2, float eps, uint64_t step, void* out,
+                      uint32_t out_is_bf16, uint32_t narrow_vectors);
+
 /* Analytic cost model (Sec. III-C: the number of arithmetic operations of a block's layers as the proxy of
  * its cost, projected on the device's throughput; memory from the shapes, Sec. III-D).  No GPU is used: with
  * these records karma_plan_pure / karma_simulate project a model at any batch size.  One multiply-add counts

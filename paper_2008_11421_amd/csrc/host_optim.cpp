@@ -1,4 +1,5 @@
 #include "host_optim.h"
+#include "karma.h"
 
 #include <cmath>
 #include <cstring>
@@ -98,10 +99,13 @@ void adam_update(float* w, float* m, float* v, const void* g, bool g_is_bf16, si
                  float eps, float c1, float c2, void* out, bool out_is_bf16);
 }  // namespace avx512
 
+static bool g_force_narrow = false;
+void host_optim_force_narrow(bool on) { g_force_narrow = on; }
+
 static bool wide_vectors() {
   static const bool yes = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") &&
                           __builtin_cpu_supports("avx512vl") && __builtin_cpu_supports("avx512dq");
-  return yes;
+  return yes && !g_force_narrow;
 }
 
 void sgd_momentum_update(float* w, float* buf, const void* g, bool g_is_bf16, size_t n, float lr, float mu, void* out,
@@ -124,3 +128,21 @@ void adam_update(float* w, float* m, float* v, const void* g, bool g_is_bf16, si
 }
 
 }  // namespace karma
+
+// One update of n parameters through the same loops the executor uses per record.
+extern "C" int karma_host_update(uint32_t optimizer, float* master, float* m, float* v, const void* grad,
+                                 uint32_t grad_is_bf16, uint64_t n, float lr, float beta1, float beta2, float eps,
+                                 uint64_t step, void* out, uint32_t out_is_bf16, uint32_t narrow_vectors) {
+  using namespace karma;
+  if (!master || !grad || !out) return KARMA_E_INVAL;
+  host_optim_force_narrow(narrow_vectors != 0);
+  int st = KARMA_OK;
+  if (optimizer == KARMA_OPT_SGD) sgd_update(master, grad, grad_is_bf16 != 0, (size_t)n, lr, out, out_is_bf16 != 0);
+  else if (optimizer == KARMA_OPT_SGD_MOMENTUM && m)
+    sgd_momentum_update(master, m, grad, grad_is_bf16 != 0, (size_t)n, lr, beta1, out, out_is_bf16 != 0);
+  else if (optimizer == KARMA_OPT_ADAM && m && v && step >= 1)
+    adam_update(master, m, v, grad, grad_is_bf16 != 0, (size_t)n, lr, beta1, beta2, eps, step, out, out_is_bf16 != 0);
+  else st = KARMA_E_INVAL;
+  host_optim_force_narrow(false);
+  return st;
+}
