@@ -59,6 +59,38 @@ def test_gemm_full_size_sampled_entries(g, m, n, k, flags, use_ws):
     assert np.all(np.abs(got - ref) <= 2.0 ** -7 * (np.abs(A) @ np.abs(Bm.T)) / np.sqrt(k) * 8 + 1e-6)
 
 
+def test_gemm_with_gelu_full_size_sampled_entries(g):
+    """The feed-forward products as the benchmark step launches them: FC1 with GELU written beside the
+    pre-activation, and dY W2 multiplied by GELU' of the stored pre-activation."""
+    import torch
+    m, n, k = T, FFN, H
+    a = dev_normal(111, (m, k), 0.5)
+    w = dev_normal(112, (n, k), 0.05)
+    bias = dev_normal(113, (n,), 0.5)
+    pre = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    act = torch.empty_like(pre)
+    g.call(K.lib().karma_k_gemm_gelu_bf16, g.ptr(a), g.ptr(w), g.ptr(pre), g.ptr(bias), g.ptr(act), m, n, k, 0,
+           K.GEMM_GELU_FWD, g.stream_ptr())
+    rng = np.random.default_rng(6)
+    ms = np.r_[0, m - 1, rng.integers(0, m, 30)]
+    ns = np.r_[0, n - 1, rng.integers(0, n, 30)]
+    A = rows_of(a, ms)
+    W = rows_of(w, ns)
+    ref = A @ W.T + bias[ns].float().cpu().numpy().astype(np.float64)
+    got_pre = pre[ms][:, ns].float().cpu().numpy().astype(np.float64)
+    got_act = act[ms][:, ns].float().cpu().numpy().astype(np.float64)
+    assert g.rel_l2(got_pre, ref) <= TOL_BF16
+    assert g.rel_l2(got_act, nn.gelu_fwd(got_pre)) <= TOL_BF16
+    # backward: dy [m][k] times W2 stored [k][n] (strided operand), times GELU'(pre)
+    w2 = dev_normal(114, (k, n), 0.05)
+    dx = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    g.call(K.lib().karma_k_gemm_gelu_bf16, g.ptr(a), g.ptr(w2), g.ptr(dx), None, g.ptr(pre), m, n, k, K.GEMM_B_STRIDED,
+           K.GEMM_GELU_BWD, g.stream_ptr())
+    W2 = w2[:, ns].t().float().cpu().numpy().astype(np.float64)
+    ref_dx = nn.gelu_bwd(got_pre, A @ W2.T)
+    assert g.rel_l2(dx[ms][:, ns].float().cpu().numpy(), ref_dx) <= TOL_BF16
+
+
 def test_attention_full_size_sampled_heads(g):
     import torch
     qkv = dev_normal(111, (B, S, 3 * H), 1.2)
