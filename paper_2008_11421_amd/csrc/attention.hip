@@ -217,18 +217,27 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
 // one piece) and transposing reads (4 rows x 4 pieces) are both free of bank conflicts.
 __device__ __forceinline__ int swz64(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
 
-// direct loads of a [ROWS][64] tile (row pitch ld elements in memory) by WAVES wavefronts
+// Direct loads of a [ROWS][64] tile (row pitch ld elements in memory) by WAVES wavefronts: the
+// per-lane byte offsets (row, swizzled piece) are computed once, a tile is then a uniform base
+// pointer plus those offsets.
 template <int ROWS, int WAVES>
-__device__ __forceinline__ void issue_tile64(const bf16_t* g, size_t ld, unsigned lds, int wave, int lane) {
-  constexpr int CH = ROWS / 8 / WAVES;   // 1 KiB pieces (8 rows) per wavefront
+struct TileLoader64 {
+  static constexpr int CH = ROWS / 8 / WAVES;   // 1 KiB pieces (8 rows) per wavefront
   static_assert(CH >= 1 && ROWS % (8 * WAVES) == 0, "tile does not divide over the wavefronts");
+  unsigned off[CH];
+  __device__ __forceinline__ void init(size_t ld, int wave, int lane) {
 #pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int c = wave * CH + i;
-    const int row = 8 * c + (lane >> 3);
-    load_to_lds16(g + (size_t)row * ld + (((lane & 7) ^ swz64(row)) * 8), lds + c * 1024);
+    for (int i = 0; i < CH; ++i) {
+      const int row = 8 * (wave * CH + i) + (lane >> 3);
+      off[i] = (unsigned)(((size_t)row * ld + (size_t)(((lane & 7) ^ swz64(row)) * 8)) * sizeof(bf16_t));
+    }
   }
-}
+  // tile: address of the tile's first row (the same in every lane); lds: byte address of the tile in LDS
+  __device__ __forceinline__ void issue(const bf16_t* tile, unsigned lds, int wave) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) load_to_lds16_s(tile, off[i], lds + (wave * CH + i) * 1024);
+  }
+};
 
 // per-lane address parts of the two fragment kinds
 struct Frag64 {
@@ -282,10 +291,12 @@ __global__ __launch_bounds__(256, WGS) void attn_fwd_dl_kernel(const bf16_t* __r
   Frag64 fr;
   fr.init(lane);
 
+  TileLoader64<KT, 4> tl;
+  tl.init(ld, w, lane);
   auto issue = [&](int kt) {
     const unsigned st = lds0 + (kt & 1) * STAGE;
-    issue_tile64<KT, 4>(Kg + (size_t)kt * KT * ld, ld, st, w, lane);
-    issue_tile64<KT, 4>(Vg + (size_t)kt * KT * ld, ld, st + TILE, w, lane);
+    tl.issue(Kg + (size_t)kt * KT * ld, st, w);
+    tl.issue(Vg + (size_t)kt * KT * ld, st + TILE, w);
   };
   const int n_kt = (q0 + 128) / KT;
   issue(0);
@@ -353,10 +364,13 @@ __global__ __launch_bounds__(256, WGS) void attn_fwd_dl_kernel(const bf16_t* __r
       }
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    // The reference maximum m follows the true maximum lazily: the accumulators are rescaled only when
+    // some query's maximum has grown by more than 2^8 in the exponent's domain; until then its
+    // probabilities are computed against the old reference and may reach 256 (harmless in fp32
+    // accumulators and in bf16, whose relative precision does not depend on the magnitude).
     const float m_new = fmaxf(m, tmax);
-    const float mc = m_new * c;
-    if (__any(m_new != m)) {   // rescale only when some query's maximum moved
-      const float alpha = fast_exp2(m * c - mc);
+    if (__any((m_new - m) * c > 8.f)) {
+      const float alpha = fast_exp2((m - m_new) * c);
       l *= alpha;
 #pragma unroll
       for (int i = 0; i < D / 32; ++i)
@@ -364,6 +378,7 @@ __global__ __launch_bounds__(256, WGS) void attn_fwd_dl_kernel(const bf16_t* __r
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
       m = m_new;
     }
+    const float mc = m * c;
     float psum = 0.f;
 #pragma unroll
     for (int mt = 0; mt < NMT; ++mt) {
@@ -561,10 +576,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
   const float scale = rsqrtf((float)D), c = LOG2E * scale;
   Frag64 fr;
   fr.init(lane);
+  TileLoader64<KT, 4> tl;
+  tl.init(ld, w, lane);
   auto issue = [&](int kt) {
     const unsigned st = lds0 + (kt & 1) * STAGE;
-    issue_tile64<KT, 4>(Kg + (size_t)kt * KT * ld, ld, st, w, lane);
-    issue_tile64<KT, 4>(Vg + (size_t)kt * KT * ld, ld, st + TILE, w, lane);
+    tl.issue(Kg + (size_t)kt * KT * ld, st, w);
+    tl.issue(Vg + (size_t)kt * KT * ld, st + TILE, w);
   };
   const int n_kt = (q0 + 128) / KT;
   issue(0);
@@ -817,11 +834,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* _
   const float scale = rsqrtf((float)D), c = LOG2E * scale;
   Frag64 fr;
   fr.init(lane);
-  auto issue = [&](int t) {   // query tile t of this workgroup: queries k0 + 128 t ..
+  TileLoader64<QT, 4> tlq, tlo;   // Q rows lie 3 h apart, dO rows h
+  tlq.init(ld, w, lane);
+  tlo.init((size_t)h, w, lane);
+  auto issue = [&](int t) {   // query tile t of this workgroup: queries k0 + QT t ..
     const unsigned st = lds0 + (t & 1) * STAGE;
     const int qq = k0 + t * QT;
-    issue_tile64<QT, 4>(base + (size_t)qq * ld, ld, st, w, lane);
-    issue_tile64<QT, 4>(dOg + (size_t)qq * h, (size_t)h, st + TILE, w, lane);
+    tlq.issue(base + (size_t)qq * ld, st, w);
+    tlo.issue(dOg + (size_t)qq * h, st + TILE, w);
   };
   const int n_t = (S - k0) / QT;
   issue(0);

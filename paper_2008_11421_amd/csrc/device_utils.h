@@ -60,6 +60,13 @@ __device__ __forceinline__ void load_to_lds16(const bf16_t* g, unsigned lds) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds)), "v"(g)
                : "memory");
 }
+// The same with the address split into a wavefront-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset: no vector arithmetic per load when the offsets are kept in registers.
+__device__ __forceinline__ void load_to_lds16_s(const void* base, unsigned byte_off, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(lds)),
+               "v"(byte_off), "s"(base)
+               : "memory");
+}
 // LDS-only workgroup barrier written with builtins, so that the compiler's own wait-count
 // bookkeeping knows that every LDS read issued before it has returned.
 __device__ __forceinline__ void lds_barrier_visible() {
