@@ -365,28 +365,31 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   static_assert((BM / WAVES) % 16 == 0 && (BN / WAVES) % 16 == 0 && (BK / WAVES) % 4 == 0, "swizzle parity per piece");
   const int a_row = A_KC ? wave * (BM / WAVES) + (lane >> 3) : wave * (BK / WAVES) + (lane >> 5);
   const int b_row = B_KC ? wave * (BN / WAVES) + (lane >> 3) : wave * (BK / WAVES) + (lane >> 5);
-  int a_col[2], b_col[2];
+  // byte offset of each of this lane's pieces from the tile's first element; a tile is then a uniform
+  // base address (scalar registers) plus these, and issuing it costs no vector arithmetic
+  unsigned a_off[CH_A], b_off[CH_B];
 #pragma unroll
-  for (int odd = 0; odd < 2; ++odd) {
+  for (int i = 0; i < (CH_A > CH_B ? CH_A : CH_B); ++i) {
+    const int odd = i & 1;
     const int kc_col = ((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) * 8;
     const int st_col = ((lane & 31) ^ ((2 * odd + (lane >> 5)) << 2)) * 8;
-    a_col[odd] = A_KC ? kc_col : st_col;
-    b_col[odd] = B_KC ? kc_col : st_col;
+    if (i < CH_A) a_off[i] = (unsigned)(((size_t)(a_row + i * (A_KC ? 8 : 2)) * lda + (A_KC ? kc_col : st_col)) * sizeof(bf16_t));
+    if (i < CH_B) b_off[i] = (unsigned)(((size_t)(b_row + i * (B_KC ? 8 : 2)) * ldb + (B_KC ? kc_col : st_col)) * sizeof(bf16_t));
   }
-  // element offset of this lane's piece 0 of k-tile 0 of an item (without the column swizzle)
-  auto a_origin = [&](int m0, int kb) { return A_KC ? (size_t)(m0 + a_row) * lda + kb : (size_t)(kb + a_row) * lda + m0; };
-  auto b_origin = [&](int n0, int kb) { return B_KC ? (size_t)(n0 + b_row) * ldb + kb : (size_t)(kb + b_row) * ldb + n0; };
+  // element offset of an item's k-tile 0 (the same in every lane)
+  auto a_origin = [&](int m0, int kb) { return A_KC ? (size_t)m0 * lda + kb : (size_t)kb * lda + m0; };
+  auto b_origin = [&](int n0, int kb) { return B_KC ? (size_t)n0 * ldb + kb : (size_t)kb * ldb + n0; };
   auto issue_a = [&](int stage, size_t ao, int t) {
     const unsigned sa = lds0 + EXTRA + stage * STAGE + wave * (CH_A * 1024);
     const bf16_t* pa = A + ao + (A_KC ? (size_t)t * BK : (size_t)t * BK * lda);
 #pragma unroll
-    for (int i = 0; i < CH_A; ++i) load_to_lds16(pa + (size_t)i * (A_KC ? 8 : 2) * lda + a_col[i & 1], sa + i * 1024);
+    for (int i = 0; i < CH_A; ++i) load_to_lds16_s(pa, a_off[i], sa + i * 1024);
   };
   auto issue_b = [&](int stage, size_t bo, int t) {
     const unsigned sb = lds0 + EXTRA + stage * STAGE + A_BYTES + wave * (CH_B * 1024);
     const bf16_t* pb = B + bo + (B_KC ? (size_t)t * BK : (size_t)t * BK * ldb);
 #pragma unroll
-    for (int i = 0; i < CH_B; ++i) load_to_lds16(pb + (size_t)i * (B_KC ? 8 : 2) * ldb + b_col[i & 1], sb + i * 1024);
+    for (int i = 0; i < CH_B; ++i) load_to_lds16_s(pb, b_off[i], sb + i * 1024);
   };
   auto issue = [&](int stage, size_t ao, size_t bo, int t) {
     issue_a(stage, ao, t);
@@ -690,8 +693,10 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   // whole tiles, 16-byte aligned rows: the direct-to-LDS kernel
   bool direct = false;
   if (!CONVS && BM == 256 && BN == 256 && BK == 64 && WGM == 2 && WGN == 4) {
+    // (a lane's piece offsets inside a tile are kept as 32-bit byte counts)
     direct = g.M % BM == 0 && g.N % BN == 0 && g.K % BK == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
-             ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (splits == 1 || g.N % 4 == 0);
+             ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (splits == 1 || g.N % 4 == 0) &&
+             (uint64_t)g.lda * 2 * 256 < (1ull << 31) && (uint64_t)g.ldb * 2 * 256 < (1ull << 31);
   }
   if (direct) {
     launch_direct<BM, BN, BK, WGM, WGN>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
