@@ -135,6 +135,19 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
     log("%d GiB: %.1f ms/step, all-keep=%s, peak %.2f GiB" % (wl["budget"] // GIB, dt * 1e3, acts == [0] * len(acts), summ["peak_bytes"] / GIB))
     acts_lo, summ_lo, dt_lo, loss_lo, _, _ = timed(wl["low_budget"], K.STEP_APPLY_OPTIMIZER)
     log("%d GiB: %.1f ms/step, plan %s" % (wl["low_budget"] // GIB, dt_lo * 1e3, "".join("KSRrc"[a] for a in acts_lo)))
+    # the same budget with the block granularity chosen by the planner as well (Sec. III-E/F, first tier)
+    acts_g, summ_g, group = ctx.karma_plan_grouped(wl["low_budget"])
+    for _ in range(2):
+        ctx.karma_step(images, labels, K.STEP_APPLY_OPTIMIZER)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.karma_step(images, labels, K.STEP_APPLY_OPTIMIZER)
+    torch.cuda.synchronize()
+    dt_g = (time.perf_counter() - t2) / args.steps
+    log("%d GiB, grouped planner: blocks of %d records, %.1f ms/step (predicted %.1f vs %.1f ms), plan %s"
+        % (wl["low_budget"] // GIB, group, dt_g * 1e3, summ_g["makespan_ns"] / 1e6, summ_lo["makespan_ns"] / 1e6,
+           "".join("KSRrc"[a] for a in acts_g)))
     n_l, ms_l, fl_l = gem
     achieved = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
     batch = cfg_m["batch"]
@@ -149,7 +162,10 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
         "supplementary_low_budget": {"hbm_budget_gib": wl["low_budget"] // GIB, "ms_per_step": dt_lo * 1e3,
                                      "samples_per_s": batch / dt_lo, "pct_of_in_core": 100.0 * dt / dt_lo,
                                      "plan": "".join("KSRrc"[a] for a in acts_lo), "arena_peak_gib": summ_lo["peak_bytes"] / GIB,
-                                     "swap_gib_each_way": summ_lo["bytes_d2h"] / GIB},
+                                     "swap_gib_each_way": summ_lo["bytes_d2h"] / GIB,
+                                     "grouped_planner": {"group_size": group, "ms_per_step": dt_g * 1e3,
+                                                         "predicted_makespan_ms": summ_g["makespan_ns"] / 1e6,
+                                                         "plan": "".join("KSRrc"[a] for a in acts_g)}},
         "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9}, "host_opt_ms": st["host_opt_ms"],
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (convolutions as implicit GEMMs and the FC layer; " + SAMPLING_NOTE + ")",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,

@@ -124,6 +124,17 @@ int karma_plan_pure(const karma_layer_cost* layers, uint32_t n_layers, const kar
                     const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
                     uint8_t* actions_out, uint8_t* weights_kept_out, karma_plan_summary* summary_out);
 
+/* The planner with the block granularity chosen as well (Sec. III-E/F: the first tier of the optimisation groups
+ * layers into blocks that are kept, swapped or recomputed as a whole).  For group sizes 1, 2, 3, 4, 6, 8 up to
+ * max_group, consecutive layers are merged, the merged stack is planned, the block-level plan is expanded to
+ * per-layer actions (a recomputed block checkpoints its first member's input and chains the rest) and priced by the
+ * per-layer simulator; the cheapest wins (the smaller size on ties), so the result is never worse than
+ * karma_plan_pure.  *group_out (may be NULL): the size chosen.  Outputs and errors as karma_plan_pure. */
+int karma_plan_grouped_pure(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                            const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes, uint32_t max_group,
+                            uint8_t* actions_out, uint8_t* weights_kept_out, karma_plan_summary* summary_out,
+                            uint32_t* group_out);
+
 /* Algorithm 1's output in the paper's notation ("F1 -> F2||S1^out -> ...", layers
  * 1-based, recompute printed as F; copies of streamed weights and of their gradients
  * print as W<i>^in and G<i>^out).  Writes a NUL-terminated string; KARMA_E_OOM if
@@ -236,6 +247,10 @@ int karma_set_costs(karma_ctx* ctx, const karma_layer_cost* layers, const karma_
  * between forward and backward. */
 int karma_plan(karma_ctx* ctx, uint64_t budget_bytes, uint8_t* actions_out, uint8_t* weights_kept_out,
                karma_plan_summary* summary_out);
+/* karma_plan with the block granularity chosen as well (see karma_plan_grouped_pure): plans on the context's
+ * cost records and installs the result.  *group_out (may be NULL): the group size chosen. */
+int karma_plan_grouped(karma_ctx* ctx, uint64_t hbm_budget_bytes, uint32_t max_group, uint8_t* actions_out,
+                       uint8_t* weights_kept_out, karma_plan_summary* summary_out, uint32_t* group_out);
 /* Forces an action vector and weight choice (weights_kept may be NULL = no layer keeps
  * its streamed weights); validated against the budget by simulation. */
 int karma_set_plan(karma_ctx* ctx, uint64_t budget_bytes, const uint8_t* actions, const uint8_t* weights_kept,

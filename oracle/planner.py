@@ -570,6 +570,77 @@ def plan(layers, link, budget, fixed, loss):
     return cur, res
 
 
+GROUP_SIZES = (1, 2, 3, 4, 6, 8)
+
+
+def merge_group(members):
+    """Cost record of consecutive layers planned as one block (Sec. III-E/F: the first tier of the
+    optimisation groups layers into blocks; a block is swapped, kept or recomputed as a whole).  Times
+    add up; the block's internals are its members' internals plus the boundaries between them; its
+    output is the last member's; workspace is the largest; streamed weights and gradients add up."""
+    return Layer(tf=sum(m.tf for m in members), tb=sum(m.tb for m in members), trc=sum(m.trc for m in members),
+                 sav=sum(m.sav for m in members) + sum(m.out for m in members[:-1]), out=members[-1].out,
+                 ws=max(m.ws for m in members), wb=sum(m.wb for m in members), gb=sum(m.gb for m in members))
+
+
+def expand_group_actions(group_actions, group_wres, sizes):
+    """Per-layer actions of a block-level plan: a kept or swapped block keeps or swaps every member; a
+    recomputed block keeps (or swaps) its first member's input as the checkpoint and recomputes the rest
+    in a chain from it; a chained block is chained throughout."""
+    acts, wres = [], []
+    for a, w, n in zip(group_actions, group_wres, sizes):
+        if a in (KEEP, SWAP, RC_CHAIN):
+            acts += [a] * n
+        else:
+            acts += [a] + [RC_CHAIN] * (n - 1)
+        wres += [w] * n
+    return acts, wres
+
+
+def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
+    """The planner with the block granularity chosen as well: for each group size g in GROUP_SIZES up to
+    max_group, consecutive layers are merged g at a time (the last block may be shorter), the merged stack
+    is planned, the block-level plan is expanded to per-layer actions and priced by the per-layer
+    simulator (which is what the executor follows; it sees every copy's latency and every allocation).
+    The cheapest expansion wins, the smaller group size on ties; g = 1 is the plain planner, so the result
+    is never worse than plan().  Returns (actions, summary, g)."""
+    L = len(layers)
+    best = None
+    for g in GROUP_SIZES:
+        if g > max_group or (g > 1 and g > L):
+            continue
+        sizes = [min(g, L - a) for a in range(0, L, g)]
+        if g == 1:
+            try:
+                acts, res = plan(layers, link, budget, fixed, loss)
+            except Infeasible:
+                continue
+            wres = res["wres"]
+        else:
+            merged, a = [], 0
+            for n in sizes:
+                merged.append(merge_group(layers[a:a + n]))
+                a += n
+            try:
+                gacts, gres = plan(merged, link, budget, fixed, loss)
+            except Infeasible:
+                continue
+            acts, wres = expand_group_actions(gacts, gres["wres"], sizes)
+            if not valid_actions(acts):
+                continue
+        c = try_cost(layers, link, budget, fixed, loss, acts, wres)
+        if c is None:
+            continue
+        if best is None or c < best[0]:
+            best = (c, acts, wres, g)
+    if best is None:
+        raise Infeasible()
+    _, acts, wres, g = best
+    res = simulate(layers, link, budget, fixed, loss, acts, wres=wres)
+    res["wres"] = wres
+    return acts, res, g
+
+
 def refine(layers, link, budget, fixed, loss, start):
     """Local search.  A candidate replaces the incumbent when its (cost tuple, action
     vector) is lexicographically smaller.  Neighbourhoods, in this order, repeated

@@ -152,6 +152,23 @@ def karma_plan_pure(layers, link, loss, budget, fixed):
     return list(act), res
 
 
+def karma_plan_grouped_pure(layers, link, loss, budget, fixed, max_group=8):
+    """Planner that also chooses the block granularity: (actions, summary incl. "wres", group size)."""
+    n = len(layers)
+    arr = _layers_array(layers)
+    lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
+    act = (C.c_uint8 * n)()
+    kept = (C.c_uint8 * n)()
+    summ = PlanSummary()
+    g = C.c_uint32()
+    st = lib().karma_plan_grouped_pure(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget), C.c_uint64(fixed),
+                                       C.c_uint32(max_group), act, kept, C.byref(summ), C.byref(g))
+    _check(st, "karma_plan_grouped_pure")
+    res = summ.as_dict()
+    res["wres"] = list(kept)
+    return list(act), res, g.value
+
+
 class DeviceRates(C.Structure):
     _fields_ = [("matrix_ops_per_s", C.c_uint64), ("other_ops_per_s", C.c_uint64)]
 
@@ -281,6 +298,17 @@ class Context:
         res = summ.as_dict()
         res["wres"] = list(kept)
         return list(act), res
+
+    def karma_plan_grouped(self, budget, max_group=8):
+        act = (C.c_uint8 * self.n_layers)()
+        kept = (C.c_uint8 * self.n_layers)()
+        summ = PlanSummary()
+        g = C.c_uint32()
+        self._chk(lib().karma_plan_grouped(self.ctx, C.c_uint64(int(budget)), C.c_uint32(max_group), act, kept,
+                                             C.byref(summ), C.byref(g)), "karma_plan_grouped")
+        res = summ.as_dict()
+        res["wres"] = list(kept)
+        return list(act), res, g.value
 
     def karma_set_plan(self, budget, actions, weights_kept=None):
         act = (C.c_uint8 * self.n_layers)(*actions)

@@ -39,6 +39,23 @@ extern "C" int karma_plan_pure(const karma_layer_cost* layers, uint32_t n_layers
   return KARMA_OK;
 }
 
+extern "C" int karma_plan_grouped_pure(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                                       const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
+                                       uint32_t max_group, uint8_t* actions_out, uint8_t* weights_kept_out,
+                                       karma_plan_summary* summary_out, uint32_t* group_out) {
+  if (!layers || !n_layers || !link || !loss || !actions_out || !link->bw_h2d || !link->bw_d2h || !max_group) return KARMA_E_INVAL;
+  Problem P{layers, n_layers, *link, *loss, budget_bytes, fixed_bytes};
+  std::vector<uint8_t> a, kw;
+  karma_plan_summary s;
+  uint32_t g = 1;
+  if (!plan_grouped(P, max_group, a, kw, &s, &g)) return KARMA_E_BUDGET;
+  std::memcpy(actions_out, a.data(), n_layers);
+  if (weights_kept_out) std::memcpy(weights_kept_out, kw.data(), n_layers);
+  if (summary_out) *summary_out = s;
+  if (group_out) *group_out = g;
+  return KARMA_OK;
+}
+
 extern "C" int karma_stage_string(const karma_op* ops, uint32_t n_ops, char* buf, size_t buf_len) {
   if (!ops || !buf) return KARMA_E_INVAL;
   std::string s = stage_string(ops, n_ops);

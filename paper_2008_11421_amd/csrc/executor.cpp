@@ -639,6 +639,24 @@ extern "C" int karma_plan(karma_ctx* c, uint64_t budget, uint8_t* actions_out, u
   return KARMA_OK;
 }
 
+extern "C" int karma_plan_grouped(karma_ctx* c, uint64_t budget, uint32_t max_group, uint8_t* actions_out,
+                                  uint8_t* weights_kept_out, karma_plan_summary* summary_out, uint32_t* group_out) {
+  if (!c || !max_group) return KARMA_E_INVAL;
+  if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
+  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
+  std::vector<uint8_t> a, kw;
+  karma_plan_summary s;
+  uint32_t g = 1;
+  if (!plan_grouped(P, max_group, a, kw, &s, &g)) return fail(c, KARMA_E_BUDGET, "no assignment fits the budget");
+  int st = install_plan(c, budget, a, kw);
+  if (st) return st;
+  if (actions_out) std::memcpy(actions_out, a.data(), c->L);
+  if (weights_kept_out) std::memcpy(weights_kept_out, kw.data(), c->L);
+  if (summary_out) *summary_out = c->summary;
+  if (group_out) *group_out = g;
+  return KARMA_OK;
+}
+
 extern "C" int karma_set_plan(karma_ctx* c, uint64_t budget, const uint8_t* actions, const uint8_t* weights_kept,
                               karma_plan_summary* summary_out) {
   if (!c || !actions) return KARMA_E_INVAL;

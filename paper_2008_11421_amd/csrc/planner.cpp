@@ -574,4 +574,69 @@ std::string stage_string(const karma_op* ops, uint32_t n) {
   return res;
 }
 
+// The planner with the block granularity chosen as well (Sec. III-E/F: the first tier of the
+// optimisation groups layers into blocks, which are then kept, swapped or recomputed as a whole).
+// For each candidate group size consecutive layers are merged (times, streamed weights and
+// gradients add up; the block's internals are its members' internals plus the boundaries between
+// them; its output is the last member's; workspace is the largest), the merged stack is planned, the
+// block-level plan is expanded to per-layer actions (a recomputed block keeps or swaps its first
+// member's input as the checkpoint and chains the rest) and priced by the per-layer simulator, which
+// is what the executor follows.  The cheapest expansion wins, the smaller group on ties; size 1 is
+// the plain planner, so the result is never worse than plan().
+bool plan_grouped(const Problem& P, uint32_t max_group, std::vector<uint8_t>& actions, std::vector<uint8_t>& keepw,
+                  karma_plan_summary* out, uint32_t* group_out) {
+  static const uint32_t sizes_tried[] = {1, 2, 3, 4, 6, 8};
+  const uint32_t L = P.n;
+  bool have = false;
+  Cost best{};
+  std::vector<uint8_t> best_a, best_w;
+  uint32_t best_g = 1;
+  for (uint32_t g : sizes_tried) {
+    if (g > max_group || (g > 1 && g > L)) continue;
+    std::vector<uint8_t> a, w;
+    if (g == 1) {
+      karma_plan_summary s;
+      if (!plan(P, a, w, &s)) continue;
+    } else {
+      std::vector<karma_layer_cost> merged;
+      std::vector<uint32_t> count;
+      for (uint32_t first = 0; first < L; first += g) {
+        const uint32_t n = std::min(g, L - first);
+        karma_layer_cost m{};
+        for (uint32_t k = 0; k < n; ++k) {
+          const karma_layer_cost& l = P.layers[first + k];
+          m.tf_ns += l.tf_ns; m.tb_ns += l.tb_ns; m.trc_ns += l.trc_ns;
+          m.sav_bytes += l.sav_bytes + (k + 1 < n ? l.out_bytes : 0);
+          m.ws_bytes = std::max(m.ws_bytes, l.ws_bytes);
+          m.w_bytes += l.w_bytes; m.g_bytes += l.g_bytes;
+        }
+        m.out_bytes = P.layers[first + n - 1].out_bytes;
+        merged.push_back(m);
+        count.push_back(n);
+      }
+      Problem G{merged.data(), (uint32_t)merged.size(), P.link, P.loss, P.budget, P.fixed};
+      std::vector<uint8_t> ga, gw;
+      karma_plan_summary s;
+      if (!plan(G, ga, gw, &s)) continue;
+      for (size_t b = 0; b < count.size(); ++b)
+        for (uint32_t k = 0; k < count[b]; ++k) {
+          const bool whole = ga[b] == KARMA_KEEP || ga[b] == KARMA_SWAP || ga[b] == KARMA_RC_CHAIN;
+          a.push_back(whole || k == 0 ? ga[b] : (uint8_t)KARMA_RC_CHAIN);
+          w.push_back(gw[b]);
+        }
+    }
+    Cost c;
+    if (!evaluate(P, a, c, w.data())) continue;
+    if (!have || c < best) {
+      have = true;
+      best = c; best_a = a; best_w = w; best_g = g;
+    }
+  }
+  if (!have) return false;
+  actions = best_a;
+  keepw = best_w;
+  if (group_out) *group_out = best_g;
+  return simulate(P, actions.data(), keepw.data(), out, nullptr);
+}
+
 }  // namespace karma

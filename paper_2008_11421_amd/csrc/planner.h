@@ -33,6 +33,8 @@ bool actions_valid(const uint8_t* a, uint32_t n);
 bool simulate(const Problem& P, const uint8_t* actions, const uint8_t* keepw, karma_plan_summary* out,
               std::vector<karma_op>* ops);
 bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>& keepw, karma_plan_summary* out);
+bool plan_grouped(const Problem& P, uint32_t max_group, std::vector<uint8_t>& actions, std::vector<uint8_t>& keepw,
+                  karma_plan_summary* out, uint32_t* group_out);
 std::string stage_string(const karma_op* ops, uint32_t n);
 
 }  // namespace karma
