@@ -46,46 +46,60 @@ __device__ __forceinline__ float wave_max(float v) {
 constexpr float LN_EPS = 1e-5f;
 constexpr int LN_MAXV_LIMIT = 12;   // 16-byte vectors per lane: rows up to 64*8*12 = 6144 elements
 
-// ---- LayerNorm forward: one wavefront per row, row held in registers ---------------
-template <int LN_MAXV>
+// ---- LayerNorm forward: a wavefront takes RW rows at a time, held in registers, all loads issued
+// before the first reduction.  RW = 1 is what runs: with several rows per wavefront the kernel
+// measured slower (fewer wavefronts to spread over the chip outweigh the deeper load queue).
+template <int LN_MAXV, int RW>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
                                                              const bf16_t* __restrict__ b, bf16_t* __restrict__ y,
                                                              float* __restrict__ stats, int rows, int h) {
-  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
+  const int lane = threadIdx.x & 63, row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * RW;
+  if (row0 >= rows) return;
   const int nv = h / 8;
-  float v[LN_MAXV][8];
-  float s = 0.f;
+  u32x4 raw[RW][LN_MAXV];
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    int c = lane + i * 64;
-    if (c < nv) {
-      unpack8(*(const u32x4*)(x + (size_t)row * h + c * 8), v[i]);
+  for (int r = 0; r < RW; ++r)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += v[i][e];
+    for (int i = 0; i < LN_MAXV; ++i) {
+      const int c = lane + i * 64;
+      if (c < nv && row0 + r < rows) raw[r][i] = *(const u32x4*)(x + (size_t)(row0 + r) * h + c * 8);
     }
-  }
-  const float mean = wave_sum(s) / (float)h;
-  float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i)
-    if (lane + i * 64 < nv)
+  for (int r = 0; r < RW; ++r) {
+    const int row = row0 + r;
+    if (row >= rows) break;
+    float v[LN_MAXV][8];
+    float s = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { float d = v[i][e] - mean; q = fmaf(d, d, q); }
-  const float rstd = rsqrtf(wave_sum(q) / (float)h + LN_EPS);
+    for (int i = 0; i < LN_MAXV; ++i) {
+      if (lane + i * 64 < nv) {
+        unpack8(raw[r][i], v[i]);
 #pragma unroll
-  for (int i = 0; i < LN_MAXV; ++i) {
-    int c = lane + i * 64;
-    if (c < nv) {
-      float gg[8], bb[8], o[8];
-      unpack8(*(const u32x4*)(g + c * 8), gg);
-      unpack8(*(const u32x4*)(b + c * 8), bb);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
-      *(u32x4*)(y + (size_t)row * h + c * 8) = pack8(o);
+        for (int e = 0; e < 8; ++e) s += v[i][e];
+      }
     }
+    const float mean = wave_sum(s) / (float)h;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i)
+      if (lane + i * 64 < nv)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { float d = v[i][e] - mean; q = fmaf(d, d, q); }
+    const float rstd = rsqrtf(wave_sum(q) / (float)h + LN_EPS);
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+      int c = lane + i * 64;
+      if (c < nv) {
+        float gg[8], bb[8], o[8];
+        unpack8(*(const u32x4*)(g + c * 8), gg);
+        unpack8(*(const u32x4*)(b + c * 8), bb);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
+        *(u32x4*)(y + (size_t)row * h + c * 8) = pack8(o);
+      }
+    }
+    if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
   }
-  if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
 }
 
 // ---- LayerNorm backward: dx per row (one wavefront per row); per-workgroup partial sums
@@ -108,19 +122,36 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) { dgam[i][e] = 0.f; dbet[i][e] = 0.f; }
   }
+  // the next row's vectors are requested before this row is reduced (a wavefront walks 16 rows)
+  const int first = blockIdx.x * LNB_ROWS + w * (LNB_ROWS / 4);
+  u32x4 nx[LN_MAXV], nd[LN_MAXV], na[LN_MAXV];
+  auto fetch = [&](int row) {
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+      const int c = lane + i * 64;
+      if (c < nv && row < rows) {
+        nx[i] = *(const u32x4*)(x + (size_t)row * h + c * 8);
+        nd[i] = *(const u32x4*)(dy + (size_t)row * h + c * 8);
+        if (add) na[i] = *(const u32x4*)(add + (size_t)row * h + c * 8);
+      }
+    }
+  };
+  fetch(first);
   for (int r = 0; r < LNB_ROWS / 4; ++r) {
-    const int row = blockIdx.x * LNB_ROWS + w * (LNB_ROWS / 4) + r;
+    const int row = first + r;
     if (row >= rows) break;
     const float mean = stats[2 * row], rstd = stats[2 * row + 1];
     float xh[LN_MAXV][8], dyg[LN_MAXV][8];
+    u32x4 cur_add[LN_MAXV];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
       int c = lane + i * 64;
       if (c < nv) {
         float xv[8], dv[8];
-        unpack8(*(const u32x4*)(x + (size_t)row * h + c * 8), xv);
-        unpack8(*(const u32x4*)(dy + (size_t)row * h + c * 8), dv);
+        unpack8(nx[i], xv);
+        unpack8(nd[i], dv);
+        cur_add[i] = na[i];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           xh[i][e] = (xv[e] - mean) * rstd;
@@ -132,13 +163,14 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
         }
       }
     }
+    if (r + 1 < LNB_ROWS / 4) fetch(row + 1);
     const float m1 = wave_sum(s1) / (float)h, m2 = wave_sum(s2) / (float)h;
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
       int c = lane + i * 64;
       if (c < nv) {
         float o[8], av[8];
-        if (add) unpack8(*(const u32x4*)(add + (size_t)row * h + c * 8), av);
+        if (add) unpack8(cur_add[i], av);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           o[e] = rstd * (dyg[i][e] - m1 - xh[i][e] * m2);
@@ -404,7 +436,7 @@ int layernorm_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, bf16_t* y, 
                   hipStream_t s) {
   if (h % 8 || h > 64 * 8 * LN_MAXV_LIMIT || rows <= 0) return KARMA_E_INVAL;
   const int per_lane = (h / 8 + 63) / 64;
-#define KARMA_LN_FWD(V) hipLaunchKernelGGL(layernorm_fwd_kernel<V>, dim3((rows + 3) / 4), dim3(256), 0, s, x, g, b, y, stats, rows, h)
+#define KARMA_LN_FWD(V) hipLaunchKernelGGL((layernorm_fwd_kernel<V, 1>), dim3((rows + 3) / 4), dim3(256), 0, s, x, g, b, y, stats, rows, h)
   if (per_lane <= 2) KARMA_LN_FWD(2);
   else if (per_lane <= 4) KARMA_LN_FWD(4);
   else if (per_lane <= 6) KARMA_LN_FWD(6);
