@@ -60,6 +60,28 @@ def test_gemm_layouts(g, m, n, k, flags):
     assert np.all(np.abs(back(c32) - ref) <= 1e-5 * scale + 1e-30)
 
 
+@pytest.mark.parametrize("m,n,k", [(256, 256, 64), (4096, 4352, 64), (4096, 4352, 128), (2048, 8704, 192)])
+@pytest.mark.parametrize("flags", [0, K.GEMM_A_STRIDED | K.GEMM_B_STRIDED])
+def test_gemm_whole_tile_shapes_with_few_k_tiles(g, m, n, k, flags):
+    """Shapes made of whole 256x256x64 tiles take the direct-to-LDS kernel; with one to three k-tiles
+    per output tile and more output tiles than workgroups (272 > 256) its tile stream crosses from one
+    work item into the next after every one, two or three tiles."""
+    import torch
+    a, ad = bf(si.normal(11, (m, k)))
+    b, bd = bf(si.normal(12, (n, k)))
+    ref = a @ b.T
+    if flags & K.GEMM_A_STRIDED:
+        ad = ad.t().contiguous()
+    if flags & K.GEMM_B_STRIDED:
+        bd = bd.t().contiguous()
+    c32 = torch.empty(m, n, dtype=torch.float32, device="cuda")
+    g.call(K.lib().karma_k_gemm_bf16, g.ptr(ad), g.ptr(bd), g.ptr(c32), None, None, m, n, k, flags | K.GEMM_OUT_F32,
+           None, 0, g.stream_ptr())
+    assert g.rel_l2(back(c32), ref) <= TOL_F32
+    scale = np.abs(a) @ np.abs(b.T)
+    assert np.all(np.abs(back(c32) - ref) <= 1e-5 * scale + 1e-30)
+
+
 def test_gemm_epilogues(g):
     import torch
     m, n, k = 200, 136, 72
