@@ -35,6 +35,11 @@ WORKLOADS = {
             name="configs[3]: 72-layer pre-LN GPT (8.3B parameters), hidden 3072, 24 heads, FFN 12288, seq 1024, "
                  "batch 8, vocab 51200, bf16 weights streamed per layer from pinned host memory, fp32 host "
                  "master/Adam, HBM budget 32 GiB"),
+    4: dict(cfg=dict(n_layers=78, hidden=4256, heads=28, ffn=17024, vocab=51200, seq=1024, batch=4),
+            budget=32 * GIB, arena=96 * GIB, seed=2008114205, stream=1,
+            name="configs[4]: 78-layer pre-LN GPT (17B parameters), hidden 4256, 28 heads of 152, FFN 17024, seq 1024, "
+                 "batch 4, vocab 51200, bf16 weights streamed per layer from pinned host memory and activations "
+                 "swapped, fp32 host master/Adam (about 256 GiB of host memory), HBM budget 32 GiB"),
 }
 CFG = WORKLOADS[1]["cfg"]
 BUDGET = WORKLOADS[1]["budget"]
@@ -73,6 +78,21 @@ def cpu_baseline(n_seq):
                 sample="fp64 numpy oracle, full step on %d sequences of 1024 tokens at true widths, depth 1 and 2 "
                        "(%.1f s + %.1f s); per-block %.2f s and embedding+head %.2f s extrapolated to %d blocks"
                        % (n_seq, ts[0], ts[1], t_block, t_rest, CFG["n_layers"]))
+
+
+def host_memory_note():
+    """Resident and pinned memory of this process as the kernel reports them (a log line only)."""
+    out = []
+    try:
+        for line in open("/proc/self/status"):
+            if line.split(":")[0] in ("VmRSS", "VmHWM", "VmLck", "VmPin"):
+                out.append(" ".join(line.split()))
+        for line in open("/proc/meminfo"):
+            if line.split(":")[0] in ("MemAvailable",):
+                out.append(" ".join(line.split()))
+    except OSError:
+        pass
+    return ", ".join(out)
 
 
 # KARMA_STEP_KERNEL_TIMES puts HIP events around one GEMM launch in eight and rotates which ones
@@ -184,9 +204,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-policies", action="store_true", help="skip the comparison policies (profiling runs)")
     ap.add_argument("--config", type=int, default=1, choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0,
+                    help="GPT workloads: truncate the depth to this many blocks (named in config.workload)")
     args = ap.parse_args()
     global CFG, BUDGET, ARENA, SEED
-    wl = WORKLOADS[args.config]
+    wl = dict(WORKLOADS[args.config])
+    if args.layers and wl.get("kind") != "cnn" and 0 < args.layers < wl["cfg"]["n_layers"]:
+        wl["cfg"] = dict(wl["cfg"], n_layers=args.layers)
+        wl["name"] += " -- DEPTH TRUNCATED to %d blocks for this run" % args.layers
     CFG, BUDGET, ARENA, SEED = wl["cfg"], wl["budget"], wl["arena"], wl["seed"]
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not supported"
@@ -240,7 +265,7 @@ def main():
     del params
     ids = ids.astype(np.int32)
     labels = labels.astype(np.int32)
-    log("setup %.1f s" % (time.perf_counter() - t0))
+    log("setup %.1f s; host memory of this process: %s" % (time.perf_counter() - t0, host_memory_note()))
 
     link = ctx.karma_measure(3)
     layers, loss_c, fixed = ctx.karma_get_costs()

@@ -153,7 +153,7 @@ typedef struct {
   uint32_t width;     /* MLP width / GPT hidden size / CNN: bottleneck width of the first stage (64) */
   uint32_t batch;
   uint32_t seq;       /* GPT: sequence length; CNN: image height = width (multiple of 32) */
-  uint32_t n_heads;   /* GPT only; width / n_heads must be 64 or 128 */
+  uint32_t n_heads;   /* GPT only; width / n_heads must be 64, 128 or 152 */
   uint32_t ffn;       /* GPT only */
   uint32_t vocab;     /* GPT: vocabulary; CNN: number of classes (multiple of 8) */
   uint32_t stream_weights; /* 1: the weights of every MLP layer / transformer block live in
@@ -365,7 +365,7 @@ int karma_k_sum_f32(const float* x_dev, float* out_dev, float* ws_dev, uint64_t 
  * (Sec. III-C self-attention layer).  qkv_dev bf16 [batch][seq][3*heads*d] with q|k|v in
  * thirds and head j in columns j*d..; ctx_dev bf16 [batch][seq][heads*d]; lse_dev fp32
  * [batch][heads][seq] receives log2 of the row sums of 2^(score*log2(e)/sqrt(d)).
- * seq must be a multiple of 128, d 64 or 128 (else KARMA_E_INVAL). */
+ * seq must be a multiple of 128, d 64, 128 or 152 (else KARMA_E_INVAL). */
 int karma_k_attention_fwd_bf16(const void* qkv_dev, void* ctx_dev, float* lse_dev, uint32_t batch, uint32_t seq,
                                uint32_t heads, uint32_t d, void* stream);
 /* Its backward: dqkv_dev (same layout as qkv) from dctx_dev, the forward's ctx and lse.

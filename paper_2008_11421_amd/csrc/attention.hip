@@ -57,9 +57,25 @@ __device__ __forceinline__ bf16x8 frag_regs(const f32x16& a, int s, float mul) {
   return f.v;
 }
 
+// Eight elements of a row starting at column col, zeros where the row (D columns) has ended
+template <int D>
+__device__ __forceinline__ bf16x8 row_frag(const bf16_t* row, int col) {
+  Frag f;
+  if (col < D) f.u = *(const u32x4*)(row + col);
+  else f.u = u32x4{0, 0, 0, 0};
+  return f.v;
+}
+// Threads that run a transposing TileMover over a [ROWS][COLS] tile: it hands out whole patches of
+// 4 rows x 8 columns, so the thread count has to divide their number.
+template <int ROWS, int COLS>
+constexpr int transposer_threads() {
+  constexpr int patches = ROWS * COLS / 32;
+  return patches % 256 == 0 ? 256 : patches < 256 ? patches : patches % 160 == 0 ? 160 : 64;
+}
+
 // ------------------------------------------------------------------------------- forward
 // grid (seq/128, heads, batch), 256 threads; wavefront w owns queries q0+32w .. q0+32w+31
-// and walks the keys in tiles of 128 (four 32-key sub-tiles; sub-tiles entirely after the
+// and walks the keys in tiles of 128 (64 for head dimensions above 128) made of 32-key sub-tiles (those entirely after the
 // wavefront's queries are skipped).
 // Workgroup -> (tile, head, batch).  Workgroup ids go round-robin over the 8 XCDs; all tiles
 // of one (batch, head) are given to the same XCD, so that head's K and V are fetched into one
@@ -82,13 +98,19 @@ __device__ __forceinline__ void attn_block(int& tile, int& head, int& b, bool he
   b = hb / H;
 }
 
-template <int D>
-__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+// Head dimensions that are no multiple of 32 (D = 152) run with the tiles padded to DP columns:
+// the movers fill columns D..DP-1 with zeros, so the padded part of Q, K, V and dO adds nothing to
+// any product, and the results' padded columns are not stored.
+template <int D, int DP>
+__global__ __launch_bounds__(256, (DP == 64 ? 2 : 1)) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                         float* __restrict__ lse, int S, int H) {
-  constexpr int KT = 128;   // keys per tile
-  constexpr int PK = D + LDS_PAD, PV = KT + LDS_PAD;
+  constexpr int KT = DP > 128 ? 64 : 128;   // keys per tile (the score tiles of one step stay in registers)
+  constexpr int NMT = KT / 32;
+  constexpr bool EXACT = D == DP;
+  constexpr int TV = transposer_threads<DP, KT>();
+  constexpr int PK = DP + LDS_PAD, PV = KT + LDS_PAD;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[KT * PK];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[D * PV];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[DP * PV];
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
   int tile, head, b;
@@ -102,46 +124,42 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
   const int qbase = q0 + 32 * w, query = qbase + lrow;
   const float c = LOG2E * rsqrtf((float)D);
 
-  bf16x8 qf[D / 16];
+  bf16x8 qf[DP / 16];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    Frag f;
-    f.u = *(const u32x4*)(Qg + (size_t)query * ld + ks * 16 + g * 8);
-    qf[ks] = f.v;
-  }
-  f32x16 o[D / 32];
+  for (int ks = 0; ks < DP / 16; ++ks) qf[ks] = row_frag<D>(Qg + (size_t)query * ld, ks * 16 + g * 8);
+  f32x16 o[DP / 32];
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i)
+  for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
   float m = -INFINITY, l = 0.f;   // m: running maximum of the raw scores (before the 1/sqrt(d) scale)
 
-  TileMover<KT, D, 256, true> mk;
-  TileMover<D, KT, 256, false> mv;
+  TileMover<KT, DP, 256, true> mk;
+  TileMover<DP, KT, TV, false> mv;
   const int n_kt = (q0 + 128) / KT;
-  mk.load(Kg, ld, 0, 0, S, D, tid, true);
-  mv.load(Vg, ld, 0, 0, D, S, tid, true);
+  mk.load(Kg, ld, 0, 0, S, D, tid, EXACT);
+  if (tid < TV) mv.load(Vg, ld, 0, 0, D, S, tid, EXACT);
   for (int kt = 0; kt < n_kt; ++kt) {
     const int key0 = kt * KT;
     __syncthreads();   // previous tile fully consumed
     mk.store(Ks, tid);
-    mv.store(Vt, tid);
+    if (tid < TV) mv.store(Vt, tid);
     __syncthreads();
     if (kt + 1 < n_kt) {   // next tile's loads stay in flight while this one is computed
-      mk.load(Kg, ld, key0 + KT, 0, S, D, tid, true);
-      mv.load(Vg, ld, 0, key0 + KT, D, S, tid, true);
+      mk.load(Kg, ld, key0 + KT, 0, S, D, tid, EXACT);
+      if (tid < TV) mv.load(Vg, ld, 0, key0 + KT, D, S, tid, EXACT);
     }
     // sub-tiles this wavefront needs: keys key0 + 32*mt <= last query
-    const int n_mt = min(4, (qbase + 31 - key0) / 32 + 1);
-    f32x16 s[4];
+    const int n_mt = min(NMT, (qbase + 31 - key0) / 32 + 1);
+    f32x16 s[NMT];
     float tmax = -INFINITY;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {
       if (mt < n_mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
+        for (int ks = 0; ks < DP / 16; ++ks) {
           bf16x8 kf = *(const bf16x8*)(Ks + (mt * 32 + lrow) * PK + ks * 16 + g * 8);
           s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[mt], 0, 0, 0);
         }
@@ -163,14 +181,14 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
       const float alpha = fast_exp2(m * c - mc);
       l *= alpha;
 #pragma unroll
-      for (int i = 0; i < D / 32; ++i)
+      for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
       m = m_new;
     }
     float psum = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {
       if (mt < n_mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -183,7 +201,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
         for (int st = 0; st < 2; ++st) {
           bf16x8 pf = frag_regs(s[mt], st, 1.f);
 #pragma unroll
-          for (int i = 0; i < D / 32; ++i) {
+          for (int i = 0; i < DP / 32; ++i) {
             bf16x8 vf = frag2(Vt + (i * 32 + lrow) * PV + mt * 32 + st * 16 + g * 4);
             o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[i], 0, 0, 0);
           }
@@ -196,13 +214,13 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_fwd_kernel(const 
   const float inv = 1.f / l;
   bf16_t* out = ctx + ((size_t)b * S + query) * h + (size_t)head * D;
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i)
+  for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
     for (int rg = 0; rg < 4; ++rg) {
       u32x2 v;
       v.x = pack2(o[i][rg * 4 + 0] * inv, o[i][rg * 4 + 1] * inv);
       v.y = pack2(o[i][rg * 4 + 2] * inv, o[i][rg * 4 + 3] * inv);
-      *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
+      if (EXACT || i * 32 + rg * 8 + g * 4 < D) *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
     }
   if (g == 0) lse[((size_t)b * H + head) * S + query] = m * c + log2f(l);
 }
@@ -446,17 +464,19 @@ __global__ void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __
 }
 
 // ------------------------------------------------------------------ backward: dQ
-// Same tiling as forward: wavefront owns 32 queries, walks the keys in tiles of 128.
-template <int D>
-__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
+// Same tiling as forward: wavefront owns 32 queries, walks the keys in tiles of 128 (or 64).
+template <int D, int DP>
+__global__ __launch_bounds__(256, (DP == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout, const float* __restrict__ lse,
     const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H) {
-  constexpr int KT = 128;
-  constexpr int PK = D + LDS_PAD, PT = KT + LDS_PAD;
+  constexpr int KT = DP > 128 ? 64 : 128, NMT = KT / 32;
+  constexpr bool EXACT = D == DP;
+  constexpr int TV = transposer_threads<DP, KT>();
+  constexpr int PK = DP + LDS_PAD, PT = KT + LDS_PAD;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   bf16_t* Ks = (bf16_t*)smem_attn;   // [KT][PK]
   bf16_t* Vs = Ks + KT * PK;         // [KT][PK]
-  bf16_t* Kt = Vs + KT * PK;         // [D][PT]   K transposed
+  bf16_t* Kt = Vs + KT * PK;         // [DP][PT]  K transposed
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
   int tile, head, b;
@@ -469,50 +489,47 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
   const int qbase = q0 + 32 * w, query = qbase + lrow;
   const float scale = rsqrtf((float)D), c = LOG2E * scale;
 
-  bf16x8 qf[D / 16], dof[D / 16];
+  bf16x8 qf[DP / 16], dof[DP / 16];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    Frag f;
-    f.u = *(const u32x4*)(base + (size_t)query * ld + ks * 16 + g * 8);
-    qf[ks] = f.v;
-    f.u = *(const u32x4*)(dout + ((size_t)b * S + query) * h + (size_t)head * D + ks * 16 + g * 8);
-    dof[ks] = f.v;
+  for (int ks = 0; ks < DP / 16; ++ks) {
+    qf[ks] = row_frag<D>(base + (size_t)query * ld, ks * 16 + g * 8);
+    dof[ks] = row_frag<D>(dout + ((size_t)b * S + query) * h + (size_t)head * D, ks * 16 + g * 8);
   }
   const float my_lse = lse[((size_t)b * H + head) * S + query];
   const float my_delta = delta[((size_t)b * H + head) * S + query];
-  f32x16 dq[D / 32];
+  f32x16 dq[DP / 32];
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i)
+  for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
-  TileMover<KT, D, 256, true> mk, mv;
-  TileMover<D, KT, 256, false> mkt;
+  TileMover<KT, DP, 256, true> mk, mv;
+  TileMover<DP, KT, TV, false> mkt;
   const int n_kt = (q0 + 128) / KT;
-  mk.load(Kg, ld, 0, 0, S, D, tid, true);
-  mv.load(Vg, ld, 0, 0, S, D, tid, true);
-  mkt.load(Kg, ld, 0, 0, D, S, tid, true);
+  mk.load(Kg, ld, 0, 0, S, D, tid, EXACT);
+  mv.load(Vg, ld, 0, 0, S, D, tid, EXACT);
+  if (tid < TV) mkt.load(Kg, ld, 0, 0, D, S, tid, EXACT);
   for (int kt = 0; kt < n_kt; ++kt) {
     const int key0 = kt * KT;
     __syncthreads();
     mk.store(Ks, tid);
     mv.store(Vs, tid);
-    mkt.store(Kt, tid);
+    if (tid < TV) mkt.store(Kt, tid);
     __syncthreads();
     if (kt + 1 < n_kt) {
-      mk.load(Kg, ld, key0 + KT, 0, S, D, tid, true);
-      mv.load(Vg, ld, key0 + KT, 0, S, D, tid, true);
-      mkt.load(Kg, ld, 0, key0 + KT, D, S, tid, true);
+      mk.load(Kg, ld, key0 + KT, 0, S, D, tid, EXACT);
+      mv.load(Vg, ld, key0 + KT, 0, S, D, tid, EXACT);
+      if (tid < TV) mkt.load(Kg, ld, 0, key0 + KT, D, S, tid, EXACT);
     }
-    const int n_mt = min(4, (qbase + 31 - key0) / 32 + 1);
+    const int n_mt = min(NMT, (qbase + 31 - key0) / 32 + 1);
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {
       if (mt < n_mt) {
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
+        for (int ks = 0; ks < DP / 16; ++ks) {
           bf16x8 kf = *(const bf16x8*)(Ks + (mt * 32 + lrow) * PK + ks * 16 + g * 8);
           bf16x8 vf = *(const bf16x8*)(Vs + (mt * 32 + lrow) * PK + ks * 16 + g * 8);
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
@@ -532,7 +549,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
         for (int st = 0; st < 2; ++st) {
           bf16x8 dsf = frag_regs(s, st, scale);
 #pragma unroll
-          for (int i = 0; i < D / 32; ++i) {
+          for (int i = 0; i < DP / 32; ++i) {
             bf16x8 ktf = frag2(Kt + (i * 32 + lrow) * PT + mt * 32 + st * 16 + g * 4);
             dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf, dq[i], 0, 0, 0);
           }
@@ -542,13 +559,13 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
   }
   bf16_t* out = dqkv + ((size_t)b * S + query) * ld + (size_t)head * D;
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i)
+  for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
     for (int rg = 0; rg < 4; ++rg) {
       u32x2 v;
       v.x = pack2(dq[i][rg * 4 + 0], dq[i][rg * 4 + 1]);
       v.y = pack2(dq[i][rg * 4 + 2], dq[i][rg * 4 + 3]);
-      *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
+      if (EXACT || i * 32 + rg * 8 + g * 4 < D) *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
     }
 }
 
@@ -675,19 +692,20 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
 // query tiles (64 queries, two 32-query sub-tiles) at or after them.  Scores are computed
 // with queries on the rows so that the probabilities sit in registers as the (key x query)
 // operand of dV = P^T dO and dK = dS^T Q.
-template <int D>
-__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
+template <int D, int DP>
+__global__ __launch_bounds__(256, (DP == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
     const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout, const float* __restrict__ lse,
     const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H) {
   constexpr int QT = 64;
-  constexpr int TT = (D * QT / 32 < 256) ? D * QT / 32 : 256;   // threads of the transposing movers
-  constexpr int PK = D + LDS_PAD, PT = QT + LDS_PAD;
+  constexpr bool EXACT = D == DP;
+  constexpr int TT = transposer_threads<DP, QT>();
+  constexpr int PK = DP + LDS_PAD, PT = QT + LDS_PAD;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   bf16_t* Qs = (bf16_t*)smem_attn;   // [QT][PK]
   bf16_t* Os = Qs + QT * PK;         // [QT][PK]   dO
-  bf16_t* Qt = Os + QT * PK;         // [D][PT]    Q transposed
-  bf16_t* Ot = Qt + D * PT;          // [D][PT]    dO transposed
-  float* lse_s = (float*)(Ot + D * PT);
+  bf16_t* Qt = Os + QT * PK;         // [DP][PT]   Q transposed
+  bf16_t* Ot = Qt + DP * PT;         // [DP][PT]   dO transposed
+  float* lse_s = (float*)(Ot + DP * PT);
   float* delta_s = lse_s + QT;
   const int h = H * D;
   const size_t ld = 3 * (size_t)h;
@@ -700,29 +718,26 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
   const int kbase = k0 + 32 * w, key = kbase + lrow;
   const float scale = rsqrtf((float)D), c = LOG2E * scale;
 
-  bf16x8 kf[D / 16], vf[D / 16];
+  bf16x8 kf[DP / 16], vf[DP / 16];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    Frag f;
-    f.u = *(const u32x4*)(base + h + (size_t)key * ld + ks * 16 + g * 8);
-    kf[ks] = f.v;
-    f.u = *(const u32x4*)(base + 2 * h + (size_t)key * ld + ks * 16 + g * 8);
-    vf[ks] = f.v;
+  for (int ks = 0; ks < DP / 16; ++ks) {
+    kf[ks] = row_frag<D>(base + h + (size_t)key * ld, ks * 16 + g * 8);
+    vf[ks] = row_frag<D>(base + 2 * h + (size_t)key * ld, ks * 16 + g * 8);
   }
-  f32x16 dk[D / 32], dv[D / 32];
+  f32x16 dk[DP / 32], dv[DP / 32];
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i)
+  for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-  TileMover<QT, D, 256, true> mq, mo;
-  TileMover<D, QT, TT, false> mqt, mot;
+  TileMover<QT, DP, 256, true> mq, mo;
+  TileMover<DP, QT, TT, false> mqt, mot;
   auto fetch = [&](int qq) {
-    mq.load(base, ld, qq, 0, S, D, tid, true);
-    mo.load(dOg, (size_t)h, qq, 0, S, D, tid, true);
+    mq.load(base, ld, qq, 0, S, D, tid, EXACT);
+    mo.load(dOg, (size_t)h, qq, 0, S, D, tid, EXACT);
     if (tid < TT) {
-      mqt.load(base, ld, 0, qq, D, S, tid, true);
-      mot.load(dOg, (size_t)h, 0, qq, D, S, tid, true);
+      mqt.load(base, ld, 0, qq, D, S, tid, EXACT);
+      mot.load(dOg, (size_t)h, 0, qq, D, S, tid, EXACT);
     }
   };
   fetch(k0);
@@ -760,7 +775,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
+        for (int ks = 0; ks < DP / 16; ++ks) {
           bf16x8 qfr = *(const bf16x8*)(Qs + (mt * 32 + lrow) * PK + ks * 16 + g * 8);
           bf16x8 ofr = *(const bf16x8*)(Os + (mt * 32 + lrow) * PK + ks * 16 + g * 8);
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[ks], s, 0, 0, 0);
@@ -788,7 +803,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
           bf16x8 pf = frag_regs(s, st, 1.f);
           bf16x8 dsf = frag_regs(dp, st, scale);
 #pragma unroll
-          for (int i = 0; i < D / 32; ++i) {
+          for (int i = 0; i < DP / 32; ++i) {
             bf16x8 otf = frag2(Ot + (i * 32 + lrow) * PT + mt * 32 + st * 16 + g * 4);
             bf16x8 qtf = frag2(Qt + (i * 32 + lrow) * PT + mt * 32 + st * 16 + g * 4);
             dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, otf, dv[i], 0, 0, 0);
@@ -800,13 +815,15 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
   }
   // dk[i][r]: key = kbase + (r/4)*8 + 4g + r%4, d = i*32 + lane%32
 #pragma unroll
-  for (int i = 0; i < D / 32; ++i)
+  for (int i = 0; i < DP / 32; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int kk = kbase + (r >> 2) * 8 + g * 4 + (r & 3);
       bf16_t* row = dqkv + ((size_t)b * S + kk) * ld + (size_t)head * D + i * 32 + lrow;
-      row[h] = f2bf(dk[i][r]);
-      row[2 * h] = f2bf(dv[i][r]);
+      if (EXACT || i * 32 + lrow < D) {
+        row[h] = f2bf(dk[i][r]);
+        row[2 * h] = f2bf(dv[i][r]);
+      }
     }
 }
 
@@ -945,7 +962,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* _
 }
 
 template <int D>
-constexpr size_t attn_dq_lds() { return (size_t)(2 * 128 * (D + LDS_PAD) + D * (128 + LDS_PAD)) * sizeof(bf16_t); }
+constexpr size_t attn_dq_lds() {
+  constexpr int KT = D > 128 ? 64 : 128;
+  return (size_t)(2 * KT * (D + LDS_PAD) + D * (KT + LDS_PAD)) * sizeof(bf16_t);
+}
 template <int D>
 constexpr size_t attn_dkv_lds() {
   return (size_t)(2 * 64 * (D + LDS_PAD) + 2 * D * (64 + LDS_PAD)) * sizeof(bf16_t) + 2 * 64 * sizeof(float);
@@ -955,7 +975,7 @@ constexpr size_t attn_dkv_lds() {
 static inline int ok() { return hipGetLastError() == hipSuccess ? KARMA_OK : KARMA_E_HIP; }
 
 int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq, int heads, int d, hipStream_t s) {
-  if (seq % 128 || (d != 64 && d != 128) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
+  if (seq % 128 || (d != 64 && d != 128 && d != 152) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
   dim3 grid(seq / 128, heads, batch);
   if (d == 64) {
     constexpr int KT = ATTN_FWD_KT, lds = 2 * 2 * KT * 64 * 2;   // two stages of (K tile, V tile)
@@ -963,11 +983,12 @@ int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, qkv, ctx, lse, seq, heads);
   }
-  else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, s, qkv, ctx, lse, seq, heads);
+  else if (d == 128) hipLaunchKernelGGL((attn_fwd_kernel<128, 128>), grid, dim3(256), 0, s, qkv, ctx, lse, seq, heads);
+  else hipLaunchKernelGGL((attn_fwd_kernel<152, 160>), grid, dim3(256), 0, s, qkv, ctx, lse, seq, heads);
   return ok();
 }
 
-template <int D>
+template <int D, int DP = D>
 static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse,
                        float* delta, bf16_t* dqkv, int seq, int heads) {
   if constexpr (D == 64) {
@@ -981,27 +1002,30 @@ static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t
     hipLaunchKernelGGL(kq, grid, dim3(256), l1, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
     hipLaunchKernelGGL(kkv, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
   } else {
-    constexpr size_t l1 = attn_dq_lds<D>(), l2 = attn_dkv_lds<D>();
-    if (l1 > 64 * 1024)
-      (void)hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l1);
-    if (l2 > 64 * 1024)
-      (void)hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<D>, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    constexpr size_t l1 = attn_dq_lds<DP>(), l2 = attn_dkv_lds<DP>();
+    auto kq = attn_bwd_dq_kernel<D, DP>;
+    auto kkv = attn_bwd_dkv_kernel<D, DP>;
+    if (l1 > 64 * 1024) (void)hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l1);
+    if (l2 > 64 * 1024) (void)hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, (int)l2);
+    hipLaunchKernelGGL(kq, grid, dim3(256), l1, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    hipLaunchKernelGGL(kkv, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
   }
 }
 
 int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,
                   bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s) {
-  if (seq % 128 || (d != 64 && d != 128) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
+  if (seq % 128 || (d != 64 && d != 128 && d != 152) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
   dim3 grid(seq / 128, heads, batch);
   const size_t total = (size_t)batch * seq * heads;
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (d == 64) {   // the dQ pass computes delta itself
     launch_bwd<64>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
-  } else {
+  } else if (d == 128) {
     hipLaunchKernelGGL(attn_delta_kernel<128>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
     launch_bwd<128>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
+  } else {
+    hipLaunchKernelGGL(attn_delta_kernel<152>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
+    launch_bwd<152, 160>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
   }
   return ok();
 }

@@ -141,7 +141,7 @@ int gpt_build_records(Ctx& c) {
   if (!md.n_layers || !md.width || !md.batch || !md.seq || !md.n_heads || !md.ffn || !md.vocab) return KARMA_E_INVAL;
   if (md.width % md.n_heads) return KARMA_E_INVAL;
   Dims d(md);
-  if ((d.D != 64 && d.D != 128) || d.S % 128 || d.h % 8 || d.ffn % 8 || d.V % 8) return KARMA_E_INVAL;
+  if ((d.D != 64 && d.D != 128 && d.D != 152) || d.S % 128 || d.h % 8 || d.ffn % 8 || d.V % 8) return KARMA_E_INVAL;
   if ((uint64_t)d.V * 2 > 150 * 1024) return KARMA_E_INVAL;
   const uint64_t act = (uint64_t)d.T * d.h * 2;
   c.rec.clear();

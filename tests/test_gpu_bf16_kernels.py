@@ -290,7 +290,8 @@ def test_softmax_cross_entropy(g, rows, cols):
     assert np.allclose(rowloss.cpu().numpy(), np.log(cols), rtol=1e-5)
 
 
-@pytest.mark.parametrize("B,S,H,D", [(2, 256, 3, 64), (1, 128, 1, 64), (1, 384, 2, 128), (2, 1024, 2, 64)])
+@pytest.mark.parametrize("B,S,H,D", [(2, 256, 3, 64), (1, 128, 1, 64), (1, 384, 2, 128), (2, 1024, 2, 64),
+                                     (1, 384, 2, 152), (2, 256, 3, 152)])
 def test_attention(g, B, S, H, D):
     import torch
     h = H * D
@@ -328,4 +329,4 @@ def test_attention_rejects_unsupported(g):
     t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda"); f = torch.zeros(1 << 12, device="cuda")
     lib = K.lib()
     assert lib.karma_k_attention_fwd_bf16(g.ptr(t), g.ptr(t), g.ptr(f), 1, 100, 1, 64, g.stream_ptr()) == K.E_INVAL
-    assert lib.karma_k_attention_fwd_bf16(g.ptr(t), g.ptr(t), g.ptr(f), 1, 128, 1, 152, g.stream_ptr()) == K.E_INVAL
+    assert lib.karma_k_attention_fwd_bf16(g.ptr(t), g.ptr(t), g.ptr(f), 1, 128, 1, 96, g.stream_ptr()) == K.E_INVAL

@@ -114,6 +114,32 @@ def test_attention_full_size_sampled_heads(g):
             assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
 
 
+def test_attention_head_dimension_152_full_shape_sampled_heads(g):
+    """The attention shape of the 17B-parameter configuration: batch 4, 28 heads of 152, 1024 tokens."""
+    import torch
+    b_, heads, d = 4, 28, 152
+    h = heads * d
+    qkv = dev_normal(113, (b_, S, 3 * h), 1.2)
+    dctx = dev_normal(114, (b_, S, h))
+    ctx = torch.empty(b_, S, h, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(b_, heads, S, device="cuda")
+    dqkv = torch.empty_like(qkv)
+    delta = torch.empty(b_, heads, S, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_attention_fwd_bf16, g.ptr(qkv), g.ptr(ctx), g.ptr(lse), b_, S, heads, d, g.stream_ptr())
+    g.call(lib.karma_k_attention_bwd_bf16, g.ptr(qkv), g.ptr(ctx), g.ptr(dctx), g.ptr(lse), g.ptr(delta), g.ptr(dqkv),
+           b_, S, heads, d, g.stream_ptr())
+    for (b, hd) in [(0, 0), (3, 27), (2, 13)]:
+        sl = [slice(c * h + hd * d, c * h + (hd + 1) * d) for c in range(3)]
+        q, k, v = (qkv[b, :, s_].float().cpu().numpy().astype(np.float64) for s_ in sl)
+        do = dctx[b, :, sl[0]].float().cpu().numpy().astype(np.float64)
+        o, p = nn.attention_fwd(q, k, v)
+        assert g.rel_l2(back(ctx[b, :, sl[0]]), o) <= TOL_ATTN
+        dq, dk, dv = nn.attention_bwd(q, k, v, p, do)
+        for name, ref, s_ in (("dq", dq, sl[0]), ("dk", dk, sl[1]), ("dv", dv, sl[2])):
+            assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
+
+
 def test_rowwise_kernels_full_size_sampled_rows(g):
     import torch
     lib = K.lib()

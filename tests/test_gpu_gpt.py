@@ -118,6 +118,32 @@ def test_gpt_step_matches_oracle_and_plans_are_bit_identical(g):
     ctx.close()
 
 
+def test_gpt_head_dimension_152_and_ragged_widths(g):
+    """Two blocks with heads of 152 (the 17B-parameter configuration's head size) and widths that are no
+    multiple of the GEMM tiles: the step against the oracle, swap and recompute plans bit-identical."""
+    dims = dict(n_layers=2, hidden=304, heads=2, ffn=600, vocab=520, seq=128, batch=2)
+    params, ids, labels = si.gpt_problem(seed=2008114205, n_layers=2, hidden=304, ffn=600, vocab=520, seq=128, batch=2,
+                                         std=0.05, bias_std=0.05)
+    ids, labels = ids.astype(np.int32), labels.astype(np.int32)
+    ctx = make_ctx(arena=512 << 20, **dims)
+    load_params(ctx, params)
+    big = 512 << 20
+    ctx.karma_set_plan(big, [K.KEEP] * 3)
+    loss = ctx.karma_step(ids, labels)
+    ref = all_grads(ctx, 2)
+    lo, go, _, _ = nn.gpt_step(rounded(params), ids, labels, dims["heads"])
+    assert abs(loss - lo) <= 2e-3 * abs(lo), (loss, lo)
+    og = oracle_grads(go)
+    for name, v in ref.items():
+        assert g.rel_l2(v, og[name]) <= TOL, (name, g.rel_l2(v, og[name]))
+    for pl in ([K.SWAP, K.RC_SWAP, K.RC_CHAIN], [K.KEEP, K.SWAP, K.RC_KEEP]):
+        ctx.karma_set_plan(big, pl)
+        assert ctx.karma_step(ids, labels) == loss, pl
+        for name, v in all_grads(ctx, 2).items():
+            assert np.array_equal(v, ref[name]), (pl, name)
+    ctx.close()
+
+
 def test_gpt_host_adam(g):
     params, ids, labels = small_problem()
     ctx = make_ctx(arena=512 << 20, lr=1e-2, **SMALL)

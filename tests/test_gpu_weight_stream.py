@@ -159,11 +159,14 @@ def test_gpt_streamed_weights_bit_identical_and_adam(g):
     ref_ctx.close()
 
 
-def test_gpt_8b_block_shape_streamed(g):
-    """Two blocks at the width of the 8.3B-parameter configuration (hidden 3072, 24 heads of
-    128, FFN 12288, vocabulary 51200, batch 8 x 1024 tokens): streamed against resident."""
-    dims = dict(n_layers=2, hidden=3072, heads=24, ffn=12288, vocab=51200, seq=1024, batch=8)
-    params, ids, labels = si.gpt_problem(seed=2008114204, n_layers=2, hidden=3072, ffn=12288, vocab=51200, seq=1024, batch=8)
+@pytest.mark.parametrize("hidden,heads,ffn,batch", [(3072, 24, 12288, 8), (4256, 28, 17024, 4)])
+def test_gpt_large_block_shapes_streamed(g, hidden, heads, ffn, batch):
+    """Two blocks at the widths of the 8.3B-parameter configuration (hidden 3072, 24 heads of 128, FFN 12288,
+    batch 8 x 1024 tokens) and of the 17B-parameter one (hidden 4256, 28 heads of 152, FFN 17024, batch 4 x
+    1024), vocabulary 51200: streamed against resident."""
+    dims = dict(n_layers=2, hidden=hidden, heads=heads, ffn=ffn, vocab=51200, seq=1024, batch=batch)
+    params, ids, labels = si.gpt_problem(seed=2008114204, n_layers=2, hidden=hidden, ffn=ffn, vocab=51200, seq=1024,
+                                         batch=batch)
     ids, labels = ids.astype(np.int32), labels.astype(np.int32)
     arena = 12 << 30
     out = []
@@ -172,7 +175,7 @@ def test_gpt_8b_block_shape_streamed(g):
         TG.load_params(ctx, params)
         layers, loss_c, fixed = ctx.karma_get_costs()
         if stream:
-            assert layers[1][6] >= 2 * 12 * 3072 * 3072 and fixed < out[0][3]
+            assert layers[1][6] >= 2 * 12 * hidden * hidden and fixed < out[0][3]
             ctx.karma_set_plan(arena, [K.KEEP, K.SWAP, K.RC_KEEP], [0, 0, 1])
         else:
             ctx.karma_set_plan(arena, [K.KEEP] * 3)
