@@ -140,6 +140,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
         acts, summ = ctx.karma_plan(budget)
         for _ in range(args.warmup):
             ctx.karma_step(images, labels, flags)
+        ctx.karma_finish_updates()   # host updates a step put off belong to the steps that produced them
         torch.cuda.synchronize()
         n_l, ms_l, fl_l = 0, 0.0, 0.0
         t1 = time.perf_counter()
@@ -148,6 +149,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
             if flags & K.STEP_KERNEL_TIMES:
                 n, ms, fl = ctx.karma_get_gemm_stats()
                 n_l += n; ms_l += ms; fl_l += fl
+        ctx.karma_finish_updates()
         torch.cuda.synchronize()
         return acts, summ, (time.perf_counter() - t1) / args.steps, loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
 
@@ -159,10 +161,12 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
     acts_g, summ_g, group = ctx.karma_plan_grouped(wl["low_budget"])
     for _ in range(2):
         ctx.karma_step(images, labels, K.STEP_APPLY_OPTIMIZER)
+    ctx.karma_finish_updates()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     for _ in range(args.steps):
         ctx.karma_step(images, labels, K.STEP_APPLY_OPTIMIZER)
+    ctx.karma_finish_updates()
     torch.cuda.synchronize()
     dt_g = (time.perf_counter() - t2) / args.steps
     log("%d GiB, grouped planner: blocks of %d records, %.1f ms/step (predicted %.1f vs %.1f ms), plan %s"
@@ -276,6 +280,7 @@ def main():
         acts, summ = ctx.karma_plan(budget)
         for _ in range(args.warmup):
             ctx.karma_step(ids, labels, flags)
+        ctx.karma_finish_updates()
         torch.cuda.synchronize()
         n_l, ms_l, fl_l = 0, 0.0, 0.0
         t0 = time.perf_counter()
@@ -284,6 +289,7 @@ def main():
             if flags & K.STEP_KERNEL_TIMES:
                 n, ms, fl = ctx.karma_get_gemm_stats()
                 n_l += n; ms_l += ms; fl_l += fl
+        ctx.karma_finish_updates()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
         return acts, summ, dt, loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
@@ -333,10 +339,12 @@ def main():
             policies[name] = {"feasible": False}
             continue
         ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+        ctx.karma_finish_updates()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for _ in range(n_pol):
             ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+        ctx.karma_finish_updates()
         torch.cuda.synchronize()
         dtp = (time.perf_counter() - t1) / n_pol
         policies[name] = {"feasible": True, "ms_per_step": dtp * 1e3, "samples_per_s": CFG["batch"] / dtp,

@@ -264,7 +264,8 @@ int karma_plan_string(karma_ctx* ctx, char* buf, size_t buf_len);
 /* One training step.  MLP: inputs_host fp32 [batch, width], labels_host fp32 targets of
  * the same shape.  GPT: inputs_host int32 token ids [batch, seq], labels_host int32
  * [batch, seq].  Synchronous: on return the loss is valid, all streams are drained and
- * gradients can be read. */
+ * gradients can be read; with KARMA_STEP_APPLY_OPTIMIZER some records' host updates may still
+ * be pending (karma_finish_updates). */
 int karma_step(karma_ctx* ctx, const void* inputs_host, const void* labels_host, uint32_t flags, float* loss_out);
 
 typedef struct {
@@ -274,8 +275,19 @@ typedef struct {
   uint64_t bytes_d2h, bytes_h2d;
   uint64_t arena_peak_bytes;
   double host_opt_ms;      /* host optimiser wall time */
+  uint64_t updates_deferred; /* records whose host update the step left pending (karma_finish_updates) */
 } karma_step_stats;
 int karma_get_stats(karma_ctx* ctx, karma_step_stats* out);
+/* Host updates that the last karma_step put off (Sec. III-G: the update of stage 5 overlaps the
+ * next iteration).  A step run with KARMA_STEP_APPLY_OPTIMIZER updates records on the host while
+ * the GPU is still busy with that step; once the GPU has finished, the records not yet updated are
+ * left pending and karma_step returns.  Each pending update is finished right before the first
+ * operation that reads the record's weights in the next karma_step, and before karma_get_param,
+ * karma_set_param, karma_plan / karma_set_plan and karma_measure touch anything.  This call
+ * finishes all of them now and waits for the weight copies they start (host thread blocks).
+ * A caller that times steps calls it before stopping the clock.  Steps run with
+ * KARMA_STEP_PROFILE never leave updates pending.  Returns KARMA_OK or the first error. */
+int karma_finish_updates(karma_ctx* ctx);
 /* The sampled GEMM launches of the last step run with KARMA_STEP_KERNEL_TIMES: how many were
  * timed, the sum of their durations (HIP events on the compute stream) and of their 2*m*n*k
  * flop counts.  Eight consecutive steps sample every launch of a step once. */

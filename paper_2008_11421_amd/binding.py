@@ -68,7 +68,7 @@ class Config(C.Structure):
 class StepStats(C.Structure):
     _fields_ = [("step_ms", C.c_double), ("compute_busy_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("bytes_d2h", C.c_uint64), ("bytes_h2d", C.c_uint64),
-                ("arena_peak_bytes", C.c_uint64), ("host_opt_ms", C.c_double)]
+                ("arena_peak_bytes", C.c_uint64), ("host_opt_ms", C.c_double), ("updates_deferred", C.c_uint64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}
@@ -333,6 +333,9 @@ class Context:
                                   C.byref(loss))
         self._chk(st, "karma_step")
         return loss.value
+
+    def karma_finish_updates(self):
+        self._chk(lib().karma_finish_updates(self.ctx), "karma_finish_updates")
 
     def karma_get_stats(self):
         s = StepStats()

@@ -107,6 +107,11 @@ struct Ctx {
   uint32_t n_segments = 0;                // GPT: distinct token ids of the current step
   std::unique_ptr<HostPool> pool;
   uint64_t step_no = 0;
+  // Host updates a step left for later (Sec. III-G, stage 5 overlapped with the next iteration): per record
+  // the step number its update belongs to, 0 = none.  The gradients are already in pinned host memory.
+  std::vector<uint64_t> pending_update;
+  hipEvent_t weights_uploaded = nullptr;  // recorded on the H2D stream after a late update's weight copies
+  hipEvent_t program_h2d_done = nullptr;  // recorded on the H2D stream behind the last copy of a step's program
   karma_step_stats stats{};
   std::string err;
 

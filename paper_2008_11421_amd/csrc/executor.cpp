@@ -218,8 +218,12 @@ struct Builder {
   }
 };
 
+int finish_all_updates(Ctx* c);
+
 int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions, const std::vector<uint8_t>& keepw) {
   if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
+  int fst = finish_all_updates(c);
+  if (fst) return fst;
   Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
   std::vector<karma_op> ops;
   karma_plan_summary s;
@@ -300,18 +304,19 @@ int send_grads(Ctx* c, uint32_t r, hipEvent_t after) {
 
 // host update of one record's master weights, chunk by chunk as the gradients land; each
 // chunk's new device weights go back at once
-int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed) {
+// step: the optimiser step the gradients belong to; landed: the gradients are known to be on the host
+// already (an update left over from a finished step), no event is waited for
+int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed, uint64_t step, bool landed) {
   const karma_config& g = c->cfg;
-  const uint64_t step = c->step_no;
   const bool streamed = c->rec[r].streamed;
   // streamed records: the whole gradient buffer arrives with one copy of the program, and
   // the new weights stay in pinned memory for the next step's copy-in
-  if (streamed) KARMA_HIP(c, hipEventSynchronize(grads_landed));
+  if (streamed && !landed) KARMA_HIP(c, hipEventSynchronize(grads_landed));
   for (Param& p : c->rec[r].p) {
     const uint64_t gs = p.grad_bf16 ? 2 : 4, ws = p.dev_bf16 ? 2 : 4;
     for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
       const uint64_t base = k * PARAM_CHUNK, n = std::min(PARAM_CHUNK, p.n - base);
-      if (!streamed) KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
+      if (!streamed && !landed) KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
       double t0 = now_ms();
       c->pool->parallel_for(n, [&](size_t lo, size_t hi) {
         const char* gp = (const char*)p.stage_g + (base + lo) * gs;
@@ -331,6 +336,34 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed) {
                                     hipMemcpyHostToDevice, c->st[1]));
     }
   }
+  return KARMA_OK;
+}
+
+// An update that the step which produced its gradients left for later: run it now.  reader: the stream of the
+// op about to read the record's weights (nullptr: none); it is made to wait for the weight copies.
+int finish_update(Ctx* c, uint32_t r, hipStream_t reader) {
+  if (r >= c->pending_update.size() || !c->pending_update[r]) return KARMA_OK;
+  const uint64_t step = c->pending_update[r];
+  c->pending_update[r] = 0;
+  int st = update_record(c, r, nullptr, step, true);
+  if (st) return st;
+  if (!c->rec[r].streamed && reader && reader != c->st[1]) {
+    KARMA_HIP(c, hipEventRecord(c->weights_uploaded, c->st[1]));
+    KARMA_HIP(c, hipStreamWaitEvent(reader, c->weights_uploaded, 0));
+  }
+  return KARMA_OK;
+}
+
+// Every update still owed, in record order, and the weight copies they start
+int finish_all_updates(Ctx* c) {
+  bool any = false;
+  for (uint32_t r = 0; r < c->pending_update.size(); ++r)
+    if (c->pending_update[r]) {
+      any = true;
+      int st = finish_update(c, r, nullptr);
+      if (st) return st;
+    }
+  if (any) KARMA_HIP(c, hipStreamSynchronize(c->st[1]));
   return KARMA_OK;
 }
 
@@ -367,6 +400,12 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
       if (st) return st;
       KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->misc_off), c->stage_misc, c->misc_bytes, hipMemcpyHostToDevice, s));
     }
+    // weights whose update the previous step left for now: finished right before their first reader (the
+    // forward pass asks for them in record order; the loss also reads tensors of other records)
+    if (p.kind == 'L') st = finish_all_updates(c);
+    else if (p.kind == 'F' || p.kind == 'R' || p.kind == 'B' || p.kind == 'W') st = finish_update(c, p.layer, s);
+    else st = KARMA_OK;
+    if (st) return st;
     if (profile) KARMA_HIP(c, hipEventRecord(c->ev_begin[k], s));
     st = issue(c, p);
     if (st) return st;
@@ -384,11 +423,28 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
     if (apply && p.kind == 'G') done_order.push_back({p.layer, c->ev[k]});
   }
   KARMA_HIP(c, hipMemcpyAsync(c->stage_loss, c->fixed_ptr(c->loss_off), sizeof(float), hipMemcpyDeviceToHost, sc));
-  for (const auto& d : done_order) {
-    st = update_record(c, d.first, d.second);
+  // Updates run here as their gradients land, while the GPU works on the rest of the step.  Once the GPU has
+  // finished the step, what is left is put off: the next step (or whoever asks for the weights) finishes each
+  // record's update right before its first use, so the forward pass of the next iteration overlaps them.
+  // (the H2D stream is asked through an event behind the program's own copies: the updates below add their
+  // weight copies to it)
+  KARMA_HIP(c, hipEventRecord(c->program_h2d_done, c->st[1]));
+  auto gpu_finished = [&]() {
+    if (hipStreamQuery(c->st[0]) == hipSuccess && hipStreamQuery(c->st[2]) == hipSuccess &&
+        hipEventQuery(c->program_h2d_done) == hipSuccess)
+      return true;
+    (void)hipGetLastError();   // "not ready" is an answer, not an error for the next launch check to find
+    return false;
+  };
+  size_t di = 0;
+  for (; di < done_order.size(); ++di) {
+    if (!profile && gpu_finished()) break;
+    st = update_record(c, done_order[di].first, done_order[di].second, c->step_no, false);
     if (st) return st;
   }
   for (int k = 0; k < 3; ++k) KARMA_HIP(c, hipStreamSynchronize(c->st[k]));
+  c->stats.updates_deferred = done_order.size() - di;
+  for (; di < done_order.size(); ++di) c->pending_update[done_order[di].first] = c->step_no;
   if (loss_out) *loss_out = *c->stage_loss;
   c->stats.step_ms = now_ms() - t0;
   c->stats.bytes_d2h = c->summary.bytes_d2h;
@@ -527,6 +583,12 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
         }
     }
   if (!ok) { karma_destroy(c); return KARMA_E_HOSTMEM; }
+  c->pending_update.assign(c->rec.size(), 0);
+  if (hipEventCreateWithFlags(&c->weights_uploaded, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->program_h2d_done, hipEventDisableTiming) != hipSuccess) {
+    karma_destroy(c);
+    return KARMA_E_HIP;
+  }
   c->pool.reset(new HostPool(cfg->host_threads ? cfg->host_threads : 1));
   *out = c;
   return KARMA_OK;
@@ -550,6 +612,8 @@ extern "C" void karma_destroy(karma_ctx* c) {
   if (c->stage_loss) (void)hipHostFree(c->stage_loss);
   if (c->stage_misc) (void)hipHostFree(c->stage_misc);
   for (auto e : c->kev) (void)hipEventDestroy(e);
+  if (c->weights_uploaded) (void)hipEventDestroy(c->weights_uploaded);
+  if (c->program_h2d_done) (void)hipEventDestroy(c->program_h2d_done);
   delete c;
 }
 
@@ -571,6 +635,8 @@ extern "C" int karma_set_param(karma_ctx* c, uint32_t layer, uint32_t t, const f
   if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
   Param& p = c->rec[layer].p[t];
   if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_set_param: element count mismatch");
+  int st = finish_all_updates(c);
+  if (st) return st;
   std::memcpy(p.master.data(), host, n * sizeof(float));
   if (p.dev_bf16) for (uint64_t i = 0; i < n; ++i) ((uint16_t*)p.stage_w)[i] = f32_to_bf16_rne(host[i]);
   else std::memcpy(p.stage_w, host, n * sizeof(float));
@@ -582,6 +648,8 @@ extern "C" int karma_get_param(karma_ctx* c, uint32_t layer, uint32_t t, float* 
   if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
   Param& p = c->rec[layer].p[t];
   if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_get_param: element count mismatch");
+  int st = finish_all_updates(c);
+  if (st) return st;
   std::memcpy(host, p.master.data(), n * sizeof(float));
   return KARMA_OK;
 }
@@ -681,6 +749,11 @@ extern "C" int karma_plan_string(karma_ctx* c, char* buf, size_t len) {
 extern "C" int karma_step(karma_ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out) {
   if (!c || !in || !lab) return KARMA_E_INVAL;
   return run_step(c, in, lab, flags, loss_out, (flags & KARMA_STEP_PROFILE) != 0);
+}
+
+extern "C" int karma_finish_updates(karma_ctx* c) {
+  if (!c) return KARMA_E_INVAL;
+  return finish_all_updates(c);
 }
 
 extern "C" int karma_get_stats(karma_ctx* c, karma_step_stats* out) {

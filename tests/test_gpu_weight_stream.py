@@ -104,6 +104,36 @@ def test_mlp_streamed_sgd_updates_reach_the_next_step(g):
     ctx.close()
 
 
+@pytest.mark.parametrize("stream", [False, True])
+def test_updates_left_for_the_next_step_change_nothing(g, stream):
+    """A host that is slower than the GPU (one thread, 8 layers of 1024 x 1024) leaves updates pending when a
+    step returns; the next step finishes each right before the record's first use.  Losses and parameters
+    equal, bit for bit, those of a run that finishes all updates after every step."""
+    Ws, bs, x, t = si.mlp_problem(seed=91, n_layers=8, width=1024, batch=16)
+    res = []
+    for finish_each_step in (False, True):
+        desc = dict(kind=K.MODEL_MLP, n_layers=8, width=1024, batch=16, seq=0, n_heads=0, ffn=0, vocab=0,
+                    stream_weights=int(stream))
+        ctx = K.Context(desc, dict(optimizer=K.OPT_ADAM, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=1), 256 << 20)
+        TM.load_problem(ctx, Ws, bs)
+        ctx.karma_set_plan(128 << 20, [K.KEEP, K.SWAP, K.RC_KEEP, K.RC_CHAIN, K.KEEP, K.RC_SWAP, K.KEEP, K.KEEP],
+                           [0, 1, 0, 1, 0, 0, 1, 0] if stream else None)
+        losses, deferred = [], 0
+        for _ in range(4):
+            losses.append(ctx.karma_step(x, t, K.STEP_APPLY_OPTIMIZER))
+            deferred += ctx.karma_get_stats()["updates_deferred"]
+            if finish_each_step:
+                ctx.karma_finish_updates()
+        losses.append(ctx.karma_step(x, t))           # a step without the optimiser still sees the last update
+        params = [ctx.karma_get_param(i, k) for i in range(8) for k in range(2)]
+        res.append((losses, params, deferred))
+        ctx.close()
+    assert res[0][2] > 0, "no update was ever left pending: the test does not exercise the path"
+    assert res[0][0] == res[1][0] and res[0][0][-1] < res[0][0][0]
+    for a, b in zip(res[0][1], res[1][1]):
+        assert np.array_equal(a, b)
+
+
 def gpt_ctx(stream, arena, dims, lr=1e-2):
     desc = dict(kind=K.MODEL_GPT, n_layers=dims["n_layers"], width=dims["hidden"], batch=dims["batch"], seq=dims["seq"],
                 n_heads=dims["heads"], ffn=dims["ffn"], vocab=dims["vocab"], stream_weights=int(stream))
