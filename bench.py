@@ -36,10 +36,11 @@ WORKLOADS = {
                  "batch 8, vocab 51200, bf16 weights streamed per layer from pinned host memory, fp32 host "
                  "master/Adam, HBM budget 32 GiB"),
     4: dict(cfg=dict(n_layers=78, hidden=4256, heads=28, ffn=17024, vocab=51200, seq=1024, batch=4),
-            budget=32 * GIB, arena=96 * GIB, seed=2008114205, stream=1,
+            budget=32 * GIB, arena=96 * GIB, seed=2008114205, stream=2,
             name="configs[4]: 78-layer pre-LN GPT (17B parameters), hidden 4256, 28 heads of 152, FFN 17024, seq 1024, "
-                 "batch 4, vocab 51200, bf16 weights streamed per layer from pinned host memory and activations "
-                 "swapped, fp32 host master/Adam (about 256 GiB of host memory), HBM budget 32 GiB"),
+                 "batch 4, vocab 51200, bf16 weights streamed per layer from pinned host memory (gradients land in "
+                 "the same pinned buffers) and activations swapped, fp32 host master/Adam (about 225 GiB of host "
+                 "memory), HBM budget 32 GiB"),
 }
 CFG = WORKLOADS[1]["cfg"]
 BUDGET = WORKLOADS[1]["budget"]
@@ -283,16 +284,23 @@ def main():
         ctx.karma_finish_updates()
         torch.cuda.synchronize()
         n_l, ms_l, fl_l = 0, 0.0, 0.0
+        host_ms = []
         t0 = time.perf_counter()
         for _ in range(args.steps):
             loss = ctx.karma_step(ids, labels, flags)
+            host_ms.append(ctx.karma_get_stats()["host_opt_ms"])
             if flags & K.STEP_KERNEL_TIMES:
                 n, ms, fl = ctx.karma_get_gemm_stats()
                 n_l += n; ms_l += ms; fl_l += fl
         ctx.karma_finish_updates()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
-        return acts, summ, dt, loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
+        st = ctx.karma_get_stats()
+        # updates a step leaves pending are counted where they run (the next step, or the call above): the
+        # average over the timed steps is the host optimiser's time per step
+        host_ms[-1] = st["host_opt_ms"]
+        st["host_opt_ms"] = sum(host_ms) / len(host_ms)
+        return acts, summ, dt, loss, (n_l, ms_l, fl_l), st
 
     acts_in, summ_in, dt_in, loss_in, _, st_in = timed(ARENA, K.STEP_APPLY_OPTIMIZER)
     log("in-core: %.1f ms/step (host optimiser %.1f ms), plan all-keep=%s" % (dt_in * 1e3, st_in["host_opt_ms"], acts_in == [0] * len(acts_in)))

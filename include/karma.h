@@ -159,7 +159,14 @@ typedef struct {
   uint32_t stream_weights; /* 1: the weights of every MLP layer / transformer block live in
                               pinned host memory and are streamed through the arena around the
                               layer's ops, their gradients streamed out after its backward
-                              (Sec. III-G); embeddings and the final LayerNorm stay resident */
+                              (Sec. III-G); embeddings and the final LayerNorm stay resident.
+                              2: the same, and a block's gradients land in the pinned buffer its
+                              weights were copied from (the host update replaces each gradient by
+                              the new weight): half the pinned memory.  The gradients then leave the
+                              device only in steps run with KARMA_STEP_APPLY_OPTIMIZER, and
+                              karma_get_grad on such a block returns KARMA_E_STATE.  Tensors whose
+                              gradient is wider than the weight (fp32 gradients of bf16 vectors)
+                              keep a small gradient buffer of their own */
   uint32_t stage_blocks[4]; /* CNN only: bottleneck blocks per stage (ResNet-200: 3, 24, 36, 3).
                                Stage k has bottleneck width `width << k` and 4x that many output
                                channels; its first block carries stride 2 (stage 0: 1) on the 3x3
@@ -205,6 +212,8 @@ int karma_get_grad(karma_ctx* ctx, uint32_t layer, uint32_t tensor, float* host_
  * the loops karma_step runs per record as its gradients land.  All pointers are host pointers.  master (fp32,
  * updated in place), m and v (fp32 moments, in place; m alone for SGD with momentum, none for SGD), grad (fp32 or,
  * with grad_is_bf16, bf16 bit patterns), out (the new weights in device format: bf16 when out_is_bf16, else fp32).
+ * out may be the gradient buffer itself when both have one element type (each gradient is then replaced by its new
+ * weight); no other overlap is allowed.
  * optimizer: karma_opt_kind; Adam is bias-corrected, step counts from 1.  narrow_vectors != 0 forces the AVX2
  * build of the loops (the AVX-512 build is used where the CPU has it; both give identical results).  Not
  * thread-safe.  Errors: KARMA_E_INVAL. */

@@ -46,6 +46,8 @@ struct Record {
   uint64_t w_total = 0, g_total = 0;     // bytes of the two buffers (parameters 256-B aligned)
   char* stage_w_all = nullptr;           // pinned; Param::stage_w point into it
   char* stage_g_all = nullptr;           // pinned; Param::stage_g point into it
+  uint64_t shared_bytes = 0;             // leading part of both buffers: tensors whose gradient has the weight's type
+  bool shared_staging = false;           // that part of the gradients lands in stage_w_all; stage_g_all holds the rest
 };
 
 // One op of the executable schedule; offsets are relative to the activation region,
@@ -107,6 +109,7 @@ struct Ctx {
   uint32_t n_segments = 0;                // GPT: distinct token ids of the current step
   std::unique_ptr<HostPool> pool;
   uint64_t step_no = 0;
+  bool applying = false;                  // the step being issued applies the optimiser
   // Host updates a step left for later (Sec. III-G, stage 5 overlapped with the next iteration): per record
   // the step number its update belongs to, 0 = none.  The gradients are already in pinned host memory.
   std::vector<uint64_t> pending_update;

@@ -281,6 +281,18 @@ int issue(Ctx* c, const ProgOp& p) {
       KARMA_HIP(c, hipMemcpyAsync(c->act_ptr(p.w), c->rec[p.layer].stage_w_all, c->rec[p.layer].w_total, hipMemcpyHostToDevice, s));
       return KARMA_OK;
     case 'G':
+      // gradients that share the weights' pinned buffer leave the device only when the host update that
+      // turns them into the next weights is part of the step
+      if (c->rec[p.layer].shared_staging) {
+        const Record& r = c->rec[p.layer];
+        if (!c->applying) return KARMA_OK;
+        if (r.shared_bytes)
+          KARMA_HIP(c, hipMemcpyAsync(r.stage_w_all, c->act_ptr(p.g), r.shared_bytes, hipMemcpyDeviceToHost, s));
+        if (r.g_total > r.shared_bytes)
+          KARMA_HIP(c, hipMemcpyAsync(r.stage_g_all, c->act_ptr(p.g) + r.shared_bytes, r.g_total - r.shared_bytes,
+                                      hipMemcpyDeviceToHost, s));
+        return KARMA_OK;
+      }
       KARMA_HIP(c, hipMemcpyAsync(c->rec[p.layer].stage_g_all, c->act_ptr(p.g), c->rec[p.layer].g_total, hipMemcpyDeviceToHost, s));
       return KARMA_OK;
   }
@@ -373,6 +385,7 @@ static const unsigned GEMM_TIMER_STRIDE = 8;
 int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out, bool profile) {
   if (!c->planned) return fail(c, KARMA_E_STATE, "karma_step before karma_plan / karma_set_plan");
   const bool apply = flags & KARMA_STEP_APPLY_OPTIMIZER;
+  c->applying = apply;
   c->ktime = (flags & KARMA_STEP_KERNEL_TIMES) != 0;
   c->kev_used = 0;
   c->kflops.clear();
@@ -487,9 +500,15 @@ int karma::derive_layout(Ctx& c) {
   uint64_t off = 0;
   for (Record& r : c.rec) {
     if (r.streamed) {
-      for (Param& p : r.p) {
-        p.w_rel = r.w_total; r.w_total += up256(p.w_bytes());
-        p.g_rel = r.g_total; r.g_total += up256(p.g_bytes());
+      // tensors whose gradient has the weight's element type come first: their offsets in the record's
+      // weight and gradient buffers coincide (one pinned buffer can then serve both)
+      for (int pass = 0; pass < 2; ++pass) {
+        for (Param& p : r.p) {
+          if ((p.w_bytes() == p.g_bytes()) != (pass == 0)) continue;
+          p.w_rel = r.w_total; r.w_total += up256(p.w_bytes());
+          p.g_rel = r.g_total; r.g_total += up256(p.g_bytes());
+        }
+        if (pass == 0) r.shared_bytes = r.w_total;
       }
       continue;
     }
@@ -528,6 +547,7 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   if (((uintptr_t)arena_dev & 255) != 0) return KARMA_E_INVAL;
   if (cfg->optimizer != KARMA_OPT_SGD && cfg->optimizer != KARMA_OPT_ADAM && cfg->optimizer != KARMA_OPT_SGD_MOMENTUM)
     return KARMA_E_INVAL;
+  if (desc->stream_weights > 2) return KARMA_E_INVAL;
   karma_ctx* c = new (std::nothrow) karma_ctx();
   if (!c) return KARMA_E_HOSTMEM;
   c->desc = *desc;
@@ -554,15 +574,27 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   for (Record& r : c->rec) {
     if (r.streamed) {
       pin((void**)&r.stage_w_all, r.w_total);
-      pin((void**)&r.stage_g_all, r.g_total);
-      if (ok) { std::memset(r.stage_w_all, 0, r.w_total); std::memset(r.stage_g_all, 0, r.g_total); }
+      if (desc->stream_weights == 2) {
+        // gradients of the weight's element type land in the weights' buffer (same offsets); the others
+        // (fp32 gradients of bf16 vectors) get a small buffer of their own
+        r.shared_staging = true;
+        pin((void**)&r.stage_g_all, r.g_total - r.shared_bytes);
+        if (ok) { std::memset(r.stage_w_all, 0, r.w_total); std::memset(r.stage_g_all, 0, r.g_total - r.shared_bytes); }
+      } else {
+        pin((void**)&r.stage_g_all, r.g_total);
+        if (ok) { std::memset(r.stage_w_all, 0, r.w_total); std::memset(r.stage_g_all, 0, r.g_total); }
+      }
     }
     for (Param& p : r.p) {
       p.master.assign(p.n, 0.f);
       if (cfg->optimizer == KARMA_OPT_ADAM) { p.m.assign(p.n, 0.f); p.v.assign(p.n, 0.f); }
       if (cfg->optimizer == KARMA_OPT_SGD_MOMENTUM) p.m.assign(p.n, 0.f);
       if (r.streamed) {
-        if (ok) { p.stage_w = r.stage_w_all + p.w_rel; p.stage_g = r.stage_g_all + p.g_rel; }
+        if (ok) {
+          p.stage_w = r.stage_w_all + p.w_rel;
+          if (!r.shared_staging) p.stage_g = r.stage_g_all + p.g_rel;
+          else p.stage_g = p.g_rel < r.shared_bytes ? r.stage_w_all + p.g_rel : r.stage_g_all + (p.g_rel - r.shared_bytes);
+        }
       } else {
         pin(&p.stage_g, p.g_bytes());
         pin(&p.stage_w, p.w_bytes());
@@ -658,6 +690,8 @@ extern "C" int karma_get_grad(karma_ctx* c, uint32_t layer, uint32_t t, float* h
   if (!c || !host || layer >= c->rec.size() || t >= c->rec[layer].p.size()) return KARMA_E_INVAL;
   Param& p = c->rec[layer].p[t];
   if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_get_grad: element count mismatch");
+  if (c->rec[layer].shared_staging)
+    return fail(c, KARMA_E_STATE, "karma_get_grad: this record's gradients share the weights' pinned buffer (stream_weights 2)");
   // gradients of streamed weights were copied out by the step itself
   if (!c->rec[layer].streamed) KARMA_HIP(c, hipMemcpy(p.stage_g, c->arena + p.g_off, p.g_bytes(), hipMemcpyDeviceToHost));
   if (p.grad_bf16) for (uint64_t i = 0; i < n; ++i) host[i] = bf16_to_f32(((const uint16_t*)p.stage_g)[i]);

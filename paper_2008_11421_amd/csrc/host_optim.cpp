@@ -135,6 +135,7 @@ extern "C" int karma_host_update(uint32_t optimizer, float* master, float* m, fl
                                  uint64_t step, void* out, uint32_t out_is_bf16, uint32_t narrow_vectors) {
   using namespace karma;
   if (!master || !grad || !out) return KARMA_E_INVAL;
+  if (grad == out && (grad_is_bf16 != 0) != (out_is_bf16 != 0)) return KARMA_E_INVAL;   // in place needs equal element types
   host_optim_force_narrow(narrow_vectors != 0);
   int st = KARMA_OK;
   if (optimizer == KARMA_OPT_SGD) sgd_update(master, grad, grad_is_bf16 != 0, (size_t)n, lr, out, out_is_bf16 != 0);

@@ -42,8 +42,11 @@ static inline void store_w(void* out, size_t i, float w) {
   }
 }
 
-template <bool G_BF16, bool O_BF16>
-static void sgd_loop(float* __restrict__ w, const void* __restrict__ g, size_t n, float lr, void* __restrict__ out) {
+// INPLACE: the gradient lies in the output buffer (same element type) and each element is replaced by its new
+// weight; only `out` is then used, so that no two restrict-qualified pointers name the same memory.
+template <bool G_BF16, bool O_BF16, bool INPLACE>
+static void sgd_loop(float* __restrict__ w, const void* __restrict__ g_in, size_t n, float lr, void* __restrict__ out) {
+  const void* g = INPLACE ? out : g_in;
   for (size_t i = 0; i < n; ++i) {
     float nw = w[i] - lr * load_g<G_BF16>(g, i);
     w[i] = nw;
@@ -51,10 +54,11 @@ static void sgd_loop(float* __restrict__ w, const void* __restrict__ g, size_t n
   }
 }
 
-template <bool G_BF16, bool O_BF16>
-static void adam_loop(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v, const void* __restrict__ g,
+template <bool G_BF16, bool O_BF16, bool INPLACE>
+static void adam_loop(float* __restrict__ w, float* __restrict__ m, float* __restrict__ v, const void* __restrict__ g_in,
                       size_t n, float lr, float beta1, float beta2, float eps, float c1, float c2,
                       void* __restrict__ out) {
+  const void* g = INPLACE ? out : g_in;
   const float ob1 = 1.0f - beta1, ob2 = 1.0f - beta2;
   for (size_t i = 0; i < n; ++i) {
     float gi = load_g<G_BF16>(g, i);
@@ -68,9 +72,10 @@ static void adam_loop(float* __restrict__ w, float* __restrict__ m, float* __res
   }
 }
 
-template <bool G_BF16, bool O_BF16>
-static void sgd_momentum_loop(float* __restrict__ w, float* __restrict__ buf, const void* __restrict__ g, size_t n, float lr,
+template <bool G_BF16, bool O_BF16, bool INPLACE>
+static void sgd_momentum_loop(float* __restrict__ w, float* __restrict__ buf, const void* __restrict__ g_in, size_t n, float lr,
                               float mu, void* __restrict__ out) {
+  const void* g = INPLACE ? out : g_in;
   for (size_t i = 0; i < n; ++i) {
     float bi = mu * buf[i] + load_g<G_BF16>(g, i);
     buf[i] = bi;
@@ -80,36 +85,35 @@ static void sgd_momentum_loop(float* __restrict__ w, float* __restrict__ buf, co
   }
 }
 
+// g == out (with equal element types: the caller checks) selects the in-place loops
+#define KARMA_OPT_DISPATCH(LOOP, G, ...)                                                      \
+  do {                                                                                        \
+    if ((const void*)out == G) {                                                              \
+      if (g_is_bf16) LOOP<true, true, true>(__VA_ARGS__);                                     \
+      else LOOP<false, false, true>(__VA_ARGS__);                                             \
+    } else if (g_is_bf16) {                                                                   \
+      if (out_is_bf16) LOOP<true, true, false>(__VA_ARGS__);                                  \
+      else LOOP<true, false, false>(__VA_ARGS__);                                             \
+    } else {                                                                                  \
+      if (out_is_bf16) LOOP<false, true, false>(__VA_ARGS__);                                 \
+      else LOOP<false, false, false>(__VA_ARGS__);                                            \
+    }                                                                                         \
+  } while (0)
 
 inline void sgd_momentum_entry(float* w, float* buf, const void* g, bool g_is_bf16, size_t n, float lr, float mu, void* out,
                                bool out_is_bf16) {
-  if (g_is_bf16) {
-    if (out_is_bf16) sgd_momentum_loop<true, true>(w, buf, g, n, lr, mu, out);
-    else sgd_momentum_loop<true, false>(w, buf, g, n, lr, mu, out);
-  } else {
-    if (out_is_bf16) sgd_momentum_loop<false, true>(w, buf, g, n, lr, mu, out);
-    else sgd_momentum_loop<false, false>(w, buf, g, n, lr, mu, out);
-  }
+  KARMA_OPT_DISPATCH(sgd_momentum_loop, g, w, buf, (const void*)out == g ? nullptr : g, n, lr, mu, out);
 }
 
 inline void sgd_entry(float* w, const void* g, bool g_is_bf16, size_t n, float lr, void* out, bool out_is_bf16) {
-  if (g_is_bf16) {
-    if (out_is_bf16) sgd_loop<true, true>(w, g, n, lr, out); else sgd_loop<true, false>(w, g, n, lr, out);
-  } else {
-    if (out_is_bf16) sgd_loop<false, true>(w, g, n, lr, out); else sgd_loop<false, false>(w, g, n, lr, out);
-  }
+  KARMA_OPT_DISPATCH(sgd_loop, g, w, (const void*)out == g ? nullptr : g, n, lr, out);
 }
 
 inline void adam_entry(float* w, float* m, float* v, const void* g, bool g_is_bf16, size_t n, float lr, float beta1,
                        float beta2, float eps, float c1, float c2, void* out, bool out_is_bf16) {
-  if (g_is_bf16) {
-    if (out_is_bf16) adam_loop<true, true>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-    else adam_loop<true, false>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-  } else {
-    if (out_is_bf16) adam_loop<false, true>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-    else adam_loop<false, false>(w, m, v, g, n, lr, beta1, beta2, eps, c1, c2, out);
-  }
+  KARMA_OPT_DISPATCH(adam_loop, g, w, m, v, (const void*)out == g ? nullptr : g, n, lr, beta1, beta2, eps, c1, c2, out);
 }
+#undef KARMA_OPT_DISPATCH
 
 }  // namespace HOST_OPTIM_NS
 }  // namespace karma

@@ -141,6 +141,33 @@ def gpt_ctx(stream, arena, dims, lr=1e-2):
     return K.Context(desc, cfg, arena)
 
 
+def test_gradients_landing_in_the_weights_pinned_buffer(g):
+    """stream_weights 2: a block's gradients arrive in the pinned buffer its weights were copied from and the
+    host update replaces them by the next weights.  Losses over several steps and the updated parameters equal
+    those of the layout with separate buffers; the gradients themselves cannot be read back."""
+    dims = dict(n_layers=3, hidden=128, heads=2, ffn=264, vocab=520, seq=128, batch=2)
+    params, ids, labels = si.gpt_problem(seed=2008114206, std=0.05, bias_std=0.05, **{k: v for k, v in dims.items() if k != "heads"})
+    ids, labels = ids.astype(np.int32), labels.astype(np.int32)
+    res = []
+    for mode in (1, 2):
+        ctx = gpt_ctx(mode, 256 << 20, dims, lr=1e-3)
+        TG.load_params(ctx, params)
+        ctx.karma_set_plan(200 << 20, [K.KEEP, K.SWAP, K.RC_KEEP, K.RC_CHAIN], [0, 0, 1, 0])
+        losses = [ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER) for _ in range(3)]
+        losses.append(ctx.karma_step(ids, labels))          # no optimiser: the weights' buffer is left alone
+        losses.append(ctx.karma_step(ids, labels))
+        if mode == 2:
+            with pytest.raises(K.KarmaError) as e:
+                ctx.karma_get_grad(1, 2)
+            assert e.value.status == K.E_STATE
+            assert np.any(ctx.karma_get_grad(0, 0) != 0)     # resident records are read as before
+        res.append((losses, [ctx.karma_get_param(l, t) for l, t in ((0, 0), (1, 2), (2, 8), (3, 11), (4, 1))]))
+        ctx.close()
+    assert res[0][0] == res[1][0] and res[0][0][3] == res[0][0][4] and res[0][0][3] < res[0][0][0]
+    for a, b in zip(res[0][1], res[1][1]):
+        assert np.array_equal(a, b)
+
+
 def test_gpt_streamed_weights_bit_identical_and_adam(g):
     params, ids, labels = TG.small_problem()
     big = 512 << 20

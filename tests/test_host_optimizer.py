@@ -91,6 +91,34 @@ def test_first_adam_step_moves_every_weight_by_lr(data):
     assert np.allclose((w - w1)[big], 1e-2 * np.sign(g)[big], rtol=1e-3)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("opt", ["sgd", "momentum", "adam"])
+def test_update_in_place_of_the_gradient_buffer(data, opt, bf16):
+    """out == grad (one element type): every gradient is replaced by its new weight; results equal, bit for bit,
+    those of the update into a separate buffer, in both vector builds."""
+    w, m, v, g = data
+    kind = {"sgd": K.OPT_SGD, "momentum": K.OPT_SGD_MOMENTUM, "adam": K.OPT_ADAM}[opt]
+    for narrow in (False, True):
+        w0, m0, v0, out0 = run(kind, w, m, v, g, bf16, 2, bf16, narrow)
+        w1, m1, v1 = w.copy(), m.copy(), v.copy()
+        buf = (nn.bf16_round(g).view(np.uint32) >> 16).astype(np.uint16) if bf16 else g.astype(np.float32)
+        bp = buf.ctypes.data_as(C.c_void_p)
+        st = K.lib().karma_host_update(C.c_uint32(kind), fptr(w1), fptr(m1), fptr(v1), bp, C.c_uint32(int(bf16)),
+                                       C.c_uint64(len(w1)), C.c_float(1e-3), C.c_float(0.9), C.c_float(0.999), C.c_float(1e-8),
+                                       C.c_uint64(2), bp, C.c_uint32(int(bf16)), C.c_uint32(int(narrow)))
+        assert st == K.OK
+        assert np.array_equal(buf, out0) and np.array_equal(w1, w0)
+        if opt != "sgd":
+            assert np.array_equal(m1, m0)
+        if opt == "adam":
+            assert np.array_equal(v1, v0)
+    # differing element types cannot share a buffer
+    st = K.lib().karma_host_update(C.c_uint32(K.OPT_SGD), fptr(w.copy()), None, None, bp, C.c_uint32(1), C.c_uint64(8),
+                                   C.c_float(1e-3), C.c_float(0.9), C.c_float(0.999), C.c_float(1e-8), C.c_uint64(1), bp,
+                                   C.c_uint32(0), C.c_uint32(0))
+    assert st == K.E_INVAL
+
+
 def test_rejects_bad_arguments(data):
     w, m, v, g = data
     lib = K.lib()
