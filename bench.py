@@ -81,6 +81,36 @@ def cpu_baseline(n_seq):
                        % (n_seq, ts[0], ts[1], t_block, t_rest, CFG["n_layers"]))
 
 
+def backward_stalls(ctx, step_fn, n_records):
+    """The stall profile of the backward phase (Sec. V, Fig. 6): one step with events around every op; for each
+    compute op from the loss on, the time the compute stream stood idle before it began (waiting for a swap-in,
+    a weight copy or a free buffer), summed per layer; the plan's simulated schedule read the same way."""
+    step_fn()
+    ops = ctx.karma_get_op_times()
+    starts = ctx.karma_get_op_starts()
+
+    def per_layer(times):
+        stall = [0.0] * (n_records + 1)
+        prev_end, backward = None, False
+        for (kind, layer, _, _, _), (t0, t1) in zip(ops, times):
+            if kind not in "FRBL":
+                continue
+            backward = backward or kind == "L"
+            if backward and prev_end is not None:
+                stall[min(layer, n_records)] += max(0.0, t0 - prev_end)
+            prev_end = t1
+        return stall
+
+    measured = per_layer([(st, st + op[4]) for op, st in zip(ops, starts)])
+    predicted = per_layer([(op[2] / 1e6, op[3] / 1e6) for op in ops])
+    return {"by_layer_ms": [round(x, 4) for x in measured], "total_ms": sum(measured),
+            "simulated_total_ms": sum(predicted)}
+
+
+STALL_NOTE = ("compute-stream idle time before the backward-phase ops (loss, recompute, backward) of each layer, from one "
+              "step with events around every op; index = layer record, last = loss")
+
+
 def host_memory_note():
     """Resident and pinned memory of this process as the kernel reports them (a log line only)."""
     out = []
@@ -156,7 +186,12 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
 
     acts, summ, dt, loss, gem, st = timed(wl["budget"], K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
     log("%d GiB: %.1f ms/step, all-keep=%s, peak %.2f GiB" % (wl["budget"] // GIB, dt * 1e3, acts == [0] * len(acts), summ["peak_bytes"] / GIB))
+    profiled_step = lambda: ctx.karma_step(images, labels, K.STEP_APPLY_OPTIMIZER | K.STEP_PROFILE)
+    stalls_in = backward_stalls(ctx, profiled_step, len(acts))
     acts_lo, summ_lo, dt_lo, loss_lo, _, _ = timed(wl["low_budget"], K.STEP_APPLY_OPTIMIZER)
+    stalls_lo = backward_stalls(ctx, profiled_step, len(acts_lo))
+    log("backward-phase stalls of the compute stream: %d GiB %.2f ms, %d GiB %.2f ms (simulated %.2f ms)"
+        % (wl["budget"] // GIB, stalls_in["total_ms"], wl["low_budget"] // GIB, stalls_lo["total_ms"], stalls_lo["simulated_total_ms"]))
     log("%d GiB: %.1f ms/step, plan %s" % (wl["low_budget"] // GIB, dt_lo * 1e3, "".join("KSRrc"[a] for a in acts_lo)))
     # the same budget with the block granularity chosen by the planner as well (Sec. III-E/F, first tier)
     acts_g, summ_g, group = ctx.karma_plan_grouped(wl["low_budget"])
@@ -188,6 +223,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
                                      "samples_per_s": batch / dt_lo, "pct_of_in_core": 100.0 * dt / dt_lo,
                                      "plan": "".join("KSRrc"[a] for a in acts_lo), "arena_peak_gib": summ_lo["peak_bytes"] / GIB,
                                      "swap_gib_each_way": summ_lo["bytes_d2h"] / GIB,
+                                     "backward_stall_profile": {"what": STALL_NOTE, "in_core": stalls_in, "out_of_core": stalls_lo},
                                      "grouped_planner": {"group_size": group, "ms_per_step": dt_g * 1e3,
                                                          "predicted_makespan_ms": summ_g["makespan_ns"] / 1e6,
                                                          "plan": "".join("KSRrc"[a] for a in acts_g)}},
@@ -304,6 +340,8 @@ def main():
 
     acts_in, summ_in, dt_in, loss_in, _, st_in = timed(ARENA, K.STEP_APPLY_OPTIMIZER)
     log("in-core: %.1f ms/step (host optimiser %.1f ms), plan all-keep=%s" % (dt_in * 1e3, st_in["host_opt_ms"], acts_in == [0] * len(acts_in)))
+    profiled_step = lambda: ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER | K.STEP_PROFILE)
+    stalls_in = backward_stalls(ctx, profiled_step, len(acts_in))
     acts, summ, dt, loss, gem, st = timed(BUDGET, K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
     log("%d GiB: %.1f ms/step, plan %s, weights kept %s" % (BUDGET // GIB, dt * 1e3, acts, summ.get("wres")))
     log("predicted makespan %.1f ms, peak %.2f GiB, swap %.2f GiB each way" %
@@ -311,7 +349,9 @@ def main():
 
     # one more step with events around every op: achieved host-link rate during the swaps and
     # the measured occupancy of the compute stream (Eq. 1)
-    ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER | K.STEP_PROFILE)
+    stalls_out = backward_stalls(ctx, profiled_step, len(acts))
+    log("backward-phase stalls of the compute stream: in-core %.2f ms, %d GiB %.2f ms (simulated %.2f ms)"
+        % (stalls_in["total_ms"], BUDGET // GIB, stalls_out["total_ms"], stalls_out["simulated_total_ms"]))
     st_prof = ctx.karma_get_stats()
     swap = {"O": [0.0, 0.0], "I": [0.0, 0.0]}
     for kind, layer, t0_, t1_, ms in ctx.karma_get_op_times():
@@ -355,9 +395,12 @@ def main():
         ctx.karma_finish_updates()
         torch.cuda.synchronize()
         dtp = (time.perf_counter() - t1) / n_pol
+        stalls_p = backward_stalls(ctx, profiled_step, L)
         policies[name] = {"feasible": True, "ms_per_step": dtp * 1e3, "samples_per_s": CFG["batch"] / dtp,
-                          "predicted_makespan_ms": sp["makespan_ns"] / 1e6, "planned_over_this": dtp / dt}
-        log("policy %s: %.1f ms/step (planned schedule is %.2fx faster)" % (name, dtp * 1e3, dtp / dt))
+                          "predicted_makespan_ms": sp["makespan_ns"] / 1e6, "planned_over_this": dtp / dt,
+                          "backward_stall_ms": stalls_p["total_ms"], "backward_stall_simulated_ms": stalls_p["simulated_total_ms"]}
+        log("policy %s: %.1f ms/step (planned schedule is %.2fx faster), backward-phase stalls %.1f ms (simulated %.1f)"
+            % (name, dtp * 1e3, dtp / dt, stalls_p["total_ms"], stalls_p["simulated_total_ms"]))
 
     n_l, ms_l, fl_l = gem
     achieved = fl_l / (ms_l * 1e-3) / 1e12 if ms_l > 0 else 0.0
@@ -391,6 +434,7 @@ def main():
         "compute_occupancy_measured": occupancy,
         "compute_occupancy_predicted": summ["busy_ns"] / max(summ["busy_ns"] + summ["stall_ns"], 1),
         "host_opt_ms": st["host_opt_ms"],
+        "backward_stall_profile": {"what": STALL_NOTE, "in_core": stalls_in, "out_of_core": stalls_out},
         "comparison_policies": policies,
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel and gemm_bf16_dl_kernel (" + SAMPLING_NOTE + ")",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,

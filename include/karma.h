@@ -304,6 +304,11 @@ int karma_get_gemm_stats(karma_ctx* ctx, uint64_t* launches_out, double* ms_out,
 /* The ops of the current plan (predicted times) and, for the last step run with
  * KARMA_STEP_PROFILE, their measured durations in ms.  *n_inout: capacity in, count out. */
 int karma_get_op_times(karma_ctx* ctx, karma_op* ops_out, float* ms_out, uint32_t* n_inout);
+/* When each op of the last step run with KARMA_STEP_PROFILE began on its stream, in ms from the begin of the
+ * first op (same order and count as karma_get_op_times).  With the durations this gives the time the compute
+ * stream stood idle before each op (the stall profile of Sec. V, Fig. 6).  *n_inout: capacity in, count out;
+ * KARMA_E_OOM with the count when the capacity is too small. */
+int karma_get_op_starts(karma_ctx* ctx, float* start_ms_out, uint32_t* n_inout);
 
 /* ---- single kernels (device pointers, launched on `stream`, asynchronous) --------
  * Exposed so that each can be checked against the CPU oracle on its own.  Shapes are

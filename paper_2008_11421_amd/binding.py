@@ -353,3 +353,9 @@ class Context:
         ms = (C.c_float * n.value)()
         self._chk(lib().karma_get_op_times(self.ctx, ops, ms, C.byref(n)), "karma_get_op_times")
         return [(chr(ops[k].kind), ops[k].layer, ops[k].start_ns, ops[k].end_ns, ms[k]) for k in range(n.value)]
+
+    def karma_get_op_starts(self):
+        n = C.c_uint32(6 * self.n_layers + 2)
+        starts = (C.c_float * n.value)()
+        self._chk(lib().karma_get_op_starts(self.ctx, starts, C.byref(n)), "karma_get_op_starts")
+        return [starts[k] for k in range(n.value)]

@@ -94,6 +94,7 @@ struct Ctx {
   karma_plan_summary summary{};
   std::vector<hipEvent_t> ev, ev_begin;   // per op: end event, begin event (profiling)
   std::vector<float> op_ms;               // per-op durations of the last profiled step
+  std::vector<float> op_start_ms;         // and when each began on its stream, from the first op's begin
   char* swap_pool = nullptr;              // pinned host memory for swapped tensors
   uint64_t swap_pool_bytes = 0;
 

@@ -249,6 +249,7 @@ int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions, c
     KARMA_HIP(c, hipEventCreate(&c->ev_begin[k]));
   }
   c->op_ms.assign(c->prog.size(), 0.f);
+  c->op_start_ms.assign(c->prog.size(), 0.f);
   c->planned = true;
   return KARMA_OK;
 }
@@ -479,6 +480,9 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
       float ms = 0.f;
       KARMA_HIP(c, hipEventElapsedTime(&ms, c->ev_begin[k], c->ev[k]));
       c->op_ms[k] = ms;
+      float since = 0.f;
+      if (k) KARMA_HIP(c, hipEventElapsedTime(&since, c->ev_begin[0], c->ev_begin[k]));
+      c->op_start_ms[k] = since;
       int sidx = c->prog[k].stream;
       if (sidx == 0) c->stats.compute_busy_ms += ms;
       else if (sidx == 1) c->stats.h2d_ms += ms;
@@ -811,6 +815,16 @@ extern "C" int karma_get_op_times(karma_ctx* c, karma_op* ops_out, float* ms_out
   if (*n_inout < n) { *n_inout = n; return KARMA_E_OOM; }
   if (ops_out) std::memcpy(ops_out, c->ops.data(), n * sizeof(karma_op));
   if (ms_out) std::memcpy(ms_out, c->op_ms.data(), n * sizeof(float));
+  *n_inout = n;
+  return KARMA_OK;
+}
+
+extern "C" int karma_get_op_starts(karma_ctx* c, float* start_ms_out, uint32_t* n_inout) {
+  if (!c || !n_inout) return KARMA_E_INVAL;
+  if (!c->planned) return fail(c, KARMA_E_STATE, "no plan");
+  uint32_t n = (uint32_t)c->op_start_ms.size();
+  if (*n_inout < n) { *n_inout = n; return KARMA_E_OOM; }
+  if (start_ms_out) std::memcpy(start_ms_out, c->op_start_ms.data(), n * sizeof(float));
   *n_inout = n;
   return KARMA_OK;
 }

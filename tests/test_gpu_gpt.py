@@ -144,6 +144,32 @@ def test_gpt_head_dimension_152_and_ragged_widths(g):
     ctx.close()
 
 
+def test_profiled_step_gives_op_starts_in_stream_order(g):
+    """KARMA_STEP_PROFILE: every op's begin and duration; ops of one stream follow each other without overlap,
+    and the compute stream's busy time plus its idle gaps span the step."""
+    params, ids, labels = small_problem()
+    ctx = make_ctx(arena=512 << 20, **SMALL)
+    load_params(ctx, params)
+    ctx.karma_set_plan(512 << 20, [K.SWAP, K.RC_SWAP, K.RC_CHAIN, K.KEEP])
+    ctx.karma_step(ids, labels, K.STEP_PROFILE)
+    ops = ctx.karma_get_op_times()
+    starts = ctx.karma_get_op_starts()
+    assert len(starts) == len(ops) and starts[0] == 0.0
+    streams = {"F": 0, "R": 0, "B": 0, "L": 0, "I": 1, "W": 1, "O": 2, "G": 2}
+    last_end = {}
+    for (kind, layer, _, _, ms), st in zip(ops, starts):
+        sid = streams[kind]
+        assert ms >= 0.0 and st >= 0.0
+        if sid in last_end:
+            assert st >= last_end[sid] - 0.02, (kind, layer, st, last_end[sid])   # event resolution
+        last_end[sid] = st + ms
+    compute = [(st, ms) for (kind, _, _, _, ms), st in zip(ops, starts) if streams[kind] == 0]
+    busy = sum(ms for _, ms in compute)
+    span = compute[-1][0] + compute[-1][1] - compute[0][0]
+    assert busy <= span + 0.05 and abs(busy - ctx.karma_get_stats()["compute_busy_ms"]) <= 1e-3 * busy + 1e-3
+    ctx.close()
+
+
 def test_gpt_host_adam(g):
     params, ids, labels = small_problem()
     ctx = make_ctx(arena=512 << 20, lr=1e-2, **SMALL)
