@@ -283,7 +283,8 @@ typedef struct {
   double d2h_ms, h2d_ms;   /* busy time of the copy streams */
   uint64_t bytes_d2h, bytes_h2d;
   uint64_t arena_peak_bytes;
-  double host_opt_ms;      /* host optimiser wall time */
+  double host_opt_ms;      /* host optimiser wall time spent since this step began: updates the previous step left
+                              pending and finished here count, updates this step leaves pending do not */
   uint64_t updates_deferred; /* records whose host update the step left pending (karma_finish_updates) */
 } karma_step_stats;
 int karma_get_stats(karma_ctx* ctx, karma_step_stats* out);
