@@ -31,9 +31,9 @@ WORKLOADS = {
             name="configs[2]: ResNet-200-shaped bottleneck CNN (stages 3/24/36/3, widths 256..2048), 224x224x3 images, "
                  "batch 64, 1000 classes, BatchNorm + ReLU, bf16, host SGD with momentum, HBM budget 32 GiB"),
     3: dict(cfg=dict(n_layers=72, hidden=3072, heads=24, ffn=12288, vocab=51200, seq=1024, batch=8),
-            budget=32 * GIB, arena=96 * GIB, seed=2008114204, stream=1,
+            budget=32 * GIB, arena=96 * GIB, seed=2008114204, stream=2,
             name="configs[3]: 72-layer pre-LN GPT (8.3B parameters), hidden 3072, 24 heads, FFN 12288, seq 1024, "
-                 "batch 8, vocab 51200, bf16 weights streamed per layer from pinned host memory, fp32 host "
+                 "batch 8, vocab 51200, bf16 weights streamed per layer from pinned host memory (gradients land in the same pinned buffers), fp32 host "
                  "master/Adam, HBM budget 32 GiB"),
     4: dict(cfg=dict(n_layers=78, hidden=4256, heads=28, ffn=17024, vocab=51200, seq=1024, batch=4),
             budget=32 * GIB, arena=96 * GIB, seed=2008114205, stream=2,
@@ -383,8 +383,8 @@ def main():
     for name, cand in ({} if args.no_policies else candidates).items():
         try:
             sp = ctx.karma_set_plan(BUDGET, cand)
-        except K.KarmaError:
-            policies[name] = {"feasible": False}
+        except K.KarmaError as e:
+            policies[name] = {"feasible": False, "reason": str(e)}
             continue
         ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
         ctx.karma_finish_updates()

@@ -239,8 +239,12 @@ int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions, c
   int st = b.run();
   if (st) return fail(c, st, "schedule compilation failed");
   if (c->swap_pool_bytes) {
-    if (hipHostMalloc((void**)&c->swap_pool, c->swap_pool_bytes, hipHostMallocDefault) != hipSuccess)
+    if (hipHostMalloc((void**)&c->swap_pool, c->swap_pool_bytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();   // or the next launch check would report this allocation's error as its own
+      c->swap_pool = nullptr;
+      c->planned = false;        // the previous plan's resources are gone and this one's are not there
       return fail(c, KARMA_E_HOSTMEM, "pinned swap pool allocation failed");
+    }
   }
   c->ev.assign(c->prog.size(), nullptr);
   c->ev_begin.assign(c->prog.size(), nullptr);
@@ -572,6 +576,7 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
     hipError_t e = hipHostMalloc(p, bytes ? bytes : 256, hipHostMallocDefault);
     if (e != hipSuccess) {
       std::fprintf(stderr, "karma_create: hipHostMalloc(%llu) failed: %s\n", (unsigned long long)bytes, hipGetErrorString(e));
+      (void)hipGetLastError();
       ok = false;
     }
   };
@@ -869,7 +874,10 @@ extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) 
   uint64_t big = std::min<uint64_t>(256ull << 20, (c->arena_bytes - c->fixed_bytes) / 2 / 256 * 256);
   if (big >= (1u << 20)) {
     char* host = nullptr;
-    if (hipHostMalloc((void**)&host, big, hipHostMallocDefault) != hipSuccess) return fail(c, KARMA_E_HOSTMEM, "pinned");
+    if (hipHostMalloc((void**)&host, big, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(c, KARMA_E_HOSTMEM, "pinned buffer for the link measurement");
+    }
     std::memset(host, 0, big);
     hipEvent_t e0, e1;
     KARMA_HIP(c, hipEventCreate(&e0));
