@@ -202,9 +202,11 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
 
 // out[c] = sum_p partial[p][c]: eight slices of threads sum every eighth partial, then the
 // slices are added in ascending order (a fixed association, so results are reproducible)
+// Columns split.. go to out_f32_b (two results that lie side by side in the partials, one launch).
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial, int parts, int stride,
                                                              int cols, bf16_t* __restrict__ out_bf16,
-                                                             float* __restrict__ out_f32) {
+                                                             float* __restrict__ out_f32, int split,
+                                                             float* __restrict__ out_f32_b) {
   __shared__ float red[8][32];
   const int cl = threadIdx.x & 31, slice = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cl;
@@ -227,7 +229,10 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restr
 #pragma unroll
     for (int k = 1; k < 8; ++k) t += red[k][cl];
     if (out_bf16) out_bf16[c] = f2bf_(t);
-    if (out_f32) out_f32[c] = t;
+    if (out_f32) {
+      if (c < split) out_f32[c] = t;
+      else out_f32_b[c - split] = t;
+    }
   }
 }
 
@@ -343,15 +348,19 @@ __global__ void embed_bwd_wpe_kernel(const bf16_t* __restrict__ dx, bf16_t* __re
 // ---- softmax cross-entropy, forward and gradient fused -------------------------------
 // One workgroup per row: the row of logits is read once into LDS, reduced (max, sum of
 // exponentials), then overwritten with (softmax - onehot) * scale.  rowloss[row] = lse - z[label].
-__global__ __launch_bounds__(256) void softmax_ce_kernel(bf16_t* __restrict__ logits, const int* __restrict__ labels,
-                                                          float* __restrict__ rowloss, int cols, float scale) {
+// CE_THREADS threads (16 wavefronts: with a 64 KB row two workgroups fill a compute unit's wave slots, which
+// lets one row's loads, exponentials and stores overlap another's); partial results of the wavefronts are
+// combined in ascending order.
+constexpr int CE_THREADS = 1024, CE_WAVES = CE_THREADS / 64;
+__global__ __launch_bounds__(CE_THREADS) void softmax_ce_kernel(bf16_t* __restrict__ logits, const int* __restrict__ labels,
+                                                                 float* __restrict__ rowloss, int cols, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_ce[];
   bf16_t* row = (bf16_t*)smem_ce;
-  __shared__ float red[8];
+  __shared__ float red[2 * CE_WAVES];
   const int r = blockIdx.x, nv = cols / 8, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   bf16_t* src = logits + (size_t)r * cols;
   float mx = -INFINITY;
-  for (int c = threadIdx.x; c < nv; c += 256) {
+  for (int c = threadIdx.x; c < nv; c += CE_THREADS) {
     u32x4 v = *(const u32x4*)(src + c * 8);
     *(u32x4*)(row + c * 8) = v;
     float f[8];
@@ -362,23 +371,27 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(bf16_t* __restrict__ lo
   mx = wave_max(mx);
   if (lane == 0) red[w] = mx;
   __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  mx = red[0];
+#pragma unroll
+  for (int k = 1; k < CE_WAVES; ++k) mx = fmaxf(mx, red[k]);
   float sum = 0.f;
-  for (int c = threadIdx.x; c < nv; c += 256) {
+  for (int c = threadIdx.x; c < nv; c += CE_THREADS) {
     float f[8];
     unpack8(*(const u32x4*)(row + c * 8), f);
 #pragma unroll
     for (int e = 0; e < 8; ++e) sum += __expf(f[e] - mx);
   }
   sum = wave_sum(sum);
-  if (lane == 0) red[4 + w] = sum;
+  if (lane == 0) red[CE_WAVES + w] = sum;
   __syncthreads();
-  sum = (red[4] + red[5]) + (red[6] + red[7]);
+  sum = red[CE_WAVES];
+#pragma unroll
+  for (int k = 1; k < CE_WAVES; ++k) sum += red[CE_WAVES + k];
   const float lse = mx + __logf(sum);
   const int label = labels[r];
   if (threadIdx.x == 0) rowloss[r] = lse - bf2f_(row[label]);
   const float inv = 1.f / sum;
-  for (int c = threadIdx.x; c < nv; c += 256) {
+  for (int c = threadIdx.x; c < nv; c += CE_THREADS) {
     float f[8];
     unpack8(*(const u32x4*)(row + c * 8), f);
 #pragma unroll
@@ -468,10 +481,8 @@ int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const b
   else if (per_lane <= 9) KARMA_LN_BWD(9);
   else KARMA_LN_BWD(12);
 #undef KARMA_LN_BWD
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((h + 31) / 32), dim3(256), 0, s, partial_ws, parts, 2 * h, h,
-                     (bf16_t*)nullptr, dgamma);
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((h + 31) / 32), dim3(256), 0, s, partial_ws + h, parts, 2 * h, h,
-                     (bf16_t*)nullptr, dbeta);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((2 * h + 31) / 32), dim3(256), 0, s, partial_ws, parts, 2 * h, 2 * h,
+                     (bf16_t*)nullptr, dgamma, h, dbeta);
   return ok();
 }
 
@@ -482,7 +493,7 @@ int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int co
   const int parts = (rows + CS_ROWS - 1) / CS_ROWS;
   hipLaunchKernelGGL(colsum_partial_kernel, dim3(parts, (cols / 8 + 255) / 256), dim3(256), 0, s, x, partial_ws, rows, cols);
   hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, partial_ws, parts, cols, cols,
-                     (bf16_t*)nullptr, out);
+                     (bf16_t*)nullptr, out, cols, (float*)nullptr);
   return ok();
 }
 
@@ -518,7 +529,7 @@ int softmax_ce(bf16_t* logits, const int* labels, float* rowloss, int rows, int 
   if (cols % 8 || rows <= 0 || lds > 150 * 1024) return KARMA_E_INVAL;
   if (lds > 64 * 1024)
     (void)hipFuncSetAttribute((const void*)softmax_ce_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL(softmax_ce_kernel, dim3(rows), dim3(256), lds, s, logits, labels, rowloss, cols, scale);
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(rows), dim3(CE_THREADS), lds, s, logits, labels, rowloss, cols, scale);
   return ok();
 }
 
