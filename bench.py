@@ -245,6 +245,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-policies", action="store_true", help="skip the comparison policies (profiling runs)")
     ap.add_argument("--config", type=int, default=1, choices=sorted(WORKLOADS))
+    ap.add_argument("--whole-blocks", action="store_true",
+                    help="GPT workloads: one plannable record per transformer block instead of two (attention half, "
+                         "feed-forward half)")
     ap.add_argument("--layers", type=int, default=0,
                     help="GPT workloads: truncate the depth to this many blocks (named in config.workload)")
     args = ap.parse_args()
@@ -283,7 +286,15 @@ def main():
     if wl.get("kind") == "cnn":
         return bench_cnn(args, wl, K, si, torch, np, threads)
     desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=CFG["batch"], seq=CFG["seq"],
-                n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=wl["stream"])
+                n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=wl["stream"],
+                split_blocks=0 if args.whole_blocks else 1)
+    split = not args.whole_blocks
+
+    def slot(block, t):   # (record, tensor) of tensor t of transformer block `block`
+        if not split:
+            return block + 1, t
+        return (2 * block + 1, t) if t < 6 else (2 * block + 2, t - 6)
+    n_records = (2 if split else 1) * CFG["n_layers"] + 1
     cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
     t0 = time.perf_counter()
     ctx = K.Context(desc, cfg, ARENA)
@@ -298,11 +309,11 @@ def main():
         b = params["blocks"][i % n_drawn]
         for t, name in enumerate(oracle_nn.BLOCK_TENSORS):
             v = np.asarray(b[name], dtype=np.float32)
-            ctx.karma_set_param(i + 1, t, v if n_drawn > 1 else np.roll(v.reshape(-1), 97 * i))
+            ctx.karma_set_param(*slot(i, t), v if n_drawn > 1 else np.roll(v.reshape(-1), 97 * i))
         if n_drawn == 1 and i % 8 == 7:
             log("  parameters of %d layers set, %.0f s" % (i + 1, time.perf_counter() - t0))
-    ctx.karma_set_param(CFG["n_layers"] + 1, 0, params["lnf_g"])
-    ctx.karma_set_param(CFG["n_layers"] + 1, 1, params["lnf_b"])
+    ctx.karma_set_param(n_records, 0, params["lnf_g"])
+    ctx.karma_set_param(n_records, 1, params["lnf_b"])
     del params
     ids = ids.astype(np.int32)
     labels = labels.astype(np.int32)
@@ -310,8 +321,9 @@ def main():
 
     link = ctx.karma_measure(3)
     layers, loss_c, fixed = ctx.karma_get_costs()
+    blk = (layers[1][0] + (layers[2][0] if split else 0), layers[1][1] + (layers[2][1] if split else 0))
     log("link h2d %.1f GB/s d2h %.1f GB/s lat %d ns; block fwd %.2f ms bwd %.2f ms; loss %.2f ms; fixed %.2f GiB"
-        % (link[0] / 1e9, link[1] / 1e9, link[2], layers[1][0] / 1e6, layers[1][1] / 1e6, loss_c[0] / 1e6, fixed / GIB))
+        % (link[0] / 1e9, link[1] / 1e9, link[2], blk[0] / 1e6, blk[1] / 1e6, loss_c[0] / 1e6, fixed / GIB))
 
     def timed(budget, flags):
         acts, summ = ctx.karma_plan(budget)
@@ -420,6 +432,8 @@ def main():
         "config": {"workload": wl["name"],
                    "hbm_budget_gib": BUDGET // GIB, "global_batch": CFG["batch"], "seq_len": CFG["seq"],
                    "weights_kept_between_forward_and_backward": summ.get("wres"),
+                   "records": "embedding, then per transformer block its attention half and its feed-forward half"
+                              if split else "embedding, then one per transformer block",
                    "plan": "".join("KSRrc"[a] for a in acts), "plan_legend": "K keep, S swap, R recompute from kept input, "
                    "r recompute from swapped input, c recompute in chain"},
         "in_core_samples_per_s": CFG["batch"] / dt_in,

@@ -53,7 +53,9 @@ typedef enum { KARMA_KEEP = 0, KARMA_SWAP = 1, KARMA_RC_KEEP = 2, KARMA_RC_SWAP 
 
 /* Cost-model inputs (Sec. III-C compute cost, Sec. III-D memory per variable type). */
 typedef struct {
-  int64_t tf_ns, tb_ns, trc_ns; /* forward, backward, recompute time */
+  int64_t tf_ns, tb_ns, trc_ns; /* forward, backward time; trc: recomputing the layer's internals without its output
+                                   (the last layer of a recomputed run: its output still exists as the next
+                                   layer's input); a layer inside a run is re-run whole and costs tf */
   uint64_t sav_bytes;           /* internals needed by backward, excluding x_i */
   uint64_t out_bytes;           /* output = input of the next layer (x_0 is the step input
                                    and lives in the fixed region) */
@@ -174,6 +176,12 @@ typedef struct {
                                convolution to `width` channels, batch norm, ReLU, 3x3 stride-2 max
                                pooling; head: global average pooling, fully connected layer, mean
                                cross entropy.  Inputs: fp32 images [batch][seq][seq][3]; labels int32. */
+  uint32_t split_blocks;    /* GPT only, 1: every transformer block is two plannable records, its attention half
+                               (LayerNorm, QKV projection, attention, output projection, residual add) and
+                               its feed-forward half (LayerNorm, FC1, GELU, FC2, residual add), so that the
+                               planner chooses per half (Sec. III-E: a block is any run of consecutive
+                               layers).  The same kernels run in the same order: results equal those of
+                               whole blocks bit for bit */
 } karma_model_desc;
 
 typedef struct {
@@ -183,8 +191,10 @@ typedef struct {
 } karma_config;
 
 /* Number of plannable layer records of a model (MLP: n_layers; GPT: n_layers + 1, record
- * 0 being the embedding; CNN: 1 + sum of stage_blocks, record 0 being the stem) and of
- * parameter tensors of record `layer`. */
+ * 0 being the embedding, or 2 n_layers + 1 with split_blocks: block k is then records 2k + 1
+ * (attention half: tensors LN1 gain, LN1 shift, Wqkv, bqkv, Wo, bo) and 2k + 2 (feed-forward half:
+ * LN2 gain, LN2 shift, W1, b1, W2, b2); CNN: 1 + sum of stage_blocks, record 0 being the stem) and
+ * of parameter tensors of record `layer`. */
 int karma_model_layers(const karma_model_desc* desc, uint32_t* n_out);
 
 /* Creates a context.  arena_dev: device slab of arena_bytes owned by the caller (e.g. a

@@ -54,18 +54,23 @@ def mlp_blocks(width, n_layers, batch):
     return blocks, loss
 
 
-def gpt_blocks(n_layers, hidden, heads, ffn, vocab, seq, batch):
+def gpt_blocks(n_layers, hidden, heads, ffn, vocab, seq, batch, split=False):
     """Block 0: embedding.  Blocks 1..n: LN, QKV projection, attention, output projection, residual
-    add, LN, FC1, GELU, FC2, residual add.  Loss: final LN, tied LM head, softmax cross entropy."""
+    add, LN, FC1, GELU, FC2, residual add.  Loss: final LN, tied LM head, softmax cross entropy.
+    split: each transformer block as two entries, its attention half (up to the first residual add) and
+    its feed-forward half."""
     T = batch * seq
     d = hidden // heads
     blocks = [(0, T * hidden)]
-    fc = T * (hidden * 3 * hidden + hidden * hidden + 2 * hidden * ffn)
     attn_mm = batch * heads * 2 * seq * seq * d
     attn_softmax = batch * heads * 2 * seq * seq
-    other = 2 * 9 * T * hidden + attn_softmax + T * ffn + 2 * T * hidden
+    attention = (T * (hidden * 3 * hidden + hidden * hidden) + attn_mm, 9 * T * hidden + attn_softmax + T * hidden)
+    feed_forward = (T * 2 * hidden * ffn, 9 * T * hidden + T * ffn + T * hidden)
     for _ in range(n_layers):
-        blocks.append((fc + attn_mm, other))
+        if split:
+            blocks += [attention, feed_forward]
+        else:
+            blocks.append((attention[0] + feed_forward[0], attention[1] + feed_forward[1]))
     loss = (T * hidden * vocab, 9 * T * hidden + 2 * T * vocab)
     return blocks, loss
 

@@ -41,7 +41,10 @@ KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN = 0, 1, 2, 3, 4
 N_ACTIONS = 5
 ALIGN = 256
 
-# per-layer costs.  tf/tb/trc: forward, backward, recompute time (ns).  sav: bytes of
+# per-layer costs.  tf/tb: forward, backward time (ns).  trc: time to recompute the layer's internals
+# alone, for a layer whose output need not be rebuilt because it still exists as the next layer's
+# kept or swapped-in input (the last layer of a recomputed run); a layer inside a run must rebuild
+# its output too and costs tf (Sec. III-F: a recomputed block re-runs its forward pass).  sav: bytes of
 # internals backward needs besides the layer input.  out: bytes of the layer output
 # (= the next layer's input).  ws: transient workspace bytes of any op of this layer.
 # wb/gb: bytes of the layer's weights / weight gradients when they are streamed over the
@@ -445,9 +448,10 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             if j < e:
                 X[j + 1], t = grant(xb[j + 1], True, t)
             w, t = grant(wsb[j], False, t)
-            end = t + layers[j].trc
-            busy += layers[j].trc
-            rc_ns += layers[j].trc
+            redo = layers[j].tf if j < e else layers[j].trc
+            end = t + redo
+            busy += redo
+            rc_ns += redo
             if want_ops:
                 ops.append(Op("R", j, t, end, (S[j], X[j + 1] if j < e else None, w)))
             tc = end
@@ -576,9 +580,10 @@ GROUP_SIZES = (1, 2, 3, 4, 6, 8)
 def merge_group(members):
     """Cost record of consecutive layers planned as one block (Sec. III-E/F: the first tier of the
     optimisation groups layers into blocks; a block is swapped, kept or recomputed as a whole).  Times
-    add up; the block's internals are its members' internals plus the boundaries between them; its
+    add up (recomputing the block re-runs every member's forward pass but the last one's output); the block's internals are its members' internals plus the boundaries between them; its
     output is the last member's; workspace is the largest; streamed weights and gradients add up."""
-    return Layer(tf=sum(m.tf for m in members), tb=sum(m.tb for m in members), trc=sum(m.trc for m in members),
+    return Layer(tf=sum(m.tf for m in members), tb=sum(m.tb for m in members),
+                 trc=sum(m.tf for m in members[:-1]) + members[-1].trc,
                  sav=sum(m.sav for m in members) + sum(m.out for m in members[:-1]), out=members[-1].out,
                  ws=max(m.ws for m in members), wb=sum(m.wb for m in members), gb=sum(m.gb for m in members))
 

@@ -52,7 +52,7 @@ class Op(C.Structure):
 class ModelDesc(C.Structure):
     _fields_ = [("kind", C.c_uint32), ("n_layers", C.c_uint32), ("width", C.c_uint32), ("batch", C.c_uint32),
                 ("seq", C.c_uint32), ("n_heads", C.c_uint32), ("ffn", C.c_uint32), ("vocab", C.c_uint32),
-                ("stream_weights", C.c_uint32), ("stage_blocks", C.c_uint32 * 4)]
+                ("stream_weights", C.c_uint32), ("stage_blocks", C.c_uint32 * 4), ("split_blocks", C.c_uint32)]
 
 
 class ConvShape(C.Structure):

@@ -13,7 +13,7 @@
 namespace karma {
 
 enum RecordKind {
-  REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_CNN_STEM = 4, REC_CNN_BLOCK = 5,
+  REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_CNN_STEM = 4, REC_CNN_BLOCK = 5, REC_ATTN = 6, REC_FFN = 7,
   REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11, REC_LOSS_CNN_HEAD = 12
 };
 

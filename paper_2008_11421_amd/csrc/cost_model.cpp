@@ -38,12 +38,18 @@ void count_gpt(const karma_model_desc& d, std::vector<Ops>& blocks, Ops& loss) {
   const uint64_t B = d.batch, S = d.seq, h = d.width, H = d.n_heads, f = d.ffn, V = d.vocab;
   const uint64_t T = B * S, dk = h / H;
   blocks.push_back(Ops(0, T * h));   // token + position embedding
-  const uint64_t products = T * (3 * h * h + h * h + 2 * h * f) + B * H * 2 * S * S * dk;
-  const uint64_t rest = 2 * 9 * T * h      // two layer normalisations
-                        + B * H * 2 * S * S   // softmax of the scores
-                        + T * f               // GELU
-                        + 2 * T * h;          // two residual adds
-  for (uint32_t i = 0; i < d.n_layers; ++i) blocks.push_back(Ops(products, rest));
+  // attention half: layer normalisation, QKV and output projections, the two attention products, the
+  // softmax of the scores, a residual add; feed-forward half: layer normalisation, FC1, GELU, FC2, residual add
+  const Ops attn(T * (3 * h * h + h * h) + B * H * 2 * S * S * dk, 9 * T * h + B * H * 2 * S * S + T * h);
+  const Ops ffn(T * 2 * h * f, 9 * T * h + T * f + T * h);
+  for (uint32_t i = 0; i < d.n_layers; ++i) {
+    if (d.split_blocks) {
+      blocks.push_back(attn);
+      blocks.push_back(ffn);
+    } else {
+      blocks.push_back(Ops(attn.first + ffn.first, attn.second + ffn.second));
+    }
+  }
   loss = Ops(T * h * V, 9 * T * h + 2 * T * V);   // final layer norm, tied LM head, softmax cross entropy
 }
 

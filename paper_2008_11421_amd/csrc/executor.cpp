@@ -542,7 +542,7 @@ int karma::derive_layout(Ctx& c) {
 extern "C" int karma_model_layers(const karma_model_desc* d, uint32_t* n_out) {
   if (!d || !n_out) return KARMA_E_INVAL;
   if (d->kind == KARMA_MODEL_MLP) *n_out = d->n_layers;
-  else if (d->kind == KARMA_MODEL_GPT) *n_out = d->n_layers + 1;
+  else if (d->kind == KARMA_MODEL_GPT) *n_out = (d->split_blocks ? 2 * d->n_layers : d->n_layers) + 1;
   else if (d->kind == KARMA_MODEL_CNN) *n_out = 1 + d->stage_blocks[0] + d->stage_blocks[1] + d->stage_blocks[2] + d->stage_blocks[3];
   else return KARMA_E_INVAL;
   return KARMA_OK;
@@ -869,6 +869,34 @@ extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) 
     if (p.kind == 'F') { c->cost[p.layer].tf_ns = ns; c->cost[p.layer].trc_ns = ns; }
     else if (p.kind == 'B') c->cost[p.layer].tb_ns = ns;
     else if (p.kind == 'L') c->loss_cost.t_ns = ns;
+  }
+  // Recompute times: the same step with every record recomputed from its kept input.  Each recompute is then
+  // the last of its run and rebuilds the record's internals only (its output still exists as the next
+  // record's input), which is what trc prices; inside a run a record is re-run whole and costs tf.
+  {
+    std::vector<uint8_t> again(c->L, KARMA_RC_KEEP);
+    st = install_plan(c, c->arena_bytes, again, kw);
+    if (st == KARMA_OK) {
+      std::vector<std::vector<float>> rs(c->prog.size());
+      for (uint32_t r = 0; r < reps + 1; ++r) {
+        float loss;
+        st = run_step(c, in.data(), lab.data(), 0, &loss, true);
+        if (st) return st;
+        if (r == 0) continue;
+        for (size_t k = 0; k < c->prog.size(); ++k) rs[k].push_back(c->op_ms[k]);
+      }
+      for (size_t k = 0; k < c->prog.size(); ++k) {
+        const ProgOp& p = c->prog[k];
+        if (p.kind != 'R') continue;
+        std::sort(rs[k].begin(), rs[k].end());
+        int64_t ns = (int64_t)(rs[k][rs[k].size() / 2] * 1e6);
+        c->cost[p.layer].trc_ns = std::min<int64_t>(std::max<int64_t>(ns, 1), c->cost[p.layer].tf_ns);
+      }
+    } else if (st != KARMA_E_BUDGET) {
+      return st;
+    }
+    st = install_plan(c, c->arena_bytes, keep, kw);   // leave the in-core plan installed
+    if (st) return st;
   }
   // link: one large and one small pinned copy per direction, on the copy streams
   uint64_t big = std::min<uint64_t>(256ull << 20, (c->arena_bytes - c->fixed_bytes) / 2 / 256 * 256);

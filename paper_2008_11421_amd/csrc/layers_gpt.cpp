@@ -44,6 +44,34 @@ struct BlockSaved {
   }
 };
 
+// the same internals when a block is two records: the attention half keeps a .. lse and hands r1 on as its
+// output, the feed-forward half (whose input is r1) keeps stats2 .. g
+struct AttnSaved {
+  uint64_t a, stats1, qkv, ctx, lse, total;
+  explicit AttnSaved(const Dims& d) {
+    uint64_t o = 0;
+    auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
+    a = take((uint64_t)d.T * d.h * 2);
+    stats1 = take((uint64_t)d.T * 2 * 4);
+    qkv = take((uint64_t)d.T * 3 * d.h * 2);
+    ctx = take((uint64_t)d.T * d.h * 2);
+    lse = take((uint64_t)d.B * d.H * d.S * 4);
+    total = o;
+  }
+};
+struct FfnSaved {
+  uint64_t stats2, m, f1, g, total;
+  explicit FfnSaved(const Dims& d) {
+    uint64_t o = 0;
+    auto take = [&](uint64_t bytes) { uint64_t at = o; o += up256(bytes); return at; };
+    stats2 = take((uint64_t)d.T * 2 * 4);
+    m = take((uint64_t)d.T * d.h * 2);
+    f1 = take((uint64_t)d.T * d.ffn * 2);
+    g = take((uint64_t)d.T * d.ffn * 2);
+    total = o;
+  }
+};
+
 // backward workspace of one block
 struct BlockWs {
   uint64_t wide, t1, t2, t3, delta, part, splitk, splitk_bytes, total;
@@ -140,6 +168,7 @@ int gpt_build_records(Ctx& c) {
   const karma_model_desc& md = c.desc;
   if (!md.n_layers || !md.width || !md.batch || !md.seq || !md.n_heads || !md.ffn || !md.vocab) return KARMA_E_INVAL;
   if (md.width % md.n_heads) return KARMA_E_INVAL;
+  if (md.split_blocks > 1) return KARMA_E_INVAL;
   Dims d(md);
   if ((d.D != 64 && d.D != 128 && d.D != 152) || d.S % 128 || d.h % 8 || d.ffn % 8 || d.V % 8) return KARMA_E_INVAL;
   if ((uint64_t)d.V * 2 > 150 * 1024) return KARMA_E_INVAL;
@@ -153,22 +182,29 @@ int gpt_build_records(Ctx& c) {
   emb.out_bytes = act;
   c.rec.push_back(std::move(emb));
   BlockSaved sv(d);
+  AttnSaved asv(d);
+  FfnSaved fsv(d);
   BlockWs ws(d);
   for (uint32_t i = 0; i < md.n_layers; ++i) {
-    Record r;
-    r.kind = REC_BLOCK;
-    r.p.resize(12);
-    r.p[LN1_G] = make_param(d.h, false); r.p[LN1_B] = make_param(d.h, false);
-    r.p[WQKV] = make_param((uint64_t)3 * d.h * d.h, true); r.p[BQKV] = make_param(3 * d.h, false);
-    r.p[WO] = make_param((uint64_t)d.h * d.h, true); r.p[BO] = make_param(d.h, false);
-    r.p[LN2_G] = make_param(d.h, false); r.p[LN2_B] = make_param(d.h, false);
-    r.p[W1] = make_param((uint64_t)d.ffn * d.h, true); r.p[B1] = make_param(d.ffn, false);
-    r.p[W2] = make_param((uint64_t)d.h * d.ffn, true); r.p[B2] = make_param(d.h, false);
-    r.out_bytes = act;
-    r.sav_bytes = sv.total;
-    r.ws_bytes = ws.total;
-    r.streamed = md.stream_weights != 0;
-    c.rec.push_back(std::move(r));
+    std::vector<Param> p(12);
+    p[LN1_G] = make_param(d.h, false); p[LN1_B] = make_param(d.h, false);
+    p[WQKV] = make_param((uint64_t)3 * d.h * d.h, true); p[BQKV] = make_param(3 * d.h, false);
+    p[WO] = make_param((uint64_t)d.h * d.h, true); p[BO] = make_param(d.h, false);
+    p[LN2_G] = make_param(d.h, false); p[LN2_B] = make_param(d.h, false);
+    p[W1] = make_param((uint64_t)d.ffn * d.h, true); p[B1] = make_param(d.ffn, false);
+    p[W2] = make_param((uint64_t)d.h * d.ffn, true); p[B2] = make_param(d.h, false);
+    // one record per block, or its two halves (tensors 0..5 and 6..11) as records of their own
+    for (int half = 0; half < (md.split_blocks ? 2 : 1); ++half) {
+      Record r;
+      r.kind = md.split_blocks ? (half == 0 ? REC_ATTN : REC_FFN) : REC_BLOCK;
+      if (!md.split_blocks) r.p = p;
+      else r.p.assign(p.begin() + 6 * half, p.begin() + 6 * half + 6);
+      r.out_bytes = act;
+      r.sav_bytes = !md.split_blocks ? sv.total : half == 0 ? asv.total : fsv.total;
+      r.ws_bytes = ws.total;
+      r.streamed = md.stream_weights != 0;
+      c.rec.push_back(std::move(r));
+    }
   }
   Record loss;
   loss.kind = REC_LOSS_LMHEAD;
@@ -219,6 +255,71 @@ int gpt_prepare_late(Ctx& c) {
   return KARMA_OK;
 }
 
+namespace {
+
+// The two halves of a block.  Pointers into the saved set and the workspace are handed in, so that the same
+// code serves a whole-block record (one saved set, r1 inside it) and the split records (r1 is the attention
+// half's output and the feed-forward half's input).  W / G: the record's weight / gradient tensor of a
+// BlockParam, wherever the record keeps it.
+struct AttnBufs {
+  bf16_t* a; float* stats1; bf16_t* qkv; bf16_t* ctx; float* lse;
+};
+struct FfnBufs {
+  float* stats2; bf16_t* m; bf16_t* f1; bf16_t* g;
+};
+struct BwdBufs {
+  bf16_t* wide; bf16_t* t1; bf16_t* t3; float* delta; float* part; char* splitk; uint64_t splitk_bytes;
+};
+
+template <class WF>
+int attn_half_fwd(const Dims& d, const bf16_t* x, const AttnBufs& b, bf16_t* r1, WF W, hipStream_t s) {
+  TRY(layernorm_fwd(x, W(LN1_G), W(LN1_B), b.a, b.stats1, d.T, d.h, s));
+  TRY(gemm(b.a, W(WQKV), b.qkv, W(BQKV), nullptr, d.T, 3 * d.h, d.h, true, true, false, false, s));
+  TRY(attention_fwd(b.qkv, b.ctx, b.lse, d.B, d.S, d.H, d.D, s));
+  // a recompute whose output nobody needs stops here: backward only reads the internals
+  if (r1) TRY(gemm(b.ctx, W(WO), r1, W(BO), x, d.T, d.h, d.h, true, true, false, false, s));
+  return KARMA_OK;
+}
+
+template <class WF>
+int ffn_half_fwd(const Dims& d, const bf16_t* r1, const FfnBufs& b, bf16_t* out, WF W, hipStream_t s) {
+  TRY(layernorm_fwd(r1, W(LN2_G), W(LN2_B), b.m, b.stats2, d.T, d.h, s));
+  TRY(gemm_gelu(b.m, W(W1), b.f1, W(B1), b.g, d.T, d.ffn, d.h, true, true, 1, s));   // f1 = m W1^T + b1, g = GELU(f1)
+  if (out) TRY(gemm(b.g, W(W2), out, W(B2), r1, d.T, d.h, d.ffn, true, true, false, false, s));
+  return KARMA_OK;
+}
+
+// y = r1 + g W2^T + b2 back to dr1 = LN2'(dm) + dy
+template <class WF, class GF>
+int ffn_half_bwd(const Dims& d, const bf16_t* dy, const bf16_t* r1, const FfnBufs& b, const BwdBufs& w, bf16_t* dr1, WF W,
+                 GF G, hipStream_t s) {
+  TRY(gemm_gelu(dy, W(W2), w.wide, nullptr, b.f1, d.T, d.ffn, d.h, true, false, 2, s));         // df1 = (dy W2) * GELU'(f1)
+  TRY(gemm(dy, b.g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));        // dW2 = dy^T g
+  TRY(colsum_bf16(dy, (float*)G(B2), w.part, d.T, d.h, s));
+  TRY(gemm(w.wide, W(W1), w.t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
+  TRY(gemm(w.wide, b.m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));    // dW1 = df1^T m
+  TRY(colsum_bf16(w.wide, (float*)G(B1), w.part, d.T, d.ffn, s));
+  TRY(layernorm_bwd(w.t1, r1, b.stats2, W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), w.part, d.T, d.h, s));
+  return KARMA_OK;
+}
+
+// r1 = x + ctx Wo^T + bo back to dx = LN1'(da) + dr1
+template <class WF, class GF>
+int attn_half_bwd(const Dims& d, const bf16_t* dr1, const bf16_t* x, const AttnBufs& b, const BwdBufs& w, bf16_t* dx, WF W,
+                  GF G, hipStream_t s) {
+  TRY(gemm(dr1, W(WO), w.t1, nullptr, nullptr, d.T, d.h, d.h, true, false, false, false, s));         // dctx = dr1 Wo
+  TRY(gemm(dr1, b.ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));       // dWo = dr1^T ctx
+  TRY(colsum_bf16(dr1, (float*)G(BO), w.part, d.T, d.h, s));
+  TRY(attention_bwd(b.qkv, b.ctx, w.t1, b.lse, w.delta, w.wide, d.B, d.S, d.H, d.D, s));
+  TRY(gemm(w.wide, W(WQKV), w.t3, nullptr, nullptr, d.T, d.h, 3 * d.h, true, false, false, false, s));  // da = dqkv Wqkv
+  TRY(gemm(w.wide, b.a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));  // dWqkv = dqkv^T a
+  TRY(colsum_bf16(w.wide, (float*)G(BQKV), w.part, d.T, 3 * d.h, s));
+  TRY(layernorm_bwd(w.t3, x, b.stats1, W(LN1_G), dr1, dx, (float*)G(LN1_G), (float*)G(LN1_B), w.part, d.T, d.h, s));
+  return KARMA_OK;
+}
+
+}  // namespace
+
 int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   Dims d(c.desc);
   if (i == 0) {
@@ -226,26 +327,28 @@ int gpt_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
     return embed_fwd((const int*)io.x, (const bf16_t*)c.w_ptr(0, 0), (const bf16_t*)c.w_ptr(0, 1), (bf16_t*)io.out, d.T,
                      d.S, d.h, s);
   }
-  BlockSaved sv(d);
   char* S = (char*)io.sav;
   const bf16_t* x = (const bf16_t*)io.x;
-  bf16_t* a = (bf16_t*)(S + sv.a);
-  bf16_t* qkv = (bf16_t*)(S + sv.qkv);
-  bf16_t* ctx = (bf16_t*)(S + sv.ctx);
+  const int kind = c.rec[i].kind;
+  // a split record holds six of the block's twelve tensors: the feed-forward half's start at LN2_G
+  const int first = kind == REC_FFN ? (int)LN2_G : 0;
+  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t - first, io.w); };
+  if (kind == REC_ATTN) {
+    AttnSaved sv(d);
+    AttnBufs ab{(bf16_t*)(S + sv.a), (float*)(S + sv.stats1), (bf16_t*)(S + sv.qkv), (bf16_t*)(S + sv.ctx), (float*)(S + sv.lse)};
+    return attn_half_fwd(d, x, ab, (bf16_t*)io.out, W, s);
+  }
+  if (kind == REC_FFN) {
+    FfnSaved sv(d);
+    FfnBufs fb{(float*)(S + sv.stats2), (bf16_t*)(S + sv.m), (bf16_t*)(S + sv.f1), (bf16_t*)(S + sv.g)};
+    return ffn_half_fwd(d, x, fb, (bf16_t*)io.out, W, s);
+  }
+  BlockSaved sv(d);
+  AttnBufs ab{(bf16_t*)(S + sv.a), (float*)(S + sv.stats1), (bf16_t*)(S + sv.qkv), (bf16_t*)(S + sv.ctx), (float*)(S + sv.lse)};
+  FfnBufs fb{(float*)(S + sv.stats2), (bf16_t*)(S + sv.m), (bf16_t*)(S + sv.f1), (bf16_t*)(S + sv.g)};
   bf16_t* r1 = (bf16_t*)(S + sv.r1);
-  bf16_t* m = (bf16_t*)(S + sv.m);
-  bf16_t* f1 = (bf16_t*)(S + sv.f1);
-  bf16_t* g = (bf16_t*)(S + sv.g);
-  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t, io.w); };
-  TRY(layernorm_fwd(x, W(LN1_G), W(LN1_B), a, (float*)(S + sv.stats1), d.T, d.h, s));
-  TRY(gemm(a, W(WQKV), qkv, W(BQKV), nullptr, d.T, 3 * d.h, d.h, true, true, false, false, s));
-  TRY(attention_fwd(qkv, ctx, (float*)(S + sv.lse), d.B, d.S, d.H, d.D, s));
-  TRY(gemm(ctx, W(WO), r1, W(BO), x, d.T, d.h, d.h, true, true, false, false, s));
-  TRY(layernorm_fwd(r1, W(LN2_G), W(LN2_B), m, (float*)(S + sv.stats2), d.T, d.h, s));
-  TRY(gemm_gelu(m, W(W1), f1, W(B1), g, d.T, d.ffn, d.h, true, true, 1, s));   // f1 = m W1^T + b1, g = GELU(f1)
-  // a recompute whose output nobody needs stops here: backward only reads the internals
-  if (io.out) TRY(gemm(g, W(W2), io.out, W(B2), r1, d.T, d.h, d.ffn, true, true, false, false, s));
-  return KARMA_OK;
+  TRY(attn_half_fwd(d, x, ab, r1, W, s));
+  return ffn_half_fwd(d, r1, fb, (bf16_t*)io.out, W, s);
 }
 
 int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
@@ -258,51 +361,32 @@ int gpt_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
     return embed_bwd(dy, order, seg_start, seg_id, (int)c.n_segments, (float*)c.g_ptr(0, 0), (bf16_t*)c.g_ptr(0, 1),
                      d.B, d.S, d.h, s);
   }
-  BlockSaved sv(d);
   BlockWs wl(d);
   char* S = (char*)io.sav;
   char* Wk = (char*)io.ws;
   const bf16_t* x = (const bf16_t*)io.x;
-  const bf16_t* a = (const bf16_t*)(S + sv.a);
-  const bf16_t* qkv = (const bf16_t*)(S + sv.qkv);
-  const bf16_t* ctx = (const bf16_t*)(S + sv.ctx);
-  const bf16_t* r1 = (const bf16_t*)(S + sv.r1);
-  const bf16_t* m = (const bf16_t*)(S + sv.m);
-  const bf16_t* f1 = (const bf16_t*)(S + sv.f1);
-  const bf16_t* g = (const bf16_t*)(S + sv.g);
-  bf16_t* wide = (bf16_t*)(Wk + wl.wide);
-  bf16_t* t1 = (bf16_t*)(Wk + wl.t1);
+  BwdBufs wb{(bf16_t*)(Wk + wl.wide), (bf16_t*)(Wk + wl.t1), (bf16_t*)(Wk + wl.t3), (float*)(Wk + wl.delta),
+             (float*)(Wk + wl.part), Wk + wl.splitk, wl.splitk_bytes};
+  const int kind = c.rec[i].kind;
+  const int first = kind == REC_FFN ? (int)LN2_G : 0;
+  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t - first, io.w); };
+  auto G = [&](int t) { return c.g_ptr(i, t - first, io.g); };
+  if (kind == REC_ATTN) {
+    AttnSaved sv(d);
+    AttnBufs ab{(bf16_t*)(S + sv.a), (float*)(S + sv.stats1), (bf16_t*)(S + sv.qkv), (bf16_t*)(S + sv.ctx), (float*)(S + sv.lse)};
+    return attn_half_bwd(d, dy, x, ab, wb, (bf16_t*)io.dx, W, G, s);
+  }
+  if (kind == REC_FFN) {
+    FfnSaved sv(d);
+    FfnBufs fb{(float*)(S + sv.stats2), (bf16_t*)(S + sv.m), (bf16_t*)(S + sv.f1), (bf16_t*)(S + sv.g)};
+    return ffn_half_bwd(d, dy, x, fb, wb, (bf16_t*)io.dx, W, G, s);
+  }
+  BlockSaved sv(d);
+  AttnBufs ab{(bf16_t*)(S + sv.a), (float*)(S + sv.stats1), (bf16_t*)(S + sv.qkv), (bf16_t*)(S + sv.ctx), (float*)(S + sv.lse)};
+  FfnBufs fb{(float*)(S + sv.stats2), (bf16_t*)(S + sv.m), (bf16_t*)(S + sv.f1), (bf16_t*)(S + sv.g)};
   bf16_t* dr1 = (bf16_t*)(Wk + wl.t2);
-  bf16_t* da = (bf16_t*)(Wk + wl.t3);
-  float* part = (float*)(Wk + wl.part);
-  auto W = [&](int t) { return (const bf16_t*)c.w_ptr(i, t, io.w); };
-  auto G = [&](int t) { return c.g_ptr(i, t, io.g); };
-
-  // FC2: y = r1 + g W2^T + b2
-  TRY(gemm_gelu(dy, W(W2), wide, nullptr, (bf16_t*)f1, d.T, d.ffn, d.h, true, false, 2, s));         // df1 = (dy W2) * GELU'(f1)
-  TRY(gemm(dy, g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));        // dW2 = dy^T g
-  TRY(colsum_bf16(dy, (float*)G(B2), part, d.T, d.h, s));
-  // FC1
-  TRY(gemm(wide, W(W1), t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
-  TRY(gemm(wide, m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));      // dW1 = df1^T m
-  TRY(colsum_bf16(wide, (float*)G(B1), part, d.T, d.ffn, s));
-  // LN2 and the residual branch: dr1 = LN2'(dm) + dy
-  TRY(layernorm_bwd(t1, r1, (const float*)(S + sv.stats2), W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), part,
-                    d.T, d.h, s));
-  // attention output projection
-  TRY(gemm(dr1, W(WO), t1, nullptr, nullptr, d.T, d.h, d.h, true, false, false, false, s));         // dctx = dr1 Wo
-  TRY(gemm(dr1, ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));       // dWo = dr1^T ctx
-  TRY(colsum_bf16(dr1, (float*)G(BO), part, d.T, d.h, s));
-  // attention
-  TRY(attention_bwd(qkv, ctx, t1, (const float*)(S + sv.lse), (float*)(Wk + wl.delta), wide, d.B, d.S, d.H, d.D, s));
-  // QKV projection
-  TRY(gemm(wide, W(WQKV), da, nullptr, nullptr, d.T, d.h, 3 * d.h, true, false, false, false, s));  // da = dqkv Wqkv
-  TRY(gemm(wide, a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s, Wk + wl.splitk, wl.splitk_bytes));  // dWqkv = dqkv^T a
-  TRY(colsum_bf16(wide, (float*)G(BQKV), part, d.T, 3 * d.h, s));
-  // LN1 and the residual: dx = LN1'(da) + dr1
-  TRY(layernorm_bwd(da, x, (const float*)(S + sv.stats1), W(LN1_G), dr1, (bf16_t*)io.dx, (float*)G(LN1_G),
-                    (float*)G(LN1_B), part, d.T, d.h, s));
-  return KARMA_OK;
+  TRY(ffn_half_bwd(d, dy, (const bf16_t*)(S + sv.r1), fb, wb, dr1, W, G, s));
+  return attn_half_bwd(d, dr1, x, ab, wb, (bf16_t*)io.dx, W, G, s);
 }
 
 // Final LayerNorm, tied LM head and mean cross-entropy with their gradients, chunked over

@@ -387,9 +387,11 @@ struct Timeline {
         if (j < u.tail) x_at[j + 1] = obtain(x_sz[j + 1], true, now);
         int64_t w = obtain(w_sz[j], false, now);
         if (failed) break;
-        int64_t end = now + P.layers[j].trc_ns;
-        busy += P.layers[j].trc_ns;
-        redo += P.layers[j].trc_ns;
+        // inside a run the layer's output is rebuilt too (a forward pass); the run's last layer rebuilds its internals only
+        const int64_t again = j < u.tail ? P.layers[j].tf_ns : P.layers[j].trc_ns;
+        int64_t end = now + again;
+        busy += again;
+        redo += again;
         emit('R', j, now, end, s_at[j], j < u.tail ? x_at[j + 1] : -1, w);
         t_comp = end;
         drop(w, w_sz[j]);
@@ -605,7 +607,7 @@ bool plan_grouped(const Problem& P, uint32_t max_group, std::vector<uint8_t>& ac
         karma_layer_cost m{};
         for (uint32_t k = 0; k < n; ++k) {
           const karma_layer_cost& l = P.layers[first + k];
-          m.tf_ns += l.tf_ns; m.tb_ns += l.tb_ns; m.trc_ns += l.trc_ns;
+          m.tf_ns += l.tf_ns; m.tb_ns += l.tb_ns; m.trc_ns += k + 1 < n ? l.tf_ns : l.trc_ns;
           m.sav_bytes += l.sav_bytes + (k + 1 < n ? l.out_bytes : 0);
           m.ws_bytes = std::max(m.ws_bytes, l.ws_bytes);
           m.w_bytes += l.w_bytes; m.g_bytes += l.g_bytes;

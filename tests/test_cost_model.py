@@ -15,7 +15,7 @@ CNN = dict(width=64, stage_blocks=(3, 24, 36, 3), image=224, batch=64, classes=1
 def gpt_desc(batch=32, **over):
     g = dict(GPT, batch=batch, **over)
     return dict(kind=K.MODEL_GPT, n_layers=g["n_layers"], width=g["hidden"], batch=g["batch"], seq=g["seq"],
-                n_heads=g["heads"], ffn=g["ffn"], vocab=g["vocab"], stream_weights=0)
+                n_heads=g["heads"], ffn=g["ffn"], vocab=g["vocab"], stream_weights=0, split_blocks=g.get("split_blocks", 0))
 
 
 def cnn_desc(batch=64):
@@ -95,6 +95,26 @@ def test_library_times_bit_exact():
                 *CM.gpt_blocks(n_layers=72, hidden=3072, heads=24, ffn=12288, vocab=51200, seq=1024, batch=8))
     for batch in (2, 64):
         check_times(cnn_desc(batch), *CM.cnn_blocks(**dict(CNN, batch=batch)))
+
+
+def test_split_transformer_blocks_counts_and_bytes():
+    """Two records per block: their counts add up to the whole block's, the library's times equal the oracle's,
+    and the halves' bytes make up the block's (r1 moves from the saved set to the attention half's output)."""
+    whole, loss = CM.gpt_blocks(**GPT)
+    halves, loss2 = CM.gpt_blocks(split=True, **GPT)
+    assert loss == loss2 and len(halves) == 2 * GPT["n_layers"] + 1 and halves[0] == whole[0]
+    for k in range(GPT["n_layers"]):
+        a, f = halves[2 * k + 1], halves[2 * k + 2]
+        assert (a[0] + f[0], a[1] + f[1]) == whole[k + 1]
+    T, h, ffn = GPT["batch"] * GPT["seq"], GPT["hidden"], GPT["ffn"]
+    assert halves[2][0] == T * 2 * h * ffn                      # FC1 and FC2
+    lay_s, fixed_s = check_times(gpt_desc(split_blocks=1), halves, loss)
+    lay_w, fixed_w = check_times(gpt_desc(), whole, loss)
+    assert fixed_s == fixed_w
+    for k in range(GPT["n_layers"]):
+        a, f, w = lay_s[2 * k + 1], lay_s[2 * k + 2], lay_w[k + 1]
+        assert a[3] + f[3] + a[4] == w[3] and a[4] == f[4] == w[4]
+        assert a[6] + f[6] == w[6] and a[7] + f[7] == w[7]
 
 
 def test_library_bytes_match_the_shape_arithmetic():

@@ -144,6 +144,90 @@ def test_gpt_head_dimension_152_and_ragged_widths(g):
     ctx.close()
 
 
+def split_ctx(arena, dims, lr=1e-3):
+    desc = dict(kind=K.MODEL_GPT, n_layers=dims["n_layers"], width=dims["hidden"], batch=dims["batch"], seq=dims["seq"],
+                n_heads=dims["heads"], ffn=dims["ffn"], vocab=dims["vocab"], split_blocks=1)
+    cfg = dict(optimizer=K.OPT_ADAM, lr=lr, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=8)
+    return K.Context(desc, cfg, arena)
+
+
+def split_slot(block, t):
+    """(record, tensor) of block tensor t when every block is two records."""
+    return (2 * block + 1, t) if t < 6 else (2 * block + 2, t - 6)
+
+
+def load_params_split(ctx, params):
+    ctx.karma_set_param(0, 0, params["wte"])
+    ctx.karma_set_param(0, 1, params["wpe"])
+    for i, b in enumerate(params["blocks"]):
+        for t, name in enumerate(BLOCK_T):
+            ctx.karma_set_param(*split_slot(i, t), b[name])
+    L = 2 * len(params["blocks"]) + 1
+    ctx.karma_set_param(L, 0, params["lnf_g"])
+    ctx.karma_set_param(L, 1, params["lnf_b"])
+
+
+def all_grads_split(ctx, n_blocks):
+    out = {"wte": ctx.karma_get_grad(0, 0), "wpe": ctx.karma_get_grad(0, 1)}
+    for i in range(n_blocks):
+        for t, name in enumerate(BLOCK_T):
+            out["b%d.%s" % (i, name)] = ctx.karma_get_grad(*split_slot(i, t))
+    out["lnf_g"] = ctx.karma_get_grad(2 * n_blocks + 1, 0)
+    out["lnf_b"] = ctx.karma_get_grad(2 * n_blocks + 1, 1)
+    return out
+
+
+def test_blocks_split_into_attention_and_feed_forward_records(g):
+    """split_blocks: the planner sees two records per transformer block.  The same kernels run in the same
+    order, so loss and gradients equal those of whole blocks bit for bit, under any plan over the seven
+    records; the plan equals the oracle's plan on the context's cost records; Adam reaches the same weights."""
+    params, ids, labels = small_problem()
+    whole = make_ctx(arena=512 << 20, **SMALL)
+    load_params(whole, params)
+    whole.karma_set_plan(512 << 20, [K.KEEP] * 4)
+    loss = whole.karma_step(ids, labels)
+    ref = all_grads(whole, 3)
+
+    ctx = split_ctx(512 << 20, SMALL)
+    load_params_split(ctx, params)
+    layers, loss_c, fixed = ctx.karma_get_costs()
+    assert len(layers) == 7
+    lw = whole.karma_get_costs()[0]
+    # the halves' saved sets make up the block's but for r1, which is now the attention half's output
+    assert layers[1][3] + layers[2][3] + layers[1][4] == lw[1][3]
+    assert layers[1][6] + layers[2][6] == lw[1][6] and layers[1][6] > 0 or lw[1][6] == 0
+    big = 512 << 20
+    plans = [[K.KEEP] * 7,
+             [K.KEEP, K.KEEP, K.RC_KEEP, K.KEEP, K.RC_KEEP, K.KEEP, K.RC_KEEP],        # feed-forward halves recomputed
+             [K.KEEP, K.RC_KEEP, K.RC_CHAIN, K.SWAP, K.RC_SWAP, K.RC_KEEP, K.KEEP],
+             [K.SWAP, K.RC_SWAP, K.RC_CHAIN, K.RC_CHAIN, K.RC_CHAIN, K.SWAP, K.SWAP]]
+    for pl in plans:
+        ctx.karma_set_plan(big, pl)
+        assert ctx.karma_step(ids, labels) == loss, pl
+        for name, v in all_grads_split(ctx, 3).items():
+            assert np.array_equal(v, ref[name]), (pl, name)
+    # planner parity on the seven records, under a budget that forces choices
+    layers = [(1000 + 10 * i, 2000 + 10 * i, 1000 + 10 * i) + l[3:] for i, l in enumerate(layers)]
+    link = (2 * 10**9, 2 * 10**9, 1000)
+    ctx.karma_set_costs(layers, (3000, loss_c[1]), link)
+    budget = fixed + int(0.55 * sum(l[3] + l[4] for l in layers)) + max(max(l[5] for l in layers), loss_c[1])
+    acts, summ = ctx.karma_plan(budget)
+    ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(3000, loss_c[1]))
+    assert acts == ao and summ["makespan_ns"] == so["makespan_ns"] and summ["peak_bytes"] == so["peak_bytes"]
+    assert acts != [K.KEEP] * 7
+    assert ctx.karma_step(ids, labels) == loss
+    for name, v in all_grads_split(ctx, 3).items():
+        assert np.array_equal(v, ref[name]), name
+    # one Adam step in both: the same master weights
+    l0 = whole.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+    l1 = ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+    assert l0 == l1
+    for blk, t in ((0, 2), (1, 8), (2, 11), (2, 0)):
+        assert np.array_equal(whole.karma_get_param(blk + 1, t), ctx.karma_get_param(*split_slot(blk, t))), (blk, t)
+    whole.close()
+    ctx.close()
+
+
 def test_profiled_step_gives_op_starts_in_stream_order(g):
     """KARMA_STEP_PROFILE: every op's begin and duration; ops of one stream follow each other without overlap,
     and the compute stream's busy time plus its idle gaps span the step."""

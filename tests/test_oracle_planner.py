@@ -44,6 +44,25 @@ def test_all_keep_timeline_by_hand():
     assert r["peak_bytes"] == 1234 + al(500) + al(1000) + al(700) + al(3000) + al(700) + al(300)
 
 
+def test_recompute_run_prices_inner_layers_as_forward_and_the_last_as_internals_only():
+    """A run of recomputed layers re-runs the forward pass of every layer but rebuilds the output of all
+    except the last (whose output still exists as the next layer's input): inner layers cost tf, the last
+    one trc (Sec. III-F).  By hand: tf 100, tb 200, trc 40 each."""
+    layers = [P.Layer(100, 200, 40, 1024, 1024, 0) for _ in range(4)]
+    link = P.Link(10**9, 10**9, 0)
+    # layers 1..2 form one run (checkpoint at 1, chained 2): R1 = tf, R2 = trc
+    r = P.simulate(layers, link, 10**6, 0, P.Loss(10, 0), [0, 2, 4, 0], want_ops=True)
+    redo = [(o.layer, o.end - o.start) for o in r["ops"] if o.kind == "R"]
+    assert redo == [(1, 100), (2, 40)]
+    assert r["recompute_ns"] == 140 and r["makespan_ns"] == 4 * 100 + 10 + 4 * 200 + 140
+    # two runs of one: each is the last of its run
+    r = P.simulate(layers, link, 10**6, 0, P.Loss(10, 0), [0, 2, 2, 0])
+    assert r["recompute_ns"] == 80
+    # a merged block of three: re-running it costs two forward passes and one internals-only pass
+    m = P.merge_group(layers[:3])
+    assert (m.tf, m.tb, m.trc) == (300, 600, 240)
+
+
 def test_single_swap_timeline_by_hand():
     # layer 1 swapped: 4000 B out at 2 B/ns -> 2000 ns + 5 latency, starts when F1 ends
     layers = [P.Layer(100, 100, 100, 1024, 1024, 0), P.Layer(100, 100, 100, 3072 - 96, 1024, 0),
