@@ -36,7 +36,7 @@ WORKLOADS = {
                  "batch 8, vocab 51200, bf16 weights streamed per layer from pinned host memory (gradients land in the same pinned buffers), fp32 host "
                  "master/Adam, HBM budget 32 GiB"),
     4: dict(cfg=dict(n_layers=78, hidden=4256, heads=28, ffn=17024, vocab=51200, seq=1024, batch=4),
-            budget=32 * GIB, arena=96 * GIB, seed=2008114205, stream=2,
+            budget=32 * GIB, arena=96 * GIB, seed=2008114205, stream=2, whole_blocks=True,
             name="configs[4]: 78-layer pre-LN GPT (17B parameters), hidden 4256, 28 heads of 152, FFN 17024, seq 1024, "
                  "batch 4, vocab 51200, bf16 weights streamed per layer from pinned host memory (gradients land in "
                  "the same pinned buffers) and activations swapped, fp32 host master/Adam (about 225 GiB of host "
@@ -287,8 +287,8 @@ def main():
         return bench_cnn(args, wl, K, si, torch, np, threads)
     desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=CFG["batch"], seq=CFG["seq"],
                 n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=wl["stream"],
-                split_blocks=0 if args.whole_blocks else 1)
-    split = not args.whole_blocks
+                split_blocks=0 if (args.whole_blocks or wl.get("whole_blocks")) else 1)
+    split = bool(desc["split_blocks"])
 
     def slot(block, t):   # (record, tensor) of tensor t of transformer block `block`
         if not split:
