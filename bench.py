@@ -380,6 +380,7 @@ def main():
     # without recompute (longest resident tail, the prefix swapped); plain checkpointing
     # every 5 blocks.  A few steps each: context for the planner's choice, not the metric.
     L = len(acts)
+    swapped_prefix = 0
     candidates = {"eager_swap_all": [K.SWAP] * L,
                   "checkpoint_every_5": [K.RC_KEEP if i % 5 == 0 else K.RC_CHAIN for i in range(L)]}
     for k in range(1, L + 1):
@@ -389,6 +390,7 @@ def main():
         except K.KarmaError:
             continue
         candidates["capacity_swap_no_recompute"] = cand
+        swapped_prefix = k
         break
     policies = {}
     n_pol = max(2, min(5, args.steps))
@@ -408,9 +410,11 @@ def main():
         torch.cuda.synchronize()
         dtp = (time.perf_counter() - t1) / n_pol
         stalls_p = backward_stalls(ctx, profiled_step, L)
+        extra = {"swapped_prefix_records": swapped_prefix, "of_records": L} if name == "capacity_swap_no_recompute" else {}
         policies[name] = {"feasible": True, "ms_per_step": dtp * 1e3, "samples_per_s": CFG["batch"] / dtp,
                           "predicted_makespan_ms": sp["makespan_ns"] / 1e6, "planned_over_this": dtp / dt,
-                          "backward_stall_ms": stalls_p["total_ms"], "backward_stall_simulated_ms": stalls_p["simulated_total_ms"]}
+                          "backward_stall_ms": stalls_p["total_ms"], "backward_stall_simulated_ms": stalls_p["simulated_total_ms"],
+                          **extra}
         log("policy %s: %.1f ms/step (planned schedule is %.2fx faster), backward-phase stalls %.1f ms (simulated %.1f)"
             % (name, dtp * 1e3, dtp / dt, stalls_p["total_ms"], stalls_p["simulated_total_ms"]))
 
