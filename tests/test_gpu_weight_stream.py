@@ -168,6 +168,42 @@ def test_gradients_landing_in_the_weights_pinned_buffer(g):
         assert np.array_equal(a, b)
 
 
+def test_half_block_records_shared_staging_and_late_updates_together(g):
+    """The combination the large benchmark workloads run: two records per block, weights streamed with the
+    gradients landing in the weights' pinned buffers, a slow host (one thread) that leaves updates to the next
+    step.  Losses over several Adam steps and the final parameters equal those of whole blocks with resident
+    weights and every update finished inside its step."""
+    dims = dict(n_layers=3, hidden=256, heads=4, ffn=1024, vocab=2048, seq=128, batch=2)
+    params, ids, labels = si.gpt_problem(seed=2008114207, std=0.05, bias_std=0.05, **{k: v for k, v in dims.items() if k != "heads"})
+    ids, labels = ids.astype(np.int32), labels.astype(np.int32)
+
+    def run(stream, split, finish_each_step, plan, kept):
+        desc = dict(kind=K.MODEL_GPT, n_layers=3, width=256, batch=2, seq=128, n_heads=4, ffn=1024, vocab=2048,
+                    stream_weights=stream, split_blocks=split)
+        ctx = K.Context(desc, dict(optimizer=K.OPT_ADAM, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=1), 512 << 20)
+        (TG.load_params_split if split else TG.load_params)(ctx, params)
+        ctx.karma_set_plan(400 << 20, plan, kept)
+        losses, deferred = [], 0
+        for _ in range(4):
+            losses.append(ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER))
+            deferred += ctx.karma_get_stats()["updates_deferred"]
+            if finish_each_step:
+                ctx.karma_finish_updates()
+        losses.append(ctx.karma_step(ids, labels))
+        slots = [(b, t) for b in range(3) for t in (0, 2, 5, 8, 11)]
+        got = [ctx.karma_get_param(*(TG.split_slot(b, t) if split else (b + 1, t))) for b, t in slots]
+        got += [ctx.karma_get_param(0, 0), ctx.karma_get_param(7 if split else 4, 1)]
+        ctx.close()
+        return losses, got, deferred
+
+    ref = run(0, 0, True, [K.KEEP] * 4, None)
+    new = run(2, 1, False, [K.KEEP, K.SWAP, K.RC_KEEP, K.KEEP, K.RC_SWAP, K.RC_KEEP, K.RC_CHAIN], [0, 1, 0, 0, 1, 0, 0])
+    assert new[2] > 0, "no update was left pending: the test does not exercise that path"
+    assert ref[0] == new[0] and ref[0][-1] < ref[0][0]
+    for a, b in zip(ref[1], new[1]):
+        assert np.array_equal(a, b)
+
+
 def test_gpt_streamed_weights_bit_identical_and_adam(g):
     params, ids, labels = TG.small_problem()
     big = 512 << 20
