@@ -371,10 +371,17 @@ int karma_k_gemm_gelu_bf16(const void* a_dev, const void* b_dev, void* c_dev, co
 int karma_k_layernorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const void* beta_dev, void* y_dev,
                                float* stats_dev, uint32_t rows, uint32_t h, void* stream);
 /* Its backward: dx (+ add_dev if not NULL, e.g. a residual gradient), dgamma/dbeta fp32 [h]
- * reduced in a fixed order.  ws_dev: ceil(rows/64)*2*h floats (KARMA_E_OOM if smaller). */
+ * reduced in a fixed order.  ws_dev: ceil(rows/64)*3*h floats (KARMA_E_OOM if smaller). */
 int karma_k_layernorm_bwd_bf16(const void* dy_dev, const void* x_dev, const float* stats_dev, const void* gamma_dev,
                                const void* add_dev, void* dx_dev, float* dgamma_dev, float* dbeta_dev, float* ws_dev,
                                uint64_t ws_bytes, uint32_t rows, uint32_t h, void* stream);
+/* The same with add_dev required and its column sums delivered as well: add_colsum_dev[c] = sum over rows of
+ * add[r][c], fp32 [h] (add is the gradient of the sum the LayerNorm's input went into; its column sums are that
+ * sum's bias gradient, taken here without another pass over the tensor). */
+int karma_k_layernorm_bwd_addsum_bf16(const void* dy_dev, const void* x_dev, const float* stats_dev, const void* gamma_dev,
+                                      const void* add_dev, void* dx_dev, float* dgamma_dev, float* dbeta_dev,
+                                      float* add_colsum_dev, float* ws_dev, uint64_t ws_bytes, uint32_t rows, uint32_t h,
+                                      void* stream);
 /* out[c] = sum over rows of x[r][c] (bias gradients), fixed order.  ws: ceil(rows/64)*cols floats. */
 int karma_k_colsum_bf16(const void* x_dev, float* out_dev, float* ws_dev, uint64_t ws_bytes, uint32_t rows,
                         uint32_t cols, void* stream);

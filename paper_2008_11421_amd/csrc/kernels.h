@@ -69,7 +69,8 @@ int layernorm_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, bf16_t* y, 
 size_t layernorm_bwd_ws_bytes(int rows, int h);
 // dx = LayerNorm backward (+ add, may be null); dgamma/dbeta fp32 [h]
 int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* add, bf16_t* dx,
-                  float* dgamma, float* dbeta, float* partial_ws, int rows, int h, hipStream_t s);
+                  float* dgamma, float* dbeta, float* partial_ws, int rows, int h, hipStream_t s,
+                  float* add_colsum = nullptr);
 size_t colsum_ws_bytes(int rows, int cols);
 int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int cols, hipStream_t s);
 int gelu_fwd(const bf16_t* x, bf16_t* y, size_t n, hipStream_t s);

@@ -295,11 +295,12 @@ int ffn_half_bwd(const Dims& d, const bf16_t* dy, const bf16_t* r1, const FfnBuf
                  GF G, hipStream_t s) {
   TRY(gemm_gelu(dy, W(W2), w.wide, nullptr, b.f1, d.T, d.ffn, d.h, true, false, 2, s));         // df1 = (dy W2) * GELU'(f1)
   TRY(gemm(dy, b.g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));        // dW2 = dy^T g
-  TRY(colsum_bf16(dy, (float*)G(B2), w.part, d.T, d.h, s));
   TRY(gemm(w.wide, W(W1), w.t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
   TRY(gemm(w.wide, b.m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));    // dW1 = df1^T m
   TRY(colsum_bf16(w.wide, (float*)G(B1), w.part, d.T, d.ffn, s));
-  TRY(layernorm_bwd(w.t1, r1, b.stats2, W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), w.part, d.T, d.h, s));
+  // dr1 = LN2'(dm) + dy; the same pass sums dy's columns: the gradient of FC2's bias
+  TRY(layernorm_bwd(w.t1, r1, b.stats2, W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), w.part, d.T, d.h, s,
+                    (float*)G(B2)));
   return KARMA_OK;
 }
 
@@ -309,12 +310,13 @@ int attn_half_bwd(const Dims& d, const bf16_t* dr1, const bf16_t* x, const AttnB
                   GF G, hipStream_t s) {
   TRY(gemm(dr1, W(WO), w.t1, nullptr, nullptr, d.T, d.h, d.h, true, false, false, false, s));         // dctx = dr1 Wo
   TRY(gemm(dr1, b.ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));       // dWo = dr1^T ctx
-  TRY(colsum_bf16(dr1, (float*)G(BO), w.part, d.T, d.h, s));
   TRY(attention_bwd(b.qkv, b.ctx, w.t1, b.lse, w.delta, w.wide, d.B, d.S, d.H, d.D, s));
   TRY(gemm(w.wide, W(WQKV), w.t3, nullptr, nullptr, d.T, d.h, 3 * d.h, true, false, false, false, s));  // da = dqkv Wqkv
   TRY(gemm(w.wide, b.a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));  // dWqkv = dqkv^T a
   TRY(colsum_bf16(w.wide, (float*)G(BQKV), w.part, d.T, 3 * d.h, s));
-  TRY(layernorm_bwd(w.t3, x, b.stats1, W(LN1_G), dr1, dx, (float*)G(LN1_G), (float*)G(LN1_B), w.part, d.T, d.h, s));
+  // dx = LN1'(da) + dr1; the same pass sums dr1's columns: the gradient of the output projection's bias
+  TRY(layernorm_bwd(w.t3, x, b.stats1, W(LN1_G), dr1, dx, (float*)G(LN1_G), (float*)G(LN1_B), w.part, d.T, d.h, s,
+                    (float*)G(BO)));
   return KARMA_OK;
 }
 

@@ -105,22 +105,30 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __rest
 // ---- LayerNorm backward: dx per row (one wavefront per row); per-workgroup partial sums
 // of dgamma/dbeta over a contiguous band of rows, reduced by colsum_finish_kernel.
 // dx = rstd * (dy*g - mean(dy*g) - xhat * mean(dy*g*xhat)) (+ add)
+// ADDSUM: the column sums of `add` are reduced along with dgamma and dbeta (the added tensor is the gradient
+// of the sum the LayerNorm's input went into, whose bias gradient is exactly that column sum: one pass less
+// over it).  The partial rows then hold three vectors of h instead of two.
 constexpr int LNB_ROWS = 64;   // rows per workgroup: 4 wavefronts x 16 rows
-template <int LN_MAXV>
+template <int LN_MAXV, bool ADDSUM>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
                                                              const float* __restrict__ stats, const bf16_t* __restrict__ g,
                                                              const bf16_t* __restrict__ add, bf16_t* __restrict__ dx,
                                                              float* __restrict__ partial, int rows, int h) {
-  extern __shared__ float lds[];   // [4][2][h]
+  constexpr int NS = ADDSUM ? 3 : 2;
+  extern __shared__ float lds[];   // [4][NS][h]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nv = h / 8;
-  float dgam[LN_MAXV][8], dbet[LN_MAXV][8], gg[LN_MAXV][8];
+  float dgam[LN_MAXV][8], dbet[LN_MAXV][8], gg[LN_MAXV][8], asum[ADDSUM ? LN_MAXV : 1][8];
 #pragma unroll
   for (int i = 0; i < LN_MAXV; ++i) {
     int c = lane + i * 64;
     if (c < nv) unpack8(*(const u32x4*)(g + c * 8), gg[i]);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { dgam[i][e] = 0.f; dbet[i][e] = 0.f; }
+    for (int e = 0; e < 8; ++e) {
+      dgam[i][e] = 0.f;
+      dbet[i][e] = 0.f;
+      if (ADDSUM) asum[i][e] = 0.f;
+    }
   }
   // the next row's vectors are requested before this row is reduced (a wavefront walks 16 rows)
   const int first = blockIdx.x * LNB_ROWS + w * (LNB_ROWS / 4);
@@ -175,6 +183,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
         for (int e = 0; e < 8; ++e) {
           o[e] = rstd * (dyg[i][e] - m1 - xh[i][e] * m2);
           if (add) o[e] += av[e];
+          if (ADDSUM) asum[i][e] += av[e];
         }
         *(u32x4*)(dx + (size_t)row * h + c * 8) = pack8(o);
       }
@@ -187,16 +196,17 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
     if (c < nv)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        lds[(w * 2 + 0) * h + c * 8 + e] = dgam[i][e];
-        lds[(w * 2 + 1) * h + c * 8 + e] = dbet[i][e];
+        lds[(w * NS + 0) * h + c * 8 + e] = dgam[i][e];
+        lds[(w * NS + 1) * h + c * 8 + e] = dbet[i][e];
+        if (ADDSUM) lds[(w * NS + 2) * h + c * 8 + e] = asum[i][e];
       }
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < 2 * h; c += 256) {
+  for (int c = threadIdx.x; c < NS * h; c += 256) {
     int which = c / h, col = c % h;
-    float s = lds[(0 * 2 + which) * h + col] + lds[(1 * 2 + which) * h + col] + lds[(2 * 2 + which) * h + col] +
-              lds[(3 * 2 + which) * h + col];
-    partial[((size_t)blockIdx.x * 2 + which) * h + col] = s;
+    float s = lds[(0 * NS + which) * h + col] + lds[(1 * NS + which) * h + col] + lds[(2 * NS + which) * h + col] +
+              lds[(3 * NS + which) * h + col];
+    partial[((size_t)blockIdx.x * NS + which) * h + col] = s;
   }
 }
 
@@ -206,7 +216,8 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial, int parts, int stride,
                                                              int cols, bf16_t* __restrict__ out_bf16,
                                                              float* __restrict__ out_f32, int split,
-                                                             float* __restrict__ out_f32_b) {
+                                                             float* __restrict__ out_f32_b, int split2 = 1 << 30,
+                                                             float* __restrict__ out_f32_c = nullptr) {
   __shared__ float red[8][32];
   const int cl = threadIdx.x & 31, slice = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cl;
@@ -231,7 +242,8 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restr
     if (out_bf16) out_bf16[c] = f2bf_(t);
     if (out_f32) {
       if (c < split) out_f32[c] = t;
-      else out_f32_b[c - split] = t;
+      else if (c < split2) out_f32_b[c - split] = t;
+      else out_f32_c[c - split2] = t;
     }
   }
 }
@@ -459,21 +471,33 @@ int layernorm_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, bf16_t* y, 
   return ok();
 }
 
-size_t layernorm_bwd_ws_bytes(int rows, int h) { return (size_t)((rows + LNB_ROWS - 1) / LNB_ROWS) * 2 * h * sizeof(float); }
+// room for three vectors per workgroup (dgamma, dbeta and, when asked for, the column sums of add)
+size_t layernorm_bwd_ws_bytes(int rows, int h) { return (size_t)((rows + LNB_ROWS - 1) / LNB_ROWS) * 3 * h * sizeof(float); }
 
+// add_colsum (may be null; needs add): out[c] = sum over rows of add[r][c]
 int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* add, bf16_t* dx,
-                  float* dgamma, float* dbeta, float* partial_ws, int rows, int h, hipStream_t s) {
-  if (h % 8 || h > 64 * 8 * LN_MAXV_LIMIT || rows <= 0) return KARMA_E_INVAL;
+                  float* dgamma, float* dbeta, float* partial_ws, int rows, int h, hipStream_t s, float* add_colsum) {
+  if (h % 8 || h > 64 * 8 * LN_MAXV_LIMIT || rows <= 0 || (add_colsum && !add)) return KARMA_E_INVAL;
   const int parts = (rows + LNB_ROWS - 1) / LNB_ROWS;
   const int per_lane = (h / 8 + 63) / 64;
-  const size_t lds = (size_t)8 * h * sizeof(float);
-#define KARMA_LN_BWD(V)                                                                                          \
+  // rows too wide for three vectors per wavefront in LDS: the plain kernel, then a pass of its own over add
+  if (add_colsum && (size_t)4 * 3 * h * sizeof(float) > 160 * 1024) {
+    int st = layernorm_bwd(dy, x, stats, g, add, dx, dgamma, dbeta, partial_ws, rows, h, s, nullptr);
+    if (st) return st;
+    return colsum_bf16(add, add_colsum, partial_ws, rows, h, s);
+  }
+  const int ns = add_colsum ? 3 : 2;
+  const size_t lds = (size_t)4 * ns * h * sizeof(float);
+#define KARMA_LN_BWD_K(V, AS)                                                                                    \
   do {                                                                                                           \
-    if (lds > 64 * 1024)                                                                                         \
-      (void)hipFuncSetAttribute((const void*)layernorm_bwd_kernel<V>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)lds);                                                                       \
-    hipLaunchKernelGGL(layernorm_bwd_kernel<V>, dim3(parts), dim3(256), lds, s, dy, x, stats, g, add, dx,         \
-                       partial_ws, rows, h);                                                                     \
+    auto kern = layernorm_bwd_kernel<V, AS>;                                                                     \
+    if (lds > 64 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+    hipLaunchKernelGGL(kern, dim3(parts), dim3(256), lds, s, dy, x, stats, g, add, dx, partial_ws, rows, h);      \
+  } while (0)
+#define KARMA_LN_BWD(V)                   \
+  do {                                    \
+    if (add_colsum) KARMA_LN_BWD_K(V, true); \
+    else KARMA_LN_BWD_K(V, false);        \
   } while (0)
   if (per_lane <= 2) KARMA_LN_BWD(2);
   else if (per_lane <= 4) KARMA_LN_BWD(4);
@@ -481,8 +505,9 @@ int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const b
   else if (per_lane <= 9) KARMA_LN_BWD(9);
   else KARMA_LN_BWD(12);
 #undef KARMA_LN_BWD
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((2 * h + 31) / 32), dim3(256), 0, s, partial_ws, parts, 2 * h, 2 * h,
-                     (bf16_t*)nullptr, dgamma, h, dbeta);
+#undef KARMA_LN_BWD_K
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((ns * h + 31) / 32), dim3(256), 0, s, partial_ws, parts, ns * h, ns * h,
+                     (bf16_t*)nullptr, dgamma, h, dbeta, 2 * h, add_colsum);
   return ok();
 }
 
@@ -569,7 +594,16 @@ extern "C" int karma_k_layernorm_bwd_bf16(const void* dy, const void* x, const f
   if (!dy || !x || !stats || !g || !dx || !dgamma || !dbeta || !ws) return KARMA_E_INVAL;
   if (ws_bytes < layernorm_bwd_ws_bytes((int)rows, (int)h)) return KARMA_E_OOM;
   return layernorm_bwd((const bf16_t*)dy, (const bf16_t*)x, stats, (const bf16_t*)g, (const bf16_t*)add, (bf16_t*)dx,
-                       dgamma, dbeta, ws, (int)rows, (int)h, (hipStream_t)stream);
+                       dgamma, dbeta, ws, (int)rows, (int)h, (hipStream_t)stream, nullptr);
+}
+extern "C" int karma_k_layernorm_bwd_addsum_bf16(const void* dy, const void* x, const float* stats, const void* g,
+                                                 const void* add, void* dx, float* dgamma, float* dbeta,
+                                                 float* add_colsum, float* ws, uint64_t ws_bytes, uint32_t rows, uint32_t h,
+                                                 void* stream) {
+  if (!dy || !x || !stats || !g || !add || !dx || !dgamma || !dbeta || !add_colsum || !ws) return KARMA_E_INVAL;
+  if (ws_bytes < layernorm_bwd_ws_bytes((int)rows, (int)h)) return KARMA_E_OOM;
+  return layernorm_bwd((const bf16_t*)dy, (const bf16_t*)x, stats, (const bf16_t*)g, (const bf16_t*)add, (bf16_t*)dx,
+                       dgamma, dbeta, ws, (int)rows, (int)h, (hipStream_t)stream, add_colsum);
 }
 extern "C" int karma_k_colsum_bf16(const void* x, float* out, float* ws, uint64_t ws_bytes, uint32_t rows, uint32_t cols,
                                    void* stream) {

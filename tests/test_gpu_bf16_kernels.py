@@ -194,7 +194,7 @@ def test_layernorm(g, rows, h):
     assert g.rel_l2(stats[:, 1].cpu().numpy(), cache[1].reshape(-1)) <= TOL_F32
     dx = torch.empty_like(y)
     dg = torch.empty(h, device="cuda"); db = torch.empty(h, device="cuda")
-    nws = ((rows + 63) // 64) * 2 * h
+    nws = ((rows + 63) // 64) * 3 * h
     ws = torch.empty(nws, device="cuda")
     for use_add in (False, True):
         g.call(lib.karma_k_layernorm_bwd_bf16, g.ptr(dyd), g.ptr(xd), g.ptr(stats), g.ptr(gd), g.ptr(addd) if use_add else None,
@@ -205,6 +205,16 @@ def test_layernorm(g, rows, h):
         assert g.rel_l2(back(dx), dxo) <= TOL_BF16
         assert g.rel_l2(dg.cpu().numpy(), dgo) <= TOL_F32 * 10
         assert g.rel_l2(db.cpu().numpy(), dbo) <= TOL_F32
+    # the variant that also sums the added tensor's columns (a bias gradient) in the same pass
+    dx2 = torch.empty_like(y)
+    dg2 = torch.empty(h, device="cuda"); db2 = torch.empty(h, device="cuda"); asum = torch.empty(h, device="cuda")
+    g.call(lib.karma_k_layernorm_bwd_addsum_bf16, g.ptr(dyd), g.ptr(xd), g.ptr(stats), g.ptr(gd), g.ptr(addd), g.ptr(dx2),
+           g.ptr(dg2), g.ptr(db2), g.ptr(asum), g.ptr(ws), C.c_uint64(nws * 4), rows, h, g.stream_ptr())
+    assert torch.equal(dx2, dx) and torch.equal(dg2, dg) and torch.equal(db2, db)
+    assert g.rel_l2(asum.cpu().numpy(), add.sum(0)) <= TOL_F32
+    assert lib.karma_k_layernorm_bwd_addsum_bf16(g.ptr(dyd), g.ptr(xd), g.ptr(stats), g.ptr(gd), None, g.ptr(dx2), g.ptr(dg2),
+                                                 g.ptr(db2), g.ptr(asum), g.ptr(ws), C.c_uint64(nws * 4), rows, h,
+                                                 g.stream_ptr()) == K.E_INVAL
     assert lib.karma_k_layernorm_bwd_bf16(g.ptr(dyd), g.ptr(xd), g.ptr(stats), g.ptr(gd), None, g.ptr(dx), g.ptr(dg),
                                           g.ptr(db), g.ptr(ws), C.c_uint64(8), rows, h, g.stream_ptr()) == K.E_OOM
 

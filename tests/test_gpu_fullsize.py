@@ -153,7 +153,7 @@ def test_rowwise_kernels_full_size_sampled_rows(g):
     y = torch.empty_like(x); dx = torch.empty_like(x)
     stats = torch.empty(T, 2, device="cuda")
     dg = torch.empty(H, device="cuda"); db = torch.empty(H, device="cuda")
-    nws = (T // 64) * 2 * H
+    nws = (T // 64) * 3 * H
     ws = torch.empty(nws, device="cuda")
     g.call(lib.karma_k_layernorm_fwd_bf16, g.ptr(x), g.ptr(gam), g.ptr(bet), g.ptr(y), g.ptr(stats), T, H, g.stream_ptr())
     g.call(lib.karma_k_layernorm_bwd_bf16, g.ptr(dy), g.ptr(x), g.ptr(stats), g.ptr(gam), None, g.ptr(dx), g.ptr(dg),
