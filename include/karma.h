@@ -366,6 +366,14 @@ int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const v
 int karma_k_gemm_gelu_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev, void* aux_dev,
                            uint32_t m, uint32_t n, uint32_t k, uint32_t flags, uint32_t mode, void* stream);
 
+/* KARMA_GEMM_GELU_BWD (b_dev strided) together with the column sums of its result, colsum_out_dev[j] = sum over i
+ * of c[i][j], fp32 [n]: the gradient of the bias of the layer whose pre-activation aux_dev holds.  Whole 256-tiles
+ * take the sums in the kernel's output stage (from the fp32 values, before they are rounded to bf16); other shapes
+ * run the product and then sum the stored bf16 result.  ws_dev: ceil(m/64)*n floats (KARMA_E_OOM if smaller). */
+int karma_k_gemm_gelu_bwd_colsum_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* aux_dev,
+                                      float* colsum_out_dev, float* ws_dev, uint64_t ws_bytes, uint32_t m, uint32_t n,
+                                      uint32_t k, void* stream);
+
 /* LayerNorm over the last dimension (eps 1e-5, biased variance), bf16 in/out, fp32
  * statistics: stats_dev[2*row] = mean, [2*row+1] = 1/std.  h multiple of 8, <= 6144. */
 int karma_k_layernorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const void* beta_dev, void* y_dev,

@@ -26,11 +26,19 @@ struct GemmEpilogue {
   int out_f32;             // store fp32 instead of bf16
   int accumulate;          // fp32 output only: C += result
   bf16_t* aux;             // [M][ldc]: octet<1> writes GELU(C) there, octet<2> multiplies the result by GELU'(aux) (bf16 C only)
+  float* colsum;           // direct-load kernel, octet<2> only, or null: [tiles_m * 2][N] partial column sums of the result
   // eight consecutive columns n..n+7 of row m (n multiple of 8); cols = how many are inside the matrix
   // pre (when have_pre): the eight residual (or, ACT 2, pre-activation) values of this octet, fetched by the caller
   template <int ACT = 0>
   __device__ __forceinline__ void octet(int m, int n, int cols, const float4& lo, const float4& hi,
                                         bool have_pre = false, u32x4 pre = u32x4{0, 0, 0, 0}) const {
+    float unused[8];
+    octet<ACT>(m, n, cols, lo, hi, have_pre, pre, false, unused);
+  }
+  // do_sum (octet<2>, full octets): the eight results are also added to sum8
+  template <int ACT>
+  __device__ __forceinline__ void octet(int m, int n, int cols, const float4& lo, const float4& hi, bool have_pre, u32x4 pre,
+                                        bool do_sum, float (&sum8)[8]) const {
     float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     const size_t at = (size_t)m * ldc + n;
     if (cols == 8 && (ldc & 7) == 0) {
@@ -61,6 +69,10 @@ struct GemmEpilogue {
           for (int e = 0; e < 4; ++e) {
             v[2 * e] *= gelu_grad_f(__uint_as_float(r[e] << 16));
             v[2 * e + 1] *= gelu_grad_f(__uint_as_float(r[e] & 0xffff0000u));
+          }
+          if (do_sum) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum8[e] += v[e];
           }
         }
         u32x4 o;
@@ -526,6 +538,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
     u32x4 pre[PASSES];
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) pre[pass] = fetch_in ? fetch(0, pass) : u32x4{0, 0, 0, 0};
+    // column sums of this wavefront's part of the tile (the bias gradient of the layer whose input gradient
+    // this product is): every octet of a lane lies in the same eight columns
+    const bool col_sums = ACT == 2 && ep.colsum != nullptr && splits == 1;
+    float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -547,8 +563,22 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
         } else {
           const u32x4 cur = pre[pass];
           if (fetch_in && i + 1 < TM) pre[pass] = fetch(i + 1, pass);
-          ep.template octet<ACT>(m, n, 8, v, u, fetch_in, cur);
+          ep.template octet<ACT>(m, n, 8, v, u, fetch_in, cur, col_sums, cs);
         }
+      }
+    }
+    if (col_sums) {
+      // lanes that share a column octet differ in lane bits 2, 4 and 5 (the row they take in a pass)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        cs[e] += __shfl_xor(cs[e], 4, 64);
+        cs[e] += __shfl_xor(cs[e], 16, 64);
+        cs[e] += __shfl_xor(cs[e], 32, 64);
+      }
+      if (rr == 0) {
+        float* dst = ep.colsum + ((size_t)(m0 / BM) * WGM + wm) * N + n;
+        *(float4*)dst = make_float4(cs[0], cs[1], cs[2], cs[3]);
+        *(float4*)(dst + 4) = make_float4(cs[4], cs[5], cs[6], cs[7]);
       }
     }
     if (!have_next) break;
@@ -680,7 +710,7 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   k_per_split = (k_per_split + BK - 1) / BK * BK;
   splits = (g.K + k_per_split - 1) / k_per_split;
   const size_t lds = (size_t)2 * (BM + BN) * (BK + LDS_PAD) * sizeof(bf16_t);
-  GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate, (bf16_t*)g.aux};
+  GemmEpilogue ep{g.C, g.bias, g.residual, g.ldc, g.out_f32, g.accumulate, (bf16_t*)g.aux, nullptr};
   // a multiple of 8 workgroups: the kernel deals work items out per XCD
   dim3 grid(std::min((tiles * splits + 7) / 8 * 8, std::max(8, cus / 8 * 8))), block(WGM * WGN * 64);
 #define KARMA_GEMM_LAUNCH(AK, BKC, CV, ACT)                                                                 \
@@ -699,6 +729,10 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
              (uint64_t)g.lda * 2 * 256 < (1ull << 31) && (uint64_t)g.ldb * 2 * 256 < (1ull << 31);
   }
   if (direct) {
+    if (g.act == 2 && g.colsum_partial && splits == 1 && g.ldc == g.N) {
+      ep.colsum = g.colsum_partial;
+      if (g.colsum_rows) *g.colsum_rows = tiles_m * WGM;
+    }
     launch_direct<BM, BN, BK, WGM, WGN>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
   } else if (CONVS) {   // the convolution variants exist for one tile shape only
     if (g.conv_mode == 1) KARMA_GEMM_LAUNCH(true, true, (CONVS ? 1 : 0), 0);
@@ -792,6 +826,33 @@ extern "C" int karma_k_gemm_gelu_bf16(const void* a, const void* b, void* c, con
   g.act = (int)mode;
   g.aux = aux;
   return gemm_bf16(g, (hipStream_t)stream);
+}
+
+// The backward product with GELU' and the column sums of its result (fused where the shape allows)
+extern "C" int karma_k_gemm_gelu_bwd_colsum_bf16(const void* a, const void* b, void* c, const void* aux, float* colsum_out,
+                                                 float* ws, uint64_t ws_bytes, uint32_t m, uint32_t n, uint32_t k,
+                                                 void* stream) {
+  if (!a || !b || !c || !aux || !colsum_out || !ws) return KARMA_E_INVAL;
+  if (ws_bytes < colsum_ws_bytes((int)m, (int)n)) return KARMA_E_OOM;
+  GemmArgs g{};
+  g.A = (const bf16_t*)a;
+  g.B = (const bf16_t*)b;
+  g.C = c;
+  g.M = (int)m; g.N = (int)n; g.K = (int)k;
+  g.a_kc = true;
+  g.b_kc = false;
+  g.lda = (int)k;
+  g.ldb = (int)n;
+  g.ldc = (int)n;
+  g.act = 2;
+  g.aux = const_cast<void*>(aux);
+  int rows = 0;
+  g.colsum_partial = ws;
+  g.colsum_rows = &rows;
+  int st = gemm_bf16(g, (hipStream_t)stream);
+  if (st) return st;
+  if (rows) return colsum_finish(ws, rows, (int)n, colsum_out, (hipStream_t)stream);
+  return colsum_bf16((const bf16_t*)c, colsum_out, ws, (int)m, (int)n, (hipStream_t)stream);
 }
 
 extern "C" int karma_k_gemm_bf16(const void* a, const void* b, void* c, const void* bias, const void* residual,

@@ -47,6 +47,11 @@ struct GemmArgs {
   // act 2: C = (A B^T) * GELU'(aux), aux (read) holding the pre-activation.  bf16 C, no residual, no split.
   int act;
   void* aux;
+  // act 2, optional: room for ceil(M / 128) rows of N floats.  When the product runs on the kernel that can do
+  // it, partial column sums of C (fp32, before rounding) are left there and *colsum_rows (preset to 0 by the
+  // caller) is set to their number; colsum_finish adds them up.  Otherwise nothing is written.
+  float* colsum_partial;
+  int* colsum_rows;
 };
 int gemm_bf16(const GemmArgs& g, hipStream_t s);
 // While non-null on the calling thread, gemm_bf16 calls record an event before and after
@@ -73,6 +78,8 @@ int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const b
                   float* add_colsum = nullptr);
 size_t colsum_ws_bytes(int rows, int cols);
 int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int cols, hipStream_t s);
+// out[c] = sum over p < parts of partial[p][c] (rows of cols floats), in a fixed order
+int colsum_finish(const float* partial, int parts, int cols, float* out, hipStream_t s);
 int gelu_fwd(const bf16_t* x, bf16_t* y, size_t n, hipStream_t s);
 int gelu_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, size_t n, hipStream_t s);
 int embed_fwd(const int* ids, const bf16_t* wte, const bf16_t* wpe, bf16_t* out, int tokens, int seq, int h, hipStream_t s);

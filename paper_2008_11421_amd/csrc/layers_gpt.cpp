@@ -143,7 +143,7 @@ int gemm(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, const bf
 // the product with the feed-forward GELU folded into its output stage (mode 1: aux = GELU(C) written;
 // mode 2: C = (A B^T) * GELU'(aux))
 int gemm_gelu(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, bf16_t* aux, int M, int N, int K, bool a_kc,
-              bool b_kc, int mode, hipStream_t s) {
+              bool b_kc, int mode, hipStream_t s, float* colsum_partial = nullptr, int* colsum_rows = nullptr) {
   GemmArgs g{};
   g.A = A; g.B = B; g.C = C; g.bias = bias;
   g.M = M; g.N = N; g.K = K;
@@ -153,6 +153,8 @@ int gemm_gelu(const bf16_t* A, const bf16_t* B, void* C, const bf16_t* bias, bf1
   g.ldc = N;
   g.act = mode;
   g.aux = aux;
+  g.colsum_partial = colsum_partial;
+  g.colsum_rows = colsum_rows;
   return gemm_bf16(g, s);
 }
 
@@ -293,11 +295,14 @@ int ffn_half_fwd(const Dims& d, const bf16_t* r1, const FfnBufs& b, bf16_t* out,
 template <class WF, class GF>
 int ffn_half_bwd(const Dims& d, const bf16_t* dy, const bf16_t* r1, const FfnBufs& b, const BwdBufs& w, bf16_t* dr1, WF W,
                  GF G, hipStream_t s) {
-  TRY(gemm_gelu(dy, W(W2), w.wide, nullptr, b.f1, d.T, d.ffn, d.h, true, false, 2, s));         // df1 = (dy W2) * GELU'(f1)
+  // df1 = (dy W2) * GELU'(f1); where the kernel can, it leaves partial column sums of df1 (FC1's bias gradient)
+  int sum_rows = 0;
+  TRY(gemm_gelu(dy, W(W2), w.wide, nullptr, b.f1, d.T, d.ffn, d.h, true, false, 2, s, w.part, &sum_rows));
+  if (sum_rows) TRY(colsum_finish(w.part, sum_rows, d.ffn, (float*)G(B1), s));
   TRY(gemm(dy, b.g, G(W2), nullptr, nullptr, d.h, d.ffn, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));        // dW2 = dy^T g
   TRY(gemm(w.wide, W(W1), w.t1, nullptr, nullptr, d.T, d.h, d.ffn, true, false, false, false, s));      // dm = df1 W1
   TRY(gemm(w.wide, b.m, G(W1), nullptr, nullptr, d.ffn, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));    // dW1 = df1^T m
-  TRY(colsum_bf16(w.wide, (float*)G(B1), w.part, d.T, d.ffn, s));
+  if (!sum_rows) TRY(colsum_bf16(w.wide, (float*)G(B1), w.part, d.T, d.ffn, s));
   // dr1 = LN2'(dm) + dy; the same pass sums dy's columns: the gradient of FC2's bias
   TRY(layernorm_bwd(w.t1, r1, b.stats2, W(LN2_G), dy, dr1, (float*)G(LN2_G), (float*)G(LN2_B), w.part, d.T, d.h, s,
                     (float*)G(B2)));

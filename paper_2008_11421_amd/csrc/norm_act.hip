@@ -522,6 +522,13 @@ int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int co
   return ok();
 }
 
+int colsum_finish(const float* partial, int parts, int cols, float* out, hipStream_t s) {
+  if (parts <= 0 || cols <= 0) return KARMA_E_INVAL;
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, partial, parts, cols, cols,
+                     (bf16_t*)nullptr, out, cols, (float*)nullptr);
+  return ok();
+}
+
 int gelu_fwd(const bf16_t* x, bf16_t* y, size_t n, hipStream_t s) {
   if (n % 8) return KARMA_E_INVAL;
   hipLaunchKernelGGL(gelu_fwd_kernel, dim3(blocks_for(n / 8, 256)), dim3(256), 0, s, x, y, n / 8);

@@ -176,6 +176,35 @@ def test_gemm_rejects_bad_shapes(g):
 TOL_ATTN = 1e-2   # three chained bf16 roundings (probabilities, dS, result), each <= 2^-9
 
 
+@pytest.mark.parametrize("m,n,k", [(512, 512, 256), (768, 256, 128), (200, 136, 72)])
+def test_gemm_gelu_backward_with_column_sums(g, m, n, k):
+    """dX = (dY W) * GELU'(pre) with the column sums of dX (the bias gradient of the layer before the GELU) taken
+    in the same launch where the shape is made of whole tiles, by a pass over the result otherwise."""
+    import torch
+    a, ad = bf(si.normal(46, (m, k), 0.5))
+    w, wd = bf(si.normal(47, (n, k), 0.1))
+    x, xd = bf(si.normal(48, (m, n), 2.0))
+    wt = wd.t().contiguous()
+    dx = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    sums = torch.empty(n, device="cuda")
+    nws = ((m + 63) // 64) * n
+    ws = torch.empty(nws, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_gemm_gelu_bwd_colsum_bf16, g.ptr(ad), g.ptr(wt), g.ptr(dx), g.ptr(xd), g.ptr(sums), g.ptr(ws),
+           C.c_uint64(nws * 4), m, n, k, g.stream_ptr())
+    ref = nn.gelu_bwd(x, a @ w.T)
+    assert g.rel_l2(back(dx), ref) <= TOL_BF16
+    # a sum of m values each carrying up to one bf16 rounding (only when the result was stored before summing)
+    assert g.rel_l2(sums.cpu().numpy(), ref.sum(0)) <= TOL_BF16
+    # the same bits as the plain entry point gives for dX
+    dx2 = torch.empty_like(dx)
+    g.call(lib.karma_k_gemm_gelu_bf16, g.ptr(ad), g.ptr(wt), g.ptr(dx2), None, g.ptr(xd), m, n, k, K.GEMM_B_STRIDED,
+           K.GEMM_GELU_BWD, g.stream_ptr())
+    assert torch.equal(dx, dx2)
+    assert lib.karma_k_gemm_gelu_bwd_colsum_bf16(g.ptr(ad), g.ptr(wt), g.ptr(dx), g.ptr(xd), g.ptr(sums), g.ptr(ws),
+                                                 C.c_uint64(16), m, n, k, g.stream_ptr()) == K.E_OOM
+
+
 @pytest.mark.parametrize("rows,h", [(64, 1024), (37, 256), (5, 3072), (130, 4256), (3, 8)])
 def test_layernorm(g, rows, h):
     import torch
