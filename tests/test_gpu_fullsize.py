@@ -89,6 +89,20 @@ def test_gemm_with_gelu_full_size_sampled_entries(g):
     W2 = w2[:, ns].t().float().cpu().numpy().astype(np.float64)
     ref_dx = nn.gelu_bwd(got_pre, A @ W2.T)
     assert g.rel_l2(dx[ms][:, ns].float().cpu().numpy(), ref_dx) <= TOL_BF16
+    # the same launch leaving the column sums of dx (FC1's bias gradient): three columns summed over all rows
+    dx3 = torch.empty_like(dx)
+    sums = torch.empty(n, device="cuda")
+    nws = (m // 64) * n
+    ws = torch.empty(nws, device="cuda")
+    g.call(K.lib().karma_k_gemm_gelu_bwd_colsum_bf16, g.ptr(a), g.ptr(w2), g.ptr(dx3), g.ptr(pre), g.ptr(sums), g.ptr(ws),
+           C.c_uint64(nws * 4), m, n, k, g.stream_ptr())
+    assert torch.equal(dx3, dx)
+    cols = [0, 1777, n - 1]
+    a_all = a.float().cpu().numpy().astype(np.float64)
+    pre_c = pre[:, cols].float().cpu().numpy().astype(np.float64)
+    w2_c = w2[:, cols].float().cpu().numpy().astype(np.float64)
+    ref_sum = nn.gelu_bwd(pre_c, a_all @ w2_c).sum(0)
+    assert g.rel_l2(sums[cols].cpu().numpy(), ref_sum) <= TOL_BF16
 
 
 def test_attention_full_size_sampled_heads(g):
@@ -170,6 +184,16 @@ def test_rowwise_kernels_full_size_sampled_rows(g):
     xhat = (xc - st[:, :1]) * st[:, 1:]
     assert g.rel_l2(dg[cols].cpu().numpy(), (dyc * xhat).sum(0)) <= 1e-3
     assert g.rel_l2(db[cols].cpu().numpy(), dyc.sum(0)) <= TOL_F32
+    # the variant the transformer block launches: the residual branch's gradient is added to dx and its column
+    # sums (a bias gradient) come out of the same pass
+    add = dev_normal(125, (T, H))
+    dx2 = torch.empty_like(x)
+    dg2 = torch.empty(H, device="cuda"); db2 = torch.empty(H, device="cuda"); asum = torch.empty(H, device="cuda")
+    g.call(lib.karma_k_layernorm_bwd_addsum_bf16, g.ptr(dy), g.ptr(x), g.ptr(stats), g.ptr(gam), g.ptr(add), g.ptr(dx2),
+           g.ptr(dg2), g.ptr(db2), g.ptr(asum), g.ptr(ws), C.c_uint64(nws * 4), T, H, g.stream_ptr())
+    assert g.rel_l2(rows_of(dx2, rows), dxo + rows_of(add, rows)) <= TOL_BF16
+    assert torch.equal(dg2, dg) and torch.equal(db2, db)
+    assert g.rel_l2(asum[cols].cpu().numpy(), add[:, cols].float().cpu().numpy().astype(np.float64).sum(0)) <= TOL_F32
     # GELU on the FFN activation
     f = dev_normal(131, (T, FFN), 1.5)
     gy = torch.empty_like(f)
