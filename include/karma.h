@@ -366,6 +366,15 @@ int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const v
 int karma_k_gemm_gelu_bf16(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev, void* aux_dev,
                            uint32_t m, uint32_t n, uint32_t k, uint32_t flags, uint32_t mode, void* stream);
 
+/* karma_k_attention_bwd_bf16 together with the column sums of dqkv over all batch * seq tokens, colsum_out_dev fp32
+ * [3 * heads * d]: the gradient of the QKV projection's bias.  Head dimension 64 takes them inside the kernels (one
+ * row of partial sums per 32 tokens, from the fp32 values), other head dimensions by a pass over dqkv.
+ * ws_dev: batch * seq / 32 * 3 * heads * d floats (KARMA_E_OOM if smaller). */
+int karma_k_attention_bwd_colsum_bf16(const void* qkv_dev, const void* ctx_dev, const void* dctx_dev, const float* lse_dev,
+                                      float* delta_ws_dev, void* dqkv_dev, float* colsum_out_dev, float* ws_dev,
+                                      uint64_t ws_bytes, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d,
+                                      void* stream);
+
 /* KARMA_GEMM_GELU_BWD (b_dev strided) together with the column sums of its result, colsum_out_dev[j] = sum over i
  * of c[i][j], fp32 [n]: the gradient of the bias of the layer whose pre-activation aux_dev holds.  Whole 256-tiles
  * take the sums in the kernel's output stage (from the fp32 values, before they are rounded to bf16); other shapes

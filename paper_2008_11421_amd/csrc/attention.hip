@@ -16,6 +16,7 @@
 // Reductions over tiles run in a fixed order; there are no atomics (dQ has its own pass).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "karma.h"
@@ -576,7 +577,8 @@ __global__ __launch_bounds__(256, (DP == 64 ? 2 : 1)) void attn_bwd_dq_kernel(
 template <int KT>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
                                                                  const bf16_t* __restrict__ dout, const float* __restrict__ lse,
-                                                                 float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H) {
+                                                                 float* __restrict__ delta, bf16_t* __restrict__ dqkv, int S, int H,
+                                                                 float* __restrict__ colsum) {
   constexpr int D = 64, NMT = KT / 32, TILE = KT * D * 2, STAGE = 2 * TILE;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
@@ -685,6 +687,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
       v.y = pack2(dq[i][rg * 4 + 2], dq[i][rg * 4 + 3]);
       *(u32x2*)(out + i * 32 + rg * 8 + g * 4) = v;
     }
+  // Column sums of dQ over this wavefront's 32 queries (the gradient of the QKV bias, first third): the
+  // queries lie on the lanes of each half-wavefront, so five exchanges per register; one row of partial sums
+  // per wavefront, [batch * S / 32][3 h], added up afterwards in a fixed order.
+  if (colsum) {
+    float* dst = colsum + ((size_t)b * (S / 32) + qbase / 32) * ld + (size_t)head * D;
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        float t[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          t[e] = dq[i][rg * 4 + e];
+#pragma unroll
+          for (int sh = 1; sh < 32; sh <<= 1) t[e] += __shfl_xor(t[e], sh, 64);
+        }
+        if (lrow == 0) *(float4*)(dst + i * 32 + rg * 8 + g * 4) = make_float4(t[0], t[1], t[2], t[3]);
+      }
+  }
 }
 
 // ------------------------------------------------------------------ backward: dK, dV
@@ -832,7 +853,8 @@ __global__ __launch_bounds__(256, (DP == 64 ? 2 : 1)) void attn_bwd_dkv_kernel(
 template <int QT>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                  bf16_t* __restrict__ dqkv, int S, int H) {
+                                                                  bf16_t* __restrict__ dqkv, int S, int H,
+                                                                  float* __restrict__ colsum) {
   constexpr int D = 64, TILE = QT * D * 2, STAGE = 2 * TILE;   // stage = Q tile | dO tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
   const unsigned lds0 = (unsigned)(uintptr_t)((KARMA_LDS(unsigned char)*)smem_attn);
@@ -959,6 +981,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_dl_kernel(const bf16_t* _
       row[h] = f2bf(dk[i][r]);
       row[2 * h] = f2bf(dv[i][r]);
     }
+  // Column sums of dK and dV over this wavefront's 32 keys (second and third third of the QKV bias gradient):
+  // a lane holds 16 keys of one column in its registers, the other half-wavefront the other 16.
+  if (colsum) {
+    float* dst = colsum + ((size_t)b * (S / 32) + kbase / 32) * ld + (size_t)head * D;
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+      float sk = 0.f, sv = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sk += dk[i][r]; sv += dv[i][r]; }
+      sk += __shfl_xor(sk, 32, 64);
+      sv += __shfl_xor(sv, 32, 64);
+      if (g == 0) {
+        dst[h + i * 32 + lrow] = sk;
+        dst[2 * h + i * 32 + lrow] = sv;
+      }
+    }
+  }
 }
 
 template <int D>
@@ -990,7 +1029,7 @@ int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq
 
 template <int D, int DP = D>
 static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse,
-                       float* delta, bf16_t* dqkv, int seq, int heads) {
+                       float* delta, bf16_t* dqkv, int seq, int heads, float* colsum = nullptr) {
   if constexpr (D == 64) {
     constexpr int KT = ATTN_DQ_KT, QT = ATTN_DKV_QT;
     constexpr int l1 = 2 * 2 * KT * 64 * 2;                      // two stages of (K tile, V tile)
@@ -999,8 +1038,8 @@ static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t
     auto kkv = attn_bwd_dkv_dl_kernel<QT>;
     (void)hipFuncSetAttribute((const void*)kq, hipFuncAttributeMaxDynamicSharedMemorySize, l1);
     (void)hipFuncSetAttribute((const void*)kkv, hipFuncAttributeMaxDynamicSharedMemorySize, l2);
-    hipLaunchKernelGGL(kq, grid, dim3(256), l1, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
-    hipLaunchKernelGGL(kkv, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads);
+    hipLaunchKernelGGL(kq, grid, dim3(256), l1, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads, colsum);
+    hipLaunchKernelGGL(kkv, grid, dim3(256), l2, s, qkv, dctx, lse, delta, dqkv, seq, heads, colsum);
   } else {
     constexpr size_t l1 = attn_dq_lds<DP>(), l2 = attn_dkv_lds<DP>();
     auto kq = attn_bwd_dq_kernel<D, DP>;
@@ -1012,14 +1051,24 @@ static void launch_bwd(dim3 grid, hipStream_t s, const bf16_t* qkv, const bf16_t
   }
 }
 
+size_t attention_bwd_colsum_bytes(int batch, int seq, int heads, int d) {
+  return (size_t)batch * (seq / 32) * 3 * heads * d * sizeof(float);
+}
+
+// colsum_partial (may be null) with room for attention_bwd_colsum_bytes: where the kernels can (head dimension
+// 64) they leave one row of column sums of dqkv per 32 tokens there and *colsum_rows is set to the number of
+// rows (colsum_finish adds them up: the gradient of the QKV bias); otherwise *colsum_rows stays 0.
 int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,
-                  bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s) {
+                  bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s, float* colsum_partial,
+                  int* colsum_rows) {
   if (seq % 128 || (d != 64 && d != 128 && d != 152) || batch <= 0 || heads <= 0) return KARMA_E_INVAL;
+  if (colsum_rows) *colsum_rows = 0;
   dim3 grid(seq / 128, heads, batch);
   const size_t total = (size_t)batch * seq * heads;
   const unsigned blocks = (unsigned)((total + 255) / 256);
   if (d == 64) {   // the dQ pass computes delta itself
-    launch_bwd<64>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
+    launch_bwd<64>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads, colsum_rows ? colsum_partial : nullptr);
+    if (colsum_partial && colsum_rows) *colsum_rows = batch * (seq / 32);
   } else if (d == 128) {
     hipLaunchKernelGGL(attn_delta_kernel<128>, dim3(blocks), dim3(256), 0, s, ctx, dctx, delta, seq, heads, total);
     launch_bwd<128>(grid, s, qkv, ctx, dctx, lse, delta, dqkv, seq, heads);
@@ -1046,5 +1095,22 @@ extern "C" int karma_k_attention_bwd_bf16(const void* qkv, const void* ctx, cons
                                           uint32_t d, void* stream) {
   if (!qkv || !ctx || !dctx || !lse || !delta_ws || !dqkv) return KARMA_E_INVAL;
   return attention_bwd((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta_ws, (bf16_t*)dqkv,
-                       (int)batch, (int)seq, (int)heads, (int)d, (hipStream_t)stream);
+                       (int)batch, (int)seq, (int)heads, (int)d, (hipStream_t)stream, nullptr, nullptr);
+}
+
+// The same with the column sums of dqkv (the QKV bias gradient), from the kernels where they can, else by a pass
+// over dqkv.  ws: max(batch * seq / 32, ceil(batch * seq / 64)) * 3 * heads * d floats.
+extern "C" int karma_k_attention_bwd_colsum_bf16(const void* qkv, const void* ctx, const void* dctx, const float* lse,
+                                                 float* delta_ws, void* dqkv, float* colsum_out, float* ws, uint64_t ws_bytes,
+                                                 uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d, void* stream) {
+  if (!qkv || !ctx || !dctx || !lse || !delta_ws || !dqkv || !colsum_out || !ws) return KARMA_E_INVAL;
+  const int rows = (int)(batch * seq), cols = (int)(3 * heads * d);
+  if (ws_bytes < std::max(attention_bwd_colsum_bytes((int)batch, (int)seq, (int)heads, (int)d), colsum_ws_bytes(rows, cols)))
+    return KARMA_E_OOM;
+  int parts = 0;
+  int st = attention_bwd((const bf16_t*)qkv, (const bf16_t*)ctx, (const bf16_t*)dctx, lse, delta_ws, (bf16_t*)dqkv,
+                         (int)batch, (int)seq, (int)heads, (int)d, (hipStream_t)stream, ws, &parts);
+  if (st) return st;
+  if (parts) return colsum_finish(ws, parts, cols, colsum_out, (hipStream_t)stream);
+  return colsum_bf16((const bf16_t*)dqkv, colsum_out, ws, rows, cols, (hipStream_t)stream);
 }

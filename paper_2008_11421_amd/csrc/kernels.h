@@ -122,6 +122,8 @@ int avgpool_bwd(const bf16_t* dy, bf16_t* dx, int n, int hw, int c, hipStream_t 
 // ---- fused causal attention (attention.hip); seq multiple of 128, d in {64, 128}
 int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq, int heads, int d, hipStream_t s);
 int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,
-                  bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s);
+                  bf16_t* dqkv, int batch, int seq, int heads, int d, hipStream_t s, float* colsum_partial = nullptr,
+                  int* colsum_rows = nullptr);
+size_t attention_bwd_colsum_bytes(int batch, int seq, int heads, int d);
 
 }  // namespace karma

@@ -83,7 +83,8 @@ struct BlockWs {
     t2 = take((uint64_t)d.T * d.h * 2);                           // dr1
     t3 = take((uint64_t)d.T * d.h * 2);                           // da
     delta = take((uint64_t)d.B * d.H * d.S * 4);
-    part = take(std::max(layernorm_bwd_ws_bytes(d.T, d.h), colsum_ws_bytes(d.T, std::max(d.ffn, 3 * d.h))));
+    part = take(std::max({layernorm_bwd_ws_bytes(d.T, d.h), colsum_ws_bytes(d.T, std::max(d.ffn, 3 * d.h)),
+                          attention_bwd_colsum_bytes(d.B, d.S, d.H, d.D)}));
     splitk_bytes = (uint64_t)8 * std::max(d.ffn, 3 * d.h) * d.h * 4;   // partial sums of the weight-gradient GEMMs
     splitk = take(splitk_bytes);
     total = o;
@@ -315,10 +316,13 @@ int attn_half_bwd(const Dims& d, const bf16_t* dr1, const bf16_t* x, const AttnB
                   GF G, hipStream_t s) {
   TRY(gemm(dr1, W(WO), w.t1, nullptr, nullptr, d.T, d.h, d.h, true, false, false, false, s));         // dctx = dr1 Wo
   TRY(gemm(dr1, b.ctx, G(WO), nullptr, nullptr, d.h, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));       // dWo = dr1^T ctx
-  TRY(attention_bwd(b.qkv, b.ctx, w.t1, b.lse, w.delta, w.wide, d.B, d.S, d.H, d.D, s));
+  // where the kernels can they leave partial column sums of dqkv (the QKV bias gradient) in the workspace
+  int sum_rows = 0;
+  TRY(attention_bwd(b.qkv, b.ctx, w.t1, b.lse, w.delta, w.wide, d.B, d.S, d.H, d.D, s, w.part, &sum_rows));
+  if (sum_rows) TRY(colsum_finish(w.part, sum_rows, 3 * d.h, (float*)G(BQKV), s));
   TRY(gemm(w.wide, W(WQKV), w.t3, nullptr, nullptr, d.T, d.h, 3 * d.h, true, false, false, false, s));  // da = dqkv Wqkv
   TRY(gemm(w.wide, b.a, G(WQKV), nullptr, nullptr, 3 * d.h, d.h, d.T, false, false, false, false, s, w.splitk, w.splitk_bytes));  // dWqkv = dqkv^T a
-  TRY(colsum_bf16(w.wide, (float*)G(BQKV), w.part, d.T, 3 * d.h, s));
+  if (!sum_rows) TRY(colsum_bf16(w.wide, (float*)G(BQKV), w.part, d.T, 3 * d.h, s));
   // dx = LN1'(da) + dr1; the same pass sums dr1's columns: the gradient of the output projection's bias
   TRY(layernorm_bwd(w.t3, x, b.stats1, W(LN1_G), dr1, dx, (float*)G(LN1_G), (float*)G(LN1_B), w.part, d.T, d.h, s,
                     (float*)G(BO)));

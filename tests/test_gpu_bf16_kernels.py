@@ -363,6 +363,36 @@ def test_attention(g, B, S, H, D):
     assert torch.equal(dqkv, dqkv2)
 
 
+@pytest.mark.parametrize("B,S,H,D", [(2, 256, 3, 64), (1, 1024, 2, 64), (1, 256, 2, 128)])
+def test_attention_backward_with_qkv_bias_gradient(g, B, S, H, D):
+    """The backward pass also delivering the column sums of dqkv over all tokens (the QKV bias gradient): inside the
+    kernels for head dimension 64, by a pass over dqkv otherwise; dqkv itself is unchanged."""
+    import torch
+    h = H * D
+    qkv, qkvd = bf(si.normal(63, (B, S, 3 * h), 1.5))
+    dctx, dctxd = bf(si.normal(64, (B, S, h)))
+    ctx = torch.empty(B, S, h, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(B, H, S, device="cuda")
+    lib = K.lib()
+    g.call(lib.karma_k_attention_fwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(lse), B, S, H, D, g.stream_ptr())
+    delta = torch.empty(B, H, S, device="cuda")
+    ref = torch.zeros(B, S, 3 * h, dtype=torch.bfloat16, device="cuda")
+    g.call(lib.karma_k_attention_bwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(dctxd), g.ptr(lse), g.ptr(delta), g.ptr(ref),
+           B, S, H, D, g.stream_ptr())
+    dqkv = torch.zeros_like(ref)
+    sums = torch.empty(3 * h, device="cuda")
+    nws = max(B * S // 32, (B * S + 63) // 64) * 3 * h
+    ws = torch.empty(nws, device="cuda")
+    g.call(lib.karma_k_attention_bwd_colsum_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(dctxd), g.ptr(lse), g.ptr(delta), g.ptr(dqkv),
+           g.ptr(sums), g.ptr(ws), C.c_uint64(nws * 4), B, S, H, D, g.stream_ptr())
+    assert torch.equal(dqkv, ref)
+    _, probs = nn.mha_fwd(qkv, H)
+    want = nn.mha_bwd(qkv, H, probs, dctx).reshape(B * S, 3 * h).sum(0)
+    assert g.rel_l2(sums.cpu().numpy(), want) <= TOL_ATTN
+    assert lib.karma_k_attention_bwd_colsum_bf16(g.ptr(qkvd), g.ptr(ctx), g.ptr(dctxd), g.ptr(lse), g.ptr(delta), g.ptr(dqkv),
+                                                 g.ptr(sums), g.ptr(ws), C.c_uint64(64), B, S, H, D, g.stream_ptr()) == K.E_OOM
+
+
 def test_attention_rejects_unsupported(g):
     import torch
     t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda"); f = torch.zeros(1 << 12, device="cuda")
