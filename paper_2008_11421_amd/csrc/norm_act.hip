@@ -248,6 +248,51 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restr
   }
 }
 
+// The same for many partial rows: 8 columns x 32 slices per workgroup, so that a thread walks parts / 32 rows
+// (the walk is a chain of dependent-latency steps; with 8 slices and hundreds of parts it was most of the
+// kernel's time).  Slices are added in ascending order.
+__global__ __launch_bounds__(256) void colsum_finish_tall_kernel(const float* __restrict__ partial, int parts, int stride,
+                                                                  int cols, float* __restrict__ out_f32, int split,
+                                                                  float* __restrict__ out_f32_b, int split2,
+                                                                  float* __restrict__ out_f32_c) {
+  __shared__ float red[32][8];
+  const int cl = threadIdx.x & 7, slice = threadIdx.x >> 3;
+  const int c = blockIdx.x * 8 + cl;
+  float s = 0.f;
+  if (c < cols) {
+    int p = slice;
+    for (; p + 224 < parts; p += 256) {   // eight loads in flight, added in ascending order
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = partial[(size_t)(p + 32 * k) * stride + c];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += v[k];
+    }
+    for (; p < parts; p += 32) s += partial[(size_t)p * stride + c];
+  }
+  red[slice][cl] = s;
+  __syncthreads();
+  if (slice == 0 && c < cols) {
+    float t = red[0][cl];
+#pragma unroll
+    for (int k = 1; k < 32; ++k) t += red[k][cl];
+    if (c < split) out_f32[c] = t;
+    else if (c < split2) out_f32_b[c - split] = t;
+    else out_f32_c[c - split2] = t;
+  }
+}
+
+// fp32 results from `parts` partial rows: the kernel that suits their number
+static void launch_colsum_finish(const float* partial, int parts, int stride, int cols, float* out, int split, float* out_b,
+                                 int split2, float* out_c, hipStream_t s) {
+  if (parts >= 128)
+    hipLaunchKernelGGL(colsum_finish_tall_kernel, dim3((cols + 7) / 8), dim3(256), 0, s, partial, parts, stride, cols, out,
+                       split, out_b, split2, out_c);
+  else
+    hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, partial, parts, stride, cols,
+                       (bf16_t*)nullptr, out, split, out_b, split2, out_c);
+}
+
 // column sums of a bf16 matrix [rows][cols]: each workgroup sums a band of rows
 constexpr int CS_ROWS = 64;
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ x, float* __restrict__ partial,
@@ -506,8 +551,7 @@ int layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const b
   else KARMA_LN_BWD(12);
 #undef KARMA_LN_BWD
 #undef KARMA_LN_BWD_K
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((ns * h + 31) / 32), dim3(256), 0, s, partial_ws, parts, ns * h, ns * h,
-                     (bf16_t*)nullptr, dgamma, h, dbeta, 2 * h, add_colsum);
+  launch_colsum_finish(partial_ws, parts, ns * h, ns * h, dgamma, h, dbeta, 2 * h, add_colsum, s);
   return ok();
 }
 
@@ -517,15 +561,13 @@ int colsum_bf16(const bf16_t* x, float* out, float* partial_ws, int rows, int co
   if (cols % 8 || rows <= 0) return KARMA_E_INVAL;
   const int parts = (rows + CS_ROWS - 1) / CS_ROWS;
   hipLaunchKernelGGL(colsum_partial_kernel, dim3(parts, (cols / 8 + 255) / 256), dim3(256), 0, s, x, partial_ws, rows, cols);
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, partial_ws, parts, cols, cols,
-                     (bf16_t*)nullptr, out, cols, (float*)nullptr);
+  launch_colsum_finish(partial_ws, parts, cols, cols, out, cols, nullptr, 1 << 30, nullptr, s);
   return ok();
 }
 
 int colsum_finish(const float* partial, int parts, int cols, float* out, hipStream_t s) {
   if (parts <= 0 || cols <= 0) return KARMA_E_INVAL;
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((cols + 31) / 32), dim3(256), 0, s, partial, parts, cols, cols,
-                     (bf16_t*)nullptr, out, cols, (float*)nullptr);
+  launch_colsum_finish(partial, parts, cols, cols, out, cols, nullptr, 1 << 30, nullptr, s);
   return ok();
 }
 
