@@ -74,6 +74,20 @@ constexpr int transposer_threads() {
   return patches % 256 == 0 ? 256 : patches < 256 ? patches : patches % 160 == 0 ? 160 : 64;
 }
 
+// Sum over the 32 lanes of each half-wavefront, left in every lane: four data-parallel-primitive steps inside
+// the rows of 16 lanes (swap neighbours, swap pairs, mirror the half row, mirror the row), one exchange across rows.
+__device__ __forceinline__ float half_wave_sum(float v) {
+  auto dpp_add = [](float x, auto ctrl) {
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, false);
+    return x + __int_as_float(y);
+  };
+  v = dpp_add(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1, 0, 3, 2]
+  v = dpp_add(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2, 3, 0, 1]
+  v = dpp_add(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v = dpp_add(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  return v + __shfl_xor(v, 16, 64);
+}
+
 // ------------------------------------------------------------------------------- forward
 // grid (seq/128, heads, batch), 256 threads; wavefront w owns queries q0+32w .. q0+32w+31
 // and walks the keys in tiles of 128 (64 for head dimensions above 128) made of 32-key sub-tiles (those entirely after the
@@ -699,9 +713,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_dl_kernel(const bf16_t* __
         float t[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          t[e] = dq[i][rg * 4 + e];
-#pragma unroll
-          for (int sh = 1; sh < 32; sh <<= 1) t[e] += __shfl_xor(t[e], sh, 64);
+          t[e] = half_wave_sum(dq[i][rg * 4 + e]);
         }
         if (lrow == 0) *(float4*)(dst + i * 32 + rg * 8 + g * 4) = make_float4(t[0], t[1], t[2], t[3]);
       }
