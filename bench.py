@@ -49,8 +49,8 @@ SEED = WORKLOADS[1]["seed"]
 PEAK_BF16_TFLOPS = 2500.0
 # Average HBM-side bytes per GEMM launch of this workload: FETCH_SIZE + WRITE_SIZE of all
 # gemm_bf16_kernel launches, each scaled by the same counter's reading for the 1 GiB copy
-# below (profiles/gpt24_step_kernel_stats_and_hbm_traffic.txt: 350.2 MiB + 141.1 MiB).
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = (350.2 + 141.1) * 1048576
+# below (profiles/gpt24_step_kernel_stats_and_hbm_traffic.txt: 350.1 MiB + 141.3 MiB).
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (350.1 + 141.3) * 1048576
 CPU_SAMPLE_BATCH = 8   # sequences in the oracle's timed sample (about 20 s of host work)
 
 
