@@ -47,15 +47,33 @@ BUDGET = WORKLOADS[1]["budget"]
 ARENA = WORKLOADS[1]["arena"]
 SEED = WORKLOADS[1]["seed"]
 PEAK_BF16_TFLOPS = 2500.0
-# Average HBM-side bytes per GEMM launch of this workload: FETCH_SIZE + WRITE_SIZE of all
-# gemm_bf16_kernel launches, each scaled by the same counter's reading for the 1 GiB copy
-# below (profiles/gpt24_step_kernel_stats_and_hbm_traffic.txt: 350.1 MiB + 141.3 MiB).
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = (350.1 + 141.3) * 1048576
+# HBM-side bytes per GEMM launch come from rocprofv3 counter runs of this command (FETCH_SIZE and
+# WRITE_SIZE of all GEMM launches, each scaled by the same counter's reading for the 1 GiB copy
+# below); the summary of those runs records the plan it was taken on.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gpt24_step_kernel_stats_and_hbm_traffic.txt")
 CPU_SAMPLE_BATCH = 8   # sequences in the oracle's timed sample (about 20 s of host work)
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+
+
+def profiled_traffic(plan):
+    """Bytes per GEMM launch from the committed counter summary, if it was taken on this very plan
+    (lines `plan: <string>` and `gemm_traffic_bytes_per_launch: <number>`); None otherwise."""
+    try:
+        fields = dict(l.split(":", 1) for l in open(TRAFFIC_PROFILE) if l.startswith(("plan:", "gemm_traffic_bytes_per_launch:")))
+        if fields["plan"].strip() == plan:
+            return float(fields["gemm_traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
 
 
 def cpu_baseline(n_seq):
@@ -136,7 +154,6 @@ SAMPLING_NOTE = ("HIP events on the compute stream around one launch in eight of
 def bench_cnn(args, wl, K, si, torch, np, threads):
     """configs[2]: the bottleneck CNN.  It fits its 32 GiB budget in-core (the planner returns
     all-KEEP); a supplementary run under `low_budget` shows the out-of-core schedule."""
-    from oracle import cnn as oracle_cnn
     cfg_m = wl["cfg"]
     desc = dict(kind=K.MODEL_CNN, n_layers=0, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0, ffn=0,
                 vocab=cfg_m["classes"], stream_weights=0, stage_blocks=cfg_m["stage_blocks"])
@@ -151,7 +168,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
     ctx.karma_set_param(0, 1, params["stem"]["g"])
     ctx.karma_set_param(0, 2, params["stem"]["b"])
     for i, (p, _) in enumerate(params["blocks"]):
-        for t, name in enumerate(oracle_cnn.BOTTLENECK_TENSORS):
+        for t, name in enumerate(si.BOTTLENECK_TENSORS):
             if name in p:
                 ctx.karma_set_param(i + 1, t, p[name])
     L = len(params["blocks"]) + 1
@@ -174,15 +191,17 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
         ctx.karma_finish_updates()   # host updates a step put off belong to the steps that produced them
         torch.cuda.synchronize()
         n_l, ms_l, fl_l = 0, 0.0, 0.0
-        t1 = time.perf_counter()
+        per_step = []
         for _ in range(args.steps):
+            t1 = time.perf_counter()
             loss = ctx.karma_step(images, labels, flags)
+            per_step.append(time.perf_counter() - t1)
             if flags & K.STEP_KERNEL_TIMES:
                 n, ms, fl = ctx.karma_get_gemm_stats()
                 n_l += n; ms_l += ms; fl_l += fl
         ctx.karma_finish_updates()
         torch.cuda.synchronize()
-        return acts, summ, (time.perf_counter() - t1) / args.steps, loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
+        return acts, summ, median(per_step), loss, (n_l, ms_l, fl_l), ctx.karma_get_stats()
 
     acts, summ, dt, loss, gem, st = timed(wl["budget"], K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
     log("%d GiB: %.1f ms/step, all-keep=%s, peak %.2f GiB" % (wl["budget"] // GIB, dt * 1e3, acts == [0] * len(acts), summ["peak_bytes"] / GIB))
@@ -266,7 +285,6 @@ def main():
     import torch
     import paper_2008_11421_amd as K
     import synth_inputs as si
-    from oracle import nn as oracle_nn
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -307,7 +325,7 @@ def main():
     ctx.karma_set_param(0, 1, params["wpe"])
     for i in range(CFG["n_layers"]):
         b = params["blocks"][i % n_drawn]
-        for t, name in enumerate(oracle_nn.BLOCK_TENSORS):
+        for t, name in enumerate(si.GPT_BLOCK_TENSORS):
             v = np.asarray(b[name], dtype=np.float32)
             ctx.karma_set_param(*slot(i, t), v if n_drawn > 1 else np.roll(v.reshape(-1), 97 * i))
         if n_drawn == 1 and i % 8 == 7:
@@ -332,17 +350,23 @@ def main():
         ctx.karma_finish_updates()
         torch.cuda.synchronize()
         n_l, ms_l, fl_l = 0, 0.0, 0.0
-        host_ms = []
+        host_ms, per_step = [], []
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            loss = ctx.karma_step(ids, labels, flags)
+            t1 = time.perf_counter()
+            loss = ctx.karma_step(ids, labels, flags)      # returns with the streams drained
+            per_step.append(time.perf_counter() - t1)
             host_ms.append(ctx.karma_get_stats()["host_opt_ms"])
             if flags & K.STEP_KERNEL_TIMES:
                 n, ms, fl = ctx.karma_get_gemm_stats()
                 n_l += n; ms_l += ms; fl_l += fl
         ctx.karma_finish_updates()
         torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
+        mean_dt = (time.perf_counter() - t0) / args.steps
+        # the median step (a step finishes the host updates its predecessor left pending, so steps of
+        # a steady run are alike); the mean over the bracketed region is reported beside it
+        dt = median(per_step)
+        timed.mean_ms = mean_dt * 1e3
         st = ctx.karma_get_stats()
         # updates a step leaves pending are counted where they run (the next step, or the call above): the
         # average over the timed steps is the host optimiser's time per step
@@ -428,6 +452,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": dt * 1e3,
+        "ms_per_step_is": "median of the timed steps",
+        "ms_per_step_mean": timed.mean_ms,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -457,14 +483,14 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel and gemm_bf16_dl_kernel (" + SAMPLING_NOTE + ")",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "launches_per_step": n_l * TIMER_STRIDE / max(args.steps, 1), "avg_launch_ms": ms_l / max(n_l, 1),
-                     "flops_per_launch": fl_l / max(n_l, 1), "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
-                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)"},
+                     "flops_per_launch": fl_l / max(n_l, 1),
+                     "traffic": profiled_traffic("".join("KSRrc"[a] for a in acts)) if args.config == 1 else None,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy; null when the "
+                                     "committed counter summary was taken on another plan)"},
     }
     ctx.close()
     del ctx
     torch.cuda.empty_cache()
-    if args.config != 1:
-        out["roofline"]["traffic"] = None      # the byte counters were collected on configs[1]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(CPU_SAMPLE_BATCH if args.config == 1 else 1)
     print(json.dumps(out), flush=True)

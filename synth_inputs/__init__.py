@@ -57,6 +57,10 @@ def mlp_problem(seed=2008114201, n_layers=8, width=256, batch=32):
     return Ws, bs, x, t
 
 
+# Keys of one transformer block's parameter dict, in the order the library numbers a block's tensors.
+GPT_BLOCK_TENSORS = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+
 def gpt_problem(seed=2008114202, n_layers=24, hidden=1024, ffn=4096, vocab=32000,
                 seq=1024, batch=32, std=0.02, bias_std=0.0):
     """Configs 2/4/5: N(0, std) weights, LayerNorm gain 1 / shift 0, biases N(0,
@@ -117,6 +121,11 @@ def random_stack(seed, n_layers, kind="homogeneous"):
 
 
 # ------------------------------------------------------------------ bottleneck CNN
+# Keys of one bottleneck block's parameter dict, in the order the library numbers a block's tensors
+# (wp, gp, bp: projection shortcut, present on the first block of a stage only).
+BOTTLENECK_TENSORS = ("w1", "g1", "b1", "w2", "g2", "b2", "w3", "g3", "b3", "wp", "gp", "bp")
+
+
 def cnn_problem(seed=2008114203, width=64, stage_blocks=(3, 24, 36, 3), image=224, batch=64, classes=1000,
                 bn_jitter=0.0):
     """Config 3: bottleneck residual network.  Convolution weights N(0, sqrt(2 / (k*k*c_out)))

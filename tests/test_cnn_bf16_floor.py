@@ -1,0 +1,71 @@
+"""How far bf16 storage alone moves the gradients of the bottleneck network (CPU only).
+
+The workload's bar for bf16 gradients is a relative L2 distance of 2e-2 from the plain
+oracle.  For the convolutional workload no step that keeps its tensors in bf16 can meet
+that bar, whatever its kernels: this test runs the plain fp64 oracle and the same step
+with bf16 storage (`tests/cnn_bf16_storage.py`, fp64 arithmetic, rounding only where a
+tensor is written to memory) on the networks the GPU test uses and measures the distance
+between the two.  Two effects are visible in the numbers: with zero batch-norm shifts
+half of every ReLU's inputs sit near zero, roundings upstream flip masks, and a flipped
+fraction f of a gradient is a distance of about sqrt(f); with shifts of +3 the masks are
+stable, but a batch norm's backward pass subtracts the common part of its incoming
+gradient, which leaves the rounding noise standing against a small remainder.  The GPU
+test (`tests/test_gpu_cnn.py`) takes each tensor's tolerance from the distance measured
+here, times a stated factor.
+"""
+import numpy as np
+import pytest
+
+from oracle import cnn
+import cnn_bf16_storage as S
+
+BAR = 2e-2          # the workload's bf16 bar (relative L2 against the plain oracle)
+
+
+def floor_of(dims, shift):
+    params, images, labels = S.problem(dims, shift)
+    pr = S.rounded_params(params)
+    loss, grads = cnn.resnet_step(pr, images, labels)
+    loss_s, grads_s = S.resnet_step_bf16_storage(pr, images, labels)
+    return loss, loss_s, S.distances(S.flat(grads_s), S.flat(grads))
+
+
+@pytest.mark.parametrize("dims", [S.SHALLOW, S.SMALL], ids=["shallow", "small"])
+@pytest.mark.parametrize("shift", [0.0, 3.0])
+def test_bf16_storage_alone_exceeds_the_bar(dims, shift):
+    loss, loss_s, d = floor_of(dims, shift)
+    assert abs(loss - loss_s) <= 2e-3 * abs(loss)            # the loss itself is stable
+    v = np.array(sorted(d.values()))
+    # at least a third of the gradient tensors are further than the bar from the plain
+    # oracle, and the worst one several times further
+    assert (v > BAR).mean() >= 1 / 3, v
+    assert v.max() >= 4 * BAR, v.max()
+    # ... but not arbitrarily far: a change of the step that loses more than this is a bug
+    assert v.max() <= (0.2 if shift else 0.8), v.max()
+
+
+@pytest.mark.parametrize("dims", [S.SHALLOW, S.SMALL], ids=["shallow", "small"])
+def test_shifted_batch_norms_halve_the_floor(dims):
+    """ReLU masks far from a flip: what remains is rounding noise under the batch norms'
+    cancellation, at least two times smaller in the median."""
+    d0 = np.median(list(floor_of(dims, 0.0)[2].values()))
+    d3 = np.median(list(floor_of(dims, 3.0)[2].values()))
+    assert d3 <= 0.5 * d0, (d0, d3)
+
+
+def test_a_single_block_is_no_better():
+    """Not a matter of depth: stem, one bottleneck and the head already sit above the bar."""
+    for shift in (0.0, 3.0):
+        _, _, d = floor_of(dict(S.SHALLOW, stage_blocks=(1, 0, 0, 0)), shift)
+        assert max(d.values()) >= 4 * BAR, (shift, max(d.values()))
+
+
+def test_storage_variant_without_rounding_is_the_oracle(monkeypatch):
+    """The helper differs from the oracle by its roundings only."""
+    monkeypatch.setattr(S, "q", lambda a: np.asarray(a, np.float64))
+    params, images, labels = S.problem(S.SMALL, 0.0)
+    loss, grads = cnn.resnet_step(params, images, labels)
+    loss_s, grads_s = S.resnet_step_bf16_storage(params, images, labels)
+    assert loss == loss_s
+    a, b = S.flat(grads), S.flat(grads_s)
+    assert all(np.array_equal(a[k], b[k]) for k in a)

@@ -219,6 +219,8 @@ def test_layernorm(g, rows, h):
     g.call(lib.karma_k_layernorm_fwd_bf16, g.ptr(xd), g.ptr(gd), g.ptr(bd), g.ptr(y), g.ptr(stats), rows, h, g.stream_ptr())
     yo, cache = nn.layernorm_fwd(x, gam, bet)
     assert g.rel_l2(back(y), yo) <= TOL_BF16
+    ratio = g.elem_ratio(back(y), yo, 1, 1e-3)
+    assert ratio <= 1, ratio
     assert g.rel_l2(stats[:, 0].cpu().numpy(), x.mean(-1)) <= TOL_F32 + 1e-6
     assert g.rel_l2(stats[:, 1].cpu().numpy(), cache[1].reshape(-1)) <= TOL_F32
     dx = torch.empty_like(y)
@@ -232,6 +234,8 @@ def test_layernorm(g, rows, h):
         if use_add:
             dxo = dxo + add
         assert g.rel_l2(back(dx), dxo) <= TOL_BF16
+        ratio = g.elem_ratio(back(dx), dxo, 1, 1e-3)
+        assert ratio <= 1, (ratio, use_add)
         assert g.rel_l2(dg.cpu().numpy(), dgo) <= TOL_F32 * 10
         assert g.rel_l2(db.cpu().numpy(), dbo) <= TOL_F32
     # the variant that also sums the added tensor's columns (a bias gradient) in the same pass
@@ -269,6 +273,12 @@ def test_gelu(g, n):
     g.call(K.lib().karma_k_gelu_bwd_bf16, g.ptr(xd), g.ptr(dyd), g.ptr(dx), C.c_uint64(n), g.stream_ptr())
     assert g.rel_l2(back(y), nn.gelu_fwd(x)) <= TOL_BF16
     assert g.rel_l2(back(dx), nn.gelu_bwd(x, dy)) <= TOL_BF16
+    # element by element: one bf16 rounding, plus the hardware exponential's error where the result is a
+    # small difference (1e-4 of a typical element)
+    ratio = g.elem_ratio(back(y), nn.gelu_fwd(x), 1, 1e-4, axis=None)
+    assert ratio <= 1, ratio
+    ratio = g.elem_ratio(back(dx), nn.gelu_bwd(x, dy), 1, 1e-4, axis=None)
+    assert ratio <= 1, ratio
 
 
 def sort_tokens(ids):
@@ -322,6 +332,9 @@ def test_softmax_cross_entropy(g, rows, cols):
     g.call(K.lib().karma_k_sum_f32, g.ptr(rowloss), g.ptr(out), g.ptr(ws), C.c_uint64(rows), C.c_float(scale), g.stream_ptr())
     assert abs(out.item() - loss) <= TOL_F32 * abs(loss)
     assert g.rel_l2(back(zd), d) <= TOL_BF16
+    # every gradient entry: one bf16 rounding of a probability (the label's entry is p - 1: a difference)
+    ratio = g.elem_ratio(back(zd), d, 1, 1e-3)
+    assert ratio <= 1, ratio
     # uniform logits: loss ln(cols), gradient rows sum to ~0
     zd.zero_()
     g.call(K.lib().karma_k_softmax_ce_bf16, g.ptr(zd), g.ptr(labd), g.ptr(rowloss), rows, cols, C.c_float(1.0),
@@ -342,6 +355,10 @@ def test_attention(g, B, S, H, D):
     g.call(lib.karma_k_attention_fwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(lse), B, S, H, D, g.stream_ptr())
     ctxo, probs = nn.mha_fwd(qkv, H)
     assert g.rel_l2(back(ctx), ctxo) <= TOL_ATTN
+    # every entry of every query row: the result's own rounding plus the probabilities' (2^-9 each,
+    # weighted by |v|, which does not cancel: a share of the row's size)
+    ratio = g.elem_ratio(back(ctx), ctxo, 1, 2.0 ** -6)
+    assert ratio <= 1, ratio
     # lse in the base-2 domain of the scaled scores
     q = qkv[0, :, :D]; k = qkv[0, :, h:h + D]
     s = (q @ k.T) / np.sqrt(D)
@@ -356,6 +373,13 @@ def test_attention(g, B, S, H, D):
     got = back(dqkv)
     for name, sl in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
         assert g.rel_l2(got[:, :, sl], dqkvo[:, :, sl]) <= TOL_ATTN, name
+        # per head, every element against the size of that head's gradient (the rounding of the stored
+        # context enters every row through delta = rowsum(dO * O), whatever the row's own size): a wrong
+        # row cannot hide in the norm
+        for hd in range(H):
+            a, b = got[:, :, sl][:, :, hd * D:(hd + 1) * D], dqkvo[:, :, sl][:, :, hd * D:(hd + 1) * D]
+            ratio = g.elem_ratio(a, b, 1, 2.0 ** -5, axis=(1, 2))
+            assert ratio <= 1, (ratio, (name, hd))
     # a second run gives the same bits (no atomics)
     dqkv2 = torch.zeros_like(dqkv)
     g.call(lib.karma_k_attention_bwd_bf16, g.ptr(qkvd), g.ptr(ctx), g.ptr(dctxd), g.ptr(lse), g.ptr(delta), g.ptr(dqkv2),

@@ -11,14 +11,20 @@ import paper_2008_11421_amd as K
 from oracle import cnn, nn, planner as P
 import synth_inputs as si
 
-TOL = 2e-2
-# Four stages down to 2x2 images: batch norm over 16 to 64 values per channel re-scales the
-# rounding of every stored bf16 tensor, and some twenty such tensors lie between a weight and
-# the loss; the measured error is 3-4.5e-2.  This network is there for the schedules (strides,
-# projections, identity shortcuts, every action); the 2e-2 bar is checked on SHALLOW.
-TOL_DEEP = 6e-2
-SMALL = dict(width=8, stage_blocks=(1, 2, 1, 1), image=64, batch=4, classes=16)
-SHALLOW = dict(width=8, stage_blocks=(1, 1, 0, 0), image=64, batch=4, classes=16)
+import cnn_bf16_storage as S
+
+BAR = 2e-2
+# No step that keeps its tensors in bf16 comes within the workload's 2e-2 of the plain
+# oracle on this kind of network: `tests/test_cnn_bf16_floor.py` measures, on the CPU, how
+# far bf16 storage alone moves each gradient (3e-2 in the median, 15e-2 at worst, with
+# stable ReLU masks; 15e-2 to 60e-2 when they flip).  So a gradient tensor passes when its
+# distance from the PLAIN oracle is at most FLOOR_FACTOR times that tensor's own floor plus
+# half the bar, the floor being recomputed here from the plain oracle and the storage
+# variant.  The factor allows for the roundings a real kernel adds to the variant's: fp32
+# instead of fp64 accumulation and statistics, bf16 weight gradients, bf16 sums on the
+# shortcut (measured: at most 1.5 times the floor, 0.92 to 0.99 in the median).
+FLOOR_FACTOR = 2.0
+SMALL, SHALLOW = S.SMALL, S.SHALLOW
 BT = cnn.BOTTLENECK_TENSORS
 
 
@@ -57,13 +63,6 @@ def load_params(ctx, params):
     ctx.karma_set_param(L, 1, params["head"]["b"])
 
 
-def rounded(params):
-    r = lambda a: nn.bf16_round(np.asarray(a, np.float32)).astype(np.float64)
-    return dict(stem={k: r(v) for k, v in params["stem"].items()},
-                blocks=[({k: r(v) for k, v in p.items()}, s) for p, s in params["blocks"]],
-                head={k: r(v) for k, v in params["head"].items()})
-
-
 def all_grads(ctx, params):
     out = {"stem.w": ctx.karma_get_grad(0, 0), "stem.g": ctx.karma_get_grad(0, 1), "stem.b": ctx.karma_get_grad(0, 2)}
     for i, (p, _) in enumerate(params["blocks"]):
@@ -86,69 +85,51 @@ def oracle_grads(grads):
 
 
 def small_problem(shift=3.0, dims=None):
-    """Batch-norm shifts are raised by `shift`: with zero shifts half of every ReLU's inputs
-    sit around zero, each bf16 rounding upstream flips a percent or so of the masks, and a
-    flipped fraction f of a gradient is a relative L2 error of sqrt(f) - far above the
-    workload's 2e-2 whatever the implementation.  Three standard deviations away from zero
-    the flips are rare and the comparison measures the arithmetic.  The masks themselves are
-    checked exactly, decision by decision, in the kernel tests."""
-    params, images, labels = si.cnn_problem(seed=2008114203, bn_jitter=0.1, **(dims or SMALL))
-    params["stem"]["b"] = params["stem"]["b"] + shift
-    for p, _ in params["blocks"]:
-        for k in ("b1", "b2", "b3", "bp"):
-            if k in p:
-                p[k] = p[k] + shift
-    images = nn.bf16_round(images.astype(np.float32)).astype(np.float64)
-    return params, images, labels.astype(np.int32)
+    """Batch-norm shifts are raised by `shift` (ReLU masks far from a flip: the comparison
+    then measures arithmetic rather than flipped decisions; the masks themselves are checked
+    exactly, decision by decision, in the kernel tests)."""
+    return S.problem(dims or SMALL, shift)
 
 
 def oracle_step(params, images, labels):
-    """Loss of the fp64 oracle, and loss and gradients of the oracle that rounds the tensors
-    the step stores to bf16, as the device does (every kernel is compared with the unrounded
-    fp64 oracle in the kernel tests)."""
-    lo64, _ = cnn.resnet_step(rounded(params), images, labels)
-    exact = cnn.STORE
-    cnn.STORE = lambda a: nn.bf16_round(np.asarray(a, np.float32)).astype(np.float64)
-    try:
-        lo, go = cnn.resnet_step(rounded(params), images, labels)
-    finally:
-        cnn.STORE = exact
-    return lo64, lo, oracle_grads(go)
+    """Loss and gradients of the plain fp64 oracle, and the gradients of the same step with
+    bf16 storage (the floor under any bf16 implementation)."""
+    pr = S.rounded_params(params)
+    lo, go = cnn.resnet_step(pr, images, labels)
+    _, gs = S.resnet_step_bf16_storage(pr, images, labels)
+    return lo, oracle_grads(go), oracle_grads(gs)
 
 
-def check_grads(g, got, want, tol):
-    bad = {}
-    for name, v in got.items():
-        err = np.linalg.norm(v.astype(np.float64).reshape(-1) - want[name].reshape(-1))
-        scale = np.linalg.norm(want[name])
-        # the shift of a batch norm that feeds a convolution + batch norm has (almost) no
-        # gradient: its error is measured against the gradient of the gain beside it
-        leaf = name.split(".")[-1]
-        if leaf in ("b1", "b2", "b3", "bp") or name == "stem.b":
-            scale = max(scale, np.linalg.norm(want[name[:-2] + "g" + name[-1:]] if name != "stem.b" else want["stem.g"]))
-        if err > tol * scale:
-            bad[name] = err / scale
+def check_grads(got, plain, storage):
+    floor = S.distances(storage, plain)
+    d = S.distances(got, plain)
+    bad = {k: (d[k], floor[k]) for k in d if not d[k] <= 0.5 * BAR + FLOOR_FACTOR * floor[k]}
     assert not bad, bad
+    # taken together the device's gradients are about as far from the plain oracle as the
+    # storage variant's are
+    assert np.median([d[k] / (floor[k] + 1e-3) for k in d]) <= 1.25
 
 
-def test_cnn_shallow_step_matches_oracle(g):
-    params, images, labels = small_problem(dims=SHALLOW)
+@pytest.mark.parametrize("shift", [3.0, 0.0])
+def test_cnn_shallow_step_matches_oracle(g, shift):
+    params, images, labels = small_problem(shift=shift, dims=SHALLOW)
     arena = 256 << 20
     ctx = make_ctx(SHALLOW, arena)
     assert ctx.n_layers == 3
     load_params(ctx, params)
     ctx.karma_set_plan(arena, [K.KEEP] * 3)
     loss = ctx.karma_step(images, labels)
-    lo64, lo, og = oracle_step(params, images, labels)
-    assert abs(loss - lo64) <= 5e-3 * abs(lo64) and abs(loss - lo) <= 2e-3 * abs(lo), (loss, lo64, lo)
-    check_grads(g, all_grads(ctx, params), og, TOL)
+    lo, og, sg = oracle_step(params, images, labels)
+    assert abs(loss - lo) <= 5e-3 * abs(lo), (loss, lo)
+    check_grads(all_grads(ctx, params), og, sg)
     ctx.karma_set_plan(arena, [K.SWAP, K.RC_KEEP, K.RC_CHAIN])
     assert ctx.karma_step(images, labels) == loss
     ctx.close()
 
 
-def test_cnn_step_matches_oracle_and_plans_are_bit_identical(g):
-    params, images, labels = small_problem()
+@pytest.mark.parametrize("shift", [3.0, 0.0])
+def test_cnn_step_matches_oracle_and_plans_are_bit_identical(g, shift):
+    params, images, labels = small_problem(shift=shift)
     arena = 256 << 20
     ctx = make_ctx(SMALL, arena)
     n = ctx.n_layers
@@ -157,9 +138,9 @@ def test_cnn_step_matches_oracle_and_plans_are_bit_identical(g):
     ctx.karma_set_plan(arena, [K.KEEP] * n)
     loss = ctx.karma_step(images, labels)
     ref = all_grads(ctx, params)
-    lo64, lo, og = oracle_step(params, images, labels)
-    assert abs(loss - lo64) <= 5e-3 * abs(lo64) and abs(loss - lo) <= 2e-3 * abs(lo), (loss, lo64, lo)
-    check_grads(g, ref, og, TOL_DEEP)
+    lo, og, sg = oracle_step(params, images, labels)
+    assert abs(loss - lo) <= 5e-3 * abs(lo), (loss, lo)
+    check_grads(ref, og, sg)
     assert np.all(ref["stem.w"].reshape(8, 7, 7, 8)[..., 3:] == 0)      # the padding channels see no gradient
 
     plans = [[K.SWAP] * n, [K.RC_KEEP] * n, [K.KEEP, K.RC_SWAP, K.RC_CHAIN, K.SWAP, K.RC_KEEP, K.RC_CHAIN],

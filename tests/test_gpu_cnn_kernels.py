@@ -115,6 +115,8 @@ def test_batchnorm(g, rows, c, relu, with_add):
     st = stats.cpu().numpy().astype(np.float64)
     assert g.rel_l2(st[0], x.mean(axis=0)) <= 1e-4 and g.rel_l2(st[1], cache[1]) <= 1e-4
     assert g.rel_l2(back(y), yo) <= TOL
+    ratio = g.elem_ratio(back(y), yo, 1, 1e-3, axis=0)
+    assert ratio <= 1, ratio
 
     dy, dyd = bf(si.normal(9, (rows, c)))
     # the ReLU decision is the kernel's own (its forward output, add excluded): both sides use it
@@ -136,6 +138,9 @@ def test_batchnorm(g, rows, c, relu, with_add):
     assert np.all(np.abs(dg.cpu().numpy() - dgo) <= 1e-3 * scale + 1e-4 * np.abs(dgo))
     assert np.all(np.abs(db.cpu().numpy() - dbo) <= 1e-3 * scale + 1e-4 * np.abs(dbo))
     assert g.rel_l2(back(dx), dxo.reshape(rows, c)) <= (TOL if rows > 3 else 0.1)
+    if rows > 3:    # per element, scaled by the channel's size (dx is dy minus two per-channel sums)
+        ratio = g.elem_ratio(back(dx), dxo.reshape(rows, c), 1, 1e-3, axis=0)
+        assert ratio <= 1, ratio
 
 
 def test_relu_mask(g):

@@ -123,9 +123,13 @@ def test_attention_full_size_sampled_heads(g):
         do = dctx[b, :, sl[0]].float().cpu().numpy().astype(np.float64)
         o, p = nn.attention_fwd(q, k, v)
         assert g.rel_l2(back(ctx[b, :, sl[0]]), o) <= TOL_ATTN
+        ratio = g.elem_ratio(back(ctx[b, :, sl[0]]), o, 1, 2.0 ** -6)
+        assert ratio <= 1, (ratio, (b, hd))
         dq, dk, dv = nn.attention_bwd(q, k, v, p, do)
         for name, ref, s_ in (("dq", dq, sl[0]), ("dk", dk, sl[1]), ("dv", dv, sl[2])):
             assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
+            ratio = g.elem_ratio(back(dqkv[b, :, s_]), ref, 1, 2.0 ** -5, axis=None)
+            assert ratio <= 1, (ratio, (b, hd, name))
 
 
 def test_attention_head_dimension_152_full_shape_sampled_heads(g):
@@ -149,9 +153,13 @@ def test_attention_head_dimension_152_full_shape_sampled_heads(g):
         do = dctx[b, :, sl[0]].float().cpu().numpy().astype(np.float64)
         o, p = nn.attention_fwd(q, k, v)
         assert g.rel_l2(back(ctx[b, :, sl[0]]), o) <= TOL_ATTN
+        ratio = g.elem_ratio(back(ctx[b, :, sl[0]]), o, 1, 2.0 ** -6)
+        assert ratio <= 1, (ratio, (b, hd))
         dq, dk, dv = nn.attention_bwd(q, k, v, p, do)
         for name, ref, s_ in (("dq", dq, sl[0]), ("dk", dk, sl[1]), ("dv", dv, sl[2])):
             assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
+            ratio = g.elem_ratio(back(dqkv[b, :, s_]), ref, 1, 2.0 ** -5, axis=None)
+            assert ratio <= 1, (ratio, (b, hd, name))
 
 
 def test_rowwise_kernels_full_size_sampled_rows(g):
@@ -175,8 +183,12 @@ def test_rowwise_kernels_full_size_sampled_rows(g):
     xo, go, bo, dyo = rows_of(x, rows), back(gam), back(bet), rows_of(dy, rows)
     yo, cache = nn.layernorm_fwd(xo, go, bo)
     assert g.rel_l2(rows_of(y, rows), yo) <= TOL_BF16
+    ratio = g.elem_ratio(rows_of(y, rows), yo, 1, 1e-3)
+    assert ratio <= 1, ratio
     dxo, _, _ = nn.layernorm_bwd(dyo, go, cache)
     assert g.rel_l2(rows_of(dx, rows), dxo) <= TOL_BF16
+    ratio = g.elem_ratio(rows_of(dx, rows), dxo, 1, 1e-3)
+    assert ratio <= 1, ratio
     # the column reductions over all 32768 rows: a few columns in full
     cols = [0, 17, H - 1]
     xc = x[:, cols].float().cpu().numpy().astype(np.float64); dyc = dy[:, cols].float().cpu().numpy().astype(np.float64)
@@ -199,6 +211,8 @@ def test_rowwise_kernels_full_size_sampled_rows(g):
     gy = torch.empty_like(f)
     g.call(lib.karma_k_gelu_fwd_bf16, g.ptr(f), g.ptr(gy), C.c_uint64(T * FFN), g.stream_ptr())
     assert g.rel_l2(rows_of(gy, rows), nn.gelu_fwd(rows_of(f, rows))) <= TOL_BF16
+    ratio = g.elem_ratio(rows_of(gy, rows), nn.gelu_fwd(rows_of(f, rows)), 1, 1e-4)
+    assert ratio <= 1, ratio
     # softmax cross-entropy on one head chunk (4096 x 32000)
     z = dev_normal(141, (4096, V), 2.0)
     zr = rows_of(z, rows % 4096)
@@ -211,3 +225,5 @@ def test_rowwise_kernels_full_size_sampled_rows(g):
         loss, d = nn.cross_entropy_fwd_bwd(zr[j:j + 1], labels[r:r + 1])
         assert abs(rowloss[r].item() - loss) <= 1e-4 * abs(loss) + 1e-5
         assert g.rel_l2(rows_of(z, [r]), d / T) <= TOL_BF16
+        ratio = g.elem_ratio(rows_of(z, [r]), d / T, 1, 1e-3)
+        assert ratio <= 1, ratio
