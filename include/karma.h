@@ -355,6 +355,18 @@ int karma_k_gemm_bf16(const void* a_dev, const void* b_dev, void* c_dev, const v
                       const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* ws_dev,
                       uint64_t ws_bytes, void* stream);
 
+/* karma_k_gemm_bf16 for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the split-reduction workspace is a fixed device array inside the
+ * library (KARMA_GEMM_STATIC_WS_BYTES per GPU the library runs on, held until the process ends) instead of a
+ * caller's buffer; the call allocates nothing.  Same arguments, result and errors as karma_k_gemm_bf16 called with
+ * a workspace of that size; products whose result is too large for two partial results in the array (2 * m * n * 4
+ * bytes > KARMA_GEMM_STATIC_WS_BYTES) are refused with KARMA_E_OOM.  All calls on one GPU share the array: calls
+ * that overlap on one GPU (different streams or threads) race and must be serialised by the caller. */
+#define KARMA_GEMM_STATIC_WS_BYTES (64u << 20)
+int karma_k_gemm_bf16_static_ws(const void* a_dev, const void* b_dev, void* c_dev, const void* bias_dev,
+                                const void* residual_dev, uint32_t m, uint32_t n, uint32_t k, uint32_t flags,
+                                void* stream);
+
 /* The same product with the GELU of the feed-forward layer (Sec. III-C, fully connected layer followed by its
  * activation) folded into the kernel's output stage, bf16 output only.
  * KARMA_GEMM_GELU_FWD: c_dev = a b^T + bias (the pre-activation, which backward needs) and aux_dev (bf16 [m][n],

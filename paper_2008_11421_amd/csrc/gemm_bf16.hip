@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 #include <algorithm>
 #include <cstdint>
+#include <mutex>
 
 #include "karma.h"
 #include "device_utils.h"
@@ -875,4 +876,39 @@ extern "C" int karma_k_gemm_bf16(const void* a, const void* b, void* c, const vo
   g.ws = ws;
   g.ws_bytes = ws ? (size_t)ws_bytes : 0;
   return gemm_bf16(g, (hipStream_t)stream);
+}
+
+// ---- the product for callers that cannot allocate -------------------------------------------
+// The split-reduction workspace lives in a file-scope device array instead of a caller's buffer.
+// In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device (each GPU holds its own copy at its own address).
+namespace {
+constexpr size_t STATIC_WS_BYTES = KARMA_GEMM_STATIC_WS_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device, or nullptr (HIP error).
+void* static_ws() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int karma_k_gemm_bf16_static_ws(const void* a, const void* b, void* c, const void* bias, const void* residual,
+                                           uint32_t m, uint32_t n, uint32_t k, uint32_t flags, void* stream) {
+  // two partial results must fit, or the workspace could not serve any split
+  if ((uint64_t)m * n * sizeof(float) * 2 > STATIC_WS_BYTES) return KARMA_E_OOM;
+  void* ws = static_ws();
+  if (!ws) return KARMA_E_HIP;
+  return karma_k_gemm_bf16(a, b, c, bias, residual, m, n, k, flags, ws, STATIC_WS_BYTES, stream);
 }
