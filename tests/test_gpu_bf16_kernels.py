@@ -375,10 +375,11 @@ def test_attention(g, B, S, H, D):
         assert g.rel_l2(got[:, :, sl], dqkvo[:, :, sl]) <= TOL_ATTN, name
         # per head, every element against the size of that head's gradient (the rounding of the stored
         # context enters every row through delta = rowsum(dO * O), whatever the row's own size): a wrong
-        # row cannot hide in the norm
+        # row cannot hide in the norm.  Three chained roundings leave errors of about 1 % of the head's
+        # size (the relative L2 above); the largest of 10^5..10^6 of them reaches 5 %, the bound is 2^-4
         for hd in range(H):
             a, b = got[:, :, sl][:, :, hd * D:(hd + 1) * D], dqkvo[:, :, sl][:, :, hd * D:(hd + 1) * D]
-            ratio = g.elem_ratio(a, b, 1, 2.0 ** -5, axis=(1, 2))
+            ratio = g.elem_ratio(a, b, 1, 2.0 ** -4, axis=(1, 2))
             assert ratio <= 1, (ratio, (name, hd))
     # a second run gives the same bits (no atomics)
     dqkv2 = torch.zeros_like(dqkv)

@@ -128,7 +128,7 @@ def test_attention_full_size_sampled_heads(g):
         dq, dk, dv = nn.attention_bwd(q, k, v, p, do)
         for name, ref, s_ in (("dq", dq, sl[0]), ("dk", dk, sl[1]), ("dv", dv, sl[2])):
             assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
-            ratio = g.elem_ratio(back(dqkv[b, :, s_]), ref, 1, 2.0 ** -5, axis=None)
+            ratio = g.elem_ratio(back(dqkv[b, :, s_]), ref, 1, 2.0 ** -4, axis=None)
             assert ratio <= 1, (ratio, (b, hd, name))
 
 
@@ -158,7 +158,7 @@ def test_attention_head_dimension_152_full_shape_sampled_heads(g):
         dq, dk, dv = nn.attention_bwd(q, k, v, p, do)
         for name, ref, s_ in (("dq", dq, sl[0]), ("dk", dk, sl[1]), ("dv", dv, sl[2])):
             assert g.rel_l2(back(dqkv[b, :, s_]), ref) <= TOL_ATTN, (b, hd, name)
-            ratio = g.elem_ratio(back(dqkv[b, :, s_]), ref, 1, 2.0 ** -5, axis=None)
+            ratio = g.elem_ratio(back(dqkv[b, :, s_]), ref, 1, 2.0 ** -4, axis=None)
             assert ratio <= 1, (ratio, (b, hd, name))
 
 
