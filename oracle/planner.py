@@ -537,6 +537,7 @@ def plan(layers, link, budget, fixed, loss):
     # step 2: Eq. 10.1 scan over the swapped prefix of the first start, descending
     xraw = [0] + [l.out for l in layers]
     cur = starts[0]
+    unmarked = list(cur)
     for i in range(L - 1, -1, -1):
         if cur[i] != SWAP:
             continue
@@ -549,6 +550,8 @@ def plan(layers, link, budget, fixed, loss):
                     cur = cand
                     break
     starts[0] = cur
+    if cur != unmarked:
+        starts.append(unmarked)     # the capacity-based schedule itself (Fig. 2(b)) is a start too
 
     # step 3: refinement of each start; the best local optimum wins
     best = None
@@ -646,12 +649,18 @@ def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
     return acts, res, g
 
 
+PAIR_WINDOW = 4
+
+
 def refine(layers, link, budget, fixed, loss, start):
-    """Local search.  A candidate replaces the incumbent when its (cost tuple, action
-    vector) is lexicographically smaller.  Neighbourhoods, in this order, repeated
-    until a full round changes nothing: (a) one layer takes another action; (b) two
-    layers exchange their actions; (c) two neighbouring layers take any pair of
-    actions.  Returns (cost tuple, actions)."""
+    """Local search (variable neighbourhood descent).  A candidate replaces the incumbent
+    when its (cost tuple, action vector) is lexicographically smaller.  Neighbourhoods:
+    (a) one layer takes another action; (b) two layers exchange their actions; (c) two
+    layers at most PAIR_WINDOW apart take any pair of actions; (d) three consecutive
+    layers take any triple of actions.  A larger neighbourhood is searched only when a
+    full pass over every smaller one has changed nothing; any improvement sends the
+    search back to (a).  It ends when a pass over (d) changes nothing.  Returns
+    (cost tuple, actions)."""
     L = len(layers)
     key = (try_cost(layers, link, budget, fixed, loss, start), list(start))
 
@@ -665,8 +674,7 @@ def refine(layers, link, budget, fixed, loss, start):
             return True
         return False
 
-    changed = True
-    while changed:
+    def singles():
         changed = False
         for i in range(L):
             for a in range(N_ACTIONS):
@@ -674,28 +682,60 @@ def refine(layers, link, budget, fixed, loss, start):
                     cand = list(key[1])
                     cand[i] = a
                     changed |= consider(cand)
+        return changed
+
+    def exchanges():
+        changed = False
         for i in range(L):
             for j in range(i + 1, L):
                 if key[1][i] != key[1][j]:
                     cand = list(key[1])
                     cand[i], cand[j] = cand[j], cand[i]
                     changed |= consider(cand)
+        return changed
+
+    def pairs():
+        changed = False
         for i in range(L - 1):
+            for j in range(i + 1, min(L, i + 1 + PAIR_WINDOW)):
+                for a in range(N_ACTIONS):
+                    for b in range(N_ACTIONS):
+                        if (a, b) != (key[1][i], key[1][j]):
+                            cand = list(key[1])
+                            cand[i], cand[j] = a, b
+                            changed |= consider(cand)
+        return changed
+
+    def triples():
+        changed = False
+        for i in range(L - 2):
             for a in range(N_ACTIONS):
                 for b in range(N_ACTIONS):
-                    if (a, b) != (key[1][i], key[1][i + 1]):
-                        cand = list(key[1])
-                        cand[i], cand[i + 1] = a, b
-                        changed |= consider(cand)
+                    for c in range(N_ACTIONS):
+                        if (a, b, c) != tuple(key[1][i:i + 3]):
+                            cand = list(key[1])
+                            cand[i:i + 3] = [a, b, c]
+                            changed |= consider(cand)
+        return changed
+
+    hoods = (singles, exchanges, pairs, triples)
+    k = 0
+    while k < len(hoods):
+        k = 0 if hoods[k]() else k + 1
     return key
 
 
-def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN), wres=None):
+def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN), wres=None,
+                prefix=()):
     """Exhaustive search over every valid assignment: smallest cost tuple, ties to the
-    lexicographically smallest action vector.  Exponential; for small stacks only."""
+    lexicographically smallest action vector.  Exponential; for small stacks only.
+    `prefix` fixes the actions of the first layers (a caller may split the enumeration
+    over processes by prefix and take the smallest result)."""
     L = len(layers)
     best = None
-    cur = [alphabet[0]] * L
+    cur = list(prefix) + [alphabet[0]] * (L - len(prefix))
+    if not valid_actions(list(prefix)):
+        return None
 
     def rec(i):
         nonlocal best
@@ -710,7 +750,7 @@ def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP
             cur[i] = a
             rec(i + 1)
 
-    rec(0)
+    rec(len(prefix))
     return best
 
 

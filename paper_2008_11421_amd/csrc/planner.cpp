@@ -443,30 +443,50 @@ struct Incumbent {
   }
 };
 
-// Local search: single-layer changes, exchanges of two layers' actions, pairs of
-// neighbouring layers; repeated until a whole round changes nothing.
+// Local search (variable neighbourhood descent) on (cost, action vector).  Neighbourhoods: one
+// layer takes another action; two layers exchange their actions; two layers at most PAIR_WINDOW
+// apart take any pair of actions; three consecutive layers take any triple of actions.  A larger
+// neighbourhood is searched only when a full pass over every smaller one changed nothing; any
+// improvement sends the search back to the smallest.
+static const uint32_t PAIR_WINDOW = 4;
+
 void improve(const Problem& P, Incumbent& inc) {
   const uint32_t L = P.n;
-  auto attempt = [&](const std::vector<uint8_t>& cand) {
+  std::vector<uint8_t> cand;
+  auto attempt = [&]() {
     Cost c;
     if (evaluate(P, cand, c) && inc.beaten_by(c, cand)) { inc.cost = c; inc.act = cand; return true; }
     return false;
   };
-  bool moved = true;
-  std::vector<uint8_t> cand;
-  while (moved) {
-    moved = false;
-    for (uint32_t i = 0; i < L; ++i)
-      for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
-        if (a != inc.act[i]) { cand = inc.act; cand[i] = a; moved |= attempt(cand); }
-    for (uint32_t i = 0; i < L; ++i)
-      for (uint32_t j = i + 1; j < L; ++j)
-        if (inc.act[i] != inc.act[j]) { cand = inc.act; std::swap(cand[i], cand[j]); moved |= attempt(cand); }
-    for (uint32_t i = 0; i + 1 < L; ++i)
-      for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
-        for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b)
-          if (a != inc.act[i] || b != inc.act[i + 1]) { cand = inc.act; cand[i] = a; cand[i + 1] = b; moved |= attempt(cand); }
-  }
+  auto pass = [&](int hood) {
+    bool moved = false;
+    if (hood == 0) {
+      for (uint32_t i = 0; i < L; ++i)
+        for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
+          if (a != inc.act[i]) { cand = inc.act; cand[i] = a; moved |= attempt(); }
+    } else if (hood == 1) {
+      for (uint32_t i = 0; i < L; ++i)
+        for (uint32_t j = i + 1; j < L; ++j)
+          if (inc.act[i] != inc.act[j]) { cand = inc.act; std::swap(cand[i], cand[j]); moved |= attempt(); }
+    } else if (hood == 2) {
+      for (uint32_t i = 0; i + 1 < L; ++i)
+        for (uint32_t j = i + 1; j < L && j <= i + PAIR_WINDOW; ++j)
+          for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
+            for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b)
+              if (a != inc.act[i] || b != inc.act[j]) { cand = inc.act; cand[i] = a; cand[j] = b; moved |= attempt(); }
+    } else {
+      for (uint32_t i = 0; i + 2 < L; ++i)
+        for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
+          for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b)
+            for (uint8_t d = 0; d <= KARMA_RC_CHAIN; ++d)
+              if (a != inc.act[i] || b != inc.act[i + 1] || d != inc.act[i + 2]) {
+                cand = inc.act; cand[i] = a; cand[i + 1] = b; cand[i + 2] = d;
+                moved |= attempt();
+              }
+    }
+    return moved;
+  };
+  for (int hood = 0; hood < 4;) hood = pass(hood) ? 0 : hood + 1;
 }
 
 }  // namespace
@@ -507,7 +527,8 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
   }
   // Eq. 10.1: recompute where it is cheaper than the swap-in it replaces
   {
-    std::vector<uint8_t>& cur = starts[0];
+    const std::vector<uint8_t> unmarked = starts[0];
+    std::vector<uint8_t> cur = starts[0];
     for (int64_t i = (int64_t)L - 1; i >= 0; --i) {
       if (cur[i] != KARMA_SWAP) continue;
       uint64_t xin = i ? P.layers[i - 1].out_bytes : 0;
@@ -520,6 +541,8 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
         }
       }
     }
+    starts[0] = cur;
+    if (cur != unmarked) starts.push_back(unmarked);   // the capacity-based schedule itself (Fig. 2(b)) is a start too
   }
   bool have = false;
   Incumbent best;

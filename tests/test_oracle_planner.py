@@ -1,6 +1,8 @@
 """Pins for the planner oracle: the paper's worked schedule, hand-computed timelines,
 an independent bitmap model of the allocator, exhaustive search on small stacks and the
 invariants the method guarantees."""
+import itertools
+import multiprocessing
 import os
 
 import pytest
@@ -143,25 +145,72 @@ def cases(L, seeds, kinds=("homogeneous", "front_heavy", "back_heavy", "imbalanc
                     yield layers, P.Link(bw, bw, 50), int(full * frac) + maxl, P.Loss(100, 256)
 
 
-def test_plan_against_brute_force_small_stacks():
-    """Exhaustive enumeration over all five actions, L = 5.  The local search is not
-    exact: it must never beat the optimum, must hit it on at least 90 % of the cases
-    and stay within 6 % of the optimal makespan everywhere."""
-    n = hit = 0
-    worst = 0.0
-    for layers, link, budget, loss in cases(5, seeds=(0, 1), fracs=(0.35, 0.6), bwmuls=(0.3, 1.0, 4.0)):
-        bf = P.brute_force(layers, link, budget, 0, loss)
-        try:
-            acts, summ = P.plan(layers, link, budget, 0, loss)
-        except P.Infeasible:
+def _bf_vs_plan(case):
+    """(plan's (cost, actions), brute force's) for one case; runs in a worker process."""
+    layers, link, budget, loss, alphabet, prefix_len = case
+    if prefix_len:
+        parts = [P.brute_force(layers, link, budget, 0, loss, alphabet=alphabet, prefix=pre)
+                 for pre in itertools.product(alphabet, repeat=prefix_len)]
+        parts = [r for r in parts if r is not None]
+        bf = min(parts) if parts else None
+    else:
+        bf = P.brute_force(layers, link, budget, 0, loss, alphabet=alphabet)
+    try:
+        acts, summ = P.plan(layers, link, budget, 0, loss)
+    except P.Infeasible:
+        return None, bf
+    return (P.cost_tuple(summ), acts), bf
+
+
+def _bf_prefix(job):
+    layers, link, budget, loss, alphabet, prefix = job
+    return P.brute_force(layers, link, budget, 0, loss, alphabet=alphabet, prefix=prefix)
+
+
+ALL5 = (P.KEEP, P.SWAP, P.RC_KEEP, P.RC_SWAP, P.RC_CHAIN)
+KSR = (P.KEEP, P.SWAP, P.RC_KEEP)
+
+
+def test_plan_equals_brute_force_small_stacks():
+    """Exhaustive enumeration over all five actions, L = 5, 48 cases (four kinds of stack, two
+    seeds, two budgets, three link speeds): the planner returns the optimum itself, cost
+    tuple and action vector."""
+    todo = [(layers, link, budget, loss, ALL5, 0)
+            for layers, link, budget, loss in cases(5, seeds=(0, 1), fracs=(0.35, 0.6), bwmuls=(0.3, 1.0, 4.0))]
+    with multiprocessing.Pool(min(8, os.cpu_count() or 1)) as pool:
+        res = pool.map(_bf_vs_plan, todo)
+    n = 0
+    for got, bf in res:
+        if got is None:
             assert bf is None
             continue
-        c = P.cost_tuple(summ)
-        assert bf is not None and (c, acts) >= (bf[0], bf[1])
+        assert got == (bf[0], bf[1]), (got, bf)
         n += 1
-        hit += (c, acts) == (bf[0], bf[1])
-        worst = max(worst, (c[0] - bf[0][0]) / bf[0][0])
-    assert n >= 40 and hit >= 0.9 * n and worst <= 0.06, (n, hit, worst)
+    assert n >= 40
+
+
+def test_plan_against_brute_force_wider_suite():
+    """More seeds, a looser budget and six layers (5^6 assignments each).  The local search is
+    not exact in general: it never beats the optimum, hits it on at least 95 % of these 120
+    cases and stays within 2 % of the optimal makespan everywhere (measured: 119 of 120,
+    worst 1.9 %)."""
+    todo = [(layers, link, budget, loss, ALL5, 0)
+            for layers, link, budget, loss in cases(5, seeds=(2, 3), fracs=(0.35, 0.6, 0.85), bwmuls=(0.3, 1.0, 4.0))]
+    todo += [(layers, link, budget, loss, ALL5, 0)
+             for layers, link, budget, loss in cases(6, seeds=(0, 1), fracs=(0.35, 0.6), bwmuls=(0.3, 1.0, 4.0))]
+    with multiprocessing.Pool(min(8, os.cpu_count() or 1)) as pool:
+        res = pool.map(_bf_vs_plan, todo)
+    n = hit = 0
+    worst = 0.0
+    for got, bf in res:
+        if got is None:
+            assert bf is None
+            continue
+        assert bf is not None and got >= (bf[0], bf[1])
+        n += 1
+        hit += got == (bf[0], bf[1])
+        worst = max(worst, (got[0][0] - bf[0][0]) / bf[0][0])
+    assert n >= 100 and hit >= 0.95 * n and worst <= 0.02, (n, hit, worst)
 
 
 def test_brute_force_three_actions_nine_layers():
@@ -169,20 +218,40 @@ def test_brute_force_three_actions_nine_layers():
     full = sum(P.al(l.sav) + P.al(l.out) for l in layers)
     bw = int(full / sum(l.tf for l in layers) * 1e9)
     link, loss, budget = P.Link(bw, bw, 20), P.Loss(50, 0), int(full * 0.5)
-    bf = P.brute_force(layers, link, budget, 0, loss, alphabet=(P.KEEP, P.SWAP, P.RC_KEEP))
+    bf = P.brute_force(layers, link, budget, 0, loss, alphabet=KSR)
     acts, summ = P.plan(layers, link, budget, 0, loss)
-    assert P.cost_tuple(summ)[0] <= bf[0][0] * 1.06     # the planner may also use RC_SWAP / chains
+    # the planner may also use RC_SWAP and chains: it can only be as good or better
+    assert (P.cost_tuple(summ), acts) <= (bf[0], bf[1])
+    assert P.cost_tuple(summ)[0] == bf[0][0]
 
 
-@pytest.mark.skipif(not os.environ.get("KARMA_SLOW"), reason="3^12 simulations; set KARMA_SLOW=1")
-def test_brute_force_twelve_layers():
-    layers = mk(3, 12, "homogeneous")
+@pytest.mark.parametrize("seed,kind,frac", [(3, "homogeneous", 0.5), (4, "front_heavy", 0.4)])
+def test_brute_force_twelve_layers(seed, kind, frac):
+    """All 3^12 = 531 441 keep / swap / recompute assignments of a 12-layer stack, the
+    enumeration split over processes by the first three layers' actions: the planner's plan
+    is the optimum (it could only be better, having two more actions to choose from)."""
+    layers = mk(seed, 12, kind)
+    full = sum(P.al(l.sav) + P.al(l.out) for l in layers)
+    bw = int(full / sum(l.tf for l in layers) * 1e9)
+    link, loss, budget = P.Link(bw, bw, 20), P.Loss(50, 0), int(full * frac)
+    jobs = [(layers, link, budget, loss, KSR, pre) for pre in itertools.product(KSR, repeat=3)]
+    with multiprocessing.Pool(min(8, os.cpu_count() or 1)) as pool:
+        parts = [r for r in pool.map(_bf_prefix, jobs) if r is not None]
+    bf = min(parts)
+    acts, summ = P.plan(layers, link, budget, 0, loss)
+    assert (P.cost_tuple(summ), acts) <= (bf[0], bf[1])
+    assert P.cost_tuple(summ)[0] == bf[0][0]
+
+
+def test_brute_force_prefix_split_is_the_whole_enumeration():
+    layers = mk(2, 6, "imbalanced")
     full = sum(P.al(l.sav) + P.al(l.out) for l in layers)
     bw = int(full / sum(l.tf for l in layers) * 1e9)
     link, loss, budget = P.Link(bw, bw, 20), P.Loss(50, 0), int(full * 0.5)
-    bf = P.brute_force(layers, link, budget, 0, loss, alphabet=(P.KEEP, P.SWAP, P.RC_KEEP))
-    acts, summ = P.plan(layers, link, budget, 0, loss)
-    assert P.cost_tuple(summ)[0] <= bf[0][0] * 1.06
+    whole = P.brute_force(layers, link, budget, 0, loss)
+    parts = [P.brute_force(layers, link, budget, 0, loss, prefix=pre) for pre in itertools.product(ALL5, repeat=2)]
+    assert min(r for r in parts if r is not None) == whole
+    assert P.brute_force(layers, link, budget, 0, loss, prefix=(P.RC_CHAIN,)) is None     # no valid vector starts so
 
 
 def test_invariants_on_random_stacks():
