@@ -64,16 +64,27 @@ typedef struct {
                                    a swapped block carries its weights); 0 = weights resident,
                                    their bytes are part of the fixed region */
   uint64_t g_bytes;             /* gradients of those weights (ignored when w_bytes is 0) */
+  int64_t th_ns;                /* host optimiser time for the layer's parameters (Sec. III-G, stage 5: the
+                                   weights are updated on the CPU); 0 = no host update is priced */
+  uint64_t hg_bytes;            /* resident weights: gradients that leave for the host after B_i */
+  uint64_t hw_bytes;            /* resident weights: new weights that come back after the update (a streamed
+                                   layer's gradients are g_bytes, its new weights stay on the host) */
 } karma_layer_cost;
 
 typedef struct {
   uint64_t bw_h2d, bw_d2h; /* bytes per second, one measured figure per direction (Eq. 4) */
   int64_t lat_ns;          /* fixed cost per copy */
+  uint64_t bw_h2d_loaded, bw_d2h_loaded; /* the same while the other direction copies and the host optimiser
+                                            streams through host memory: the price of every copy issued after
+                                            the forward pass of a step with host updates; 0 = as above */
 } karma_link;
 
 typedef struct {
   int64_t t_ns;      /* loss op (forward and gradient w.r.t. its input) */
   uint64_t ws_bytes; /* its workspace */
+  int64_t th_ns;     /* host optimiser time, gradient and weight bytes of the parameters that belong */
+  uint64_t hg_bytes; /* to the loss record (a final normalisation, a classifier), as for a layer */
+  uint64_t hw_bytes;
 } karma_loss_cost;
 
 typedef struct {
@@ -83,6 +94,8 @@ typedef struct {
   int64_t recompute_ns; /* part of busy_ns spent recomputing */
   uint64_t peak_bytes;  /* fixed + high-water mark of the arena */
   uint64_t bytes_d2h, bytes_h2d;
+  int64_t host_busy_ns; /* host optimiser queue: sum of the updates, */
+  int64_t host_end_ns;  /* and the end of the last one */
 } karma_plan_summary;
 
 /* One op of the simulated/executed timeline, in issue order.
@@ -107,7 +120,11 @@ typedef struct {
  * with streamed weights whether they stay in HBM from F_i to B_i (1) or are freed after
  * F_i and copied in again before R_i / B_i (0); weights are copied in one layer ahead of
  * the forward pass and queued with the swap-ins, in order of need, during backward;
- * gradients leave right after B_i (Sec. III-G, pipeline stage 3).  ops_out may be NULL;
+ * gradients leave right after B_i (Sec. III-G, pipeline stage 3).  Host optimiser (stage 5), a fourth in-order
+ * queue: a layer's update (th_ns) starts when its gradients have landed on the host and the updates before it,
+ * in the order of the backward ops, are done; new weights of a resident layer go back on the host-to-device
+ * queue behind every copy of the step's own program; the makespan ends with the last update and weight copy
+ * (one step in isolation).  ops_out may be NULL;
  * otherwise *n_ops_inout holds its capacity on entry and the number of ops on return
  * (KARMA_E_OOM if too small: at most 8*n+2 are written).
  * Errors: KARMA_E_INVAL (invalid vector), KARMA_E_BUDGET (does not fit). */

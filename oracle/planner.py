@@ -26,6 +26,18 @@ Model of one step (a "block" of the paper is one layer record here):
   buffers (layer inputs x_i, saved internals s_i) are carved from the lowest fitting
   free range, short-lived ones (workspace, activation gradients dx_i) from the highest.
 
+Host optimiser (Sec. III-G, stages 3 and 5: a block's gradients are swapped out after its
+backward and the weights are updated on the CPU): a fourth in-order queue.  The gradients
+of layer i leave on the device-to-host queue when B_i ends (gb bytes for streamed weights,
+hg bytes for resident ones); the update of layer i starts when they have landed and the
+host is free, and takes th_i; updates run in the order the backward ops complete.  New weights of
+a resident layer (hw bytes) go back on the host-to-device queue behind every copy of the
+step's own program (the program is enqueued ahead of time, the weight copies as updates
+finish).  The makespan ends with the last update and the last weight copy: one step in
+isolation.  (An executor may hide that tail under the next step's forward pass; the model
+does not count on it.)  Copies issued after the forward pass are priced at the link's loaded
+rates.
+
 Weight streaming (Sec. III-G: a swapped block carries its weights; stage 3 of the
 pipeline swaps a block's gradients out after its backward while earlier blocks are
 swapped in): a layer with wb > 0 keeps its weights on the host.  They are copied in
@@ -49,11 +61,18 @@ ALIGN = 256
 # (= the next layer's input).  ws: transient workspace bytes of any op of this layer.
 # wb/gb: bytes of the layer's weights / weight gradients when they are streamed over the
 # host link instead of living in the fixed region (0 = resident).
-Layer = namedtuple("Layer", "tf tb trc sav out ws wb gb", defaults=(0, 0))
-# host link: bytes/s per direction and a fixed per-copy latency (ns)
-Link = namedtuple("Link", "bw_h2d bw_d2h lat_ns")
-# loss op that sits between forward and backward: time and workspace
-Loss = namedtuple("Loss", "t ws")
+# th: time (ns) the host optimiser needs for the layer's parameters (Sec. III-G, stage 5: the
+# weights are updated on the CPU); hg / hw: for a layer whose weights are resident, the bytes of
+# gradients that leave for the host after its backward and of new weights that come back after
+# the update (a streamed layer's gradients are gb, its new weights stay on the host).
+Layer = namedtuple("Layer", "tf tb trc sav out ws wb gb th hg hw", defaults=(0, 0, 0, 0, 0))
+# host link: bytes/s per direction and a fixed per-copy latency (ns).  The *_loaded rates hold
+# while gradients stream to the host and the host optimiser runs (every copy issued after the
+# forward pass of a step with host updates); 0 = same as the idle rate.
+Link = namedtuple("Link", "bw_h2d bw_d2h lat_ns bw_h2d_loaded bw_d2h_loaded", defaults=(0, 0))
+# loss op that sits between forward and backward: time and workspace; th / hg / hw as for a
+# layer (the parameters that belong to the loss record, e.g. a final normalisation)
+Loss = namedtuple("Loss", "t ws th hg hw", defaults=(0, 0, 0))
 Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN WIN GOUT
 
 
@@ -196,6 +215,9 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     tc = td = th = 0
     busy = 0
     d2h = h2d = rc_ns = 0
+    hosted = loss.th > 0 or any(l.th > 0 for l in layers)   # a step with host updates
+    rate = {"h2d": link.bw_h2d, "d2h": link.bw_d2h}          # current price of a copy
+    landed = []               # (time the gradients are on the host, th, hw) in landing order
 
     def apply_pending(t):
         while pending and pending[0][0] <= t:
@@ -226,7 +248,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         """Copy of layer i's weights into W[i] (already allocated), on the H2D queue."""
         nonlocal th, h2d
         st = max(th, t)
-        th = st + copy_ns(layers[i].wb, link.bw_h2d, link.lat_ns)
+        th = st + copy_ns(layers[i].wb, rate["h2d"], link.lat_ns)
         h2d += layers[i].wb
         warr[i] = th
         if want_ops:
@@ -268,7 +290,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
                 bufs.append((S[i], sb[i]))
             if nbytes:
                 st = max(td, end)
-                td = st + copy_ns(nbytes, link.bw_d2h, link.lat_ns)
+                td = st + copy_ns(nbytes, rate["d2h"], link.lat_ns)
                 d2h += nbytes
                 pending.append((td, bufs))
                 out_end[i] = td
@@ -349,7 +371,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             return
         nbytes = xraw[i] + (layers[i].sav if actions[i] == SWAP else 0)
         st = max(th, t, out_end[i])
-        th = st + copy_ns(nbytes, link.bw_h2d, link.lat_ns)
+        th = st + copy_ns(nbytes, rate["h2d"], link.lat_ns)
         h2d += nbytes
         arrive[it] = th
         if want_ops:
@@ -387,7 +409,29 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             t = max(t, arrive[it])
         return t
 
+    def grads_leave(rec, end, streamed_landing):
+        """Gradients of a record go to the host after the op that completed them (at `end`);
+        its update is queued for when they have landed."""
+        nonlocal td, d2h
+        if streamed_landing is not None:
+            if rec.th:
+                landed.append((streamed_landing, rec.th, 0))
+            return
+        when = end
+        if rec.hg:
+            st = max(td, end)
+            td = st + copy_ns(rec.hg, rate["d2h"], link.lat_ns)
+            d2h += rec.hg
+            when = td
+        if rec.th or rec.hw:
+            landed.append((when, rec.th, rec.hw))
+
     # ---------------- loss ----------------
+    if hosted:
+        # the forward pass is over: from here on gradients stream to the host and the optimiser
+        # works on them, and every copy issued is priced at the loaded rates
+        rate["h2d"] = link.bw_h2d_loaded or link.bw_h2d
+        rate["d2h"] = link.bw_d2h_loaded or link.bw_d2h
     admit(tc, max(res_all, loss_need))
     t = tc
     apply_pending(t)
@@ -400,6 +444,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     tc = end
     rel(w, al(loss.ws))
     rel(X[L], xb[L])
+    grads_leave(loss, end, None)
     admit(tc, res_all)
 
     # ---------------- backward ----------------
@@ -424,11 +469,14 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         if gB[j]:
             # the gradients leave right after the layer's backward (pipeline stage 3)
             st = max(td, end)
-            td = st + copy_ns(layers[j].gb, link.bw_d2h, link.lat_ns)
+            td = st + copy_ns(layers[j].gb, rate["d2h"], link.lat_ns)
             d2h += layers[j].gb
             pending.append((td, [(G[j], gB[j])]))
             if want_ops:
                 ops.append(Op("GOUT", j, st, td, ()))
+            grads_leave(layers[j], end, td)
+        else:
+            grads_leave(layers[j], end, None)
         admit(tc, reserve)
 
     for k, (h, e) in enumerate(units):
@@ -462,10 +510,18 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
 
     apply_pending(max(tc, td, th))
     assert ar.used == 0, "ledger leak"
-    makespan = max(tc, td, th)
+    # ---------------- host optimiser queue ----------------
+    t_host = host_busy = 0
+    for when, t_upd, back in landed:
+        t_host = max(t_host, when) + t_upd
+        host_busy += t_upd
+        if back:    # new weights of a resident layer: behind the program's own copies
+            th = max(th, t_host) + copy_ns(back, rate["h2d"], link.lat_ns)
+            h2d += back
+    makespan = max(tc, td, th, t_host)
     res = dict(makespan_ns=makespan, stall_ns=tc - busy, busy_ns=busy,
                peak_bytes=fixed + ar.peak_used, bytes_d2h=d2h, bytes_h2d=h2d,
-               recompute_ns=rc_ns)
+               recompute_ns=rc_ns, host_busy_ns=host_busy, host_end_ns=t_host)
     if want_ops:
         res["ops"] = ops
     return res
@@ -536,12 +592,14 @@ def plan(layers, link, budget, fixed, loss):
 
     # step 2: Eq. 10.1 scan over the swapped prefix of the first start, descending
     xraw = [0] + [l.out for l in layers]
+    hosted = loss.th > 0 or any(l.th > 0 for l in layers)
+    bw_in = (link.bw_h2d_loaded or link.bw_h2d) if hosted else link.bw_h2d   # swap-ins run in the backward phase
     cur = starts[0]
     unmarked = list(cur)
     for i in range(L - 1, -1, -1):
         if cur[i] != SWAP:
             continue
-        t_in = copy_ns(xraw[i] + layers[i].sav, link.bw_h2d, link.lat_ns)
+        t_in = copy_ns(xraw[i] + layers[i].sav, bw_in, link.lat_ns)
         if layers[i].trc < t_in:
             for a in (RC_KEEP, RC_SWAP):
                 cand = list(cur)
@@ -588,7 +646,8 @@ def merge_group(members):
     return Layer(tf=sum(m.tf for m in members), tb=sum(m.tb for m in members),
                  trc=sum(m.tf for m in members[:-1]) + members[-1].trc,
                  sav=sum(m.sav for m in members) + sum(m.out for m in members[:-1]), out=members[-1].out,
-                 ws=max(m.ws for m in members), wb=sum(m.wb for m in members), gb=sum(m.gb for m in members))
+                 ws=max(m.ws for m in members), wb=sum(m.wb for m in members), gb=sum(m.gb for m in members),
+                 th=sum(m.th for m in members), hg=sum(m.hg for m in members), hw=sum(m.hw for m in members))
 
 
 def expand_group_actions(group_actions, group_wres, sizes):

@@ -24,21 +24,24 @@ GEMM_GELU_FWD, GEMM_GELU_BWD = 1, 2
 class LayerCost(C.Structure):
     _fields_ = [("tf_ns", C.c_int64), ("tb_ns", C.c_int64), ("trc_ns", C.c_int64),
                 ("sav_bytes", C.c_uint64), ("out_bytes", C.c_uint64), ("ws_bytes", C.c_uint64),
-                ("w_bytes", C.c_uint64), ("g_bytes", C.c_uint64)]
+                ("w_bytes", C.c_uint64), ("g_bytes", C.c_uint64),
+                ("th_ns", C.c_int64), ("hg_bytes", C.c_uint64), ("hw_bytes", C.c_uint64)]
 
 
 class Link(C.Structure):
-    _fields_ = [("bw_h2d", C.c_uint64), ("bw_d2h", C.c_uint64), ("lat_ns", C.c_int64)]
+    _fields_ = [("bw_h2d", C.c_uint64), ("bw_d2h", C.c_uint64), ("lat_ns", C.c_int64),
+                ("bw_h2d_loaded", C.c_uint64), ("bw_d2h_loaded", C.c_uint64)]
 
 
 class LossCost(C.Structure):
-    _fields_ = [("t_ns", C.c_int64), ("ws_bytes", C.c_uint64)]
+    _fields_ = [("t_ns", C.c_int64), ("ws_bytes", C.c_uint64), ("th_ns", C.c_int64), ("hg_bytes", C.c_uint64),
+                ("hw_bytes", C.c_uint64)]
 
 
 class PlanSummary(C.Structure):
     _fields_ = [("makespan_ns", C.c_int64), ("stall_ns", C.c_int64), ("busy_ns", C.c_int64),
                 ("recompute_ns", C.c_int64), ("peak_bytes", C.c_uint64), ("bytes_d2h", C.c_uint64),
-                ("bytes_h2d", C.c_uint64)]
+                ("bytes_h2d", C.c_uint64), ("host_busy_ns", C.c_int64), ("host_end_ns", C.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}
@@ -119,8 +122,8 @@ def _check(st, where, ctx=None):
 
 # ------------------------------------------------------------------ pure planner
 def karma_simulate(layers, link, loss, budget, fixed, actions, want_ops=False, weights_kept=None):
-    """layers: sequence of (tf, tb, trc, sav, out, ws[, wb, gb]); link: (bw_h2d, bw_d2h, lat);
-    loss: (t, ws).  Returns summary dict (and ops list when asked)."""
+    """layers: sequence of (tf, tb, trc, sav, out, ws[, wb, gb[, th, hg, hw]]); link: (bw_h2d, bw_d2h, lat[,
+    bw_h2d_loaded, bw_d2h_loaded]); loss: (t, ws[, th, hg, hw]).  Returns summary dict (and ops list when asked)."""
     n = len(layers)
     arr = _layers_array(layers)
     lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
@@ -276,8 +279,9 @@ class Context:
         loss = LossCost()
         fixed = C.c_uint64()
         self._chk(lib().karma_get_costs(self.ctx, arr, C.byref(loss), C.byref(fixed)), "karma_get_costs")
-        layers = [(l.tf_ns, l.tb_ns, l.trc_ns, l.sav_bytes, l.out_bytes, l.ws_bytes, l.w_bytes, l.g_bytes) for l in arr]
-        return layers, (loss.t_ns, loss.ws_bytes), fixed.value
+        layers = [(l.tf_ns, l.tb_ns, l.trc_ns, l.sav_bytes, l.out_bytes, l.ws_bytes, l.w_bytes, l.g_bytes, l.th_ns,
+                   l.hg_bytes, l.hw_bytes) for l in arr]
+        return layers, (loss.t_ns, loss.ws_bytes, loss.th_ns, loss.hg_bytes, loss.hw_bytes), fixed.value
 
     def karma_set_costs(self, layers=None, loss=None, link=None):
         arr = _layers_array(layers) if layers is not None else None
@@ -288,7 +292,7 @@ class Context:
     def karma_measure(self, reps=3):
         lk = Link()
         self._chk(lib().karma_measure(self.ctx, C.c_uint32(reps), C.byref(lk)), "karma_measure")
-        return (lk.bw_h2d, lk.bw_d2h, lk.lat_ns)
+        return (lk.bw_h2d, lk.bw_d2h, lk.lat_ns, lk.bw_h2d_loaded, lk.bw_d2h_loaded)
 
     def karma_plan(self, budget):
         act = (C.c_uint8 * self.n_layers)()

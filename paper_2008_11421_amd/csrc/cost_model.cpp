@@ -117,10 +117,12 @@ extern "C" int karma_model_costs(const karma_model_desc* desc, const karma_devic
     k.tf_ns = time_ns(blocks[i], *rates);
     k.tb_ns = 2 * k.tf_ns;
     k.trc_ns = k.tf_ns;
+    k.th_ns = 0;   // the analytic model prices the device and the link, not the host optimiser
+    k.hg_bytes = k.hw_bytes = 0;
     layers_out[i] = k;
   }
   *n_inout = c.L;
-  if (loss_out) *loss_out = karma_loss_cost{3 * time_ns(loss, *rates), c.loss_cost.ws_bytes};
+  if (loss_out) *loss_out = karma_loss_cost{3 * time_ns(loss, *rates), c.loss_cost.ws_bytes, 0, 0, 0};
   if (fixed_out) *fixed_out = c.fixed_bytes;
   return KARMA_OK;
 }

@@ -531,10 +531,25 @@ int karma::derive_layout(Ctx& c) {
   c.misc_off = off; off += up256(c.misc_bytes);
   c.fixed_bytes = off;
   c.cost.resize(c.L);
-  for (uint32_t i = 0; i < c.L; ++i)
+  // gradients that go to the host after a record's backward and new weights that come back, for records whose
+  // weights are resident (a streamed record's are its w_total / g_total; its new weights stay on the host)
+  auto host_bytes = [](const Record& r, uint64_t& g, uint64_t& w) {
+    g = w = 0;
+    if (r.streamed) return;
+    for (const Param& p : r.p) { g += p.g_bytes(); w += p.w_bytes(); }
+  };
+  for (uint32_t i = 0; i < c.L; ++i) {
+    uint64_t hg, hw;
+    host_bytes(c.rec[i], hg, hw);
     c.cost[i] = karma_layer_cost{0, 0, 0, c.rec[i].sav_bytes, c.rec[i].out_bytes, c.rec[i].ws_bytes,
-                                  c.rec[i].streamed ? c.rec[i].w_total : 0, c.rec[i].streamed ? c.rec[i].g_total : 0};
-  c.loss_cost = karma_loss_cost{0, c.rec[c.L].ws_bytes};
+                                  c.rec[i].streamed ? c.rec[i].w_total : 0, c.rec[i].streamed ? c.rec[i].g_total : 0,
+                                  0, hg, hw};
+  }
+  {
+    uint64_t hg, hw;
+    host_bytes(c.rec[c.L], hg, hw);
+    c.loss_cost = karma_loss_cost{0, c.rec[c.L].ws_bytes, 0, hg, hw};
+  }
   return KARMA_OK;
 }
 
@@ -568,7 +583,7 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
   int st = derive_layout(*c);
   if (st) { delete c; return st; }
   if (c->fixed_bytes >= arena_bytes) { delete c; return KARMA_E_OOM; }
-  c->link = karma_link{50000000000ull, 50000000000ull, 10000};
+  c->link = karma_link{50000000000ull, 50000000000ull, 10000, 0, 0};
   // host state
   bool ok = true;
   auto pin = [&](void** p, uint64_t bytes) {
@@ -724,8 +739,9 @@ extern "C" int karma_set_costs(karma_ctx* c, const karma_layer_cost* layers, con
       c->cost[i].tf_ns = layers[i].tf_ns;
       c->cost[i].tb_ns = layers[i].tb_ns;
       c->cost[i].trc_ns = layers[i].trc_ns;
+      c->cost[i].th_ns = layers[i].th_ns;
     }
-  if (loss) c->loss_cost.t_ns = loss->t_ns;
+  if (loss) { c->loss_cost.t_ns = loss->t_ns; c->loss_cost.th_ns = loss->th_ns; }
   if (link) {
     if (!link->bw_h2d || !link->bw_d2h) return KARMA_E_INVAL;
     c->link = *link;
@@ -939,6 +955,85 @@ extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) 
     c->link.bw_h2d = (uint64_t)bw[0];
     c->link.bw_d2h = (uint64_t)bw[1];
     c->link.lat_ns = (int64_t)std::max(lat[0], lat[1]);
+  }
+  // Host optimiser (Sec. III-G, stage 5) and the link while it runs: the configured update over a scratch
+  // parameter tensor on the context's threads, with copies of both directions in flight when the arena has room
+  // for them.  Gives the loaded link rates and the update time per parameter, from which each record's th.
+  {
+    const size_t n = (size_t)16 << 20;
+    std::vector<float> w(n, 0.5f), m1(n, 0.f), m2(n, 0.f);
+    std::vector<uint16_t> g(n, 0x3c00), out(n);
+    const karma_config& cf = c->cfg;
+    auto one_pass = [&](uint64_t step) {
+      c->pool->parallel_for(n, [&](size_t lo, size_t hi) {
+        if (cf.optimizer == KARMA_OPT_ADAM)
+          adam_update(w.data() + lo, m1.data() + lo, m2.data() + lo, g.data() + lo, true, hi - lo, cf.lr, cf.beta1, cf.beta2,
+                      cf.eps, step, out.data() + lo, true);
+        else if (cf.optimizer == KARMA_OPT_SGD_MOMENTUM)
+          sgd_momentum_update(w.data() + lo, m1.data() + lo, g.data() + lo, true, hi - lo, cf.lr, cf.beta1, out.data() + lo, true);
+        else
+          sgd_update(w.data() + lo, g.data() + lo, true, hi - lo, cf.lr, out.data() + lo, true);
+      });
+    };
+    one_pass(1);   // first touch
+    char *h_in = nullptr, *h_out = nullptr;
+    hipEvent_t a0 = nullptr, a1 = nullptr, b0 = nullptr, b1 = nullptr;
+    bool copies = big >= (1u << 20);
+    if (copies && (hipHostMalloc((void**)&h_in, big, hipHostMallocDefault) != hipSuccess ||
+                   hipHostMalloc((void**)&h_out, big, hipHostMallocDefault) != hipSuccess)) {
+      (void)hipGetLastError();
+      if (h_in) (void)hipHostFree(h_in);
+      h_in = h_out = nullptr;
+      copies = false;
+    }
+    const int rounds = 8;
+    if (copies) {
+      std::memset(h_in, 0, big);
+      std::memset(h_out, 0, big);
+      KARMA_HIP(c, hipEventCreate(&a0)); KARMA_HIP(c, hipEventCreate(&a1));
+      KARMA_HIP(c, hipEventCreate(&b0)); KARMA_HIP(c, hipEventCreate(&b1));
+      char* dev = c->act_ptr(0);
+      KARMA_HIP(c, hipEventRecord(a0, c->st[1]));
+      KARMA_HIP(c, hipEventRecord(b0, c->st[2]));
+      for (int r = 0; r < rounds; ++r) {
+        KARMA_HIP(c, hipMemcpyAsync(dev, h_in, big, hipMemcpyHostToDevice, c->st[1]));
+        KARMA_HIP(c, hipMemcpyAsync(h_out, dev + big, big, hipMemcpyDeviceToHost, c->st[2]));
+      }
+      KARMA_HIP(c, hipEventRecord(a1, c->st[1]));
+      KARMA_HIP(c, hipEventRecord(b1, c->st[2]));
+    }
+    uint64_t passes = 0;
+    const double t0 = now_ms();
+    for (;;) {
+      one_pass(2 + passes);
+      ++passes;
+      if (!copies) { if (passes >= 4) break; continue; }
+      const bool in_done = hipEventQuery(a1) == hipSuccess, out_done = hipEventQuery(b1) == hipSuccess;
+      (void)hipGetLastError();
+      if (in_done || out_done) break;   // once one direction is through, the other is no longer loaded
+    }
+    const double host_ms = now_ms() - t0;
+    const double ns_per_param = host_ms * 1e6 / ((double)passes * (double)n);
+    if (copies) {
+      KARMA_HIP(c, hipEventSynchronize(a1));
+      KARMA_HIP(c, hipEventSynchronize(b1));
+      float t_in_ms = 0.f, t_out_ms = 0.f;
+      KARMA_HIP(c, hipEventElapsedTime(&t_in_ms, a0, a1));
+      KARMA_HIP(c, hipEventElapsedTime(&t_out_ms, b0, b1));
+      // never above the idle figure (the tail of the slower direction runs unloaded)
+      c->link.bw_h2d_loaded = std::min<uint64_t>(c->link.bw_h2d, (uint64_t)((double)rounds * big / (t_in_ms * 1e-3)));
+      c->link.bw_d2h_loaded = std::min<uint64_t>(c->link.bw_d2h, (uint64_t)((double)rounds * big / (t_out_ms * 1e-3)));
+      (void)hipEventDestroy(a0); (void)hipEventDestroy(a1); (void)hipEventDestroy(b0); (void)hipEventDestroy(b1);
+      (void)hipHostFree(h_in);
+      (void)hipHostFree(h_out);
+    }
+    auto th_of = [&](const Record& r) {
+      uint64_t params = 0;
+      for (const Param& p : r.p) params += p.n;
+      return (int64_t)((double)params * ns_per_param);
+    };
+    for (uint32_t i = 0; i < c->L; ++i) c->cost[i].th_ns = th_of(c->rec[i]);
+    c->loss_cost.th_ns = th_of(c->rec[c->L]);
   }
   c->have_times = true;
   if (link_out) *link_out = c->link;

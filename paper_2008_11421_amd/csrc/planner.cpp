@@ -111,6 +111,11 @@ struct Timeline {
   int64_t t_comp = 0, t_out = 0, t_in = 0, busy = 0, redo = 0;
   uint64_t moved_out = 0, moved_in = 0;
   bool failed = false;
+  // host optimiser queue (Sec. III-G, stages 3 and 5): updates in the order of the backward ops
+  struct Update { int64_t landed, t_ns; uint64_t back_bytes; };
+  std::vector<Update> updates;
+  bool hosted = false;                            // a step with host updates
+  uint64_t bw_in = 0, bw_out = 0;                 // current price of a copy (idle rates, then loaded ones)
 
   Timeline(const Problem& p, const uint8_t* a, const uint8_t* kw, std::vector<karma_op>* o)
       : P(p), act(a), keepw(kw), ops(o), L(p.n) {}
@@ -148,7 +153,7 @@ struct Timeline {
   // copy of layer i's weights into p_at[i] (already allocated)
   void fetch_weights(uint32_t i, int64_t now) {
     int64_t s = std::max(t_in, now);
-    t_in = s + copy_ns(P.layers[i].w_bytes, P.link.bw_h2d, P.link.lat_ns);
+    t_in = s + copy_ns(P.layers[i].w_bytes, bw_in, P.link.lat_ns);
     moved_in += P.layers[i].w_bytes;
     p_here[i] = t_in;
     emit('W', i, s, t_in, p_at[i], -1, -1);
@@ -162,7 +167,7 @@ struct Timeline {
     }
     int64_t nbytes = move_bytes(i);
     int64_t s = std::max(std::max(t_in, now), left[i]);   // data must have reached the host first
-    t_in = s + copy_ns((uint64_t)nbytes, P.link.bw_h2d, P.link.lat_ns);
+    t_in = s + copy_ns((uint64_t)nbytes, bw_in, P.link.lat_ns);
     moved_in += (uint64_t)nbytes;
     arrival[i] = t_in;
     emit('I', i, s, t_in, x_at[i], swapped_whole(i) ? s_at[i] : -1, -1);
@@ -212,6 +217,18 @@ struct Timeline {
     if (failed) return now;
     return std::max(now, arr[it.layer]);
   }
+  // gradients of a record with resident weights go to the host after the op that completed them; its
+  // update is queued for when they have landed
+  void grads_leave(int64_t t_ns, uint64_t out_bytes, uint64_t back_bytes, int64_t end) {
+    int64_t when = end;
+    if (out_bytes) {
+      int64_t s = std::max(t_out, end);
+      t_out = s + copy_ns(out_bytes, bw_out, P.link.lat_ns);
+      moved_out += out_bytes;
+      when = t_out;
+    }
+    if (t_ns || back_bytes) updates.push_back(Update{when, t_ns, back_bytes});
+  }
   void backward(uint32_t j, int64_t now, int64_t reserve) {
     settle(now);
     dx_at[j] = obtain(x_sz[j], false, now);
@@ -230,11 +247,14 @@ struct Timeline {
     if (g_sz[j]) {
       // the gradients leave right after the layer's backward (pipeline stage 3)
       int64_t s = std::max(t_out, end);
-      t_out = s + copy_ns(P.layers[j].g_bytes, P.link.bw_d2h, P.link.lat_ns);
+      t_out = s + copy_ns(P.layers[j].g_bytes, bw_out, P.link.lat_ns);
       moved_out += P.layers[j].g_bytes;
       outgoing.push_back(Pending{t_out, {g_at[j], 0}, {g_sz[j], 0}, 1});
       g_at[j] = -1;
       emit('G', j, s, t_out, -1, -1, -1);
+      if (P.layers[j].th_ns) updates.push_back(Update{t_out, P.layers[j].th_ns, 0});
+    } else {
+      grads_leave(P.layers[j].th_ns, P.layers[j].hg_bytes, P.layers[j].hw_bytes, end);
     }
     prefetch_ahead(t_comp, reserve);
   }
@@ -243,6 +263,10 @@ struct Timeline {
     int64_t cap = (int64_t)P.budget - (int64_t)P.fixed;
     if (cap <= 0) return false;
     arena.reset(cap);
+    hosted = P.loss.th_ns > 0;
+    for (uint32_t i = 0; i < L; ++i) hosted |= P.layers[i].th_ns > 0;
+    bw_in = P.link.bw_h2d;
+    bw_out = P.link.bw_d2h;
     x_raw.assign(L + 1, 0); x_sz.assign(L + 1, 0); s_sz.assign(L, 0); w_sz.assign(L, 0);
     p_sz.assign(L, 0); g_sz.assign(L, 0);
     for (uint32_t i = 0; i < L; ++i) {
@@ -294,7 +318,7 @@ struct Timeline {
           if (act[i] == KARMA_SWAP && s_at[i] >= 0) { p.off[p.n] = s_at[i]; p.size[p.n] = s_sz[i]; ++p.n; }
           if (nbytes) {
             int64_t s = std::max(t_out, end);
-            t_out = s + copy_ns((uint64_t)nbytes, P.link.bw_d2h, P.link.lat_ns);
+            t_out = s + copy_ns((uint64_t)nbytes, bw_out, P.link.lat_ns);
             moved_out += (uint64_t)nbytes;
             p.when = t_out;
             left[i] = t_out;
@@ -349,6 +373,12 @@ struct Timeline {
 
     // loss
     int64_t lw_sz = align_up((int64_t)P.loss.ws_bytes);
+    if (hosted) {
+      // the forward pass is over: from here on gradients stream to the host and the optimiser works
+      // on them, and every copy issued is priced at the loaded rates
+      if (P.link.bw_h2d_loaded) bw_in = P.link.bw_h2d_loaded;
+      if (P.link.bw_d2h_loaded) bw_out = P.link.bw_d2h_loaded;
+    }
     prefetch_ahead(t_comp, std::max(any, x_sz[L] + lw_sz));
     {
       int64_t now = t_comp;
@@ -362,6 +392,7 @@ struct Timeline {
       t_comp = end;
       drop(w, lw_sz);
       drop(x_at[L], x_sz[L]);
+      grads_leave(P.loss.th_ns, P.loss.hg_bytes, P.loss.hw_bytes, end);
       prefetch_ahead(t_comp, any);
     }
 
@@ -401,7 +432,17 @@ struct Timeline {
         backward((uint32_t)j, t_comp, j == (int64_t)u.head ? after[k] : std::max(after[k], u.inner));
     }
     if (failed) return false;
-    int64_t endall = std::max(t_comp, std::max(t_out, t_in));
+    // host optimiser queue; new weights of resident layers go back behind the program's own copies
+    int64_t t_host = 0, host_busy = 0;
+    for (const Update& u : updates) {
+      t_host = std::max(t_host, u.landed) + u.t_ns;
+      host_busy += u.t_ns;
+      if (u.back_bytes) {
+        t_in = std::max(t_in, t_host) + copy_ns(u.back_bytes, bw_in, P.link.lat_ns);
+        moved_in += u.back_bytes;
+      }
+    }
+    int64_t endall = std::max(std::max(t_comp, t_host), std::max(t_out, t_in));
     if (out) {
       out->makespan_ns = endall;
       out->stall_ns = t_comp - busy;
@@ -410,6 +451,8 @@ struct Timeline {
       out->peak_bytes = P.fixed + (uint64_t)arena.peak;
       out->bytes_d2h = moved_out;
       out->bytes_h2d = moved_in;
+      out->host_busy_ns = host_busy;
+      out->host_end_ns = t_host;
     }
     return true;
   }
@@ -528,11 +571,15 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
   // Eq. 10.1: recompute where it is cheaper than the swap-in it replaces
   {
     const std::vector<uint8_t> unmarked = starts[0];
+    bool hosted = P.loss.th_ns > 0;
+    for (uint32_t i = 0; i < L; ++i) hosted |= P.layers[i].th_ns > 0;
+    // swap-ins run in the backward phase
+    const uint64_t bw_swap_in = hosted && P.link.bw_h2d_loaded ? P.link.bw_h2d_loaded : P.link.bw_h2d;
     std::vector<uint8_t> cur = starts[0];
     for (int64_t i = (int64_t)L - 1; i >= 0; --i) {
       if (cur[i] != KARMA_SWAP) continue;
       uint64_t xin = i ? P.layers[i - 1].out_bytes : 0;
-      int64_t t_in = copy_ns(xin + P.layers[i].sav_bytes, P.link.bw_h2d, P.link.lat_ns);
+      int64_t t_in = copy_ns(xin + P.layers[i].sav_bytes, bw_swap_in, P.link.lat_ns);
       if (P.layers[i].trc_ns < t_in) {
         for (uint8_t a : {(uint8_t)KARMA_RC_KEEP, (uint8_t)KARMA_RC_SWAP}) {
           std::vector<uint8_t> cand = cur;
@@ -634,6 +681,7 @@ bool plan_grouped(const Problem& P, uint32_t max_group, std::vector<uint8_t>& ac
           m.sav_bytes += l.sav_bytes + (k + 1 < n ? l.out_bytes : 0);
           m.ws_bytes = std::max(m.ws_bytes, l.ws_bytes);
           m.w_bytes += l.w_bytes; m.g_bytes += l.g_bytes;
+          m.th_ns += l.th_ns; m.hg_bytes += l.hg_bytes; m.hw_bytes += l.hw_bytes;
         }
         m.out_bytes = P.layers[first + n - 1].out_bytes;
         merged.push_back(m);

@@ -154,7 +154,7 @@ def test_cnn_step_matches_oracle_and_plans_are_bit_identical(g, shift):
     # a budget that holds about half of the saved sets: plan equals the oracle's plan
     layers, loss_c, fixed = ctx.karma_get_costs()
     layers = [(1000 + 10 * i, 2000 + 10 * i, 1000 + 10 * i) + l[3:] for i, l in enumerate(layers)]
-    loss_c = (500, loss_c[1])
+    loss_c = (500,) + tuple(loss_c[1:])
     link = (2 * 10**9, 2 * 10**9, 1000)
     ctx.karma_set_costs(layers, loss_c, link)
     full = sum(l[3] + l[4] for l in layers)

@@ -76,7 +76,7 @@ def small_problem():
 def unit_costs(ctx):
     layers, loss, fixed = ctx.karma_get_costs()
     layers = [(1000 + 10 * i, 2000 + 10 * i, 1000 + 10 * i) + l[3:] for i, l in enumerate(layers)]
-    return layers, (3000, loss[1]), fixed
+    return layers, (3000,) + tuple(loss[1:]), fixed
 
 
 def test_gpt_step_matches_oracle_and_plans_are_bit_identical(g):
@@ -209,10 +209,11 @@ def test_blocks_split_into_attention_and_feed_forward_records(g):
     # planner parity on the seven records, under a budget that forces choices
     layers = [(1000 + 10 * i, 2000 + 10 * i, 1000 + 10 * i) + l[3:] for i, l in enumerate(layers)]
     link = (2 * 10**9, 2 * 10**9, 1000)
-    ctx.karma_set_costs(layers, (3000, loss_c[1]), link)
+    loss_c = (3000,) + tuple(loss_c[1:])
+    ctx.karma_set_costs(layers, loss_c, link)
     budget = fixed + int(0.55 * sum(l[3] + l[4] for l in layers)) + max(max(l[5] for l in layers), loss_c[1])
     acts, summ = ctx.karma_plan(budget)
-    ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(3000, loss_c[1]))
+    ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(*loss_c))
     assert acts == ao and summ["makespan_ns"] == so["makespan_ns"] and summ["peak_bytes"] == so["peak_bytes"]
     assert acts != [K.KEEP] * 7
     assert ctx.karma_step(ids, labels) == loss

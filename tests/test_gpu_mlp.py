@@ -78,7 +78,7 @@ def unit_costs(ctx):
     """Deterministic cost records: the library's exact byte counts with fixed times."""
     layers, loss, fixed = ctx.karma_get_costs()
     layers = [(1000, 2000, 1000) + l[3:] for l in layers]
-    return layers, (100, loss[1]), fixed
+    return layers, (100,) + tuple(loss[1:]), fixed
 
 
 def test_mlp_step_matches_oracle_and_out_of_core_is_bit_identical(g):

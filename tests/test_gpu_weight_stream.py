@@ -60,7 +60,7 @@ def test_mlp_streamed_weights_bit_identical(g):
 
     # planned under a budget: equals the oracle's plan, weights included
     layers = [(1000, 2000, 1000) + l[3:] for l in layers]
-    loss_c = (100, loss_c[1])
+    loss_c = (100,) + tuple(loss_c[1:])
     link = (10**9, 10**9, 100)
     ctx.karma_set_costs(layers, loss_c, link)
     per_layer = layers[0][3] + layers[0][4]
@@ -227,7 +227,7 @@ def test_gpt_streamed_weights_bit_identical_and_adam(g):
 
     # planned: oracle's plan, weights included
     layers = [(1000 + 10 * i, 2000 + 10 * i, 1000 + 10 * i) + l[3:] for i, l in enumerate(layers)]
-    loss_c = (3000, loss_c[1])
+    loss_c = (3000,) + tuple(loss_c[1:])
     link = (2 * 10**9, 2 * 10**9, 1000)
     ctx.karma_set_costs(layers, loss_c, link)
     per_block = layers[1][3] + layers[1][4]

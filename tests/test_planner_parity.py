@@ -20,7 +20,8 @@ def ops_equal(lib_ops, ora_ops):
 
 
 def summaries_equal(s_lib, s_ora):
-    for k in ("makespan_ns", "stall_ns", "busy_ns", "recompute_ns", "peak_bytes", "bytes_d2h", "bytes_h2d"):
+    for k in ("makespan_ns", "stall_ns", "busy_ns", "recompute_ns", "peak_bytes", "bytes_d2h", "bytes_h2d", "host_busy_ns",
+              "host_end_ns"):
         assert s_lib[k] == s_ora[k], k
 
 
@@ -124,3 +125,60 @@ def test_streamed_weights_bit_exact():
         assert al == ao and sl["wres"] == so["wres"]
         summaries_equal(sl, so)
     assert n > 100
+
+
+def with_host(layers, seed, streamed=False):
+    """Host-optimiser fields on every record: update times from a tenth of to three times the record's
+    backward time, gradient / weight bytes of resident records around the size of their output."""
+    r = [int(v) for v in si.splitmix64(seed, 4 * len(layers))]
+    out = []
+    for k, l in enumerate(layers):
+        th = l.tb * (1 + r[4 * k] % 30) // 10
+        if streamed and l.wb:
+            out.append(l._replace(th=th))
+        else:
+            out.append(l._replace(th=th, hg=64 * (1 + r[4 * k + 1] % 64), hw=32 * (1 + r[4 * k + 2] % 64)))
+    return out
+
+
+def test_host_queue_bit_exact():
+    """Simulator and planner with the host-optimiser queue and the loaded link rates (Sec. III-G, stages 3 and 5)
+    against the oracle: random vectors, then whole plans, with resident and with streamed weights."""
+    from test_oracle_weight_stream import with_weights
+    n = 0
+    for streamed in (False, True):
+        for base, link, budget, loss in cases(7, seeds=(6,), fracs=(0.45, 0.9), bwmuls=(0.5, 3.0)):
+            layers = with_weights(base, 23, scale=2.0) if streamed else base
+            layers = with_host(layers, 31, streamed)
+            if streamed:
+                budget += 2 * max(P.al(l.wb) + P.al(l.gb) for l in layers)
+            link = link._replace(bw_h2d_loaded=link.bw_h2d * 3 // 4, bw_d2h_loaded=link.bw_d2h * 2 // 3)
+            loss = loss._replace(th=77, hg=640, hw=320)
+            for vi, v in enumerate(all_vectors(7, 3, 41)):
+                wres = [(vi >> k) & 1 if layers[k].wb else 0 for k in range(7)]
+                try:
+                    so = P.simulate(layers, link, budget, 0, loss, v, want_ops=True, wres=wres)
+                except P.Infeasible:
+                    with pytest.raises(K.KarmaError) as e:
+                        K.karma_simulate(layers, link, loss, budget, 0, v, weights_kept=wres)
+                    assert e.value.status == K.E_BUDGET
+                    continue
+                sl, ops = K.karma_simulate(layers, link, loss, budget, 0, v, want_ops=True, weights_kept=wres)
+                summaries_equal(sl, so)
+                ops_equal(ops, so["ops"])
+                assert so["host_busy_ns"] == sum(l.th for l in layers) + loss.th
+                n += 1
+            try:
+                ao, so = P.plan(layers, link, budget, 0, loss)
+            except P.Infeasible:
+                with pytest.raises(K.KarmaError):
+                    K.karma_plan_pure(layers, link, loss, budget, 0)
+                continue
+            al, sl = K.karma_plan_pure(layers, link, loss, budget, 0)
+            assert al == ao and sl["wres"] == so["wres"]
+            summaries_equal(sl, so)
+            ag, sg, gg = K.karma_plan_grouped_pure(layers, link, loss, budget, 0)
+            aog, sog, gog = P.plan_grouped(layers, link, budget, 0, loss)
+            assert (ag, gg) == (aog, gog)
+            summaries_equal(sg, sog)
+    assert n > 150
