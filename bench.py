@@ -64,6 +64,32 @@ def median(xs):
     return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
+COSTS_DIR = os.path.join(ROOT, "paper_2008_11421_amd", "costs")
+
+
+def costs_file(config):
+    return os.path.join(COSTS_DIR, "configs%d_mi355x.json" % config)
+
+
+def save_costs(path, layers, loss_c, link):
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        json.dump({"what": "cost records measured once by karma_measure on an MI355X (Sec. III-D: the model is profiled "
+                           "once); bench.py plans on these so that the benchmarked plan is the same from run to run",
+                   "layers": [list(l) for l in layers], "loss": list(loss_c), "link": list(link)}, f, indent=0)
+        f.write("\n")
+
+
+def load_costs(path, n_layers):
+    try:
+        d = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    if len(d.get("layers", ())) != n_layers:
+        return None
+    return [tuple(l) for l in d["layers"]], tuple(d["loss"]), tuple(d["link"])
+
+
 def profiled_traffic(plan):
     """Bytes per GEMM launch from the committed counter summary, if it was taken on this very plan
     (lines `plan: <string>` and `gemm_traffic_bytes_per_launch: <number>`); None otherwise."""
@@ -241,7 +267,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
         "supplementary_low_budget": {"hbm_budget_gib": wl["low_budget"] // GIB, "ms_per_step": dt_lo * 1e3,
                                      "samples_per_s": batch / dt_lo, "pct_of_in_core": 100.0 * dt / dt_lo,
                                      "plan": "".join("KSRrc"[a] for a in acts_lo), "arena_peak_gib": summ_lo["peak_bytes"] / GIB,
-                                     "swap_gib_each_way": summ_lo["bytes_d2h"] / GIB,
+                                     "link_gib_d2h_total": summ_lo["bytes_d2h"] / GIB,
                                      "backward_stall_profile": {"what": STALL_NOTE, "in_core": stalls_in, "out_of_core": stalls_lo},
                                      "grouped_planner": {"group_size": group, "ms_per_step": dt_g * 1e3,
                                                          "predicted_makespan_ms": summ_g["makespan_ns"] / 1e6,
@@ -267,6 +293,10 @@ def main():
     ap.add_argument("--whole-blocks", action="store_true",
                     help="GPT workloads: one plannable record per transformer block instead of two (attention half, "
                          "feed-forward half)")
+    ap.add_argument("--costs", default="frozen", choices=("frozen", "measured"),
+                    help="plan on the committed cost records of this workload (default; falls back to this run's own "
+                         "measurements when there are none) or on this run's measurements")
+    ap.add_argument("--save-costs", action="store_true", help="write this run's measured cost records to the committed file")
     ap.add_argument("--layers", type=int, default=0,
                     help="GPT workloads: truncate the depth to this many blocks (named in config.workload)")
     args = ap.parse_args()
@@ -340,8 +370,24 @@ def main():
     link = ctx.karma_measure(3)
     layers, loss_c, fixed = ctx.karma_get_costs()
     blk = (layers[1][0] + (layers[2][0] if split else 0), layers[1][1] + (layers[2][1] if split else 0))
-    log("link h2d %.1f GB/s d2h %.1f GB/s lat %d ns; block fwd %.2f ms bwd %.2f ms; loss %.2f ms; fixed %.2f GiB"
-        % (link[0] / 1e9, link[1] / 1e9, link[2], blk[0] / 1e6, blk[1] / 1e6, loss_c[0] / 1e6, fixed / GIB))
+    log("link h2d %.1f GB/s d2h %.1f GB/s lat %d ns (while the other direction and the host optimiser run: %.1f / %.1f); "
+        "block fwd %.2f ms bwd %.2f ms; loss %.2f ms; host optimiser %.1f ms; fixed %.2f GiB"
+        % (link[0] / 1e9, link[1] / 1e9, link[2], link[3] / 1e9, link[4] / 1e9, blk[0] / 1e6, blk[1] / 1e6, loss_c[0] / 1e6,
+           (sum(l[8] for l in layers) + loss_c[2]) / 1e6, fixed / GIB))
+    # The plan this run's own measurements give, and the plan on the committed cost records (the model is profiled
+    # once, Sec. III-D): the second is what is timed, so that the benchmarked plan is the same from run to run.
+    cfile = costs_file(args.config) if not (args.layers or args.whole_blocks) else None
+    if args.save_costs and cfile:
+        save_costs(cfile, layers, loss_c, link)
+        log("cost records written to", cfile)
+    acts_own, summ_own = ctx.karma_plan(BUDGET)
+    costs_used = "measured in this run"
+    frozen = load_costs(cfile, len(layers)) if (cfile and args.costs == "frozen") else None
+    if frozen:
+        ctx.karma_set_costs(*frozen)
+        costs_used = "committed records " + os.path.relpath(cfile, ROOT)
+    log("costs: %s; plan on this run's own measurements: %s (predicted %.1f ms)"
+        % (costs_used, "".join("KSRrc"[a] for a in acts_own), summ_own["makespan_ns"] / 1e6))
 
     def timed(budget, flags):
         acts, summ = ctx.karma_plan(budget)
@@ -380,8 +426,11 @@ def main():
     stalls_in = backward_stalls(ctx, profiled_step, len(acts_in))
     acts, summ, dt, loss, gem, st = timed(BUDGET, K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
     log("%d GiB: %.1f ms/step, plan %s, weights kept %s" % (BUDGET // GIB, dt * 1e3, acts, summ.get("wres")))
-    log("predicted makespan %.1f ms, peak %.2f GiB, swap %.2f GiB each way" %
-        (summ["makespan_ns"] / 1e6, summ["peak_bytes"] / GIB, summ["bytes_d2h"] / GIB))
+    # activations that cross the link each way (the summary's totals also count streamed weights and gradients)
+    swap_bytes = sum((layers[i - 1][4] if i else 0) + (layers[i][3] if a == K.SWAP else 0)
+                     for i, a in enumerate(acts) if a in (K.SWAP, K.RC_SWAP))
+    log("predicted makespan %.1f ms (host optimiser done at %.1f ms), peak %.2f GiB, swap %.2f GiB each way" %
+        (summ["makespan_ns"] / 1e6, summ["host_end_ns"] / 1e6, summ["peak_bytes"] / GIB, swap_bytes / GIB))
 
     # one more step with events around every op: achieved host-link rate during the swaps and
     # the measured occupancy of the compute stream (Eq. 1)
@@ -471,9 +520,15 @@ def main():
         "pct_of_in_core": 100.0 * dt_in / dt,
         "loss": loss,
         "predicted_makespan_ms": summ["makespan_ns"] / 1e6,
+        "predicted_host_optimiser_end_ms": summ["host_end_ns"] / 1e6,
+        "predicted_over_measured": summ["makespan_ns"] / 1e6 / (dt * 1e3),
+        "costs": costs_used,
+        "plan_on_this_runs_measurements": {"plan": "".join("KSRrc"[a] for a in acts_own),
+                                           "predicted_makespan_ms": summ_own["makespan_ns"] / 1e6},
         "arena_peak_gib": summ["peak_bytes"] / GIB,
-        "swap_gib_each_way": summ["bytes_d2h"] / GIB,
-        "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9},
+        "swap_gib_each_way": swap_bytes / GIB,
+        "plan_moves_gib": {"d2h": summ["bytes_d2h"] / GIB, "h2d": summ["bytes_h2d"] / GIB},
+        "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9, "h2d_loaded": link[3] / 1e9, "d2h_loaded": link[4] / 1e9},
         "swap_link_achieved_gbps": link_achieved,
         "compute_occupancy_measured": occupancy,
         "compute_occupancy_predicted": summ["busy_ns"] / max(summ["busy_ns"] + summ["stall_ns"], 1),

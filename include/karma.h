@@ -93,7 +93,8 @@ typedef struct {
   int64_t busy_ns;      /* compute-queue busy time, recompute included */
   int64_t recompute_ns; /* part of busy_ns spent recomputing */
   uint64_t peak_bytes;  /* fixed + high-water mark of the arena */
-  uint64_t bytes_d2h, bytes_h2d;
+  uint64_t bytes_d2h, bytes_h2d; /* what the plan moves: swapped activations, streamed weights and their gradients
+                                    (gradients and weights of resident layers, the same under every plan, not counted) */
   int64_t host_busy_ns; /* host optimiser queue: sum of the updates, */
   int64_t host_end_ns;  /* and the end of the last one */
 } karma_plan_summary;

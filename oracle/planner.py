@@ -182,7 +182,9 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     layers with streamed weights, the per-layer choice `wres`).
 
     Returns a dict with makespan_ns, stall_ns, busy_ns, peak_bytes, bytes_d2h,
-    bytes_h2d, recompute_ns (and `ops` when asked).  Raises Infeasible when the arena
+    bytes_h2d (what the plan moves: swapped activations, streamed weights and their
+    gradients; the gradients and weights of resident layers, the same under every plan,
+    are not counted), recompute_ns, host_busy_ns, host_end_ns (and `ops` when asked).  Raises Infeasible when the arena
     cannot grant an allocation (constraint 9.4)."""
     L = len(layers)
     if not valid_actions(actions) or len(actions) != L:
@@ -412,7 +414,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     def grads_leave(rec, end, streamed_landing):
         """Gradients of a record go to the host after the op that completed them (at `end`);
         its update is queued for when they have landed."""
-        nonlocal td, d2h
+        nonlocal td
         if streamed_landing is not None:
             if rec.th:
                 landed.append((streamed_landing, rec.th, 0))
@@ -421,7 +423,6 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         if rec.hg:
             st = max(td, end)
             td = st + copy_ns(rec.hg, rate["d2h"], link.lat_ns)
-            d2h += rec.hg
             when = td
         if rec.th or rec.hw:
             landed.append((when, rec.th, rec.hw))
@@ -517,7 +518,6 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         host_busy += t_upd
         if back:    # new weights of a resident layer: behind the program's own copies
             th = max(th, t_host) + copy_ns(back, rate["h2d"], link.lat_ns)
-            h2d += back
     makespan = max(tc, td, th, t_host)
     res = dict(makespan_ns=makespan, stall_ns=tc - busy, busy_ns=busy,
                peak_bytes=fixed + ar.peak_used, bytes_d2h=d2h, bytes_h2d=h2d,

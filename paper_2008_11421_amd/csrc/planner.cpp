@@ -223,8 +223,7 @@ struct Timeline {
     int64_t when = end;
     if (out_bytes) {
       int64_t s = std::max(t_out, end);
-      t_out = s + copy_ns(out_bytes, bw_out, P.link.lat_ns);
-      moved_out += out_bytes;
+      t_out = s + copy_ns(out_bytes, bw_out, P.link.lat_ns);   // (the same under every plan: not counted as moved)
       when = t_out;
     }
     if (t_ns || back_bytes) updates.push_back(Update{when, t_ns, back_bytes});
@@ -439,7 +438,6 @@ struct Timeline {
       host_busy += u.t_ns;
       if (u.back_bytes) {
         t_in = std::max(t_in, t_host) + copy_ns(u.back_bytes, bw_in, P.link.lat_ns);
-        moved_in += u.back_bytes;
       }
     }
     int64_t endall = std::max(std::max(t_comp, t_host), std::max(t_out, t_in));
