@@ -60,12 +60,14 @@ def test_gemm_layouts(g, m, n, k, flags):
     assert np.all(np.abs(back(c32) - ref) <= 1e-5 * scale + 1e-30)
 
 
-@pytest.mark.parametrize("m,n,k", [(256, 256, 64), (4096, 4352, 64), (4096, 4352, 128), (2048, 8704, 192)])
-@pytest.mark.parametrize("flags", [0, K.GEMM_A_STRIDED | K.GEMM_B_STRIDED])
+@pytest.mark.parametrize("m,n,k", [(256, 256, 64), (4096, 4352, 64), (4096, 4352, 128), (2048, 8704, 192), (128, 256, 32),
+                                   (4096, 4352, 32), (8192, 4352, 96), (384, 768, 160)])
+@pytest.mark.parametrize("flags", [0, K.GEMM_B_STRIDED, K.GEMM_A_STRIDED | K.GEMM_B_STRIDED])
 def test_gemm_whole_tile_shapes_with_few_k_tiles(g, m, n, k, flags):
     """Shapes made of whole 256x256x64 tiles take the direct-to-LDS kernel; with one to three k-tiles
     per output tile and more output tiles than workgroups (272 > 256) its tile stream crosses from one
-    work item into the next after every one, two or three tiles."""
+    work item into the next after every one, two or three tiles.  Reductions that are no multiple of 64 (32, 96,
+    160) and row counts that are no multiple of 256 take the register-staged kernel on the same data."""
     import torch
     a, ad = bf(si.normal(11, (m, k)))
     b, bd = bf(si.normal(12, (n, k)))
