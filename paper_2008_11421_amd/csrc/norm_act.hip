@@ -32,15 +32,37 @@ __device__ __forceinline__ u32x4 pack8(const float* f) {
   for (int i = 0; i < 4; ++i) v[i] = (unsigned)f2bf_(f[2 * i]) | ((unsigned)f2bf_(f[2 * i + 1]) << 16);
   return v;
 }
+// Wavefront reductions with data-parallel-primitive moves (full-rate vector instructions; a cross-lane read
+// through the LDS crossbar costs an LDS round trip per step, and a row's two reductions are a chain of twelve).
+// Steps: the other lane of a pair, the other pair of a quad, the other quad of a half-row (row_half_mirror), the
+// other half of a row of 16 (row_mirror): every lane of a row then holds the row's value; lane 15 of rows 0 and 2
+// goes to rows 1 and 3 (row_bcast:15), lane 31 to rows 2 and 3 (row_bcast:31): lane 63 holds the wavefront's value,
+// which is read back as a scalar.  `old` is what a lane of a row that a step does not write combines with.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_from(float old, float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v), CTRL,
+                                                               ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float lane63(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_from<0xB1, 0xf>(0.f, v);    // quad_perm [1,0,3,2]
+  v += dpp_from<0x4E, 0xf>(0.f, v);    // quad_perm [2,3,0,1]
+  v += dpp_from<0x141, 0xf>(0.f, v);   // row_half_mirror
+  v += dpp_from<0x140, 0xf>(0.f, v);   // row_mirror
+  v += dpp_from<0x142, 0xa>(0.f, v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_from<0x143, 0xc>(0.f, v);   // row_bcast:31 into rows 2 and 3
+  return lane63(v);
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_from<0xB1, 0xf>(v, v));
+  v = fmaxf(v, dpp_from<0x4E, 0xf>(v, v));
+  v = fmaxf(v, dpp_from<0x141, 0xf>(v, v));
+  v = fmaxf(v, dpp_from<0x140, 0xf>(v, v));
+  v = fmaxf(v, dpp_from<0x142, 0xa>(v, v));
+  v = fmaxf(v, dpp_from<0x143, 0xc>(v, v));
+  return lane63(v);
 }
 
 constexpr float LN_EPS = 1e-5f;
