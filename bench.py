@@ -374,21 +374,6 @@ def main():
         "block fwd %.2f ms bwd %.2f ms; loss %.2f ms; host optimiser %.1f ms; fixed %.2f GiB"
         % (link[0] / 1e9, link[1] / 1e9, link[2], link[3] / 1e9, link[4] / 1e9, blk[0] / 1e6, blk[1] / 1e6, loss_c[0] / 1e6,
            (sum(l[8] for l in layers) + loss_c[2]) / 1e6, fixed / GIB))
-    # The plan this run's own measurements give, and the plan on the committed cost records (the model is profiled
-    # once, Sec. III-D): the second is what is timed, so that the benchmarked plan is the same from run to run.
-    cfile = costs_file(args.config) if not (args.layers or args.whole_blocks) else None
-    if args.save_costs and cfile:
-        save_costs(cfile, layers, loss_c, link)
-        log("cost records written to", cfile)
-    acts_own, summ_own = ctx.karma_plan(BUDGET)
-    costs_used = "measured in this run"
-    frozen = load_costs(cfile, len(layers)) if (cfile and args.costs == "frozen") else None
-    if frozen:
-        ctx.karma_set_costs(*frozen)
-        costs_used = "committed records " + os.path.relpath(cfile, ROOT)
-    log("costs: %s; plan on this run's own measurements: %s (predicted %.1f ms)"
-        % (costs_used, "".join("KSRrc"[a] for a in acts_own), summ_own["makespan_ns"] / 1e6))
-
     def timed(budget, flags):
         acts, summ = ctx.karma_plan(budget)
         for _ in range(args.warmup):
@@ -424,6 +409,25 @@ def main():
     log("in-core: %.1f ms/step (host optimiser %.1f ms), plan all-keep=%s" % (dt_in * 1e3, st_in["host_opt_ms"], acts_in == [0] * len(acts_in)))
     profiled_step = lambda: ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER | K.STEP_PROFILE)
     stalls_in = backward_stalls(ctx, profiled_step, len(acts_in))
+    # host-update times as the in-core steps above measured them on the real master weights and moments
+    ctx.karma_refine_host_costs()
+    layers, loss_c, fixed = ctx.karma_get_costs()
+    log("host optimiser per step, from the steps themselves: %.1f ms" % ((sum(l[8] for l in layers) + loss_c[2]) / 1e6))
+    # The plan this run's own measurements give, and the plan on the committed cost records (the model is profiled
+    # once, Sec. III-D): the second is what is timed, so that the benchmarked plan is the same from run to run.
+    cfile = costs_file(args.config) if not (args.layers or args.whole_blocks) else None
+    if args.save_costs and cfile:
+        save_costs(cfile, layers, loss_c, link)
+        log("cost records written to", cfile)
+    acts_own, summ_own = ctx.karma_plan(BUDGET)
+    costs_used = "measured in this run"
+    frozen = load_costs(cfile, len(layers)) if (cfile and args.costs == "frozen") else None
+    if frozen:
+        ctx.karma_set_costs(*frozen)
+        costs_used = "committed records " + os.path.relpath(cfile, ROOT)
+    log("costs: %s; plan on this run's own measurements: %s (predicted %.1f ms)"
+        % (costs_used, "".join("KSRrc"[a] for a in acts_own), summ_own["makespan_ns"] / 1e6))
+
     acts, summ, dt, loss, gem, st = timed(BUDGET, K.STEP_APPLY_OPTIMIZER | K.STEP_KERNEL_TIMES)
     log("%d GiB: %.1f ms/step, plan %s, weights kept %s" % (BUDGET // GIB, dt * 1e3, acts, summ.get("wres")))
     # activations that cross the link each way (the summary's totals also count streamed weights and gradients)

@@ -270,10 +270,16 @@ int karma_model_costs(const karma_model_desc* desc, const karma_device_rates* ra
  * entries.  fixed_out: bytes resident for the whole step (weights, gradients, inputs). */
 int karma_get_costs(karma_ctx* ctx, karma_layer_cost* layers_out, karma_loss_cost* loss_out,
                     uint64_t* fixed_out);
-/* Measures per-layer forward/backward/recompute times (in-core, median of `reps`) and the
- * pinned-copy bandwidth of both directions (Sec. III-D: profiled once per model).  Needs
- * arena_bytes large enough for one layer in-core. */
+/* Measures per-layer forward/backward/recompute times (in-core, median of `reps`), the
+ * pinned-copy bandwidth of both directions, alone and while the other direction copies and the host
+ * optimiser runs, and the host optimiser's rate on a scratch tensor, from which every record's th_ns
+ * (Sec. III-D: profiled once per model).  Needs arena_bytes large enough for one layer in-core. */
 int karma_measure(karma_ctx* ctx, uint32_t reps, karma_link* link_out);
+/* Replaces every record's th_ns by the time its host update actually took the last time it ran in a step
+ * with KARMA_STEP_APPLY_OPTIMIZER (on the real master weights and moments, whose working set can be far
+ * larger than the scratch tensor karma_measure times: 200 GB for the largest workload).  Records that have
+ * not been updated yet keep their value.  KARMA_E_STATE if no update has run. */
+int karma_refine_host_costs(karma_ctx* ctx);
 /* Overrides measured figures (tests, reproducible plans). */
 int karma_set_costs(karma_ctx* ctx, const karma_layer_cost* layers, const karma_loss_cost* loss,
                     const karma_link* link);

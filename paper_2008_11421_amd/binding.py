@@ -294,6 +294,9 @@ class Context:
         self._chk(lib().karma_measure(self.ctx, C.c_uint32(reps), C.byref(lk)), "karma_measure")
         return (lk.bw_h2d, lk.bw_d2h, lk.lat_ns, lk.bw_h2d_loaded, lk.bw_d2h_loaded)
 
+    def karma_refine_host_costs(self):
+        self._chk(lib().karma_refine_host_costs(self.ctx), "karma_refine_host_costs")
+
     def karma_plan(self, budget):
         act = (C.c_uint8 * self.n_layers)()
         kept = (C.c_uint8 * self.n_layers)()

@@ -114,6 +114,7 @@ struct Ctx {
   // Host updates a step left for later (Sec. III-G, stage 5 overlapped with the next iteration): per record
   // the step number its update belongs to, 0 = none.  The gradients are already in pinned host memory.
   std::vector<uint64_t> pending_update;
+  std::vector<int64_t> update_ns;   // per record: duration of its last host update (0 = none yet)
   hipEvent_t weights_uploaded = nullptr;  // recorded on the H2D stream after a late update's weight copies
   hipEvent_t program_h2d_done = nullptr;  // recorded on the H2D stream behind the last copy of a step's program
   karma_step_stats stats{};

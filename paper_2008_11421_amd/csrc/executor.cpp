@@ -329,6 +329,7 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed, uint64_t step, bo
   // streamed records: the whole gradient buffer arrives with one copy of the program, and
   // the new weights stay in pinned memory for the next step's copy-in
   if (streamed && !landed) KARMA_HIP(c, hipEventSynchronize(grads_landed));
+  double spent_ms = 0.0;
   for (Param& p : c->rec[r].p) {
     const uint64_t gs = p.grad_bf16 ? 2 : 4, ws = p.dev_bf16 ? 2 : 4;
     for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
@@ -347,12 +348,15 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed, uint64_t step, bo
         else
           sgd_update(p.master.data() + base + lo, gp, p.grad_bf16, hi - lo, g.lr, wp, p.dev_bf16);
       });
-      c->stats.host_opt_ms += now_ms() - t0;
+      const double dt = now_ms() - t0;
+      c->stats.host_opt_ms += dt;
+      spent_ms += dt;
       if (!streamed)
         KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off + base * ws, (char*)p.stage_w + base * ws, n * ws,
                                     hipMemcpyHostToDevice, c->st[1]));
     }
   }
+  if (r < c->update_ns.size()) c->update_ns[r] = (int64_t)(spent_ms * 1e6);
   return KARMA_OK;
 }
 
@@ -640,6 +644,7 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
     }
   if (!ok) { karma_destroy(c); return KARMA_E_HOSTMEM; }
   c->pending_update.assign(c->rec.size(), 0);
+  c->update_ns.assign(c->rec.size(), 0);
   if (hipEventCreateWithFlags(&c->weights_uploaded, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&c->program_h2d_done, hipEventDisableTiming) != hipSuccess) {
     karma_destroy(c);
@@ -748,6 +753,20 @@ extern "C" int karma_set_costs(karma_ctx* c, const karma_layer_cost* layers, con
   }
   c->have_times = true;
   return KARMA_OK;
+}
+
+extern "C" int karma_refine_host_costs(karma_ctx* c) {
+  if (!c) return KARMA_E_INVAL;
+  int st = finish_all_updates(c);   // updates a step left pending are timed when they run
+  if (st) return st;
+  bool any = false;
+  for (uint32_t r = 0; r < c->update_ns.size(); ++r) {
+    if (c->update_ns[r] <= 0) continue;
+    any = true;
+    if (r < c->L) c->cost[r].th_ns = c->update_ns[r];
+    else c->loss_cost.th_ns = c->update_ns[r];
+  }
+  return any ? KARMA_OK : fail(c, KARMA_E_STATE, "karma_refine_host_costs: no host update has run yet");
 }
 
 extern "C" int karma_plan(karma_ctx* c, uint64_t budget, uint8_t* actions_out, uint8_t* weights_kept_out,
