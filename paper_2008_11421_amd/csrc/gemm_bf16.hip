@@ -326,7 +326,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
 // The tile stream is continuous across work items: while the last k-tile of an item is being
 // multiplied, the first k-tile of the next item is already landing in the other stage; the
 // epilogue's fp32 strip aliases the stage of the last tile (plus a small margin).
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0>
+// EDGE: the matrix need not be made of whole tiles.  Pieces of an operand tile that lie outside the matrix are
+// not fetched (their lanes are masked out of the direct load) and their 16 bytes of LDS are zeroed instead, so
+// that the products they enter vanish; results outside the matrix are not stored.
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0, bool EDGE = false>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                          int M, int N, int K, int lda, int ldb, int tiles_m,
                                                                          int tiles_n, int splits, int k_per_split,
@@ -392,21 +395,45 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   // element offset of an item's k-tile 0 (the same in every lane)
   auto a_origin = [&](int m0, int kb) { return A_KC ? (size_t)m0 * lda + kb : (size_t)kb * lda + m0; };
   auto b_origin = [&](int n0, int kb) { return B_KC ? (size_t)n0 * ldb + kb : (size_t)kb * ldb + n0; };
-  auto issue_a = [&](int stage, size_t ao, int t) {
+  // EDGE: where piece i of this lane lies inside a tile: (row of the operand, k) for a k-contiguous tile,
+  // (k, first of its eight rows) for a strided one; `rows` is how many rows the operand has from the tile's
+  // first row on, `ks` how many k are left from the tile's first k on
+  auto piece_inside = [&](bool kc, int rowbase, int i, int rows, int ks) {
+    const int odd = i & 1;
+    if (kc) {
+      const int r = rowbase + i * 8, k = ((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) * 8;
+      return r < rows && k < ks;
+    }
+    const int k = rowbase + i * 2, r = ((lane & 31) ^ ((2 * odd + (lane >> 5)) << 2)) * 8;
+    return r < rows && k < ks;
+  };
+  auto fetch_piece = [&](const bf16_t* base, unsigned off, unsigned lds, bool inside) {
+    if (!EDGE) {
+      load_to_lds16_s(base, off, lds);
+    } else if (inside) {
+      load_to_lds16_s(base, off, lds);
+    } else {
+      *(KARMA_LDS(u32x4)*)(uintptr_t)(lds + 16 * lane) = u32x4{0, 0, 0, 0};
+    }
+  };
+  // m0 / n0: the tile's first row of the operand; k0: the item's first k; kend: its last k + 1 (EDGE only)
+  auto issue_a = [&](int stage, size_t ao, int t, int m0 = 0, int k0 = 0, int kend = 0) {
     const unsigned sa = lds0 + EXTRA + stage * STAGE + wave * (CH_A * 1024);
     const bf16_t* pa = A + ao + (A_KC ? (size_t)t * BK : (size_t)t * BK * lda);
 #pragma unroll
-    for (int i = 0; i < CH_A; ++i) load_to_lds16_s(pa, a_off[i], sa + i * 1024);
+    for (int i = 0; i < CH_A; ++i)
+      fetch_piece(pa, a_off[i], sa + i * 1024, !EDGE || piece_inside(A_KC, a_row, i, M - m0, kend - k0 - t * BK));
   };
-  auto issue_b = [&](int stage, size_t bo, int t) {
+  auto issue_b = [&](int stage, size_t bo, int t, int n0 = 0, int k0 = 0, int kend = 0) {
     const unsigned sb = lds0 + EXTRA + stage * STAGE + A_BYTES + wave * (CH_B * 1024);
     const bf16_t* pb = B + bo + (B_KC ? (size_t)t * BK : (size_t)t * BK * ldb);
 #pragma unroll
-    for (int i = 0; i < CH_B; ++i) load_to_lds16_s(pb, b_off[i], sb + i * 1024);
+    for (int i = 0; i < CH_B; ++i)
+      fetch_piece(pb, b_off[i], sb + i * 1024, !EDGE || piece_inside(B_KC, b_row, i, N - n0, kend - k0 - t * BK));
   };
-  auto issue = [&](int stage, size_t ao, size_t bo, int t) {
-    issue_a(stage, ao, t);
-    issue_b(stage, bo, t);
+  auto issue = [&](int stage, size_t ao, size_t bo, int t, int m0 = 0, int n0 = 0, int k0 = 0, int kend = 0) {
+    issue_a(stage, ao, t, m0, k0, kend);
+    issue_b(stage, bo, t, n0, k0, kend);
   };
 
   // ---- LDS side: fragment addresses (bytes from the start of the operand's tile).
@@ -451,10 +478,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   decode(pos, m0, n0, kb, ke, split);
   size_t ao = a_origin(m0, kb), bo = b_origin(n0, kb);
   int s0 = 0;   // stage of the current item's first k-tile
-  issue(s0, ao, bo, 0);
+  issue(s0, ao, bo, 0, m0, n0, kb, ke);
 
   for (;;) {
-    const int KT = (ke - kb) / BK;
+    const int KT = EDGE ? (ke - kb + BK - 1) / BK : (ke - kb) / BK;
     // the next item, whose first k-tile is fetched while this one is still computing
     int m0n = 0, n0n = 0, kbn = 0, ken = 0, splitn = 0;
     const bool have_next = valid(pos + xcd_step);
@@ -465,8 +492,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
       bon = b_origin(n0n, kbn);
     }
     lds_barrier_visible();   // the previous item's strip (which overlays stage s0 ^ 1) has been read out by every wavefront
-    if (KT > 1) issue(s0 ^ 1, ao, bo, 1);
-    else if (have_next) issue(s0 ^ 1, aon, bon, 0);
+    if (KT > 1) issue(s0 ^ 1, ao, bo, 1, m0, n0, kb, ke);
+    else if (have_next) issue(s0 ^ 1, aon, bon, 0, m0n, n0n, kbn, ken);
     if (KT > 1 || have_next) wait_vm<LPT>();   // everything older than the loads just issued: tile 0 has landed
     else wait_vm<0>();
     lds_barrier_visible();
@@ -504,13 +531,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
           // fetched before this step's MFMAs), so the tile after next goes into it at once.
           wait_vm<0>();
           lds_barrier_visible();
-          if (kt + 2 < KT) issue_a(st, ao, kt + 2);
-          else if (have_next) issue_a(st, aon, 0);
+          if (kt + 2 < KT) issue_a(st, ao, kt + 2, m0, kb, ke);
+          else if (have_next) issue_a(st, aon, 0, m0n, kbn, ken);
           __builtin_amdgcn_sched_barrier(0);
         }
         if (kk == KSTEPS - 1 && more) {
-          if (kt + 2 < KT) issue_b(st, bo, kt + 2);
-          else if (have_next) issue_b(st, bon, 0);
+          if (kt + 2 < KT) issue_b(st, bo, kt + 2, n0, kb, ke);
+          else if (have_next) issue_b(st, bon, 0, n0n, kbn, ken);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -534,7 +561,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
     const bool fetch_in = ein != nullptr && splits == 1 && (ep.ldc & 7) == 0;
     const int n = n0 + wn * WTN + q * 8;
     auto fetch = [&](int i, int pass) {
-      return *(const u32x4*)(ein + (size_t)(m0 + wm * WTM + i * 32 + pass * RPI + rr) * ep.ldc + n);
+      const int m = m0 + wm * WTM + i * 32 + pass * RPI + rr;
+      if (EDGE && (m >= M || n >= N)) return u32x4{0, 0, 0, 0};
+      return *(const u32x4*)(ein + (size_t)m * ep.ldc + n);
     };
     u32x4 pre[PASSES];
 #pragma unroll
@@ -557,14 +586,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
         const int m = m0 + wm * WTM + i * 32 + row;
         const float4 v = *(const float4*)(strip + row * SP + q * 8);
         const float4 u = *(const float4*)(strip + row * SP + q * 8 + 4);
+        const bool inside = !EDGE || (m < M && n < N);
         if (splits > 1) {
-          float* dst = partial + ((size_t)split * M + m) * N + n;
-          *(float4*)dst = v;
-          *(float4*)(dst + 4) = u;
+          if (inside) {
+            float* dst = partial + ((size_t)split * M + m) * N + n;
+            *(float4*)dst = v;
+            *(float4*)(dst + 4) = u;
+          }
         } else {
           const u32x4 cur = pre[pass];
           if (fetch_in && i + 1 < TM) pre[pass] = fetch(i + 1, pass);
-          ep.template octet<ACT>(m, n, 8, v, u, fetch_in, cur, col_sums, cs);
+          // (rows outside the matrix were multiplied from zeroed operand rows: they add nothing to the column sums)
+          if (inside) ep.template octet<ACT>(m, n, 8, v, u, fetch_in, cur, col_sums, cs);
         }
       }
     }
@@ -576,7 +609,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
         cs[e] += __shfl_xor(cs[e], 16, 64);
         cs[e] += __shfl_xor(cs[e], 32, 64);
       }
-      if (rr == 0) {
+      if (rr == 0 && (!EDGE || n < N)) {
         float* dst = ep.colsum + ((size_t)(m0 / BM) * WGM + wm) * N + n;
         *(float4*)dst = make_float4(cs[0], cs[1], cs[2], cs[3]);
         *(float4*)(dst + 4) = make_float4(cs[4], cs[5], cs[6], cs[7]);
@@ -659,7 +692,7 @@ static int compute_units() {
   return g_cus;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, bool EDGE>
 static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 block, int tiles_m, int tiles_n, int splits,
                           int k_per_split, const GemmEpilogue& ep) {
   if constexpr (BM == 256 && BN == 256 && BK == 64) {
@@ -668,7 +701,7 @@ static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 bloc
     const int lds = 2 * STAGE + 2 * EXTRA;
 #define KARMA_DL_LAUNCH(AK, BKC, ACT)                                                                             \
   do {                                                                                                            \
-    auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC, ACT>;                                          \
+    auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC, ACT, EDGE>;                                    \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);                \
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits, \
                        k_per_split, ep, (float*)g.ws);                                                            \
@@ -722,19 +755,23 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
                        k_per_split, ep, (float*)g.ws, g.conv);                                          \
   } while (0)
   // whole tiles, 16-byte aligned rows: the direct-to-LDS kernel
-  bool direct = false;
+  bool direct = false, whole = false;
   if (!CONVS && BM == 256 && BN == 256 && BK == 64 && WGM == 2 && WGN == 4) {
     // (a lane's piece offsets inside a tile are kept as 32-bit byte counts)
-    direct = g.M % BM == 0 && g.N % BN == 0 && g.K % BK == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
-             ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (splits == 1 || g.N % 4 == 0) &&
-             (uint64_t)g.lda * 2 * 256 < (1ull << 31) && (uint64_t)g.ldb * 2 * 256 < (1ull << 31);
+    direct = g.M % 8 == 0 && g.N % 8 == 0 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
+             ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && g.ldc % 8 == 0 &&
+             (uint64_t)g.lda * 2 * 256 < (1ull << 31) && (uint64_t)g.ldb * 2 * 256 < (1ull << 31) &&
+             // tiles that hang over the matrix pay for a whole tile: worth it when most of the work lies inside
+             g.M >= BM && g.N >= BN && g.K >= 2 * BK;
+    whole = g.M % BM == 0 && g.N % BN == 0 && g.K % BK == 0;
   }
   if (direct) {
     if (g.act == 2 && g.colsum_partial && splits == 1 && g.ldc == g.N) {
       ep.colsum = g.colsum_partial;
       if (g.colsum_rows) *g.colsum_rows = tiles_m * WGM;
     }
-    launch_direct<BM, BN, BK, WGM, WGN>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
+    if (whole) launch_direct<BM, BN, BK, WGM, WGN, false>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
+    else launch_direct<BM, BN, BK, WGM, WGN, true>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
   } else if (CONVS) {   // the convolution variants exist for one tile shape only
     if (g.conv_mode == 1) KARMA_GEMM_LAUNCH(true, true, (CONVS ? 1 : 0), 0);
     else KARMA_GEMM_LAUNCH(false, false, (CONVS ? 2 : 0), 0);

@@ -259,7 +259,9 @@ struct Timeline {
   }
 
   bool run(karma_plan_summary* out) {
-    int64_t cap = (int64_t)P.budget - (int64_t)P.fixed;
+    // whole alignment units: buffers carved from the high end then start on 256-byte boundaries too, so that
+    // which kernel a shape takes (some need 16-byte aligned operands) never depends on the budget
+    int64_t cap = ((int64_t)P.budget - (int64_t)P.fixed) / 256 * 256;
     if (cap <= 0) return false;
     arena.reset(cap);
     hosted = P.loss.th_ns > 0;
