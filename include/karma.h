@@ -135,7 +135,9 @@ int karma_simulate(const karma_layer_cost* layers, uint32_t n_layers, const karm
                    karma_op* ops_out, uint32_t* n_ops_inout);
 
 /* The planner (Sec. III-E capacity rule, Eq. 10.1 recompute marking, makespan
- * refinement by local search over the simulator; then, for layers with streamed weights,
+ * refinement by local search over the simulator, which starts with a feasibility phase when
+ * none of the start patterns fits: an assignment that does not fit is measured by how many
+ * compute ops its timeline completes before an allocation fails; then, for layers with streamed weights,
  * the capacity rule applied to weights: going down from the last layer, a layer keeps
  * its weights between F_i and B_i while that fits and does not lengthen the step).
  * Writes n_layers actions and, when weights_kept_out is not NULL, n_layers bytes.
@@ -154,6 +156,40 @@ int karma_plan_grouped_pure(const karma_layer_cost* layers, uint32_t n_layers, c
                             const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes, uint32_t max_group,
                             uint8_t* actions_out, uint8_t* weights_kept_out, karma_plan_summary* summary_out,
                             uint32_t* group_out);
+
+/* ---- the same three calls for a model with connections between non-consecutive layers
+ * (Sec. III-F.3: residual connections that cross blocks, connections from the contracting to
+ * the expansive path of a fully convolutional network).  skips (host, n_skips entries, may be
+ * NULL when n_skips is 0): the output of layer src, which is the input x_s of layer s = src + 1,
+ * is read again by layer dst >= src + 2, in its forward and in its backward pass.  x_s follows
+ * the action of layer s: kept, or kept as a recompute checkpoint, it is still there; swapped
+ * out, it needs a premature swap-in on the host-to-device queue before F_dst (queued one layer
+ * ahead of its first reader when memory allows, else at the reader, which waits) and then stays
+ * until B_s, whose own swap-in brings only the internals; it cannot be KARMA_RC_CHAIN (a chained
+ * layer drops its input).  B_dst leaves a gradient for x_s that is held, from the first such
+ * backward, until B_s adds it to its own.  The planner searches two more neighbourhoods when
+ * connections are present (four consecutive layers; one layer forced and the rest descending).
+ * karma_simulate_graph writes at most 8*n_layers + 2 + n_skips ops.
+ * Errors as the plain calls; KARMA_E_INVAL also for a connection with dst < src + 2 or
+ * dst >= n_layers, and for an action vector that chains a read-again input. */
+typedef struct {
+  uint32_t src, dst;
+} karma_skip;
+int karma_simulate_graph(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                         const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
+                         const karma_skip* skips, uint32_t n_skips, const uint8_t* actions,
+                         const uint8_t* weights_kept, karma_plan_summary* summary_out, karma_op* ops_out,
+                         uint32_t* n_ops_inout);
+int karma_plan_graph(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                     const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
+                     const karma_skip* skips, uint32_t n_skips, uint8_t* actions_out, uint8_t* weights_kept_out,
+                     karma_plan_summary* summary_out);
+/* Block level: a connection is kept between blocks when its source is the last member of its block
+ * and its reader sits at least two blocks on; every expansion is priced per layer with all of them. */
+int karma_plan_grouped_graph(const karma_layer_cost* layers, uint32_t n_layers, const karma_link* link,
+                             const karma_loss_cost* loss, uint64_t budget_bytes, uint64_t fixed_bytes,
+                             const karma_skip* skips, uint32_t n_skips, uint32_t max_group, uint8_t* actions_out,
+                             uint8_t* weights_kept_out, karma_plan_summary* summary_out, uint32_t* group_out);
 
 /* Algorithm 1's output in the paper's notation ("F1 -> F2||S1^out -> ...", layers
  * 1-based, recompute printed as F; copies of streamed weights and of their gradients

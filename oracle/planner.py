@@ -38,6 +38,19 @@ isolation.  (An executor may hide that tail under the next step's forward pass; 
 does not count on it.)  Copies issued after the forward pass are priced at the link's loaded
 rates.
 
+Connections between non-consecutive layers (Sec. III-F.3: residual networks, fully
+convolutional networks with connections from the contracting to the expansive path): a
+skip (src, dst), dst >= src + 2, says that the output of layer src, which is the input x_s
+of layer s = src + 1, is read again by layer dst, in its forward and in its backward pass.
+x_s follows the action of layer s.  Kept, or kept as a recompute checkpoint, it is simply
+still there.  Swapped out after F_s, it has to come back before F_dst: a premature
+swap-in on the host-to-device queue during the forward pass (issued one layer ahead of
+dst when it can be placed then), after which it stays until B_s (only the internals of s
+are left to fetch for the backward pass).  A chained layer's input is dropped, so the
+input of a layer that something else reads again cannot be RC_CHAIN.  In the backward pass
+B_dst leaves a gradient with respect to x_s, which is held (high end) until B_s adds it
+to its own.
+
 Weight streaming (Sec. III-G: a swapped block carries its weights; stage 3 of the
 pipeline swaps a block's gradients out after its backward while earlier blocks are
 swapped in): a layer with wb > 0 keeps its weights on the host.  They are copied in
@@ -77,7 +90,11 @@ Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN WI
 
 
 class Infeasible(Exception):
-    pass
+    """The arena could not grant an allocation.  `progress` = compute ops (F, L, R, B) completed before that."""
+
+    def __init__(self, progress=0):
+        super().__init__(progress)
+        self.progress = progress
 
 
 def al(b):
@@ -150,7 +167,7 @@ class Arena:
         self.used -= size
 
 
-def valid_actions(actions):
+def valid_actions(actions, skips=()):
     prev = KEEP
     for i, a in enumerate(actions):
         if not 0 <= a < N_ACTIONS:
@@ -158,7 +175,14 @@ def valid_actions(actions):
         if a == RC_CHAIN and (i == 0 or prev not in (RC_KEEP, RC_SWAP, RC_CHAIN)):
             return False
         prev = a
+    for src, dst in skips:
+        if src + 1 < len(actions) and actions[src + 1] == RC_CHAIN:
+            return False        # the tensor another layer reads again would be dropped
     return True
+
+
+def valid_skips(skips, L):
+    return all(0 <= src and src + 2 <= dst < L for src, dst in skips)
 
 
 def backward_units(actions):
@@ -177,9 +201,10 @@ def backward_units(actions):
     return units
 
 
-def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=None):
+def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=None, skips=()):
     """Timeline of one training step under a given per-layer action vector (and, for
-    layers with streamed weights, the per-layer choice `wres`).
+    layers with streamed weights, the per-layer choice `wres`; `skips`: connections
+    (src, dst) between non-consecutive layers).
 
     Returns a dict with makespan_ns, stall_ns, busy_ns, peak_bytes, bytes_d2h,
     bytes_h2d (what the plan moves: swapped activations, streamed weights and their
@@ -187,12 +212,13 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     are not counted), recompute_ns, host_busy_ns, host_end_ns (and `ops` when asked).  Raises Infeasible when the arena
     cannot grant an allocation (constraint 9.4)."""
     L = len(layers)
-    if not valid_actions(actions) or len(actions) != L:
+    if len(actions) != L or not valid_skips(skips, L) or not valid_actions(actions, skips):
         raise ValueError("invalid action vector")
-    cap = budget - fixed
+    cap = (budget - fixed) // ALIGN * ALIGN     # whole alignment units: offsets from either end stay aligned
     if cap <= 0:
         raise Infeasible()
     ar = Arena(cap)
+    done = [0]                # compute ops completed
     # xb[i] = aligned bytes of x_i, the input of layer i; x_0 is the step input and
     # lives in the fixed region, x_L feeds the loss.
     xraw = [0] + [layers[i].out for i in range(L)]
@@ -220,6 +246,19 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     hosted = loss.th > 0 or any(l.th > 0 for l in layers)   # a step with host updates
     rate = {"h2d": link.bw_h2d, "d2h": link.bw_d2h}          # current price of a copy
     landed = []               # (time the gradients are on the host, th, hw) in landing order
+    # connections between non-consecutive layers: readers[s] = the layers that read x_s again
+    readers = {}
+    for src, dst in skips:
+        readers.setdefault(src + 1, set()).add(dst)
+    early_at, early_need, early_arr = {}, {}, {}   # premature swap-ins: where issued, where needed, arrival
+    extra = [0] * L           # bytes of skip gradients first allocated by B_j
+    for s_, ds in sorted(readers.items()):
+        first, last = min(ds), max(ds)
+        extra[last] += xb[s_]
+        if actions[s_] in (SWAP, RC_SWAP) and xraw[s_]:
+            early_at.setdefault(first - 1 if first - 1 > s_ else first, []).append(s_)
+            early_need.setdefault(first, []).append(s_)
+    DSK = {}                  # offset of the gradient w.r.t. x_s left by its readers, until B_s
 
     def apply_pending(t):
         while pending and pending[0][0] <= t:
@@ -235,7 +274,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             if off is not None:
                 return off, t
             if not pending:
-                raise Infeasible()
+                raise Infeasible(done[0])
             tm, bufs = pending.popleft()
             for o, s in bufs:
                 ar.release(o, s)
@@ -256,10 +295,34 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         if want_ops:
             ops.append(Op("WIN", i, st, th, (W[i],)))
 
+    def early_in(s_, t, must):
+        """Premature swap-in of x_s for a forward reader; `must`: the reader is next, wait for memory."""
+        nonlocal th, h2d
+        if s_ in early_arr:
+            return t
+        if must:
+            X[s_], t = grant(xb[s_], True, t)
+        else:
+            X[s_] = ar.alloc(xb[s_], True)
+            if X[s_] is None:
+                return t
+        st = max(th, t, out_end[s_])
+        th = st + copy_ns(xraw[s_], rate["h2d"], link.lat_ns)
+        h2d += xraw[s_]
+        early_arr[s_] = th
+        if want_ops:
+            ops.append(Op("IN", s_, st, th, (X[s_], None)))
+        return t
+
     # ---------------- forward ----------------
     for i in range(L):
         t = tc
         apply_pending(t)
+        for s_ in early_at.get(i, ()):
+            t = early_in(s_, t, i in readers[s_])
+        for s_ in early_need.get(i, ()):
+            t = early_in(s_, t, True)
+            t = max(t, early_arr[s_])
         if wB[i] and W[i] is None:      # not prefetched: fetched now, the layer waits
             W[i], t = grant(wB[i], bool(wres[i]), t)
             weight_in(i, t)
@@ -275,6 +338,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
                 weight_in(i + 1, t)
         end = t + layers[i].tf
         busy += layers[i].tf
+        done[0] += 1
         if want_ops:
             ops.append(Op("F", i, t, end, (X[i + 1], S[i], w)))
         tc = end
@@ -311,8 +375,13 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     # tensors of layer i, ("W", i) = the weights of a layer that did not keep them.
     units = backward_units(actions)
     items = deque()
+    def in_bytes(i):
+        """What the backward swap-in of layer i still has to bring (x_i is there already after a premature swap-in)."""
+        x_part = 0 if i in early_arr else xraw[i]
+        return x_part + (layers[i].sav if actions[i] == SWAP else 0)
+
     for h, e in units:
-        if (actions[h] == SWAP and xraw[h] + layers[h].sav) or (actions[h] == RC_SWAP and xraw[h]):
+        if actions[h] in (SWAP, RC_SWAP) and in_bytes(h):
             items.append(("A", h))
         for j in range(h, e + 1):
             if wB[j] and not wres[j]:
@@ -321,9 +390,9 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
 
     def unit_need(h, e):
         if actions[h] in (KEEP, SWAP):
-            return xb[h] + wsb[h] + gB[h]
+            return xb[h] + wsb[h] + gB[h] + extra[h]
         s = sum(sb[j] for j in range(h, e + 1)) + sum(xb[j + 1] for j in range(h, e))
-        return s + max(xb[j] + wsb[j] + gB[j] for j in range(h, e + 1))
+        return s + max(xb[j] + wsb[j] + gB[j] + extra[j] for j in range(h, e + 1))
 
     needs = [unit_need(h, e) for h, e in units]
     res_after = [0] * len(units)
@@ -336,7 +405,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         kind, i = it
         if kind == "W":
             return wB[i]
-        return xb[i] + (sb[i] if actions[i] == SWAP else 0)
+        return (0 if i in early_arr else xb[i]) + (sb[i] if actions[i] == SWAP else 0)
 
     def place(it):
         """Try to allocate the buffers of a queued copy (low end); roll back on
@@ -349,7 +418,8 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             W[i] = off
             return True
         xo = so = None
-        if xb[i]:
+        fetch_x = i not in early_arr
+        if fetch_x and xb[i]:
             xo = ar.alloc(xb[i], True)
             if xo is None:
                 return False
@@ -359,7 +429,8 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
                 if xo is not None:
                     ar.release(xo, xb[i])
                 return False
-        X[i] = xo
+        if fetch_x:
+            X[i] = xo
         if actions[i] == SWAP:
             S[i] = so
         return True
@@ -371,13 +442,13 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             weight_in(i, t)
             arrive[it] = th
             return
-        nbytes = xraw[i] + (layers[i].sav if actions[i] == SWAP else 0)
+        nbytes = in_bytes(i)
         st = max(th, t, out_end[i])
         th = st + copy_ns(nbytes, rate["h2d"], link.lat_ns)
         h2d += nbytes
         arrive[it] = th
         if want_ops:
-            ops.append(Op("IN", i, st, th, (X[i], S[i] if actions[i] == SWAP else None)))
+            ops.append(Op("IN", i, st, th, (None if i in early_arr else X[i], S[i] if actions[i] == SWAP else None)))
 
     def admit(t, reserve):
         """Copy in ahead of need, in order of need, while the arena keeps `reserve`
@@ -399,7 +470,8 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             if kind == "W":
                 W[j], t = grant(wB[j], True, t)
             else:
-                X[j], t = grant(xb[j], True, t)
+                if j not in early_arr:
+                    X[j], t = grant(xb[j], True, t)
                 if actions[j] == SWAP:
                     S[j], t = grant(sb[j], True, t)
             issue_in(jt, t)
@@ -440,6 +512,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
     w, t = grant(al(loss.ws), False, t)
     end = t + loss.t
     busy += loss.t
+    done[0] += 1
     if want_ops:
         ops.append(Op("L", L, t, end, (DX[L], w)))
     tc = end
@@ -455,8 +528,12 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         DX[j], t = grant(xb[j], False, t)
         w, t = grant(wsb[j], False, t)
         G[j], t = grant(gB[j], False, t)
+        for s_ in sorted(readers):          # gradients this layer leaves for the inputs it read again
+            if j in readers[s_] and s_ not in DSK:
+                DSK[s_], t = grant(xb[s_], False, t)
         end = t + layers[j].tb
         busy += layers[j].tb
+        done[0] += 1
         if want_ops:
             ops.append(Op("B", j, t, end, (DX[j], w, G[j])))
         tc = end
@@ -464,6 +541,8 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         rel(DX[j + 1], xb[j + 1])
         rel(S[j], sb[j])
         rel(X[j], xb[j])
+        if j in DSK:                        # added to dx_j by this backward
+            rel(DSK.pop(j), xb[j])
         if wB[j]:
             rel(W[j], wB[j])
             W[j] = None
@@ -489,7 +568,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             t = wait_for(("W", h), t)
             backward_op(h, t, res_after[k])
             continue
-        inner = max(xb[j] + wsb[j] + gB[j] for j in range(h, e + 1))
+        inner = max(xb[j] + wsb[j] + gB[j] + extra[j] for j in range(h, e + 1))
         for j in range(h, e + 1):
             t = wait_for(("W", j), t)
             apply_pending(t)
@@ -500,6 +579,7 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
             redo = layers[j].tf if j < e else layers[j].trc
             end = t + redo
             busy += redo
+            done[0] += 1
             rc_ns += redo
             if want_ops:
                 ops.append(Op("R", j, t, end, (S[j], X[j + 1] if j < e else None, w)))
@@ -537,15 +617,18 @@ def cost_tuple(summary):
             summary["recompute_ns"])
 
 
-def try_cost(layers, link, budget, fixed, loss, actions, wres=None):
+def try_cost(layers, link, budget, fixed, loss, actions, wres=None, skips=()):
+    if not valid_actions(actions, skips):
+        return None
     try:
-        return cost_tuple(simulate(layers, link, budget, fixed, loss, actions, wres=wres))
+        return cost_tuple(simulate(layers, link, budget, fixed, loss, actions, wres=wres, skips=skips))
     except Infeasible:
         return None
 
 
-def plan(layers, link, budget, fixed, loss):
-    """Deterministic stand-in for the paper's two-tier optimisation.
+def plan(layers, link, budget, fixed, loss, skips=()):
+    """Deterministic stand-in for the paper's two-tier optimisation (`skips`: connections
+    between non-consecutive layers, priced by the simulator and respected by every candidate).
 
     1. Capacity rule (Sec. III-E): everything fits -> all KEEP (streamed weights stay
        from F_i to B_i).  Otherwise the resident tail is as long as memory allows, the
@@ -566,29 +649,42 @@ def plan(layers, link, budget, fixed, loss):
     L = len(layers)
     streamed = [1 if l.wb else 0 for l in layers]
     cur = [KEEP] * L
-    c = try_cost(layers, link, budget, fixed, loss, cur, streamed)
+    c = try_cost(layers, link, budget, fixed, loss, cur, streamed, skips)
     if c is not None:
-        res = simulate(layers, link, budget, fixed, loss, cur, wres=streamed)
+        res = simulate(layers, link, budget, fixed, loss, cur, wres=streamed, skips=skips)
         res["wres"] = streamed
         return cur, res
 
     # step 1: longest resident tail; the prefix before it swapped, or (second start)
     # recomputed from kept checkpoints; patterns that hold less memory as fall-backs.
-    def longest_tail(fill):
+    reread = {src + 1 for src, _ in skips}     # inputs that a later layer reads again: never dropped
+
+    def longest_tail(fill, at_reread=None):
+        """Longest resident tail whose prefix takes `fill`; the prefix's read-again inputs (and, for
+        chains, layer 0) take `at_reread` when given."""
         for k in range(1, L + 1):
             cand = [fill] * k + [KEEP] * (L - k)
-            if fill == RC_CHAIN:
-                cand[0] = RC_KEEP
-            if try_cost(layers, link, budget, fixed, loss, cand) is not None:
+            if at_reread is not None:
+                for i in range(k):
+                    if i in reread or (i == 0 and fill == RC_CHAIN):
+                        cand[i] = at_reread
+            if try_cost(layers, link, budget, fixed, loss, cand, None, skips) is not None:
                 return cand
         return None
 
     starts = [s for s in (longest_tail(SWAP), longest_tail(RC_KEEP)) if s is not None]
+    if not starts or skips:
+        # chains from as few checkpoints as the connections allow; with connections also a swapped
+        # prefix whose read-again tensors stay, as checkpoints or whole
+        more = [longest_tail(RC_CHAIN, RC_KEEP) or longest_tail(RC_CHAIN, RC_SWAP)]
+        if skips:
+            more += [longest_tail(SWAP, RC_KEEP), longest_tail(SWAP, KEEP)]
+        for s in more:
+            if s is not None and s not in starts:
+                starts.append(s)
     if not starts:
-        s = longest_tail(RC_CHAIN)
-        if s is None:
-            raise Infeasible()
-        starts = [s]
+        # none of the patterns fits: the search starts from one that does not (its feasibility phase)
+        starts = [[RC_SWAP if i == 0 or i in reread else RC_CHAIN for i in range(L)]]
 
     # step 2: Eq. 10.1 scan over the swapped prefix of the first start, descending
     xraw = [0] + [l.out for l in layers]
@@ -604,7 +700,7 @@ def plan(layers, link, budget, fixed, loss):
             for a in (RC_KEEP, RC_SWAP):
                 cand = list(cur)
                 cand[i] = a
-                if valid_actions(cand) and try_cost(layers, link, budget, fixed, loss, cand) is not None:
+                if try_cost(layers, link, budget, fixed, loss, cand, None, skips) is not None:
                     cur = cand
                     break
     starts[0] = cur
@@ -614,10 +710,12 @@ def plan(layers, link, budget, fixed, loss):
     # step 3: refinement of each start; the best local optimum wins
     best = None
     for start in starts:
-        key = refine(layers, link, budget, fixed, loss, start)
+        key = refine(layers, link, budget, fixed, loss, start, skips)
         if best is None or key < best:
             best = key
-    cost, cur = best
+    (unfit, cost), cur = best
+    if unfit:
+        raise Infeasible()
 
     # step 4: the tail keeps its streamed weights
     wres = [0] * L
@@ -626,11 +724,11 @@ def plan(layers, link, budget, fixed, loss):
             continue
         cand = list(wres)
         cand[i] = 1
-        cc = try_cost(layers, link, budget, fixed, loss, cur, cand)
+        cc = try_cost(layers, link, budget, fixed, loss, cur, cand, skips)
         if cc is None or not cc < cost:
             break
         wres, cost = cand, cc
-    res = simulate(layers, link, budget, fixed, loss, cur, wres=wres)
+    res = simulate(layers, link, budget, fixed, loss, cur, wres=wres, skips=skips)
     res["wres"] = wres
     return cur, res
 
@@ -664,13 +762,36 @@ def expand_group_actions(group_actions, group_wres, sizes):
     return acts, wres
 
 
-def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
+def group_skips(skips, sizes):
+    """Connections of the merged stack: a connection survives at block level when its source is the
+    last member of its block (the tensor is then that block's output) and its reader sits at least two
+    blocks further on; the others lie inside a block or between neighbours and are priced only by the
+    per-layer simulator."""
+    first, a = [], 0
+    for n in sizes:
+        first.append(a)
+        a += n
+    def block_of(i):
+        k = 0
+        while k + 1 < len(first) and first[k + 1] <= i:
+            k += 1
+        return k
+    out = set()
+    for src, dst in skips:
+        gs, gd = block_of(src), block_of(dst)
+        if src == first[gs] + sizes[gs] - 1 and gd >= gs + 2:
+            out.add((gs, gd))
+    return tuple(sorted(out))
+
+
+def plan_grouped(layers, link, budget, fixed, loss, max_group=8, skips=()):
     """The planner with the block granularity chosen as well: for each group size g in GROUP_SIZES up to
     max_group, consecutive layers are merged g at a time (the last block may be shorter), the merged stack
     is planned, the block-level plan is expanded to per-layer actions and priced by the per-layer
     simulator (which is what the executor follows; it sees every copy's latency and every allocation).
     The cheapest expansion wins, the smaller group size on ties; g = 1 is the plain planner, so the result
-    is never worse than plan().  Returns (actions, summary, g)."""
+    is never worse than plan().  `skips` are per-layer connections between non-consecutive layers; every
+    expansion is priced with all of them.  Returns (actions, summary, g)."""
     L = len(layers)
     best = None
     for g in GROUP_SIZES:
@@ -679,7 +800,7 @@ def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
         sizes = [min(g, L - a) for a in range(0, L, g)]
         if g == 1:
             try:
-                acts, res = plan(layers, link, budget, fixed, loss)
+                acts, res = plan(layers, link, budget, fixed, loss, skips)
             except Infeasible:
                 continue
             wres = res["wres"]
@@ -689,13 +810,13 @@ def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
                 merged.append(merge_group(layers[a:a + n]))
                 a += n
             try:
-                gacts, gres = plan(merged, link, budget, fixed, loss)
+                gacts, gres = plan(merged, link, budget, fixed, loss, group_skips(skips, sizes))
             except Infeasible:
                 continue
             acts, wres = expand_group_actions(gacts, gres["wres"], sizes)
-            if not valid_actions(acts):
+            if not valid_actions(acts, skips):
                 continue
-        c = try_cost(layers, link, budget, fixed, loss, acts, wres)
+        c = try_cost(layers, link, budget, fixed, loss, acts, wres, skips)
         if c is None:
             continue
         if best is None or c < best[0]:
@@ -703,7 +824,7 @@ def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
     if best is None:
         raise Infeasible()
     _, acts, wres, g = best
-    res = simulate(layers, link, budget, fixed, loss, acts, wres=wres)
+    res = simulate(layers, link, budget, fixed, loss, acts, wres=wres, skips=skips)
     res["wres"] = wres
     return acts, res, g
 
@@ -711,24 +832,38 @@ def plan_grouped(layers, link, budget, fixed, loss, max_group=8):
 PAIR_WINDOW = 4
 
 
-def refine(layers, link, budget, fixed, loss, start):
+def refine(layers, link, budget, fixed, loss, start, skips=()):
     """Local search (variable neighbourhood descent).  A candidate replaces the incumbent
     when its (cost tuple, action vector) is lexicographically smaller.  Neighbourhoods:
     (a) one layer takes another action; (b) two layers exchange their actions; (c) two
     layers at most PAIR_WINDOW apart take any pair of actions; (d) three consecutive
     layers take any triple of actions.  A larger neighbourhood is searched only when a
     full pass over every smaller one has changed nothing; any improvement sends the
-    search back to (a).  It ends when a pass over (d) changes nothing.  Returns
-    (cost tuple, actions)."""
+    search back to (a).  It ends when a pass over (d) changes nothing.
+
+    Feasibility phase: an assignment that does not fit is measured by how many compute ops
+    its timeline completes before an allocation fails.  While the incumbent does not fit, a
+    candidate replaces it when it fits or gets strictly further; every assignment that fits
+    is better than every one that does not.  Returns (((0, cost tuple) or (1, -ops
+    completed)), actions)."""
     L = len(layers)
-    key = (try_cost(layers, link, budget, fixed, loss, start), list(start))
+
+    def measure(acts):
+        if not valid_actions(acts, skips):
+            return None
+        try:
+            return (0, cost_tuple(simulate(layers, link, budget, fixed, loss, acts, skips=skips)))
+        except Infeasible as e:
+            return (1, -e.progress)
+
+    key = (measure(start), list(start))
 
     def consider(cand):
         nonlocal key
-        if not valid_actions(cand):
+        cc = measure(cand)
+        if cc is None:
             return False
-        cc = try_cost(layers, link, budget, fixed, loss, cand)
-        if cc is not None and (cc, cand) < key:
+        if (cc, cand) < key if not key[0][0] else cc < key[0]:
             key = (cc, cand)
             return True
         return False
@@ -777,7 +912,51 @@ def refine(layers, link, budget, fixed, loss, start):
                             changed |= consider(cand)
         return changed
 
-    hoods = (singles, exchanges, pairs, triples)
+    def quads():
+        changed = False
+        for i in range(L - 3):
+            for q in range(N_ACTIONS ** 4):
+                abcd = [q // 125, q // 25 % 5, q // 5 % 5, q % 5]
+                if abcd != key[1][i:i + 4]:
+                    cand = list(key[1])
+                    cand[i:i + 4] = abcd
+                    changed |= consider(cand)
+        return changed
+
+    def kicks():
+        """One layer is forced to another action and held there while single-layer changes of the
+        others descend from that point; the end of the descent is the candidate."""
+        nonlocal key
+        for i in range(L):
+            for a in range(N_ACTIONS):
+                if a == key[1][i]:
+                    continue
+                cand = list(key[1])
+                cand[i] = a
+                m = measure(cand)
+                if m is None:
+                    continue
+                local = (m, cand)
+                moved = True
+                while moved:
+                    moved = False
+                    for j in range(L):
+                        if j == i:
+                            continue
+                        for b in range(N_ACTIONS):
+                            if b != local[1][j]:
+                                c2 = list(local[1])
+                                c2[j] = b
+                                m2 = measure(c2)
+                                if m2 is not None and (m2, c2) < local:
+                                    local = (m2, c2)
+                                    moved = True
+                if local < key:
+                    key = local
+                    return True
+        return False
+
+    hoods = (singles, exchanges, pairs, triples) + ((quads, kicks) if skips else ())
     k = 0
     while k < len(hoods):
         k = 0 if hoods[k]() else k + 1
@@ -785,7 +964,7 @@ def refine(layers, link, budget, fixed, loss, start):
 
 
 def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN), wres=None,
-                prefix=()):
+                prefix=(), skips=()):
     """Exhaustive search over every valid assignment: smallest cost tuple, ties to the
     lexicographically smallest action vector.  Exponential; for small stacks only.
     `prefix` fixes the actions of the first layers (a caller may split the enumeration
@@ -799,7 +978,7 @@ def brute_force(layers, link, budget, fixed, loss, alphabet=(KEEP, SWAP, RC_KEEP
     def rec(i):
         nonlocal best
         if i == L:
-            c = try_cost(layers, link, budget, fixed, loss, cur, wres)
+            c = try_cost(layers, link, budget, fixed, loss, cur, wres, skips)
             if c is not None and (best is None or (c, cur) < best):
                 best = (c, list(cur))
             return

@@ -121,9 +121,23 @@ def _check(st, where, ctx=None):
 
 
 # ------------------------------------------------------------------ pure planner
-def karma_simulate(layers, link, loss, budget, fixed, actions, want_ops=False, weights_kept=None):
+class Skip(C.Structure):
+    _fields_ = [("src", C.c_uint32), ("dst", C.c_uint32)]
+
+
+def _skips_array(skips):
+    arr = (Skip * max(1, len(skips)))()
+    for k, (src, dst) in enumerate(skips):
+        arr[k] = Skip(int(src), int(dst))
+    return arr, C.c_uint32(len(skips))
+
+
+def karma_simulate(layers, link, loss, budget, fixed, actions, want_ops=False, weights_kept=None, skips=None):
     """layers: sequence of (tf, tb, trc, sav, out, ws[, wb, gb[, th, hg, hw]]); link: (bw_h2d, bw_d2h, lat[,
-    bw_h2d_loaded, bw_d2h_loaded]); loss: (t, ws[, th, hg, hw]).  Returns summary dict (and ops list when asked)."""
+    bw_h2d_loaded, bw_d2h_loaded]); loss: (t, ws[, th, hg, hw]); skips: (src, dst) pairs -> karma_simulate_graph.
+    Returns summary dict (and ops list when asked)."""
+    if skips is not None:
+        return karma_simulate_graph(layers, link, loss, budget, fixed, skips, actions, want_ops, weights_kept)
     n = len(layers)
     arr = _layers_array(layers)
     lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
@@ -138,6 +152,59 @@ def karma_simulate(layers, link, loss, budget, fixed, actions, want_ops=False, w
     if want_ops:
         return summ.as_dict(), [ops[k] for k in range(nops.value)]
     return summ.as_dict()
+
+
+def karma_simulate_graph(layers, link, loss, budget, fixed, skips, actions, want_ops=False, weights_kept=None):
+    n = len(layers)
+    arr = _layers_array(layers)
+    lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
+    sk, nsk = _skips_array(skips)
+    act = (C.c_uint8 * n)(*actions)
+    kept = (C.c_uint8 * n)(*weights_kept) if weights_kept is not None else None
+    summ = PlanSummary()
+    cap = 8 * n + 2 + len(skips)
+    ops = (Op * cap)() if want_ops else None
+    nops = C.c_uint32(cap)
+    st = lib().karma_simulate_graph(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget), C.c_uint64(fixed),
+                                    sk, nsk, act, kept, C.byref(summ), ops, C.byref(nops))
+    _check(st, "karma_simulate_graph")
+    if want_ops:
+        return summ.as_dict(), [ops[k] for k in range(nops.value)]
+    return summ.as_dict()
+
+
+def karma_plan_graph(layers, link, loss, budget, fixed, skips):
+    n = len(layers)
+    arr = _layers_array(layers)
+    lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
+    sk, nsk = _skips_array(skips)
+    act = (C.c_uint8 * n)()
+    kept = (C.c_uint8 * n)()
+    summ = PlanSummary()
+    st = lib().karma_plan_graph(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget), C.c_uint64(fixed),
+                                sk, nsk, act, kept, C.byref(summ))
+    _check(st, "karma_plan_graph")
+    res = summ.as_dict()
+    res["wres"] = list(kept)
+    return list(act), res
+
+
+def karma_plan_grouped_graph(layers, link, loss, budget, fixed, skips, max_group=8):
+    n = len(layers)
+    arr = _layers_array(layers)
+    lk, ls = Link(*[int(v) for v in link]), LossCost(*[int(v) for v in loss])
+    sk, nsk = _skips_array(skips)
+    act = (C.c_uint8 * n)()
+    kept = (C.c_uint8 * n)()
+    summ = PlanSummary()
+    g = C.c_uint32()
+    st = lib().karma_plan_grouped_graph(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget),
+                                        C.c_uint64(fixed), sk, nsk, C.c_uint32(max_group), act, kept, C.byref(summ),
+                                        C.byref(g))
+    _check(st, "karma_plan_grouped_graph")
+    res = summ.as_dict()
+    res["wres"] = list(kept)
+    return list(act), res, g.value
 
 
 def karma_plan_pure(layers, link, loss, budget, fixed):

@@ -76,13 +76,21 @@ void Arena::give(int64_t off, int64_t size) {
   used -= size;
 }
 
-bool actions_valid(const uint8_t* a, uint32_t n) {
+bool actions_valid(const uint8_t* a, uint32_t n, const karma_skip* skips, uint32_t n_skips) {
   uint8_t prev = KARMA_KEEP;
   for (uint32_t i = 0; i < n; ++i) {
     if (a[i] > KARMA_RC_CHAIN) return false;
     if (a[i] == KARMA_RC_CHAIN && (i == 0 || prev < KARMA_RC_KEEP)) return false;
     prev = a[i];
   }
+  for (uint32_t k = 0; k < n_skips; ++k)
+    if (skips[k].src + 1 < n && a[skips[k].src + 1] == KARMA_RC_CHAIN) return false;
+  return true;
+}
+
+bool skips_valid(const karma_skip* skips, uint32_t n_skips, uint32_t n) {
+  for (uint32_t k = 0; k < n_skips; ++k)
+    if ((uint64_t)skips[k].src + 2 > skips[k].dst || skips[k].dst >= n) return false;
   return true;
 }
 
@@ -116,6 +124,14 @@ struct Timeline {
   std::vector<Update> updates;
   bool hosted = false;                            // a step with host updates
   uint64_t bw_in = 0, bw_out = 0;                 // current price of a copy (idle rates, then loaded ones)
+  int64_t done = 0;                               // compute ops completed (how far a timeline that does not fit got)
+  // Connections between non-consecutive layers (Sec. III-F.3).  x_s is "read again" when a layer
+  // other than s reads it.  reads[j]: the inputs layer j reads again, ascending.  A swapped x_s
+  // comes back ahead of its first reader (a premature swap-in) and then stays until B_s;
+  // the gradient its readers leave for it waits in hold_at[s] until B_s adds it in.
+  std::vector<std::vector<uint32_t>> reads, early_try, early_due;
+  std::vector<int64_t> back_early;                // end of the premature swap-in of x_s, -1 = none
+  std::vector<int64_t> hold_at, hold_first;       // offset of that gradient; bytes B_j is the first to hold
 
   Timeline(const Problem& p, const uint8_t* a, const uint8_t* kw, std::vector<karma_op>* o)
       : P(p), act(a), keepw(kw), ops(o), L(p.n) {}
@@ -149,6 +165,27 @@ struct Timeline {
   }
   bool swapped_whole(uint32_t i) const { return act[i] == KARMA_SWAP; }
   int64_t move_bytes(uint32_t i) const { return x_raw[i] + (swapped_whole(i) ? (int64_t)P.layers[i].sav_bytes : 0); }
+  bool here_already(uint32_t i) const { return back_early[i] >= 0; }
+  // what the backward swap-in of layer i still has to bring
+  int64_t fetch_bytes(uint32_t i) const {
+    return (here_already(i) ? 0 : x_raw[i]) + (swapped_whole(i) ? (int64_t)P.layers[i].sav_bytes : 0);
+  }
+  // premature swap-in of x_s for a forward reader; `must`: the reader is next, wait for memory
+  void fetch_early(uint32_t s, int64_t& now, bool must) {
+    if (here_already(s) || failed) return;
+    if (must) {
+      x_at[s] = obtain(x_sz[s], true, now);
+      if (failed) return;
+    } else {
+      x_at[s] = arena.take(x_sz[s], true);
+      if (x_at[s] < 0) return;
+    }
+    int64_t st = std::max(std::max(t_in, now), left[s]);
+    t_in = st + copy_ns((uint64_t)x_raw[s], bw_in, P.link.lat_ns);
+    moved_in += (uint64_t)x_raw[s];
+    back_early[s] = t_in;
+    emit('I', s, st, t_in, x_at[s], -1, -1);
+  }
 
   // copy of layer i's weights into p_at[i] (already allocated)
   void fetch_weights(uint32_t i, int64_t now) {
@@ -165,19 +202,19 @@ struct Timeline {
       w_arrival[i] = t_in;
       return;
     }
-    int64_t nbytes = move_bytes(i);
+    int64_t nbytes = fetch_bytes(i);
     int64_t s = std::max(std::max(t_in, now), left[i]);   // data must have reached the host first
     t_in = s + copy_ns((uint64_t)nbytes, bw_in, P.link.lat_ns);
     moved_in += (uint64_t)nbytes;
     arrival[i] = t_in;
-    emit('I', i, s, t_in, x_at[i], swapped_whole(i) ? s_at[i] : -1, -1);
+    emit('I', i, s, t_in, here_already(i) ? -1 : x_at[i], swapped_whole(i) ? s_at[i] : -1, -1);
   }
   void prefetch_ahead(int64_t now, int64_t reserve) {
     settle(now);
     while (!wanted.empty()) {
       const Want it = wanted.front();
       const uint32_t i = it.layer;
-      int64_t need = it.weights ? p_sz[i] : x_sz[i] + (swapped_whole(i) ? s_sz[i] : 0);
+      int64_t need = it.weights ? p_sz[i] : (here_already(i) ? 0 : x_sz[i]) + (swapped_whole(i) ? s_sz[i] : 0);
       if (arena.cap - arena.used < need + reserve) break;
       if (it.weights) {
         int64_t pa = arena.take(p_sz[i], true);
@@ -185,12 +222,13 @@ struct Timeline {
         p_at[i] = pa;
       } else {
         int64_t xa = -1, sa = -1;
-        if (x_sz[i]) { xa = arena.take(x_sz[i], true); if (xa < 0) break; }
+        const bool fetch_x = !here_already(i);
+        if (fetch_x && x_sz[i]) { xa = arena.take(x_sz[i], true); if (xa < 0) break; }
         if (swapped_whole(i) && s_sz[i]) {
           sa = arena.take(s_sz[i], true);
           if (sa < 0) { if (xa >= 0) arena.give(xa, x_sz[i]); break; }
         }
-        x_at[i] = xa;
+        if (fetch_x) x_at[i] = xa;
         if (swapped_whole(i)) s_at[i] = sa;
       }
       wanted.pop_front();
@@ -209,7 +247,7 @@ struct Timeline {
       if (j.weights) {
         p_at[j.layer] = obtain(p_sz[j.layer], true, now);
       } else {
-        x_at[j.layer] = obtain(x_sz[j.layer], true, now);
+        if (!here_already(j.layer)) x_at[j.layer] = obtain(x_sz[j.layer], true, now);
         if (swapped_whole(j.layer)) s_at[j.layer] = obtain(s_sz[j.layer], true, now);
       }
       if (!failed) start_prefetch(j, now);
@@ -233,15 +271,19 @@ struct Timeline {
     dx_at[j] = obtain(x_sz[j], false, now);
     int64_t w = obtain(w_sz[j], false, now);
     g_at[j] = obtain(g_sz[j], false, now);
+    for (uint32_t s : reads[j])           // gradients this layer leaves for the inputs it read again
+      if (hold_at[s] < 0) hold_at[s] = obtain(x_sz[s], false, now);
     if (failed) return;
     int64_t end = now + P.layers[j].tb_ns;
     busy += P.layers[j].tb_ns;
+    ++done;
     emit('B', j, now, end, dx_at[j], w, g_at[j]);
     t_comp = end;
     drop(w, w_sz[j]);
     drop(dx_at[j + 1], x_sz[j + 1]);
     drop(s_at[j], s_sz[j]);
     drop(x_at[j], x_sz[j]);
+    drop(hold_at[j], x_sz[j]);            // added to dx_j by this backward
     if (p_sz[j]) drop(p_at[j], p_sz[j]);
     if (g_sz[j]) {
       // the gradients leave right after the layer's backward (pipeline stage 3)
@@ -284,11 +326,42 @@ struct Timeline {
     arrival.assign(L, -1);
     w_arrival.assign(L, -1);
     left.assign(L, 0);
+    reads.assign(L, {}); early_try.assign(L, {}); early_due.assign(L, {});
+    back_early.assign(L, -1); hold_at.assign(L + 1, -1); hold_first.assign(L, 0);
+    if (P.n_skips) {
+      std::vector<int64_t> first(L, -1), last(L, -1);
+      for (uint32_t k = 0; k < P.n_skips; ++k) {
+        const uint32_t s = P.skips[k].src + 1, d = P.skips[k].dst;
+        reads[d].push_back(s);
+        first[s] = first[s] < 0 ? (int64_t)d : std::min(first[s], (int64_t)d);
+        last[s] = std::max(last[s], (int64_t)d);
+      }
+      for (uint32_t j = 0; j < L; ++j) {
+        std::sort(reads[j].begin(), reads[j].end());
+        reads[j].erase(std::unique(reads[j].begin(), reads[j].end()), reads[j].end());
+      }
+      for (uint32_t s = 0; s < L; ++s) {
+        if (first[s] < 0) continue;
+        hold_first[last[s]] += x_sz[s];
+        if ((act[s] == KARMA_SWAP || act[s] == KARMA_RC_SWAP) && x_raw[s]) {
+          // queued one layer ahead of the first reader when there is a layer between, else at the reader
+          early_try[first[s] - 1 > (int64_t)s ? first[s] - 1 : first[s]].push_back(s);
+          early_due[first[s]].push_back(s);
+        }
+      }
+    }
 
     // forward
     for (uint32_t i = 0; i < L && !failed; ++i) {
       int64_t now = t_comp;
       settle(now);
+      for (uint32_t s : early_try[i]) fetch_early(s, now, std::binary_search(reads[i].begin(), reads[i].end(), s));
+      for (uint32_t s : early_due[i]) {
+        fetch_early(s, now, true);
+        if (failed) break;
+        now = std::max(now, back_early[s]);
+      }
+      if (failed) break;
       if (p_sz[i] && p_at[i] < 0) {   // not prefetched: fetched now, the layer waits
         p_at[i] = obtain(p_sz[i], keeps(i), now);
         if (failed) break;
@@ -306,6 +379,7 @@ struct Timeline {
       }
       int64_t end = now + P.layers[i].tf_ns;
       busy += P.layers[i].tf_ns;
+      ++done;
       emit('F', i, now, end, x_at[i + 1], s_at[i], w);
       t_comp = end;
       drop(w, w_sz[i]);
@@ -346,13 +420,13 @@ struct Timeline {
       while (act[h] == KARMA_RC_CHAIN) --h;
       Unit u{(uint32_t)h, (uint32_t)i, 0, 0};
       if (act[h] <= KARMA_SWAP) {
-        u.need = x_sz[h] + w_sz[h] + g_sz[h];
+        u.need = x_sz[h] + w_sz[h] + g_sz[h] + hold_first[h];
       } else {
         int64_t held = 0, top = 0;
         for (int64_t j = h; j <= i; ++j) {
           held += s_sz[j];
           if (j < i) held += x_sz[j + 1];
-          top = std::max(top, x_sz[j] + w_sz[j] + g_sz[j]);
+          top = std::max(top, x_sz[j] + w_sz[j] + g_sz[j] + hold_first[j]);
         }
         u.need = held + top;
         u.inner = top;
@@ -366,8 +440,7 @@ struct Timeline {
     for (const Unit& u : units) any = std::max(any, u.need);
     for (const Unit& u : units) {
       const uint32_t h = u.head;
-      if ((act[h] == KARMA_SWAP && move_bytes(h) > 0) || (act[h] == KARMA_RC_SWAP && x_raw[h] > 0))
-        wanted.push_back(Want{false, h});
+      if ((act[h] == KARMA_SWAP || act[h] == KARMA_RC_SWAP) && fetch_bytes(h) > 0) wanted.push_back(Want{false, h});
       for (uint32_t j = h; j <= u.tail; ++j)
         if (p_sz[j] && !keeps(j)) wanted.push_back(Want{true, j});
     }
@@ -389,6 +462,7 @@ struct Timeline {
       if (failed) return false;
       int64_t end = now + P.loss.t_ns;
       busy += P.loss.t_ns;
+      ++done;
       emit('L', L, now, end, dx_at[L], w, -1);
       t_comp = end;
       drop(w, lw_sz);
@@ -424,6 +498,7 @@ struct Timeline {
         int64_t end = now + again;
         busy += again;
         redo += again;
+        ++done;
         emit('R', j, now, end, s_at[j], j < u.tail ? x_at[j + 1] : -1, w);
         t_comp = end;
         drop(w, w_sz[j]);
@@ -458,39 +533,54 @@ struct Timeline {
   }
 };
 
+// What the search minimises.  An assignment that fits: (makespan, bytes moved, recompute time).  One
+// that does not fit is worse than every one that does, and is measured by how many compute ops its
+// timeline completes before an allocation fails (makespan holds minus that count).
 struct Cost {
-  int64_t makespan; uint64_t moved; int64_t redo;
+  int unfit; int64_t makespan; uint64_t moved; int64_t redo;
   bool operator<(const Cost& o) const {
+    if (unfit != o.unfit) return unfit < o.unfit;
     if (makespan != o.makespan) return makespan < o.makespan;
     if (moved != o.moved) return moved < o.moved;
     return redo < o.redo;
   }
-  bool operator==(const Cost& o) const { return makespan == o.makespan && moved == o.moved && redo == o.redo; }
+  bool operator==(const Cost& o) const {
+    return unfit == o.unfit && makespan == o.makespan && moved == o.moved && redo == o.redo;
+  }
 };
 
+// false: not a valid assignment
 bool evaluate(const Problem& P, const std::vector<uint8_t>& a, Cost& c, const uint8_t* keepw = nullptr) {
   karma_plan_summary s;
-  if (!actions_valid(a.data(), P.n)) return false;
+  if (!actions_valid(a.data(), P.n, P.skips, P.n_skips)) return false;
   Timeline tl(P, a.data(), keepw, nullptr);
-  if (!tl.run(&s)) return false;
-  c = Cost{s.makespan_ns, s.bytes_d2h + s.bytes_h2d, s.recompute_ns};
+  if (tl.run(&s)) c = Cost{0, s.makespan_ns, s.bytes_d2h + s.bytes_h2d, s.recompute_ns};
+  else c = Cost{1, -tl.done, 0, 0};
   return true;
+}
+bool fits(const Problem& P, const std::vector<uint8_t>& a, Cost& c, const uint8_t* keepw = nullptr) {
+  return evaluate(P, a, c, keepw) && !c.unfit;
 }
 
 struct Incumbent {
   Cost cost; std::vector<uint8_t> act;
-  bool beaten_by(const Cost& c, const std::vector<uint8_t>& a) const {
+  bool after(const Cost& c, const std::vector<uint8_t>& a) const {   // (c, a) < (cost, act)
     if (c < cost) return true;
     if (!(c == cost)) return false;
     return a < act;   // lexicographic
   }
+  // the search's acceptance rule: while the incumbent does not fit only strict progress counts
+  bool beaten_by(const Cost& c, const std::vector<uint8_t>& a) const { return cost.unfit ? c < cost : after(c, a); }
 };
 
 // Local search (variable neighbourhood descent) on (cost, action vector).  Neighbourhoods: one
 // layer takes another action; two layers exchange their actions; two layers at most PAIR_WINDOW
 // apart take any pair of actions; three consecutive layers take any triple of actions.  A larger
 // neighbourhood is searched only when a full pass over every smaller one changed nothing; any
-// improvement sends the search back to the smallest.
+// improvement sends the search back to the smallest.  With connections between non-consecutive
+// layers two more follow: four consecutive layers take any four actions; and "kicks": one layer is
+// forced to another action and held there while single-layer changes of the others descend from that
+// point, the end of the descent being the candidate.
 static const uint32_t PAIR_WINDOW = 4;
 
 void improve(const Problem& P, Incumbent& inc) {
@@ -517,7 +607,7 @@ void improve(const Problem& P, Incumbent& inc) {
           for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
             for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b)
               if (a != inc.act[i] || b != inc.act[j]) { cand = inc.act; cand[i] = a; cand[j] = b; moved |= attempt(); }
-    } else {
+    } else if (hood == 3) {
       for (uint32_t i = 0; i + 2 < L; ++i)
         for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a)
           for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b)
@@ -526,10 +616,44 @@ void improve(const Problem& P, Incumbent& inc) {
                 cand = inc.act; cand[i] = a; cand[i + 1] = b; cand[i + 2] = d;
                 moved |= attempt();
               }
+    } else if (hood == 4) {
+      for (uint32_t i = 0; i + 3 < L; ++i)
+        for (uint32_t q = 0; q < 625; ++q) {
+          const uint8_t w[4] = {(uint8_t)(q / 125), (uint8_t)(q / 25 % 5), (uint8_t)(q / 5 % 5), (uint8_t)(q % 5)};
+          if (w[0] != inc.act[i] || w[1] != inc.act[i + 1] || w[2] != inc.act[i + 2] || w[3] != inc.act[i + 3]) {
+            cand = inc.act;
+            for (int k = 0; k < 4; ++k) cand[i + k] = w[k];
+            moved |= attempt();
+          }
+        }
+    } else {
+      for (uint32_t i = 0; i < L; ++i)
+        for (uint8_t a = 0; a <= KARMA_RC_CHAIN; ++a) {
+          if (a == inc.act[i]) continue;
+          Incumbent local;
+          local.act = inc.act;
+          local.act[i] = a;
+          if (!evaluate(P, local.act, local.cost)) continue;
+          for (bool went = true; went;) {
+            went = false;
+            for (uint32_t j = 0; j < L; ++j) {
+              if (j == i) continue;
+              for (uint8_t b = 0; b <= KARMA_RC_CHAIN; ++b) {
+                if (b == local.act[j]) continue;
+                cand = local.act;
+                cand[j] = b;
+                Cost c;
+                if (evaluate(P, cand, c) && local.after(c, cand)) { local.cost = c; local.act = cand; went = true; }
+              }
+            }
+          }
+          if (inc.after(local.cost, local.act)) { inc = local; return true; }
+        }
     }
     return moved;
   };
-  for (int hood = 0; hood < 4;) hood = pass(hood) ? 0 : hood + 1;
+  const int hoods = P.n_skips ? 6 : 4;
+  for (int hood = 0; hood < hoods;) hood = pass(hood) ? 0 : hood + 1;
 }
 
 }  // namespace
@@ -546,26 +670,45 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
   actions.assign(L, KARMA_KEEP);
   keepw.assign(L, 0);
   for (uint32_t i = 0; i < L; ++i) keepw[i] = P.layers[i].w_bytes ? 1 : 0;
-  if (evaluate(P, actions, c, keepw.data())) return simulate(P, actions.data(), keepw.data(), out, nullptr);   // everything fits
+  if (fits(P, actions, c, keepw.data())) return simulate(P, actions.data(), keepw.data(), out, nullptr);   // everything fits
   const std::vector<uint8_t> streamed = keepw;
   keepw.assign(L, 0);
 
-  // capacity rule: the longest resident tail for a given treatment of the prefix
-  auto longest_tail = [&](uint8_t fill, std::vector<uint8_t>& res) {
+  // capacity rule: the longest resident tail for a given treatment of the prefix.  The prefix's read-again
+  // inputs (and, for chains, layer 0) take `special` when it is an action.
+  std::vector<uint8_t> reread(L, 0);
+  for (uint32_t k = 0; k < P.n_skips; ++k) reread[P.skips[k].src + 1] = 1;
+  const int NONE = -1;
+  auto longest_tail = [&](uint8_t fill, int special, std::vector<uint8_t>& res) {
     for (uint32_t k = 1; k <= L; ++k) {
       res.assign(L, KARMA_KEEP);
-      for (uint32_t i = 0; i < k; ++i) res[i] = fill;
-      if (fill == KARMA_RC_CHAIN) res[0] = KARMA_RC_KEEP;
-      if (evaluate(P, res, c)) return true;
+      for (uint32_t i = 0; i < k; ++i)
+        res[i] = special != NONE && (reread[i] || (i == 0 && fill == KARMA_RC_CHAIN)) ? (uint8_t)special : fill;
+      if (fits(P, res, c)) return true;
     }
     return false;
   };
   std::vector<std::vector<uint8_t>> starts;
   std::vector<uint8_t> s;
-  if (longest_tail(KARMA_SWAP, s)) starts.push_back(s);
-  if (longest_tail(KARMA_RC_KEEP, s)) starts.push_back(s);
+  if (longest_tail(KARMA_SWAP, NONE, s)) starts.push_back(s);
+  if (longest_tail(KARMA_RC_KEEP, NONE, s)) starts.push_back(s);
+  if (starts.empty() || P.n_skips) {
+    // chains from as few checkpoints as the connections allow; with connections also a swapped prefix
+    // whose read-again tensors stay, as checkpoints or whole
+    auto add = [&](bool found) {
+      if (found && std::find(starts.begin(), starts.end(), s) == starts.end()) starts.push_back(s);
+    };
+    add(longest_tail(KARMA_RC_CHAIN, KARMA_RC_KEEP, s) || longest_tail(KARMA_RC_CHAIN, KARMA_RC_SWAP, s));
+    if (P.n_skips) {
+      add(longest_tail(KARMA_SWAP, KARMA_RC_KEEP, s));
+      add(longest_tail(KARMA_SWAP, KARMA_KEEP, s));
+    }
+  }
   if (starts.empty()) {
-    if (!longest_tail(KARMA_RC_CHAIN, s)) return false;
+    // none of the patterns fits: the search starts from one that does not (its feasibility phase)
+    s.assign(L, KARMA_RC_CHAIN);
+    for (uint32_t i = 0; i < L; ++i)
+      if (i == 0 || reread[i]) s[i] = KARMA_RC_SWAP;
     starts.push_back(s);
   }
   // Eq. 10.1: recompute where it is cheaper than the swap-in it replaces
@@ -584,7 +727,7 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
         for (uint8_t a : {(uint8_t)KARMA_RC_KEEP, (uint8_t)KARMA_RC_SWAP}) {
           std::vector<uint8_t> cand = cur;
           cand[i] = a;
-          if (evaluate(P, cand, c)) { cur = cand; break; }
+          if (fits(P, cand, c)) { cur = cand; break; }
         }
       }
     }
@@ -598,9 +741,9 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
     inc.act = st;
     if (!evaluate(P, st, inc.cost)) continue;
     improve(P, inc);
-    if (!have || best.beaten_by(inc.cost, inc.act)) { best = inc; have = true; }
+    if (!have || best.after(inc.cost, inc.act)) { best = inc; have = true; }
   }
-  if (!have) return false;
+  if (!have || best.cost.unfit) return false;
   actions = best.act;
   // the tail of the model keeps its streamed weights between forward and backward for as
   // long as that fits and does not lengthen the step; the first layer that cannot ends the scan
@@ -608,7 +751,7 @@ bool plan(const Problem& P, std::vector<uint8_t>& actions, std::vector<uint8_t>&
   for (int64_t i = (int64_t)L - 1; i >= 0; --i) {
     if (!streamed[i]) continue;
     keepw[i] = 1;
-    if (evaluate(P, actions, c, keepw.data()) && c < cost) {
+    if (fits(P, actions, c, keepw.data()) && c < cost) {
       cost = c;
     } else {
       keepw[i] = 0;
@@ -687,7 +830,21 @@ bool plan_grouped(const Problem& P, uint32_t max_group, std::vector<uint8_t>& ac
         merged.push_back(m);
         count.push_back(n);
       }
-      Problem G{merged.data(), (uint32_t)merged.size(), P.link, P.loss, P.budget, P.fixed};
+      // a connection survives at block level when its source is the last member of its block (the tensor
+      // is then that block's output) and its reader sits at least two blocks on; the others lie inside a
+      // block or between neighbours and are priced only by the per-layer simulator
+      std::vector<karma_skip> gs;
+      for (uint32_t k = 0; k < P.n_skips; ++k) {
+        const uint32_t bs = P.skips[k].src / g, bd = P.skips[k].dst / g;
+        if (P.skips[k].src == bs * g + count[bs] - 1 && bd >= bs + 2) gs.push_back(karma_skip{bs, bd});
+      }
+      std::sort(gs.begin(), gs.end(), [](const karma_skip& a, const karma_skip& b) {
+        return a.src != b.src ? a.src < b.src : a.dst < b.dst;
+      });
+      gs.erase(std::unique(gs.begin(), gs.end(), [](const karma_skip& a, const karma_skip& b) {
+        return a.src == b.src && a.dst == b.dst;
+      }), gs.end());
+      Problem G{merged.data(), (uint32_t)merged.size(), P.link, P.loss, P.budget, P.fixed, gs.data(), (uint32_t)gs.size()};
       std::vector<uint8_t> ga, gw;
       karma_plan_summary s;
       if (!plan(G, ga, gw, &s)) continue;
@@ -699,7 +856,7 @@ bool plan_grouped(const Problem& P, uint32_t max_group, std::vector<uint8_t>& ac
         }
     }
     Cost c;
-    if (!evaluate(P, a, c, w.data())) continue;
+    if (!fits(P, a, c, w.data())) continue;
     if (!have || c < best) {
       have = true;
       best = c; best_a = a; best_w = w; best_g = g;

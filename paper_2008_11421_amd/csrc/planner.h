@@ -14,6 +14,9 @@ struct Problem {
   karma_link link;
   karma_loss_cost loss;
   uint64_t budget, fixed;
+  // connections between non-consecutive layers: the output of layer src is read again by layer dst
+  const karma_skip* skips = nullptr;
+  uint32_t n_skips = 0;
 };
 
 // Two-ended first-fit allocator with a coalescing hole list.  Long-lived buffers come
@@ -28,7 +31,9 @@ struct Arena {
 };
 
 int64_t copy_ns(uint64_t bytes, uint64_t bw, int64_t lat);
-bool actions_valid(const uint8_t* a, uint32_t n);
+// a chained layer drops its input: the input of a layer that is read again (skips[k].src + 1) cannot be chained
+bool actions_valid(const uint8_t* a, uint32_t n, const karma_skip* skips = nullptr, uint32_t n_skips = 0);
+bool skips_valid(const karma_skip* skips, uint32_t n_skips, uint32_t n);
 // keepw: per layer, streamed weights stay in HBM from F_i to B_i (null = no layer keeps them)
 bool simulate(const Problem& P, const uint8_t* actions, const uint8_t* keepw, karma_plan_summary* out,
               std::vector<karma_op>* ops);

@@ -182,3 +182,125 @@ def test_host_queue_bit_exact():
             assert (ag, gg) == (aog, gog)
             summaries_equal(sg, sog)
     assert n > 150
+
+
+# ---- connections between non-consecutive layers ---------------------------------------
+def graph_cases(seed, n, L_range=(4, 8)):
+    import random
+    from test_oracle_skips import random_case
+    rng = random.Random(seed)
+    for _ in range(n):
+        L = rng.randrange(*L_range)
+        layers, skips, link = random_case(rng, L)
+        if rng.random() < 0.4:          # some stacks with host updates and loaded link rates
+            layers = [l._replace(th=rng.randrange(0, 90), hg=rng.randrange(0, 3) * 128, hw=rng.randrange(0, 3) * 128) for l in layers]
+            link = link._replace(bw_h2d_loaded=link.bw_h2d // 2, bw_d2h_loaded=link.bw_d2h * 2 // 3)
+        full = P.simulate(layers, link, 1 << 30, 0, P.Loss(5, 256), [0] * L, skips=skips)["peak_bytes"]
+        yield layers, skips, link, P.Loss(5, 256), full, rng
+
+
+def test_graph_simulator_bit_exact():
+    n = unfit = 0
+    for layers, skips, link, loss, full, rng in graph_cases(21, 40):
+        L = len(layers)
+        for frac in (0.5, 0.8, 2.0):
+            budget = int(full * frac)
+            for _ in range(30):
+                v = [rng.randrange(5) for _ in range(L)]
+                if not P.valid_actions(v, skips):
+                    if P.valid_actions(v):
+                        with pytest.raises(K.KarmaError) as e:
+                            K.karma_simulate_graph(layers, link, loss, budget, 0, skips, v)
+                        assert e.value.status == K.E_INVAL
+                    continue
+                try:
+                    so = P.simulate(layers, link, budget, 0, loss, v, want_ops=True, skips=skips)
+                except P.Infeasible:
+                    with pytest.raises(K.KarmaError) as e:
+                        K.karma_simulate_graph(layers, link, loss, budget, 0, skips, v)
+                    assert e.value.status == K.E_BUDGET
+                    unfit += 1
+                    continue
+                sl, ops = K.karma_simulate_graph(layers, link, loss, budget, 0, skips, v, want_ops=True)
+                summaries_equal(sl, so)
+                ops_equal(ops, so["ops"])
+                n += 1
+    assert n > 300 and unfit > 50
+
+
+def test_graph_plan_bit_exact():
+    n = none = 0
+    for layers, skips, link, loss, full, rng in graph_cases(22, 9, L_range=(5, 9)):
+        for frac in (0.45, 0.7):
+            budget = int(full * frac)
+            try:
+                ao, so = P.plan(layers, link, budget, 0, loss, skips)
+            except P.Infeasible:
+                with pytest.raises(K.KarmaError) as e:
+                    K.karma_plan_graph(layers, link, loss, budget, 0, skips)
+                assert e.value.status == K.E_BUDGET
+                none += 1
+                continue
+            al, sl = K.karma_plan_graph(layers, link, loss, budget, 0, skips)
+            assert al == ao, (skips, budget)
+            summaries_equal(sl, so)
+            n += 1
+    assert n >= 8 and none >= 1
+
+
+def test_graph_grouped_plan_bit_exact_and_bad_connections():
+    for layers, skips, link, loss, full, rng in graph_cases(23, 4, L_range=(8, 11)):
+        link = link._replace(lat_ns=60)
+        budget = int(full * 0.65)
+        try:
+            ao, so, go = P.plan_grouped(layers, link, budget, 0, loss, skips=skips)
+        except P.Infeasible:
+            with pytest.raises(K.KarmaError):
+                K.karma_plan_grouped_graph(layers, link, loss, budget, 0, skips)
+            continue
+        al, sl, gl = K.karma_plan_grouped_graph(layers, link, loss, budget, 0, skips)
+        assert (al, gl) == (ao, go)
+        summaries_equal(sl, so)
+        assert sl["wres"] == so["wres"]
+    layers = mk(1, 5, "homogeneous")
+    for bad in ([(0, 1)], [(3, 5)], [(4, 2)]):
+        with pytest.raises(K.KarmaError) as e:
+            K.karma_plan_graph(layers, (10**9, 10**9, 0), (0, 0), 1 << 30, 0, bad)
+        assert e.value.status == K.E_INVAL
+
+
+def test_smallest_budgets_bit_exact_without_connections():
+    """Budgets around the smallest that fits, where no start pattern may fit and the search's
+    feasibility phase runs: both implementations find the same assignment or none."""
+    found = none = 0
+    for L, seeds in ((5, (0, 1)), (7, (5,))):
+        for layers, link, budget, loss in cases(L, seeds=seeds, fracs=(0.0,), bwmuls=(1.0,)):
+            for q in (0.6, 0.95, 1.0, 1.05):
+                b = int(budget * q)
+                try:
+                    ao, so = P.plan(layers, link, b, 0, loss)
+                except P.Infeasible:
+                    with pytest.raises(K.KarmaError):
+                        K.karma_plan_pure(layers, link, loss, b, 0)
+                    none += 1
+                    continue
+                al, sl = K.karma_plan_pure(layers, link, loss, b, 0)
+                assert al == ao
+                summaries_equal(sl, so)
+                found += 1
+    assert found and none
+
+
+def test_premature_swap_in_through_library():
+    """Four equal layers (forward 10, backward 20, 256-byte outputs, 1 byte/ns, loss 5), the input of
+    layer 1 swapped and read again by layer 3: OUT 20-276, copy back 276-532, F3 532-542, makespan 627
+    (worked out by hand in the oracle's pins)."""
+    layers = [(10, 20, 5, 0, 256, 0)] * 4
+    s, ops = K.karma_simulate_graph(layers, (10**9, 10**9, 0), (5, 0), 1 << 20, 0, [(0, 3)], [K.KEEP, K.SWAP, K.KEEP, K.KEEP],
+                                    want_ops=True)
+    assert [(o.start_ns, o.end_ns) for o in ops if chr(o.kind) == "I"] == [(276, 532)]
+    assert [(o.start_ns, o.end_ns) for o in ops if chr(o.kind) == "F"][3] == (532, 542)
+    assert s["makespan_ns"] == 627 and s["bytes_h2d"] == s["bytes_d2h"] == 256 and s["peak_bytes"] == 1536
+    with pytest.raises(K.KarmaError) as e:      # the input of layer 2 is read again: it cannot be chained
+        K.karma_simulate_graph(layers, (10**9, 10**9, 0), (5, 0), 1 << 20, 0, [(1, 3)], [K.KEEP, K.RC_KEEP, K.RC_CHAIN, K.KEEP])
+    assert e.value.status == K.E_INVAL
