@@ -167,3 +167,53 @@ def cnn_problem(seed=2008114203, width=64, stage_blocks=(3, 24, 36, 3), image=22
     images = normal(nxt(), (batch, image, image, 3))
     labels = randint(nxt(), (batch,), classes)
     return params, images, labels
+
+
+# ------------------------------------------------------------------ wide residual network
+# Keys of one basic block's parameter dict, in the order the library numbers a block's tensors
+# (ws: the shortcut convolution, present on blocks that change the shape only).
+BASIC_TENSORS = ("g1", "b1", "w1", "g2", "b2", "w2", "ws")
+
+
+def wrn_problem(seed=2008114204, width=160, group_blocks=(4, 4, 4), image=32, batch=128, classes=10, stem=16,
+                bn_jitter=0.0):
+    """WRN-28-10 shapes by default: a 3x3 convolution to `stem` channels, three groups of basic blocks of
+    width, 2*width and 4*width channels (stride 2 at the start of the second and third), batch norm, ReLU,
+    global average pooling, fully connected layer.  Weights as for the bottleneck network: Kaiming-normal
+    (fan-out) convolutions, batch-norm gain 1 / shift 0 (plus N(0, bn_jitter) in tests), fully connected
+    layer N(0, 0.01) with zero bias; images N(0, 1); labels uniform over the classes."""
+    k = [0]
+
+    def nxt():
+        k[0] += 1
+        return seed + 7919 * k[0]
+
+    def conv(co, r, ci):
+        return normal(nxt(), (co, r, r, ci), (2.0 / (r * r * co)) ** 0.5)
+
+    def bn(c):
+        g, b = np.ones(c), np.zeros(c)
+        if bn_jitter:
+            g = g + normal(nxt(), (c,), bn_jitter)
+            b = b + normal(nxt(), (c,), bn_jitter)
+        return g, b
+
+    params = dict(stem=dict(w=conv(stem, 3, 3)), blocks=[], head=None)
+    cin = stem
+    for gi, nb in enumerate(group_blocks):
+        cout = width << gi
+        for j in range(nb):
+            p = {}
+            p["g1"], p["b1"] = bn(cin)
+            p["w1"] = conv(cout, 3, cin)
+            p["g2"], p["b2"] = bn(cout)
+            p["w2"] = conv(cout, 3, cout)
+            if cin != cout:
+                p["ws"] = conv(cout, 1, cin)
+            params["blocks"].append((p, 2 if (j == 0 and gi > 0) else 1))
+            cin = cout
+    g, b = bn(cin)
+    params["head"] = dict(g=g, b=b, w=normal(nxt(), (classes, cin), 0.01), bias=np.zeros(classes))
+    images = normal(nxt(), (batch, image, image, 3))
+    labels = randint(nxt(), (batch,), classes)
+    return params, images, labels
