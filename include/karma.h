@@ -199,7 +199,16 @@ int karma_stage_string(const karma_op* ops, uint32_t n_ops, char* buf, size_t bu
 
 /* ---- model and context ---------------------------------------------------------- */
 
-typedef enum { KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2, KARMA_MODEL_CNN = 3 } karma_model_kind;
+/* KARMA_MODEL_WRN: a wide residual network (the WRN-28-10 row of Table III).  width = channels of the first
+ * group (160 = 16 * 10), stage_blocks[0..2] = basic blocks per group (4, 4, 4; stage_blocks[3] must be 0), group k
+ * has width << k channels and starts with stride 2 (group 0: 1); seq = image size (32, a multiple of 4); vocab =
+ * classes, a multiple of 8 (10 classes are stored as 16: rows 10..15 of the fully connected weight zero and their
+ * bias -30000, so that their probabilities and gradients are exactly zero).  Records: 0 = the 3x3 convolution to 16
+ * channels (one tensor: its weight, 3 image channels stored as 8); 1.. = pre-activated basic blocks (tensors: BN1
+ * gain, BN1 shift, first 3x3 weight, BN2 gain, BN2 shift, second 3x3 weight and, where the shape changes, the 1x1
+ * shortcut weight, which convolves the activated input); loss record: batch norm, ReLU, global average pooling, fully
+ * connected layer, mean cross entropy (tensors: gain, shift, weight, bias).  No dropout.  Inputs as for the CNN. */
+typedef enum { KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2, KARMA_MODEL_CNN = 3, KARMA_MODEL_WRN = 4 } karma_model_kind;
 /* SGD with momentum: buf = beta1 * buf + g; w -= lr * buf (no dampening, no Nesterov) */
 typedef enum { KARMA_OPT_SGD = 1, KARMA_OPT_ADAM = 2, KARMA_OPT_SGD_MOMENTUM = 3 } karma_opt_kind;
 
@@ -518,6 +527,10 @@ typedef struct {
 /* y[n][ho][wo][c_out] = sum over the r x s taps and c_in channels, padding counting as
  * zero: the direct convolution of Sec. III-C computed as an implicit GEMM (no im2col). */
 int karma_k_conv2d_fwd_bf16(const void* x_dev, const void* w_dev, void* y_dev, const karma_conv_shape* shape, void* stream);
+/* The same with add_dev (y's shape, may be NULL) added to the result before it is rounded: the residual
+ * sum of a pre-activated block, whose last layer is a convolution. */
+int karma_k_conv2d_fwd_add_bf16(const void* x_dev, const void* w_dev, const void* add_dev, void* y_dev,
+                                const karma_conv_shape* shape, void* stream);
 /* dx_dev [n][h][w][c_in] (+ add_dev, same shape, may be NULL) from dy_dev [n][ho][wo][c_out].
  * wt_ws_dev: r*s*c_in*c_out bf16 elements of workspace (transposed weights); may be NULL
  * for a 1x1 stride-1 convolution. */
@@ -544,6 +557,12 @@ int karma_k_batchnorm_fwd_bf16(const void* x_dev, const void* gamma_dev, const v
 int karma_k_batchnorm_bwd_bf16(const void* dy_dev, const void* x_dev, const void* stats_dev, const void* gamma_dev,
                                const void* beta_dev, uint32_t relu, void* dx_dev, void* dgamma_dev, void* dbeta_dev,
                                void* ws_dev, uint32_t rows, uint32_t c, void* stream);
+/* The same with add_dev (x's shape, may be NULL, may be dy_dev) added to dx before it is rounded: the gradient
+ * that reaches x through a shortcut around the normalisation. */
+int karma_k_batchnorm_bwd_add_bf16(const void* dy_dev, const void* x_dev, const void* stats_dev, const void* gamma_dev,
+                                   const void* beta_dev, uint32_t relu, const void* add_dev, void* dx_dev,
+                                   void* dgamma_dev, void* dbeta_dev, void* ws_dev, uint32_t rows, uint32_t c,
+                                   void* stream);
 /* dz = dy where y > 0, else 0; n elements, multiple of 8. */
 int karma_k_relu_mask_bwd_bf16(const void* dy_dev, const void* y_dev, void* dz_dev, uint64_t n, void* stream);
 /* 3x3 max pooling, stride 2, padding 1 (Sec. III-C pooling layer); the backward gives the

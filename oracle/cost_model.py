@@ -103,6 +103,32 @@ def cnn_blocks(width, stage_blocks, image, batch, classes):
     return blocks, loss
 
 
+def wrn_blocks(width, group_blocks, image, batch, classes, stem=16):
+    """Block 0: the first 3x3 convolution (3 -> stem channels).  Then the pre-activated basic blocks: batch
+    norm + ReLU on the input, 3x3 convolution carrying the stride, batch norm + ReLU, 3x3 convolution,
+    residual add, and a 1x1 shortcut convolution where the shape changes.  Loss: batch norm, ReLU, global
+    average pooling, fully connected layer, softmax cross entropy."""
+    hw, cin = image, stem
+    blocks = [(batch * hw * hw * stem * 3 * 3 * 3, 0)]
+    for gi in range(3):
+        cout = width << gi
+        for k in range(group_blocks[gi]):
+            stride = 2 if (k == 0 and gi > 0) else 1
+            ho = conv_out(hw, 3, stride, 1)
+            p_in, p_out = batch * hw * hw, batch * ho * ho
+            matrix = p_out * cout * 9 * cin + p_out * cout * 9 * cout
+            if cin != cout:
+                matrix += p_out * cout * cin
+            other = 9 * p_in * cin + p_in * cin         # BN + ReLU on the input
+            other += 9 * p_out * cout + p_out * cout    # BN + ReLU between the convolutions
+            other += p_out * cout                       # residual add
+            blocks.append((matrix, other))
+            hw, cin = ho, cout
+    pix = batch * hw * hw
+    loss = (batch * cin * classes, 9 * pix * cin + pix * cin + pix * cin + 2 * batch * classes)
+    return blocks, loss
+
+
 def times(blocks, loss, rates):
     """Per block (t_fwd, t_bwd, t_recompute) in ns and the loss op's time (forward + gradient)."""
     out = []

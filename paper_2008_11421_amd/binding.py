@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libkarma.so")
 
 KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN = range(5)
 OK, E_INVAL, E_BUDGET, E_OOM, E_HIP, E_STATE, E_HOSTMEM = 0, -1, -2, -3, -4, -5, -6
-MODEL_MLP, MODEL_GPT, MODEL_CNN = 1, 2, 3
+MODEL_MLP, MODEL_GPT, MODEL_CNN, MODEL_WRN = 1, 2, 3, 4
 OPT_SGD, OPT_ADAM, OPT_SGD_MOMENTUM = 1, 2, 3
 STEP_APPLY_OPTIMIZER = 1
 STEP_PROFILE = 2

@@ -14,7 +14,8 @@ namespace karma {
 
 enum RecordKind {
   REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_CNN_STEM = 4, REC_CNN_BLOCK = 5, REC_ATTN = 6, REC_FFN = 7,
-  REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11, REC_LOSS_CNN_HEAD = 12
+  REC_WRN_STEM = 8, REC_WRN_BLOCK = 9,
+  REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11, REC_LOSS_CNN_HEAD = 12, REC_LOSS_WRN_HEAD = 13
 };
 
 struct Param {

@@ -200,12 +200,12 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(const bf16_t* __restr
   }
 }
 
-// dx = g * rstd * (dy' - dbeta/M - xhat * dgamma/M)
+// dx = g * rstd * (dy' - dbeta/M - xhat * dgamma/M) (+ add)
 __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
                                                             const float* __restrict__ stats, const bf16_t* __restrict__ g,
                                                             const bf16_t* __restrict__ b, const float* __restrict__ dgamma,
-                                                            const float* __restrict__ dbeta, bf16_t* __restrict__ dx, int rows,
-                                                            int C, float inv_rows, int relu) {
+                                                            const float* __restrict__ dbeta, const bf16_t* __restrict__ add,
+                                                            bf16_t* __restrict__ dx, int rows, int C, float inv_rows, int relu) {
   const int nv = C / 8;
   const int VC = min(nv - (int)blockIdx.y * 256, 256), RL = 256 / VC;
   const int vc = threadIdx.x % VC, rl = threadIdx.x / VC;
@@ -233,6 +233,12 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(const bf16_t* __restr
       const float xh = (v[e] - mean[e]) * rstd[e];
       const float dd = (relu && !(xh * gg[e] + bb[e] > 0.f)) ? 0.f : d[e];
       v[e] = gg[e] * rstd[e] * (dd - k0[e] - xh * k1[e]);
+    }
+    if (add) {
+      float a[8];
+      unpack8(*(const u32x4*)(add + at), a);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += a[e];
     }
     *(u32x4*)(dx + at) = pack8(v);
   }
@@ -376,11 +382,12 @@ bool shape_ok(const ConvShape& c) {
 
 int conv_out_dim(int n, int k, int stride, int pad) { return (n + 2 * pad - k) / stride + 1; }
 
-int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s, void* ws, size_t ws_bytes) {
+int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s, void* ws, size_t ws_bytes,
+               const bf16_t* add) {
   if (!x || !w || !y || !shape_ok(c)) return KARMA_E_INVAL;
   const int Ho = conv_out_dim(c.H, c.R, c.stride, c.pad), Wo = conv_out_dim(c.W, c.S, c.stride, c.pad);
   GemmArgs g{};
-  g.A = x; g.B = w; g.C = y;
+  g.A = x; g.B = w; g.C = y; g.residual = add;
   g.M = c.N * Ho * Wo; g.N = c.Cout; g.K = c.R * c.S * c.Cin;
   g.a_kc = g.b_kc = true;
   g.lda = g.K; g.ldb = g.K; g.ldc = g.N;
@@ -468,7 +475,7 @@ int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t*
 }
 
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
-           float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s) {
+           float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s, const bf16_t* add) {
   if (!dy || !x || !stats || !g || !b || !dx || !dgamma || !dbeta || !ws || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
   const int bands = (rows + bn_band(c) - 1) / bn_band(c);
   hipLaunchKernelGGL(bn_partial_kernel<true>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, dy, stats, g, b, ws, rows,
@@ -476,7 +483,7 @@ int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* 
   hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, (const bf16_t*)nullptr, dbeta,
                      dgamma, 1);
   hipLaunchKernelGGL(bn_apply_bwd_kernel, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, dy, x, stats, g, b, dgamma, dbeta,
-                     dx, rows, c, 1.f / (float)rows, relu);
+                     add, dx, rows, c, 1.f / (float)rows, relu);
   return ok();
 }
 
@@ -528,6 +535,13 @@ extern "C" int karma_k_conv2d_fwd_bf16(const void* x, const void* w, void* y, co
   return conv2d_fwd((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, shape_of(c), (hipStream_t)stream, nullptr, 0);
 }
 
+extern "C" int karma_k_conv2d_fwd_add_bf16(const void* x, const void* w, const void* add, void* y, const karma_conv_shape* c,
+                                           void* stream) {
+  if (!c) return KARMA_E_INVAL;
+  return conv2d_fwd((const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, shape_of(c), (hipStream_t)stream, nullptr, 0,
+                    (const bf16_t*)add);
+}
+
 extern "C" int karma_k_conv2d_dgrad_bf16(const void* dy, const void* w, void* wt_ws, const void* add, void* dx,
                                          const karma_conv_shape* c, void* stream) {
   if (!c) return KARMA_E_INVAL;
@@ -554,6 +568,14 @@ extern "C" int karma_k_batchnorm_bwd_bf16(const void* dy, const void* x, const v
                                           uint32_t rows, uint32_t c, void* stream) {
   return bn_bwd((const bf16_t*)dy, (const bf16_t*)x, (const float*)stats, (const bf16_t*)gamma, (const bf16_t*)beta, (int)relu,
                 (bf16_t*)dx, (float*)dgamma, (float*)dbeta, (float*)ws, (int)rows, (int)c, (hipStream_t)stream);
+}
+
+extern "C" int karma_k_batchnorm_bwd_add_bf16(const void* dy, const void* x, const void* stats, const void* gamma,
+                                              const void* beta, uint32_t relu, const void* add, void* dx, void* dgamma,
+                                              void* dbeta, void* ws, uint32_t rows, uint32_t c, void* stream) {
+  return bn_bwd((const bf16_t*)dy, (const bf16_t*)x, (const float*)stats, (const bf16_t*)gamma, (const bf16_t*)beta, (int)relu,
+                (bf16_t*)dx, (float*)dgamma, (float*)dbeta, (float*)ws, (int)rows, (int)c, (hipStream_t)stream,
+                (const bf16_t*)add);
 }
 
 extern "C" int karma_k_relu_mask_bwd_bf16(const void* dy, const void* y, void* dz, uint64_t n, void* stream) {

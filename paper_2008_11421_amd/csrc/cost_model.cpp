@@ -82,6 +82,32 @@ void count_cnn(const karma_model_desc& d, std::vector<Ops>& blocks, Ops& loss) {
   loss = Ops(N * cin * d.vocab, N * hw * hw * cin + 2 * N * d.vocab);   // average pooling, FC, softmax cross entropy
 }
 
+// Wide residual network: first 3x3 convolution; basic blocks (batch norm + ReLU on the input, 3x3 convolution
+// carrying the stride, batch norm + ReLU, 3x3 convolution, residual add; 1x1 shortcut convolution where the shape
+// changes); loss record: batch norm, ReLU, average pooling, FC, softmax cross entropy.
+void count_wrn(const karma_model_desc& d, std::vector<Ops>& blocks, Ops& loss) {
+  const uint64_t N = d.batch;
+  int hw = (int)d.seq;
+  uint64_t cin = 16;
+  blocks.push_back(Ops(N * hw * hw * cin * 9 * 3, 0));
+  for (int gr = 0; gr < 3; ++gr) {
+    const uint64_t cout = (uint64_t)d.width << gr;
+    for (uint32_t k = 0; k < d.stage_blocks[gr]; ++k) {
+      const int stride = (k == 0 && gr > 0) ? 2 : 1;
+      const int ho = out_dim(hw, 3, stride, 1);
+      const uint64_t pin = N * hw * hw, pout = N * ho * ho;
+      uint64_t m = pout * cout * 9 * cin + pout * cout * 9 * cout;
+      const uint64_t o = 10 * pin * cin + 10 * pout * cout + pout * cout;
+      if (cin != cout) m += pout * cout * cin;
+      blocks.push_back(Ops(m, o));
+      hw = ho;
+      cin = cout;
+    }
+  }
+  const uint64_t pix = N * hw * hw;
+  loss = Ops(N * cin * d.vocab, 10 * pix * cin + pix * cin + 2 * N * d.vocab);
+}
+
 // ceil(ops * 1e9 / rate) with a 128-bit intermediate
 int64_t ops_time_ns(uint64_t ops, uint64_t rate) {
   const unsigned __int128 num = (unsigned __int128)ops * 1000000000ull;
@@ -110,6 +136,7 @@ extern "C" int karma_model_costs(const karma_model_desc* desc, const karma_devic
   if (desc->kind == KARMA_MODEL_MLP) count_mlp(*desc, blocks, loss);
   else if (desc->kind == KARMA_MODEL_GPT) count_gpt(*desc, blocks, loss);
   else if (desc->kind == KARMA_MODEL_CNN) count_cnn(*desc, blocks, loss);
+  else if (desc->kind == KARMA_MODEL_WRN) count_wrn(*desc, blocks, loss);
   else return KARMA_E_INVAL;
   if (blocks.size() != c.L) return KARMA_E_STATE;
   for (uint32_t i = 0; i < c.L; ++i) {

@@ -563,6 +563,7 @@ extern "C" int karma_model_layers(const karma_model_desc* d, uint32_t* n_out) {
   if (d->kind == KARMA_MODEL_MLP) *n_out = d->n_layers;
   else if (d->kind == KARMA_MODEL_GPT) *n_out = (d->split_blocks ? 2 * d->n_layers : d->n_layers) + 1;
   else if (d->kind == KARMA_MODEL_CNN) *n_out = 1 + d->stage_blocks[0] + d->stage_blocks[1] + d->stage_blocks[2] + d->stage_blocks[3];
+  else if (d->kind == KARMA_MODEL_WRN) *n_out = 1 + d->stage_blocks[0] + d->stage_blocks[1] + d->stage_blocks[2];
   else return KARMA_E_INVAL;
   return KARMA_OK;
 }

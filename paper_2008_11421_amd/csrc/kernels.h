@@ -93,9 +93,10 @@ int cast_f32_to_bf16(const float* x, bf16_t* y, size_t n, hipStream_t s);
 // ---- convolutional workload (conv_bn.hip): NHWC bf16, weights [c_out][r][s][c_in]
 struct ConvShape { int N, H, W, Cin, Cout, R, S, stride, pad; };
 int conv_out_dim(int n, int k, int stride, int pad);
-// ws / ws_bytes: optional fp32 workspace that lets a product with few output tiles split its reduction
+// ws / ws_bytes: optional fp32 workspace that lets a product with few output tiles split its reduction;
+// add (may be null): a tensor of y's shape added to the result (a residual sum)
 int conv2d_fwd(const bf16_t* x, const bf16_t* w, bf16_t* y, const ConvShape& c, hipStream_t s, void* ws = nullptr,
-               size_t ws_bytes = 0);
+               size_t ws_bytes = 0, const bf16_t* add = nullptr);
 size_t conv2d_dgrad_ws_elems(const ConvShape& c);   // elements of the transposed-weight buffer (0 for 1x1 stride 1)
 // dx = gradient w.r.t. the input (+ add, may be null)
 int conv2d_dgrad(const bf16_t* dy, const bf16_t* w, bf16_t* wt_ws, const bf16_t* add, bf16_t* dx, const ConvShape& c,
@@ -110,9 +111,10 @@ int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add,
 // the normalisation alone, from statistics already computed (recomputing an output)
 int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, int rows,
              int c, int relu, hipStream_t s);
-// relu != 0: dy first passes the ReLU that followed the normalisation (mask recomputed)
+// relu != 0: dy first passes the ReLU that followed the normalisation (mask recomputed);
+// add (may be null, may be dy): a tensor of x's shape added to dx (the gradient of a shortcut from x)
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
-           float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s);
+           float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s, const bf16_t* add = nullptr);
 int relu_mask_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dz, size_t n, hipStream_t s);
 int maxpool_fwd(const bf16_t* x, bf16_t* y, int n, int h, int w, int c, hipStream_t s);   // 3x3, stride 2, pad 1
 int maxpool_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int w, int c, hipStream_t s);

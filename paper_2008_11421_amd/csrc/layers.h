@@ -22,4 +22,11 @@ int cnn_prepare_late(Ctx& c);
 int cnn_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int cnn_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int cnn_loss(Ctx& c, const LayerIO& io, hipStream_t s);
+
+int wrn_build_records(Ctx& c);
+int wrn_prepare_step(Ctx& c, const void* in, const void* lab);
+int wrn_prepare_late(Ctx& c);
+int wrn_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int wrn_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int wrn_loss(Ctx& c, const LayerIO& io, hipStream_t s);
 }  // namespace karma

@@ -134,3 +134,68 @@ def distances(got, want):
     """Per tensor: ||got - want|| / scale_of(want)."""
     return {k: float(np.linalg.norm(np.asarray(got[k], np.float64).reshape(-1) - want[k].reshape(-1)) / scale_of(k, want))
             for k in want}
+
+
+# ------------------------------------------------------------------ wide residual network
+def _basic_fwd(p, x, stride):
+    n1, s1 = cnn.batchnorm_fwd(x, p["g1"], p["b1"])
+    o1 = q(np.maximum(n1, 0))
+    c1 = q(cnn.conv2d_fwd(o1, p["w1"], stride, 1))
+    n2, s2 = cnn.batchnorm_fwd(c1, p["g2"], p["b2"])
+    o2 = q(np.maximum(n2, 0))
+    sc = q(cnn.conv2d_fwd(o1, p["ws"], stride, 0)) if "ws" in p else x
+    return q(cnn.conv2d_fwd(o2, p["w2"], 1, 1) + sc), (n1, o1, s1, n2, o2, s2)
+
+
+def _basic_bwd(p, saved, dy, stride):
+    n1, o1, s1, n2, o2, s2 = saved
+    g = {}
+    do2, g["w2"] = cnn.conv2d_bwd(o2, p["w2"], dy, 1, 1)
+    dc1, g["g2"], g["b2"] = cnn.batchnorm_bwd(q(do2) * (n2 > 0), p["g2"], s2)
+    do1, g["w1"] = cnn.conv2d_bwd(o1, p["w1"], q(dc1), stride, 1)
+    if "ws" in p:
+        dos, g["ws"] = cnn.conv2d_bwd(o1, p["ws"], dy, stride, 0)
+        do1 = do1 + q(dos)
+    dx, g["g1"], g["b1"] = cnn.batchnorm_bwd(q(do1) * (n1 > 0), p["g1"], s1)
+    if "ws" not in p:
+        dx = dx + dy
+    return q(dx), g
+
+
+def wrn_step_bf16_storage(params, images, labels):
+    """Same signature and result layout as `oracle.wrn.wrn_step`, tensors between operations rounded to bf16."""
+    x = q(cnn.conv2d_fwd(images, params["stem"]["w"], 1, 1))
+    saved = []
+    for p, stride in params["blocks"]:
+        x, s = _basic_fwd(p, x, stride)
+        saved.append(s)
+    hd = params["head"]
+    n, sh = cnn.batchnorm_fwd(x, hd["g"], hd["b"])
+    o = q(np.maximum(n, 0))
+    feat = q(cnn.avgpool_fwd(o))
+    logits = q(nn.linear_fwd(feat, hd["w"], hd["bias"]))
+    loss, dlogits = nn.cross_entropy_fwd_bwd(logits, labels)
+    grads = {"blocks": [None] * len(params["blocks"]), "head": {}, "stem": {}}
+    dfeat, grads["head"]["w"], grads["head"]["bias"] = nn.linear_bwd(feat, hd["w"], q(dlogits))
+    do = q(cnn.avgpool_bwd(q(dfeat), o.shape))
+    dx, grads["head"]["g"], grads["head"]["b"] = cnn.batchnorm_bwd(do * (n > 0), hd["g"], sh)
+    dx = q(dx)
+    for i in range(len(params["blocks"]) - 1, -1, -1):
+        p, stride = params["blocks"][i]
+        dx, grads["blocks"][i] = _basic_bwd(p, saved[i], dx, stride)
+    _, grads["stem"]["w"] = cnn.conv2d_bwd(images, params["stem"]["w"], dx, 1, 1)
+    return loss, grads
+
+
+WRN_SMALL = dict(width=16, group_blocks=(1, 2, 1), image=16, batch=4, classes=16)
+
+
+def wrn_problem(dims, shift, seed=2008114204):
+    """Seeded wide residual network and batch; every batch-norm shift raised by `shift`; images on the bf16 grid."""
+    import synth_inputs as si
+    params, images, labels = si.wrn_problem(seed=seed, bn_jitter=0.1, **dims)
+    for p, _ in params["blocks"]:
+        p["b1"] = p["b1"] + shift
+        p["b2"] = p["b2"] + shift
+    params["head"]["b"] = params["head"]["b"] + shift
+    return params, q(images), labels.astype(np.int32)

@@ -69,3 +69,37 @@ def test_storage_variant_without_rounding_is_the_oracle(monkeypatch):
     assert loss == loss_s
     a, b = S.flat(grads), S.flat(grads_s)
     assert all(np.array_equal(a[k], b[k]) for k in a)
+
+
+# ------------------------------------------------------------------ wide residual network
+def wrn_floor(shift):
+    from oracle import wrn
+    params, images, labels = S.wrn_problem(S.WRN_SMALL, shift)
+    pr = S.rounded_params(params)
+    loss, grads = wrn.wrn_step(pr, images, labels)
+    loss_s, grads_s = S.wrn_step_bf16_storage(pr, images, labels)
+    return loss, loss_s, S.distances(S.flat(grads_s), S.flat(grads))
+
+
+def test_wide_residual_network_has_the_same_floor():
+    """The pre-activated network behaves like the bottleneck one: with free ReLU masks bf16 storage alone
+    moves most gradients five and more times the bar away; with stable masks a third still miss it."""
+    loss, loss_s, d0 = wrn_floor(0.0)
+    assert abs(loss - loss_s) <= 2e-3 * abs(loss)
+    v0 = np.array(sorted(d0.values()))
+    assert np.median(v0) >= 5 * BAR and v0.max() <= 0.8, v0
+    _, _, d3 = wrn_floor(3.0)
+    v3 = np.array(sorted(d3.values()))
+    assert (v3 > BAR).mean() >= 1 / 3 and v3.max() <= 0.2, v3
+    assert np.median(v3) <= 0.5 * np.median(v0)
+
+
+def test_wrn_storage_variant_without_rounding_is_the_oracle(monkeypatch):
+    from oracle import wrn
+    monkeypatch.setattr(S, "q", lambda a: np.asarray(a, np.float64))
+    params, images, labels = S.wrn_problem(S.WRN_SMALL, 0.0)
+    loss, grads = wrn.wrn_step(params, images, labels)
+    loss_s, grads_s = S.wrn_step_bf16_storage(params, images, labels)
+    assert loss == loss_s
+    a, b = S.flat(grads), S.flat(grads_s)
+    assert all(np.array_equal(a[k], b[k]) for k in a)

@@ -23,7 +23,32 @@ def cnn_desc(batch=64):
                 vocab=CNN["classes"], stream_weights=0, stage_blocks=CNN["stage_blocks"])
 
 
+WRN = dict(width=160, group_blocks=(4, 4, 4), image=32, batch=128, classes=16)
+
+
+def wrn_desc(batch=128):
+    return dict(kind=K.MODEL_WRN, n_layers=0, width=WRN["width"], batch=batch, seq=WRN["image"], n_heads=0, ffn=0,
+                vocab=WRN["classes"], stream_weights=0, stage_blocks=WRN["group_blocks"] + (0,))
+
+
 # ------------------------------------------------------------------ oracle pins
+def test_oracle_wrn_28_10_total_and_blocks():
+    """WRN-28-10 on a 32x32 image is known as a 5.2 G multiply-add network; its blocks written out."""
+    blocks, loss = CM.wrn_blocks(**dict(WRN, batch=1))
+    assert len(blocks) == 13
+    total = sum(b[0] for b in blocks) + loss[0]
+    assert 5.1e9 < total < 5.4e9
+    assert blocks[0] == (32 * 32 * 16 * 27, 0)
+    # first block: 16 -> 160 on 32x32, two 3x3 convolutions and the 1x1 shortcut
+    assert blocks[1][0] == 32 * 32 * (160 * 9 * 16 + 160 * 9 * 160 + 160 * 16)
+    assert blocks[1][1] == 32 * 32 * (10 * 16 + 10 * 160 + 160)
+    assert blocks[2][0] == 32 * 32 * 2 * 160 * 9 * 160
+    # first block of the second group: strided 3x3 from 32x32 to 16x16
+    assert blocks[5][0] == 16 * 16 * (320 * 9 * 160 + 320 * 9 * 320 + 320 * 160)
+    assert blocks[5][1] == 10 * 32 * 32 * 160 + 11 * 16 * 16 * 320
+    assert loss == (640 * 16, 11 * 8 * 8 * 640 + 2 * 16)
+
+
 def test_oracle_fully_connected_and_mlp_counts():
     blocks, loss = CM.mlp_blocks(width=256, n_layers=8, batch=32)
     assert len(blocks) == 8
@@ -95,6 +120,8 @@ def test_library_times_bit_exact():
                 *CM.gpt_blocks(n_layers=72, hidden=3072, heads=24, ffn=12288, vocab=51200, seq=1024, batch=8))
     for batch in (2, 64):
         check_times(cnn_desc(batch), *CM.cnn_blocks(**dict(CNN, batch=batch)))
+    for batch in (4, 128):
+        check_times(wrn_desc(batch), *CM.wrn_blocks(**dict(WRN, batch=batch)))
 
 
 def test_split_transformer_blocks_counts_and_bytes():
