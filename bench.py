@@ -41,6 +41,11 @@ WORKLOADS = {
                  "batch 4, vocab 51200, bf16 weights streamed per layer from pinned host memory (gradients land in "
                  "the same pinned buffers) and activations swapped, fp32 host master/Adam (about 225 GiB of host "
                  "memory), HBM budget 32 GiB"),
+    5: dict(cfg=dict(width=160, group_blocks=(4, 4, 4), image=32, batch=1024, classes=10),
+            budget=16 * GIB, arena=20 * GIB, seed=2008114206, stream=0, kind="wrn", low_budget=5 * GIB,
+            name="supplementary (Table III, second CNN family): WRN-28-10 (pre-activated basic blocks, widths 160/320/640), "
+                 "32x32x3 images, batch 1024, 10 classes stored as 16, BatchNorm + ReLU, bf16, host SGD with momentum, "
+                 "HBM budget 16 GiB"),
 }
 CFG = WORKLOADS[1]["cfg"]
 BUDGET = WORKLOADS[1]["budget"]
@@ -178,28 +183,50 @@ SAMPLING_NOTE = ("HIP events on the compute stream around one launch in eight of
 
 
 def bench_cnn(args, wl, K, si, torch, np, threads):
-    """configs[2]: the bottleneck CNN.  It fits its 32 GiB budget in-core (the planner returns
-    all-KEEP); a supplementary run under `low_budget` shows the out-of-core schedule."""
+    """configs[2]: the bottleneck CNN, and the wide residual network (the second CNN family of Table III).
+    Both fit their budget in-core (the planner returns all-KEEP); a supplementary run under `low_budget`
+    shows the out-of-core schedule."""
     cfg_m = wl["cfg"]
-    desc = dict(kind=K.MODEL_CNN, n_layers=0, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0, ffn=0,
-                vocab=cfg_m["classes"], stream_weights=0, stage_blocks=cfg_m["stage_blocks"])
     cfg = dict(optimizer=K.OPT_SGD_MOMENTUM, lr=1e-3, beta1=0.9, beta2=0.0, eps=0.0, host_threads=threads)
     t0 = time.perf_counter()
-    ctx = K.Context(desc, cfg, wl["arena"])
-    params, images, labels = si.cnn_problem(seed=wl["seed"], **cfg_m)
-    w = params["stem"]["w"]
-    wp = np.zeros(w.shape[:3] + (8,), dtype=np.float32)
-    wp[..., :3] = w
-    ctx.karma_set_param(0, 0, wp)
-    ctx.karma_set_param(0, 1, params["stem"]["g"])
-    ctx.karma_set_param(0, 2, params["stem"]["b"])
+    if wl["kind"] == "wrn":
+        classes = (cfg_m["classes"] + 7) // 8 * 8      # stored classes: the extra ones can never be predicted
+        desc = dict(kind=K.MODEL_WRN, n_layers=0, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0,
+                    ffn=0, vocab=classes, stream_weights=0, stage_blocks=tuple(cfg_m["group_blocks"]) + (0,))
+        ctx = K.Context(desc, cfg, wl["arena"])
+        params, images, labels = si.wrn_problem(seed=wl["seed"], **cfg_m)
+        tensors = si.BASIC_TENSORS
+        w = params["stem"]["w"]
+        wp = np.zeros(w.shape[:3] + (8,), dtype=np.float32)
+        wp[..., :3] = w
+        ctx.karma_set_param(0, 0, wp)
+        L = len(params["blocks"]) + 1
+        hd = params["head"]
+        fc = np.zeros((classes, hd["w"].shape[1]), dtype=np.float32)
+        fc[:cfg_m["classes"]] = hd["w"]
+        bias = np.full(classes, -30000.0, dtype=np.float32)
+        bias[:cfg_m["classes"]] = hd["bias"]
+        for t, v in enumerate((hd["g"], hd["b"], fc, bias)):
+            ctx.karma_set_param(L, t, v)
+    else:
+        desc = dict(kind=K.MODEL_CNN, n_layers=0, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0,
+                    ffn=0, vocab=cfg_m["classes"], stream_weights=0, stage_blocks=cfg_m["stage_blocks"])
+        ctx = K.Context(desc, cfg, wl["arena"])
+        params, images, labels = si.cnn_problem(seed=wl["seed"], **cfg_m)
+        tensors = si.BOTTLENECK_TENSORS
+        w = params["stem"]["w"]
+        wp = np.zeros(w.shape[:3] + (8,), dtype=np.float32)
+        wp[..., :3] = w
+        ctx.karma_set_param(0, 0, wp)
+        ctx.karma_set_param(0, 1, params["stem"]["g"])
+        ctx.karma_set_param(0, 2, params["stem"]["b"])
+        L = len(params["blocks"]) + 1
+        ctx.karma_set_param(L, 0, params["head"]["w"])
+        ctx.karma_set_param(L, 1, params["head"]["b"])
     for i, (p, _) in enumerate(params["blocks"]):
-        for t, name in enumerate(si.BOTTLENECK_TENSORS):
+        for t, name in enumerate(tensors):
             if name in p:
                 ctx.karma_set_param(i + 1, t, p[name])
-    L = len(params["blocks"]) + 1
-    ctx.karma_set_param(L, 0, params["head"]["w"])
-    ctx.karma_set_param(L, 1, params["head"]["b"])
     del params
     images = images.astype(np.float32)
     labels = labels.astype(np.int32)
@@ -302,7 +329,7 @@ def main():
     args = ap.parse_args()
     global CFG, BUDGET, ARENA, SEED
     wl = dict(WORKLOADS[args.config])
-    if args.layers and wl.get("kind") != "cnn" and 0 < args.layers < wl["cfg"]["n_layers"]:
+    if args.layers and wl.get("kind") not in ("cnn", "wrn") and 0 < args.layers < wl["cfg"]["n_layers"]:
         wl["cfg"] = dict(wl["cfg"], n_layers=args.layers)
         wl["name"] += " -- DEPTH TRUNCATED to %d blocks for this run" % args.layers
     CFG, BUDGET, ARENA, SEED = wl["cfg"], wl["budget"], wl["arena"], wl["seed"]
@@ -331,7 +358,7 @@ def main():
     torch.cuda.empty_cache()
 
     threads = int(os.environ.get("OMP_NUM_THREADS", "16"))
-    if wl.get("kind") == "cnn":
+    if wl.get("kind") in ("cnn", "wrn"):
         return bench_cnn(args, wl, K, si, torch, np, threads)
     desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=CFG["batch"], seq=CFG["seq"],
                 n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=wl["stream"],

@@ -126,6 +126,36 @@ def test_wrn_step_matches_oracle_and_plans_are_bit_identical(g, shift):
     ctx.close()
 
 
+def test_wrn_true_width_depth_one_block_per_group_batch_8(g):
+    """The widths, image size and strides of WRN-28-10 itself (16 -> 160 -> 320 -> 640 channels on 32 x 32
+    images), one block per group instead of four, batch 8: every shape of the full model's convolutions."""
+    dims = dict(width=160, group_blocks=(1, 1, 1), image=32, batch=8, classes=16)
+    params, images, labels = S.wrn_problem(dims, 3.0)
+    arena = 1 << 30
+    ctx = make_ctx(dims, arena)
+    n = ctx.n_layers
+    assert n == 4
+    load_params(ctx, params)
+    ctx.karma_set_plan(arena, [K.KEEP] * n)
+    loss = ctx.karma_step(images, labels)
+    ref = all_grads(ctx, params)
+    pr = S.rounded_params(params)
+    lo, go = wrn.wrn_step(pr, images, labels)
+    _, gs = S.wrn_step_bf16_storage(pr, images, labels)
+    og, sg = oracle_grads(go), oracle_grads(gs)
+    assert abs(loss - lo) <= 5e-3 * abs(lo), (loss, lo)
+    floor = S.distances(sg, og)
+    d = S.distances(ref, og)
+    bad = {k: (d[k], floor[k]) for k in d if not d[k] <= 0.5 * BAR + FLOOR_FACTOR * floor[k]}
+    assert not bad, bad
+    assert np.median([d[k] / (floor[k] + 1e-3) for k in d]) <= 1.25
+    ctx.karma_set_plan(arena, [K.SWAP, K.RC_KEEP, K.RC_CHAIN, K.RC_SWAP])
+    assert ctx.karma_step(images, labels) == loss
+    for name, v in all_grads(ctx, params).items():
+        assert np.array_equal(v, ref[name]), name
+    ctx.close()
+
+
 def test_wrn_sgd_momentum_step_lowers_the_loss(g):
     params, images, labels = S.wrn_problem(DIMS, 3.0)
     arena = 256 << 20
