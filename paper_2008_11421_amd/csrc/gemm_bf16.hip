@@ -329,11 +329,19 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
 // EDGE: the matrix need not be made of whole tiles.  Pieces of an operand tile that lie outside the matrix are
 // not fetched (their lanes are masked out of the direct load) and their 16 bytes of LDS are zeroed instead, so
 // that the products they enter vanish; results outside the matrix are not stored.
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0, bool EDGE = false>
+// CONV 1 (with EDGE, both operands k-contiguous): A is an NHWC tensor gathered through a convolution, rows =
+// pixels of the grid cg.Ho x cg.Wo, k = (tap, channel).  A 16-byte piece is eight channels of one (pixel, tap), so
+// the direct load takes it from wherever the convolution reads it, and pieces that fall on padding (or on the
+// holes of a strided convolution's gradient) are zeroed in LDS like pieces outside the matrix.  The pixel of each
+// of a lane's rows is decoded once per work item; per k-tile only (tap, channel) of the lane's two k offsets are
+// (multiplications by reciprocals: magic_c = 2^32 / C + 1, magic_s = 2^32 / S + 1, exact for the sizes admitted).
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0, bool EDGE = false, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                          int M, int N, int K, int lda, int ldb, int tiles_m,
                                                                          int tiles_n, int splits, int k_per_split,
-                                                                         GemmEpilogue ep, float* __restrict__ partial) {
+                                                                         GemmEpilogue ep, float* __restrict__ partial,
+                                                                         ConvGather cg, unsigned magic_c, unsigned magic_s) {
+  static_assert(CONV == 0 || (CONV == 1 && A_KC && B_KC && EDGE && ACT == 0), "the gathered form");
   constexpr int WAVES = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -416,9 +424,57 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
       *(KARMA_LDS(u32x4)*)(uintptr_t)(lds + 16 * lane) = u32x4{0, 0, 0, 0};
     }
   };
+  // CONV: where the pixels of this lane's CH_A rows lie, for the item whose tiles are being issued (dec_m0)
+  // one register per row: image << 20 | (h0 + CBIAS) << 10 | (w0 + CBIAS), (h0, w0) = top-left input position of
+  // the pixel's window (or, transposed, the pixel's own position plus the padding); image 4095 = row outside the matrix
+  constexpr int CBIAS = 64;   // keeps the packed coordinates non-negative
+  unsigned c_pix[CONV ? CH_A : 1], c_pix_next[CONV ? CH_A : 1];   // of the current item's rows, of the next item's
+  const int c_shift = cg.stride == 2 ? 1 : 0;
+  auto conv_decode = [&](int m0x, unsigned (&pix)[CONV ? CH_A : 1]) {
+    const int grid = cg.Ho * cg.Wo;
+#pragma unroll
+    for (int i = 0; i < CH_A; ++i) {
+      const int row = m0x + a_row + 8 * i;
+      const int img = row / grid, rem = row - img * grid;
+      const int ho = rem / cg.Wo, wo = rem - ho * cg.Wo;
+      const int h0 = cg.transposed ? ho + cg.pad : ho * cg.stride - cg.pad;
+      const int w0 = cg.transposed ? wo + cg.pad : wo * cg.stride - cg.pad;
+      pix[i] = ((unsigned)(row < M ? img : 4095) << 20) | ((unsigned)(h0 + CBIAS) << 10) | (unsigned)(w0 + CBIAS);
+    }
+  };
   // m0 / n0: the tile's first row of the operand; k0: the item's first k; kend: its last k + 1 (EDGE only)
-  auto issue_a = [&](int stage, size_t ao, int t, int m0 = 0, int k0 = 0, int kend = 0) {
+  // nxt (CONV): the tile belongs to the next item (whose rows were decoded into c_pix_next)
+  auto issue_a = [&](int stage, size_t ao, int t, int m0 = 0, int k0 = 0, int kend = 0, bool nxt = false) {
     const unsigned sa = lds0 + EXTRA + stage * STAGE + wave * (CH_A * 1024);
+    if constexpr (CONV == 1) {
+#pragma unroll
+      for (int i = 0; i < CH_A; ++i) {
+        // (tap, channel) of this piece's k; recomputed per piece: a few multiplications against registers held
+        // across the MFMA steps
+        const int k = k0 + t * BK + ((lane & 7) ^ ((4 * (i & 1) + (lane >> 4)) & 7)) * 8;
+        const int tap = (int)__umulhi((unsigned)k, magic_c);
+        const int ch = k - tap * cg.C;
+        const int r = (int)__umulhi((unsigned)tap, magic_s), sx = tap - r * cg.S;
+        const unsigned px = nxt ? c_pix_next[i] : c_pix[i];
+        const int img = (int)(px >> 20), h0 = (int)((px >> 10) & 1023u) - CBIAS, w0 = (int)(px & 1023u) - CBIAS;
+        int hi, wi;
+        bool ok = k < kend && img != 4095;
+        if (!cg.transposed) {
+          hi = h0 + r;
+          wi = w0 + sx;
+        } else {
+          const int th = h0 - r, tw = w0 - sx;
+          ok = ok && th >= 0 && tw >= 0 && !((th | tw) & c_shift);
+          hi = th >> c_shift;
+          wi = tw >> c_shift;
+        }
+        ok = ok && (unsigned)hi < (unsigned)cg.H && (unsigned)wi < (unsigned)cg.W;
+        const unsigned off = (unsigned)(((img * cg.H + hi) * cg.W + wi) * cg.C + ch) * 2u;
+        fetch_piece(A, off, sa + i * 1024, ok);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      return;
+    }
     const bf16_t* pa = A + ao + (A_KC ? (size_t)t * BK : (size_t)t * BK * lda);
 #pragma unroll
     for (int i = 0; i < CH_A; ++i)
@@ -431,8 +487,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
     for (int i = 0; i < CH_B; ++i)
       fetch_piece(pb, b_off[i], sb + i * 1024, !EDGE || piece_inside(B_KC, b_row, i, N - n0, kend - k0 - t * BK));
   };
-  auto issue = [&](int stage, size_t ao, size_t bo, int t, int m0 = 0, int n0 = 0, int k0 = 0, int kend = 0) {
-    issue_a(stage, ao, t, m0, k0, kend);
+  auto issue = [&](int stage, size_t ao, size_t bo, int t, int m0 = 0, int n0 = 0, int k0 = 0, int kend = 0, bool nxt = false) {
+    issue_a(stage, ao, t, m0, k0, kend, nxt);
     issue_b(stage, bo, t, n0, k0, kend);
   };
 
@@ -478,6 +534,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   decode(pos, m0, n0, kb, ke, split);
   size_t ao = a_origin(m0, kb), bo = b_origin(n0, kb);
   int s0 = 0;   // stage of the current item's first k-tile
+  if constexpr (CONV == 1) conv_decode(m0, c_pix);
   issue(s0, ao, bo, 0, m0, n0, kb, ke);
 
   for (;;) {
@@ -490,10 +547,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
       decode(pos + xcd_step, m0n, n0n, kbn, ken, splitn);
       aon = a_origin(m0n, kbn);
       bon = b_origin(n0n, kbn);
+      if constexpr (CONV == 1) conv_decode(m0n, c_pix_next);
     }
     lds_barrier_visible();   // the previous item's strip (which overlays stage s0 ^ 1) has been read out by every wavefront
     if (KT > 1) issue(s0 ^ 1, ao, bo, 1, m0, n0, kb, ke);
-    else if (have_next) issue(s0 ^ 1, aon, bon, 0, m0n, n0n, kbn, ken);
+    else if (have_next) issue(s0 ^ 1, aon, bon, 0, m0n, n0n, kbn, ken, true);
     if (KT > 1 || have_next) wait_vm<LPT>();   // everything older than the loads just issued: tile 0 has landed
     else wait_vm<0>();
     lds_barrier_visible();
@@ -532,7 +590,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
           wait_vm<0>();
           lds_barrier_visible();
           if (kt + 2 < KT) issue_a(st, ao, kt + 2, m0, kb, ke);
-          else if (have_next) issue_a(st, aon, 0, m0n, kbn, ken);
+          else if (have_next) issue_a(st, aon, 0, m0n, kbn, ken, true);
           __builtin_amdgcn_sched_barrier(0);
         }
         if (kk == KSTEPS - 1 && more) {
@@ -619,6 +677,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
     pos += xcd_step;
     m0 = m0n; n0 = n0n; kb = kbn; ke = ken; split = splitn;
     ao = aon; bo = bon;
+    if constexpr (CONV == 1) {
+#pragma unroll
+      for (int i = 0; i < CH_A; ++i) c_pix[i] = c_pix_next[i];
+    }
     s0 = st;
   }
 }
@@ -704,9 +766,17 @@ static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 bloc
     auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC, ACT, EDGE>;                                    \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);                \
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits, \
-                       k_per_split, ep, (float*)g.ws);                                                            \
+                       k_per_split, ep, (float*)g.ws, g.conv, 0u, 0u);                                            \
   } while (0)
-    if (g.act == 1) KARMA_DL_LAUNCH(true, true, 1);          // the layouts were checked by the caller
+    if (g.conv_mode == 1) {
+      if constexpr (EDGE) {
+        auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, true, true, 0, true, 1>;
+        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        const unsigned magic_c = (unsigned)((1ull << 32) / (unsigned)g.conv.C + 1), magic_s = (unsigned)((1ull << 32) / (unsigned)g.conv.S + 1);
+        hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,
+                           k_per_split, ep, (float*)g.ws, g.conv, magic_c, magic_s);
+      }
+    } else if (g.act == 1) KARMA_DL_LAUNCH(true, true, 1);          // the layouts were checked by the caller
     else if (g.act == 2) KARMA_DL_LAUNCH(true, false, 2);
     else if (g.a_kc && g.b_kc) KARMA_DL_LAUNCH(true, true, 0);
     else if (g.a_kc && !g.b_kc) KARMA_DL_LAUNCH(true, false, 0);
@@ -756,6 +826,10 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   } while (0)
   // whole tiles, 16-byte aligned rows: the direct-to-LDS kernel
   bool direct = false, whole = false;
+  if constexpr (CONVS && BM == 256) {
+    // a gathered first operand through the direct-to-LDS kernel (eligibility was checked by the caller)
+    launch_direct<BM, BN, BK, WGM, WGN, true>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
+  } else {
   if (!CONVS && BM == 256 && BN == 256 && BK == 64 && WGM == 2 && WGN == 4) {
     // (a lane's piece offsets inside a tile are kept as 32-bit byte counts)
     direct = g.M % 8 == 0 && g.N % 8 == 0 && g.K % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
@@ -781,6 +855,7 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   else if (g.a_kc && !g.b_kc) KARMA_GEMM_LAUNCH(true, false, 0, 0);
   else if (!g.a_kc && g.b_kc) KARMA_GEMM_LAUNCH(false, true, 0, 0);
   else KARMA_GEMM_LAUNCH(false, false, 0, 0);
+  }
 #undef KARMA_GEMM_LAUNCH
   if (splits > 1) {
     const size_t mn = (size_t)g.M * g.N;
@@ -836,6 +911,16 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
     // the gathered operand's index ranges must be what the convolution spans
     const long pixels = (long)cg.Ho * cg.Wo, taps_c = (long)cg.R * cg.S * cg.C;
     if (g.conv_mode == 1 ? (g.M % pixels || g.K != taps_c) : (g.K % pixels || g.N != taps_c)) return KARMA_E_INVAL;
+    // Large products with a gathered first operand (forward and input gradient) take the direct-to-LDS kernel
+    // with its 256 x 256 tile: worth it from 128 output channels on (below that most of the tile is empty).
+    // Its piece offsets are 32-bit byte counts and its index arithmetic assumes strides 1 and 2.
+    const uint64_t gathered_bytes = (uint64_t)(g.M / pixels) * cg.H * cg.W * cg.C * 2;
+    const long tiles256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);   // enough of the large tiles to fill the chip
+    if (g.conv_mode == 1 && g.N >= 128 && tiles256 >= 192 && g.K >= 128 && g.N % 8 == 0 && g.ldc % 8 == 0 && cg.stride <= 2 &&
+        cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 && cg.Ho + cg.pad + 64 < 1024 &&
+        cg.Wo + cg.pad + 64 < 1024 && g.M / pixels < 4095 && gathered_bytes < (1ull << 32) && (uint64_t)g.K * cg.C < (1ull << 31) &&
+        ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
+      return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
     return launch_cfg<128, 128, 64, 2, 2, true>(g, s);
   }
   if (g.M > 128 && g.N > 128) return launch_cfg<256, 256, 64, 2, 4>(g, s);

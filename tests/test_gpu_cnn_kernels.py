@@ -39,6 +39,12 @@ CONV_CASES = [
     (2, 14, 14, 256, 136, 1, 2, 0),    # strided 1x1 (projection shortcut)
     (2, 32, 32, 8, 64, 7, 2, 3),       # the stem: 3 channels stored as 8
     (1, 5, 5, 8, 8, 3, 1, 1),          # one tile, mostly padding
+    # large enough for the direct-to-LDS kernel with a gathered operand (>= 1024 pixels, >= 128 output channels)
+    (4, 20, 20, 160, 136, 3, 1, 1),    # forward and input gradient, every dimension leaves a tail
+    (4, 18, 18, 128, 136, 3, 2, 1),    # input gradient of a strided 3x3 (three taps in four fall between pixels)
+    (16, 16, 16, 256, 136, 1, 2, 0),   # strided 1x1, both directions
+    (2, 33, 31, 128, 128, 3, 1, 1),    # odd image sizes
+    (3, 24, 24, 136, 264, 5, 1, 2),    # 5x5 taps, two tile columns
 ]
 
 
