@@ -335,13 +335,19 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
 // holes of a strided convolution's gradient) are zeroed in LDS like pieces outside the matrix.  The pixel of each
 // of a lane's rows is decoded once per work item; per k-tile only (tap, channel) of the lane's two k offsets are
 // (multiplications by reciprocals: magic_c = 2^32 / C + 1, magic_s = 2^32 / S + 1, exact for the sizes admitted).
+// CONV 2 (with EDGE, both operands strided): B is gathered, k = pixels of the grid cg.Ho x cg.Wo, n = (tap, channel):
+// the weight gradient.  A lane's four k-rows are four pixels that change with every k-tile: each is decoded per tile
+// (image by a float reciprocal with an exact correction, row and column by reciprocal multiplication: magic_w =
+// 2^32 / Wo + 1, inv_grid = 1 / (Ho * Wo)).
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0, bool EDGE = false, int CONV = 0>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                          int M, int N, int K, int lda, int ldb, int tiles_m,
                                                                          int tiles_n, int splits, int k_per_split,
                                                                          GemmEpilogue ep, float* __restrict__ partial,
-                                                                         ConvGather cg, unsigned magic_c, unsigned magic_s) {
-  static_assert(CONV == 0 || (CONV == 1 && A_KC && B_KC && EDGE && ACT == 0), "the gathered form");
+                                                                         ConvGather cg, unsigned magic_c, unsigned magic_s,
+                                                                         unsigned magic_w, float inv_grid) {
+  static_assert(CONV == 0 || (CONV == 1 && A_KC && B_KC && EDGE && ACT == 0) || (CONV == 2 && !A_KC && !B_KC && EDGE && ACT == 0),
+                "the gathered forms");
   constexpr int WAVES = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -482,6 +488,30 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   };
   auto issue_b = [&](int stage, size_t bo, int t, int n0 = 0, int k0 = 0, int kend = 0) {
     const unsigned sb = lds0 + EXTRA + stage * STAGE + A_BYTES + wave * (CH_B * 1024);
+    if constexpr (CONV == 2) {
+      const int grid = cg.Ho * cg.Wo;
+#pragma unroll
+      for (int i = 0; i < CH_B; ++i) {
+        // n = (tap, channel) of this piece's eight columns
+        const int n = n0 + ((lane & 31) ^ ((2 * (i & 1) + (lane >> 5)) << 2)) * 8;
+        const int tap = (int)__umulhi((unsigned)n, magic_c);
+        const int ch = n - tap * cg.C;
+        const int r = (int)__umulhi((unsigned)tap, magic_s), sx = tap - r * cg.S;
+        // its k-row is one pixel
+        const int p = k0 + t * BK + b_row + 2 * i;
+        int img = (int)((float)p * inv_grid);
+        int rem = p - img * grid;
+        if (rem < 0) { --img; rem += grid; }
+        if (rem >= grid) { ++img; rem -= grid; }
+        const int ho = (int)__umulhi((unsigned)rem, magic_w), wo = rem - ho * cg.Wo;
+        const int hi = ho * cg.stride - cg.pad + r, wi = wo * cg.stride - cg.pad + sx;
+        const bool ok = p < kend && n < N && (unsigned)hi < (unsigned)cg.H && (unsigned)wi < (unsigned)cg.W;
+        const unsigned off = (unsigned)(((img * cg.H + hi) * cg.W + wi) * cg.C + ch) * 2u;
+        fetch_piece(B, off, sb + i * 1024, ok);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      return;
+    }
     const bf16_t* pb = B + bo + (B_KC ? (size_t)t * BK : (size_t)t * BK * ldb);
 #pragma unroll
     for (int i = 0; i < CH_B; ++i)
@@ -766,15 +796,24 @@ static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 bloc
     auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, AK, BKC, ACT, EDGE>;                                    \
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);                \
     hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits, \
-                       k_per_split, ep, (float*)g.ws, g.conv, 0u, 0u);                                            \
+                       k_per_split, ep, (float*)g.ws, g.conv, 0u, 0u, 0u, 0.f);                                   \
   } while (0)
-    if (g.conv_mode == 1) {
+    if (g.conv_mode) {
       if constexpr (EDGE) {
-        auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, true, true, 0, true, 1>;
-        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         const unsigned magic_c = (unsigned)((1ull << 32) / (unsigned)g.conv.C + 1), magic_s = (unsigned)((1ull << 32) / (unsigned)g.conv.S + 1);
-        hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,
-                           k_per_split, ep, (float*)g.ws, g.conv, magic_c, magic_s);
+        const unsigned magic_w = (unsigned)((1ull << 32) / (unsigned)g.conv.Wo + 1);
+        const float inv_grid = 1.0f / (float)(g.conv.Ho * g.conv.Wo);
+        if (g.conv_mode == 1) {
+          auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, true, true, 0, true, 1>;
+          (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+          hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,
+                             k_per_split, ep, (float*)g.ws, g.conv, magic_c, magic_s, magic_w, inv_grid);
+        } else {
+          auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, false, false, 0, true, 2>;
+          (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+          hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,
+                             k_per_split, ep, (float*)g.ws, g.conv, magic_c, magic_s, magic_w, inv_grid);
+        }
       }
     } else if (g.act == 1) KARMA_DL_LAUNCH(true, true, 1);          // the layouts were checked by the caller
     else if (g.act == 2) KARMA_DL_LAUNCH(true, false, 2);
@@ -920,6 +959,14 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
         cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 && cg.Ho + cg.pad + 64 < 1024 &&
         cg.Wo + cg.pad + 64 < 1024 && g.M / pixels < 4095 && gathered_bytes < (1ull << 32) && (uint64_t)g.K * cg.C < (1ull << 31) &&
         ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
+      return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
+    // The weight gradient (second operand gathered, reduction over the pixels): few output tiles and a very long
+    // reduction, which the split fills the chip with; worth the large tile from 128 x 1024 results on.
+    if (g.conv_mode == 2 && g.M >= 128 && g.N >= 1024 && g.K >= 4096 && g.M % 8 == 0 && g.lda % 8 == 0 && g.ldc % 8 == 0 &&
+        g.ws != nullptr && cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 &&
+        (uint64_t)(g.K / pixels) * cg.H * cg.W * cg.C * 2 < (1ull << 32) && (uint64_t)g.N * cg.C < (1ull << 31) &&
+        pixels < (1 << 16) && g.K < (1 << 24) && ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 &&
+        (uint64_t)g.lda * 2 * 256 < (1ull << 31))
       return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
     return launch_cfg<128, 128, 64, 2, 2, true>(g, s);
   }

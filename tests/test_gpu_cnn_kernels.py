@@ -45,6 +45,8 @@ CONV_CASES = [
     (16, 16, 16, 256, 136, 1, 2, 0),   # strided 1x1, both directions
     (2, 33, 31, 128, 128, 3, 1, 1),    # odd image sizes
     (3, 24, 24, 136, 264, 5, 1, 2),    # 5x5 taps, two tile columns
+    (8, 24, 24, 128, 136, 3, 1, 1),    # weight gradient over 4608 pixels: the gathered second operand
+    (32, 32, 32, 128, 160, 3, 2, 1),   # the same, strided, 8192 pixels
 ]
 
 
