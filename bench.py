@@ -107,6 +107,54 @@ def profiled_traffic(plan):
     return None
 
 
+def bandwidth_kernels(K, torch):
+    """The HBM-bound kernels of the step at the workload's shapes, timed standalone with events on the stream
+    they are launched on; each call works on its own buffers out of a ring larger than the 256 MB last-level
+    cache, so that what is measured is memory, not cache.  Algorithmic bytes: what the kernel has to read and
+    write once (LayerNorm forward x, y; its backward dy, x, the residual gradient it adds, dx; softmax
+    cross-entropy reads the logits and writes their gradient)."""
+    import ctypes as C
+    lib = K.lib()
+    rows, h, vocab, chunk = CFG["batch"] * CFG["seq"], CFG["hidden"], CFG["vocab"], 4096
+    s = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: C.c_void_p(t.data_ptr())
+    ring = 6
+    bf = lambda *shape: [torch.randn(*shape, device="cuda").to(torch.bfloat16) for _ in range(ring)]
+    x, y, dy, add = bf(rows, h), bf(rows, h), bf(rows, h), bf(rows, h)
+    g = torch.ones(h, device="cuda").to(torch.bfloat16)
+    b = torch.zeros(h, device="cuda").to(torch.bfloat16)
+    stats = torch.empty(rows, 2, dtype=torch.float32, device="cuda")
+    ws = torch.empty((rows + 63) // 64 * 3 * h, dtype=torch.float32, device="cuda")
+    dg, db, cs = (torch.empty(h, dtype=torch.float32, device="cuda") for _ in range(3))
+    logits = bf(chunk, vocab)
+    labels = torch.randint(0, vocab, (chunk,), dtype=torch.int32, device="cuda")
+    rowloss = torch.empty(chunk, dtype=torch.float32, device="cuda")
+    lib.karma_k_layernorm_fwd_bf16(p(x[0]), p(g), p(b), p(y[0]), p(stats), rows, h, s)   # statistics for the backward
+    calls = {
+        "layernorm_fwd": (4 * rows * h, lambda k: lib.karma_k_layernorm_fwd_bf16(p(x[k]), p(g), p(b), p(y[k]), p(stats), rows, h, s)),
+        "layernorm_bwd_with_residual_gradient_and_its_column_sums":
+            (8 * rows * h, lambda k: lib.karma_k_layernorm_bwd_addsum_bf16(p(dy[k]), p(x[k]), p(stats), p(g), p(add[k]), p(y[k]), p(dg),
+                                                                        p(db), p(cs), p(ws), C.c_uint64(ws.numel() * 4), rows, h, s)),
+        "softmax_cross_entropy_4096_rows": (4 * chunk * vocab, lambda k: lib.karma_k_softmax_ce_bf16(p(logits[k]), p(labels), p(rowloss), chunk, vocab,
+                                                                                                C.c_float(1.0 / chunk), s)),
+    }
+    out = {}
+    for name, (nbytes, f) in calls.items():
+        for k in range(ring):
+            assert f(k) == 0, name
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 4 * ring
+        e0.record()
+        for k in range(reps):
+            f(k % ring)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        out[name] = {"algorithmic_bytes": nbytes, "avg_us": us, "achieved_gbps": nbytes / us / 1e3, "frac_of_8000_gbps": nbytes / us / 1e3 / 8000.0}
+    return out
+
+
 def cpu_baseline(n_seq):
     """The oracle as it stands, timed on the host: a few sequences at true widths with the
     depth truncated to 1 and to 2 blocks; block and head costs extrapolated to 24 blocks."""
@@ -577,6 +625,9 @@ def main():
     ctx.close()
     del ctx
     torch.cuda.empty_cache()
+    if args.config == 1 and not args.no_policies:
+        out["bandwidth_bound_kernels"] = bandwidth_kernels(K, torch)
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(CPU_SAMPLE_BATCH if args.config == 1 else 1)
     print(json.dumps(out), flush=True)

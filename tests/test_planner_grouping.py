@@ -23,8 +23,8 @@ def test_merge_and_expand_rules():
 
 def test_grouped_plan_is_valid_and_never_worse_than_plain():
     n = 0
-    for L in (5, 9):
-        for layers, link, budget, loss in cases(L, seeds=(0,), fracs=(0.35, 0.7), bwmuls=(0.3, 4.0)):
+    for L, kinds in ((5, ("homogeneous", "front_heavy", "back_heavy", "imbalanced")), (9, ("back_heavy", "imbalanced"))):
+        for layers, link, budget, loss in cases(L, seeds=(0,), kinds=kinds, fracs=(0.35, 0.7), bwmuls=(0.3, 4.0)):
             try:
                 acts, res, g = P.plan_grouped(layers, link, budget, 0, loss)
             except P.Infeasible:
@@ -61,8 +61,8 @@ def test_many_small_layers_behind_a_slow_link_prefer_blocks():
 
 def test_library_bit_exact():
     n = 0
-    for L, seeds in ((6, (0,)), (11, (2,))):
-        for base, link, budget, loss in cases(L, seeds=seeds, fracs=(0.35, 0.7), bwmuls=(1.0,)):
+    for L, seeds, kinds in ((6, (0,), ("homogeneous", "front_heavy", "back_heavy", "imbalanced")), (11, (2,), ("front_heavy", "imbalanced"))):
+        for base, link, budget, loss in cases(L, seeds=seeds, kinds=kinds, fracs=(0.35, 0.7), bwmuls=(1.0,)):
             for layers in (base, with_weights(base, 5, scale=1.5)):
                 bud = budget + (2 * max(P.al(l.wb) + P.al(l.gb) for l in layers) if layers is not base else 0)
                 try:
