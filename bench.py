@@ -155,6 +155,76 @@ def bandwidth_kernels(K, torch):
     return out
 
 
+def batch_sweep(args, K, si, torch, np, threads):
+    """The benchmark model across batch sizes under one fixed HBM budget (the x-axis of the paper's Fig. 5: the
+    first points fit the budget, the rest do not), each beside the same batch with all of HBM (in-core) and beside
+    what the analytic cost model (operation counts on two device rates, no measurement of the model) projects.
+    One JSON line; not the benchmark line."""
+    rows = []
+    rates = (490 * 10**12, 3 * 10**12)      # multiply-adds per second on the matrix cores, other operations per second
+    for batch in (8, 16, 32, 64, 128):
+        desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=batch, seq=CFG["seq"],
+                    n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=0, split_blocks=1)
+        a_layers, a_loss, fixed = K.karma_model_costs(desc, *rates)
+        in_core_need = fixed + sum(l[3] + l[4] for l in a_layers) + 2 * max(max(l[5] for l in a_layers), a_loss[1])
+        arena = max(min(in_core_need + 2 * GIB, 200 * GIB), BUDGET) // 256 * 256
+        cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
+        ctx = K.Context(desc, cfg, arena)
+        params, ids, labels = si.gpt_problem(seed=SEED, n_layers=1, hidden=CFG["hidden"], ffn=CFG["ffn"], vocab=CFG["vocab"],
+                                             seq=CFG["seq"], batch=batch)
+        ctx.karma_set_param(0, 0, params["wte"])
+        ctx.karma_set_param(0, 1, params["wpe"])
+        for i in range(CFG["n_layers"]):
+            for t, name in enumerate(si.GPT_BLOCK_TENSORS):
+                v = np.roll(np.asarray(params["blocks"][0][name], dtype=np.float32).reshape(-1), 97 * i)
+                ctx.karma_set_param(2 * i + 1 if t < 6 else 2 * i + 2, t if t < 6 else t - 6, v)
+        ctx.karma_set_param(2 * CFG["n_layers"] + 1, 0, params["lnf_g"])
+        ctx.karma_set_param(2 * CFG["n_layers"] + 1, 1, params["lnf_b"])
+        ids, labels = ids.astype(np.int32), labels.astype(np.int32)
+        link = ctx.karma_measure(2)
+
+        def timed(budget):
+            acts, summ = ctx.karma_plan(budget)
+            for _ in range(2):
+                ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+            ctx.karma_finish_updates()
+            torch.cuda.synchronize()
+            per_step = []
+            for _ in range(max(3, args.steps // 4)):
+                t1 = time.perf_counter()
+                ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
+                per_step.append(time.perf_counter() - t1)
+            ctx.karma_finish_updates()
+            torch.cuda.synchronize()
+            return acts, summ, median(per_step)
+
+        acts_in, _, dt_in = timed(arena)
+        ctx.karma_refine_host_costs()
+        acts, summ, dt = timed(BUDGET)
+        # the analytic projection of the same question: planned step over in-core step
+        link3 = (int(link[0]), int(link[1]), int(link[2]))
+        try:
+            _, s_an = K.karma_plan_pure(a_layers, link3, a_loss, BUDGET, fixed)
+            _, s_an_in = K.karma_plan_pure(a_layers, link3, a_loss, 1 << 50, fixed)
+            analytic_pct = 100.0 * s_an_in["makespan_ns"] / s_an["makespan_ns"]
+        except K.KarmaError:
+            analytic_pct = None
+        row = {"batch": batch, "in_core_fits_budget": acts == [K.KEEP] * len(acts), "in_core_ms_per_step": dt_in * 1e3,
+               "in_core_samples_per_s": batch / dt_in, "budget_ms_per_step": dt * 1e3, "budget_samples_per_s": batch / dt,
+               "pct_of_in_core": 100.0 * dt_in / dt, "predicted_ms": summ["makespan_ns"] / 1e6,
+               "analytic_model_pct_of_in_core": analytic_pct, "plan": "".join("KSRrc"[a] for a in acts),
+               "in_core_arena_gib": arena / GIB, "link_gib_each_way": [summ["bytes_d2h"] / GIB, summ["bytes_h2d"] / GIB]}
+        log("batch %d: in-core %.1f ms (%.0f samples/s, arena %.0f GiB), %d GiB budget %.1f ms (%.0f samples/s, %.1f %%), plan %s"
+            % (batch, dt_in * 1e3, batch / dt_in, arena / GIB, BUDGET // GIB, dt * 1e3, batch / dt, 100 * dt_in / dt, row["plan"]))
+        row["in_core_run_kept_everything"] = acts_in == [K.KEEP] * len(acts_in)
+        rows.append(row)
+        ctx.close()
+        del ctx
+        torch.cuda.empty_cache()
+    print(json.dumps({"what": "batch sweep of the configs[1] model under a %d GiB HBM budget, beside the same batch in-core"
+                              % (BUDGET // GIB), "unit": "samples/s", "data": "synthetic", "dtype": "bf16", "rows": rows}), flush=True)
+
+
 def cpu_baseline(n_seq):
     """The oracle as it stands, timed on the host: a few sequences at true widths with the
     depth truncated to 1 and to 2 blocks; block and head costs extrapolated to 24 blocks."""
@@ -372,6 +442,8 @@ def main():
                     help="plan on the committed cost records of this workload (default; falls back to this run's own "
                          "measurements when there are none) or on this run's measurements")
     ap.add_argument("--save-costs", action="store_true", help="write this run's measured cost records to the committed file")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="configs[1] only: batches 8..128 under the budget and in-core (a supplementary line, not the benchmark)")
     ap.add_argument("--layers", type=int, default=0,
                     help="GPT workloads: truncate the depth to this many blocks (named in config.workload)")
     args = ap.parse_args()
@@ -408,6 +480,11 @@ def main():
     threads = int(os.environ.get("OMP_NUM_THREADS", "16"))
     if wl.get("kind") in ("cnn", "wrn"):
         return bench_cnn(args, wl, K, si, torch, np, threads)
+    if args.batch_sweep:
+        if args.config != 1:
+            print("bench.py: --batch-sweep is for the default workload", file=sys.stderr)
+            sys.exit(2)
+        return batch_sweep(args, K, si, torch, np, threads)
     desc = dict(kind=K.MODEL_GPT, n_layers=CFG["n_layers"], width=CFG["hidden"], batch=CFG["batch"], seq=CFG["seq"],
                 n_heads=CFG["heads"], ffn=CFG["ffn"], vocab=CFG["vocab"], stream_weights=wl["stream"],
                 split_blocks=0 if (args.whole_blocks or wl.get("whole_blocks")) else 1)
