@@ -168,10 +168,12 @@ __global__ __launch_bounds__(256) void bn_finish_kernel(const float* __restrict_
 
 // y = (x - mean) * rstd * g + b (+ add) (ReLU).  Same thread layout as the partial sums: a
 // thread keeps its eight channels' scale and shift in registers and walks the rows of a band.
+// gate (may be null): instead of the value itself, gate's element is written where the value as stored (bf16)
+// is positive and zero elsewhere: the gradient through the ReLU, without a pass of its own.
 __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(const bf16_t* __restrict__ x, const float* __restrict__ stats,
                                                             const bf16_t* __restrict__ g, const bf16_t* __restrict__ b,
-                                                            const bf16_t* __restrict__ add, bf16_t* __restrict__ y, int rows,
-                                                            int C, int relu) {
+                                                            const bf16_t* __restrict__ add, const bf16_t* __restrict__ gate,
+                                                            bf16_t* __restrict__ y, int rows, int C, int relu) {
   const int nv = C / 8;
   const int VC = min(nv - (int)blockIdx.y * 256, 256), RL = 256 / VC;
   const int vc = threadIdx.x % VC, rl = threadIdx.x / VC;
@@ -196,7 +198,17 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(const bf16_t* __restr
       if (add) t += a[e];
       v[e] = relu ? fmaxf(t, 0.f) : t;
     }
-    *(u32x4*)(y + at) = pack8(v);
+    u32x4 out = pack8(v);
+    if (gate) {
+      const u32x4 gv = *(const u32x4*)(gate + at);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const unsigned w = out[k];
+        const unsigned keep = ((w & 0x7fffu) && !(w & 0x8000u) ? 0xffffu : 0u) | ((w & 0x7fff0000u) && !(w & 0x80000000u) ? 0xffff0000u : 0u);
+        out[k] = gv[k] & keep;
+      }
+    }
+    *(u32x4*)(y + at) = out;
   }
 }
 
@@ -462,15 +474,15 @@ int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add,
                      (const float*)nullptr, g, b, ws, rows, c, 0);
   hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, x, stats, stats + c, 0);
   hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3((rows + bn_band(c) - 1) / bn_band(c), (c / 8 + 255) / 256), dim3(256), 0, s, x, stats,
-                     g, b, add, y, rows, c, relu);
+                     g, b, add, (const bf16_t*)nullptr, y, rows, c, relu);
   return ok();
 }
 
 int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, int rows,
-             int c, int relu, hipStream_t s) {
+             int c, int relu, hipStream_t s, const bf16_t* gate) {
   if (!x || !stats || !g || !b || !y || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
   hipLaunchKernelGGL(bn_apply_fwd_kernel, dim3((rows + bn_band(c) - 1) / bn_band(c), (c / 8 + 255) / 256), dim3(256), 0, s, x, stats,
-                     g, b, add, y, rows, c, relu);
+                     g, b, add, gate, y, rows, c, relu);
   return ok();
 }
 

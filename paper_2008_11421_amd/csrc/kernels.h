@@ -109,8 +109,10 @@ size_t bn_ws_bytes(int rows, int c);
 int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, float* stats, float* ws,
            int rows, int c, int relu, hipStream_t s);
 // the normalisation alone, from statistics already computed (recomputing an output)
+// gate (may be null): y receives gate's element where the value as stored is positive, zero elsewhere
+// (the gradient through the ReLU that follows the normalisation)
 int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, int rows,
-             int c, int relu, hipStream_t s);
+             int c, int relu, hipStream_t s, const bf16_t* gate = nullptr);
 // relu != 0: dy first passes the ReLU that followed the normalisation (mask recomputed);
 // add (may be null, may be dy): a tensor of x's shape added to dx (the gradient of a shortcut from x)
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,

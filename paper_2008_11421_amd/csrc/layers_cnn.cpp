@@ -351,11 +351,10 @@ int cnn_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s) {
   // (it is the next block's input and may be gone by now)
   if (g.proj) {
     TRY(bn_apply(cp, stp, W(GP), W(BP), nullptr, big2, g.P2(), g.cout, 0, s));
-    TRY(bn_apply(c3, st3, W(G3), W(B3), big2, dz, g.P2(), g.cout, 1, s));
+    TRY(bn_apply(c3, st3, W(G3), W(B3), big2, dz, g.P2(), g.cout, 1, s, dy));
   } else {
-    TRY(bn_apply(c3, st3, W(G3), W(B3), x, dz, g.P2(), g.cout, 1, s));
+    TRY(bn_apply(c3, st3, W(G3), W(B3), x, dz, g.P2(), g.cout, 1, s, dy));
   }
-  TRY(relu_mask_bwd(dy, dz, dz, (size_t)g.P2() * g.cout, s));
   // main branch
   TRY(bn_bwd(dz, c3, st3, W(G3), W(B3), 0, big2, (float*)G(G3), (float*)G(B3), bnws, g.P2(), g.cout, s));   // dc3
   TRY(conv2d_wgrad(big2, a2, (bf16_t*)G(W3), sk, wl.splitk_bytes, s3, s));
