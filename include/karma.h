@@ -215,12 +215,13 @@ typedef enum { KARMA_OPT_SGD = 1, KARMA_OPT_ADAM = 2, KARMA_OPT_SGD_MOMENTUM = 3
 typedef struct {
   uint32_t kind;      /* karma_model_kind */
   uint32_t n_layers;  /* MLP: Linear+ReLU layers; GPT: transformer blocks; CNN: ignored */
-  uint32_t width;     /* MLP width / GPT hidden size / CNN: bottleneck width of the first stage (64) */
+  uint32_t width;     /* MLP width / GPT hidden size / CNN: bottleneck width of the first stage (64) / WRN: channels of
+                         the first group (160) */
   uint32_t batch;
-  uint32_t seq;       /* GPT: sequence length; CNN: image height = width (multiple of 32) */
+  uint32_t seq;       /* GPT: sequence length; CNN: image height = width (multiple of 32); WRN: the same (multiple of 4) */
   uint32_t n_heads;   /* GPT only; width / n_heads must be 64, 128 or 152 */
   uint32_t ffn;       /* GPT only */
-  uint32_t vocab;     /* GPT: vocabulary; CNN: number of classes (multiple of 8) */
+  uint32_t vocab;     /* GPT: vocabulary; CNN, WRN: number of classes (multiple of 8) */
   uint32_t stream_weights; /* 1: the weights of every MLP layer / transformer block live in
                               pinned host memory and are streamed through the arena around the
                               layer's ops, their gradients streamed out after its backward
@@ -256,7 +257,8 @@ typedef struct {
 /* Number of plannable layer records of a model (MLP: n_layers; GPT: n_layers + 1, record
  * 0 being the embedding, or 2 n_layers + 1 with split_blocks: block k is then records 2k + 1
  * (attention half: tensors LN1 gain, LN1 shift, Wqkv, bqkv, Wo, bo) and 2k + 2 (feed-forward half:
- * LN2 gain, LN2 shift, W1, b1, W2, b2); CNN: 1 + sum of stage_blocks, record 0 being the stem) and
+ * LN2 gain, LN2 shift, W1, b1, W2, b2); CNN: 1 + sum of stage_blocks, record 0 being the stem; WRN: 1 + sum of
+ * stage_blocks[0..2], record 0 being the first convolution) and
  * of parameter tensors of record `layer`. */
 int karma_model_layers(const karma_model_desc* desc, uint32_t* n_out);
 
