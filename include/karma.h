@@ -355,7 +355,11 @@ int karma_plan_string(karma_ctx* ctx, char* buf, size_t buf_len);
  * the same shape.  GPT: inputs_host int32 token ids [batch, seq], labels_host int32
  * [batch, seq].  Synchronous: on return the loss is valid, all streams are drained and
  * gradients can be read; with KARMA_STEP_APPLY_OPTIMIZER some records' host updates may still
- * be pending (karma_finish_updates). */
+ * be pending (karma_finish_updates).  CNN, WRN: inputs_host fp32 images [batch][seq][seq][3], labels_host int32.
+ * inputs_host and labels_host both NULL: the batch of the previous karma_step, which is still resident in HBM
+ * (and in the pinned staging buffers), is used again without being converted or copied (a training loop whose
+ * data already lives on the device; KARMA_E_STATE when there is no such batch: before the first step, after
+ * karma_measure).  One of them NULL: KARMA_E_INVAL. */
 int karma_step(karma_ctx* ctx, const void* inputs_host, const void* labels_host, uint32_t flags, float* loss_out);
 
 typedef struct {

@@ -399,9 +399,14 @@ class Context:
     def karma_step(self, inputs, labels, flags=0):
         """inputs/labels: numpy arrays of the dtype the model takes (MLP: fp32 / fp32, GPT:
         int32 ids / int32, CNN: fp32 images [n][h][w][3] / int32 classes).  Returns the loss."""
+        loss = C.c_float()
+        if inputs is None and labels is None:      # the previous step's batch, still resident in HBM
+            with self.torch.cuda.device(self.device):
+                st = lib().karma_step(self.ctx, None, None, C.c_uint32(flags), C.byref(loss))
+            self._chk(st, "karma_step")
+            return loss.value
         a = np.ascontiguousarray(inputs, dtype=np.int32 if self.desc.kind == MODEL_GPT else np.float32)
         b = np.ascontiguousarray(labels, dtype=np.float32 if self.desc.kind == MODEL_MLP else np.int32)
-        loss = C.c_float()
         with self.torch.cuda.device(self.device):
             st = lib().karma_step(self.ctx, C.c_void_p(a.ctypes.data), C.c_void_p(b.ctypes.data), C.c_uint32(flags),
                                   C.byref(loss))

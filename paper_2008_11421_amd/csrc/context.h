@@ -87,6 +87,7 @@ struct Ctx {
   bool have_times = false;
 
   bool planned = false;
+  bool inputs_resident = false;           // the fixed region and the staging buffers hold a caller's batch
   uint64_t budget = 0;
   std::vector<uint8_t> actions;
   std::vector<uint8_t> keepw;             // per record: streamed weights stay from F_i to B_i

@@ -405,11 +405,16 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
   } timer_scope(c->ktime ? &timer : nullptr);
   double t0 = now_ms();
   c->stats = karma_step_stats{};
-  int st = model_prepare_step(*c, in, lab);
-  if (st) return st;
+  int st = KARMA_OK;
   hipStream_t sc = c->st[0];
-  KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->in_off), c->stage_in, c->in_bytes, hipMemcpyHostToDevice, sc));
-  KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->lab_off), c->stage_lab, c->lab_bytes, hipMemcpyHostToDevice, sc));
+  if (in) {
+    st = model_prepare_step(*c, in, lab);
+    if (st) return st;
+    KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->in_off), c->stage_in, c->in_bytes, hipMemcpyHostToDevice, sc));
+    KARMA_HIP(c, hipMemcpyAsync(c->fixed_ptr(c->lab_off), c->stage_lab, c->lab_bytes, hipMemcpyHostToDevice, sc));
+  } else if (!c->inputs_resident) {
+    return fail(c, KARMA_E_STATE, "karma_step without inputs before any step with inputs");
+  }
   if (apply) ++c->step_no;
   std::vector<std::pair<uint32_t, hipEvent_t>> done_order;   // record, event after which its gradients are on the host
   for (size_t k = 0; k < c->prog.size(); ++k) {
@@ -826,8 +831,10 @@ extern "C" int karma_plan_string(karma_ctx* c, char* buf, size_t len) {
 }
 
 extern "C" int karma_step(karma_ctx* c, const void* in, const void* lab, uint32_t flags, float* loss_out) {
-  if (!c || !in || !lab) return KARMA_E_INVAL;
-  return run_step(c, in, lab, flags, loss_out, (flags & KARMA_STEP_PROFILE) != 0);
+  if (!c || (in == nullptr) != (lab == nullptr)) return KARMA_E_INVAL;
+  const int st = run_step(c, in, lab, flags, loss_out, (flags & KARMA_STEP_PROFILE) != 0);
+  if (st == KARMA_OK && in) c->inputs_resident = true;
+  return st;
 }
 
 extern "C" int karma_finish_updates(karma_ctx* c) {
@@ -879,6 +886,7 @@ extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) 
   for (uint32_t i = 0; i < c->L; ++i) kw[i] = c->rec[i].streamed ? 1 : 0;
   int st = install_plan(c, c->arena_bytes, keep, kw);
   if (st) return st;
+  c->inputs_resident = false;   // the profiling steps below replace the caller's batch
   // inputs: whatever the staging buffers hold (zeros on a fresh context are valid ids / values)
   std::vector<char> in(c->in_bytes ? c->in_bytes : 1, 0), lab(c->lab_bytes ? c->lab_bytes : 1, 0);
   if (c->desc.kind == KARMA_MODEL_GPT) {   // spread token ids over the vocabulary, as real batches do

@@ -201,6 +201,31 @@ def test_cnn_sgd_momentum_and_streamed_weights(g):
         assert np.array_equal(res[0][3][key], res[1][3][key]), key
 
 
+def test_step_on_the_resident_batch_equals_the_step_with_inputs(g):
+    params, images, labels = small_problem()
+    arena = 256 << 20
+    ctx = make_ctx(SMALL, arena)
+    load_params(ctx, params)
+    ctx.karma_set_plan(arena, [K.KEEP, K.SWAP, K.RC_KEEP, K.KEEP, K.RC_SWAP, K.KEEP])
+    with pytest.raises(K.KarmaError) as e:
+        ctx.karma_step(None, None)              # nothing resident yet
+    assert e.value.status == K.E_STATE
+    loss = ctx.karma_step(images, labels)
+    ref = all_grads(ctx, params)
+    assert ctx.karma_step(None, None) == loss
+    for name, v in all_grads(ctx, params).items():
+        assert np.array_equal(v, ref[name]), name
+    other = images[::-1].copy()
+    l2 = ctx.karma_step(other, labels)
+    assert l2 != loss and ctx.karma_step(None, None) == l2
+    ctx.karma_measure(1)                        # profiling steps replace the batch
+    ctx.karma_set_plan(arena, [K.KEEP] * 6)
+    with pytest.raises(K.KarmaError) as e:
+        ctx.karma_step(None, None)
+    assert e.value.status == K.E_STATE
+    ctx.close()
+
+
 def test_cnn_rejects_bad_descriptions(g):
     with pytest.raises(K.KarmaError):
         make_ctx(dict(SMALL, image=60), 64 << 20)             # image size not a multiple of 32

@@ -96,6 +96,10 @@ def test_gpt_step_matches_oracle_and_plans_are_bit_identical(g):
     og = oracle_grads(go)
     for name, v in ref.items():
         assert g.rel_l2(v, og[name]) <= TOL, (name, g.rel_l2(v, og[name]))
+    # the same batch again, from where it already lies in HBM
+    assert ctx.karma_step(None, None) == loss
+    for name, v in all_grads(ctx, 3).items():
+        assert np.array_equal(v, ref[name]), name
 
     plans = [[K.KEEP, K.SWAP, K.SWAP, K.SWAP], [K.KEEP, K.RC_KEEP, K.RC_KEEP, K.RC_KEEP], [K.SWAP, K.RC_SWAP, K.RC_CHAIN, K.KEEP],
              [K.RC_KEEP, K.RC_CHAIN, K.RC_CHAIN, K.RC_CHAIN], [K.KEEP, K.RC_SWAP, K.SWAP, K.RC_KEEP]]
