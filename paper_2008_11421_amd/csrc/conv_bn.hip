@@ -50,6 +50,14 @@ __host__ __device__ inline int bn_band(int C) {
   return band < 16 ? 16 : band;
 }
 
+// Rows per workgroup of the partial sums: the band above, or longer when that would make more than 2048 bands (a
+// million pixels in 96-row bands are 11 000 partial rows, which the few workgroups of the finishing kernel then
+// take longer to add up than the sums themselves took).
+__host__ __device__ inline int bn_sum_band(int rows, int C) {
+  const int b = bn_band(C), cap = (rows + 2047) / 2048;
+  return b >= cap ? b : (cap + 7) / 8 * 8;
+}
+
 // Per-channel partial sums over a band of rows.  The 256 threads form vc vector columns (8
 // channels each) times rl row lanes; a thread walks rows rl, rl + RL, ... of the band, the
 // row lanes are then added in ascending order through LDS.
@@ -79,7 +87,7 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* __restric
     } else {
       unpack8(*(const u32x4*)(x + c8), p0);
     }
-    const int band = bn_band(C);
+    const int band = bn_sum_band(rows, C);
     const int r0 = blockIdx.x * band, r1 = min(rows, r0 + band);
 #pragma unroll 2
     for (int r = r0 + rl; r < r1; r += RL) {
@@ -462,14 +470,14 @@ int conv2d_wgrad(const bf16_t* dy, const bf16_t* x, bf16_t* dw, void* ws, size_t
 }
 
 size_t bn_ws_bytes(int rows, int c) {
-  const int band = bn_band(c > 8 ? c : 8);
+  const int band = bn_sum_band(rows, c > 8 ? c : 8);
   return (size_t)((rows + band - 1) / band) * 2 * c * sizeof(float);
 }
 
 int bn_fwd(const bf16_t* x, const bf16_t* g, const bf16_t* b, const bf16_t* add, bf16_t* y, float* stats, float* ws,
            int rows, int c, int relu, hipStream_t s) {
   if (!x || !g || !b || !y || !stats || !ws || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
-  const int bands = (rows + bn_band(c) - 1) / bn_band(c);
+  const int bands = (rows + bn_sum_band(rows, c) - 1) / bn_sum_band(rows, c);
   hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, (const bf16_t*)nullptr,
                      (const float*)nullptr, g, b, ws, rows, c, 0);
   hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, x, stats, stats + c, 0);
@@ -489,12 +497,12 @@ int bn_apply(const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t*
 int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* g, const bf16_t* b, int relu, bf16_t* dx,
            float* dgamma, float* dbeta, float* ws, int rows, int c, hipStream_t s, const bf16_t* add) {
   if (!dy || !x || !stats || !g || !b || !dx || !dgamma || !dbeta || !ws || rows <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
-  const int bands = (rows + bn_band(c) - 1) / bn_band(c);
+  const int bands = (rows + bn_sum_band(rows, c) - 1) / bn_sum_band(rows, c);
   hipLaunchKernelGGL(bn_partial_kernel<true>, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, x, dy, stats, g, b, ws, rows,
                      c, relu);
   hipLaunchKernelGGL(bn_finish_kernel, dim3((c + 7) / 8), dim3(256), 0, s, ws, bands, c, rows, (const bf16_t*)nullptr, dbeta,
                      dgamma, 1);
-  hipLaunchKernelGGL(bn_apply_bwd_kernel, dim3(bands, (c / 8 + 255) / 256), dim3(256), 0, s, dy, x, stats, g, b, dgamma, dbeta,
+  hipLaunchKernelGGL(bn_apply_bwd_kernel, dim3((rows + bn_band(c) - 1) / bn_band(c), (c / 8 + 255) / 256), dim3(256), 0, s, dy, x, stats, g, b, dgamma, dbeta,
                      add, dx, rows, c, 1.f / (float)rows, relu);
   return ok();
 }
