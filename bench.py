@@ -507,7 +507,10 @@ def main():
             return block + 1, t
         return (2 * block + 1, t) if t < 6 else (2 * block + 2, t - 6)
     n_records = (2 if split else 1) * CFG["n_layers"] + 1
-    cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
+    # the embedding record (last to finish in backward, first to be read in forward) keeps its optimiser state in
+    # HBM and is updated there; every transformer block and the final LayerNorm are updated on the host
+    cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads,
+               device_update_first=1 if args.config == 1 else 0)
     t0 = time.perf_counter()
     ctx = K.Context(desc, cfg, ARENA)
     # the 8.3B model draws one block's tensors and gives every layer a rolled copy of them

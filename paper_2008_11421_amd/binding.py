@@ -65,7 +65,7 @@ class ConvShape(C.Structure):
 
 class Config(C.Structure):
     _fields_ = [("optimizer", C.c_uint32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float), ("host_threads", C.c_uint32)]
+                ("eps", C.c_float), ("host_threads", C.c_uint32), ("device_update_first", C.c_uint32)]
 
 
 class StepStats(C.Structure):

@@ -24,6 +24,9 @@ struct Param {
   bool grad_bf16 = false;   // device gradient: bf16 (else fp32)
   uint64_t w_off = 0, g_off = 0;   // byte offsets in the fixed region (resident weights)
   uint64_t w_rel = 0, g_rel = 0;   // byte offsets in the record's streamed weight / gradient buffer
+  // updated on the device: fp32 master weights and optimiser state live in the fixed region at these offsets
+  bool dev_opt = false;
+  uint64_t dmaster_off = 0, dm_off = 0, dv_off = 0;
   std::vector<float> master, m, v; // host fp32 master copy and optimiser state
   void* stage_g = nullptr;         // pinned: gradient as it arrives from the device
   void* stage_w = nullptr;         // pinned: new weight in device format

@@ -441,7 +441,16 @@ int run_step(Ctx* c, const void* in, const void* lab, uint32_t flags, float* los
       uint32_t r = p.kind == 'L' ? c->L : p.layer;
       // gradients of a record are complete after its backward; a tied tensor that several
       // records add to is owned by the record that finishes last
-      if (!c->rec[r].p.empty() && !c->rec[r].streamed) {
+      if (!c->rec[r].p.empty() && c->rec[r].p[0].dev_opt) {
+        // updated where they are, behind the backward op on the compute stream
+        const karma_config& g = c->cfg;
+        for (Param& q : c->rec[r].p) {
+          st = optim_update_dev((int)g.optimizer, (float*)(c->arena + q.dmaster_off), (float*)(c->arena + q.dm_off),
+                                (float*)(c->arena + q.dv_off), c->arena + q.g_off, q.grad_bf16, (size_t)q.n, g.lr, g.beta1,
+                                g.beta2, g.eps, c->step_no, c->arena + q.w_off, q.dev_bf16, s);
+          if (st) return st;
+        }
+      } else if (!c->rec[r].p.empty() && !c->rec[r].streamed) {
         st = send_grads(c, r, c->ev[k]);
         if (st) return st;
         done_order.push_back({r, nullptr});
@@ -513,6 +522,8 @@ int karma::derive_layout(Ctx& c) {
   int st = model_build_records(c);
   if (st) return st;
   c.L = (uint32_t)c.rec.size() - 1;
+  if (c.cfg.device_update_first && !c.rec[0].streamed)
+    for (Param& p : c.rec[0].p) p.dev_opt = true;
   // fixed-region layout: weights, gradients, inputs, labels, loss, misc
   uint64_t off = 0;
   for (Record& r : c.rec) {
@@ -532,6 +543,11 @@ int karma::derive_layout(Ctx& c) {
     for (Param& p : r.p) {
       p.w_off = off; off += up256(p.w_bytes());
       p.g_off = off; off += up256(p.g_bytes());
+      if (p.dev_opt) {
+        p.dmaster_off = off; off += up256(p.n * 4);
+        p.dm_off = off; off += up256(p.n * 4);
+        p.dv_off = off; off += up256(p.n * 4);
+      }
     }
   }
   c.in_off = off; off += up256(c.in_bytes);
@@ -545,7 +561,8 @@ int karma::derive_layout(Ctx& c) {
   auto host_bytes = [](const Record& r, uint64_t& g, uint64_t& w) {
     g = w = 0;
     if (r.streamed) return;
-    for (const Param& p : r.p) { g += p.g_bytes(); w += p.w_bytes(); }
+    for (const Param& p : r.p)
+      if (!p.dev_opt) { g += p.g_bytes(); w += p.w_bytes(); }
   };
   for (uint32_t i = 0; i < c.L; ++i) {
     uint64_t hg, hw;
@@ -621,8 +638,17 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
     }
     for (Param& p : r.p) {
       p.master.assign(p.n, 0.f);
-      if (cfg->optimizer == KARMA_OPT_ADAM) { p.m.assign(p.n, 0.f); p.v.assign(p.n, 0.f); }
-      if (cfg->optimizer == KARMA_OPT_SGD_MOMENTUM) p.m.assign(p.n, 0.f);
+      if (p.dev_opt) {
+        // master weights and optimiser state in the fixed region start at zero like the host's
+        if (ok && (hipMemset(c->arena + p.dmaster_off, 0, p.n * 4) != hipSuccess || hipMemset(c->arena + p.dm_off, 0, p.n * 4) != hipSuccess ||
+                   hipMemset(c->arena + p.dv_off, 0, p.n * 4) != hipSuccess)) {
+          (void)hipGetLastError();
+          ok = false;
+        }
+      } else {
+        if (cfg->optimizer == KARMA_OPT_ADAM) { p.m.assign(p.n, 0.f); p.v.assign(p.n, 0.f); }
+        if (cfg->optimizer == KARMA_OPT_SGD_MOMENTUM) p.m.assign(p.n, 0.f);
+      }
       if (r.streamed) {
         if (ok) {
           p.stage_w = r.stage_w_all + p.w_rel;
@@ -708,6 +734,7 @@ extern "C" int karma_set_param(karma_ctx* c, uint32_t layer, uint32_t t, const f
   if (p.dev_bf16) for (uint64_t i = 0; i < n; ++i) ((uint16_t*)p.stage_w)[i] = f32_to_bf16_rne(host[i]);
   else std::memcpy(p.stage_w, host, n * sizeof(float));
   if (!c->rec[layer].streamed) KARMA_HIP(c, hipMemcpy(c->arena + p.w_off, p.stage_w, p.w_bytes(), hipMemcpyHostToDevice));
+  if (p.dev_opt) KARMA_HIP(c, hipMemcpy(c->arena + p.dmaster_off, host, n * sizeof(float), hipMemcpyHostToDevice));
   return KARMA_OK;
 }
 
@@ -717,6 +744,7 @@ extern "C" int karma_get_param(karma_ctx* c, uint32_t layer, uint32_t t, float* 
   if (n != p.n) return fail(c, KARMA_E_INVAL, "karma_get_param: element count mismatch");
   int st = finish_all_updates(c);
   if (st) return st;
+  if (p.dev_opt) KARMA_HIP(c, hipMemcpy(p.master.data(), c->arena + p.dmaster_off, n * sizeof(float), hipMemcpyDeviceToHost));
   std::memcpy(host, p.master.data(), n * sizeof(float));
   return KARMA_OK;
 }
@@ -1057,7 +1085,8 @@ extern "C" int karma_measure(karma_ctx* c, uint32_t reps, karma_link* link_out) 
     }
     auto th_of = [&](const Record& r) {
       uint64_t params = 0;
-      for (const Param& p : r.p) params += p.n;
+      for (const Param& p : r.p)
+        if (!p.dev_opt) params += p.n;
       return (int64_t)((double)params * ns_per_param);
     };
     for (uint32_t i = 0; i < c->L; ++i) c->cost[i].th_ns = th_of(c->rec[i]);

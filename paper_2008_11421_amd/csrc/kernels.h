@@ -123,6 +123,11 @@ int maxpool_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int
 int avgpool_fwd(const bf16_t* x, bf16_t* y, int n, int hw, int c, hipStream_t s);         // global
 int avgpool_bwd(const bf16_t* dy, bf16_t* dx, int n, int hw, int c, hipStream_t s);
 
+// ---- the optimiser's update on the device (optim_dev.hip): kind = karma_opt_kind; fp32 master weights and state,
+// g the gradient (bf16 or fp32), out the device copy of the weight (bf16 or fp32); step counts from 1
+int optim_update_dev(int kind, float* w, float* m, float* v, const void* g, bool g_bf16, size_t n, float lr, float beta1,
+                     float beta2, float eps, uint64_t step, void* out, bool out_bf16, hipStream_t s);
+
 // ---- fused causal attention (attention.hip); seq multiple of 128, d in {64, 128}
 int attention_fwd(const bf16_t* qkv, bf16_t* ctx, float* lse, int batch, int seq, int heads, int d, hipStream_t s);
 int attention_bwd(const bf16_t* qkv, const bf16_t* ctx, const bf16_t* dctx, const float* lse, float* delta,

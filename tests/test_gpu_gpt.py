@@ -22,9 +22,10 @@ def g():
     return gpu_util
 
 
-def make_ctx(n_layers, hidden, heads, ffn, vocab, seq, batch, arena, lr=1e-3, threads=8):
+def make_ctx(n_layers, hidden, heads, ffn, vocab, seq, batch, arena, lr=1e-3, threads=8, device_update_first=0):
     desc = dict(kind=K.MODEL_GPT, n_layers=n_layers, width=hidden, batch=batch, seq=seq, n_heads=heads, ffn=ffn, vocab=vocab)
-    cfg = dict(optimizer=K.OPT_ADAM, lr=lr, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
+    cfg = dict(optimizer=K.OPT_ADAM, lr=lr, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads,
+               device_update_first=device_update_first)
     return K.Context(desc, cfg, arena)
 
 
@@ -259,9 +260,11 @@ def test_profiled_step_gives_op_starts_in_stream_order(g):
     ctx.close()
 
 
-def test_gpt_host_adam(g):
+@pytest.mark.parametrize("device_first", [0, 1], ids=["all_on_host", "first_record_on_device"])
+def test_gpt_host_adam(g, device_first):
+    """device_first: the embedding record's master weights and moments live in HBM and are updated there."""
     params, ids, labels = small_problem()
-    ctx = make_ctx(arena=512 << 20, lr=1e-2, **SMALL)
+    ctx = make_ctx(arena=512 << 20, lr=1e-2, device_update_first=device_first, **SMALL)
     load_params(ctx, params)
     ctx.karma_set_plan(512 << 20, [K.KEEP, K.RC_KEEP, K.SWAP, K.KEEP])
     loss0 = ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
@@ -277,6 +280,19 @@ def test_gpt_host_adam(g):
     check(4, 0, params["lnf_g"], "lnf_g")
     loss1 = ctx.karma_step(ids, labels, K.STEP_APPLY_OPTIMIZER)
     assert loss1 < loss0          # the update went in the descent direction and reached the device
+    # a second update, on the first one's moments: the embedding tensors against the oracle's two steps
+    g1 = all_grads(ctx, 3)
+    for tensor, name in ((0, "wte"), (1, "wpe")):
+        w0 = np.asarray(params[name], np.float32).astype(np.float64).reshape(-1)
+        w1, m1, v1 = nn.adam_update(w0, 0.0, 0.0, grads[name].astype(np.float64), 1, 1e-2)
+        w2, _, _ = nn.adam_update(w1, m1, v1, g1[name].astype(np.float64), 2, 1e-2)
+        assert g.rel_l2(ctx.karma_get_param(0, tensor), w2) <= 1e-6, name
+    layers, loss_c, fixed = ctx.karma_get_costs()
+    if device_first:
+        assert layers[0][9] == 0 and layers[0][10] == 0         # no gradients out, no weights back for record 0
+        assert fixed >= 12 * (params["wte"].size + params["wpe"].size)
+    else:
+        assert layers[0][9] > 0 and layers[0][10] > 0
     ctx.close()
 
 
