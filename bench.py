@@ -173,7 +173,7 @@ def batch_sweep(args, K, si, torch, np, threads):
         a_layers, a_loss, fixed = K.karma_model_costs(desc, *rates)
         in_core_need = fixed + sum(l[3] + l[4] for l in a_layers) + 2 * max(max(l[5] for l in a_layers), a_loss[1])
         arena = max(min(in_core_need + 2 * GIB, 200 * GIB), BUDGET) // 256 * 256
-        cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads)
+        cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads, device_update_first=1)
         ctx = K.Context(desc, cfg, arena)
         params, ids, labels = si.gpt_problem(seed=SEED, n_layers=1, hidden=CFG["hidden"], ffn=CFG["ffn"], vocab=CFG["vocab"],
                                              seq=CFG["seq"], batch=batch)
