@@ -454,8 +454,9 @@ def main():
                     help="plan on the committed cost records of this workload (default; falls back to this run's own "
                          "measurements when there are none) or on this run's measurements")
     ap.add_argument("--save-costs", action="store_true", help="write this run's measured cost records to the committed file")
-    ap.add_argument("--device-update-first", type=int, default=None, choices=(0, 1),
-                    help="GPT workloads: update the embedding record on the device (default 1) or on the host like every other record (0)")
+    ap.add_argument("--device-update-first", type=int, default=None,
+                    help="GPT workloads: how many leading records are updated on the device instead of the host (default: the "
+                         "embedding record, and for the default workload the first block's two halves as well)")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="configs[1] only: batches 8..128 under the budget and in-core (a supplementary line, not the benchmark)")
     ap.add_argument("--layers", type=int, default=0,
@@ -509,10 +510,11 @@ def main():
             return block + 1, t
         return (2 * block + 1, t) if t < 6 else (2 * block + 2, t - 6)
     n_records = (2 if split else 1) * CFG["n_layers"] + 1
-    # the embedding record (last to finish in backward, first to be read in forward) keeps its optimiser state in
-    # HBM and is updated there; every transformer block and the final LayerNorm are updated on the host
+    # the embedding record and, where weights are resident, the first transformer block (last to finish in backward,
+    # first to be read in forward) keep their optimiser state in HBM and are updated there; every other block and
+    # the final LayerNorm are updated on the host
     cfg = dict(optimizer=K.OPT_ADAM, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, host_threads=threads,
-               device_update_first=1 if args.device_update_first is None else args.device_update_first)
+               device_update_first=(3 if args.config == 1 else 1) if args.device_update_first is None else args.device_update_first)
     t0 = time.perf_counter()
     ctx = K.Context(desc, cfg, ARENA)
     # the 8.3B model draws one block's tensors and gives every layer a rolled copy of them

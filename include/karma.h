@@ -252,13 +252,13 @@ typedef struct {
   uint32_t optimizer; /* karma_opt_kind */
   float lr, beta1, beta2, eps;
   uint32_t host_threads; /* worker threads of the host optimiser (0 = 1) */
-  uint32_t device_update_first; /* 1: the parameters of record 0 (resident weights only) keep their fp32 master copy and
-                                   optimiser state in HBM, inside the fixed region (12 bytes per parameter, charged to the
-                                   budget), and are updated there by a kernel right after the record's backward.  They are
-                                   the last tensors the backward pass completes and the first the next forward pass reads:
-                                   on the host their update (gradients out, update, weights back) is a tail nothing can
-                                   hide.  Every other record is updated on the host as Sec. III-G describes.  Same
-                                   arithmetic as the host update */
+  uint32_t device_update_first; /* n: the parameters of records 0 .. n-1 (those with resident weights) keep their fp32
+                                   master copy and optimiser state in HBM, inside the fixed region (12 bytes per
+                                   parameter, charged to the budget), and are updated there by a kernel right after the
+                                   record's backward.  The first records are the last the backward pass completes and the
+                                   first the next forward pass reads: on the host their update (gradients out, update,
+                                   weights back) is a tail nothing can hide.  Every other record is updated on the host as
+                                   Sec. III-G describes.  Same arithmetic as the host update */
 } karma_config;
 
 /* Number of plannable layer records of a model (MLP: n_layers; GPT: n_layers + 1, record

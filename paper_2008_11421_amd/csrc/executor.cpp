@@ -522,8 +522,9 @@ int karma::derive_layout(Ctx& c) {
   int st = model_build_records(c);
   if (st) return st;
   c.L = (uint32_t)c.rec.size() - 1;
-  if (c.cfg.device_update_first && !c.rec[0].streamed)
-    for (Param& p : c.rec[0].p) p.dev_opt = true;
+  for (uint32_t r = 0; r < c.cfg.device_update_first && r < c.L; ++r)
+    if (!c.rec[r].streamed)
+      for (Param& p : c.rec[r].p) p.dev_opt = true;
   // fixed-region layout: weights, gradients, inputs, labels, loss, misc
   uint64_t off = 0;
   for (Record& r : c.rec) {
