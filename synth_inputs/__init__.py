@@ -217,3 +217,57 @@ def wrn_problem(seed=2008114204, width=160, group_blocks=(4, 4, 4), image=32, ba
     images = normal(nxt(), (batch, image, image, 3))
     labels = randint(nxt(), (batch,), classes)
     return params, images, labels
+
+
+LEVEL_TENSORS = ("w1", "g1", "b1", "w2", "g2", "b2")
+UP_TENSORS = ("wu",) + LEVEL_TENSORS
+
+
+def unet_problem(seed=2008114205, width=64, depth=4, image=512, batch=4, classes=2, bn_jitter=0.0):
+    """U-Net shapes by default (the ssTEM sections of Table III: 512x512, one channel, two classes): depth + 1
+    contracting levels of two 3x3 convolutions with width << level channels, depth expansive levels (2x2
+    up-convolution [c_in][2][2][c_out], then two 3x3 convolutions, the first reading the contracting
+    output's channels followed by the up-convolution's), 1x1 classifier.  Kaiming-normal (fan-out)
+    convolutions, batch-norm gain 1 / shift 0 (plus N(0, bn_jitter) in tests), classifier N(0, 0.01) with zero
+    bias; images N(0, 1); labels per pixel, smooth blobs: the sign pattern of a coarse random field, so that
+    neighbouring pixels mostly agree as they do in a segmentation mask."""
+    k = [0]
+
+    def nxt():
+        k[0] += 1
+        return seed + 7919 * k[0]
+
+    def conv(co, r, ci):
+        return normal(nxt(), (co, r, r, ci), (2.0 / (r * r * co)) ** 0.5)
+
+    def bn(c):
+        g, b = np.ones(c), np.zeros(c)
+        if bn_jitter:
+            g = g + normal(nxt(), (c,), bn_jitter)
+            b = b + normal(nxt(), (c,), bn_jitter)
+        return g, b
+
+    def level(cin, c):
+        p = {}
+        p["w1"] = conv(c, 3, cin)
+        p["g1"], p["b1"] = bn(c)
+        p["w2"] = conv(c, 3, c)
+        p["g2"], p["b2"] = bn(c)
+        return p
+
+    params = dict(down=[], up=[], head=None)
+    cin = 1
+    for l in range(depth + 1):
+        params["down"].append(level(cin, width << l))
+        cin = width << l
+    for j in range(depth):
+        c = width << (depth - 1 - j)
+        p = level(2 * c, c)
+        p["wu"] = normal(nxt(), (2 * c, 2, 2, c), (2.0 / (4 * c)) ** 0.5)
+        params["up"].append(p)
+    params["head"] = dict(w=normal(nxt(), (classes, width), 0.01), bias=np.zeros(classes))
+    images = normal(nxt(), (batch, image, image, 1))
+    coarse = max(1, image // 8)
+    field = randint(nxt(), (batch, (image + coarse - 1) // coarse, (image + coarse - 1) // coarse), classes)
+    labels = np.repeat(np.repeat(field, coarse, axis=1), coarse, axis=2)[:, :image, :image]
+    return params, images, np.ascontiguousarray(labels)
