@@ -101,11 +101,13 @@ typedef struct {
 
 /* One op of the simulated/executed timeline, in issue order.
  * kind: 'F' forward, 'B' backward, 'R' recompute, 'L' loss, 'O' swap-out, 'I' swap-in,
- *   'W' copy-in of a layer's streamed weights, 'G' copy-out of their gradients.
+ *   'W' copy-in of a layer's streamed weights, 'G' copy-out of their gradients, 'H' (models with connections
+ *   between non-consecutive layers only; no time passes) the buffer in which the readers of x_layer leave their
+ *   gradient for it starts to exist: issued right before the first backward op that writes it.
  * off[]: arena offsets (relative to the end of the fixed region, -1 = none) of what the
  *   op allocates: F {x_{i+1}, internals, workspace}; R {internals, x_{i+1}, workspace};
  *   B {dx, workspace, gradients of streamed weights}; L {dx, workspace, -1};
- *   I {x_i, internals, -1}; W {weights, -1, -1}; O and G {-1,-1,-1}. */
+ *   I {x_i, internals, -1}; W {weights, -1, -1}; H {that buffer, -1, -1}; O and G {-1,-1,-1}. */
 typedef struct {
   uint8_t kind;
   uint32_t layer;
@@ -169,7 +171,7 @@ int karma_plan_grouped_pure(const karma_layer_cost* layers, uint32_t n_layers, c
  * layer drops its input).  B_dst leaves a gradient for x_s that is held, from the first such
  * backward, until B_s adds it to its own.  The planner searches two more neighbourhoods when
  * connections are present (four consecutive layers; one layer forced and the rest descending).
- * karma_simulate_graph writes at most 8*n_layers + 2 + n_skips ops.
+ * karma_simulate_graph writes at most 8*n_layers + 2 + 2*n_skips ops.
  * Errors as the plain calls; KARMA_E_INVAL also for a connection with dst < src + 2 or
  * dst >= n_layers, and for an action vector that chains a read-again input. */
 typedef struct {

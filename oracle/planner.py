@@ -86,7 +86,7 @@ Link = namedtuple("Link", "bw_h2d bw_d2h lat_ns bw_h2d_loaded bw_d2h_loaded", de
 # loss op that sits between forward and backward: time and workspace; th / hg / hw as for a
 # layer (the parameters that belong to the loss record, e.g. a final normalisation)
 Loss = namedtuple("Loss", "t ws th hg hw", defaults=(0, 0, 0))
-Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN WIN GOUT
+Op = namedtuple("Op", "kind layer start end offs")   # kind in F B R L OUT IN WIN GOUT HOLD
 
 
 class Infeasible(Exception):
@@ -531,6 +531,8 @@ def simulate(layers, link, budget, fixed, loss, actions, want_ops=False, wres=No
         for s_ in sorted(readers):          # gradients this layer leaves for the inputs it read again
             if j in readers[s_] and s_ not in DSK:
                 DSK[s_], t = grant(xb[s_], False, t)
+                if want_ops:                # where the executor finds that buffer
+                    ops.append(Op("HOLD", s_, t, t, (DSK[s_],)))
         end = t + layers[j].tb
         busy += layers[j].tb
         done[0] += 1

@@ -162,7 +162,7 @@ def karma_simulate_graph(layers, link, loss, budget, fixed, skips, actions, want
     act = (C.c_uint8 * n)(*actions)
     kept = (C.c_uint8 * n)(*weights_kept) if weights_kept is not None else None
     summ = PlanSummary()
-    cap = 8 * n + 2 + len(skips)
+    cap = 8 * n + 2 + 2 * len(skips)
     ops = (Op * cap)() if want_ops else None
     nops = C.c_uint32(cap)
     st = lib().karma_simulate_graph(arr, C.c_uint32(n), C.byref(lk), C.byref(ls), C.c_uint64(budget), C.c_uint64(fixed),

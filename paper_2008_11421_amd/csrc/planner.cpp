@@ -272,7 +272,10 @@ struct Timeline {
     int64_t w = obtain(w_sz[j], false, now);
     g_at[j] = obtain(g_sz[j], false, now);
     for (uint32_t s : reads[j])           // gradients this layer leaves for the inputs it read again
-      if (hold_at[s] < 0) hold_at[s] = obtain(x_sz[s], false, now);
+      if (hold_at[s] < 0) {
+        hold_at[s] = obtain(x_sz[s], false, now);
+        if (!failed) emit('H', s, now, now, hold_at[s], -1, -1);   // where the executor finds that buffer
+      }
     if (failed) return;
     int64_t end = now + P.layers[j].tb_ns;
     busy += P.layers[j].tb_ns;

@@ -7,7 +7,7 @@ from oracle import planner as P
 import synth_inputs as si
 from test_oracle_planner import cases, golden_schedule, mk, six_block_model
 
-KIND = {"F": "F", "B": "B", "R": "R", "L": "L", "OUT": "O", "IN": "I", "WIN": "W", "GOUT": "G"}
+KIND = {"F": "F", "B": "B", "R": "R", "L": "L", "OUT": "O", "IN": "I", "WIN": "W", "GOUT": "G", "HOLD": "H"}
 
 
 def ops_equal(lib_ops, ora_ops):
