@@ -210,13 +210,29 @@ int karma_stage_string(const karma_op* ops, uint32_t n_ops, char* buf, size_t bu
  * gain, BN1 shift, first 3x3 weight, BN2 gain, BN2 shift, second 3x3 weight and, where the shape changes, the 1x1
  * shortcut weight, which convolves the activated input); loss record: batch norm, ReLU, global average pooling, fully
  * connected layer, mean cross entropy (tensors: gain, shift, weight, bias).  No dropout.  Inputs as for the CNN. */
-typedef enum { KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2, KARMA_MODEL_CNN = 3, KARMA_MODEL_WRN = 4 } karma_model_kind;
+/* KARMA_MODEL_UNET: a fully convolutional network (the U-Net row of Table III; Sec. III-F.3: connections from the
+ * contracting to the expansive path).  n_layers = depth D (1..6), width = channels of level 0 (64), level l has
+ * width << l channels at (seq >> l)^2 pixels; seq = image size, a multiple of 2^D; vocab = classes stored, 8 or 16
+ * (two classes are stored as 8: rows 2..7 of the classifier weight zero and their bias -30000).  Records 0..D:
+ * contracting levels (2x2 max pooling of the record above, except record 0; then twice: 3x3 convolution with padding
+ * 1 and no bias, batch normalisation, ReLU; tensors: first weight [C][3][3][c_in], gain, shift, second weight, gain,
+ * shift; the one image channel is stored as 8).  Records D+1..2D: expansive levels D-1..0 (2x2 stride-2
+ * up-convolution [c_below][2][2][C] without bias, then the same two convolutions, the first of them over the
+ * contracting record's output followed by the up-convolution's result; tensors: up-convolution weight, the first
+ * weight's half for the contracting output [C][3][3][C], its half for the up-convolution's result [C][3][3][C],
+ * gain, shift, second weight, gain, shift).  Record 2D - l reads the output of record l again (karma_model_skips).
+ * Loss record: 1x1 classifier with bias and the mean cross entropy over all pixels (tensors: weight [classes][width],
+ * bias).  Inputs: fp32 images [batch][seq][seq] (one channel), int32 labels [batch][seq][seq].  stream_weights
+ * must be 0. */
+typedef enum {
+  KARMA_MODEL_MLP = 1, KARMA_MODEL_GPT = 2, KARMA_MODEL_CNN = 3, KARMA_MODEL_WRN = 4, KARMA_MODEL_UNET = 5
+} karma_model_kind;
 /* SGD with momentum: buf = beta1 * buf + g; w -= lr * buf (no dampening, no Nesterov) */
 typedef enum { KARMA_OPT_SGD = 1, KARMA_OPT_ADAM = 2, KARMA_OPT_SGD_MOMENTUM = 3 } karma_opt_kind;
 
 typedef struct {
   uint32_t kind;      /* karma_model_kind */
-  uint32_t n_layers;  /* MLP: Linear+ReLU layers; GPT: transformer blocks; CNN: ignored */
+  uint32_t n_layers;  /* MLP: Linear+ReLU layers; GPT: transformer blocks; UNET: depth; CNN, WRN: ignored */
   uint32_t width;     /* MLP width / GPT hidden size / CNN: bottleneck width of the first stage (64) / WRN: channels of
                          the first group (160) */
   uint32_t batch;
@@ -270,6 +286,13 @@ typedef struct {
  * stage_blocks[0..2], record 0 being the first convolution) and
  * of parameter tensors of record `layer`. */
 int karma_model_layers(const karma_model_desc* desc, uint32_t* n_out);
+
+/* The model's connections between non-consecutive records (Sec. III-F.3), the ones karma_plan, karma_set_plan and
+ * karma_step of a context of this model honour (premature swap-in of a swapped record input that a later record
+ * reads again, the readers' gradient held until that record's backward adds it to its own).  skips_out (host, may
+ * be NULL to ask for the count): *n_inout holds its capacity on entry and the number of connections on return
+ * (KARMA_E_OOM if too small).  Only KARMA_MODEL_UNET has any. */
+int karma_model_skips(const karma_model_desc* desc, karma_skip* skips_out, uint32_t* n_inout);
 
 /* Creates a context.  arena_dev: device slab of arena_bytes owned by the caller (e.g. a
  * torch uint8 tensor), 256-byte aligned, must outlive the context.  The three streams are
@@ -585,6 +608,15 @@ int karma_k_relu_mask_bwd_bf16(const void* dy_dev, const void* y_dev, void* dz_d
 int karma_k_maxpool_fwd_bf16(const void* x_dev, void* y_dev, uint32_t n, uint32_t h, uint32_t w, uint32_t c, void* stream);
 int karma_k_maxpool_bwd_bf16(const void* x_dev, const void* dy_dev, void* dx_dev, uint32_t n, uint32_t h, uint32_t w,
                              uint32_t c, void* stream);
+/* 2x2 max pooling with stride 2 (Sec. III-C pooling layer; the contracting path of the fully convolutional
+ * network): x_dev [n][h][w][c] -> y_dev [n][h/2][w/2][c]; h and w even, c a multiple of 8.  The backward writes
+ * all of dx_dev (x's shape): dy to the first maximum of each window in row-major window order, zero elsewhere. */
+int karma_k_maxpool2_fwd_bf16(const void* x_dev, void* y_dev, uint32_t n, uint32_t h, uint32_t w, uint32_t c, void* stream);
+int karma_k_maxpool2_bwd_bf16(const void* x_dev, const void* dy_dev, void* dx_dev, uint32_t n, uint32_t h, uint32_t w,
+                              uint32_t c, void* stream);
+/* y += a, n bf16 elements (a multiple of 8), one rounding: how the gradient that other readers of a tensor left
+ * for it (Sec. III-F.3, connections between non-consecutive layers) joins the gradient of its direct consumer. */
+int karma_k_add_inplace_bf16(void* y_dev, const void* a_dev, uint64_t n, void* stream);
 /* Global average pooling over hw positions: x [n][hw][c] -> y [n][c], and its backward. */
 int karma_k_avgpool_fwd_bf16(const void* x_dev, void* y_dev, uint32_t n, uint32_t hw, uint32_t c, void* stream);
 int karma_k_avgpool_bwd_bf16(const void* dy_dev, void* dx_dev, uint32_t n, uint32_t hw, uint32_t c, void* stream);

@@ -129,6 +129,27 @@ def wrn_blocks(width, group_blocks, image, batch, classes, stem=16):
     return blocks, loss
 
 
+def unet_blocks(width, depth, image, batch, classes):
+    """Contracting levels 0..depth (level l >= 1: 2x2 max pooling of the level above, |Y| K K; then two 3x3
+    convolutions, each with batch norm and ReLU), expansive levels depth-1..0 (2x2 stride-2 up-convolution: each
+    output element takes one tap, |Y| C_in; then the two convolutions, the first over the concatenation of 2C
+    channels).  Loss: 1x1 classifier over one image channel's worth of pixels, softmax cross entropy per pixel.
+    The network reads one image channel."""
+    blocks = []
+    for l in range(depth + 1):
+        p, c = batch * (image >> l) ** 2, width << l
+        cin = (width << (l - 1)) if l else 1
+        matrix = p * c * 9 * cin + p * c * 9 * c
+        other = (p * cin * 2 * 2 if l else 0) + 2 * (9 * p * c + p * c)
+        blocks.append((matrix, other))
+    for l in range(depth - 1, -1, -1):
+        p, c = batch * (image >> l) ** 2, width << l
+        matrix = p * c * (width << (l + 1)) + p * c * 9 * (2 * c) + p * c * 9 * c
+        blocks.append((matrix, 2 * (9 * p * c + p * c)))
+    p0 = batch * image * image
+    return blocks, (p0 * width * classes, 2 * p0 * classes)
+
+
 def times(blocks, loss, rates):
     """Per block (t_fwd, t_bwd, t_recompute) in ns and the loss op's time (forward + gradient)."""
     out = []

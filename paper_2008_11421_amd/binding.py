@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libkarma.so")
 
 KEEP, SWAP, RC_KEEP, RC_SWAP, RC_CHAIN = range(5)
 OK, E_INVAL, E_BUDGET, E_OOM, E_HIP, E_STATE, E_HOSTMEM = 0, -1, -2, -3, -4, -5, -6
-MODEL_MLP, MODEL_GPT, MODEL_CNN, MODEL_WRN = 1, 2, 3, 4
+MODEL_MLP, MODEL_GPT, MODEL_CNN, MODEL_WRN, MODEL_UNET = 1, 2, 3, 4, 5
 OPT_SGD, OPT_ADAM, OPT_SGD_MOMENTUM = 1, 2, 3
 STEP_APPLY_OPTIMIZER = 1
 STEP_PROFILE = 2
@@ -265,6 +265,16 @@ def karma_model_costs(desc, matrix_ops_per_s, other_ops_per_s):
            "karma_model_costs")
     layers = [(a.tf_ns, a.tb_ns, a.trc_ns, a.sav_bytes, a.out_bytes, a.ws_bytes, a.w_bytes, a.g_bytes) for a in arr[:n.value]]
     return layers, (loss.t_ns, loss.ws_bytes), fixed.value
+
+
+def karma_model_skips(desc):
+    """Connections between non-consecutive records of a model: [(src, dst), ...] (empty for most kinds)."""
+    d = _model_desc(desc)
+    n = C.c_uint32(0)
+    _check(lib().karma_model_skips(C.byref(d), None, C.byref(n)), "karma_model_skips")
+    arr = (Skip * max(1, n.value))()
+    _check(lib().karma_model_skips(C.byref(d), arr, C.byref(n)), "karma_model_skips")
+    return [(arr[k].src, arr[k].dst) for k in range(n.value)]
 
 
 def karma_stage_string(ops):

@@ -15,7 +15,8 @@ namespace karma {
 enum RecordKind {
   REC_LINEAR_RELU = 1, REC_EMBED = 2, REC_BLOCK = 3, REC_CNN_STEM = 4, REC_CNN_BLOCK = 5, REC_ATTN = 6, REC_FFN = 7,
   REC_WRN_STEM = 8, REC_WRN_BLOCK = 9,
-  REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11, REC_LOSS_CNN_HEAD = 12, REC_LOSS_WRN_HEAD = 13
+  REC_LOSS_MSE = 10, REC_LOSS_LMHEAD = 11, REC_LOSS_CNN_HEAD = 12, REC_LOSS_WRN_HEAD = 13,
+  REC_UNET_DOWN = 14, REC_UNET_UP = 15, REC_LOSS_UNET_HEAD = 16
 };
 
 struct Param {
@@ -66,6 +67,12 @@ struct ProgOp {
   int stream = 0;                 // 0 compute, 1 h2d, 2 d2h
   int64_t host_x = -1, host_s = -1;   // offsets in the pinned swap pool
   uint64_t x_bytes = 0, s_bytes = 0;  // bytes moved by a swap op
+  // Connections between non-consecutive records (Sec. III-F.3)
+  std::vector<int64_t> rx;            // F, R, B of a reader: the inputs of other records it reads again, ascending
+  std::vector<int64_t> rdx;           // B of a reader: where it leaves its gradient for each of them ...
+  std::vector<uint8_t> rdx_first;     // ... writing it (1: the first reader to run) or adding to it (0)
+  int64_t hold = -1;                  // B of a record whose input was read again: the readers' gradient, added to dx
+  uint64_t hold_elems = 0;            // elements of that tensor
 };
 
 struct Ctx {
@@ -75,6 +82,7 @@ struct Ctx {
   uint64_t arena_bytes = 0;
   hipStream_t st[3] = {nullptr, nullptr, nullptr};   // compute, h2d, d2h
   std::vector<Record> rec;       // plannable records followed by the loss record
+  std::vector<karma_skip> skips; // connections between non-consecutive records (the model's; empty for most)
   uint32_t L = 0;                // number of plannable records
   uint64_t fixed_bytes = 0;
   uint64_t in_off = 0, lab_off = 0, loss_off = 0, misc_off = 0;   // fixed-region offsets
@@ -158,6 +166,13 @@ struct LayerIO {
   void* dx = nullptr;        // gradient w.r.t. the input (null for record 0)
   const void* w = nullptr;   // streamed weights of the record (null when resident)
   void* g = nullptr;         // buffer for the gradients of streamed weights (backward only)
+  // inputs of other records that this one reads again (Sec. III-F.3), ascending by record; backward: where the
+  // gradient with respect to each goes, and whether this op writes it or adds to what is there
+  static constexpr int MAX_SKIPS = 4;
+  int n_skips = 0;
+  const void* skip_x[MAX_SKIPS] = {nullptr, nullptr, nullptr, nullptr};
+  void* skip_dx[MAX_SKIPS] = {nullptr, nullptr, nullptr, nullptr};
+  bool skip_dx_first[MAX_SKIPS] = {false, false, false, false};
 };
 
 // Model-specific pieces (layers_mlp.cpp, layers_gpt.cpp)

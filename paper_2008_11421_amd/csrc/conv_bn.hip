@@ -349,6 +349,79 @@ __global__ void maxpool_bwd_kernel(const bf16_t* __restrict__ x, const bf16_t* _
   ((u32x4*)dx)[i] = pack8(acc);
 }
 
+// 2x2 max pooling, stride 2 (H and W even): one thread per output pixel and eight channels
+__global__ void maxpool2_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y, int N, int H, int W, int C) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int nv = C / 8, Ho = H / 2, Wo = W / 2;
+  if (i >= (size_t)N * Ho * Wo * nv) return;
+  const int c8 = (int)(i % nv) * 8;
+  size_t p = i / nv;
+  const int wo = (int)(p % Wo); p /= Wo;
+  const int ho = (int)(p % Ho);
+  const int n = (int)(p / Ho);
+  const bf16_t* at = x + (((size_t)n * H + 2 * ho) * W + 2 * wo) * C + c8;
+  float best[8], v[8];
+  unpack8(*(const u32x4*)at, best);
+  unpack8(*(const u32x4*)(at + C), v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], v[e]);
+  unpack8(*(const u32x4*)(at + (size_t)W * C), v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], v[e]);
+  unpack8(*(const u32x4*)(at + (size_t)W * C + C), v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], v[e]);
+  ((u32x4*)y)[i] = pack8(best);
+}
+
+// Its gradient: the windows are disjoint, so the thread of an output pixel writes all four input
+// positions: dy to the first maximum in row-major window order, zero to the others.
+__global__ void maxpool2_bwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, bf16_t* __restrict__ dx,
+                                    int N, int H, int W, int C) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int nv = C / 8, Ho = H / 2, Wo = W / 2;
+  if (i >= (size_t)N * Ho * Wo * nv) return;
+  const int c8 = (int)(i % nv) * 8;
+  size_t p = i / nv;
+  const int wo = (int)(p % Wo); p /= Wo;
+  const int ho = (int)(p % Ho);
+  const int n = (int)(p / Ho);
+  const size_t base = (((size_t)n * H + 2 * ho) * W + 2 * wo) * C + c8;
+  const size_t pos[4] = {base, base + C, base + (size_t)W * C, base + (size_t)W * C + C};
+  float v[4][8], d[8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) unpack8(*(const u32x4*)(x + pos[k]), v[k]);
+  unpack8(((const u32x4*)dy)[i], d);
+  int first[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    first[e] = 0;
+    float best = v[0][e];
+#pragma unroll
+    for (int k = 1; k < 4; ++k)
+      if (v[k][e] > best) { best = v[k][e]; first[e] = k; }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = first[e] == k ? d[e] : 0.f;
+    *(u32x4*)(dx + pos[k]) = pack8(o);
+  }
+}
+
+// y += a, eight elements per thread (a gradient that arrived by another path)
+__global__ void add_inplace_kernel(bf16_t* __restrict__ y, const bf16_t* __restrict__ a, size_t nvec) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nvec) return;
+  float u[8], v[8];
+  unpack8(((const u32x4*)y)[i], u);
+  unpack8(((const u32x4*)a)[i], v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) u[e] += v[e];
+  ((u32x4*)y)[i] = pack8(u);
+}
+
 // global average pooling: y[n][c] = mean over the HW positions, summed in position order
 __global__ void avgpool_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y, int N, int HW, int C) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -529,6 +602,27 @@ int maxpool_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int
   return ok();
 }
 
+int maxpool2_fwd(const bf16_t* x, bf16_t* y, int n, int h, int w, int c, hipStream_t s) {
+  if (!x || !y || n <= 0 || h <= 0 || w <= 0 || c <= 0 || c % 8 || h % 2 || w % 2) return KARMA_E_INVAL;
+  hipLaunchKernelGGL(maxpool2_fwd_kernel, dim3(blocks_for((size_t)n * (h / 2) * (w / 2) * (c / 8), 256)), dim3(256), 0, s, x, y,
+                     n, h, w, c);
+  return ok();
+}
+
+int maxpool2_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int w, int c, hipStream_t s) {
+  if (!x || !dy || !dx || n <= 0 || h <= 0 || w <= 0 || c <= 0 || c % 8 || h % 2 || w % 2) return KARMA_E_INVAL;
+  hipLaunchKernelGGL(maxpool2_bwd_kernel, dim3(blocks_for((size_t)n * (h / 2) * (w / 2) * (c / 8), 256)), dim3(256), 0, s, x, dy,
+                     dx, n, h, w, c);
+  return ok();
+}
+
+int add_inplace_bf16(bf16_t* y, const bf16_t* a, size_t n, hipStream_t s) {
+  if (!y || !a || n % 8) return KARMA_E_INVAL;
+  if (!n) return KARMA_OK;
+  hipLaunchKernelGGL(add_inplace_kernel, dim3(blocks_for(n / 8, 256)), dim3(256), 0, s, y, a, n / 8);
+  return ok();
+}
+
 int avgpool_fwd(const bf16_t* x, bf16_t* y, int n, int hw, int c, hipStream_t s) {
   if (!x || !y || n <= 0 || hw <= 0 || c <= 0 || c % 8) return KARMA_E_INVAL;
   hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(blocks_for((size_t)n * (c / 8), 256)), dim3(256), 0, s, x, y, n, hw, c);
@@ -609,6 +703,19 @@ extern "C" int karma_k_maxpool_fwd_bf16(const void* x, void* y, uint32_t n, uint
 extern "C" int karma_k_maxpool_bwd_bf16(const void* x, const void* dy, void* dx, uint32_t n, uint32_t h, uint32_t w,
                                         uint32_t c, void* stream) {
   return maxpool_bwd((const bf16_t*)x, (const bf16_t*)dy, (bf16_t*)dx, (int)n, (int)h, (int)w, (int)c, (hipStream_t)stream);
+}
+
+extern "C" int karma_k_maxpool2_fwd_bf16(const void* x, void* y, uint32_t n, uint32_t h, uint32_t w, uint32_t c, void* stream) {
+  return maxpool2_fwd((const bf16_t*)x, (bf16_t*)y, (int)n, (int)h, (int)w, (int)c, (hipStream_t)stream);
+}
+
+extern "C" int karma_k_maxpool2_bwd_bf16(const void* x, const void* dy, void* dx, uint32_t n, uint32_t h, uint32_t w,
+                                         uint32_t c, void* stream) {
+  return maxpool2_bwd((const bf16_t*)x, (const bf16_t*)dy, (bf16_t*)dx, (int)n, (int)h, (int)w, (int)c, (hipStream_t)stream);
+}
+
+extern "C" int karma_k_add_inplace_bf16(void* y, const void* a, uint64_t n, void* stream) {
+  return add_inplace_bf16((bf16_t*)y, (const bf16_t*)a, (size_t)n, (hipStream_t)stream);
 }
 
 extern "C" int karma_k_avgpool_fwd_bf16(const void* x, void* y, uint32_t n, uint32_t hw, uint32_t c, void* stream) {

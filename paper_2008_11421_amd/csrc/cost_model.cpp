@@ -108,6 +108,24 @@ void count_wrn(const karma_model_desc& d, std::vector<Ops>& blocks, Ops& loss) {
   loss = Ops(N * cin * d.vocab, 10 * pix * cin + pix * cin + 2 * N * d.vocab);
 }
 
+// Fully convolutional network: contracting levels (2x2 max pooling except at level 0, then twice 3x3 convolution,
+// batch norm, ReLU), expansive levels (2x2 up-convolution: every fine pixel takes one tap, |Y| C_in; then the two
+// convolutions, the first over twice the channels), loss record: 1x1 classifier, softmax cross entropy per pixel.
+void count_unet(const karma_model_desc& d, std::vector<Ops>& blocks, Ops& loss) {
+  const uint64_t N = d.batch, D = d.n_layers;
+  auto pixels = [&](uint64_t l) { return N * (d.seq >> l) * (d.seq >> l); };
+  auto chans = [&](uint64_t l) { return (uint64_t)d.width << l; };
+  for (uint64_t l = 0; l <= D; ++l) {
+    const uint64_t p = pixels(l), c = chans(l), cin = l ? chans(l - 1) : 1;
+    blocks.push_back(Ops(p * c * 9 * cin + p * c * 9 * c, (l ? p * cin * 4 : 0) + 20 * p * c));
+  }
+  for (uint64_t l = D; l-- > 0;) {
+    const uint64_t p = pixels(l), c = chans(l);
+    blocks.push_back(Ops(p * c * chans(l + 1) + p * c * 9 * 2 * c + p * c * 9 * c, 20 * p * c));
+  }
+  loss = Ops(pixels(0) * chans(0) * d.vocab, 2 * pixels(0) * d.vocab);
+}
+
 // ceil(ops * 1e9 / rate) with a 128-bit intermediate
 int64_t ops_time_ns(uint64_t ops, uint64_t rate) {
   const unsigned __int128 num = (unsigned __int128)ops * 1000000000ull;
@@ -137,6 +155,7 @@ extern "C" int karma_model_costs(const karma_model_desc* desc, const karma_devic
   else if (desc->kind == KARMA_MODEL_GPT) count_gpt(*desc, blocks, loss);
   else if (desc->kind == KARMA_MODEL_CNN) count_cnn(*desc, blocks, loss);
   else if (desc->kind == KARMA_MODEL_WRN) count_wrn(*desc, blocks, loss);
+  else if (desc->kind == KARMA_MODEL_UNET) count_unet(*desc, blocks, loss);
   else return KARMA_E_INVAL;
   if (blocks.size() != c.L) return KARMA_E_STATE;
   for (uint32_t i = 0; i < c.L; ++i) {

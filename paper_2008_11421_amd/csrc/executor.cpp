@@ -10,6 +10,7 @@
 
 #include "context.h"
 #include "kernels.h"
+#include "layers.h"
 
 using namespace karma;
 
@@ -83,6 +84,26 @@ struct Builder {
     const int64_t lw_sz = (int64_t)up256(c.loss_cost.ws_bytes);
     x_at.assign(L + 2, -1); s_at.assign(L, -1); dx_at.assign(L + 2, -1);
     std::vector<int64_t> f_op(L, -1), in_op(L, -1), out_op(L, -1);
+    // connections between non-consecutive records: reads[j] = the inputs x_s record j reads again (ascending);
+    // hold_at[s] = the buffer in which the readers' gradient for x_s waits for B_s
+    std::vector<std::vector<uint32_t>> reads(L);
+    for (const karma_skip& e : c.skips) reads[e.dst].push_back(e.src + 1);
+    for (auto& r : reads) {
+      std::sort(r.begin(), r.end());
+      r.erase(std::unique(r.begin(), r.end()), r.end());
+      if (r.size() > (size_t)LayerIO::MAX_SKIPS) return KARMA_E_INVAL;
+    }
+    std::vector<int64_t> hold_at(L + 1, -1), x_in_op(L + 1, -1);   // x_in_op[s]: the copy that brought x_s back
+    std::vector<uint8_t> hold_written(L + 1, 0);
+    // what a reader's op takes from the records it reads again; false when one of them is not in memory
+    auto read_again = [&](ProgOp& p, uint32_t j) {
+      for (uint32_t s : reads[j]) {
+        if (x_at[s] < 0) return false;
+        p.rx.push_back(x_at[s]);
+        if (x_in_op[s] >= 0) p.waits.push_back((uint32_t)x_in_op[s]);   // a premature swap-in
+      }
+      return true;
+    };
     uint64_t host_top = 0;
     std::vector<int64_t> host_x(L, -1), host_s(L, -1);
     c.prog.clear();
@@ -101,6 +122,7 @@ struct Builder {
           p.out = o.off[0]; p.s = o.off[1]; p.ws = o.off[2];
           claim(p, p.out, x_sz[i + 1]); claim(p, p.s, s_sz[i]); claim(p, p.ws, w_sz[i]);
           x_at[i + 1] = p.out; s_at[i] = p.s;
+          if (!read_again(p, i)) return KARMA_E_INVAL;
           f_op[i] = k;
           { int64_t w = p.ws; release(w, w_sz[i], k); }
           if (p_sz[i]) {
@@ -135,8 +157,8 @@ struct Builder {
           p.host_x = host_x[i]; p.host_s = host_s[i];
           claim(p, p.x, x_sz[i]); claim(p, p.s, s_sz[i]);
           if (out_op[i] >= 0) p.waits.push_back((uint32_t)out_op[i]);   // host copy must be complete
-          x_at[i] = p.x;
-          if (a == KARMA_SWAP) s_at[i] = p.s;
+          if (p.x >= 0) { x_at[i] = p.x; x_in_op[i] = k; }   // (an input that came back early for a reader stays where it is)
+          if (a == KARMA_SWAP && p.s >= 0) s_at[i] = p.s;
           in_op[i] = k;
           break;
         case 'W':
@@ -170,11 +192,21 @@ struct Builder {
           s_at[i] = p.s;
           if (p.out >= 0) x_at[i + 1] = p.out;
           if (in_op[i] >= 0) p.waits.push_back((uint32_t)in_op[i]);
+          if (!read_again(p, i)) return KARMA_E_INVAL;
           { int64_t w = p.ws; release(w, w_sz[i], k); }
           if (p_sz[i]) {
             p.w = p_at[i];
             p.waits.push_back((uint32_t)win_op[i]);
           }
+          break;
+        case 'H':
+          // no work of its own: on the compute stream, so that the backward op behind it inherits the waits
+          // for whoever held this memory before
+          p.stream = 0;
+          if (i > L || hold_at[i] >= 0) return KARMA_E_INVAL;
+          claim(p, o.off[0], x_sz[i]);
+          hold_at[i] = o.off[0];
+          hold_written[i] = 0;
           break;
         case 'B':
           p.stream = 0;
@@ -183,6 +215,19 @@ struct Builder {
           claim(p, p.dx, x_sz[i]); claim(p, p.ws, w_sz[i]);
           dx_at[i] = p.dx;
           if (in_op[i] >= 0) p.waits.push_back((uint32_t)in_op[i]);
+          if (!read_again(p, i)) return KARMA_E_INVAL;
+          for (uint32_t sdx : reads[i]) {
+            if (hold_at[sdx] < 0) return KARMA_E_INVAL;
+            p.rdx.push_back(hold_at[sdx]);
+            p.rdx_first.push_back(hold_written[sdx] ? 0 : 1);
+            hold_written[sdx] = 1;
+          }
+          if (hold_at[i] >= 0) {
+            if (!hold_written[i] || p.dx < 0) return KARMA_E_INVAL;
+            p.hold = hold_at[i];
+            p.hold_elems = c.cost[i - 1].out_bytes / 2;
+            release(hold_at[i], x_sz[i], k);
+          }
           { int64_t w = p.ws; release(w, w_sz[i], k); }
           release(dx_at[i + 1], x_sz[i + 1], k);
           release(s_at[i], s_sz[i], k);
@@ -224,10 +269,10 @@ int install_plan(Ctx* c, uint64_t budget, const std::vector<uint8_t>& actions, c
   if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
   int fst = finish_all_updates(c);
   if (fst) return fst;
-  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
+  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes, c->skips.data(), (uint32_t)c->skips.size()};
   std::vector<karma_op> ops;
   karma_plan_summary s;
-  if (!actions_valid(actions.data(), c->L)) return fail(c, KARMA_E_INVAL, "invalid action vector");
+  if (!actions_valid(actions.data(), c->L, P.skips, P.n_skips)) return fail(c, KARMA_E_INVAL, "invalid action vector");
   if (!simulate(P, actions.data(), keepw.data(), &s, &ops)) return fail(c, KARMA_E_BUDGET, "assignment does not fit the budget");
   free_plan_resources(c);
   c->actions = actions;
@@ -269,10 +314,23 @@ int issue(Ctx* c, const ProgOp& p) {
   io.dx = c->act_ptr(p.dx);
   io.w = c->act_ptr(p.w);
   io.g = c->act_ptr(p.g);
+  io.n_skips = (int)p.rx.size();
+  for (size_t j = 0; j < p.rx.size(); ++j) io.skip_x[j] = c->act_ptr(p.rx[j]);
+  for (size_t j = 0; j < p.rdx.size(); ++j) {
+    io.skip_dx[j] = c->act_ptr(p.rdx[j]);
+    io.skip_dx_first[j] = p.rdx_first[j] != 0;
+  }
   switch (p.kind) {
     case 'F':
     case 'R': return layer_forward(*c, p.layer, io, s);
-    case 'B': return layer_backward(*c, p.layer, io, s);
+    case 'B': {
+      int st = layer_backward(*c, p.layer, io, s);
+      if (st) return st;
+      // the gradient its other readers left for this record's input joins the one just computed
+      if (p.hold >= 0) return add_inplace_bf16((bf16_t*)io.dx, (const bf16_t*)c->act_ptr(p.hold), p.hold_elems, s);
+      return KARMA_OK;
+    }
+    case 'H': return KARMA_OK;
     case 'L': return loss_op(*c, io, s);
     case 'O':
       if (p.x_bytes) KARMA_HIP(c, hipMemcpyAsync(c->swap_pool + p.host_x, c->act_ptr(p.x), p.x_bytes, hipMemcpyDeviceToHost, s));
@@ -587,7 +645,23 @@ extern "C" int karma_model_layers(const karma_model_desc* d, uint32_t* n_out) {
   else if (d->kind == KARMA_MODEL_GPT) *n_out = (d->split_blocks ? 2 * d->n_layers : d->n_layers) + 1;
   else if (d->kind == KARMA_MODEL_CNN) *n_out = 1 + d->stage_blocks[0] + d->stage_blocks[1] + d->stage_blocks[2] + d->stage_blocks[3];
   else if (d->kind == KARMA_MODEL_WRN) *n_out = 1 + d->stage_blocks[0] + d->stage_blocks[1] + d->stage_blocks[2];
+  else if (d->kind == KARMA_MODEL_UNET) *n_out = 2 * d->n_layers + 1;
   else return KARMA_E_INVAL;
+  return KARMA_OK;
+}
+
+extern "C" int karma_model_skips(const karma_model_desc* d, karma_skip* skips_out, uint32_t* n_inout) {
+  if (!d || !n_inout) return KARMA_E_INVAL;
+  std::vector<karma_skip> sk;
+  if (d->kind == KARMA_MODEL_UNET) {
+    int st = unet_skips(*d, sk);
+    if (st) return st;
+  }
+  if (skips_out) {
+    if (*n_inout < sk.size()) { *n_inout = (uint32_t)sk.size(); return KARMA_E_OOM; }
+    std::memcpy(skips_out, sk.data(), sk.size() * sizeof(karma_skip));
+  }
+  *n_inout = (uint32_t)sk.size();
   return KARMA_OK;
 }
 
@@ -808,7 +882,7 @@ extern "C" int karma_plan(karma_ctx* c, uint64_t budget, uint8_t* actions_out, u
                           karma_plan_summary* summary_out) {
   if (!c) return KARMA_E_INVAL;
   if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
-  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
+  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes, c->skips.data(), (uint32_t)c->skips.size()};
   std::vector<uint8_t> a, kw;
   karma_plan_summary s;
   if (!plan(P, a, kw, &s)) return fail(c, KARMA_E_BUDGET, "no assignment fits the budget");
@@ -824,7 +898,7 @@ extern "C" int karma_plan_grouped(karma_ctx* c, uint64_t budget, uint32_t max_gr
                                   uint8_t* weights_kept_out, karma_plan_summary* summary_out, uint32_t* group_out) {
   if (!c || !max_group) return KARMA_E_INVAL;
   if (budget > c->arena_bytes) return fail(c, KARMA_E_OOM, "budget exceeds the arena handed to karma_create");
-  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes};
+  Problem P{c->cost.data(), c->L, c->link, c->loss_cost, budget, c->fixed_bytes, c->skips.data(), (uint32_t)c->skips.size()};
   std::vector<uint8_t> a, kw;
   karma_plan_summary s;
   uint32_t g = 1;

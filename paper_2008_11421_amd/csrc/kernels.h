@@ -120,6 +120,9 @@ int bn_bwd(const bf16_t* dy, const bf16_t* x, const float* stats, const bf16_t* 
 int relu_mask_bwd(const bf16_t* dy, const bf16_t* y, bf16_t* dz, size_t n, hipStream_t s);
 int maxpool_fwd(const bf16_t* x, bf16_t* y, int n, int h, int w, int c, hipStream_t s);   // 3x3, stride 2, pad 1
 int maxpool_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int w, int c, hipStream_t s);
+int maxpool2_fwd(const bf16_t* x, bf16_t* y, int n, int h, int w, int c, hipStream_t s);  // 2x2, stride 2; h, w even
+int maxpool2_bwd(const bf16_t* x, const bf16_t* dy, bf16_t* dx, int n, int h, int w, int c, hipStream_t s);
+int add_inplace_bf16(bf16_t* y, const bf16_t* a, size_t n, hipStream_t s);                // y += a; n a multiple of 8
 int avgpool_fwd(const bf16_t* x, bf16_t* y, int n, int hw, int c, hipStream_t s);         // global
 int avgpool_bwd(const bf16_t* dy, bf16_t* dx, int n, int hw, int c, hipStream_t s);
 

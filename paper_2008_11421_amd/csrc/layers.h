@@ -29,4 +29,12 @@ int wrn_prepare_late(Ctx& c);
 int wrn_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int wrn_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
 int wrn_loss(Ctx& c, const LayerIO& io, hipStream_t s);
+
+int unet_build_records(Ctx& c);   // also fills c.skips
+int unet_skips(const karma_model_desc& d, std::vector<karma_skip>& out);
+int unet_prepare_step(Ctx& c, const void* in, const void* lab);
+int unet_prepare_late(Ctx& c);
+int unet_forward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int unet_backward(Ctx& c, uint32_t i, const LayerIO& io, hipStream_t s);
+int unet_loss(Ctx& c, const LayerIO& io, hipStream_t s);
 }  // namespace karma

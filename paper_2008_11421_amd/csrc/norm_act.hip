@@ -483,6 +483,38 @@ __global__ __launch_bounds__(CE_THREADS) void softmax_ce_kernel(bf16_t* __restri
   }
 }
 
+// The same for many short rows (a per-pixel classifier: millions of rows of a few classes): one thread per row,
+// the row in registers.  NV = cols / 8.
+template <int NV>
+__global__ __launch_bounds__(256) void softmax_ce_rows_kernel(bf16_t* __restrict__ logits, const int* __restrict__ labels,
+                                                              float* __restrict__ rowloss, int rows, float scale) {
+  const size_t r = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= (size_t)rows) return;
+  bf16_t* src = logits + r * (NV * 8);
+  float f[NV * 8];
+#pragma unroll
+  for (int c = 0; c < NV; ++c) unpack8(*(const u32x4*)(src + c * 8), f + c * 8);
+  float mx = f[0];
+#pragma unroll
+  for (int e = 1; e < NV * 8; ++e) mx = fmaxf(mx, f[e]);
+  float sum = 0.f;
+#pragma unroll
+  for (int e = 0; e < NV * 8; ++e) sum += __expf(f[e] - mx);
+  const int label = labels[r];
+  float at_label = 0.f;
+  const float inv = 1.f / sum;
+#pragma unroll
+  for (int e = 0; e < NV * 8; ++e) {
+    if (e == label) at_label = f[e];
+    float p = __expf(f[e] - mx) * inv;
+    if (e == label) p -= 1.f;
+    f[e] = p * scale;
+  }
+  rowloss[r] = mx + __logf(sum) - at_label;
+#pragma unroll
+  for (int c = 0; c < NV; ++c) *(u32x4*)(src + c * 8) = pack8(f + c * 8);
+}
+
 // fixed-order sum of n floats (two stages) scaled: the mean loss
 __global__ __launch_bounds__(256) void sum_stage1_kernel(const float* __restrict__ x, float* __restrict__ partial, size_t n) {
   __shared__ float red[256];
@@ -623,6 +655,15 @@ int embed_bwd(const bf16_t* dx, const int* order, const int* seg_start, const in
 int softmax_ce(bf16_t* logits, const int* labels, float* rowloss, int rows, int cols, float scale, hipStream_t s) {
   const size_t lds = (size_t)cols * sizeof(bf16_t);
   if (cols % 8 || rows <= 0 || lds > 150 * 1024) return KARMA_E_INVAL;
+  if (cols <= 16 && rows >= 4096) {   // short rows, many of them: a thread per row
+    if (cols == 8)
+      hipLaunchKernelGGL(softmax_ce_rows_kernel<1>, dim3(blocks_for((size_t)rows, 256)), dim3(256), 0, s, logits, labels, rowloss,
+                         rows, scale);
+    else
+      hipLaunchKernelGGL(softmax_ce_rows_kernel<2>, dim3(blocks_for((size_t)rows, 256)), dim3(256), 0, s, logits, labels, rowloss,
+                         rows, scale);
+    return ok();
+  }
   if (lds > 64 * 1024)
     (void)hipFuncSetAttribute((const void*)softmax_ce_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(softmax_ce_kernel, dim3(rows), dim3(CE_THREADS), lds, s, logits, labels, rowloss, cols, scale);

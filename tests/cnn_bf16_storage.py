@@ -199,3 +199,115 @@ def wrn_problem(dims, shift, seed=2008114204):
         p["b2"] = p["b2"] + shift
     params["head"]["b"] = params["head"]["b"] + shift
     return params, q(images), labels.astype(np.int32)
+
+
+# ------------------------------------------------------------------ fully convolutional network
+def _double_conv_fwd(p, x, x2=None):
+    """x2: second half of the concatenated input (the convolution over the concatenation is computed as the
+    sum of one convolution per half, the first half's result stored in between)."""
+    if x2 is None:
+        c1 = q(cnn.conv2d_fwd(x, p["w1"], 1, 1))
+    else:
+        c = x.shape[3]
+        half = q(cnn.conv2d_fwd(x, p["w1"][..., :c], 1, 1))
+        c1 = q(cnn.conv2d_fwd(x2, p["w1"][..., c:], 1, 1) + half)
+    n1, s1 = cnn.batchnorm_fwd(c1, p["g1"], p["b1"])
+    a1 = q(np.maximum(n1, 0))
+    c2 = q(cnn.conv2d_fwd(a1, p["w2"], 1, 1))
+    n2, s2 = cnn.batchnorm_fwd(c2, p["g2"], p["b2"])
+    return q(np.maximum(n2, 0)), (x, x2, n1, a1, s1, n2, s2)
+
+
+def _double_conv_bwd(p, saved, dy):
+    x, x2, n1, a1, s1, n2, s2 = saved
+    g = {}
+    dc2, g["g2"], g["b2"] = cnn.batchnorm_bwd(dy * (n2 > 0), p["g2"], s2)
+    da1, g["w2"] = cnn.conv2d_bwd(a1, p["w2"], q(dc2), 1, 1)
+    dc1, g["g1"], g["b1"] = cnn.batchnorm_bwd(q(da1) * (n1 > 0), p["g1"], s1)
+    dc1 = q(dc1)
+    if x2 is None:
+        dx, g["w1"] = cnn.conv2d_bwd(x, p["w1"], dc1, 1, 1)
+        return q(dx), None, g
+    c = x.shape[3]
+    dx, gw_a = cnn.conv2d_bwd(x, p["w1"][..., :c], dc1, 1, 1)
+    dx2, gw_b = cnn.conv2d_bwd(x2, p["w1"][..., c:], dc1, 1, 1)
+    g["w1"] = np.concatenate([gw_a, gw_b], axis=3)
+    return q(dx), q(dx2), g
+
+
+def unet_step_bf16_storage(params, images, labels):
+    """Same signature and result layout as `oracle.unet.unet_step`, tensors between operations rounded to bf16."""
+    from oracle import unet
+    depth = len(params["up"])
+    outs, saved, pools = [], [], []
+    x = images
+    for l, p in enumerate(params["down"]):
+        if l:
+            x, arg = cnn.maxpool_fwd(x, 2, 2, 0)
+            pools.append((arg, outs[-1].shape))
+        x, s = _double_conv_fwd(p, x)
+        outs.append(x)
+        saved.append(s)
+    up_saved = []
+    for j, p in enumerate(params["up"]):
+        l = depth - 1 - j
+        u = q(unet.upconv2x2_fwd(x, p["wu"]))
+        below = x
+        x, s = _double_conv_fwd(p, outs[l], u)
+        up_saved.append((below, s))
+    hd = params["head"]
+    ch = x.shape[3]
+    flatx = x.reshape(-1, ch)
+    logits = q(nn.linear_fwd(flatx, hd["w"], hd["bias"]))
+    loss, dlogits = nn.cross_entropy_fwd_bwd(logits, labels.reshape(-1))
+    grads = {"down": [None] * (depth + 1), "up": [None] * depth, "head": {}}
+    dflat, grads["head"]["w"], grads["head"]["bias"] = nn.linear_bwd(flatx, hd["w"], q(dlogits))
+    dx = q(dflat).reshape(x.shape)
+    dskip = [None] * depth
+    for j in range(depth - 1, -1, -1):
+        l = depth - 1 - j
+        p = params["up"][j]
+        below, s = up_saved[j]
+        dskip[l], du, g = _double_conv_bwd(p, s, dx)
+        dxb, g["wu"] = unet.upconv2x2_bwd(below, p["wu"], du)
+        dx = q(dxb)
+        grads["up"][j] = g
+    for l in range(depth, -1, -1):
+        if l < depth:
+            dx = q(dx + dskip[l])
+        dx, _, grads["down"][l] = _double_conv_bwd(params["down"][l], saved[l], dx)
+        if l:
+            arg, shape = pools[l - 1]
+            dx = cnn.maxpool_bwd(dx, arg, shape, 2, 2, 0)
+    return loss, grads
+
+
+UNET_SMALL = dict(width=8, depth=2, image=32, batch=2, classes=2)
+
+
+def unet_problem(dims, shift, seed=2008114205):
+    """Seeded fully convolutional network and batch; every batch-norm shift raised by `shift`; images on the bf16 grid."""
+    import synth_inputs as si
+    params, images, labels = si.unet_problem(seed=seed, bn_jitter=0.1, **dims)
+    params["head"]["w"] = si.normal(seed + 99, params["head"]["w"].shape, 0.3)   # a classifier that already discriminates
+    for p in params["down"] + params["up"]:
+        p["b1"] = p["b1"] + shift
+        p["b2"] = p["b2"] + shift
+    return params, q(images), labels.astype(np.int32)
+
+
+def unet_rounded_params(params):
+    return dict(down=[{k: q(v) for k, v in p.items()} for p in params["down"]],
+                up=[{k: q(v) for k, v in p.items()} for p in params["up"]],
+                head={k: q(v) for k, v in params["head"].items()})
+
+
+def unet_flat(grads):
+    out = {"head." + k: v for k, v in grads["head"].items()}
+    for l, gl in enumerate(grads["down"]):
+        for k, v in gl.items():
+            out["d%d.%s" % (l, k)] = v
+    for j, gl in enumerate(grads["up"]):
+        for k, v in gl.items():
+            out["u%d.%s" % (j, k)] = v
+    return out

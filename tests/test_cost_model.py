@@ -31,7 +31,35 @@ def wrn_desc(batch=128):
                 vocab=WRN["classes"], stream_weights=0, stage_blocks=WRN["group_blocks"] + (0,))
 
 
+UNET = dict(width=64, depth=4, image=512, batch=4, classes=8)
+
+
+def unet_desc(batch=4):
+    return dict(kind=K.MODEL_UNET, n_layers=UNET["depth"], width=UNET["width"], batch=batch, seq=UNET["image"], n_heads=0,
+                ffn=0, vocab=UNET["classes"], stream_weights=0, stage_blocks=(0, 0, 0, 0))
+
+
 # ------------------------------------------------------------------ oracle pins
+def test_oracle_unet_counts_written_out():
+    """Padded 3x3 convolutions keep the image size, so every level's convolution count has a closed form."""
+    blocks, loss = CM.unet_blocks(**dict(UNET, batch=1))
+    assert len(blocks) == 9
+    px = 512 * 512
+    assert blocks[0] == (px * 64 * 9 * (1 + 64), 20 * px * 64)
+    # level 1: pooling of 64 channels down to 256x256, then 64 -> 128 -> 128
+    assert blocks[1] == (px // 4 * 128 * 9 * (64 + 128), px // 4 * 64 * 4 + 20 * (px // 4) * 128)
+    # lowest level
+    assert blocks[4][0] == px // 256 * 1024 * 9 * (512 + 1024)
+    # expansive level 3: up-convolution 1024 -> 512 on 64x64, then 1024 -> 512 -> 512
+    assert blocks[5] == (px // 64 * 512 * (1024 + 9 * 1024 + 9 * 512), 20 * (px // 64) * 512)
+    assert blocks[8][0] == px * 64 * (128 + 9 * 128 + 9 * 64)
+    assert loss == (px * 64 * 8, 2 * px * 8)
+    # channels double where pixels quarter, so every level below the first costs the same: contracting levels
+    # 9 * 1.5 * 64^2 per level-0 pixel, expansive levels (2 + 18 + 9) * 64^2
+    total = sum(b[0] for b in blocks) + loss[0]
+    assert total == px * (64 * 9 * 65 + 4 * 9 * 3 * 64 * 64 // 2 + 4 * 29 * 64 * 64 + 64 * 8)
+
+
 def test_oracle_wrn_28_10_total_and_blocks():
     """WRN-28-10 on a 32x32 image is known as a 5.2 G multiply-add network; its blocks written out."""
     blocks, loss = CM.wrn_blocks(**dict(WRN, batch=1))
@@ -122,6 +150,29 @@ def test_library_times_bit_exact():
         check_times(cnn_desc(batch), *CM.cnn_blocks(**dict(CNN, batch=batch)))
     for batch in (4, 128):
         check_times(wrn_desc(batch), *CM.wrn_blocks(**dict(WRN, batch=batch)))
+    for batch in (1, 16):
+        check_times(unet_desc(batch), *CM.unet_blocks(**dict(UNET, batch=batch)))
+
+
+def test_unet_connections_and_plan_on_analytic_costs():
+    """The library names the model's connections, and its planner on the analytic costs agrees with the oracle
+    planner given the same connections; with connections present no record whose input is read again is chained."""
+    desc = unet_desc(16)
+    skips = K.karma_model_skips(desc)
+    assert skips == [(0, 8), (1, 7), (2, 6), (3, 5)]
+    assert K.karma_model_skips(wrn_desc()) == []
+    layers, (t_loss, ws_loss), fixed = K.karma_model_costs(desc, *RATES)
+    link = (50 * 10**9, 50 * 10**9, 10000)
+    need = fixed + sum(l[3] + l[4] for l in layers)
+    seen = set()
+    for share in (1.0, 0.6, 0.4):
+        budget = fixed + int((need - fixed) * share) + 2 * max(l[5] for l in layers)
+        ao, so = P.plan([P.Layer(*l) for l in layers], P.Link(*link), budget, fixed, P.Loss(t_loss, ws_loss), skips=skips)
+        al, sl = K.karma_plan_graph(layers, link, (t_loss, ws_loss), budget, fixed, skips)
+        assert list(al) == list(ao) and sl["makespan_ns"] == so["makespan_ns"] and sl["peak_bytes"] == so["peak_bytes"]
+        assert all(al[s + 1] != P.RC_CHAIN for s, _ in skips)
+        seen.add(tuple(al))
+    assert len(seen) >= 2
 
 
 def test_split_transformer_blocks_counts_and_bytes():
