@@ -51,6 +51,11 @@ WORKLOADS = {
             name="supplementary (Table III; the setting of the paper's blocking study, Fig. 7): ResNet-50-shaped bottleneck CNN "
                  "(stages 3/4/6/3), 224x224x3 images, batch 512, 1000 classes, bf16, host SGD with momentum; in-core under 48 GiB, "
                  "then under a 16 GiB budget"),
+    7: dict(cfg=dict(width=64, depth=4, image=512, batch=16, classes=2),
+            budget=24 * GIB, arena=28 * GIB, seed=2008114208, stream=0, kind="unet", low_budget=6 * GIB,
+            name="supplementary (Table III, fully convolutional; Sec. III-F.3: connections from the contracting to the expansive "
+                 "path): U-Net (depth 4, 64..1024 channels, 31 M parameters), 512x512 one-channel images, batch 16, 2 classes "
+                 "stored as 8, BatchNorm + ReLU, bf16, host SGD with momentum; in-core under 24 GiB, then under a 6 GiB budget"),
 }
 CFG = WORKLOADS[1]["cfg"]
 BUDGET = WORKLOADS[1]["budget"]
@@ -312,7 +317,33 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
     cfg_m = wl["cfg"]
     cfg = dict(optimizer=K.OPT_SGD_MOMENTUM, lr=1e-3, beta1=0.9, beta2=0.0, eps=0.0, host_threads=threads)
     t0 = time.perf_counter()
-    if wl["kind"] == "wrn":
+    if wl["kind"] == "unet":
+        classes = (cfg_m["classes"] + 7) // 8 * 8
+        depth = cfg_m["depth"]
+        desc = dict(kind=K.MODEL_UNET, n_layers=depth, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0,
+                    ffn=0, vocab=classes, stream_weights=0, stage_blocks=(0, 0, 0, 0))
+        ctx = K.Context(desc, cfg, wl["arena"])
+        params, images, labels = si.unet_problem(seed=wl["seed"], **cfg_m)
+        images = images[..., 0]
+        for l, p in enumerate(params["down"]):
+            for t, name in enumerate(si.LEVEL_TENSORS):
+                v = p[name]
+                if l == 0 and name == "w1":      # the one image channel is stored as eight
+                    v = np.concatenate([v, np.zeros(v.shape[:3] + (7,))], axis=3)
+                ctx.karma_set_param(l, t, v)
+        for j, p in enumerate(params["up"]):
+            c = p["w1"].shape[3] // 2            # the first weight as two tensors: contracting half, up-convolution half
+            for t, v in enumerate((p["wu"], p["w1"][..., :c], p["w1"][..., c:], p["g1"], p["b1"], p["w2"], p["g2"], p["b2"])):
+                ctx.karma_set_param(depth + 1 + j, t, v)
+        hd = params["head"]
+        fc = np.zeros((classes, hd["w"].shape[1]), dtype=np.float32)
+        fc[:cfg_m["classes"]] = hd["w"]
+        bias = np.full(classes, -30000.0, dtype=np.float32)
+        bias[:cfg_m["classes"]] = hd["bias"]
+        ctx.karma_set_param(2 * depth + 1, 0, fc)
+        ctx.karma_set_param(2 * depth + 1, 1, bias)
+        params = dict(blocks=[])
+    elif wl["kind"] == "wrn":
         classes = (cfg_m["classes"] + 7) // 8 * 8      # stored classes: the extra ones can never be predicted
         desc = dict(kind=K.MODEL_WRN, n_layers=0, width=cfg_m["width"], batch=cfg_m["batch"], seq=cfg_m["image"], n_heads=0,
                     ffn=0, vocab=classes, stream_weights=0, stage_blocks=tuple(cfg_m["group_blocks"]) + (0,))
@@ -347,7 +378,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
         ctx.karma_set_param(L, 0, params["head"]["w"])
         ctx.karma_set_param(L, 1, params["head"]["b"])
     for i, (p, _) in enumerate(params["blocks"]):
-        for t, name in enumerate(tensors):
+        for t, name in enumerate(tensors):   # (the fully convolutional network has loaded its levels above)
             if name in p:
                 ctx.karma_set_param(i + 1, t, p[name])
     del params
@@ -430,7 +461,7 @@ def bench_cnn(args, wl, K, si, torch, np, threads):
                                                          "predicted_makespan_ms": summ_g["makespan_ns"] / 1e6,
                                                          "plan": "".join("KSRrc"[a] for a in acts_g)}},
         "host_link_gbps": {"h2d": link[0] / 1e9, "d2h": link[1] / 1e9}, "host_opt_ms": st["host_opt_ms"],
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel (convolutions as implicit GEMMs and the FC layer; " + SAMPLING_NOTE + ")",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel and gemm_bf16_dl_kernel (convolutions as implicit GEMMs, the FC layer / classifier; " + SAMPLING_NOTE + ")",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "launches_per_step": n_l * TIMER_STRIDE / max(args.steps, 1), "avg_launch_ms": ms_l / max(n_l, 1),
                      "flops_per_launch": fl_l / max(n_l, 1), "traffic": None},
@@ -464,7 +495,7 @@ def main():
     args = ap.parse_args()
     global CFG, BUDGET, ARENA, SEED
     wl = dict(WORKLOADS[args.config])
-    if args.layers and wl.get("kind") not in ("cnn", "wrn") and 0 < args.layers < wl["cfg"]["n_layers"]:
+    if args.layers and wl.get("kind") not in ("cnn", "wrn", "unet") and 0 < args.layers < wl["cfg"]["n_layers"]:
         wl["cfg"] = dict(wl["cfg"], n_layers=args.layers)
         wl["name"] += " -- DEPTH TRUNCATED to %d blocks for this run" % args.layers
     CFG, BUDGET, ARENA, SEED = wl["cfg"], wl["budget"], wl["arena"], wl["seed"]
@@ -493,7 +524,7 @@ def main():
     torch.cuda.empty_cache()
 
     threads = int(os.environ.get("OMP_NUM_THREADS", "16"))
-    if wl.get("kind") in ("cnn", "wrn"):
+    if wl.get("kind") in ("cnn", "wrn", "unet"):
         return bench_cnn(args, wl, K, si, torch, np, threads)
     if args.batch_sweep:
         if args.config != 1:

@@ -437,14 +437,14 @@ class Context:
         return n.value, ms.value, fl.value
 
     def karma_get_op_times(self):
-        n = C.c_uint32(6 * self.n_layers + 2)
+        n = C.c_uint32(10 * self.n_layers + 2)
         ops = (Op * n.value)()
         ms = (C.c_float * n.value)()
         self._chk(lib().karma_get_op_times(self.ctx, ops, ms, C.byref(n)), "karma_get_op_times")
         return [(chr(ops[k].kind), ops[k].layer, ops[k].start_ns, ops[k].end_ns, ms[k]) for k in range(n.value)]
 
     def karma_get_op_starts(self):
-        n = C.c_uint32(6 * self.n_layers + 2)
+        n = C.c_uint32(10 * self.n_layers + 2)
         starts = (C.c_float * n.value)()
         self._chk(lib().karma_get_op_starts(self.ctx, starts, C.byref(n)), "karma_get_op_starts")
         return [starts[k] for k in range(n.value)]
