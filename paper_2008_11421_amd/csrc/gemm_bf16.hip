@@ -353,7 +353,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int KSTEPS = BK / 16;
   static_assert(BK == 64 && KSTEPS == 4, "swizzles below are written for 128-byte k-rows");
-  static_assert(BM == 256 && BN == 256, "strided swizzle assumes 512-byte k-rows");
+  // the narrow tile (BN = 64: convolutions with 64 output channels) exists for k-contiguous operands only
+  static_assert(BM == 256 && (BN == 256 || (BN == 64 && A_KC && B_KC)), "strided swizzle assumes 512-byte k-rows");
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int CH_A = A_BYTES / 1024 / WAVES, CH_B = B_BYTES / 1024 / WAVES;   // 1 KiB pieces per wavefront
   constexpr int LPT = CH_A + CH_B;                                               // direct loads per lane per k-tile
@@ -392,7 +393,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   // 512-byte k-row).  The lane at LDS piece p of a row fetches global piece p ^ swizzle(row):
   //   k-contiguous: swizzle = (row / 2) % 8     strided: swizzle = (k % 4) * 4
   // Both depend on i only through its parity, so two column offsets per lane suffice.
-  static_assert((BM / WAVES) % 16 == 0 && (BN / WAVES) % 16 == 0 && (BK / WAVES) % 4 == 0, "swizzle parity per piece");
+  // (a wavefront whose share of a k-contiguous B tile is a single piece of eight rows, BN / WAVES = 8, starts on an
+  // odd or even piece depending on its number: B_ODD0 below)
+  static_assert((BM / WAVES) % 16 == 0 && ((BN / WAVES) % 16 == 0 || (BN / WAVES == 8 && B_KC)) && (BK / WAVES) % 4 == 0,
+                "swizzle parity per piece");
+  const int B_ODD0 = (B_KC && (BN / WAVES) % 16 != 0) ? (wave & 1) : 0;
   const int a_row = A_KC ? wave * (BM / WAVES) + (lane >> 3) : wave * (BK / WAVES) + (lane >> 5);
   const int b_row = B_KC ? wave * (BN / WAVES) + (lane >> 3) : wave * (BK / WAVES) + (lane >> 5);
   // byte offset of each of this lane's pieces from the tile's first element; a tile is then a uniform
@@ -400,11 +405,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   unsigned a_off[CH_A], b_off[CH_B];
 #pragma unroll
   for (int i = 0; i < (CH_A > CH_B ? CH_A : CH_B); ++i) {
-    const int odd = i & 1;
+    const int odd = i & 1, odd_b = (i + B_ODD0) & 1;
     const int kc_col = ((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) * 8;
+    const int kc_col_b = ((lane & 7) ^ ((4 * odd_b + (lane >> 4)) & 7)) * 8;
     const int st_col = ((lane & 31) ^ ((2 * odd + (lane >> 5)) << 2)) * 8;
     if (i < CH_A) a_off[i] = (unsigned)(((size_t)(a_row + i * (A_KC ? 8 : 2)) * lda + (A_KC ? kc_col : st_col)) * sizeof(bf16_t));
-    if (i < CH_B) b_off[i] = (unsigned)(((size_t)(b_row + i * (B_KC ? 8 : 2)) * ldb + (B_KC ? kc_col : st_col)) * sizeof(bf16_t));
+    if (i < CH_B) b_off[i] = (unsigned)(((size_t)(b_row + i * (B_KC ? 8 : 2)) * ldb + (B_KC ? kc_col_b : st_col)) * sizeof(bf16_t));
   }
   // element offset of an item's k-tile 0 (the same in every lane)
   auto a_origin = [&](int m0, int kb) { return A_KC ? (size_t)m0 * lda + kb : (size_t)kb * lda + m0; };
@@ -412,8 +418,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   // EDGE: where piece i of this lane lies inside a tile: (row of the operand, k) for a k-contiguous tile,
   // (k, first of its eight rows) for a strided one; `rows` is how many rows the operand has from the tile's
   // first row on, `ks` how many k are left from the tile's first k on
-  auto piece_inside = [&](bool kc, int rowbase, int i, int rows, int ks) {
-    const int odd = i & 1;
+  auto piece_inside = [&](bool kc, int rowbase, int i, int rows, int ks, int odd0 = 0) {
+    const int odd = (i + odd0) & 1;
     if (kc) {
       const int r = rowbase + i * 8, k = ((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) * 8;
       return r < rows && k < ks;
@@ -515,7 +521,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
     const bf16_t* pb = B + bo + (B_KC ? (size_t)t * BK : (size_t)t * BK * ldb);
 #pragma unroll
     for (int i = 0; i < CH_B; ++i)
-      fetch_piece(pb, b_off[i], sb + i * 1024, !EDGE || piece_inside(B_KC, b_row, i, N - n0, kend - k0 - t * BK));
+      fetch_piece(pb, b_off[i], sb + i * 1024, !EDGE || piece_inside(B_KC, b_row, i, N - n0, kend - k0 - t * BK, B_ODD0));
   };
   auto issue = [&](int stage, size_t ao, size_t bo, int t, int m0 = 0, int n0 = 0, int k0 = 0, int kend = 0, bool nxt = false) {
     issue_a(stage, ao, t, m0, k0, kend, nxt);
@@ -608,10 +614,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
         // one LDS read in the shadow of each MFMA
 #pragma unroll
         for (int r = 0; r < TM + TN; ++r) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (r < TM * TN) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+        if constexpr (TM * TN > TM + TN) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
         __builtin_amdgcn_sched_barrier(0);
         if (kk == KSTEPS - 2 && more) {
           // The next k-tile (issued one tile ago) must have landed, for every wavefront; past
@@ -787,6 +793,19 @@ static int compute_units() {
 template <int BM, int BN, int BK, int WGM, int WGN, bool EDGE>
 static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 block, int tiles_m, int tiles_n, int splits,
                           int k_per_split, const GemmEpilogue& ep) {
+  if constexpr (BM == 256 && BN == 64 && BK == 64 && EDGE) {
+    // the narrow tile: a gathered first operand against 64 output channels
+    constexpr int STAGE = (BM + BN) * BK * 2, STRIP = WGM * WGN * 32 * (BN / WGN + 4) * 4;
+    constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
+    const int lds = 2 * STAGE + 2 * EXTRA;
+    if (g.conv_mode == 1) {
+      const unsigned magic_c = (unsigned)((1ull << 32) / (unsigned)g.conv.C + 1), magic_s = (unsigned)((1ull << 32) / (unsigned)g.conv.S + 1);
+      auto kern = gemm_bf16_dl_kernel<BM, BN, BK, WGM, WGN, true, true, 0, true, 1>;
+      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      hipLaunchKernelGGL(kern, grid, block, lds, s, g.A, g.B, g.M, g.N, g.K, g.lda, g.ldb, tiles_m, tiles_n, splits,
+                         k_per_split, ep, (float*)g.ws, g.conv, magic_c, magic_s, 0u, 0.f);
+    }
+  }
   if constexpr (BM == 256 && BN == 256 && BK == 64) {
     constexpr int STAGE = (BM + BN) * BK * 2, STRIP = WGM * WGN * 32 * (BN / WGN + 4) * 4;
     constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
@@ -960,6 +979,13 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
         cg.Wo + cg.pad + 64 < 1024 && g.M / pixels < 4095 && gathered_bytes < (1ull << 32) && (uint64_t)g.K * cg.C < (1ull << 31) &&
         ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
       return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
+    // The same with 64 output channels (the first stage of the bottleneck network, the full-resolution level of the
+    // fully convolutional one): a 256 x 64 tile, eight wavefronts of 32 x 64
+    if (g.conv_mode == 1 && g.N == 64 && (g.M + 255) / 256 >= 192 && g.K >= 128 && g.ldc % 8 == 0 && cg.stride <= 2 &&
+        cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 && cg.Ho + cg.pad + 64 < 1024 &&
+        cg.Wo + cg.pad + 64 < 1024 && g.M / pixels < 4095 && gathered_bytes < (1ull << 32) && (uint64_t)g.K * cg.C < (1ull << 31) &&
+        ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
+      return launch_cfg<256, 64, 64, 8, 1, true>(g, s);
     // The weight gradient (second operand gathered, reduction over the pixels): few output tiles and a very long
     // reduction, which the split fills the chip with; worth the large tile from 128 x 1024 results on.
     if (g.conv_mode == 2 && g.M >= 128 && g.N >= 1024 && g.K >= 4096 && g.M % 8 == 0 && g.lda % 8 == 0 && g.ldc % 8 == 0 &&
