@@ -354,7 +354,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   constexpr int KSTEPS = BK / 16;
   static_assert(BK == 64 && KSTEPS == 4, "swizzles below are written for 128-byte k-rows");
   // the narrow tile (BN = 64: convolutions with 64 output channels) exists for k-contiguous operands only
-  static_assert(BM == 256 && (BN == 256 || (BN == 64 && A_KC && B_KC)), "strided swizzle assumes 512-byte k-rows");
+  static_assert((BM == 256 && BN == 256) || ((BM == 256 || BM == 512) && BN == 64 && A_KC && B_KC), "strided swizzle assumes 512-byte k-rows");
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int CH_A = A_BYTES / 1024 / WAVES, CH_B = B_BYTES / 1024 / WAVES;   // 1 KiB pieces per wavefront
   constexpr int LPT = CH_A + CH_B;                                               // direct loads per lane per k-tile
@@ -793,7 +793,7 @@ static int compute_units() {
 template <int BM, int BN, int BK, int WGM, int WGN, bool EDGE>
 static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 block, int tiles_m, int tiles_n, int splits,
                           int k_per_split, const GemmEpilogue& ep) {
-  if constexpr (BM == 256 && BN == 64 && BK == 64 && EDGE) {
+  if constexpr ((BM == 256 || BM == 512) && BN == 64 && BK == 64 && EDGE) {
     // the narrow tile: a gathered first operand against 64 output channels
     constexpr int STAGE = (BM + BN) * BK * 2, STRIP = WGM * WGN * 32 * (BN / WGN + 4) * 4;
     constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
@@ -884,7 +884,7 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   } while (0)
   // whole tiles, 16-byte aligned rows: the direct-to-LDS kernel
   bool direct = false, whole = false;
-  if constexpr (CONVS && BM == 256) {
+  if constexpr (CONVS && BM >= 256) {
     // a gathered first operand through the direct-to-LDS kernel (eligibility was checked by the caller)
     launch_direct<BM, BN, BK, WGM, WGN, true>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
   } else {
@@ -981,11 +981,11 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
       return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
     // The same with 64 output channels (the first stage of the bottleneck network, the full-resolution level of the
     // fully convolutional one): a 256 x 64 tile, eight wavefronts of 32 x 64
-    if (g.conv_mode == 1 && g.N == 64 && (g.M + 255) / 256 >= 192 && g.K >= 128 && g.ldc % 8 == 0 && cg.stride <= 2 &&
+    if (g.conv_mode == 1 && g.N == 64 && (g.M + 511) / 512 >= 192 && g.K >= 128 && g.ldc % 8 == 0 && cg.stride <= 2 &&
         cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 && cg.Ho + cg.pad + 64 < 1024 &&
         cg.Wo + cg.pad + 64 < 1024 && g.M / pixels < 4095 && gathered_bytes < (1ull << 32) && (uint64_t)g.K * cg.C < (1ull << 31) &&
         ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
-      return launch_cfg<256, 64, 64, 8, 1, true>(g, s);
+      return launch_cfg<512, 64, 64, 8, 1, true>(g, s);
     // The weight gradient (second operand gathered, reduction over the pixels): few output tiles and a very long
     // reduction, which the split fills the chip with; worth the large tile from 128 x 1024 results on.
     if (g.conv_mode == 2 && g.M >= 128 && g.N >= 1024 && g.K >= 4096 && g.M % 8 == 0 && g.lda % 8 == 0 && g.ldc % 8 == 0 &&
