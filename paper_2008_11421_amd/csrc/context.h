@@ -39,6 +39,9 @@ struct Param {
 // Large tensors cross the link and the optimiser in chunks so that gradient D2H, host update
 // and weight H2D of one tensor overlap (this matters for the record that finishes last).
 constexpr uint64_t PARAM_CHUNK = 4ull << 20;   // elements
+// Records whose gradients are at most this many bytes (a convolutional block: a dozen tensors, most of them
+// batch-norm vectors) cross the link whole; larger ones tensor by tensor in chunks, so that copy and update overlap.
+constexpr uint64_t WHOLE_RECORD_BYTES = 4ull << 20;
 
 struct Record {
   int kind = 0;
@@ -52,6 +55,12 @@ struct Record {
   char* stage_w_all = nullptr;           // pinned; Param::stage_w point into it
   char* stage_g_all = nullptr;           // pinned; Param::stage_g point into it
   uint64_t shared_bytes = 0;             // leading part of both buffers: tensors whose gradient has the weight's type
+  // Resident weights: the record's weights lie contiguously in the fixed region ([w_base, w_base + w_span)), its
+  // gradients behind them ([g_base, g_base + g_span)), and the pinned buffers mirror the two spans, so that a
+  // record of many small tensors crosses the link with one copy each way (whole_copies) instead of one per tensor
+  uint64_t w_base = 0, w_span = 0, g_base = 0, g_span = 0;
+  bool whole_copies = false;
+  hipEvent_t grads_ev = nullptr;         // whole_copies: the record's gradients have landed on the host
   bool shared_staging = false;           // that part of the gradients lands in stage_w_all; stage_g_all holds the rest
 };
 

@@ -366,6 +366,12 @@ int issue(Ctx* c, const ProgOp& p) {
 int send_grads(Ctx* c, uint32_t r, hipEvent_t after) {
   hipStream_t s = c->st[2];
   KARMA_HIP(c, hipStreamWaitEvent(s, after, 0));
+  Record& rc = c->rec[r];
+  if (rc.whole_copies) {
+    KARMA_HIP(c, hipMemcpyAsync(rc.stage_g_all, c->arena + rc.g_base, rc.g_span, hipMemcpyDeviceToHost, s));
+    KARMA_HIP(c, hipEventRecord(rc.grads_ev, s));
+    return KARMA_OK;
+  }
   for (Param& p : c->rec[r].p) {
     const uint64_t gs = p.grad_bf16 ? 2 : 4;
     for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
@@ -387,12 +393,14 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed, uint64_t step, bo
   // streamed records: the whole gradient buffer arrives with one copy of the program, and
   // the new weights stay in pinned memory for the next step's copy-in
   if (streamed && !landed) KARMA_HIP(c, hipEventSynchronize(grads_landed));
+  const bool whole = c->rec[r].whole_copies;
+  if (whole && !landed) KARMA_HIP(c, hipEventSynchronize(c->rec[r].grads_ev));
   double spent_ms = 0.0;
   for (Param& p : c->rec[r].p) {
     const uint64_t gs = p.grad_bf16 ? 2 : 4, ws = p.dev_bf16 ? 2 : 4;
     for (size_t k = 0; k < p.chunk_ev.size(); ++k) {
       const uint64_t base = k * PARAM_CHUNK, n = std::min(PARAM_CHUNK, p.n - base);
-      if (!streamed && !landed) KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
+      if (!streamed && !whole && !landed) KARMA_HIP(c, hipEventSynchronize(p.chunk_ev[k]));
       double t0 = now_ms();
       c->pool->parallel_for(n, [&](size_t lo, size_t hi) {
         const char* gp = (const char*)p.stage_g + (base + lo) * gs;
@@ -409,11 +417,14 @@ int update_record(Ctx* c, uint32_t r, hipEvent_t grads_landed, uint64_t step, bo
       const double dt = now_ms() - t0;
       c->stats.host_opt_ms += dt;
       spent_ms += dt;
-      if (!streamed)
+      if (!streamed && !whole)
         KARMA_HIP(c, hipMemcpyAsync(c->arena + p.w_off + base * ws, (char*)p.stage_w + base * ws, n * ws,
                                     hipMemcpyHostToDevice, c->st[1]));
     }
   }
+  if (whole)   // every tensor's new weights with one copy (the gaps between them are alignment padding on both sides)
+    KARMA_HIP(c, hipMemcpyAsync(c->arena + c->rec[r].w_base, c->rec[r].stage_w_all, c->rec[r].w_span, hipMemcpyHostToDevice,
+                                c->st[1]));
   if (r < c->update_ns.size()) c->update_ns[r] = (int64_t)(spent_ms * 1e6);
   return KARMA_OK;
 }
@@ -599,15 +610,19 @@ int karma::derive_layout(Ctx& c) {
       }
       continue;
     }
-    for (Param& p : r.p) {
-      p.w_off = off; off += up256(p.w_bytes());
-      p.g_off = off; off += up256(p.g_bytes());
+    r.w_base = off;
+    for (Param& p : r.p) { p.w_off = off; off += up256(p.w_bytes()); }
+    r.w_span = off - r.w_base;
+    r.g_base = off;
+    for (Param& p : r.p) { p.g_off = off; off += up256(p.g_bytes()); }
+    r.g_span = off - r.g_base;
+    r.whole_copies = r.p.size() > 1 && r.g_span <= WHOLE_RECORD_BYTES;
+    for (Param& p : r.p)
       if (p.dev_opt) {
         p.dmaster_off = off; off += up256(p.n * 4);
         p.dm_off = off; off += up256(p.n * 4);
         p.dv_off = off; off += up256(p.n * 4);
       }
-    }
   }
   c.in_off = off; off += up256(c.in_bytes);
   c.lab_off = off; off += up256(c.lab_bytes);
@@ -698,6 +713,12 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
     }
   };
   for (Record& r : c->rec) {
+    if (!r.streamed) {
+      pin((void**)&r.stage_g_all, r.g_span);
+      pin((void**)&r.stage_w_all, r.w_span);
+      if (ok) { std::memset(r.stage_g_all, 0, r.g_span ? r.g_span : 256); std::memset(r.stage_w_all, 0, r.w_span ? r.w_span : 256); }
+      if (ok && r.whole_copies && hipEventCreateWithFlags(&r.grads_ev, hipEventDisableTiming) != hipSuccess) ok = false;
+    }
     if (r.streamed) {
       pin((void**)&r.stage_w_all, r.w_total);
       if (desc->stream_weights == 2) {
@@ -730,9 +751,9 @@ extern "C" int karma_create(const karma_model_desc* desc, const karma_config* cf
           if (!r.shared_staging) p.stage_g = r.stage_g_all + p.g_rel;
           else p.stage_g = p.g_rel < r.shared_bytes ? r.stage_w_all + p.g_rel : r.stage_g_all + (p.g_rel - r.shared_bytes);
         }
-      } else {
-        pin(&p.stage_g, p.g_bytes());
-        pin(&p.stage_w, p.w_bytes());
+      } else if (ok) {
+        p.stage_g = r.stage_g_all + (p.g_off - r.g_base);
+        p.stage_w = r.stage_w_all + (p.w_off - r.w_base);
       }
     }
   }
@@ -767,11 +788,9 @@ extern "C" void karma_destroy(karma_ctx* c) {
   for (int k = 0; k < 3; ++k) if (c->st[k] || k == 0) (void)hipStreamSynchronize(c->st[k]);
   free_plan_resources(c);
   for (Record& r : c->rec) {
-    for (Param& p : r.p) {
-      if (!r.streamed && p.stage_g) (void)hipHostFree(p.stage_g);
-      if (!r.streamed && p.stage_w) (void)hipHostFree(p.stage_w);
+    for (Param& p : r.p)
       for (auto e : p.chunk_ev) if (e) (void)hipEventDestroy(e);
-    }
+    if (r.grads_ev) (void)hipEventDestroy(r.grads_ev);
     if (r.stage_w_all) (void)hipHostFree(r.stage_w_all);
     if (r.stage_g_all) (void)hipHostFree(r.stage_g_all);
   }
