@@ -987,11 +987,14 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
         ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
       return launch_cfg<512, 64, 64, 8, 1, true>(g, s);
     // The weight gradient (second operand gathered, reduction over the pixels): few output tiles and a very long
-    // reduction, which the split fills the chip with; worth the large tile from 128 x 1024 results on.
-    if (g.conv_mode == 2 && g.M >= 128 && g.N >= 1024 && g.K >= 4096 && g.M % 8 == 0 && g.lda % 8 == 0 && g.ldc % 8 == 0 &&
+    // reduction, which the split fills the chip with; worth the large tile from 64 x 512 results on (with 64 output
+    // channels three quarters of the tile's rows are zeros, and it is still faster than the small tile's gather).
+    // (pixels * Wo < 2^32: the reciprocal multiplication by magic_w = 2^32 / Wo + 1 is exact for every n with
+    // n * (magic_w * Wo - 2^32) < 2^32, and that excess is at most Wo)
+    if (g.conv_mode == 2 && g.M >= 64 && g.N >= 512 && g.K >= 4096 && g.M % 8 == 0 && g.lda % 8 == 0 && g.ldc % 8 == 0 &&
         g.ws != nullptr && cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 &&
         (uint64_t)(g.K / pixels) * cg.H * cg.W * cg.C * 2 < (1ull << 32) && (uint64_t)g.N * cg.C < (1ull << 31) &&
-        pixels < (1 << 16) && g.K < (1 << 24) && ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 &&
+        (uint64_t)pixels * cg.Wo < (1ull << 32) && g.K < (1 << 24) && ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 &&
         (uint64_t)g.lda * 2 * 256 < (1ull << 31))
       return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
     return launch_cfg<128, 128, 64, 2, 2, true>(g, s);
