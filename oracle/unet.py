@@ -50,7 +50,7 @@ def upconv2x2_bwd(x, w, dy):
         for b in range(2):
             g = dy[:, a::2, b::2, :]
             dx += g @ w[:, a, b, :].T
-            dw[:, a, b, :] = np.einsum("nhwi,nhwo->io", x, g)
+            dw[:, a, b, :] = x.reshape(-1, x.shape[3]).T @ g.reshape(-1, g.shape[3])   # sum over (n, h, w)
     return dx, dw
 
 
