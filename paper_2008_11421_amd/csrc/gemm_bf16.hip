@@ -340,7 +340,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (BM <= 128 && BN <= 128 ? 2 : 1)) vo
 // (image by a float reciprocal with an exact correction, row and column by reciprocal multiplication: magic_w =
 // 2^32 / Wo + 1, inv_grid = 1 / (Ho * Wo)).
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int ACT = 0, bool EDGE = false, int CONV = 0>
-__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+__global__ __launch_bounds__(WGM* WGN * 64, (BM == 256 && BN == 64) ? 4 : 1) void gemm_bf16_dl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                                          int M, int N, int K, int lda, int ldb, int tiles_m,
                                                                          int tiles_n, int splits, int k_per_split,
                                                                          GemmEpilogue ep, float* __restrict__ partial,
@@ -354,7 +354,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_bf16_dl_kernel(const bf
   constexpr int KSTEPS = BK / 16;
   static_assert(BK == 64 && KSTEPS == 4, "swizzles below are written for 128-byte k-rows");
   // the narrow tile (BN = 64: convolutions with 64 output channels) exists for k-contiguous operands only
-  static_assert((BM == 256 && BN == 256) || ((BM == 256 || BM == 512) && BN == 64 && A_KC && B_KC), "strided swizzle assumes 512-byte k-rows");
+  static_assert((BM == 256 && BN == 256) || (BM == 256 && BN == 64 && A_KC && B_KC), "strided swizzle assumes 512-byte k-rows");
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   constexpr int CH_A = A_BYTES / 1024 / WAVES, CH_B = B_BYTES / 1024 / WAVES;   // 1 KiB pieces per wavefront
   constexpr int LPT = CH_A + CH_B;                                               // direct loads per lane per k-tile
@@ -793,7 +793,7 @@ static int compute_units() {
 template <int BM, int BN, int BK, int WGM, int WGN, bool EDGE>
 static void launch_direct(const GemmArgs& g, hipStream_t s, dim3 grid, dim3 block, int tiles_m, int tiles_n, int splits,
                           int k_per_split, const GemmEpilogue& ep) {
-  if constexpr ((BM == 256 || BM == 512) && BN == 64 && BK == 64 && EDGE) {
+  if constexpr (BM == 256 && BN == 64 && BK == 64 && EDGE) {
     // the narrow tile: a gathered first operand against 64 output channels
     constexpr int STAGE = (BM + BN) * BK * 2, STRIP = WGM * WGN * 32 * (BN / WGN + 4) * 4;
     constexpr int EXTRA = STRIP > STAGE ? STRIP - STAGE : 0;
@@ -849,7 +849,7 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const int tiles = tiles_m * tiles_n;
   // workgroups that run at once: the small tile leaves LDS and registers for two per compute unit
-  const int cus = compute_units() * (BM <= 128 && BN <= 128 ? 2 : 1);
+  const int cus = compute_units() * ((BM <= 128 && BN <= 128) || (BM == 256 && BN == 64) ? 2 : 1);
   // split the reduction when the tiles alone cannot fill the chip (weight gradients:
   // small M x N, K = tokens); partial sums are reduced in a fixed order afterwards
   int splits = 1;
@@ -884,7 +884,7 @@ static int launch_cfg(const GemmArgs& g, hipStream_t s) {
   } while (0)
   // whole tiles, 16-byte aligned rows: the direct-to-LDS kernel
   bool direct = false, whole = false;
-  if constexpr (CONVS && BM >= 256) {
+  if constexpr (CONVS && BM == 256) {
     // a gathered first operand through the direct-to-LDS kernel (eligibility was checked by the caller)
     launch_direct<BM, BN, BK, WGM, WGN, true>(g, s, grid, block, tiles_m, tiles_n, splits, k_per_split, ep);
   } else {
@@ -980,12 +980,14 @@ static int gemm_bf16_launch(const GemmArgs& g, hipStream_t s) {
         ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
       return launch_cfg<256, 256, 64, 2, 4, true>(g, s);
     // The same with 64 output channels (the first stage of the bottleneck network, the full-resolution level of the
-    // fully convolutional one): a 256 x 64 tile, eight wavefronts of 32 x 64
-    if (g.conv_mode == 1 && g.N == 64 && (g.M + 511) / 512 >= 192 && g.K >= 128 && g.ldc % 8 == 0 && cg.stride <= 2 &&
+    // fully convolutional one): a 256 x 64 tile, eight wavefronts of 64 x 32, two workgroups per compute unit (a
+    // k-tile of this shape carries 16 MFMAs per wavefront, less than its loads' round trip: the second workgroup
+    // multiplies while the first one waits)
+    if (g.conv_mode == 1 && g.N == 64 && (g.M + 255) / 256 >= 384 && g.K >= 128 && g.ldc % 8 == 0 && cg.stride <= 2 &&
         cg.H * cg.stride + cg.pad + 64 < 1024 && cg.W * cg.stride + cg.pad + 64 < 1024 && cg.Ho + cg.pad + 64 < 1024 &&
         cg.Wo + cg.pad + 64 < 1024 && g.M / pixels < 4095 && gathered_bytes < (1ull << 32) && (uint64_t)g.K * cg.C < (1ull << 31) &&
         ((uintptr_t)g.A % 16) == 0 && ((uintptr_t)g.B % 16) == 0 && (uint64_t)g.ldb * 2 * 256 < (1ull << 31))
-      return launch_cfg<512, 64, 64, 8, 1, true>(g, s);
+      return launch_cfg<256, 64, 64, 4, 2, true>(g, s);
     // The weight gradient (second operand gathered, reduction over the pixels): few output tiles and a very long
     // reduction, which the split fills the chip with; worth the large tile from 64 x 512 results on (with 64 output
     // channels three quarters of the tile's rows are zeros, and it is still faster than the small tile's gather).
